@@ -1,0 +1,22 @@
+"""Compile the CPU oracle (plain C, gcc) into oracle/libkvcomp_oracle.so.  Test infrastructure only."""
+from __future__ import annotations
+
+import pathlib
+import subprocess
+
+HERE = pathlib.Path(__file__).resolve().parent
+SRC = HERE / "kvcomp_oracle.c"
+LIB = HERE / "libkvcomp_oracle.so"
+
+
+def build(force: bool = True) -> pathlib.Path:
+    if not force and LIB.exists() and LIB.stat().st_mtime >= SRC.stat().st_mtime:
+        return LIB
+    cmd = ["gcc", "-std=c99", "-O2", "-ffp-contract=off", "-fno-fast-math", "-fopenmp", "-fPIC", "-shared",
+           "-Wall", "-Wextra", "-o", str(LIB), str(SRC), "-lm"]
+    subprocess.run(cmd, check=True)
+    return LIB
+
+
+if __name__ == "__main__":
+    print(build())
