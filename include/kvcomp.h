@@ -1,0 +1,165 @@
+/*
+ * kvcomp.h -- C ABI of libkvcomp, a gfx950 (MI355X) implementation of the KVComp hot path:
+ * block-wise error-bounded quantization + Huffman coding of a growing fp16 KV cache, and decode attention that
+ * consumes the compressed cache directly (Huffman decode + dequantize + matrix-vector product fused in one kernel).
+ *
+ * General conventions
+ *   - Plain C; every function returns a kvcomp_status (0 = OK, negative = error) unless stated otherwise;
+ *     kvcomp_last_error() returns a thread-local, human readable description of the last failure.
+ *   - Pointers named d_* are DEVICE pointers (HIP global memory), pointers named h_* are HOST pointers.
+ *   - The caller owns all device memory, including the arena handed to kvcomp_create; the library allocates no
+ *     device memory.  `stream` arguments are a hipStream_t passed as void* (NULL = the default stream).
+ *   - One context holds the cache of one transformer layer (Section 3: buffers and codebooks are per layer).
+ *     A context must be used by one host thread at a time.
+ *   - KV tensors are fp16, shape [batch, seq, n_kv_heads, 128] (the paper's [context_len, head_num, head_dim]
+ *     of Section 2.1 with a batch dimension outermost), contiguous: element (b, t, h, c) at
+ *     ((b*seq + t)*n_kv_heads + h)*128 + c.
+ *   - A 2D block is 64 consecutive tokens x 128 channels of one (batch, head) (Section 3.2.1).
+ */
+#ifndef KVCOMP_H
+#define KVCOMP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct kvcomp_ctx kvcomp_ctx; /* opaque, host object owned by the library */
+
+typedef enum {
+    KVCOMP_OK = 0,
+    KVCOMP_ERR_INVALID_ARG = -1,
+    KVCOMP_ERR_STATE = -2,     /* call order: e.g. compress before the codebook exists, cache not empty      */
+    KVCOMP_ERR_CAPACITY = -3,  /* arena too small, or max_seq exceeded                                        */
+    KVCOMP_ERR_HIP = -4,       /* a HIP runtime call failed                                                   */
+    KVCOMP_ERR_NONFINITE = -5  /* an input held Inf or NaN (detected at the synchronising calls)              */
+} kvcomp_status;
+
+enum { KVCOMP_K = 0, KVCOMP_V = 1 };
+
+typedef struct {
+    int32_t batch;        /* sequences in the batch                                                           */
+    int32_t n_kv_heads;   /* KV heads                                                                         */
+    int32_t n_q_heads;    /* query heads; n_q_heads / n_kv_heads must be 1, 2, 4 or 8                         */
+    int32_t head_dim;     /* must be 128                                                                      */
+    int32_t block_tokens; /* must be 64 (also the size of the fp16 buffer of new tokens, Section 3.2.1)       */
+    int32_t max_seq;      /* capacity in tokens per sequence (prefill + appended)                             */
+    float rel_eb_k;       /* relative error bound for K: |x - x'| <= rel_eb * (max - min) of the unit; the    */
+    float rel_eb_v;       /*   paper's "relative quantization scale" (Section 4.2) is the bin width = 2*rel_eb */
+    int32_t k_mode;       /* 0: K units are channels inside a block (Section 3.1.1); 1: reserved (BlockQuant) */
+    int32_t max_code_len; /* longest Huffman code word allowed, 8..12 (0 = default 12)                        */
+} kvcomp_config;
+
+typedef struct {
+    int64_t n_blocks;         /* compressed 2D blocks per (batch, head), same for K and V                     */
+    int64_t n_res;            /* tokens in the fp16 buffer (0..63)                                            */
+    int64_t raw_bytes;        /* fp16 bytes of K and V for all tokens held                                    */
+    int64_t record_bytes_k;   /* compressed records of K: headers + code words + padding                      */
+    int64_t record_bytes_v;
+    int64_t header_bytes;     /* part of the records: min/max pairs and per-slice bit counts                  */
+    int64_t offsets_bytes;    /* Block Offsets Array entries in use (8 bytes per block)                       */
+    int64_t residual_bytes;   /* fp16 bytes of the buffered tokens                                            */
+    int64_t payload_bits_k;   /* sum of code-word bits                                                        */
+    int64_t payload_bits_v;
+    int64_t stored_bytes;     /* record_bytes_k + record_bytes_v + offsets_bytes + residual_bytes             */
+    int64_t max_record_bytes; /* largest record so far                                                        */
+    double compression_ratio; /* raw_bytes / stored_bytes                                                     */
+} kvcomp_stats;
+
+/* ---- life cycle ------------------------------------------------------------------------------------------ */
+
+/* Device bytes the caller must provide for `cfg` (worst case over all inputs: every code word max_code_len bits).
+ * Returns 0 if cfg is invalid. */
+size_t kvcomp_arena_bytes(const kvcomp_config *cfg);
+
+/* Create a context over a caller-owned device arena (256-byte aligned, >= kvcomp_arena_bytes(cfg), must outlive the
+ * context and must not be touched by the caller while the context lives).  The arena is initialised on `stream`.
+ * Errors: INVALID_ARG (bad cfg / alignment), CAPACITY (arena_bytes too small), HIP. */
+kvcomp_status kvcomp_create(const kvcomp_config *cfg, void *d_arena, size_t arena_bytes, void *stream, kvcomp_ctx **out);
+kvcomp_status kvcomp_destroy(kvcomp_ctx *ctx);
+
+/* Drop all cached tokens (compressed blocks and buffered tokens).  keep_codebook != 0 keeps the Huffman codebooks
+ * (they are built once at prefill and reused, Section 3).  Stream-ordered, does not synchronise. */
+kvcomp_status kvcomp_reset(kvcomp_ctx *ctx, int keep_codebook, void *stream);
+
+/* ---- the four calls of the hot path ---------------------------------------------------------------------- */
+
+/* Store stage, step "histogram on the GPU, codebook once at prefill" (Section 3; Section 3.2): quantize the
+ * floor(seq/64) full blocks of d_K and d_V (K: per channel inside each block, V: per token; Section 3.1.1),
+ * histogram the codes on the device, build one canonical Huffman codebook for K and one for V on the host and
+ * upload the encode table and the decode lookup table.  d_K, d_V: device fp16 [batch, seq, n_kv_heads, 128],
+ * read-only.  SYNCHRONISES `stream` (the histogram crosses to the host, as in the paper).
+ * Errors: INVALID_ARG (seq < 64 or > max_seq), NONFINITE, HIP. */
+kvcomp_status kvcomp_build_codebook(kvcomp_ctx *ctx, const void *d_K, const void *d_V, int seq, void *stream);
+
+/* Store stage for the prompt (Section 3.2.2, Figure 4): quantize and Huffman-encode the floor(seq/64) full
+ * blocks of every (batch, head), one record per 2D block placed compactly in the arena (K records in (b,h,block)
+ * order, then V records), fill the Block Offsets Array; the seq%64 newest tokens go to the fp16 buffer.  The cache
+ * must be empty.  Inputs as for kvcomp_build_codebook.  SYNCHRONISES `stream` once at the end (reads back the
+ * arena tail and the largest record size, and the non-finite flag).
+ * Errors: STATE (no codebook / cache not empty), CAPACITY (seq > max_seq), NONFINITE, HIP. */
+kvcomp_status kvcomp_compress_blocks(kvcomp_ctx *ctx, const void *d_K, const void *d_V, int seq, void *stream);
+
+/* Decode-phase store (Section 3.2.1, Section 3.2.3): append one token per sequence.  d_k_new, d_v_new: device fp16
+ * [batch, n_kv_heads, 128].  The token is copied into the fp16 buffer; the call that fills the 64th slot compresses
+ * that block for every (batch, head) with the existing codebooks and appends the records at the arena tail.
+ * Stream-ordered, never synchronises.  Errors: STATE (no codebook), CAPACITY (max_seq reached), HIP. */
+kvcomp_status kvcomp_append_token(kvcomp_ctx *ctx, const void *d_k_new, const void *d_v_new, void *stream);
+
+/* Fetch stage (Section 3.3.2, Figure 1): one decode-attention step over the whole cache.  For every query head:
+ * scores = scale * q.K'^T over all compressed blocks (Huffman decode + dequantize fused into the dot product) and
+ * the buffered fp16 tokens, softmax over all of them, out = weights . V'.  Query head g reads KV head
+ * g / (n_q_heads / n_kv_heads).  d_q: device fp16 [batch, n_q_heads, 128]; d_out: device fp32
+ * [batch, n_q_heads, 128], caller-owned.  Stream-ordered, never synchronises.
+ * Errors: STATE (empty cache), HIP. */
+kvcomp_status kvcomp_attn_decode(kvcomp_ctx *ctx, const void *d_q, float scale, float *d_out, void *stream);
+
+/* ---- metrics, parity and debug exports (these SYNCHRONISE `stream` and copy to HOST buffers) ------------- */
+
+kvcomp_status kvcomp_get_stats(kvcomp_ctx *ctx, kvcomp_stats *h_out, void *stream);
+
+/* Quantization codes and unit min/max of the full blocks of d_in (which = KVCOMP_K or KVCOMP_V) without touching the
+ * cache.  h_codes: [batch*n_kv_heads*floor(seq/64)][64][128] bytes, blocks in (b,h,block) order, token-major tiles;
+ * h_minmax_fp16: [blocks][units][2] fp16 bit patterns (units: 128 channels for K, 64 tokens for V).
+ * d_scratch: device scratch of at least blocks*(8192 + 4*units) bytes. */
+kvcomp_status kvcomp_debug_codes(kvcomp_ctx *ctx, int which, const void *d_in, int seq, void *d_scratch,
+                                 size_t scratch_bytes, uint8_t *h_codes, uint16_t *h_minmax_fp16, void *stream);
+kvcomp_status kvcomp_get_histogram(kvcomp_ctx *ctx, int which, uint32_t *h_hist256, void *stream);
+kvcomp_status kvcomp_get_codebook(kvcomp_ctx *ctx, int which, uint8_t *h_len256, uint32_t *h_code256);
+/* Block Offsets Array entry of block (b, h, blk): record offset and size in 16-byte units. */
+kvcomp_status kvcomp_get_block_entry(kvcomp_ctx *ctx, int which, int b, int h, int blk, uint32_t *h_off16,
+                                     uint32_t *h_size16, void *stream);
+/* Copy the record of block (b, h, blk) to h_buf (capacity cap); *h_bytes receives its size. */
+kvcomp_status kvcomp_get_block(kvcomp_ctx *ctx, int which, int b, int h, int blk, void *h_buf, size_t cap,
+                               size_t *h_bytes, void *stream);
+/* Copy the fp16 buffer (layout [batch][64][n_kv_heads][128]) to h_buf; *h_n_res receives the valid token count. */
+kvcomp_status kvcomp_get_residual(kvcomp_ctx *ctx, int which, uint16_t *h_buf, int *h_n_res, void *stream);
+
+/* Tuning knobs for measurements (0 = library default): number of sequence splits of the fused kernel, LDS staging
+ * bytes per wave (records larger than this are decoded straight from global memory). */
+kvcomp_status kvcomp_set_tuning(kvcomp_ctx *ctx, int n_splits, int stage_bytes);
+
+/* Kernel timing with HIP events on the launch stream: when enabled, every kvcomp_attn_decode records an event pair
+ * around its fused decode kernel.  kvcomp_get_profile synchronises, returns the number of timed launches and their
+ * total duration in milliseconds since the last call, and resets the counters. */
+kvcomp_status kvcomp_set_profiling(kvcomp_ctx *ctx, int enable);
+kvcomp_status kvcomp_get_profile(kvcomp_ctx *ctx, int *h_launches, double *h_total_ms);
+
+/* ---- the uncompressed comparison kernel (Section 4.3 compares against a plain fp16 matrix-vector product) - */
+
+/* Decode attention on the uncompressed fp16 cache: same result definition as kvcomp_attn_decode with K' = K and
+ * V' = V.  d_K, d_V: device fp16 [batch, seq, n_kv_heads, 128]; d_workspace: device scratch of at least
+ * kvcomp_baseline_workspace_bytes(cfg).  Stream-ordered.  n_splits 0 = default. */
+size_t kvcomp_baseline_workspace_bytes(const kvcomp_config *cfg);
+kvcomp_status kvcomp_baseline_fp16_attn(const kvcomp_config *cfg, const void *d_K, const void *d_V, int seq,
+                                        const void *d_q, float scale, float *d_out, void *d_workspace,
+                                        size_t workspace_bytes, int n_splits, void *stream);
+
+const char *kvcomp_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* KVCOMP_H */

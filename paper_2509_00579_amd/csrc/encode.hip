@@ -1,0 +1,262 @@
+// Store side, second half (Section 3.2.2, Figure 4; Section 3.2.3): Huffman-encode quantized 2D blocks into
+// one contiguous record each, place the records compactly and deterministically, and keep the fp16 buffer of
+// the newest tokens.
+//
+// The paper reserves space with a global atomic offset, which makes the layout depend on execution order.  Here
+// the same contiguous layout is produced in a fixed order by three launches:
+//   1. size pass   : quantize, sum the code lengths of the block -> record size into the Block Offsets Array
+//   2. place       : one workgroup scans the sizes in (tensor, batch, head, block) order starting at the arena tail
+//   3. write pass  : quantize again, encode, write the record at its offset
+// The store side runs once per token block while the fetch side runs every decode step (Section 3.3), so the
+// second read of the fp16 input is the cheaper trade against a staging copy of all records.
+#include "tile_quant.cuh"
+
+namespace kvc {
+
+constexpr int kCodeRow = kD + 4;  // padded row of the LDS code tile (bytes)
+
+template <int WHICH>
+struct Rec {
+    static constexpr int minmax_bytes = WHICH == 0 ? kMinMaxBytesK : kMinMaxBytesV;
+    static constexpr int hdr_bytes = WHICH == 0 ? kHdrBytesK : kHdrBytesV;
+    static constexpr int n_units = WHICH == 0 ? kD : kBT;
+    static constexpr int n_slices = WHICH == 0 ? kBT : kD;
+    static constexpr int parts = WHICH == 0 ? 4 : 2;  // threads per slice, 32 symbols each
+};
+
+__device__ __forceinline__ uint32_t record_size16(int hdr_bytes, uint32_t total_bits) {
+    const uint32_t bytes = (uint32_t)hdr_bytes + ((total_bits + 31u) >> 5) * 4u;
+    return (bytes + 15u) >> 4;
+}
+
+// Sum over the workgroup (256 threads); result valid in every thread.  scratch: 4 words of LDS.
+__device__ __forceinline__ uint32_t block_sum(uint32_t v, uint32_t *scratch, int tid) {
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m);
+    __syncthreads();
+    if ((tid & 63) == 0) scratch[tid >> 6] = v;
+    __syncthreads();
+    return scratch[0] + scratch[1] + scratch[2] + scratch[3];
+}
+
+// ---- 1. size pass ------------------------------------------------------------------------------------------
+template <int WHICH>
+__global__ __launch_bounds__(256) void size_kernel(Geo g, const uint16_t *__restrict__ X, int seq_stride,
+                                                    int n_blk_per_bh, int dst_blk0) {
+    __shared__ QuantShared sh;
+    __shared__ uint32_t enc[256];
+    __shared__ uint32_t scratch[4];
+    const int tid = threadIdx.x, blk = blockIdx.x;
+    const int bh = blk / n_blk_per_bh, j = blk - bh * n_blk_per_bh;
+    enc[tid] = g.enc[WHICH * 256 + tid];
+    TileRegs r;
+    const bool bad = load_tile(X, seq_stride, g.H, bh / g.H, bh % g.H, j, tid, r);
+    quantize_tile<WHICH>(r, sh, tid, g.two_eb[WHICH], g.n_sym[WHICH]);  // has barriers: enc[] is visible after it
+    uint32_t bits = 0;
+#pragma unroll
+    for (int i = 0; i < 4; i++)
+#pragma unroll
+        for (int k = 0; k < 8; k++) bits += enc[r.code[i][k]] >> 16;
+    const uint32_t total = block_sum(bits, scratch, tid);
+    if (tid == 0) {
+        const uint32_t s16 = record_size16(Rec<WHICH>::hdr_bytes, total);
+        g.table[((size_t)WHICH * g.B * g.H + bh) * g.max_blocks + dst_blk0 + j].size16 = s16;
+        atomicAdd(&g.ctrl->payload_bits[WHICH], (unsigned long long)total);
+        atomicAdd(&g.ctrl->record16[WHICH], (unsigned long long)s16);
+        atomicMax(&g.ctrl->max_size16, s16);
+    }
+    if (bad) atomicOr(&g.ctrl->nonfinite, 1u);
+}
+
+// ---- 2. placement ------------------------------------------------------------------------------------------
+// Items in order: tensor K then V; inside a tensor (b,h) major, block minor.  One workgroup of 1024 threads.
+__global__ __launch_bounds__(1024) void place_kernel(Geo g, int n_blk_per_bh, int dst_blk0) {
+    __shared__ uint32_t wave_tot[16];
+    __shared__ uint32_t base_s;
+    const int tid = threadIdx.x;
+    const int BH = g.B * g.H;
+    const int n_items = 2 * BH * n_blk_per_bh;
+    const int chunk = (n_items + 1023) / 1024;
+    const int i0 = tid * chunk, i1 = min(i0 + chunk, n_items);
+    auto entry = [&](int i) -> BlockEntry * {
+        const int which = i / (BH * n_blk_per_bh);
+        const int rem = i - which * BH * n_blk_per_bh;
+        const int bh = rem / n_blk_per_bh, j = rem - bh * n_blk_per_bh;
+        return &g.table[((size_t)which * BH + bh) * g.max_blocks + dst_blk0 + j];
+    };
+    uint32_t sum = 0;
+    for (int i = i0; i < i1; i++) sum += entry(i)->size16;
+    // inclusive scan of `sum` over the 1024 threads
+    uint32_t inc = sum;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const uint32_t o = __shfl_up(inc, d);
+        if ((tid & 63) >= d) inc += o;
+    }
+    if ((tid & 63) == 63) wave_tot[tid >> 6] = inc;
+    if (tid == 0) base_s = g.ctrl->tail16;
+    __syncthreads();
+    uint32_t before = 0, all = 0;
+    for (int w = 0; w < 16; w++) {
+        if (w < (tid >> 6)) before += wave_tot[w];
+        all += wave_tot[w];
+    }
+    uint32_t at = base_s + before + inc - sum;
+    for (int i = i0; i < i1; i++) {
+        BlockEntry *e = entry(i);
+        e->off16 = at;
+        at += e->size16;
+    }
+    if (tid == 0) g.ctrl->tail16 = base_s + all;
+}
+
+// ---- 3. write pass -----------------------------------------------------------------------------------------
+template <int WHICH>
+__global__ __launch_bounds__(256) void write_kernel(Geo g, const uint16_t *__restrict__ X, int seq_stride,
+                                                     int n_blk_per_bh, int dst_blk0) {
+    using R = Rec<WHICH>;
+    __shared__ QuantShared sh;
+    __shared__ uint32_t enc[256];
+    __shared__ uint32_t wave_tot[4];
+    __shared__ __attribute__((aligned(16))) uint8_t code_tile[kBT * kCodeRow];
+    __shared__ __attribute__((aligned(16))) uint32_t rec[(kMaxRecordBytes + 15) / 16 * 4];
+    const int tid = threadIdx.x, blk = blockIdx.x;
+    const int bh = blk / n_blk_per_bh, j = blk - bh * n_blk_per_bh;
+    enc[tid] = g.enc[WHICH * 256 + tid];
+    for (int i = tid; i < (int)(sizeof(rec) / 4); i += 256) rec[i] = 0;
+    TileRegs r;
+    load_tile(X, seq_stride, g.H, bh / g.H, bh % g.H, j, tid, r);
+    quantize_tile<WHICH>(r, sh, tid, g.two_eb[WHICH], g.n_sym[WHICH]);
+    // codes -> LDS tile (token-major rows, padded), header -> record
+    const int c0 = tile_chan0(tid);
+#pragma unroll
+    for (int i = 0; i < 4; i++) {
+        const int t = tile_token(tid, i);
+        uint32_t *dst = reinterpret_cast<uint32_t *>(code_tile + t * kCodeRow + c0);
+        dst[0] = r.code[i][0] | (r.code[i][1] << 8) | (r.code[i][2] << 16) | (r.code[i][3] << 24);
+        dst[1] = r.code[i][4] | (r.code[i][5] << 8) | (r.code[i][6] << 16) | (r.code[i][7] << 24);
+    }
+    if (tid < R::n_units) rec[tid] = float_to_half_bits(sh.unit_mn[tid]) | (float_to_half_bits(sh.unit_mx[tid]) << 16);
+    __syncthreads();
+    // Each thread encodes 32 symbols of one slice (Section 3.2.2 stage 2).  K: slice = token row, symbols in channel
+    // order; V: slice = channel column, symbols in token order.
+    const int slice = tid / R::parts, part = tid % R::parts;
+    uint32_t sym[32];
+    uint32_t bits = 0;
+#pragma unroll
+    for (int k = 0; k < 32; k++) {
+        const int t = WHICH == 0 ? slice : 32 * part + k;
+        const int c = WHICH == 0 ? 32 * part + k : slice;
+        sym[k] = enc[code_tile[t * kCodeRow + c]];
+        bits += sym[k] >> 16;
+    }
+    // stage 3: inclusive scan of the bit counts over the workgroup -> bit offset of every thread
+    uint32_t inc = bits;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const uint32_t o = __shfl_up(inc, d);
+        if ((tid & 63) >= d) inc += o;
+    }
+    if ((tid & 63) == 63) wave_tot[tid >> 6] = inc;
+    uint32_t slice_bits = bits;
+#pragma unroll
+    for (int m = 1; m < R::parts; m <<= 1) slice_bits += __shfl_xor(slice_bits, m);
+    if (part == 0) reinterpret_cast<uint16_t *>(rec)[R::minmax_bytes / 2 + slice] = (uint16_t)slice_bits;
+    __syncthreads();
+    uint32_t before = 0, total = 0;
+#pragma unroll
+    for (int w = 0; w < 4; w++) {
+        if (w < (tid >> 6)) before += wave_tot[w];
+        total += wave_tot[w];
+    }
+    // stage 4: aggregate all code words into one contiguous chunk in LDS.  Bit i of the chunk is bit (i % 32) of
+    // word (i / 32); a code word goes out first-bit-first, so the table holds it bit-reversed.
+    uint32_t *pay = rec + R::hdr_bytes / 4;
+    uint32_t pos = before + inc - bits;
+    uint32_t word = pos >> 5, fill = pos & 31;
+    unsigned long long acc = 0;
+#pragma unroll
+    for (int k = 0; k < 32; k++) {
+        acc |= (unsigned long long)(sym[k] & 0xffffu) << fill;
+        fill += sym[k] >> 16;
+        if (fill >= 32) {
+            atomicOr(&pay[word], (uint32_t)acc);
+            acc >>= 32;
+            fill -= 32;
+            word++;
+        }
+    }
+    if (fill) atomicOr(&pay[word], (uint32_t)acc);
+    __syncthreads();
+    // stages 5-6: the offset was fixed by place_kernel; coalesced 16-byte stores of header + chunk + padding
+    const BlockEntry e = g.table[((size_t)WHICH * g.B * g.H + bh) * g.max_blocks + dst_blk0 + j];
+    const uint32_t n16 = record_size16(R::hdr_bytes, total);  // equals e.size16 by construction
+    uint4 *dst = reinterpret_cast<uint4 *>(g.payload + (size_t)e.off16 * 16);
+    const uint4 *src = reinterpret_cast<const uint4 *>(rec);
+    for (uint32_t i = tid; i < n16 && i < e.size16; i += 256) dst[i] = src[i];
+}
+
+hipError_t launch_encode(const Geo &g, const uint16_t *XK, const uint16_t *XV, int seq_stride, int n_blk_per_bh,
+                         int dst_blk0, hipStream_t s) {
+    const int total = g.B * g.H * n_blk_per_bh;
+    if (total <= 0) return hipSuccess;
+    hipLaunchKernelGGL(size_kernel<0>, dim3(total), dim3(256), 0, s, g, XK, seq_stride, n_blk_per_bh, dst_blk0);
+    hipLaunchKernelGGL(size_kernel<1>, dim3(total), dim3(256), 0, s, g, XV, seq_stride, n_blk_per_bh, dst_blk0);
+    hipLaunchKernelGGL(place_kernel, dim3(1), dim3(1024), 0, s, g, n_blk_per_bh, dst_blk0);
+    hipLaunchKernelGGL(write_kernel<0>, dim3(total), dim3(256), 0, s, g, XK, seq_stride, n_blk_per_bh, dst_blk0);
+    hipLaunchKernelGGL(write_kernel<1>, dim3(total), dim3(256), 0, s, g, XV, seq_stride, n_blk_per_bh, dst_blk0);
+    return hipGetLastError();
+}
+
+// ---- fp16 buffer of the newest tokens (Section 3.2.1) ------------------------------------------------------
+// Buffer layout [tensor][B][64][H][128]: the same as an input tensor of 64 tokens, so a full buffer is compressed
+// by the kernels above without a gather.
+__global__ void copy_tail_kernel(Geo g, const uint16_t *__restrict__ XK, const uint16_t *__restrict__ XV, int seq,
+                                 int first_tok, int n_tok) {
+    const size_t per_tensor = (size_t)g.B * n_tok * g.H * 16;  // 16-byte chunks
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < 2 * per_tensor; i += stride) {
+        const int which = i >= per_tensor;
+        size_t r = i - which * per_tensor;
+        const int ch = (int)(r % 16); r /= 16;
+        const int h = (int)(r % g.H); r /= g.H;
+        const int t = (int)(r % n_tok);
+        const int b = (int)(r / n_tok);
+        const uint16_t *X = which ? XV : XK;
+        const uint4 v = *reinterpret_cast<const uint4 *>(X + (((size_t)b * seq + first_tok + t) * g.H + h) * kD + ch * 8);
+        uint16_t *dst = g.res + (size_t)which * g.B * kBT * g.H * kD + (((size_t)b * kBT + t) * g.H + h) * kD + ch * 8;
+        *reinterpret_cast<uint4 *>(dst) = v;
+    }
+}
+
+hipError_t launch_copy_tail(const Geo &g, const uint16_t *XK, const uint16_t *XV, int seq, int first_tok, int n_tok,
+                            hipStream_t s) {
+    if (n_tok <= 0) return hipSuccess;
+    const size_t n = 2 * (size_t)g.B * n_tok * g.H * 16;
+    const unsigned grid = (unsigned)((n + 255) / 256 > 2048 ? 2048 : (n + 255) / 256);
+    hipLaunchKernelGGL(copy_tail_kernel, dim3(grid), dim3(256), 0, s, g, XK, XV, seq, first_tok, n_tok);
+    return hipGetLastError();
+}
+
+// One new token per sequence: k_new, v_new [B][H][128] -> buffer slot `slot`.
+__global__ void append_kernel(Geo g, const uint16_t *__restrict__ k_new, const uint16_t *__restrict__ v_new, int slot) {
+    const int per_tensor = g.B * g.H * 16;
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= 2 * per_tensor) return;
+    const int which = i >= per_tensor;
+    int r = i - which * per_tensor;
+    const int ch = r % 16; r /= 16;
+    const int h = r % g.H;
+    const int b = r / g.H;
+    const uint16_t *src = (which ? v_new : k_new) + ((size_t)b * g.H + h) * kD + ch * 8;
+    uint16_t *dst = g.res + (size_t)which * g.B * kBT * g.H * kD + (((size_t)b * kBT + slot) * g.H + h) * kD + ch * 8;
+    *reinterpret_cast<uint4 *>(dst) = *reinterpret_cast<const uint4 *>(src);
+}
+
+hipError_t launch_append(const Geo &g, const uint16_t *k_new, const uint16_t *v_new, int slot, hipStream_t s) {
+    const int n = 2 * g.B * g.H * 16;
+    hipLaunchKernelGGL(append_kernel, dim3((n + 255) / 256), dim3(256), 0, s, g, k_new, v_new, slot);
+    return hipGetLastError();
+}
+
+}  // namespace kvc

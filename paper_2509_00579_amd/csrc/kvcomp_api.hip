@@ -1,0 +1,575 @@
+// Host side of libkvcomp: the C ABI declared in include/kvcomp.h, arena bookkeeping, and the host-built
+// Huffman codebook (the paper builds the codebooks on the CPU from a GPU histogram, Section 3).
+#include <algorithm>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <numeric>
+#include <vector>
+
+#include "../../include/kvcomp.h"
+#include "kvcomp_internal.h"
+
+using namespace kvc;
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+kvcomp_status fail(kvcomp_status st, const char *fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return st;
+}
+
+#define HIP_TRY(expr)                                                                              \
+    do {                                                                                           \
+        hipError_t e_ = (expr);                                                                    \
+        if (e_ != hipSuccess) return fail(KVCOMP_ERR_HIP, "%s: %s", #expr, hipGetErrorString(e_)); \
+    } while (0)
+
+size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+int n_sym_for(float rel_eb) {
+    if (!(rel_eb > 0.0f) || rel_eb > 0.5f) return -1;
+    const float two_eb = 2.0f * rel_eb;
+    const int n = (int)__builtin_rintf(1.0f / two_eb) + 1;
+    return (n < 2 || n > 256) ? -1 : n;
+}
+
+bool valid_cfg(const kvcomp_config *c) {
+    if (!c) return false;
+    if (c->batch < 1 || c->n_kv_heads < 1 || c->n_q_heads < c->n_kv_heads) return false;
+    if (c->n_q_heads % c->n_kv_heads) return false;
+    const int G = c->n_q_heads / c->n_kv_heads;
+    if (G != 1 && G != 2 && G != 4 && G != 8) return false;
+    if (c->head_dim != kD || c->block_tokens != kBT) return false;
+    if (c->max_seq < 1) return false;
+    if (n_sym_for(c->rel_eb_k) < 0 || n_sym_for(c->rel_eb_v) < 0) return false;
+    if (c->k_mode != 0) return false;
+    if (c->max_code_len != 0 && (c->max_code_len < 8 || c->max_code_len > kLutBits)) return false;
+    if ((long long)c->batch * c->n_kv_heads * ((long long)c->max_seq / kBT + 1) > (1ll << 28)) return false;
+    return true;
+}
+
+int code_len_limit(const kvcomp_config &c) { return c.max_code_len ? c.max_code_len : kLutBits; }
+
+struct Layout {
+    size_t ctrl, hist, enc, lut, table, res, partials, payload, total;
+    size_t payload_cap16;
+    int max_blocks;
+};
+
+Layout make_layout(const kvcomp_config &c) {
+    Layout L;
+    const size_t BH = (size_t)c.batch * c.n_kv_heads;
+    L.max_blocks = c.max_seq / kBT;
+    const int lim = code_len_limit(c);
+    const size_t worst_k = align_up(kHdrBytesK + (size_t)kTile * lim / 8, 16);
+    const size_t worst_v = align_up(kHdrBytesV + (size_t)kTile * lim / 8, 16);
+    size_t at = 0;
+    L.ctrl = at; at += 256;
+    L.hist = at; at += 2 * 256 * 4;
+    L.enc = at; at += 2 * 256 * 4;
+    L.lut = at; at += 2 * kLutSize * 2;
+    L.table = at; at += align_up(2 * BH * (size_t)std::max(L.max_blocks, 1) * sizeof(BlockEntry), 256);
+    L.res = at; at += align_up(2 * (size_t)c.batch * kBT * c.n_kv_heads * kD * 2, 256);
+    L.partials = at; at += align_up((size_t)c.batch * c.n_q_heads * kMaxSplits * kPartialStride * 4, 256);
+    L.payload = at;
+    const size_t pay = BH * (size_t)L.max_blocks * (worst_k + worst_v) + 256;
+    L.payload_cap16 = pay / 16;
+    at += align_up(pay, 256);
+    L.total = at;
+    return L;
+}
+
+// ---- Huffman codebook (Section 3.1.2), canonical and length-limited --------------------------------------------
+// Two-queue construction over leaves sorted by (count, symbol); on equal weight a leaf is taken before a merged
+// node and merged nodes leave in creation order, which fixes the code lengths uniquely.
+void huffman_lengths(const std::vector<uint64_t> &f, std::vector<int> &len) {
+    const int n = (int)f.size();
+    std::vector<int> order(n);
+    std::iota(order.begin(), order.end(), 0);
+    std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return f[a] < f[b]; });
+    struct Node { uint64_t w; int kid[2]; };
+    std::vector<Node> nodes;
+    nodes.reserve(2 * n);
+    for (int i = 0; i < n; i++) nodes.push_back({f[order[i]], {-1, -1}});
+    int leaf = 0, ihead = n;
+    auto take = [&]() {
+        const bool has_leaf = leaf < n, has_int = ihead < (int)nodes.size();
+        if (has_leaf && (!has_int || nodes[leaf].w <= nodes[ihead].w)) return leaf++;
+        return ihead++;
+    };
+    for (int k = 0; k < n - 1; k++) {
+        const int a = take(), b = take();
+        nodes.push_back({nodes[a].w + nodes[b].w, {a, b}});
+    }
+    std::vector<int> depth(nodes.size(), 0);
+    for (int i = (int)nodes.size() - 1; i >= n; i--) {
+        depth[nodes[i].kid[0]] = depth[i] + 1;
+        depth[nodes[i].kid[1]] = depth[i] + 1;
+    }
+    len.assign(n, 0);
+    for (int i = 0; i < n; i++) len[order[i]] = depth[i];
+}
+
+void build_codebook_host(const uint32_t *hist, int n_sym, int max_len, uint8_t *len_out, uint32_t *code_out) {
+    std::vector<uint64_t> f(n_sym);
+    for (int s = 0; s < n_sym; s++) f[s] = hist[s] ? hist[s] : 1;  // later blocks reuse the codebook: no level unencodable
+    std::vector<int> len;
+    for (;;) {
+        huffman_lengths(f, len);
+        if (*std::max_element(len.begin(), len.end()) <= max_len) break;
+        for (auto &v : f) v = std::max<uint64_t>(1, (v + 1) >> 1);
+    }
+    std::memset(len_out, 0, 256);
+    std::memset(code_out, 0, 256 * sizeof(uint32_t));
+    std::vector<int> by(n_sym);
+    std::iota(by.begin(), by.end(), 0);
+    std::stable_sort(by.begin(), by.end(), [&](int a, int b) { return len[a] < len[b]; });
+    uint32_t code = 0;
+    for (int i = 0; i < n_sym; i++) {
+        const int s = by[i];
+        if (i) code = (code + 1) << (len[s] - len[by[i - 1]]);
+        len_out[s] = (uint8_t)len[s];
+        code_out[s] = code;
+    }
+}
+
+uint32_t reverse_bits(uint32_t v, int n) {
+    uint32_t r = 0;
+    for (int i = 0; i < n; i++) r |= ((v >> i) & 1u) << (n - 1 - i);
+    return r;
+}
+
+}  // namespace
+
+struct kvcomp_ctx {
+    kvcomp_config cfg;
+    Layout lay;
+    Geo geo;
+    uint8_t *arena;
+    bool have_codebook;
+    int n_blocks, n_res;
+    uint8_t len[2][256];
+    uint32_t code[2][256];
+    uint32_t max_size16;
+    int tune_splits, tune_stage;
+    bool profiling;
+    std::vector<hipEvent_t> events;  // pairs
+    size_t events_used;
+    int prof_launches;
+    double prof_ms;
+    // pinned host staging
+    Ctrl *h_ctrl;
+    uint32_t *h_hist;  // [2][256]
+    uint32_t *h_enc;   // [2][256]
+    uint16_t *h_lut;   // [2][4096]
+};
+
+namespace {
+
+kvcomp_status read_ctrl(kvcomp_ctx *ctx, hipStream_t s) {
+    HIP_TRY(hipMemcpyAsync(ctx->h_ctrl, ctx->geo.ctrl, sizeof(Ctrl), hipMemcpyDeviceToHost, s));
+    HIP_TRY(hipStreamSynchronize(s));
+    return KVCOMP_OK;
+}
+
+kvcomp_status fold_profile(kvcomp_ctx *ctx) {
+    for (size_t i = 0; i + 1 < ctx->events_used; i += 2) {
+        HIP_TRY(hipEventSynchronize(ctx->events[i + 1]));
+        float ms = 0.f;
+        HIP_TRY(hipEventElapsedTime(&ms, ctx->events[i], ctx->events[i + 1]));
+        ctx->prof_ms += ms;
+        ctx->prof_launches++;
+    }
+    ctx->events_used = 0;
+    return KVCOMP_OK;
+}
+
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+}  // namespace
+
+extern "C" {
+
+const char *kvcomp_last_error(void) { return g_err; }
+
+size_t kvcomp_arena_bytes(const kvcomp_config *cfg) {
+    if (!valid_cfg(cfg)) return 0;
+    return make_layout(*cfg).total;
+}
+
+kvcomp_status kvcomp_create(const kvcomp_config *cfg, void *d_arena, size_t arena_bytes, void *stream,
+                            kvcomp_ctx **out) {
+    if (!out) return fail(KVCOMP_ERR_INVALID_ARG, "out is NULL");
+    *out = nullptr;
+    if (!valid_cfg(cfg)) return fail(KVCOMP_ERR_INVALID_ARG, "invalid configuration");
+    if (!d_arena || (reinterpret_cast<uintptr_t>(d_arena) & 255u))
+        return fail(KVCOMP_ERR_INVALID_ARG, "arena must be a 256-byte aligned device pointer");
+    const Layout L = make_layout(*cfg);
+    if (arena_bytes < L.total) return fail(KVCOMP_ERR_CAPACITY, "arena has %zu bytes, %zu needed", arena_bytes, L.total);
+    if (L.payload_cap16 >= (1ull << 32)) return fail(KVCOMP_ERR_CAPACITY, "payload arena exceeds 64 GiB");
+    kvcomp_ctx *c = new (std::nothrow) kvcomp_ctx();
+    if (!c) return fail(KVCOMP_ERR_INVALID_ARG, "out of host memory");
+    c->cfg = *cfg;
+    c->lay = L;
+    c->arena = static_cast<uint8_t *>(d_arena);
+    c->have_codebook = false;
+    c->n_blocks = c->n_res = 0;
+    c->max_size16 = 0;
+    c->tune_splits = c->tune_stage = 0;
+    c->profiling = false;
+    c->events_used = 0;
+    c->prof_launches = 0;
+    c->prof_ms = 0.0;
+    Geo &g = c->geo;
+    g.B = cfg->batch;
+    g.H = cfg->n_kv_heads;
+    g.Hq = cfg->n_q_heads;
+    g.G = g.Hq / g.H;
+    g.max_blocks = std::max(L.max_blocks, 1);
+    g.two_eb[0] = 2.0f * cfg->rel_eb_k;
+    g.two_eb[1] = 2.0f * cfg->rel_eb_v;
+    g.n_sym[0] = n_sym_for(cfg->rel_eb_k);
+    g.n_sym[1] = n_sym_for(cfg->rel_eb_v);
+    g.ctrl = reinterpret_cast<Ctrl *>(c->arena + L.ctrl);
+    g.hist = reinterpret_cast<uint32_t *>(c->arena + L.hist);
+    g.enc = reinterpret_cast<uint32_t *>(c->arena + L.enc);
+    g.lut = reinterpret_cast<uint16_t *>(c->arena + L.lut);
+    g.table = reinterpret_cast<BlockEntry *>(c->arena + L.table);
+    g.res = reinterpret_cast<uint16_t *>(c->arena + L.res);
+    g.partials = reinterpret_cast<float *>(c->arena + L.partials);
+    g.payload = c->arena + L.payload;
+    void *pinned = nullptr;
+    const size_t pin_bytes = 256 + 2 * 256 * 4 + 2 * 256 * 4 + 2 * kLutSize * 2;
+    hipError_t e = hipHostMalloc(&pinned, pin_bytes, hipHostMallocDefault);
+    if (e != hipSuccess) {
+        delete c;
+        return fail(KVCOMP_ERR_HIP, "hipHostMalloc: %s", hipGetErrorString(e));
+    }
+    uint8_t *pb = static_cast<uint8_t *>(pinned);
+    c->h_ctrl = reinterpret_cast<Ctrl *>(pb);
+    c->h_hist = reinterpret_cast<uint32_t *>(pb + 256);
+    c->h_enc = reinterpret_cast<uint32_t *>(pb + 256 + 2048);
+    c->h_lut = reinterpret_cast<uint16_t *>(pb + 256 + 4096);
+    // control words, histogram, tables and the Block Offsets Array start at zero
+    e = launch_fill_zero(c->arena, L.res, static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) {
+        (void)hipHostFree(pinned);
+        delete c;
+        return fail(KVCOMP_ERR_HIP, "arena init: %s", hipGetErrorString(e));
+    }
+    *out = c;
+    return KVCOMP_OK;
+}
+
+kvcomp_status kvcomp_destroy(kvcomp_ctx *ctx) {
+    if (!ctx) return KVCOMP_OK;
+    for (hipEvent_t ev : ctx->events) (void)hipEventDestroy(ev);
+    (void)hipHostFree(ctx->h_ctrl);
+    delete ctx;
+    return KVCOMP_OK;
+}
+
+kvcomp_status kvcomp_reset(kvcomp_ctx *ctx, int keep_codebook, void *stream) {
+    if (!ctx) return fail(KVCOMP_ERR_INVALID_ARG, "ctx is NULL");
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    HIP_TRY(launch_fill_zero(ctx->geo.ctrl, 256, s));
+    ctx->n_blocks = ctx->n_res = 0;
+    ctx->max_size16 = 0;
+    if (!keep_codebook) ctx->have_codebook = false;
+    return KVCOMP_OK;
+}
+
+kvcomp_status kvcomp_build_codebook(kvcomp_ctx *ctx, const void *d_K, const void *d_V, int seq, void *stream) {
+    if (!ctx || !d_K || !d_V) return fail(KVCOMP_ERR_INVALID_ARG, "NULL argument");
+    if (!aligned16(d_K) || !aligned16(d_V)) return fail(KVCOMP_ERR_INVALID_ARG, "K/V must be 16-byte aligned");
+    if (seq < kBT || seq > ctx->cfg.max_seq)
+        return fail(KVCOMP_ERR_INVALID_ARG, "seq %d outside [64, max_seq=%d]", seq, ctx->cfg.max_seq);
+    const long long symbols = (long long)ctx->geo.B * ctx->geo.H * (seq / kBT) * kTile;
+    if (symbols >= (1ll << 32)) return fail(KVCOMP_ERR_INVALID_ARG, "more than 2^32 symbols per tensor");
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const Geo &g = ctx->geo;
+    HIP_TRY(launch_fill_zero(g.hist, 2 * 256 * 4, s));
+    HIP_TRY(launch_histogram(g, 0, static_cast<const uint16_t *>(d_K), seq, seq / kBT, s));
+    HIP_TRY(launch_histogram(g, 1, static_cast<const uint16_t *>(d_V), seq, seq / kBT, s));
+    HIP_TRY(hipMemcpyAsync(ctx->h_hist, g.hist, 2 * 256 * 4, hipMemcpyDeviceToHost, s));
+    kvcomp_status st = read_ctrl(ctx, s);
+    if (st) return st;
+    if (ctx->h_ctrl->nonfinite) {
+        (void)hipMemsetAsync(&g.ctrl->nonfinite, 0, sizeof(uint32_t), s);
+        (void)hipStreamSynchronize(s);
+        return fail(KVCOMP_ERR_NONFINITE, "input holds Inf or NaN");
+    }
+    for (int w = 0; w < 2; w++) {
+        build_codebook_host(ctx->h_hist + 256 * w, g.n_sym[w], code_len_limit(ctx->cfg), ctx->len[w], ctx->code[w]);
+        uint32_t *enc = ctx->h_enc + 256 * w;
+        uint16_t *lut = ctx->h_lut + kLutSize * w;
+        std::memset(enc, 0, 256 * 4);
+        std::memset(lut, 0, kLutSize * 2);
+        for (int sy = 0; sy < 256; sy++) {
+            const int L = ctx->len[w][sy];
+            if (!L) continue;
+            const uint32_t rev = reverse_bits(ctx->code[w][sy], L);
+            enc[sy] = ((uint32_t)L << 16) | rev;
+            for (uint32_t k = 0; k < (1u << (kLutBits - L)); k++) lut[rev | (k << L)] = (uint16_t)((sy << 8) | L);
+        }
+    }
+    HIP_TRY(hipMemcpyAsync(g.enc, ctx->h_enc, 2 * 256 * 4, hipMemcpyHostToDevice, s));
+    HIP_TRY(hipMemcpyAsync(g.lut, ctx->h_lut, 2 * kLutSize * 2, hipMemcpyHostToDevice, s));
+    HIP_TRY(hipStreamSynchronize(s));
+    ctx->have_codebook = true;
+    return KVCOMP_OK;
+}
+
+kvcomp_status kvcomp_compress_blocks(kvcomp_ctx *ctx, const void *d_K, const void *d_V, int seq, void *stream) {
+    if (!ctx || !d_K || !d_V) return fail(KVCOMP_ERR_INVALID_ARG, "NULL argument");
+    if (!aligned16(d_K) || !aligned16(d_V)) return fail(KVCOMP_ERR_INVALID_ARG, "K/V must be 16-byte aligned");
+    if (!ctx->have_codebook) return fail(KVCOMP_ERR_STATE, "no codebook: call kvcomp_build_codebook first");
+    if (ctx->n_blocks || ctx->n_res) return fail(KVCOMP_ERR_STATE, "cache is not empty");
+    if (seq < 1) return fail(KVCOMP_ERR_INVALID_ARG, "seq must be positive");
+    if (seq > ctx->cfg.max_seq) return fail(KVCOMP_ERR_CAPACITY, "seq %d exceeds max_seq %d", seq, ctx->cfg.max_seq);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const Geo &g = ctx->geo;
+    const int nb = seq / kBT;
+    const uint16_t *K = static_cast<const uint16_t *>(d_K), *V = static_cast<const uint16_t *>(d_V);
+    HIP_TRY(launch_encode(g, K, V, seq, nb, 0, s));
+    HIP_TRY(launch_copy_tail(g, K, V, seq, nb * kBT, seq - nb * kBT, s));
+    kvcomp_status st = read_ctrl(ctx, s);
+    if (st) return st;
+    if (ctx->h_ctrl->nonfinite) {
+        (void)launch_fill_zero(g.ctrl, 256, s);
+        return fail(KVCOMP_ERR_NONFINITE, "input holds Inf or NaN");
+    }
+    ctx->n_blocks = nb;
+    ctx->n_res = seq - nb * kBT;
+    ctx->max_size16 = ctx->h_ctrl->max_size16;
+    return KVCOMP_OK;
+}
+
+kvcomp_status kvcomp_append_token(kvcomp_ctx *ctx, const void *d_k_new, const void *d_v_new, void *stream) {
+    if (!ctx || !d_k_new || !d_v_new) return fail(KVCOMP_ERR_INVALID_ARG, "NULL argument");
+    if (!aligned16(d_k_new) || !aligned16(d_v_new)) return fail(KVCOMP_ERR_INVALID_ARG, "k/v must be 16-byte aligned");
+    if (!ctx->have_codebook) return fail(KVCOMP_ERR_STATE, "no codebook: call kvcomp_build_codebook first");
+    if (ctx->n_blocks * kBT + ctx->n_res + 1 > ctx->cfg.max_seq)
+        return fail(KVCOMP_ERR_CAPACITY, "max_seq %d reached", ctx->cfg.max_seq);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const Geo &g = ctx->geo;
+    HIP_TRY(launch_append(g, static_cast<const uint16_t *>(d_k_new), static_cast<const uint16_t *>(d_v_new), ctx->n_res, s));
+    ctx->n_res++;
+    if (ctx->n_res == kBT) {  // the buffer is full: compress it as one block per (batch, head) and append the records
+        const uint16_t *rk = g.res, *rv = g.res + (size_t)g.B * kBT * g.H * kD;
+        HIP_TRY(launch_encode(g, rk, rv, kBT, 1, ctx->n_blocks, s));
+        ctx->n_blocks++;
+        ctx->n_res = 0;
+    }
+    return KVCOMP_OK;
+}
+
+kvcomp_status kvcomp_attn_decode(kvcomp_ctx *ctx, const void *d_q, float scale, float *d_out, void *stream) {
+    if (!ctx || !d_q || !d_out) return fail(KVCOMP_ERR_INVALID_ARG, "NULL argument");
+    if (ctx->n_blocks == 0 && ctx->n_res == 0) return fail(KVCOMP_ERR_STATE, "cache is empty");
+    if (ctx->n_blocks && !ctx->have_codebook) return fail(KVCOMP_ERR_STATE, "no codebook");
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const Geo &g = ctx->geo;
+    // Work split: one wave per block pair while that still fills the chip, 4 waves per workgroup.
+    int n_splits = ctx->tune_splits;
+    if (n_splits <= 0) {
+        const long long tasks = (long long)g.B * g.H * ctx->n_blocks;
+        long long per_wave = (tasks + 8191) / 8192;
+        if (per_wave < 1) per_wave = 1;
+        const long long bps = 4 * per_wave;
+        n_splits = (int)((ctx->n_blocks + bps - 1) / bps);
+    }
+    n_splits = std::max(1, std::min({n_splits, (int)kMaxSplits, std::max(ctx->n_blocks, 1)}));
+    int stage = ctx->tune_stage;
+    if (stage <= 0) stage = (int)align_up((size_t)ctx->max_size16 * 16 + 16, 256);
+    stage = std::max(stage, 4608);
+    stage = (int)align_up(stage, 16);
+    const size_t lds_fixed = 2 * kLutSize * 2 + (size_t)g.G * kD * 4 + 4 * (size_t)g.G * kD * 4;
+    const size_t lds_max = 160 * 1024;
+    if (lds_fixed + 4 * (size_t)stage > lds_max) stage = (int)((lds_max - lds_fixed) / 4 / 16 * 16);
+    hipEvent_t ev0 = nullptr, ev1 = nullptr;
+    if (ctx->profiling) {
+        if (ctx->events_used + 2 > ctx->events.size()) {
+            if (ctx->events.size() >= 8192) {
+                kvcomp_status st = fold_profile(ctx);
+                if (st) return st;
+            } else {
+                for (int i = 0; i < 2; i++) {
+                    hipEvent_t ev;
+                    HIP_TRY(hipEventCreate(&ev));
+                    ctx->events.push_back(ev);
+                }
+            }
+        }
+        ev0 = ctx->events[ctx->events_used];
+        ev1 = ctx->events[ctx->events_used + 1];
+        ctx->events_used += 2;
+    }
+    HIP_TRY(launch_fused_attn(g, static_cast<const uint16_t *>(d_q), scale, d_out, ctx->n_blocks, ctx->n_res, n_splits,
+                              stage, ev0, ev1, s));
+    return KVCOMP_OK;
+}
+
+kvcomp_status kvcomp_get_stats(kvcomp_ctx *ctx, kvcomp_stats *o, void *stream) {
+    if (!ctx || !o) return fail(KVCOMP_ERR_INVALID_ARG, "NULL argument");
+    kvcomp_status st = read_ctrl(ctx, static_cast<hipStream_t>(stream));
+    if (st) return st;
+    const Ctrl &c = *ctx->h_ctrl;
+    const long long BH = (long long)ctx->geo.B * ctx->geo.H;
+    const long long nblk = BH * ctx->n_blocks;
+    const long long tokens = (long long)ctx->n_blocks * kBT + ctx->n_res;
+    o->n_blocks = ctx->n_blocks;
+    o->n_res = ctx->n_res;
+    o->raw_bytes = 2 * BH * tokens * kD * 2;
+    o->record_bytes_k = (int64_t)c.record16[0] * 16;
+    o->record_bytes_v = (int64_t)c.record16[1] * 16;
+    o->header_bytes = nblk * (kHdrBytesK + kHdrBytesV);
+    o->offsets_bytes = 2 * nblk * (long long)sizeof(BlockEntry);
+    o->residual_bytes = 2 * BH * ctx->n_res * kD * 2;
+    o->payload_bits_k = (int64_t)c.payload_bits[0];
+    o->payload_bits_v = (int64_t)c.payload_bits[1];
+    o->stored_bytes = o->record_bytes_k + o->record_bytes_v + o->offsets_bytes + o->residual_bytes;
+    o->max_record_bytes = (int64_t)c.max_size16 * 16;
+    o->compression_ratio = o->stored_bytes ? (double)o->raw_bytes / (double)o->stored_bytes : 0.0;
+    return KVCOMP_OK;
+}
+
+kvcomp_status kvcomp_debug_codes(kvcomp_ctx *ctx, int which, const void *d_in, int seq, void *d_scratch,
+                                 size_t scratch_bytes, uint8_t *h_codes, uint16_t *h_minmax, void *stream) {
+    if (!ctx || !d_in || !d_scratch || !h_codes || !h_minmax) return fail(KVCOMP_ERR_INVALID_ARG, "NULL argument");
+    if (which != 0 && which != 1) return fail(KVCOMP_ERR_INVALID_ARG, "which must be 0 (K) or 1 (V)");
+    if (!aligned16(d_in) || !aligned16(d_scratch)) return fail(KVCOMP_ERR_INVALID_ARG, "pointers must be 16-byte aligned");
+    if (seq < kBT) return fail(KVCOMP_ERR_INVALID_ARG, "seq must hold a full block");
+    const Geo &g = ctx->geo;
+    const size_t nblk = (size_t)g.B * g.H * (seq / kBT);
+    const size_t units = which == 0 ? kD : kBT;
+    const size_t codes_bytes = nblk * kTile, mm_bytes = nblk * units * 4;
+    if (scratch_bytes < codes_bytes + mm_bytes) return fail(KVCOMP_ERR_CAPACITY, "scratch too small");
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    uint8_t *dc = static_cast<uint8_t *>(d_scratch);
+    uint16_t *dm = reinterpret_cast<uint16_t *>(dc + codes_bytes);
+    HIP_TRY(launch_debug_codes(g, which, static_cast<const uint16_t *>(d_in), seq, seq / kBT, dc, dm, s));
+    HIP_TRY(hipMemcpyAsync(h_codes, dc, codes_bytes, hipMemcpyDeviceToHost, s));
+    HIP_TRY(hipMemcpyAsync(h_minmax, dm, mm_bytes, hipMemcpyDeviceToHost, s));
+    HIP_TRY(hipStreamSynchronize(s));
+    return KVCOMP_OK;
+}
+
+kvcomp_status kvcomp_get_histogram(kvcomp_ctx *ctx, int which, uint32_t *h_hist256, void *stream) {
+    if (!ctx || !h_hist256 || (which != 0 && which != 1)) return fail(KVCOMP_ERR_INVALID_ARG, "bad argument");
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    HIP_TRY(hipMemcpyAsync(h_hist256, ctx->geo.hist + 256 * which, 256 * 4, hipMemcpyDeviceToHost, s));
+    HIP_TRY(hipStreamSynchronize(s));
+    return KVCOMP_OK;
+}
+
+kvcomp_status kvcomp_get_codebook(kvcomp_ctx *ctx, int which, uint8_t *h_len256, uint32_t *h_code256) {
+    if (!ctx || !h_len256 || !h_code256 || (which != 0 && which != 1)) return fail(KVCOMP_ERR_INVALID_ARG, "bad argument");
+    if (!ctx->have_codebook) return fail(KVCOMP_ERR_STATE, "no codebook");
+    std::memcpy(h_len256, ctx->len[which], 256);
+    std::memcpy(h_code256, ctx->code[which], 256 * sizeof(uint32_t));
+    return KVCOMP_OK;
+}
+
+kvcomp_status kvcomp_get_block_entry(kvcomp_ctx *ctx, int which, int b, int h, int blk, uint32_t *h_off16,
+                                     uint32_t *h_size16, void *stream) {
+    if (!ctx || !h_off16 || !h_size16 || (which != 0 && which != 1)) return fail(KVCOMP_ERR_INVALID_ARG, "bad argument");
+    const Geo &g = ctx->geo;
+    if (b < 0 || b >= g.B || h < 0 || h >= g.H || blk < 0 || blk >= ctx->n_blocks)
+        return fail(KVCOMP_ERR_INVALID_ARG, "block index out of range");
+    BlockEntry e;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const BlockEntry *src = g.table + ((size_t)which * g.B * g.H + (size_t)b * g.H + h) * g.max_blocks + blk;
+    HIP_TRY(hipMemcpyAsync(&e, src, sizeof(e), hipMemcpyDeviceToHost, s));
+    HIP_TRY(hipStreamSynchronize(s));
+    *h_off16 = e.off16;
+    *h_size16 = e.size16;
+    return KVCOMP_OK;
+}
+
+kvcomp_status kvcomp_get_block(kvcomp_ctx *ctx, int which, int b, int h, int blk, void *h_buf, size_t cap,
+                               size_t *h_bytes, void *stream) {
+    if (!h_buf || !h_bytes) return fail(KVCOMP_ERR_INVALID_ARG, "NULL argument");
+    uint32_t off16, size16;
+    kvcomp_status st = kvcomp_get_block_entry(ctx, which, b, h, blk, &off16, &size16, stream);
+    if (st) return st;
+    const size_t bytes = (size_t)size16 * 16;
+    *h_bytes = bytes;
+    if (bytes > cap) return fail(KVCOMP_ERR_CAPACITY, "record has %zu bytes, buffer %zu", bytes, cap);
+    if ((size_t)off16 + size16 > ctx->lay.payload_cap16) return fail(KVCOMP_ERR_STATE, "corrupt block entry");
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    HIP_TRY(hipMemcpyAsync(h_buf, ctx->geo.payload + (size_t)off16 * 16, bytes, hipMemcpyDeviceToHost, s));
+    HIP_TRY(hipStreamSynchronize(s));
+    return KVCOMP_OK;
+}
+
+kvcomp_status kvcomp_get_residual(kvcomp_ctx *ctx, int which, uint16_t *h_buf, int *h_n_res, void *stream) {
+    if (!ctx || !h_buf || !h_n_res || (which != 0 && which != 1)) return fail(KVCOMP_ERR_INVALID_ARG, "bad argument");
+    const Geo &g = ctx->geo;
+    const size_t n = (size_t)g.B * kBT * g.H * kD;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    HIP_TRY(hipMemcpyAsync(h_buf, g.res + n * which, n * 2, hipMemcpyDeviceToHost, s));
+    HIP_TRY(hipStreamSynchronize(s));
+    *h_n_res = ctx->n_res;
+    return KVCOMP_OK;
+}
+
+kvcomp_status kvcomp_set_tuning(kvcomp_ctx *ctx, int n_splits, int stage_bytes) {
+    if (!ctx || n_splits < 0 || stage_bytes < 0) return fail(KVCOMP_ERR_INVALID_ARG, "bad argument");
+    ctx->tune_splits = n_splits;
+    ctx->tune_stage = stage_bytes;
+    return KVCOMP_OK;
+}
+
+kvcomp_status kvcomp_set_profiling(kvcomp_ctx *ctx, int enable) {
+    if (!ctx) return fail(KVCOMP_ERR_INVALID_ARG, "ctx is NULL");
+    ctx->profiling = enable != 0;
+    return KVCOMP_OK;
+}
+
+kvcomp_status kvcomp_get_profile(kvcomp_ctx *ctx, int *h_launches, double *h_total_ms) {
+    if (!ctx || !h_launches || !h_total_ms) return fail(KVCOMP_ERR_INVALID_ARG, "NULL argument");
+    kvcomp_status st = fold_profile(ctx);
+    if (st) return st;
+    *h_launches = ctx->prof_launches;
+    *h_total_ms = ctx->prof_ms;
+    ctx->prof_launches = 0;
+    ctx->prof_ms = 0.0;
+    return KVCOMP_OK;
+}
+
+size_t kvcomp_baseline_workspace_bytes(const kvcomp_config *cfg) {
+    if (!cfg || cfg->batch < 1 || cfg->n_q_heads < 1) return 0;
+    return (size_t)cfg->batch * cfg->n_q_heads * kMaxSplits * kPartialStride * 4;
+}
+
+kvcomp_status kvcomp_baseline_fp16_attn(const kvcomp_config *cfg, const void *d_K, const void *d_V, int seq,
+                                        const void *d_q, float scale, float *d_out, void *d_workspace,
+                                        size_t workspace_bytes, int n_splits, void *stream) {
+    if (!cfg || !d_K || !d_V || !d_q || !d_out || !d_workspace) return fail(KVCOMP_ERR_INVALID_ARG, "NULL argument");
+    if (!aligned16(d_K) || !aligned16(d_V) || !aligned16(d_q)) return fail(KVCOMP_ERR_INVALID_ARG, "pointers must be 16-byte aligned");
+    if (cfg->batch < 1 || cfg->n_kv_heads < 1 || cfg->n_q_heads % cfg->n_kv_heads || cfg->head_dim != kD)
+        return fail(KVCOMP_ERR_INVALID_ARG, "invalid configuration");
+    const int G = cfg->n_q_heads / cfg->n_kv_heads;
+    if (G != 1 && G != 2 && G != 4 && G != 8) return fail(KVCOMP_ERR_INVALID_ARG, "group size must be 1, 2, 4 or 8");
+    if (seq < 1) return fail(KVCOMP_ERR_INVALID_ARG, "seq must be positive");
+    if (workspace_bytes < kvcomp_baseline_workspace_bytes(cfg)) return fail(KVCOMP_ERR_CAPACITY, "workspace too small");
+    if (n_splits <= 0) {
+        const int bh = cfg->batch * cfg->n_kv_heads;
+        n_splits = std::min({(int)kMaxSplits, std::max(1, seq / 256), std::max(1, (2048 + bh - 1) / bh)});
+    }
+    n_splits = std::max(1, std::min(n_splits, (int)kMaxSplits));
+    HIP_TRY(launch_baseline_attn(cfg->batch, cfg->n_kv_heads, cfg->n_q_heads, static_cast<const uint16_t *>(d_K),
+                                 static_cast<const uint16_t *>(d_V), seq, static_cast<const uint16_t *>(d_q), scale, d_out,
+                                 static_cast<float *>(d_workspace), n_splits, static_cast<hipStream_t>(stream)));
+    return KVCOMP_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,78 @@
+// Internal declarations shared by the host side of libkvcomp and its HIP kernels (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace kvc {
+
+constexpr int kD = 128;        // head_dim
+constexpr int kBT = 64;        // tokens per 2D block
+constexpr int kTile = kD * kBT;  // symbols per block
+constexpr int kLutBits = 12;   // decode table index width = longest code word allowed
+constexpr int kLutSize = 1 << kLutBits;
+
+// Record layout (Section 3.2.2: per-thread bit counts + one contiguous chunk per 2D block):
+//   K: [128 x {min,max} fp16][64 x u16 slice bits][payload words][pad to 16 B]
+//   V: [ 64 x {min,max} fp16][128 x u16 slice bits][payload words][pad to 16 B]
+constexpr int kMinMaxBytesK = 4 * kD;
+constexpr int kMinMaxBytesV = 4 * kBT;
+constexpr int kHdrBytesK = kMinMaxBytesK + 2 * kBT;   // 640
+constexpr int kHdrBytesV = kMinMaxBytesV + 2 * kD;    // 512
+constexpr int kMaxPayloadBytes = kTile * kLutBits / 8;  // 12288
+constexpr int kMaxRecordBytes = kHdrBytesK + kMaxPayloadBytes + 16;
+
+// Block Offsets Array entry (Section 3): where the record of a 2D block lives, in 16-byte units from the start of
+// the payload arena, and how long it is.
+struct BlockEntry {
+    uint32_t off16;
+    uint32_t size16;
+};
+
+// Device-side control words, first bytes of the arena.
+struct Ctrl {
+    uint32_t tail16;        // first free 16-byte unit of the payload arena
+    uint32_t max_size16;    // largest record so far
+    uint32_t nonfinite;     // set when an input value was Inf/NaN
+    uint32_t pad;
+    unsigned long long payload_bits[2];
+    unsigned long long record16[2];  // sum of record sizes per tensor, 16-byte units
+};
+
+// Geometry + device pointers, passed by value to kernels.
+struct Geo {
+    int B, H, Hq, G;
+    int max_blocks;
+    float two_eb[2];   // bin width factor 2*rel_eb
+    int n_sym[2];
+    Ctrl *ctrl;
+    uint32_t *hist;          // [2][256]
+    uint32_t *enc;           // [2][256]  (len << 16) | bit-reversed code word
+    uint16_t *lut;           // [2][4096] (symbol << 8) | len, indexed by the next 12 stream bits
+    BlockEntry *table;       // [2][B*H][max_blocks]
+    uint16_t *res;           // [2][B][64][H][128] fp16
+    float *partials;         // [B*Hq][max_splits][kPartialStride]
+    uint8_t *payload;        // record arena
+};
+
+constexpr int kPartialStride = kD + 2;  // o[128], m, l
+constexpr int kMaxSplits = 64;
+
+// ---- launches implemented in the .hip files ----
+hipError_t launch_histogram(const Geo &g, int which, const uint16_t *X, int seq_stride, int n_blk_per_bh,
+                            hipStream_t s);
+hipError_t launch_debug_codes(const Geo &g, int which, const uint16_t *X, int seq_stride, int n_blk_per_bh,
+                              uint8_t *d_codes, uint16_t *d_minmax, hipStream_t s);
+// size pass -> table[...].size16 ; place -> off16 + ctrl ; write pass -> records
+hipError_t launch_encode(const Geo &g, const uint16_t *XK, const uint16_t *XV, int seq_stride, int n_blk_per_bh,
+                         int dst_blk0, hipStream_t s);
+hipError_t launch_copy_tail(const Geo &g, const uint16_t *XK, const uint16_t *XV, int seq, int first_tok, int n_tok,
+                            hipStream_t s);
+hipError_t launch_append(const Geo &g, const uint16_t *k_new, const uint16_t *v_new, int slot, hipStream_t s);
+hipError_t launch_fused_attn(const Geo &g, const uint16_t *q, float scale, float *out, int n_blocks, int n_res,
+                             int n_splits, int stage_bytes, hipEvent_t ev0, hipEvent_t ev1, hipStream_t s);
+hipError_t launch_baseline_attn(int B, int H, int Hq, const uint16_t *K, const uint16_t *V, int seq, const uint16_t *q,
+                                float scale, float *out, float *partials, int n_splits, hipStream_t s);
+hipError_t launch_fill_zero(void *p, size_t bytes, hipStream_t s);
+
+}  // namespace kvc

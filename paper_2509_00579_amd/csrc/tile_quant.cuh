@@ -1,0 +1,147 @@
+// Device code shared by the store-side kernels: load one 2D block (64 tokens x 128 channels, fp16) with a
+// 256-thread workgroup, reduce the min/max of every quantization unit and produce the 8-bit codes in registers.
+//
+// Quantization follows Section 3.1.1 (K: channel-wise inside the block, V: token-wise) with the relative scale of
+// Section 4.2 read as bin width = 2 * rel_eb * (max - min):
+//     code = round_half_even((x - min) / width), clamped to [0, n_sym - 1];  range 0 -> code 0.
+// All arithmetic is IEEE binary32, one operation at a time (this file is compiled with -ffp-contract=off and
+// correctly rounded division), so that an independent implementation of the same operation sequence agrees bit
+// for bit.
+//
+// Thread map (tid = 64*w + l): load i in 0..3 covers token 16*w + 4*i + l/16, channels 8*(l%16) .. +7, i.e. one wave
+// load instruction reads four contiguous 256-byte rows.
+#pragma once
+
+#include <hip/hip_fp16.h>
+
+#include "kvcomp_internal.h"
+
+namespace kvc {
+
+struct TileRegs {
+    float x[4][8];       // values
+    uint32_t code[4][8];  // after quantize_tile
+};
+
+__device__ __forceinline__ int tile_token(int tid, int i) { return 16 * (tid >> 6) + 4 * i + ((tid & 63) >> 4); }
+__device__ __forceinline__ int tile_chan0(int tid) { return (tid & 15) * 8; }
+
+__device__ __forceinline__ float half_bits_to_float(uint32_t h) {
+    return __half2float(__ushort_as_half((unsigned short)h));
+}
+__device__ __forceinline__ uint32_t float_to_half_bits(float f) {  // f is exactly representable
+    return (uint32_t)__half_as_ushort(__float2half_rn(f));
+}
+
+// Returns true if any loaded value is Inf/NaN.
+__device__ __forceinline__ bool load_tile(const uint16_t *X, int seq_stride, int H, int b, int h, int blk, int tid,
+                                          TileRegs &r) {
+    bool bad = false;
+    const int c0 = tile_chan0(tid);
+#pragma unroll
+    for (int i = 0; i < 4; i++) {
+        const int t = blk * kBT + tile_token(tid, i);
+        const size_t off = (((size_t)b * (size_t)seq_stride + (size_t)t) * (size_t)H + (size_t)h) * kD + (size_t)c0;
+        const uint4 v = *reinterpret_cast<const uint4 *>(X + off);
+        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int k = 0; k < 4; k++) {
+            const uint32_t lo = w[k] & 0xffffu, hi = w[k] >> 16;
+            bad |= ((lo & 0x7c00u) == 0x7c00u) | ((hi & 0x7c00u) == 0x7c00u);
+            r.x[i][2 * k] = half_bits_to_float(lo);
+            r.x[i][2 * k + 1] = half_bits_to_float(hi);
+        }
+    }
+    return bad;
+}
+
+__device__ __forceinline__ uint32_t quant_code(float x, float mn, float step, float range, float top) {
+    const float d = x - mn;
+    const float q = d / step;
+    float k = rintf(q);
+    k = fminf(fmaxf(k, 0.0f), top);
+    return range == 0.0f ? 0u : (uint32_t)k;
+}
+
+__device__ __forceinline__ float canon_zero(float v) { return v == 0.0f ? 0.0f : v; }
+
+// LDS scratch needed by quantize_tile.
+struct QuantShared {
+    float part_mn[4][kD];
+    float part_mx[4][kD];
+    float unit_mn[kD];  // K: per channel;  V: per token (first 64 entries)
+    float unit_mx[kD];
+};
+
+// Computes r.code and leaves the unit minima / maxima in sh.unit_mn / sh.unit_mx.
+// Contains __syncthreads(): must be called by all 256 threads of the workgroup.
+template <int WHICH>
+__device__ __forceinline__ void quantize_tile(TileRegs &r, QuantShared &sh, int tid, float two_eb, int n_sym) {
+    const float top = (float)(n_sym - 1);
+    if (WHICH == 0) {
+        float mn[8], mx[8];
+#pragma unroll
+        for (int k = 0; k < 8; k++) {
+            mn[k] = fminf(fminf(r.x[0][k], r.x[1][k]), fminf(r.x[2][k], r.x[3][k]));
+            mx[k] = fmaxf(fmaxf(r.x[0][k], r.x[1][k]), fmaxf(r.x[2][k], r.x[3][k]));
+            mn[k] = fminf(mn[k], __shfl_xor(mn[k], 16));
+            mx[k] = fmaxf(mx[k], __shfl_xor(mx[k], 16));
+            mn[k] = fminf(mn[k], __shfl_xor(mn[k], 32));
+            mx[k] = fmaxf(mx[k], __shfl_xor(mx[k], 32));
+        }
+        const int w = tid >> 6, c0 = tile_chan0(tid);
+        if (((tid & 63) >> 4) == 0) {
+#pragma unroll
+            for (int k = 0; k < 8; k++) {
+                sh.part_mn[w][c0 + k] = mn[k];
+                sh.part_mx[w][c0 + k] = mx[k];
+            }
+        }
+        __syncthreads();
+        if (tid < kD) {
+            const float a = fminf(fminf(sh.part_mn[0][tid], sh.part_mn[1][tid]),
+                                  fminf(sh.part_mn[2][tid], sh.part_mn[3][tid]));
+            const float z = fmaxf(fmaxf(sh.part_mx[0][tid], sh.part_mx[1][tid]),
+                                  fmaxf(sh.part_mx[2][tid], sh.part_mx[3][tid]));
+            sh.unit_mn[tid] = canon_zero(a);
+            sh.unit_mx[tid] = canon_zero(z);
+        }
+        __syncthreads();
+#pragma unroll
+        for (int k = 0; k < 8; k++) {
+            const float a = sh.unit_mn[c0 + k], z = sh.unit_mx[c0 + k];
+            const float range = z - a;
+            const float step = two_eb * range;
+#pragma unroll
+            for (int i = 0; i < 4; i++) r.code[i][k] = quant_code(r.x[i][k], a, step, range, top);
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < 4; i++) {
+            float a = r.x[i][0], z = r.x[i][0];
+#pragma unroll
+            for (int k = 1; k < 8; k++) {
+                a = fminf(a, r.x[i][k]);
+                z = fmaxf(z, r.x[i][k]);
+            }
+#pragma unroll
+            for (int m = 1; m < 16; m <<= 1) {
+                a = fminf(a, __shfl_xor(a, m));
+                z = fmaxf(z, __shfl_xor(z, m));
+            }
+            a = canon_zero(a);
+            z = canon_zero(z);
+            if ((tid & 15) == 0) {
+                sh.unit_mn[tile_token(tid, i)] = a;
+                sh.unit_mx[tile_token(tid, i)] = z;
+            }
+            const float range = z - a;
+            const float step = two_eb * range;
+#pragma unroll
+            for (int k = 0; k < 8; k++) r.code[i][k] = quant_code(r.x[i][k], a, step, range, top);
+        }
+        __syncthreads();
+    }
+}
+
+}  // namespace kvc
