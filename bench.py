@@ -1,0 +1,252 @@
+"""Benchmark of the KVComp hot path on one MI355X.
+
+One step = one pass of the whole path over a seeded synthetic workload: histogram + codebook, compress the prompt's
+KV cache, then `decode_steps` decode steps, each appending one new token per sequence and running the fused
+decode attention over the compressed blocks plus the fp16 buffer.  The metric is the fused decode-attention
+throughput on COMPRESSED bytes (GB/s, also as a fraction of the HBM peak), next to the compression ratio, the same-GPU
+uncompressed fp16 decode attention, and the CPU oracle timed on the host cores.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c1]
+
+Prints one JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+HBM_PEAK_GBPS = 8000.0  # MI355X HBM3E, published
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="c1", choices=["c0", "c1", "c2", "c3", "c4"])
+    ap.add_argument("--rel-eb", type=float, default=None, help="override the workload's relative error bound")
+    ap.add_argument("--no-graph", action="store_true", help="launch the decode loop eagerly instead of replaying a HIP graph")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--n-splits", type=int, default=0)
+    ap.add_argument("--stage-bytes", type=int, default=0)
+    return ap.parse_args()
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        sys.exit("bench.py: this build runs on ONE GPU (the path shards by batch/head without exchange; see DESIGN.md); "
+                 "--gpus N with N > 1 is not supported")
+
+    import torch
+
+    import workloads as W
+    from paper_2509_00579_amd import binding
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    w = W.CONFIGS[args.workload]
+    rel_eb = args.rel_eb if args.rel_eb is not None else w.rel_eb
+    B, H, Hq, S, T = w.batch, w.n_kv_heads, w.n_q_heads, w.seq, w.decode_steps
+    scale = 1.0 / np.sqrt(128.0)
+
+    # ---- inputs: generated on the host from the seed, resident in HBM before any timed region ----
+    Kx, Vx = W.make_kv(B, H, S, w.seed)
+    qs = W.make_queries(B, Hq, T, w.seed)
+    kn, vn = W.make_new_tokens(B, H, T, w.seed)
+    dK, dV = torch.from_numpy(Kx).cuda(), torch.from_numpy(Vx).cuda()
+    dq, dkn, dvn = torch.from_numpy(qs).cuda(), torch.from_numpy(kn).cuda(), torch.from_numpy(vn).cuda()
+    out = torch.empty((B, Hq, 128), dtype=torch.float32, device="cuda")
+    max_seq = (S + T + 63) // 64 * 64
+    cache = binding.KVCompCache(B, H, Hq, max_seq, rel_eb, rel_eb)
+    cache.set_tuning(args.n_splits, args.stage_bytes)
+
+    def store():
+        cache.reset(keep_codebook=False)
+        cache.build_codebook(dK, dV)
+        cache.compress_blocks(dK, dV)
+
+    def decode_loop():
+        for i in range(T):
+            cache.append_token(dkn[i], dvn[i])
+            cache.attn_decode(dq[i], scale, out)
+
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
+
+    # ---- warm-up (eager; also sizes the kernel's LDS) ----
+    for _ in range(max(args.warmup, 1)):
+        store()
+        decode_loop()
+    torch.cuda.synchronize()
+    stats_end = cache.stats()
+
+    # algorithmic bytes of each decode step i (token i appended before it): records + offsets + fp16 buffer
+    # + q + out + split partials (written once, read once) + the two lookup tables
+    def decode_bytes(n_blocks, n_res, n_splits_est):
+        blocks = B * H * n_blocks
+        rec = rec0 + (n_blocks - nb0) * flush_bytes
+        return (rec + 2 * blocks * 8 + 2 * B * H * n_res * 128 * 2 + B * Hq * 128 * 2 + B * Hq * 128 * 4
+                + 2 * n_splits_est * B * Hq * 130 * 4 + 2 * 4096 * 2)
+
+    store()
+    stats0 = cache.stats()
+    torch.cuda.synchronize()
+    nb0 = stats0["n_blocks"]
+    rec0 = stats0["record_bytes_k"] + stats0["record_bytes_v"]
+    n_flush = stats_end["n_blocks"] - nb0
+    flush_bytes = ((stats_end["record_bytes_k"] + stats_end["record_bytes_v"] - rec0) / n_flush) if n_flush else 0.0
+    per_wave = max(1, (B * H * nb0 + 8191) // 8192)
+    n_splits_est = args.n_splits or max(1, min(64, -(-nb0 // (4 * per_wave))))
+    step_bytes = []
+    for i in range(T):
+        tokens = S + i + 1
+        step_bytes.append(decode_bytes(tokens // 64, tokens % 64, n_splits_est))
+    loop_bytes = float(sum(step_bytes))
+
+    # ---- capture the decode loop (launch-bound at this size) in a HIP graph ----
+    graph = None
+    if not args.no_graph:
+        try:
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g):
+                decode_loop()
+            graph = g
+        except Exception as e:  # noqa: BLE001
+            print(f"bench.py: graph capture failed ({e}); running the decode loop eagerly", file=sys.stderr)
+            graph = None
+        torch.cuda.synchronize()
+
+    def run_decode():
+        if graph is not None:
+            graph.replay()
+        else:
+            decode_loop()
+
+    # ---- timed region: exactly K steps ----
+    torch.cuda.synchronize()
+    store_ms, decode_ms = [], []
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        ev[0].record()
+        store()              # synchronises (histogram and sizes cross to the host)
+        ev[1].record()
+        run_decode()
+        ev[2].record()
+        ev[2].synchronize()
+        store_ms.append(ev[0].elapsed_time(ev[1]))
+        decode_ms.append(ev[1].elapsed_time(ev[2]))
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    dec_ms = float(np.mean(decode_ms))
+    value = loop_bytes / (dec_ms * 1e-3) / 1e9
+    assert torch.isfinite(out).all()
+
+    # ---- dominant kernel: HIP events around every fused-kernel launch (eager pass, same process) ----
+    cache.set_profiling(True)
+    store()
+    decode_loop()
+    launches, total_ms = cache.get_profile()
+    cache.set_profiling(False)
+    kern_ms = total_ms / max(launches, 1)
+    fused_bytes = [b - B * Hq * 128 * 4 - n_splits_est * B * Hq * 130 * 4 for b in step_bytes]  # no out, partials once
+    kern_bytes = float(np.mean(fused_bytes))
+    achieved = kern_bytes / (kern_ms * 1e-3) / 1e9
+
+    # ---- same-GPU uncompressed fp16 decode attention on the prompt ----
+    base = binding.BaselineFp16Attention(B, H, Hq)
+    for i in range(3):
+        base(dK, dV, dq[i % T], scale, out)
+    torch.cuda.synchronize()
+    nrep = max(8, min(64, T))
+    bgraph = None
+    if not args.no_graph:
+        try:
+            bg = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(bg):
+                for i in range(nrep):
+                    base(dK, dV, dq[i % T], scale, out)
+            bgraph = bg
+        except Exception:  # noqa: BLE001
+            bgraph = None
+    ev[0].record()
+    for _ in range(3):
+        if bgraph is not None:
+            bgraph.replay()
+        else:
+            for i in range(nrep):
+                base(dK, dV, dq[i % T], scale, out)
+    ev[1].record()
+    ev[1].synchronize()
+    base_ms = ev[0].elapsed_time(ev[1]) / (3 * nrep)
+    base_bytes = 2 * B * H * S * 128 * 2 + B * Hq * 128 * (2 + 4)
+
+    # ---- CPU oracle on the host cores (bounded sample; never tuned) ----
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import kvcomp_oracle as oracle
+        ob = max(1, min(B, 2))                       # bounded sample: at most 2 sequences of the batch
+        oh = H if B * H * S <= 32 * 4096 else max(1, (32 * 4096) // (ob * S))
+        oh = min(oh, H)
+        oc = oracle.OracleCache(ob, oh, oh * (Hq // H), max_seq, rel_eb, rel_eb)
+        oc.build_codebook(Kx[:ob, :, :oh], Vx[:ob, :, :oh])
+        oc.compress_blocks(np.ascontiguousarray(Kx[:ob, :, :oh]), np.ascontiguousarray(Vx[:ob, :, :oh]))
+        osteps = min(T, 16)
+        obytes = 0.0
+        tc0 = time.perf_counter()
+        for i in range(osteps):
+            oc.append_token(np.ascontiguousarray(kn[i][:ob, :oh]), np.ascontiguousarray(vn[i][:ob, :oh]))
+            oc.attn_decode(np.ascontiguousarray(qs[i][:ob, : oh * (Hq // H)]), scale)
+            st = oc.stats()
+            obytes += st["stored_bytes"] + ob * oh * (Hq // H) * 128 * 6
+        tc1 = time.perf_counter()
+        cpu = {"value": obytes / (tc1 - tc0) / 1e9, "unit": "GB/s", "cores": oracle.num_threads(), "kind": "oracle",
+               "sample": f"{osteps} decode steps (append + attention over the compressed cache) of {args.workload} "
+                         f"restricted to batch {ob} x {oh} kv heads, seq {S}",
+               "seconds": tc1 - tc0}
+
+    result = {
+        "metric": "fused decode-attention GB/s (compressed) & % HBM peak; compression ratio",
+        "value": value,
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": f"{args.workload}: batch {B}, {H} kv heads / {Hq} q heads x 128, prompt {S} tokens, "
+                               f"{T} decode steps (append one token, then fused decode attention), block 64, "
+                               f"rel_eb {rel_eb}",
+                   "decode_loop": "hip graph replay" if graph is not None else "eager launches"},
+        "pct_hbm_peak": 100.0 * value / HBM_PEAK_GBPS,
+        "compression_ratio": stats0["compression_ratio"],
+        "bits_per_symbol": {"k": stats0["payload_bits_k"] / (B * H * nb0 * 8192.0),
+                            "v": stats0["payload_bits_v"] / (B * H * nb0 * 8192.0)},
+        "decode_ms_per_token": dec_ms / T,
+        "tokens_per_s": B * T / (dec_ms * 1e-3),
+        "equivalent_fp16_GBps": (2 * B * H * S * 128 * 2) * T / (dec_ms * 1e-3) / 1e9,
+        "store_ms": float(np.mean(store_ms)),
+        "store_GBps_fp16_in": (2 * B * H * S * 128 * 2) / (float(np.mean(store_ms)) * 1e-3) / 1e9,
+        "fp16_baseline": {"ms": base_ms, "GBps": base_bytes / (base_ms * 1e-3) / 1e9,
+                          "pct_hbm_peak": 100.0 * base_bytes / (base_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+                          "fused_speedup": base_ms / (dec_ms / T)},
+        "roofline": {"bound": "hbm", "kernel": "fused_attn_kernel", "achieved": achieved, "peak": HBM_PEAK_GBPS,
+                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS, "traffic": None,
+                     "bytes_per_launch": kern_bytes, "avg_launch_ms": kern_ms, "launches_timed": launches},
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(result))
+    cache.close()
+
+
+if __name__ == "__main__":
+    main()
