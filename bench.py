@@ -34,6 +34,7 @@ def parse_args():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--n-splits", type=int, default=0)
     ap.add_argument("--stage-bytes", type=int, default=0)
+    ap.add_argument("--max-code-len", type=int, default=0, help="longest Huffman code word (0 = library default 12)")
     return ap.parse_args()
 
 
@@ -63,7 +64,7 @@ def main():
     dq, dkn, dvn = torch.from_numpy(qs).cuda(), torch.from_numpy(kn).cuda(), torch.from_numpy(vn).cuda()
     out = torch.empty((B, Hq, 128), dtype=torch.float32, device="cuda")
     max_seq = (S + T + 63) // 64 * 64
-    cache = binding.KVCompCache(B, H, Hq, max_seq, rel_eb, rel_eb)
+    cache = binding.KVCompCache(B, H, Hq, max_seq, rel_eb, rel_eb, max_code_len=args.max_code_len)
     cache.set_tuning(args.n_splits, args.stage_bytes)
 
     def store():
@@ -100,8 +101,12 @@ def main():
     rec0 = stats0["record_bytes_k"] + stats0["record_bytes_v"]
     n_flush = stats_end["n_blocks"] - nb0
     flush_bytes = ((stats_end["record_bytes_k"] + stats_end["record_bytes_v"] - rec0) / n_flush) if n_flush else 0.0
-    per_wave = max(1, (B * H * nb0 + 8191) // 8192)
-    n_splits_est = args.n_splits or max(1, min(64, -(-nb0 // (4 * per_wave))))
+    if args.n_splits:
+        n_splits_est = args.n_splits
+    else:  # mirrors the library's split heuristic (only used to count the bytes of the split partials)
+        ns = max(1, min(max(1, 1024 // (B * H)), -(-nb0 // 4)))
+        bps = -(-(-(-nb0 // ns)) // 4) * 4
+        n_splits_est = max(1, min(64, -(-nb0 // bps))) if bps else 1
     step_bytes = []
     for i in range(T):
         tokens = S + i + 1
@@ -193,7 +198,8 @@ def main():
         ob = max(1, min(B, 2))                       # bounded sample: at most 2 sequences of the batch
         oh = H if B * H * S <= 32 * 4096 else max(1, (32 * 4096) // (ob * S))
         oh = min(oh, H)
-        oc = oracle.OracleCache(ob, oh, oh * (Hq // H), max_seq, rel_eb, rel_eb)
+        oc = oracle.OracleCache(ob, oh, oh * (Hq // H), max_seq, rel_eb, rel_eb,
+                                max_code_len=args.max_code_len or 12)
         oc.build_codebook(Kx[:ob, :, :oh], Vx[:ob, :, :oh])
         oc.compress_blocks(np.ascontiguousarray(Kx[:ob, :, :oh]), np.ascontiguousarray(Vx[:ob, :, :oh]))
         osteps = min(T, 16)
@@ -225,7 +231,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": f"{args.workload}: batch {B}, {H} kv heads / {Hq} q heads x 128, prompt {S} tokens, "
                                f"{T} decode steps (append one token, then fused decode attention), block 64, "
-                               f"rel_eb {rel_eb}",
+                               f"rel_eb {rel_eb}, max code word {args.max_code_len or 12} bits",
                    "decode_loop": "hip graph replay" if graph is not None else "eager launches"},
         "pct_hbm_peak": 100.0 * value / HBM_PEAK_GBPS,
         "compression_ratio": stats0["compression_ratio"],

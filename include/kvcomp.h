@@ -49,7 +49,8 @@ typedef struct {
     float rel_eb_k;       /* relative error bound for K: |x - x'| <= rel_eb * (max - min) of the unit; the    */
     float rel_eb_v;       /*   paper's "relative quantization scale" (Section 4.2) is the bin width = 2*rel_eb */
     int32_t k_mode;       /* 0: K units are channels inside a block (Section 3.1.1); 1: reserved (BlockQuant) */
-    int32_t max_code_len; /* longest Huffman code word allowed, 8..12 (0 = default 12)                        */
+    int32_t max_code_len; /* longest Huffman code word allowed, <= 12 and 2^max_code_len >= number of levels  */
+                          /*   (0 = default 12); shorter words cost compression but decode faster            */
 } kvcomp_config;
 
 typedef struct {
@@ -151,7 +152,9 @@ kvcomp_status kvcomp_get_profile(kvcomp_ctx *ctx, int *h_launches, double *h_tot
 
 /* Decode attention on the uncompressed fp16 cache: same result definition as kvcomp_attn_decode with K' = K and
  * V' = V.  d_K, d_V: device fp16 [batch, seq, n_kv_heads, 128]; d_workspace: device scratch of at least
- * kvcomp_baseline_workspace_bytes(cfg).  Stream-ordered.  n_splits 0 = default. */
+ * kvcomp_baseline_workspace_bytes(cfg) bytes that the caller ZERO-FILLS ONCE before the first call (it holds the
+ * split tickets, which every launch leaves at zero again); two launches must not share it concurrently.
+ * Stream-ordered.  n_splits 0 = default. */
 size_t kvcomp_baseline_workspace_bytes(const kvcomp_config *cfg);
 kvcomp_status kvcomp_baseline_fp16_attn(const kvcomp_config *cfg, const void *d_K, const void *d_V, int seq,
                                         const void *d_q, float scale, float *d_out, void *d_workspace,

@@ -20,9 +20,16 @@
  *     whole block; V = one token of the block (128 values);
  *   - bin width = 2 * rel_eb * (max - min), codes = round-half-even((x - min) / width), reconstruction
  *     min + code * width, so |x - x'| <= rel_eb * (max - min);
- *   - slices: K slice i = token i (128 symbols, channel order); V slice c = channel c (64 symbols, token order);
- *   - bit stream: bit i of a payload is bit (i mod 32) of little-endian 32-bit word (i div 32); a code word is
- *     emitted first-bit-first (most significant bit of the canonical code first).
+ *   - slices (the vector one GPU thread encodes, Section 3.2.2): 128 slices of 64 symbols in every block.
+ *     K slice s = token s/2, channels 64*(s%2) .. +63 in channel order (half a token row: the dot product of
+ *     Section 3.3.2 runs along head_dim); V slice s = channel s, tokens 0..63 in token order (the dot product runs
+ *     along the context);
+ *   - bit stream: bit i of a payload is bit (i mod 32) of little-endian 32-bit word (i div 32);
+ *   - a slice is written from both ends: the code words of its symbols 0..31 follow each other first-bit-first
+ *     (most significant bit of the canonical code first) from the slice start upwards, and the code words of
+ *     symbols 32..63 come after them, each written last-bit-first.  Read DOWNWARDS from the slice end, the bits are
+ *     therefore the code words of symbols 63, 62, .., 32, first-bit-first: a slice holds two independently decodable
+ *     chains and needs no second offset, because its end is the next slice's start.
  */
 #include <math.h>
 #include <stdint.h>
@@ -62,11 +69,14 @@ static int unit_of(int which, int k_mode, int t, int c) {
     if (which == 1) return t;
     return k_mode == 1 ? 0 : c;
 }
-int orc_n_slices(int which) { return which == 0 ? BT : D; }
-static int slice_len(int which) { return which == 0 ? D : BT; }
+#define NSLICE 128       /* slices per block */
+#define SLICE 64         /* symbols per slice */
+#define HALF 32          /* symbols 0..31 are read upwards from the slice start, 63..32 downwards from its end */
+int orc_n_slices(int which) { (void)which; return NSLICE; }
+static int slice_len(int which) { (void)which; return SLICE; }
 /* symbol k of slice s sits at tile position (t, c) */
 static void slice_pos(int which, int s, int k, int *t, int *c) {
-    if (which == 0) { *t = s; *c = k; } else { *t = k; *c = s; }
+    if (which == 0) { *t = s / 2; *c = SLICE * (s % 2) + k; } else { *t = k; *c = s; }
 }
 /* record header: [min/max pairs, padded to 16 bytes][u16 bit count per slice] */
 int orc_minmax_bytes(int which, int k_mode) {
@@ -222,7 +232,7 @@ int orc_build_codebook(const uint64_t *hist, int n_sym, int max_len, uint8_t *le
     int len[NSYM_MAX], s, halvings = 0, L;
     uint32_t next = 0;
     int prev_len = 0, started = 0;
-    if (n_sym < 2 || n_sym > NSYM_MAX || max_len < 8 || max_len > 16) return -1;
+    if (n_sym < 2 || n_sym > NSYM_MAX || max_len < 1 || max_len > 16 || (1 << max_len) < n_sym) return -1;
     for (s = 0; s < n_sym; s++) f[s] = hist[s] > 0 ? hist[s] : 1;
     for (;;) {
         int longest = 0;
@@ -257,6 +267,7 @@ static int get_bit(const uint8_t *payload, size_t i) { return (payload[i >> 3] >
  * Encode one quantized 2D block into its record (Section 3.2.2 stages 2-4, Figure 4):
  *   [min/max pairs (padded to 16 B)] [u16 bit count of each slice] [all slices' code words, concatenated at bit
  *   granularity in slice order, in whole 32-bit words] [zero padding to a multiple of 16 bytes].
+ * Inside a slice the first 32 code words go out first-bit-first and the last 32 last-bit-first (see the header).
  * Returns the record size in bytes, or 0 if cap is too small / a code has no code word.
  */
 size_t orc_encode_block(int which, int k_mode, const uint8_t *codes, const uint16_t *minmax, const uint8_t *len,
@@ -289,7 +300,10 @@ size_t orc_encode_block(int which, int k_mode, const uint8_t *codes, const uint1
             slice_pos(which, s, k, &t, &c);
             sym = codes[t * D + c];
             L = len[sym];
-            for (b = L - 1; b >= 0; b--) put_bit(rec + hdr, pos++, (code[sym] >> b) & 1);
+            if (k < HALF)
+                for (b = L - 1; b >= 0; b--) put_bit(rec + hdr, pos++, (code[sym] >> b) & 1);
+            else
+                for (b = 0; b < L; b++) put_bit(rec + hdr, pos++, (code[sym] >> b) & 1);
         }
         rec[mmb + 2 * s + 0] = (uint8_t)((pos - start) & 0xff);
         rec[mmb + 2 * s + 1] = (uint8_t)((pos - start) >> 8);
@@ -332,20 +346,27 @@ int orc_decode_block_serial(int which, int k_mode, const uint8_t *rec, const uin
     for (s = 0; s < ns; s++) {
         size_t start = pos;
         size_t want = (size_t)(rec[mmb + 2 * s] | (rec[mmb + 2 * s + 1] << 8));
+        size_t up = start, down = start + want; /* next bit going up; one past the next bit going down */
         for (k = 0; k < sl; k++) {
+            /* symbols 0..31 in order from the start; then 63, 62, .., 32 from the end */
+            int sym_index = k < HALF ? k : sl - 1 - (k - HALF);
             uint32_t cand = 0;
             int t, c, found = 0;
             for (L = 1; L <= 32 && !found; L++) {
-                cand = (cand << 1) | (uint32_t)get_bit(rec + hdr, pos++);
+                int bit;
+                if (k < HALF) bit = get_bit(rec + hdr, up++);
+                else { if (down == 0) return -1; bit = get_bit(rec + hdr, --down); }
+                cand = (cand << 1) | (uint32_t)bit;
                 if (count[L] && cand >= first_code[L] && cand - first_code[L] < (uint32_t)count[L]) {
-                    slice_pos(which, s, k, &t, &c);
+                    slice_pos(which, s, sym_index, &t, &c);
                     codes[t * D + c] = (uint8_t)sorted[first_index[L] + (int)(cand - first_code[L])];
                     found = 1;
                 }
             }
             if (!found) return -1;
         }
-        if (pos - start != want) return -1;
+        if (up != down) return -1; /* the two chains must meet exactly */
+        pos = start + want;
     }
     return 0;
 }
@@ -356,7 +377,8 @@ int orc_decode_block_serial(int which, int k_mode, const uint8_t *rec, const uin
  * The decoder of Section 3.3.1: the Huffman tree is an array of nodes {is_symbol, symbol, indexes[2]}; each
  * stream bit selects the next node through indexes[bit]; the current node's symbol is always stored but the
  * write position only advances on symbol nodes; the position in the tree is reset to the root with a mask
- * computed from is_symbol instead of a branch.
+ * computed from is_symbol instead of a branch.  Each slice is walked twice: upwards from its start for symbols
+ * 0..31 and downwards from its end for symbols 63..32; the walk stops when 32 symbols have been written.
  */
 typedef struct { int is_symbol; int symbol; int indexes[2]; } tree_node;
 
@@ -386,23 +408,29 @@ int orc_decode_block_tree(int which, int k_mode, const uint8_t *rec, const uint8
     }
     read_minmax(which, k_mode, rec, minmax);
     for (s = 0; s < ns; s++) {
-        size_t nbits = (size_t)(rec[mmb + 2 * s] | (rec[mmb + 2 * s + 1] << 8)), i;
-        uint8_t buf[D + 1];
-        int write_idx = 0, index = 0, k;
-        for (i = 0; i < nbits; i++) {
-            int bit = get_bit(rec + hdr, pos++);
-            index = nodes[index].indexes[bit];
-            if (write_idx > sl) return -1;
-            buf[write_idx < sl ? write_idx : sl] = (uint8_t)nodes[index].symbol;
-            write_idx += nodes[index].is_symbol;
-            index &= ~(-nodes[index].is_symbol);
+        size_t nbits = (size_t)(rec[mmb + 2 * s] | (rec[mmb + 2 * s + 1] << 8));
+        size_t up = pos, down = pos + nbits;
+        uint8_t buf[HALF + 1];
+        int dir, k;
+        for (dir = 0; dir < 2; dir++) { /* 0: upwards from the start; 1: downwards from the end */
+            int write_idx = 0, index = 0;
+            while (write_idx < HALF) {
+                int bit;
+                if (up >= down) return -1;
+                bit = dir == 0 ? get_bit(rec + hdr, up++) : get_bit(rec + hdr, --down);
+                index = nodes[index].indexes[bit];
+                buf[write_idx] = (uint8_t)nodes[index].symbol;
+                write_idx += nodes[index].is_symbol;
+                index &= ~(-nodes[index].is_symbol);
+            }
+            for (k = 0; k < HALF; k++) {
+                int t, c;
+                slice_pos(which, s, dir == 0 ? k : sl - 1 - k, &t, &c);
+                codes[t * D + c] = buf[k];
+            }
         }
-        if (write_idx != sl || index != 0) return -1;
-        for (k = 0; k < sl; k++) {
-            int t, c;
-            slice_pos(which, s, k, &t, &c);
-            codes[t * D + c] = buf[k];
-        }
+        if (up != down) return -1;
+        pos += nbits;
     }
     return 0;
 }

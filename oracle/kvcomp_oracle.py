@@ -78,7 +78,7 @@ def _bits(x):
 K, V = 0, 1
 
 # worst-case record: header + 64*128 symbols at 16 bits each
-MAX_RECORD_BYTES = 640 + BT * D * 2 + 16
+MAX_RECORD_BYTES = 768 + BT * D * 2 + 16
 
 
 def n_sym(rel_eb):

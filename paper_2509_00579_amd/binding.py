@@ -224,8 +224,8 @@ class BaselineFp16Attention:
         self.cfg = make_config(batch, n_kv_heads, n_q_heads, 64, 0.01, 0.01)
         self.B, self.H, self.Hq = batch, n_kv_heads, n_q_heads
         self.device = torch.device(device)
-        self.ws = torch.empty(self.lib.kvcomp_baseline_workspace_bytes(C.byref(self.cfg)), dtype=torch.uint8,
-                              device=self.device)
+        self.ws = torch.zeros(self.lib.kvcomp_baseline_workspace_bytes(C.byref(self.cfg)), dtype=torch.uint8,
+                              device=self.device)  # zero-filled once: it holds the split tickets
 
     def __call__(self, Kt, Vt, q, scale, out=None, n_splits=0):
         S = Kt.shape[1]

@@ -5,10 +5,9 @@
 #include <hip/hip_fp16.h>
 
 #include "kvcomp_internal.h"
+#include "split_combine.cuh"
 
 namespace kvc {
-
-hipError_t launch_combine(const float *partials, int rows, int n_splits, float *out, hipStream_t s);
 
 __device__ __forceinline__ float bh2f(uint32_t bits) { return __half2float(__ushort_as_half((unsigned short)bits)); }
 
@@ -27,7 +26,8 @@ __global__ __launch_bounds__(64 * kBWaves) void baseline_attn_kernel(int B, int 
                                                                       const uint16_t *__restrict__ V, int seq,
                                                                       const uint16_t *__restrict__ q, float scale,
                                                                       float *__restrict__ partials,
-                                                                      int tokens_per_split) {
+                                                                      uint32_t *__restrict__ counters,
+                                                                      float *__restrict__ out, int tokens_per_split) {
     __shared__ float comb[kBWaves][G][kPartialStride];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int split = blockIdx.x, bh = blockIdx.y, b = bh / H, h = bh - b * H;
@@ -139,29 +139,34 @@ __global__ __launch_bounds__(64 * kBWaves) void baseline_attn_kernel(int B, int 
             L += comb[w][g][kD + 1] * f;
             O += comb[w][g][c] * f;
         }
-        float *dst = partials + (((size_t)b * Hq + (size_t)h * G + g) * kMaxSplits + split) * kPartialStride;
-        dst[c] = O;
-        if (c == 0) { dst[kD] = M; dst[kD + 1] = L; }
+        if (gridDim.x == 1) {
+            out[((size_t)b * Hq + (size_t)h * G + g) * kD + c] = O / L;
+        } else {
+            float *dst = partials + (((size_t)b * Hq + (size_t)h * G + g) * kMaxSplits + split) * kPartialStride;
+            store_agent(dst + c, O);
+            if (c == 0) { store_agent(dst + kD, M); store_agent(dst + kD + 1, L); }
+        }
     }
+    if (gridDim.x > 1)
+        finish_splits<G, 64 * kBWaves>(partials, counters + bh, b * Hq + h * G, (int)gridDim.x, out, tid);
 }
 
 hipError_t launch_baseline_attn(int B, int H, int Hq, const uint16_t *K, const uint16_t *V, int seq, const uint16_t *q,
-                                float scale, float *out, float *partials, int n_splits, hipStream_t s) {
+                                float scale, float *out, float *partials, uint32_t *counters, int n_splits,
+                                hipStream_t s) {
     const int G = Hq / H;
     int tps = (seq + n_splits - 1) / n_splits;
     tps = (tps + 63) / 64 * 64;
     n_splits = (seq + tps - 1) / tps;
     const dim3 grid(n_splits, B * H), block(64 * kBWaves);
     switch (G) {
-        case 1: hipLaunchKernelGGL(baseline_attn_kernel<1>, grid, block, 0, s, B, H, Hq, K, V, seq, q, scale, partials, tps); break;
-        case 2: hipLaunchKernelGGL(baseline_attn_kernel<2>, grid, block, 0, s, B, H, Hq, K, V, seq, q, scale, partials, tps); break;
-        case 4: hipLaunchKernelGGL(baseline_attn_kernel<4>, grid, block, 0, s, B, H, Hq, K, V, seq, q, scale, partials, tps); break;
-        case 8: hipLaunchKernelGGL(baseline_attn_kernel<8>, grid, block, 0, s, B, H, Hq, K, V, seq, q, scale, partials, tps); break;
+        case 1: hipLaunchKernelGGL(baseline_attn_kernel<1>, grid, block, 0, s, B, H, Hq, K, V, seq, q, scale, partials, counters, out, tps); break;
+        case 2: hipLaunchKernelGGL(baseline_attn_kernel<2>, grid, block, 0, s, B, H, Hq, K, V, seq, q, scale, partials, counters, out, tps); break;
+        case 4: hipLaunchKernelGGL(baseline_attn_kernel<4>, grid, block, 0, s, B, H, Hq, K, V, seq, q, scale, partials, counters, out, tps); break;
+        case 8: hipLaunchKernelGGL(baseline_attn_kernel<8>, grid, block, 0, s, B, H, Hq, K, V, seq, q, scale, partials, counters, out, tps); break;
         default: return hipErrorInvalidValue;
     }
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
-    return launch_combine(partials, B * Hq, n_splits, out, s);
+    return hipGetLastError();
 }
 
 }  // namespace kvc

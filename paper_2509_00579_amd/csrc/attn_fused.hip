@@ -1,22 +1,28 @@
 // Fetch side (Section 3.3, Figure 1): one decode-attention step straight from the compressed cache.
 //
-// Per 2D block a single wavefront (64 lanes) stages the K record in LDS, every lane Huffman-decodes the slice of
-// one token (128 symbols) with a 12-bit lookup table and accumulates q.k in registers; the wave then updates a
-// running softmax and decodes the V record of the same block, every lane owning two channels (two slices of 64
-// symbols) and accumulating p.v in registers.  No decompressed value ever leaves the registers (Section 3.3.2).
+// Per 2D block a single wavefront (64 lanes) stages the K record in LDS, every lane Huffman-decodes the two slices
+// of one token with a lookup table -- each slice from both ends, four independent decode chains of 32 symbols per
+// lane -- and accumulates q.k in registers; the wave then updates a running softmax and decodes the V record of the
+// same block, every lane owning two channels (two slices, again four chains) and accumulating p.v in registers.  No
+// decompressed value ever leaves the registers (Section 3.3.2).
 //
 // What differs from the paper's kernel, and why (gfx950):
 //  * lookup-table decode instead of the bit-serial tree walk of Section 3.3.1: all 64 lanes of a wave advance in
 //    symbol lock-step (same trip count for every lane, no divergence), so the dequantization weight of the current
-//    symbol is the same for the whole wave and is read from LDS as a broadcast;
+//    symbol is the same for the whole wave: it lives in one lane's register and is broadcast with v_readlane, which
+//    keeps it off the LDS pipe that the table lookups saturate.  The table is indexed by as many stream bits as the
+//    longest code word of the codebook, and one 32-bit window serves several symbols (floor(31 / longest)) with no
+//    refill test in between;
 //  * the dequantization is folded into the weights: q.k' = sum_c q_c min_c + sum_c (q_c step_c) code_tc, and
 //    p.v'  = sum_t p_t min_t + sum_t (p_t step_t) code_tc: one convert and one FMA per decoded symbol;
 //  * K and V of a block are handled by the same wave back to back with an online softmax, so scores never go to
-//    memory and the sequence is split over workgroups; a small second kernel merges the splits (the "sum
-//    reduction" of Section 3.3.2).
+//    memory; while one record is decoded the next one is already on its way from HBM into registers;
+//  * the sequence is split over workgroups; the workgroup that finishes last merges the splits (the "sum
+//    reduction" of Section 3.3.2) inside the same launch.
 #include <hip/hip_fp16.h>
 
 #include "kvcomp_internal.h"
+#include "split_combine.cuh"
 
 namespace kvc {
 
@@ -28,6 +34,11 @@ __device__ __forceinline__ void wave_sync() {
 
 __device__ __forceinline__ float h2f(uint32_t bits) { return __half2float(__ushort_as_half((unsigned short)bits)); }
 
+// value of `v` in lane `lane_idx` (wave-uniform index), delivered in a scalar register
+__device__ __forceinline__ float bcast(float v, int lane_idx) {
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), lane_idx));
+}
+
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll
     for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m);
@@ -38,55 +49,118 @@ __device__ __forceinline__ float wave_max(float v) {
     for (int m = 32; m >= 1; m >>= 1) v = fmaxf(v, __shfl_xor(v, m));
     return v;
 }
-// exclusive prefix sum over the 64 lanes; *total receives the sum
-__device__ __forceinline__ uint32_t wave_excl_scan(uint32_t v, int lane, uint32_t *total) {
+// exclusive prefix sum over the 64 lanes
+__device__ __forceinline__ uint32_t wave_excl_scan(uint32_t v, int lane) {
     uint32_t inc = v;
 #pragma unroll
     for (int d = 1; d < 64; d <<= 1) {
         const uint32_t o = __shfl_up(inc, d);
         if (lane >= d) inc += o;
     }
-    *total = __shfl(inc, 63);
     return inc - v;
 }
 
-// One lane's view of a bit stream: a 64-bit window {hi,lo} over consecutive 32-bit words, `s` = position of the
-// next unread bit inside lo.  Bit i of the stream is bit (i % 32) of word (i / 32).
-struct BitReader {
-    uint32_t lo, hi, s, next;
-    template <class Src>
-    __device__ __forceinline__ void open(const Src &src, uint32_t bitpos) {
-        const uint32_t w = bitpos >> 5;
-        s = bitpos & 31u;
-        lo = src.word(w);
-        hi = src.word(w + 1);
-        next = w + 2;
+// A slice holds two decode chains (see the record layout): symbols 0..31 are read upwards from the slice start,
+// symbols 63..32 downwards from the slice end.  Both readers keep a 64-bit piece {hi,lo} of the stream in registers
+// plus the next word in reading direction, fetched one window ahead so that the LDS read of the stream is off the
+// critical path (only the table lookups depend on each other).
+//   wm1   payload words, pointer moved back by one word: payload bit x is bit x + 32 of wm1
+// A window is 32 stream bits whose bit 0 is a don't-care and whose bits 1.. are the next unread bits in reading
+// order, i.e. the stream already scaled to the byte offset of a 16-bit table entry.
+struct UpReader {
+    uint32_t P, idx, lo, hi, nx;  // P = (next unread payload bit) + 31 = window start in wm1 bit coordinates
+    __device__ __forceinline__ void open(const uint32_t *wm1, uint32_t first_bit) {
+        P = first_bit + 31u;
+        idx = P >> 5;
+        lo = wm1[idx];
+        hi = wm1[idx + 1];
+        nx = wm1[idx + 2];
     }
-    // returns the table entry of the next symbol and consumes its bits
-    template <class Src>
-    __device__ __forceinline__ uint32_t get(const Src &src, const uint16_t *lut) {
-        const uint32_t win = __builtin_amdgcn_alignbit(hi, lo, s);
-        const uint32_t e = lut[win & (kLutSize - 1)];
-        s += e & 0xffu;
-        if (s >= 32u) {
-            lo = hi;
-            hi = src.word(next++);
-            s -= 32u;
-        }
-        return e;
+    __device__ __forceinline__ uint32_t window() const { return __builtin_amdgcn_alignbit(hi, lo, P); }
+    __device__ __forceinline__ void advance(const uint32_t *wm1, uint32_t used) {  // used <= 31
+        P += used;
+        const uint32_t nidx = P >> 5;
+        const bool adv = nidx != idx;
+        lo = adv ? hi : lo;
+        hi = adv ? nx : hi;
+        idx = nidx;
+        nx = wm1[nidx + 2];
+    }
+};
+struct DownReader {
+    uint32_t P, idx, lo, hi, pv;  // P = (one past the next unread payload bit) + 1: the window [P, P+32) of wm1 ends
+                                  // one bit above the next unread bit; bit-reversed it reads downwards
+    __device__ __forceinline__ void open(const uint32_t *wm1, uint32_t end_bit) {
+        P = end_bit + 1u;
+        idx = P >> 5;
+        lo = wm1[idx];
+        hi = wm1[idx + 1];
+        pv = wm1[(int)idx - 1];
+    }
+    __device__ __forceinline__ uint32_t window() const {
+        return __builtin_bitreverse32(__builtin_amdgcn_alignbit(hi, lo, P));
+    }
+    __device__ __forceinline__ void advance(const uint32_t *wm1, uint32_t used) {  // used <= 31
+        P -= used;
+        const uint32_t nidx = P >> 5;
+        const bool adv = nidx != idx;
+        hi = adv ? lo : hi;
+        lo = adv ? pv : lo;
+        idx = nidx;
+        pv = wm1[(int)nidx - 1];
     }
 };
 
-struct WordSrc {  // payload words, either staged in LDS or in global memory
-    const uint32_t *base;
-    __device__ __forceinline__ uint32_t word(uint32_t i) const { return base[i]; }
+// Decode CNT symbols from a window.  lut: entry = (symbol << 8) | code length, indexed by the next `bits` stream
+// bits; mask2 = ((1 << bits) - 1) << 1.  CNT * (longest code word) <= 31 is the caller's promise.  Returns the
+// number of bits used.
+template <int CNT>
+__device__ __forceinline__ uint32_t lookup(uint32_t win, const char *lut, uint32_t mask2, float (&f)[CNT]) {
+    uint32_t tot = 0;
+#pragma unroll
+    for (int k = 0; k < CNT; k++) {
+        const uint32_t e = *reinterpret_cast<const uint16_t *>(lut + (win & mask2));
+        win >>= (e & 31u);
+        tot += e;  // low byte: running sum of code lengths (at most 31, never carries)
+        f[k] = (float)(e >> 8);
+    }
+    return tot & 0xffu;
+}
+
+// The four chains of one lane (two slices x two directions) advance together, CNT symbols each.
+struct Quad {
+    UpReader au, bu;
+    DownReader ad, bd;
+    // a = [a0, a0 + abits), b follows it
+    __device__ __forceinline__ void open(const uint32_t *wm1, uint32_t a0, uint32_t abits, uint32_t bbits) {
+        au.open(wm1, a0);
+        ad.open(wm1, a0 + abits);
+        bu.open(wm1, a0 + abits);
+        bd.open(wm1, a0 + abits + bbits);
+    }
+    template <int CNT>
+    __device__ __forceinline__ void step(const uint32_t *wm1, const char *lut, uint32_t mask2, float (&fau)[CNT],
+                                         float (&fad)[CNT], float (&fbu)[CNT], float (&fbd)[CNT]) {
+        const uint32_t u0 = lookup<CNT>(au.window(), lut, mask2, fau);
+        const uint32_t u1 = lookup<CNT>(ad.window(), lut, mask2, fad);
+        const uint32_t u2 = lookup<CNT>(bu.window(), lut, mask2, fbu);
+        const uint32_t u3 = lookup<CNT>(bd.window(), lut, mask2, fbd);
+        au.advance(wm1, u0);
+        ad.advance(wm1, u1);
+        bu.advance(wm1, u2);
+        bd.advance(wm1, u3);
+    }
 };
+
+constexpr int kHalf = kSliceLen / 2;  // symbols per chain
 
 struct FusedArgs {
     Geo g;
     const uint16_t *q;
+    float *out;
     float scale;
     int n_blocks, n_res, blocks_per_split, n_splits, stage_bytes;
+    uint32_t mask2[2];
 };
 
 // softmax state of one wave for G query heads
@@ -112,116 +186,187 @@ struct Soft {
     }
 };
 
-// ---- K block: lane = token --------------------------------------------------------------------------------------
-template <int G>
-__device__ __forceinline__ void k_block(const uint32_t *hdr32, const WordSrc &pay, const uint16_t *lut, float *wts,
+// ---- K block: lane = token; its two slices are channels 0..63 and 64..127 ------------------------------------------
+// hdr32: the record (LDS or global).  Leaves scale * q.k' of this lane's token in score[].
+template <int G, int NS>
+__device__ __forceinline__ void k_block(const uint32_t *hdr32, const char *lut, uint32_t mask2,
                                         const float (&qreg)[G][2], float two_eb, float scale, int lane,
                                         float (&score)[G]) {
+    // lane c holds the folded weights q_c * step_c of channels c and c + 64
     const uint32_t mm0 = hdr32[lane], mm1 = hdr32[lane + 64];
     const float mn0 = h2f(mm0 & 0xffffu), mn1 = h2f(mm1 & 0xffffu);
     const float st0 = two_eb * (h2f(mm0 >> 16) - mn0), st1 = two_eb * (h2f(mm1 >> 16) - mn1);
-    float bias[G];
+    float w0[G], w1[G], acc[G];
 #pragma unroll
     for (int g = 0; g < G; g++) {
-        wts[g * kD + lane] = qreg[g][0] * st0;
-        wts[g * kD + lane + 64] = qreg[g][1] * st1;
-        bias[g] = wave_sum(qreg[g][0] * mn0 + qreg[g][1] * mn1);
+        w0[g] = qreg[g][0] * st0;
+        w1[g] = qreg[g][1] * st1;
+        acc[g] = 0.f;
     }
-    const uint32_t sb = reinterpret_cast<const uint16_t *>(hdr32)[kMinMaxBytesK / 2 + lane];
-    uint32_t total;
-    const uint32_t start = wave_excl_scan(sb, lane, &total);
-    wave_sync();
-    BitReader br;
-    br.open(pay, start);
-    float acc[G];
+    const uint32_t sb = hdr32[kMinMaxBytesK / 4 + lane];  // bit counts of slices 2*lane and 2*lane+1
+    const uint32_t start = wave_excl_scan((sb & 0xffffu) + (sb >> 16), lane);
+    const uint32_t *wm1 = hdr32 + kHdrBytesK / 4 - 1;
+    Quad qd;
+    qd.open(wm1, start, sb & 0xffffu, sb >> 16);
+    constexpr int kRounds = kHalf / NS, kTail = kHalf - kRounds * NS;
+#pragma unroll 2
+    for (int r = 0; r < kRounds; r++) {
+        float fau[NS], fad[NS], fbu[NS], fbd[NS];
+        qd.step<NS>(wm1, lut, mask2, fau, fad, fbu, fbd);
 #pragma unroll
-    for (int g = 0; g < G; g++) acc[g] = 0.f;
-#pragma unroll 1
-    for (int c = 0; c < kD; c += 4) {
-        float4 w[G];
+        for (int k = 0; k < NS; k++) {
+            const int up = r * NS + k, dn = kSliceLen - 1 - up;  // symbol index inside the slice
 #pragma unroll
-        for (int g = 0; g < G; g++) w[g] = *reinterpret_cast<const float4 *>(wts + g * kD + c);
-#pragma unroll
-        for (int u = 0; u < 4; u++) {
-            const float f = (float)(br.get(pay, lut) >> 8);
-#pragma unroll
-            for (int g = 0; g < G; g++) acc[g] = fmaf(u == 0 ? w[g].x : u == 1 ? w[g].y : u == 2 ? w[g].z : w[g].w, f, acc[g]);
+            for (int g = 0; g < G; g++) {
+                acc[g] = fmaf(bcast(w0[g], up), fau[k], acc[g]);
+                acc[g] = fmaf(bcast(w0[g], dn), fad[k], acc[g]);
+                acc[g] = fmaf(bcast(w1[g], up), fbu[k], acc[g]);
+                acc[g] = fmaf(bcast(w1[g], dn), fbd[k], acc[g]);
+            }
         }
     }
+    if constexpr (kTail > 0) {
+        float fau[kTail], fad[kTail], fbu[kTail], fbd[kTail];
+        qd.step<kTail>(wm1, lut, mask2, fau, fad, fbu, fbd);
 #pragma unroll
-    for (int g = 0; g < G; g++) score[g] = scale * (acc[g] + bias[g]);
+        for (int k = 0; k < kTail; k++) {
+            const int up = kRounds * NS + k, dn = kSliceLen - 1 - up;
+#pragma unroll
+            for (int g = 0; g < G; g++) {
+                acc[g] = fmaf(bcast(w0[g], up), fau[k], acc[g]);
+                acc[g] = fmaf(bcast(w0[g], dn), fad[k], acc[g]);
+                acc[g] = fmaf(bcast(w1[g], up), fbu[k], acc[g]);
+                acc[g] = fmaf(bcast(w1[g], dn), fbd[k], acc[g]);
+            }
+        }
+    }
+    // the constant part of the dot product, sum_c q_c min_c, is shared by all tokens of the block
+#pragma unroll
+    for (int g = 0; g < G; g++) score[g] = scale * (acc[g] + wave_sum(qreg[g][0] * mn0 + qreg[g][1] * mn1));
 }
 
-// ---- V block: lane = channels lane and lane+64 -------------------------------------------------------------------
-template <int G>
-__device__ __forceinline__ void v_block(const uint32_t *hdr32, const WordSrc &pay, const uint16_t *lut, float *wts,
-                                        const float (&p)[G], float two_eb, int lane, Soft<G> &st) {
+// ---- V block: lane = channels 2*lane and 2*lane+1 (its two slices) -------------------------------------------------
+// p[g] = softmax numerator of token `lane`.
+template <int G, int NS>
+__device__ __forceinline__ void v_block(const uint32_t *hdr32, const char *lut, uint32_t mask2, const float (&p)[G],
+                                        float two_eb, int lane, Soft<G> &st) {
+    // lane t holds the folded weight p_t * step_t of token t
     const uint32_t mm = hdr32[lane];
     const float mn = h2f(mm & 0xffffu);
     const float step = two_eb * (h2f(mm >> 16) - mn);
+    float w[G];
 #pragma unroll
     for (int g = 0; g < G; g++) {
-        wts[g * kBT + lane] = p[g] * step;
+        w[g] = p[g] * step;
         st.bv[g] += p[g] * mn;
     }
-    const uint16_t *sb16 = reinterpret_cast<const uint16_t *>(hdr32) + kMinMaxBytesV / 2;
-    uint32_t tot0, tot1;
-    const uint32_t s0 = wave_excl_scan(sb16[lane], lane, &tot0);
-    const uint32_t s1 = tot0 + wave_excl_scan(sb16[lane + 64], lane, &tot1);
-    wave_sync();
-    BitReader b0, b1;
-    b0.open(pay, s0);
-    b1.open(pay, s1);
-#pragma unroll 1
-    for (int t = 0; t < kBT; t += 4) {
-        float4 w[G];
+    const uint32_t sb = hdr32[kMinMaxBytesV / 4 + lane];
+    const uint32_t start = wave_excl_scan((sb & 0xffffu) + (sb >> 16), lane);
+    const uint32_t *wm1 = hdr32 + kHdrBytesV / 4 - 1;
+    Quad qd;
+    qd.open(wm1, start, sb & 0xffffu, sb >> 16);
+    constexpr int kRounds = kHalf / NS, kTail = kHalf - kRounds * NS;
+#pragma unroll 2
+    for (int r = 0; r < kRounds; r++) {
+        float fau[NS], fad[NS], fbu[NS], fbd[NS];
+        qd.step<NS>(wm1, lut, mask2, fau, fad, fbu, fbd);
 #pragma unroll
-        for (int g = 0; g < G; g++) w[g] = *reinterpret_cast<const float4 *>(wts + g * kBT + t);
-#pragma unroll
-        for (int u = 0; u < 4; u++) {
-            const float f0 = (float)(b0.get(pay, lut) >> 8);
-            const float f1 = (float)(b1.get(pay, lut) >> 8);
+        for (int k = 0; k < NS; k++) {
+            const int up = r * NS + k, dn = kSliceLen - 1 - up;  // token index inside the block
 #pragma unroll
             for (int g = 0; g < G; g++) {
-                const float wv = u == 0 ? w[g].x : u == 1 ? w[g].y : u == 2 ? w[g].z : w[g].w;
-                st.acc[g][0] = fmaf(wv, f0, st.acc[g][0]);
-                st.acc[g][1] = fmaf(wv, f1, st.acc[g][1]);
+                const float wu = bcast(w[g], up), wd = bcast(w[g], dn);
+                st.acc[g][0] = fmaf(wu, fau[k], st.acc[g][0]);
+                st.acc[g][0] = fmaf(wd, fad[k], st.acc[g][0]);
+                st.acc[g][1] = fmaf(wu, fbu[k], st.acc[g][1]);
+                st.acc[g][1] = fmaf(wd, fbd[k], st.acc[g][1]);
+            }
+        }
+    }
+    if constexpr (kTail > 0) {
+        float fau[kTail], fad[kTail], fbu[kTail], fbd[kTail];
+        qd.step<kTail>(wm1, lut, mask2, fau, fad, fbu, fbd);
+#pragma unroll
+        for (int k = 0; k < kTail; k++) {
+            const int up = kRounds * NS + k, dn = kSliceLen - 1 - up;
+#pragma unroll
+            for (int g = 0; g < G; g++) {
+                const float wu = bcast(w[g], up), wd = bcast(w[g], dn);
+                st.acc[g][0] = fmaf(wu, fau[k], st.acc[g][0]);
+                st.acc[g][0] = fmaf(wd, fad[k], st.acc[g][0]);
+                st.acc[g][1] = fmaf(wu, fbu[k], st.acc[g][1]);
+                st.acc[g][1] = fmaf(wd, fbd[k], st.acc[g][1]);
             }
         }
     }
 }
 
-// copy a record (n16 units of 16 bytes) from global memory into this wave's LDS staging area
-__device__ __forceinline__ void stage_record(uint4 *stage, const uint4 *rec, uint32_t n16, int lane) {
-    for (uint32_t i = lane; i < n16; i += 64) stage[i] = rec[i];
+// Rare path: a record larger than the LDS staging area is decoded straight from global memory.  Kept out of line so
+// that it costs the common path no registers.
+template <int G, int NS>
+__device__ __noinline__ void k_block_global(const uint32_t *rec, const char *lut, uint32_t mask2,
+                                            const float (&qreg)[G][2], float two_eb, float scale, int lane,
+                                            float (&score)[G]) {
+    k_block<G, NS>(rec, lut, mask2, qreg, two_eb, scale, lane, score);
+}
+template <int G, int NS>
+__device__ __noinline__ void v_block_global(const uint32_t *rec, const char *lut, uint32_t mask2, const float (&p)[G],
+                                            float two_eb, int lane, Soft<G> &st) {
+    v_block<G, NS>(rec, lut, mask2, p, two_eb, lane, st);
 }
 
-constexpr int kWaves = 4;
+// A record on its way from global memory to the wave's LDS staging area: the first 8 KiB travel through
+// registers (loads issued early, stored to LDS later), the rest is copied at commit time.
+constexpr int kPrefetchRegs = 8;
+struct Prefetch {
+    uint4 r[kPrefetchRegs];
+    const uint4 *src;
+    uint32_t n16;
+    __device__ __forceinline__ void issue(const uint8_t *rec, uint32_t size16, int lane) {
+        src = reinterpret_cast<const uint4 *>(rec);
+        n16 = size16;
+#pragma unroll
+        for (int i = 0; i < kPrefetchRegs; i++) {
+            const uint32_t at = min((uint32_t)(lane + 64 * i), size16 - 1u);  // clamped: every load is in bounds
+            r[i] = src[at];
+        }
+    }
+    __device__ __forceinline__ void commit(uint4 *stage, int lane) const {
+#pragma unroll
+        for (int i = 0; i < kPrefetchRegs; i++)
+            if (lane + 64 * i < n16) stage[lane + 64 * i] = r[i];
+        for (uint32_t i = lane + 64 * kPrefetchRegs; i < n16; i += 64) stage[i] = src[i];
+    }
+};
 
-template <int G>
-__global__ __launch_bounds__(64 * kWaves, 4) void fused_attn_kernel(FusedArgs a) {
-    extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
-    // LDS map: [lut K 8K][lut V 8K][q as float G*128][per wave: stage][per wave: wts G*128 floats]
-    uint16_t *lutK = reinterpret_cast<uint16_t *>(smem);
-    uint16_t *lutV = lutK + kLutSize;
-    float *qf = reinterpret_cast<float *>(smem + 2 * kLutSize * 2);
-    uint8_t *stage_base = reinterpret_cast<uint8_t *>(qf + G * kD);
+constexpr int kWaves = 4;
+constexpr int kThreads = 64 * kWaves;
+
+// NS = symbols per 32-bit window = floor(31 / longest code word), clipped to 2..5.
+template <int NS> struct LutCap { static constexpr int entries = NS >= 5 ? 64 : NS == 4 ? 128 : NS == 3 ? 1024 : kLutSize; };
+
+template <int G, int NS>
+__global__ __launch_bounds__(kThreads, 4) void fused_attn_kernel(FusedArgs a) {
+    __shared__ __attribute__((aligned(16))) uint16_t lut_s[2][LutCap<NS>::entries];
+    __shared__ __attribute__((aligned(16))) float qf[G * kD];
+    extern __shared__ __attribute__((aligned(16))) uint8_t smem[];  // one staging area per wave
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    uint8_t *stage = stage_base + (size_t)wave * a.stage_bytes;
-    float *wts = reinterpret_cast<float *>(stage_base + (size_t)kWaves * a.stage_bytes) + wave * G * kD;
+    uint8_t *stage = smem + (size_t)wave * a.stage_bytes;
+    const char *lutK = reinterpret_cast<const char *>(&lut_s[0][0]);
+    const char *lutV = reinterpret_cast<const char *>(&lut_s[1][0]);
 
     const Geo &g = a.g;
     const int split = blockIdx.x, bh = blockIdx.y;
     const int b = bh / g.H, h = bh - b * g.H;
 
-    // workgroup prologue: lookup tables and the G query vectors of this KV head
-    {
-        const uint4 *src = reinterpret_cast<const uint4 *>(g.lut);
-        uint4 *dst = reinterpret_cast<uint4 *>(smem);
-        for (int i = tid; i < 2 * kLutSize * 2 / 16; i += 64 * kWaves) dst[i] = src[i];
-        for (int i = tid; i < G * kD; i += 64 * kWaves)
-            qf[i] = h2f(a.q[((size_t)b * g.Hq + (size_t)h * G) * kD + i]);
+    // workgroup prologue: decode tables and the G query vectors of this KV head
+    for (int t = 0; t < 2; t++) {
+        const uint4 *src = reinterpret_cast<const uint4 *>(g.lut + t * kLutSize);
+        uint4 *dst = reinterpret_cast<uint4 *>(&lut_s[t][0]);
+        const int n16 = max(1, (2 << g.lut_bits[t]) / 16);
+        for (int i = tid; i < n16; i += kThreads) dst[i] = src[i];
     }
+    for (int i = tid; i < G * kD; i += kThreads) qf[i] = h2f(a.q[((size_t)b * g.Hq + (size_t)h * G) * kD + i]);
     __syncthreads();
     float qreg[G][2];
 #pragma unroll
@@ -234,46 +379,77 @@ __global__ __launch_bounds__(64 * kWaves, 4) void fused_attn_kernel(FusedArgs a)
     const int j1 = min(j0 + a.blocks_per_split, a.n_blocks);
     const BlockEntry *tabK = g.table + ((size_t)0 * g.B * g.H + bh) * g.max_blocks;
     const BlockEntry *tabV = g.table + ((size_t)1 * g.B * g.H + bh) * g.max_blocks;
-    const uint32_t stage16 = (uint32_t)a.stage_bytes / 16 - 1;  // one unit of slack for the reader's look-ahead
+    const uint32_t stage16 = (uint32_t)a.stage_bytes / 16 - 1;  // one unit of slack for the streams' look-ahead
+    uint4 *stage4 = reinterpret_cast<uint4 *>(stage);
+    const uint32_t *stage32 = reinterpret_cast<const uint32_t *>(stage);
 
-    for (int j = j0 + wave; j < j1; j += kWaves) {
+    int j = j0 + wave;
+    Prefetch pf;
+#pragma unroll
+    for (int i = 0; i < kPrefetchRegs; i++) pf.r[i] = make_uint4(0, 0, 0, 0);
+    pf.src = nullptr;
+    pf.n16 = 0;
+    BlockEntry eK = {0, 0}, eV = {0, 0};
+    if (j < j1) {
+        eK = tabK[j];
+        eV = tabV[j];
+        if (eK.size16 <= stage16) {
+            pf.issue(g.payload + (size_t)eK.off16 * 16, eK.size16, lane);
+            pf.commit(stage4, lane);
+        }
+        wave_sync();
+    }
+    while (j < j1) {
         float score[G], p[G];
-        {
-            const BlockEntry e = tabK[j];
-            const uint8_t *rec = g.payload + (size_t)e.off16 * 16;
-            if (e.size16 <= stage16) {
-                stage_record(reinterpret_cast<uint4 *>(stage), reinterpret_cast<const uint4 *>(rec), e.size16, lane);
-                wave_sync();
-                WordSrc pay{reinterpret_cast<const uint32_t *>(stage + kHdrBytesK)};
-                k_block<G>(reinterpret_cast<const uint32_t *>(stage), pay, lutK, wts, qreg, g.two_eb[0], a.scale, lane, score);
-            } else {  // record larger than the staging area: decode from global memory
-                WordSrc pay{reinterpret_cast<const uint32_t *>(rec + kHdrBytesK)};
-                k_block<G>(reinterpret_cast<const uint32_t *>(rec), pay, lutK, wts, qreg, g.two_eb[0], a.scale, lane, score);
-            }
+        const bool k_staged = eK.size16 <= stage16, v_staged = eV.size16 <= stage16;
+        const uint8_t *recK = g.payload + (size_t)eK.off16 * 16, *recV = g.payload + (size_t)eV.off16 * 16;
+        if (v_staged) pf.issue(recV, eV.size16, lane);  // V record travels while K is decoded
+        if (k_staged) {
+            k_block<G, NS>(stage32, lutK, a.mask2[0], qreg, g.two_eb[0], a.scale, lane, score);
+        } else {  // larger than the staging area: decode from global memory (copies keep the hot state in registers)
+            float q_tmp[G][2], s_tmp[G];
+#pragma unroll
+            for (int gg = 0; gg < G; gg++) { q_tmp[gg][0] = qreg[gg][0]; q_tmp[gg][1] = qreg[gg][1]; }
+            k_block_global<G, NS>(reinterpret_cast<const uint32_t *>(recK), lutK, a.mask2[0], q_tmp, g.two_eb[0], a.scale,
+                                  lane, s_tmp);
+#pragma unroll
+            for (int gg = 0; gg < G; gg++) score[gg] = s_tmp[gg];
         }
 #pragma unroll
         for (int gg = 0; gg < G; gg++) p[gg] = st.update(gg, score[gg]);
-        wave_sync();  // all lanes are done with the K stage and weights before they are overwritten
-        {
-            const BlockEntry e = tabV[j];
-            const uint8_t *rec = g.payload + (size_t)e.off16 * 16;
-            if (e.size16 <= stage16) {
-                stage_record(reinterpret_cast<uint4 *>(stage), reinterpret_cast<const uint4 *>(rec), e.size16, lane);
-                wave_sync();
-                WordSrc pay{reinterpret_cast<const uint32_t *>(stage + kHdrBytesV)};
-                v_block<G>(reinterpret_cast<const uint32_t *>(stage), pay, lutV, wts, p, g.two_eb[1], lane, st);
-            } else {
-                WordSrc pay{reinterpret_cast<const uint32_t *>(rec + kHdrBytesV)};
-                v_block<G>(reinterpret_cast<const uint32_t *>(rec), pay, lutV, wts, p, g.two_eb[1], lane, st);
-            }
+        wave_sync();  // every lane is done with the K record
+        if (v_staged) pf.commit(stage4, lane);
+        wave_sync();
+        const int jn = j + kWaves;
+        BlockEntry eKn = {0, 0}, eVn = {0, 0};
+        if (jn < j1) {
+            eKn = tabK[jn];
+            eVn = tabV[jn];
+            if (eKn.size16 <= stage16) pf.issue(g.payload + (size_t)eKn.off16 * 16, eKn.size16, lane);
+        }
+        if (v_staged) {
+            v_block<G, NS>(stage32, lutV, a.mask2[1], p, g.two_eb[1], lane, st);
+        } else {
+            Soft<G> st_tmp = st;
+            float p_tmp[G];
+#pragma unroll
+            for (int gg = 0; gg < G; gg++) p_tmp[gg] = p[gg];
+            v_block_global<G, NS>(reinterpret_cast<const uint32_t *>(recV), lutV, a.mask2[1], p_tmp, g.two_eb[1], lane,
+                                  st_tmp);
+            st = st_tmp;
         }
         wave_sync();
+        if (jn < j1 && eKn.size16 <= stage16) pf.commit(stage4, lane);
+        wave_sync();
+        eK = eKn;
+        eV = eVn;
+        j = jn;
     }
 
     // The buffered fp16 tokens (Section 3.2.3: the newest vectors take part too): last split, wave 0.
     if (split == a.n_splits - 1 && wave == 0 && a.n_res > 0) {
         const size_t res_tensor = (size_t)g.B * kBT * g.H * kD;
-        float acc[G];
+        float acc[G], pr[G];
 #pragma unroll
         for (int gg = 0; gg < G; gg++) acc[gg] = 0.f;
         if (lane < a.n_res) {
@@ -293,97 +469,85 @@ __global__ __launch_bounds__(64 * kWaves, 4) void fused_attn_kernel(FusedArgs a)
             }
         }
 #pragma unroll
-        for (int gg = 0; gg < G; gg++) {
-            const float s = lane < a.n_res ? a.scale * acc[gg] : -INFINITY;
-            wts[gg * kBT + lane] = st.update(gg, s);
-        }
-        wave_sync();
+        for (int gg = 0; gg < G; gg++) pr[gg] = st.update(gg, lane < a.n_res ? a.scale * acc[gg] : -INFINITY);
         const uint16_t *vr = g.res + res_tensor + (((size_t)b * kBT) * g.H + h) * kD;
         for (int t = 0; t < a.n_res; t++) {
-            const float v0 = h2f(vr[(size_t)t * g.H * kD + lane]);
-            const float v1 = h2f(vr[(size_t)t * g.H * kD + lane + 64]);
+            const uint32_t vv = *reinterpret_cast<const uint32_t *>(vr + (size_t)t * g.H * kD + 2 * lane);
+            const float v0 = h2f(vv & 0xffffu), v1 = h2f(vv >> 16);
 #pragma unroll
             for (int gg = 0; gg < G; gg++) {
-                const float pw = wts[gg * kBT + t];
+                const float pw = bcast(pr[gg], t);
                 st.acc[gg][0] = fmaf(pw, v0, st.acc[gg][0]);
                 st.acc[gg][1] = fmaf(pw, v1, st.acc[gg][1]);
             }
         }
-        wave_sync();
     }
+    wave_sync();
 
-    // merge the waves of this workgroup, then write one partial (o[128], m, l) per query head and split
+    // merge the waves of this workgroup into one partial (o[128], m, l) per query head
     float *comb = reinterpret_cast<float *>(stage);  // this wave's own staging area: G * 130 floats
 #pragma unroll
     for (int gg = 0; gg < G; gg++) {
         const float l = wave_sum(st.l[gg]);
         const float bv = wave_sum(st.bv[gg]);
-        comb[gg * kPartialStride + lane] = st.acc[gg][0] + bv;
-        comb[gg * kPartialStride + lane + 64] = st.acc[gg][1] + bv;
+        comb[gg * kPartialStride + 2 * lane] = st.acc[gg][0] + bv;
+        comb[gg * kPartialStride + 2 * lane + 1] = st.acc[gg][1] + bv;
         if (lane == 0) {
             comb[gg * kPartialStride + kD] = st.m[gg];
             comb[gg * kPartialStride + kD + 1] = l;
         }
     }
     __syncthreads();
-    for (int i = tid; i < G * kD; i += 64 * kWaves) {
+    const int row0 = b * g.Hq + h * G;
+    for (int i = tid; i < G * kD; i += kThreads) {
         const int gg = i / kD, c = i - gg * kD;
         float M = -INFINITY;
+#pragma unroll
         for (int w = 0; w < kWaves; w++)
-            M = fmaxf(M, reinterpret_cast<const float *>(stage_base + (size_t)w * a.stage_bytes)[gg * kPartialStride + kD]);
+            M = fmaxf(M, reinterpret_cast<const float *>(smem + (size_t)w * a.stage_bytes)[gg * kPartialStride + kD]);
         float L = 0.f, O = 0.f;
+#pragma unroll
         for (int w = 0; w < kWaves; w++) {
-            const float *cw = reinterpret_cast<const float *>(stage_base + (size_t)w * a.stage_bytes) + gg * kPartialStride;
+            const float *cw = reinterpret_cast<const float *>(smem + (size_t)w * a.stage_bytes) + gg * kPartialStride;
             const float mw = cw[kD];
             const float f = mw == -INFINITY ? 0.f : __expf(mw - M);
             L += cw[kD + 1] * f;
             O += cw[c] * f;
         }
-        float *dst = g.partials + (((size_t)b * g.Hq + (size_t)h * G + gg) * kMaxSplits + split) * kPartialStride;
-        dst[c] = O;
-        if (c == 0) { dst[kD] = M; dst[kD + 1] = L; }
+        if (a.n_splits == 1) {
+            a.out[(size_t)(row0 + gg) * kD + c] = O / L;
+        } else {
+            float *dst = g.partials + ((size_t)(row0 + gg) * kMaxSplits + split) * kPartialStride;
+            store_agent(dst + c, O);
+            if (c == 0) { store_agent(dst + kD, M); store_agent(dst + kD + 1, L); }
+        }
     }
+    if (a.n_splits > 1) finish_splits<G, kThreads>(g.partials, g.counters + bh, row0, a.n_splits, a.out, tid);
 }
 
-// Merge the sequence splits: out = sum_s o_s e^{m_s - M} / sum_s l_s e^{m_s - M}.
-__global__ __launch_bounds__(kD) void combine_kernel(const float *__restrict__ partials, int n_splits,
-                                                      float *__restrict__ out) {
-    const int row = blockIdx.x, c = threadIdx.x;
-    const float *p = partials + (size_t)row * kMaxSplits * kPartialStride;
-    float M = -INFINITY;
-    for (int s = 0; s < n_splits; s++) M = fmaxf(M, p[s * kPartialStride + kD]);
-    float L = 0.f, O = 0.f;
-    for (int s = 0; s < n_splits; s++) {
-        const float ms = p[s * kPartialStride + kD];
-        const float f = ms == -INFINITY ? 0.f : __expf(ms - M);
-        L += p[s * kPartialStride + kD + 1] * f;
-        O += p[s * kPartialStride + c] * f;
-    }
-    out[(size_t)row * kD + c] = O / L;
-}
-
-hipError_t launch_combine(const float *partials, int rows, int n_splits, float *out, hipStream_t s) {
-    hipLaunchKernelGGL(combine_kernel, dim3(rows), dim3(kD), 0, s, partials, n_splits, out);
-    return hipGetLastError();
-}
-
-template <int G>
-static hipError_t launch_fused_g(const FusedArgs &a, size_t lds, hipEvent_t ev0, hipEvent_t ev1, hipStream_t s) {
+template <int G, int NS>
+static hipError_t launch_fused_gn(const FusedArgs &a, size_t lds, hipEvent_t ev0, hipEvent_t ev1, hipStream_t s) {
     static size_t attr_set = 0;
     if (lds > attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&fused_attn_kernel<G>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&fused_attn_kernel<G, NS>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
         attr_set = lds;
     }
     if (ev0) (void)hipEventRecord(ev0, s);
-    hipLaunchKernelGGL(fused_attn_kernel<G>, dim3(a.n_splits, a.g.B * a.g.H), dim3(64 * kWaves), lds, s, a);
+    hipLaunchKernelGGL((fused_attn_kernel<G, NS>), dim3(a.n_splits, a.g.B * a.g.H), dim3(kThreads), lds, s, a);
     if (ev1) (void)hipEventRecord(ev1, s);
     return hipGetLastError();
 }
 
-size_t fused_lds_bytes(int G, int stage_bytes) {
-    return (size_t)2 * kLutSize * 2 + (size_t)G * kD * 4 + (size_t)kWaves * stage_bytes + (size_t)kWaves * G * kD * 4;
+template <int G>
+static hipError_t launch_fused_g(const FusedArgs &a, int ns, size_t lds, hipEvent_t ev0, hipEvent_t ev1, hipStream_t s) {
+    switch (ns) {
+        case 5: return launch_fused_gn<G, 5>(a, lds, ev0, ev1, s);
+        case 4: return launch_fused_gn<G, 4>(a, lds, ev0, ev1, s);
+        case 3: return launch_fused_gn<G, 3>(a, lds, ev0, ev1, s);
+        default: return launch_fused_gn<G, 2>(a, lds, ev0, ev1, s);
+    }
 }
 
 hipError_t launch_fused_attn(const Geo &g, const uint16_t *q, float scale, float *out, int n_blocks, int n_res,
@@ -391,23 +555,68 @@ hipError_t launch_fused_attn(const Geo &g, const uint16_t *q, float scale, float
     FusedArgs a;
     a.g = g;
     a.q = q;
+    a.out = out;
     a.scale = scale;
     a.n_blocks = n_blocks;
     a.n_res = n_res;
     a.blocks_per_split = n_blocks > 0 ? (n_blocks + n_splits - 1) / n_splits : 0;
     a.n_splits = n_blocks > 0 ? (n_blocks + a.blocks_per_split - 1) / a.blocks_per_split : 1;
     a.stage_bytes = stage_bytes;
-    const size_t lds = fused_lds_bytes(g.G, stage_bytes);
-    hipError_t e;
+    const int bits_k = g.lut_bits[0], bits_v = g.lut_bits[1];
+    const int longest = bits_k > bits_v ? bits_k : bits_v;
+    if (longest < 1 || longest > kLutBits) return hipErrorInvalidValue;
+    a.mask2[0] = ((1u << bits_k) - 1u) << 1;
+    a.mask2[1] = ((1u << bits_v) - 1u) << 1;
+    const int ns = longest <= 6 ? 5 : longest <= 7 ? 4 : longest <= 10 ? 3 : 2;
+    const size_t lds = (size_t)kWaves * stage_bytes;
     switch (g.G) {
-        case 1: e = launch_fused_g<1>(a, lds, ev0, ev1, s); break;
-        case 2: e = launch_fused_g<2>(a, lds, ev0, ev1, s); break;
-        case 4: e = launch_fused_g<4>(a, lds, ev0, ev1, s); break;
-        case 8: e = launch_fused_g<8>(a, lds, ev0, ev1, s); break;
+        case 1: return launch_fused_g<1>(a, ns, lds, ev0, ev1, s);
+        case 2: return launch_fused_g<2>(a, ns, lds, ev0, ev1, s);
+        case 4: return launch_fused_g<4>(a, ns, lds, ev0, ev1, s);
+        case 8: return launch_fused_g<8>(a, ns, lds, ev0, ev1, s);
         default: return hipErrorInvalidValue;
     }
-    if (e != hipSuccess) return e;
-    return launch_combine(g.partials, g.B * g.Hq, a.n_splits, out, s);
+}
+
+// ---- statistics (metrics path, not part of the hot loop) --------------------------------------------------------
+// Sums record sizes and code-word bits over all blocks in use by walking the Block Offsets Array and the slice bit
+// counts in the record headers.
+__global__ __launch_bounds__(256) void stats_kernel(Geo g, int n_blocks) {
+    const int BH = g.B * g.H;
+    const long long n_items = 2ll * BH * n_blocks;
+    unsigned long long bits[2] = {0, 0}, rec16[2] = {0, 0};
+    const int lane = threadIdx.x & 63;
+    const long long wave_id = ((long long)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+    const long long n_waves = ((long long)gridDim.x * blockDim.x) >> 6;
+    for (long long i = wave_id; i < n_items; i += n_waves) {
+        const int which = (int)(i / ((long long)BH * n_blocks));
+        const long long rem = i - (long long)which * BH * n_blocks;
+        const int bh = (int)(rem / n_blocks), j = (int)(rem - (long long)bh * n_blocks);
+        const BlockEntry e = g.table[((size_t)which * BH + bh) * g.max_blocks + j];
+        const uint16_t *sb = reinterpret_cast<const uint16_t *>(g.payload + (size_t)e.off16 * 16 +
+                                                                (which ? kMinMaxBytesV : kMinMaxBytesK));
+        const uint32_t v = (uint32_t)sb[lane] + sb[lane + 64];
+        bits[which] += v;
+        if (lane == 0) rec16[which] += e.size16;
+    }
+    for (int w = 0; w < 2; w++) {
+        unsigned long long bsum = bits[w], rsum = rec16[w];
+#pragma unroll
+        for (int m = 32; m >= 1; m >>= 1) {
+            bsum += __shfl_xor(bsum, m);
+            rsum += __shfl_xor(rsum, m);
+        }
+        if (lane == 0 && (bsum | rsum)) {
+            atomicAdd(&g.ctrl->payload_bits[w], bsum);
+            atomicAdd(&g.ctrl->record16[w], rsum);
+        }
+    }
+}
+
+hipError_t launch_stats(const Geo &g, int n_blocks, hipStream_t s) {
+    if (n_blocks <= 0) return hipSuccess;
+    hipLaunchKernelGGL(stats_kernel, dim3(128), dim3(256), 0, s, g, n_blocks);
+    return hipGetLastError();
 }
 
 }  // namespace kvc

@@ -20,8 +20,8 @@ struct Rec {
     static constexpr int minmax_bytes = WHICH == 0 ? kMinMaxBytesK : kMinMaxBytesV;
     static constexpr int hdr_bytes = WHICH == 0 ? kHdrBytesK : kHdrBytesV;
     static constexpr int n_units = WHICH == 0 ? kD : kBT;
-    static constexpr int n_slices = WHICH == 0 ? kBT : kD;
-    static constexpr int parts = WHICH == 0 ? 4 : 2;  // threads per slice, 32 symbols each
+    static constexpr int n_slices = kSlices;
+    static constexpr int parts = 2;  // threads per slice, 32 symbols each
 };
 
 __device__ __forceinline__ uint32_t record_size16(int hdr_bytes, uint32_t total_bits) {
@@ -48,7 +48,7 @@ __global__ __launch_bounds__(256) void size_kernel(Geo g, const uint16_t *__rest
     __shared__ uint32_t scratch[4];
     const int tid = threadIdx.x, blk = blockIdx.x;
     const int bh = blk / n_blk_per_bh, j = blk - bh * n_blk_per_bh;
-    enc[tid] = g.enc[WHICH * 256 + tid];
+    enc[tid] = g.enc[WHICH * 512 + tid];
     TileRegs r;
     const bool bad = load_tile(X, seq_stride, g.H, bh / g.H, bh % g.H, j, tid, r);
     quantize_tile<WHICH>(r, sh, tid, g.two_eb[WHICH], g.n_sym[WHICH]);  // has barriers: enc[] is visible after it
@@ -61,9 +61,6 @@ __global__ __launch_bounds__(256) void size_kernel(Geo g, const uint16_t *__rest
     if (tid == 0) {
         const uint32_t s16 = record_size16(Rec<WHICH>::hdr_bytes, total);
         g.table[((size_t)WHICH * g.B * g.H + bh) * g.max_blocks + dst_blk0 + j].size16 = s16;
-        atomicAdd(&g.ctrl->payload_bits[WHICH], (unsigned long long)total);
-        atomicAdd(&g.ctrl->record16[WHICH], (unsigned long long)s16);
-        atomicMax(&g.ctrl->max_size16, s16);
     }
     if (bad) atomicOr(&g.ctrl->nonfinite, 1u);
 }
@@ -84,8 +81,15 @@ __global__ __launch_bounds__(1024) void place_kernel(Geo g, int n_blk_per_bh, in
         const int bh = rem / n_blk_per_bh, j = rem - bh * n_blk_per_bh;
         return &g.table[((size_t)which * BH + bh) * g.max_blocks + dst_blk0 + j];
     };
-    uint32_t sum = 0;
-    for (int i = i0; i < i1; i++) sum += entry(i)->size16;
+    uint32_t sum = 0, biggest = 0;
+    for (int i = i0; i < i1; i++) {
+        const uint32_t s16 = entry(i)->size16;
+        sum += s16;
+        biggest = max(biggest, s16);
+    }
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) biggest = max(biggest, (uint32_t)__shfl_xor(biggest, m));
+    if ((tid & 63) == 0 && biggest) atomicMax(&g.ctrl->max_size16, biggest);
     // inclusive scan of `sum` over the 1024 threads
     uint32_t inc = sum;
 #pragma unroll
@@ -116,13 +120,14 @@ __global__ __launch_bounds__(256) void write_kernel(Geo g, const uint16_t *__res
                                                      int n_blk_per_bh, int dst_blk0) {
     using R = Rec<WHICH>;
     __shared__ QuantShared sh;
-    __shared__ uint32_t enc[256];
+    __shared__ uint32_t enc[512];  // [0..256) first-bit-first, [256..512) last-bit-first
     __shared__ uint32_t wave_tot[4];
     __shared__ __attribute__((aligned(16))) uint8_t code_tile[kBT * kCodeRow];
     __shared__ __attribute__((aligned(16))) uint32_t rec[(kMaxRecordBytes + 15) / 16 * 4];
     const int tid = threadIdx.x, blk = blockIdx.x;
     const int bh = blk / n_blk_per_bh, j = blk - bh * n_blk_per_bh;
-    enc[tid] = g.enc[WHICH * 256 + tid];
+    enc[tid] = g.enc[WHICH * 512 + tid];
+    enc[256 + tid] = g.enc[WHICH * 512 + 256 + tid];
     for (int i = tid; i < (int)(sizeof(rec) / 4); i += 256) rec[i] = 0;
     TileRegs r;
     load_tile(X, seq_stride, g.H, bh / g.H, bh % g.H, j, tid, r);
@@ -138,16 +143,17 @@ __global__ __launch_bounds__(256) void write_kernel(Geo g, const uint16_t *__res
     }
     if (tid < R::n_units) rec[tid] = float_to_half_bits(sh.unit_mn[tid]) | (float_to_half_bits(sh.unit_mx[tid]) << 16);
     __syncthreads();
-    // Each thread encodes 32 symbols of one slice (Section 3.2.2 stage 2).  K: slice = token row, symbols in channel
-    // order; V: slice = channel column, symbols in token order.
+    // Each thread encodes 32 symbols, half of one slice (Section 3.2.2 stage 2).  K: slice s = token s/2, channels
+    // 64*(s%2)..+63 in channel order; V: slice s = channel s, tokens in order.  The first half of a slice is written
+    // first-bit-first, the second half last-bit-first (it is decoded downwards from the slice end).
     const int slice = tid / R::parts, part = tid % R::parts;
     uint32_t sym[32];
     uint32_t bits = 0;
 #pragma unroll
     for (int k = 0; k < 32; k++) {
-        const int t = WHICH == 0 ? slice : 32 * part + k;
-        const int c = WHICH == 0 ? 32 * part + k : slice;
-        sym[k] = enc[code_tile[t * kCodeRow + c]];
+        const int t = WHICH == 0 ? (slice >> 1) : 32 * part + k;
+        const int c = WHICH == 0 ? kSliceLen * (slice & 1) + 32 * part + k : slice;
+        sym[k] = enc[256 * part + code_tile[t * kCodeRow + c]];
         bits += sym[k] >> 16;
     }
     // stage 3: inclusive scan of the bit counts over the workgroup -> bit offset of every thread
@@ -170,7 +176,7 @@ __global__ __launch_bounds__(256) void write_kernel(Geo g, const uint16_t *__res
         total += wave_tot[w];
     }
     // stage 4: aggregate all code words into one contiguous chunk in LDS.  Bit i of the chunk is bit (i % 32) of
-    // word (i / 32); a code word goes out first-bit-first, so the table holds it bit-reversed.
+    // word (i / 32); the table holds every code word in the bit order in which it enters the chunk.
     uint32_t *pay = rec + R::hdr_bytes / 4;
     uint32_t pos = before + inc - bits;
     uint32_t word = pos >> 5, fill = pos & 31;

@@ -50,7 +50,10 @@ bool valid_cfg(const kvcomp_config *c) {
     if (c->max_seq < 1) return false;
     if (n_sym_for(c->rel_eb_k) < 0 || n_sym_for(c->rel_eb_v) < 0) return false;
     if (c->k_mode != 0) return false;
-    if (c->max_code_len != 0 && (c->max_code_len < 8 || c->max_code_len > kLutBits)) return false;
+    if (c->max_code_len != 0) {  // every level needs a code word: 2^max_code_len >= number of levels
+        const int levels = std::max(n_sym_for(c->rel_eb_k), n_sym_for(c->rel_eb_v));
+        if (c->max_code_len > kLutBits || (1 << c->max_code_len) < levels) return false;
+    }
     if ((long long)c->batch * c->n_kv_heads * ((long long)c->max_seq / kBT + 1) > (1ll << 28)) return false;
     return true;
 }
@@ -58,7 +61,7 @@ bool valid_cfg(const kvcomp_config *c) {
 int code_len_limit(const kvcomp_config &c) { return c.max_code_len ? c.max_code_len : kLutBits; }
 
 struct Layout {
-    size_t ctrl, hist, enc, lut, table, res, partials, payload, total;
+    size_t ctrl, hist, enc, lut, counters, table, res, partials, payload, total;
     size_t payload_cap16;
     int max_blocks;
 };
@@ -73,8 +76,9 @@ Layout make_layout(const kvcomp_config &c) {
     size_t at = 0;
     L.ctrl = at; at += 256;
     L.hist = at; at += 2 * 256 * 4;
-    L.enc = at; at += 2 * 256 * 4;
+    L.enc = at; at += 4 * 256 * 4;
     L.lut = at; at += 2 * kLutSize * 2;
+    L.counters = at; at += align_up(BH * 4, 256);
     L.table = at; at += align_up(2 * BH * (size_t)std::max(L.max_blocks, 1) * sizeof(BlockEntry), 256);
     L.res = at; at += align_up(2 * (size_t)c.batch * kBT * c.n_kv_heads * kD * 2, 256);
     L.partials = at; at += align_up((size_t)c.batch * c.n_q_heads * kMaxSplits * kPartialStride * 4, 256);
@@ -167,7 +171,7 @@ struct kvcomp_ctx {
     // pinned host staging
     Ctrl *h_ctrl;
     uint32_t *h_hist;  // [2][256]
-    uint32_t *h_enc;   // [2][256]
+    uint32_t *h_enc;   // [2 tensors][2 directions][256]
     uint16_t *h_lut;   // [2][4096]
 };
 
@@ -241,12 +245,14 @@ kvcomp_status kvcomp_create(const kvcomp_config *cfg, void *d_arena, size_t aren
     g.hist = reinterpret_cast<uint32_t *>(c->arena + L.hist);
     g.enc = reinterpret_cast<uint32_t *>(c->arena + L.enc);
     g.lut = reinterpret_cast<uint16_t *>(c->arena + L.lut);
+    g.lut_bits[0] = g.lut_bits[1] = kLutBits;
+    g.counters = reinterpret_cast<uint32_t *>(c->arena + L.counters);
     g.table = reinterpret_cast<BlockEntry *>(c->arena + L.table);
     g.res = reinterpret_cast<uint16_t *>(c->arena + L.res);
     g.partials = reinterpret_cast<float *>(c->arena + L.partials);
     g.payload = c->arena + L.payload;
     void *pinned = nullptr;
-    const size_t pin_bytes = 256 + 2 * 256 * 4 + 2 * 256 * 4 + 2 * kLutSize * 2;
+    const size_t pin_bytes = 256 + 2 * 256 * 4 + 4 * 256 * 4 + 2 * kLutSize * 2;
     hipError_t e = hipHostMalloc(&pinned, pin_bytes, hipHostMallocDefault);
     if (e != hipSuccess) {
         delete c;
@@ -256,7 +262,7 @@ kvcomp_status kvcomp_create(const kvcomp_config *cfg, void *d_arena, size_t aren
     c->h_ctrl = reinterpret_cast<Ctrl *>(pb);
     c->h_hist = reinterpret_cast<uint32_t *>(pb + 256);
     c->h_enc = reinterpret_cast<uint32_t *>(pb + 256 + 2048);
-    c->h_lut = reinterpret_cast<uint16_t *>(pb + 256 + 4096);
+    c->h_lut = reinterpret_cast<uint16_t *>(pb + 256 + 2048 + 4096);
     // control words, histogram, tables and the Block Offsets Array start at zero
     e = launch_fill_zero(c->arena, L.res, static_cast<hipStream_t>(stream));
     if (e != hipSuccess) {
@@ -294,7 +300,7 @@ kvcomp_status kvcomp_build_codebook(kvcomp_ctx *ctx, const void *d_K, const void
     const long long symbols = (long long)ctx->geo.B * ctx->geo.H * (seq / kBT) * kTile;
     if (symbols >= (1ll << 32)) return fail(KVCOMP_ERR_INVALID_ARG, "more than 2^32 symbols per tensor");
     hipStream_t s = static_cast<hipStream_t>(stream);
-    const Geo &g = ctx->geo;
+    Geo &g = ctx->geo;
     HIP_TRY(launch_fill_zero(g.hist, 2 * 256 * 4, s));
     HIP_TRY(launch_histogram(g, 0, static_cast<const uint16_t *>(d_K), seq, seq / kBT, s));
     HIP_TRY(launch_histogram(g, 1, static_cast<const uint16_t *>(d_V), seq, seq / kBT, s));
@@ -308,19 +314,23 @@ kvcomp_status kvcomp_build_codebook(kvcomp_ctx *ctx, const void *d_K, const void
     }
     for (int w = 0; w < 2; w++) {
         build_codebook_host(ctx->h_hist + 256 * w, g.n_sym[w], code_len_limit(ctx->cfg), ctx->len[w], ctx->code[w]);
-        uint32_t *enc = ctx->h_enc + 256 * w;
+        uint32_t *enc = ctx->h_enc + 512 * w;  // [0..256): written first-bit-first, [256..512): last-bit-first
         uint16_t *lut = ctx->h_lut + kLutSize * w;
-        std::memset(enc, 0, 256 * 4);
+        std::memset(enc, 0, 512 * 4);
         std::memset(lut, 0, kLutSize * 2);
+        // the decode table is indexed by as many stream bits as the longest code word of this codebook
+        const int bits = *std::max_element(ctx->len[w], ctx->len[w] + 256);
+        ctx->geo.lut_bits[w] = bits;
         for (int sy = 0; sy < 256; sy++) {
             const int L = ctx->len[w][sy];
             if (!L) continue;
-            const uint32_t rev = reverse_bits(ctx->code[w][sy], L);
+            const uint32_t rev = reverse_bits(ctx->code[w][sy], L);  // first stream bit = bit 0 of the index
             enc[sy] = ((uint32_t)L << 16) | rev;
-            for (uint32_t k = 0; k < (1u << (kLutBits - L)); k++) lut[rev | (k << L)] = (uint16_t)((sy << 8) | L);
+            enc[256 + sy] = ((uint32_t)L << 16) | ctx->code[w][sy];
+            for (uint32_t k = 0; k < (1u << (bits - L)); k++) lut[rev | (k << L)] = (uint16_t)((sy << 8) | L);
         }
     }
-    HIP_TRY(hipMemcpyAsync(g.enc, ctx->h_enc, 2 * 256 * 4, hipMemcpyHostToDevice, s));
+    HIP_TRY(hipMemcpyAsync(g.enc, ctx->h_enc, 4 * 256 * 4, hipMemcpyHostToDevice, s));
     HIP_TRY(hipMemcpyAsync(g.lut, ctx->h_lut, 2 * kLutSize * 2, hipMemcpyHostToDevice, s));
     HIP_TRY(hipStreamSynchronize(s));
     ctx->have_codebook = true;
@@ -377,21 +387,25 @@ kvcomp_status kvcomp_attn_decode(kvcomp_ctx *ctx, const void *d_q, float scale, 
     if (ctx->n_blocks && !ctx->have_codebook) return fail(KVCOMP_ERR_STATE, "no codebook");
     hipStream_t s = static_cast<hipStream_t>(stream);
     const Geo &g = ctx->geo;
-    // Work split: one wave per block pair while that still fills the chip, 4 waves per workgroup.
+    // Work split: the grid should fit the chip in a single round of workgroups (256 CUs x 4 resident workgroups of
+    // 4 waves), every wave owning whole block pairs; per-workgroup costs (tables, first record, split merge) are
+    // then paid once per resident slot instead of once per small workgroup.
     int n_splits = ctx->tune_splits;
     if (n_splits <= 0) {
-        const long long tasks = (long long)g.B * g.H * ctx->n_blocks;
-        long long per_wave = (tasks + 8191) / 8192;
-        if (per_wave < 1) per_wave = 1;
-        const long long bps = 4 * per_wave;
-        n_splits = (int)((ctx->n_blocks + bps - 1) / bps);
+        const int bh = g.B * g.H;
+        const int by_chip = std::max(1, 1024 / bh);
+        const int by_work = std::max(1, (ctx->n_blocks + 3) / 4);  // at least one block pair per wave
+        n_splits = std::min(by_chip, by_work);
+        int bps = (ctx->n_blocks + n_splits - 1) / std::max(n_splits, 1);
+        bps = (bps + 3) / 4 * 4;
+        n_splits = bps > 0 ? (ctx->n_blocks + bps - 1) / bps : 1;
     }
     n_splits = std::max(1, std::min({n_splits, (int)kMaxSplits, std::max(ctx->n_blocks, 1)}));
     int stage = ctx->tune_stage;
     if (stage <= 0) stage = (int)align_up((size_t)ctx->max_size16 * 16 + 16, 256);
     stage = std::max(stage, 4608);
     stage = (int)align_up(stage, 16);
-    const size_t lds_fixed = 2 * kLutSize * 2 + (size_t)g.G * kD * 4 + 4 * (size_t)g.G * kD * 4;
+    const size_t lds_fixed = 2 * kLutSize * 2 + (size_t)g.G * kD * 4 + 1024;  // decode tables, q, slack
     const size_t lds_max = 160 * 1024;
     if (lds_fixed + 4 * (size_t)stage > lds_max) stage = (int)((lds_max - lds_fixed) / 4 / 16 * 16);
     hipEvent_t ev0 = nullptr, ev1 = nullptr;
@@ -419,7 +433,10 @@ kvcomp_status kvcomp_attn_decode(kvcomp_ctx *ctx, const void *d_q, float scale, 
 
 kvcomp_status kvcomp_get_stats(kvcomp_ctx *ctx, kvcomp_stats *o, void *stream) {
     if (!ctx || !o) return fail(KVCOMP_ERR_INVALID_ARG, "NULL argument");
-    kvcomp_status st = read_ctrl(ctx, static_cast<hipStream_t>(stream));
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    HIP_TRY(hipMemsetAsync(ctx->geo.ctrl->payload_bits, 0, 4 * sizeof(unsigned long long), s));
+    HIP_TRY(launch_stats(ctx->geo, ctx->n_blocks, s));
+    kvcomp_status st = read_ctrl(ctx, s);
     if (st) return st;
     const Ctrl &c = *ctx->h_ctrl;
     const long long BH = (long long)ctx->geo.B * ctx->geo.H;
@@ -547,7 +564,7 @@ kvcomp_status kvcomp_get_profile(kvcomp_ctx *ctx, int *h_launches, double *h_tot
 
 size_t kvcomp_baseline_workspace_bytes(const kvcomp_config *cfg) {
     if (!cfg || cfg->batch < 1 || cfg->n_q_heads < 1) return 0;
-    return (size_t)cfg->batch * cfg->n_q_heads * kMaxSplits * kPartialStride * 4;
+    return (size_t)cfg->batch * cfg->n_q_heads * kMaxSplits * kPartialStride * 4 + (size_t)cfg->batch * cfg->n_kv_heads * 4;
 }
 
 kvcomp_status kvcomp_baseline_fp16_attn(const kvcomp_config *cfg, const void *d_K, const void *d_V, int seq,
@@ -568,7 +585,10 @@ kvcomp_status kvcomp_baseline_fp16_attn(const kvcomp_config *cfg, const void *d_
     n_splits = std::max(1, std::min(n_splits, (int)kMaxSplits));
     HIP_TRY(launch_baseline_attn(cfg->batch, cfg->n_kv_heads, cfg->n_q_heads, static_cast<const uint16_t *>(d_K),
                                  static_cast<const uint16_t *>(d_V), seq, static_cast<const uint16_t *>(d_q), scale, d_out,
-                                 static_cast<float *>(d_workspace), n_splits, static_cast<hipStream_t>(stream)));
+                                 static_cast<float *>(d_workspace),
+                                 reinterpret_cast<uint32_t *>(static_cast<float *>(d_workspace) +
+                                                              (size_t)cfg->batch * cfg->n_q_heads * kMaxSplits * kPartialStride),
+                                 n_splits, static_cast<hipStream_t>(stream)));
     return KVCOMP_OK;
 }
 

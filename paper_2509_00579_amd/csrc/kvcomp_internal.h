@@ -13,12 +13,19 @@ constexpr int kLutBits = 12;   // decode table index width = longest code word a
 constexpr int kLutSize = 1 << kLutBits;
 
 // Record layout (Section 3.2.2: per-thread bit counts + one contiguous chunk per 2D block):
-//   K: [128 x {min,max} fp16][64 x u16 slice bits][payload words][pad to 16 B]
+//   K: [128 x {min,max} fp16][128 x u16 slice bits][payload words][pad to 16 B]
 //   V: [ 64 x {min,max} fp16][128 x u16 slice bits][payload words][pad to 16 B]
+// Every block has 128 slices of 64 symbols: K slice s = token s/2, channels 64*(s%2)..+63; V slice s = channel s,
+// tokens 0..63.  A decoding lane owns two consecutive slices (K: one token; V: channels 2*lane, 2*lane+1).
+// A slice is written from both ends: symbols 0..31 first-bit-first upwards from its start, symbols 32..63
+// last-bit-first after them, so that reading downwards from the slice end yields symbols 63..32 first-bit-first.
+// Each slice is thus two independent decode chains; its end needs no extra offset (it is the next slice's start).
+constexpr int kSlices = 128;
+constexpr int kSliceLen = 64;
 constexpr int kMinMaxBytesK = 4 * kD;
 constexpr int kMinMaxBytesV = 4 * kBT;
-constexpr int kHdrBytesK = kMinMaxBytesK + 2 * kBT;   // 640
-constexpr int kHdrBytesV = kMinMaxBytesV + 2 * kD;    // 512
+constexpr int kHdrBytesK = kMinMaxBytesK + 2 * kSlices;   // 768
+constexpr int kHdrBytesV = kMinMaxBytesV + 2 * kSlices;   // 512
 constexpr int kMaxPayloadBytes = kTile * kLutBits / 8;  // 12288
 constexpr int kMaxRecordBytes = kHdrBytesK + kMaxPayloadBytes + 16;
 
@@ -35,6 +42,7 @@ struct Ctrl {
     uint32_t max_size16;    // largest record so far
     uint32_t nonfinite;     // set when an input value was Inf/NaN
     uint32_t pad;
+    // filled by the statistics kernel only (kvcomp_get_stats)
     unsigned long long payload_bits[2];
     unsigned long long record16[2];  // sum of record sizes per tensor, 16-byte units
 };
@@ -47,8 +55,11 @@ struct Geo {
     int n_sym[2];
     Ctrl *ctrl;
     uint32_t *hist;          // [2][256]
-    uint32_t *enc;           // [2][256]  (len << 16) | bit-reversed code word
-    uint16_t *lut;           // [2][4096] (symbol << 8) | len, indexed by the next 12 stream bits
+    uint32_t *enc;           // [2 tensors][2][256]  (len << 16) | code word as it goes into the LSB-first stream:
+                             //   [0]: first-bit-first (symbols 0..31 of a slice), [1]: last-bit-first (32..63)
+    uint16_t *lut;           // [2][4096] (symbol << 8) | len, indexed by the next lut_bits[t] stream bits
+    int lut_bits[2];         // index width of each decode table = longest code word of that codebook
+    uint32_t *counters;      // [B*H] split tickets of the fused kernel, zero between launches
     BlockEntry *table;       // [2][B*H][max_blocks]
     uint16_t *res;           // [2][B][64][H][128] fp16
     float *partials;         // [B*Hq][max_splits][kPartialStride]
@@ -72,7 +83,9 @@ hipError_t launch_append(const Geo &g, const uint16_t *k_new, const uint16_t *v_
 hipError_t launch_fused_attn(const Geo &g, const uint16_t *q, float scale, float *out, int n_blocks, int n_res,
                              int n_splits, int stage_bytes, hipEvent_t ev0, hipEvent_t ev1, hipStream_t s);
 hipError_t launch_baseline_attn(int B, int H, int Hq, const uint16_t *K, const uint16_t *V, int seq, const uint16_t *q,
-                                float scale, float *out, float *partials, int n_splits, hipStream_t s);
+                                float scale, float *out, float *partials, uint32_t *counters, int n_splits,
+                                hipStream_t s);
+hipError_t launch_stats(const Geo &g, int n_blocks, hipStream_t s);
 hipError_t launch_fill_zero(void *p, size_t bytes, hipStream_t s);
 
 }  // namespace kvc

@@ -1,5 +1,8 @@
 """Pins for the oracle's block encoder and its two decoders (Section 3.2.2, Figure 4; Section 3.3.1).
 
+Slices are written from both ends (two decodable chains per slice); with 1-bit code words the two directions
+coincide, which the first test uses to expose the plain bit and slice order.
+
 The record layout is checked against an independent bit packer (numpy.packbits, little bit order) on streams
 whose bits are known by construction, against the closed-form sizes, and by lossless round trips through two
 structurally different decoders (canonical bit-serial; the paper's array-tree walk).
@@ -19,8 +22,8 @@ def _hist(counts):
 
 
 def _slice_order(which, codes):
-    """Symbols in stream order: K -> token rows; V -> channel columns."""
-    return codes.reshape(64, 128) if which == K else codes.reshape(64, 128).T
+    """Symbols in stream order, [128 slices][64 symbols]: K -> half token rows; V -> channel columns."""
+    return codes.reshape(128, 64) if which == K else codes.reshape(64, 128).T
 
 
 def _pack_reference(which, codes, ln, cd, hdr):
@@ -28,7 +31,10 @@ def _pack_reference(which, codes, ln, cd, hdr):
     sl = _slice_order(which, codes)
     slice_bits, bits = [], []
     for s in range(sl.shape[0]):
-        w = "".join(format(int(cd[x]), "b").zfill(int(ln[x])) for x in sl[s])
+        words = [format(int(cd[x]), "b").zfill(int(ln[x])) for x in sl[s]]
+        # symbols 0..31 first-bit-first, symbols 32..63 last-bit-first (read downwards from the slice end they are
+        # the code words of 63, 62, .., 32 first-bit-first)
+        w = "".join(words[:32]) + "".join(x[::-1] for x in words[32:])
         slice_bits.append(len(w))
         bits.extend(int(ch) for ch in w)
     payload = np.packbits(np.array(bits, np.uint8), bitorder="little")
@@ -49,7 +55,7 @@ def test_one_bit_codes_expose_bit_and_slice_order(oracle, which):
     mm = np.arange(2 * oracle.n_units(which), dtype=np.uint16).reshape(-1, 2)
     rec = oracle.encode_block(which, codes, mm, ln, cd)
     hdr = oracle.header_bytes(which)
-    assert hdr == (512 + 128 if which == K else 256 + 256)
+    assert hdr == (512 + 256 if which == K else 256 + 256)
     assert len(rec) == hdr + 1024 and len(rec) % 16 == 0
     expect = np.packbits(_slice_order(which, codes).reshape(-1), bitorder="little")
     np.testing.assert_array_equal(rec[hdr:], expect)
@@ -59,7 +65,7 @@ def test_one_bit_codes_expose_bit_and_slice_order(oracle, which):
     assert [(w0 >> i) & 1 for i in range(32)] == list(first)
     # header: min/max pairs as little-endian binary16 patterns, then u16 bit counts
     np.testing.assert_array_equal(rec[: 4 * mm.shape[0]].view("<u2").reshape(-1, 2), mm)
-    nsl = 64 if which == K else 128
+    nsl = 128
     np.testing.assert_array_equal(rec[hdr - 2 * nsl:hdr].view("<u2"), np.full(nsl, 8192 // nsl, np.uint16))
 
 
@@ -113,7 +119,7 @@ def test_decoders_reject_a_wrong_slice_length(oracle):
     mm = np.zeros((128, 2), np.uint16)
     rec = oracle.encode_block(K, codes, mm, ln, cd)
     bad = rec.copy()
-    bad[512] ^= 1  # bit count of slice 0
+    bad[512] ^= 1  # bit count of slice 0 (the K header is 512 bytes of min/max pairs, then the counts)
     with pytest.raises(ValueError):
         oracle.decode_block_serial(K, bad, ln)
     with pytest.raises(ValueError):
@@ -121,7 +127,8 @@ def test_decoders_reject_a_wrong_slice_length(oracle):
 
 
 def test_metadata_overhead_closed_form(oracle):
-    # Section 3.2.2: one unsigned 16-bit bit count per encoded vector -> 16 / (head_dim * avg_bits) of the payload
+    # Section 3.2.2: one unsigned 16-bit bit count per encoded vector -> 16 / (vector_len * avg_bits) of the payload
+    # (the paper's vector is head_dim symbols; here a K vector is half a token row, 64 symbols)
     Kx, Vx = W.make_kv(1, 2, 512, 5)
     oc = oracle.OracleCache(1, 2, 2, 512, 1e-2, 1e-2)
     oc.build_codebook(Kx, Vx)
@@ -129,12 +136,12 @@ def test_metadata_overhead_closed_form(oracle):
     st = oc.stats()
     nblk = 2 * 8
     avg_bits_k = st["payload_bits_k"] / (nblk * 8192)
-    slice_meta_k = nblk * 64 * 2
-    assert abs(slice_meta_k / (st["payload_bits_k"] / 8) - 16 / (128 * avg_bits_k)) < 1e-12
-    assert st["header_bytes"] == nblk * (640 + 512)
+    slice_meta_k = nblk * 128 * 2
+    assert abs(slice_meta_k / (st["payload_bits_k"] / 8) - 16 / (64 * avg_bits_k)) < 1e-12
+    assert st["header_bytes"] == nblk * (768 + 512)
     assert st["raw_bytes"] == 2 * 2 * 512 * 128 * 2
     # record bytes = header + payload words (+ < 16 B pad) for every block
-    assert 0 <= st["record_bytes_k"] - nblk * 640 - st["payload_bits_k"] / 8 < nblk * 20
+    assert 0 <= st["record_bytes_k"] - nblk * 768 - st["payload_bits_k"] / 8 < nblk * 20
 
 
 def test_cache_layout_and_determinism(oracle):
