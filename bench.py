@@ -21,6 +21,11 @@ import time
 import numpy as np
 
 HBM_PEAK_GBPS = 8000.0  # MI355X HBM3E, published
+VALU_ISSUE_PER_S = 256 * 4 * 2.4e9 / 4  # wave64 VALU instructions per second: 256 CUs x 4 SIMDs, 4 cycles each
+VALU_INSTR_PER_SYMBOL = 9.1  # rocprofv3 SQ_INSTS_VALU / decoded wave-symbols (profiles/fused_attn_kernel_c1.md)
+# HBM bytes per fused-kernel launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by a copy of known size
+# (profiles/); keyed by (workload, rel_eb, max code word); None where not measured.
+MEASURED_TRAFFIC = {("c1", 1e-2, 12): 26.82e6}  # bytes per launch, profiles/fused_attn_kernel_c1.md
 
 
 def parse_args():
@@ -35,6 +40,8 @@ def parse_args():
     ap.add_argument("--n-splits", type=int, default=0)
     ap.add_argument("--stage-bytes", type=int, default=0)
     ap.add_argument("--max-code-len", type=int, default=0, help="longest Huffman code word (0 = library default 12)")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also launch a 256 MiB device-to-device copy (reference for rocprofv3 FETCH_SIZE/WRITE_SIZE)")
     return ap.parse_args()
 
 
@@ -162,6 +169,15 @@ def main():
     fused_bytes = [b - B * Hq * 128 * 4 - n_splits_est * B * Hq * 130 * 4 for b in step_bytes]  # no out, partials once
     kern_bytes = float(np.mean(fused_bytes))
     achieved = kern_bytes / (kern_ms * 1e-3) / 1e9
+    symbols_per_launch = 2.0 * B * H * float(np.mean([(S + i + 1) // 64 for i in range(T)])) * 8192
+
+    if args.calibrate_copy:  # a plain copy of known size, so that the HBM byte counters of a --pmc run can be scaled
+        src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     # ---- same-GPU uncompressed fp16 decode attention on the prompt ----
     base = binding.BaselineFp16Attention(B, H, Hq)
@@ -202,14 +218,19 @@ def main():
                                 max_code_len=args.max_code_len or 12)
         oc.build_codebook(Kx[:ob, :, :oh], Vx[:ob, :, :oh])
         oc.compress_blocks(np.ascontiguousarray(Kx[:ob, :, :oh]), np.ascontiguousarray(Vx[:ob, :, :oh]))
-        osteps = min(T, 16)
-        obytes = 0.0
+        # about 10 s of CPU work: repeat decode steps (fresh query each) until the clock says so, at most 30 s
+        obytes, osteps = 0.0, 0
         tc0 = time.perf_counter()
-        for i in range(osteps):
-            oc.append_token(np.ascontiguousarray(kn[i][:ob, :oh]), np.ascontiguousarray(vn[i][:ob, :oh]))
+        while True:
+            i = osteps % T
+            if osteps < T:
+                oc.append_token(np.ascontiguousarray(kn[i][:ob, :oh]), np.ascontiguousarray(vn[i][:ob, :oh]))
             oc.attn_decode(np.ascontiguousarray(qs[i][:ob, : oh * (Hq // H)]), scale)
-            st = oc.stats()
-            obytes += st["stored_bytes"] + ob * oh * (Hq // H) * 128 * 6
+            obytes += oc.stats()["stored_bytes"] + ob * oh * (Hq // H) * 128 * 6
+            osteps += 1
+            elapsed = time.perf_counter() - tc0
+            if elapsed >= 10.0 or (osteps >= 2 and elapsed * (osteps + 1) / osteps > 30.0):
+                break
         tc1 = time.perf_counter()
         cpu = {"value": obytes / (tc1 - tc0) / 1e9, "unit": "GB/s", "cores": oracle.num_threads(), "kind": "oracle",
                "sample": f"{osteps} decode steps (append + attention over the compressed cache) of {args.workload} "
@@ -246,8 +267,17 @@ def main():
                           "pct_hbm_peak": 100.0 * base_bytes / (base_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,
                           "fused_speedup": base_ms / (dec_ms / T)},
         "roofline": {"bound": "hbm", "kernel": "fused_attn_kernel", "achieved": achieved, "peak": HBM_PEAK_GBPS,
-                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS, "traffic": None,
-                     "bytes_per_launch": kern_bytes, "avg_launch_ms": kern_ms, "launches_timed": launches},
+                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
+                     "traffic": MEASURED_TRAFFIC.get((args.workload, rel_eb, args.max_code_len or 12)),
+                     "bytes_per_launch": kern_bytes, "avg_launch_ms": kern_ms, "launches_timed": launches,
+                     "timing": "HIP events around every fused-kernel launch on the launch stream, one eager pass of "
+                               "the step right after the timed region (the timed region replays a HIP graph)"},
+        # The kernel is bound by VALU issue, not by HBM: symbols decoded per second against
+        # what the chip can issue at the measured instruction count per symbol.
+        "roofline_alu": {"bound": "alu", "achieved": symbols_per_launch / (kern_ms * 1e-3) / 1e12,
+                         "peak": VALU_ISSUE_PER_S * 64 / VALU_INSTR_PER_SYMBOL / 1e12, "unit": "Tsymbol/s",
+                         "frac": symbols_per_launch / (kern_ms * 1e-3) / (VALU_ISSUE_PER_S * 64 / VALU_INSTR_PER_SYMBOL),
+                         "valu_instr_per_symbol": VALU_INSTR_PER_SYMBOL},
         "cpu_baseline": cpu,
     }
     print(json.dumps(result))

@@ -6,6 +6,7 @@ __graft_entry__.build()); importing this module without it raises.
 from __future__ import annotations
 
 import ctypes as C
+import os
 import pathlib
 
 import numpy as np
@@ -70,10 +71,11 @@ def load():
     """Load libkvcomp.so; fails loudly when the HIP extension has not been built."""
     global _lib
     if _lib is None:
-        if not LIB_PATH.exists():
-            raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2509_00579_amd.build` "
+        path = pathlib.Path(os.environ.get("KVCOMP_LIB", LIB_PATH))  # KVCOMP_LIB: try another build of the library
+        if not path.exists():
+            raise RuntimeError(f"{path} is missing: build it with `python -m paper_2509_00579_amd.build` "
                                "(there is no CPU fallback)")
-        lib = C.CDLL(str(LIB_PATH))
+        lib = C.CDLL(str(path))
         for name, (res, args) in SIGNATURES.items():
             fn = getattr(lib, name)
             fn.restype = res

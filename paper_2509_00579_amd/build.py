@@ -29,19 +29,36 @@ def _hipcc() -> str:
 def _compile(src: str) -> pathlib.Path:
     obj = OBJ / (src + ".o")
     cmd = [_hipcc(), *FLAGS, "-c", str(CSRC / src), "-o", str(obj)]
-    subprocess.run(cmd, check=True)
+    r = subprocess.run(cmd, stderr=subprocess.PIPE, text=True)
+    # the host pass does not know the gfx-only -packed-fp32-ops feature and says so once per function: harmless
+    noise = "'-packed-fp32-ops' is not a recognized feature"
+    err = "\n".join(line for line in r.stderr.splitlines() if noise not in line)
+    if err.strip():
+        print(err, flush=True)
+    if r.returncode:
+        raise subprocess.CalledProcessError(r.returncode, cmd)
     return obj
 
 
-def build(verbose: bool = False) -> pathlib.Path:
-    OBJ.mkdir(exist_ok=True)
-    with ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as ex:
-        objs = list(ex.map(_compile, SOURCES))
-    cmd = [_hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", str(LIB), *map(str, objs)]
+def build(verbose: bool = False, extra_flags=(), out: pathlib.Path | None = None) -> pathlib.Path:
+    """Compile all sources and link the shared library (extra_flags / out: experimental variants)."""
+    global FLAGS, OBJ
+    lib = pathlib.Path(out) if out else LIB
+    saved = (FLAGS, OBJ)
+    if extra_flags:
+        FLAGS = FLAGS + list(extra_flags)
+        OBJ = HERE / "_build" / ("var_" + lib.stem)
+    OBJ.mkdir(parents=True, exist_ok=True)
+    try:
+        with ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as ex:
+            objs = list(ex.map(_compile, SOURCES))
+    finally:
+        FLAGS, OBJ = saved
+    cmd = [_hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", str(lib), *map(str, objs)]
     subprocess.run(cmd, check=True)
     if verbose:
-        print(LIB)
-    return LIB
+        print(lib)
+    return lib
 
 
 if __name__ == "__main__":

@@ -61,12 +61,16 @@ __device__ __forceinline__ uint32_t wave_excl_scan(uint32_t v, int lane) {
 }
 
 // A slice holds two decode chains (see the record layout): symbols 0..31 are read upwards from the slice start,
-// symbols 63..32 downwards from the slice end.  Both readers keep a 64-bit piece {hi,lo} of the stream in registers
-// plus the next word in reading direction, fetched one window ahead so that the LDS read of the stream is off the
-// critical path (only the table lookups depend on each other).
+// symbols 63..32 downwards from the slice end.
 //   wm1   payload words, pointer moved back by one word: payload bit x is bit x + 32 of wm1
 // A window is 32 stream bits whose bit 0 is a don't-care and whose bits 1.. are the next unread bits in reading
 // order, i.e. the stream already scaled to the byte offset of a 16-bit table entry.
+#ifndef KVC_LOOKAHEAD
+#define KVC_LOOKAHEAD 1
+#endif
+#if KVC_LOOKAHEAD
+// Readers keep a 64-bit piece {hi,lo} of the stream in registers plus the next word in reading direction, fetched
+// one window ahead: one 4-byte LDS read per window, off the critical path (only table lookups depend on each other).
 struct UpReader {
     uint32_t P, idx, lo, hi, nx;  // P = (next unread payload bit) + 31 = window start in wm1 bit coordinates
     __device__ __forceinline__ void open(const uint32_t *wm1, uint32_t first_bit) {
@@ -76,7 +80,7 @@ struct UpReader {
         hi = wm1[idx + 1];
         nx = wm1[idx + 2];
     }
-    __device__ __forceinline__ uint32_t window() const { return __builtin_amdgcn_alignbit(hi, lo, P); }
+    __device__ __forceinline__ uint32_t window(const uint32_t *) const { return __builtin_amdgcn_alignbit(hi, lo, P); }
     __device__ __forceinline__ void advance(const uint32_t *wm1, uint32_t used) {  // used <= 31
         P += used;
         const uint32_t nidx = P >> 5;
@@ -97,7 +101,7 @@ struct DownReader {
         hi = wm1[idx + 1];
         pv = wm1[(int)idx - 1];
     }
-    __device__ __forceinline__ uint32_t window() const {
+    __device__ __forceinline__ uint32_t window(const uint32_t *) const {
         return __builtin_bitreverse32(__builtin_amdgcn_alignbit(hi, lo, P));
     }
     __device__ __forceinline__ void advance(const uint32_t *wm1, uint32_t used) {  // used <= 31
@@ -110,6 +114,27 @@ struct DownReader {
         pv = wm1[(int)nidx - 1];
     }
 };
+#else
+// Every window re-reads its two words from LDS (one ds_read2_b32): least bookkeeping, more LDS traffic.
+struct UpReader {
+    uint32_t P;  // (next unread payload bit) + 31 = window start in wm1 bit coordinates
+    __device__ __forceinline__ void open(const uint32_t *, uint32_t first_bit) { P = first_bit + 31u; }
+    __device__ __forceinline__ uint32_t window(const uint32_t *wm1) const {
+        const uint32_t idx = P >> 5;
+        return __builtin_amdgcn_alignbit(wm1[idx + 1], wm1[idx], P);
+    }
+    __device__ __forceinline__ void advance(const uint32_t *, uint32_t used) { P += used; }
+};
+struct DownReader {
+    uint32_t P;  // (one past the next unread payload bit) + 1
+    __device__ __forceinline__ void open(const uint32_t *, uint32_t end_bit) { P = end_bit + 1u; }
+    __device__ __forceinline__ uint32_t window(const uint32_t *wm1) const {
+        const uint32_t idx = P >> 5;
+        return __builtin_bitreverse32(__builtin_amdgcn_alignbit(wm1[idx + 1], wm1[idx], P));
+    }
+    __device__ __forceinline__ void advance(const uint32_t *, uint32_t used) { P -= used; }
+};
+#endif
 
 // Decode CNT symbols from a window.  lut: entry = (symbol << 8) | code length, indexed by the next `bits` stream
 // bits; mask2 = ((1 << bits) - 1) << 1.  CNT * (longest code word) <= 31 is the caller's promise.  Returns the
@@ -141,10 +166,10 @@ struct Quad {
     template <int CNT>
     __device__ __forceinline__ void step(const uint32_t *wm1, const char *lut, uint32_t mask2, float (&fau)[CNT],
                                          float (&fad)[CNT], float (&fbu)[CNT], float (&fbd)[CNT]) {
-        const uint32_t u0 = lookup<CNT>(au.window(), lut, mask2, fau);
-        const uint32_t u1 = lookup<CNT>(ad.window(), lut, mask2, fad);
-        const uint32_t u2 = lookup<CNT>(bu.window(), lut, mask2, fbu);
-        const uint32_t u3 = lookup<CNT>(bd.window(), lut, mask2, fbd);
+        const uint32_t u0 = lookup<CNT>(au.window(wm1), lut, mask2, fau);
+        const uint32_t u1 = lookup<CNT>(ad.window(wm1), lut, mask2, fad);
+        const uint32_t u2 = lookup<CNT>(bu.window(wm1), lut, mask2, fbu);
+        const uint32_t u3 = lookup<CNT>(bd.window(wm1), lut, mask2, fbd);
         au.advance(wm1, u0);
         ad.advance(wm1, u1);
         bu.advance(wm1, u2);
@@ -317,7 +342,10 @@ __device__ __noinline__ void v_block_global(const uint32_t *rec, const char *lut
 
 // A record on its way from global memory to the wave's LDS staging area: the first 8 KiB travel through
 // registers (loads issued early, stored to LDS later), the rest is copied at commit time.
-constexpr int kPrefetchRegs = 8;
+#ifndef KVC_PREFETCH_REGS
+#define KVC_PREFETCH_REGS 8
+#endif
+constexpr int kPrefetchRegs = KVC_PREFETCH_REGS;
 struct Prefetch {
     uint4 r[kPrefetchRegs];
     const uint4 *src;
@@ -342,12 +370,16 @@ struct Prefetch {
 constexpr int kWaves = 4;
 constexpr int kThreads = 64 * kWaves;
 
-// NS = symbols per 32-bit window = floor(31 / longest code word), clipped to 2..5.
-template <int NS> struct LutCap { static constexpr int entries = NS >= 5 ? 64 : NS == 4 ? 128 : NS == 3 ? 1024 : kLutSize; };
+#ifndef KVC_WAVES_PER_SIMD
+#define KVC_WAVES_PER_SIMD 4
+#endif
 
-template <int G, int NS>
-__global__ __launch_bounds__(kThreads, 4) void fused_attn_kernel(FusedArgs a) {
-    __shared__ __attribute__((aligned(16))) uint16_t lut_s[2][LutCap<NS>::entries];
+// LB = index width the decode tables are sized for (>= longest code word of both codebooks); a 32-bit window then
+// serves NS = floor(31 / LB) symbols.
+template <int G, int LB>
+__global__ __launch_bounds__(kThreads, KVC_WAVES_PER_SIMD) void fused_attn_kernel(FusedArgs a) {
+    constexpr int NS = 31 / LB;
+    __shared__ __attribute__((aligned(16))) uint16_t lut_s[2][1 << LB];
     __shared__ __attribute__((aligned(16))) float qf[G * kD];
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];  // one staging area per wave
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -359,22 +391,6 @@ __global__ __launch_bounds__(kThreads, 4) void fused_attn_kernel(FusedArgs a) {
     const int split = blockIdx.x, bh = blockIdx.y;
     const int b = bh / g.H, h = bh - b * g.H;
 
-    // workgroup prologue: decode tables and the G query vectors of this KV head
-    for (int t = 0; t < 2; t++) {
-        const uint4 *src = reinterpret_cast<const uint4 *>(g.lut + t * kLutSize);
-        uint4 *dst = reinterpret_cast<uint4 *>(&lut_s[t][0]);
-        const int n16 = max(1, (2 << g.lut_bits[t]) / 16);
-        for (int i = tid; i < n16; i += kThreads) dst[i] = src[i];
-    }
-    for (int i = tid; i < G * kD; i += kThreads) qf[i] = h2f(a.q[((size_t)b * g.Hq + (size_t)h * G) * kD + i]);
-    __syncthreads();
-    float qreg[G][2];
-#pragma unroll
-    for (int gg = 0; gg < G; gg++) { qreg[gg][0] = qf[gg * kD + lane]; qreg[gg][1] = qf[gg * kD + lane + 64]; }
-
-    Soft<G> st;
-    st.init();
-
     const int j0 = split * a.blocks_per_split;
     const int j1 = min(j0 + a.blocks_per_split, a.n_blocks);
     const BlockEntry *tabK = g.table + ((size_t)0 * g.B * g.H + bh) * g.max_blocks;
@@ -383,20 +399,37 @@ __global__ __launch_bounds__(kThreads, 4) void fused_attn_kernel(FusedArgs a) {
     uint4 *stage4 = reinterpret_cast<uint4 *>(stage);
     const uint32_t *stage32 = reinterpret_cast<const uint32_t *>(stage);
 
+    // Prologue.  The first Block Offsets Array entries are requested before the decode tables and the query so that
+    // their round trip overlaps; the first K record is requested before the workgroup barrier.
     int j = j0 + wave;
+    BlockEntry eK = {0, 0}, eV = {0, 0};
+    if (j < j1) {
+        eK = tabK[j];
+        eV = tabV[j];
+    }
+    for (int t = 0; t < 2; t++) {
+        const uint4 *src = reinterpret_cast<const uint4 *>(g.lut + t * kLutSize);
+        uint4 *dst = reinterpret_cast<uint4 *>(&lut_s[t][0]);
+        const int n16 = max(1, (2 << g.lut_bits[t]) / 16);
+        for (int i = tid; i < n16; i += kThreads) dst[i] = src[i];
+    }
+    for (int i = tid; i < G * kD; i += kThreads) qf[i] = h2f(a.q[((size_t)b * g.Hq + (size_t)h * G) * kD + i]);
     Prefetch pf;
 #pragma unroll
     for (int i = 0; i < kPrefetchRegs; i++) pf.r[i] = make_uint4(0, 0, 0, 0);
     pf.src = nullptr;
     pf.n16 = 0;
-    BlockEntry eK = {0, 0}, eV = {0, 0};
+    if (j < j1 && eK.size16 <= stage16) pf.issue(g.payload + (size_t)eK.off16 * 16, eK.size16, lane);
+    __syncthreads();
+    float qreg[G][2];
+#pragma unroll
+    for (int gg = 0; gg < G; gg++) { qreg[gg][0] = qf[gg * kD + lane]; qreg[gg][1] = qf[gg * kD + lane + 64]; }
+
+    Soft<G> st;
+    st.init();
+
     if (j < j1) {
-        eK = tabK[j];
-        eV = tabV[j];
-        if (eK.size16 <= stage16) {
-            pf.issue(g.payload + (size_t)eK.off16 * 16, eK.size16, lane);
-            pf.commit(stage4, lane);
-        }
+        if (eK.size16 <= stage16) pf.commit(stage4, lane);
         wave_sync();
     }
     while (j < j1) {
@@ -525,29 +558,29 @@ __global__ __launch_bounds__(kThreads, 4) void fused_attn_kernel(FusedArgs a) {
     if (a.n_splits > 1) finish_splits<G, kThreads>(g.partials, g.counters + bh, row0, a.n_splits, a.out, tid);
 }
 
-template <int G, int NS>
+template <int G, int LB>
 static hipError_t launch_fused_gn(const FusedArgs &a, size_t lds, hipEvent_t ev0, hipEvent_t ev1, hipStream_t s) {
     static size_t attr_set = 0;
     if (lds > attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&fused_attn_kernel<G, NS>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&fused_attn_kernel<G, LB>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
         attr_set = lds;
     }
     if (ev0) (void)hipEventRecord(ev0, s);
-    hipLaunchKernelGGL((fused_attn_kernel<G, NS>), dim3(a.n_splits, a.g.B * a.g.H), dim3(kThreads), lds, s, a);
+    hipLaunchKernelGGL((fused_attn_kernel<G, LB>), dim3(a.n_splits, a.g.B * a.g.H), dim3(kThreads), lds, s, a);
     if (ev1) (void)hipEventRecord(ev1, s);
     return hipGetLastError();
 }
 
 template <int G>
-static hipError_t launch_fused_g(const FusedArgs &a, int ns, size_t lds, hipEvent_t ev0, hipEvent_t ev1, hipStream_t s) {
-    switch (ns) {
-        case 5: return launch_fused_gn<G, 5>(a, lds, ev0, ev1, s);
-        case 4: return launch_fused_gn<G, 4>(a, lds, ev0, ev1, s);
-        case 3: return launch_fused_gn<G, 3>(a, lds, ev0, ev1, s);
-        default: return launch_fused_gn<G, 2>(a, lds, ev0, ev1, s);
-    }
+static hipError_t launch_fused_g(const FusedArgs &a, int longest, size_t lds, hipEvent_t ev0, hipEvent_t ev1,
+                                 hipStream_t s) {
+    if (longest <= 6) return launch_fused_gn<G, 6>(a, lds, ev0, ev1, s);
+    if (longest <= 7) return launch_fused_gn<G, 7>(a, lds, ev0, ev1, s);
+    if (longest <= 8) return launch_fused_gn<G, 8>(a, lds, ev0, ev1, s);
+    if (longest <= 10) return launch_fused_gn<G, 10>(a, lds, ev0, ev1, s);
+    return launch_fused_gn<G, 12>(a, lds, ev0, ev1, s);
 }
 
 hipError_t launch_fused_attn(const Geo &g, const uint16_t *q, float scale, float *out, int n_blocks, int n_res,
@@ -567,13 +600,12 @@ hipError_t launch_fused_attn(const Geo &g, const uint16_t *q, float scale, float
     if (longest < 1 || longest > kLutBits) return hipErrorInvalidValue;
     a.mask2[0] = ((1u << bits_k) - 1u) << 1;
     a.mask2[1] = ((1u << bits_v) - 1u) << 1;
-    const int ns = longest <= 6 ? 5 : longest <= 7 ? 4 : longest <= 10 ? 3 : 2;
     const size_t lds = (size_t)kWaves * stage_bytes;
     switch (g.G) {
-        case 1: return launch_fused_g<1>(a, ns, lds, ev0, ev1, s);
-        case 2: return launch_fused_g<2>(a, ns, lds, ev0, ev1, s);
-        case 4: return launch_fused_g<4>(a, ns, lds, ev0, ev1, s);
-        case 8: return launch_fused_g<8>(a, ns, lds, ev0, ev1, s);
+        case 1: return launch_fused_g<1>(a, longest, lds, ev0, ev1, s);
+        case 2: return launch_fused_g<2>(a, longest, lds, ev0, ev1, s);
+        case 4: return launch_fused_g<4>(a, longest, lds, ev0, ev1, s);
+        case 8: return launch_fused_g<8>(a, longest, lds, ev0, ev1, s);
         default: return hipErrorInvalidValue;
     }
 }

@@ -37,20 +37,32 @@ __device__ __forceinline__ void finish_splits(float *partials, uint32_t *counter
     }
     __syncthreads();
     if (!s_last) return;
+    // One pass over the splits with a running maximum; the loads of a batch of splits are issued together so that
+    // the merge costs a few memory round trips, not one per split.
+    constexpr int kBatch = 16;
     for (int i = tid; i < G * kD; i += NT) {
         const int g = i / kD, c = i - g * kD;
         const float *p = partials + (size_t)(row0 + g) * kMaxSplits * kPartialStride;
-        float M = -INFINITY;
-        for (int s = 0; s < n_splits; s++) M = fmaxf(M, load_agent(p + s * kPartialStride + kD));
-        float L = 0.f, O = 0.f;
-#pragma unroll 4
-        for (int s = 0; s < n_splits; s++) {
-            const float ms = load_agent(p + s * kPartialStride + kD);
-            const float l = load_agent(p + s * kPartialStride + kD + 1);
-            const float o = load_agent(p + s * kPartialStride + c);
-            const float f = ms == -INFINITY ? 0.f : __expf(ms - M);
-            L = fmaf(l, f, L);
-            O = fmaf(o, f, O);
+        float M = -INFINITY, L = 0.f, O = 0.f;
+        for (int s0 = 0; s0 < n_splits; s0 += kBatch) {
+            float ms[kBatch], ls[kBatch], os[kBatch];
+#pragma unroll
+            for (int k = 0; k < kBatch; k++) {
+                const int s = min(s0 + k, n_splits - 1);  // clamped: every load is in bounds
+                ms[k] = load_agent(p + s * kPartialStride + kD);
+                ls[k] = load_agent(p + s * kPartialStride + kD + 1);
+                os[k] = load_agent(p + s * kPartialStride + c);
+            }
+#pragma unroll
+            for (int k = 0; k < kBatch; k++) {
+                if (s0 + k < n_splits && ms[k] != -INFINITY) {
+                    const float Mn = fmaxf(M, ms[k]);
+                    const float fa = __expf(M - Mn), fb = __expf(ms[k] - Mn);
+                    L = L * fa + ls[k] * fb;
+                    O = O * fa + os[k] * fb;
+                    M = Mn;
+                }
+            }
         }
         out[(size_t)(row0 + g) * kD + c] = O / L;
     }

@@ -262,3 +262,57 @@ def test_config1_full_size_sampled(gpu, oracle):
         _say(f"  step {i}: max abs err {err:.3e}")
     _say(f"  stats {gc.stats()}")
     gc.close()
+
+
+@pytest.mark.parametrize("max_len,rel", [(6, 1e-2), (7, 1e-2), (7, 5e-3), (8, 5e-3), (10, 1e-2), (12, 1e-2)])
+def test_code_length_limits_select_every_decoder_variant(gpu, oracle, max_len, rel):
+    """Shorter maximum code words: more symbols per decode window (5, 4, 3, 3, 2 for limits 6, 7, 8, 10, 12)."""
+    _say(f"max_code_len={max_len} rel={rel}")
+    B, H, Hq, S = 1, 2, 4, 330
+    Kx, Vx = W.make_kv(B, H, S, 31)
+    oc = oracle.OracleCache(B, H, Hq, S + 64, rel, rel, max_code_len=max_len)
+    oc.build_codebook(Kx, Vx)
+    oc.compress_blocks(Kx, Vx)
+    gc = gpu.KVCompCache(B, H, Hq, S + 64, rel, rel, max_code_len=max_len)
+    gc.build_codebook(_dev(Kx), _dev(Vx))
+    gc.compress_blocks(_dev(Kx), _dev(Vx))
+    for which in (K, V):
+        ln_g, cd_g = gc.codebook(which)
+        np.testing.assert_array_equal(ln_g, oc.len[which])
+        np.testing.assert_array_equal(cd_g, oc.code[which])
+        assert int(ln_g.max()) <= max_len
+    _assert_same_cache(oc, gc)
+    q = W.make_queries(B, Hq, 1, 31)[0]
+    _attn_close(gc.attn_decode(_dev(q), SCALE).cpu().numpy(), oc.attn_decode(q, SCALE))
+    gc.close()
+
+
+def test_long_code_words_and_length_limit(gpu, oracle):
+    """A geometric code histogram at prefill drives the code words to the 12-bit limit (count halving on both sides);
+    the later blocks then use every level, so records are large and the two-symbols-per-window decoder runs."""
+    _say("geometric prefill histogram -> 12-bit code words")
+    B, H, S = 1, 2, 256
+    rng = np.random.default_rng(32)
+    Kx, Vx = W.make_kv(B, H, S, 32)
+    geo = np.minimum(rng.geometric(0.5, size=(B, 64, H, 128)) - 1, 50)   # code k with probability 2^-(k+1)
+    kp = geo.astype(np.float16)
+    kp[:, 0], kp[:, 1] = 0, 50          # every K unit (channel over the block's tokens) spans [0, 50] -> code == value
+    vp = geo.astype(np.float16)
+    vp[..., 0], vp[..., 1] = 0, 50      # every V unit (token over the channels) spans [0, 50]
+    Kx[:, :64], Vx[:, :64] = kp, vp
+    oc = oracle.OracleCache(B, H, H, S, 1e-2, 1e-2)
+    oc.build_codebook(Kx[:, :64], Vx[:, :64])
+    assert oc.halvings[K] > 0 and int(oc.len[K].max()) == 12 and int(oc.len[V].max()) == 12
+    oc.compress_blocks(Kx, Vx)
+    gc = gpu.KVCompCache(B, H, H, S, 1e-2, 1e-2)
+    gc.build_codebook(_dev(Kx[:, :64]), _dev(Vx[:, :64]))
+    gc.compress_blocks(_dev(Kx), _dev(Vx))
+    for which in (K, V):
+        ln_g, cd_g = gc.codebook(which)
+        np.testing.assert_array_equal(ln_g, oc.len[which])
+        np.testing.assert_array_equal(cd_g, oc.code[which])
+    _assert_same_cache(oc, gc)
+    q = W.make_queries(B, H, 1, 32)[0]
+    _attn_close(gc.attn_decode(_dev(q), SCALE).cpu().numpy(), oc.attn_decode(q, SCALE))
+    _say(f"  largest record {gc.stats()['max_record_bytes']} B, CR {gc.stats()['compression_ratio']:.3f}")
+    gc.close()

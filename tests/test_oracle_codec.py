@@ -203,3 +203,35 @@ def test_append_equals_prefill_of_the_longer_sequence(oracle):
     with pytest.raises(RuntimeError):
         for _ in range(64):
             inc.append_token(Kx[:, 0], Vx[:, 0])
+
+
+def test_a_slice_decodes_from_both_ends_by_hand(oracle):
+    # An independent, bit-by-bit prefix decoder written here (dictionary of code words) reads slice 0 of a K record
+    # upwards from its start for symbols 0..31 and downwards from its end for symbols 63..32.
+    rng = np.random.default_rng(23)
+    counts = rng.integers(1, 40, 26) ** 2
+    ln, cd, _ = oracle.build_codebook(_hist(counts), 26, 12)
+    book = {format(int(cd[s]), "b").zfill(int(ln[s])): s for s in range(26)}
+    codes = rng.choice(26, size=(64, 128), p=counts / counts.sum()).astype(np.uint8)
+    rec = oracle.encode_block(K, codes, np.zeros((128, 2), np.uint16), ln, cd)
+    hdr = oracle.header_bytes(K)
+    bits = np.unpackbits(rec[hdr:], bitorder="little")
+    sb = rec[512:hdr].view("<u2").astype(np.int64)
+    for s in (0, 1, 77, 127):
+        start, end = int(sb[:s].sum()), int(sb[: s + 1].sum())
+        want = _slice_order(K, codes)[s]
+        pos, got_up = start, []
+        while len(got_up) < 32:
+            w = ""
+            while w not in book:
+                w += str(bits[pos]); pos += 1
+            got_up.append(book[w])
+        pos_dn, got_dn = end, []
+        while len(got_dn) < 32:
+            w = ""
+            while w not in book:
+                pos_dn -= 1; w += str(bits[pos_dn])
+            got_dn.append(book[w])
+        assert got_up == list(want[:32])
+        assert got_dn == list(want[:31:-1])
+        assert pos == pos_dn  # the two chains meet: no gap, no overlap
