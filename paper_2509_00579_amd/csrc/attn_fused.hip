@@ -65,10 +65,15 @@ __device__ __forceinline__ uint32_t wave_excl_scan(uint32_t v, int lane) {
 //   wm1   payload words, pointer moved back by one word: payload bit x is bit x + 32 of wm1
 // A window is 32 stream bits whose bit 0 is a don't-care and whose bits 1.. are the next unread bits in reading
 // order, i.e. the stream already scaled to the byte offset of a 16-bit table entry.
-#ifndef KVC_LOOKAHEAD
-#define KVC_LOOKAHEAD 1
+// KVC_READER selects how a chain fetches its stream bits (build-time, for measurements):
+//   1  look-ahead: {hi,lo} words in registers, next word fetched one window ahead (4-byte aligned LDS reads)
+//   0  every window re-reads its two words (one 8-byte LDS read): less bookkeeping, measured ~10 % slower
+// (Unaligned 4-byte LDS reads at byte granularity were also tried: correct on gfx950 but 2.4x slower.)
+#ifndef KVC_READER
+#define KVC_READER 1
 #endif
-#if KVC_LOOKAHEAD
+constexpr int kWindowBits = 31;
+#if KVC_READER == 1
 // Readers keep a 64-bit piece {hi,lo} of the stream in registers plus the next word in reading direction, fetched
 // one window ahead: one 4-byte LDS read per window, off the critical path (only table lookups depend on each other).
 struct UpReader {
@@ -211,36 +216,34 @@ struct Soft {
     }
 };
 
-// ---- K block: lane = token; its two slices are channels 0..63 and 64..127 ------------------------------------------
-// hdr32: the record (LDS or global).  Leaves scale * q.k' of this lane's token in score[].
-template <int G, int NS>
-__device__ __forceinline__ void k_block(const uint32_t *hdr32, const char *lut, uint32_t mask2,
-                                        const float (&qreg)[G][2], float two_eb, float scale, int lane,
-                                        float (&score)[G]) {
-    // lane c holds the folded weights q_c * step_c of channels c and c + 64
-    const uint32_t mm0 = hdr32[lane], mm1 = hdr32[lane + 64];
-    const float mn0 = h2f(mm0 & 0xffffu), mn1 = h2f(mm1 & 0xffffu);
-    const float st0 = two_eb * (h2f(mm0 >> 16) - mn0), st1 = two_eb * (h2f(mm1 >> 16) - mn1);
-    float w0[G], w1[G], acc[G];
+// ---- accumulation of one round of decoded symbols -----------------------------------------------------------------
+// Query-head groups of 1 and 2: the folded weight of the current symbol is wave-uniform, lives in one lane's register
+// and is broadcast with v_readlane; one FMA per symbol and head.
+// Groups of 4 and 8 (GQA): a decode step is a small matrix product -- (heads x 1) weights times (1 x lanes) decoded
+// symbols -- which is what v_mfma_f32_4x4x1f32 computes for each group of four lanes: lane i of a group supplies the
+// weight of head i (read from LDS, layout [symbol index][head]) and its own decoded symbol, and receives the four
+// heads' products for its own token / channel.  One MFMA replaces four broadcasts and four FMAs.
+typedef float v4f __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ v4f mfma4(float a, float b, v4f c) { return __builtin_amdgcn_mfma_f32_4x4x1f32(a, b, c, 0, 0, 0); }
+
+// K: symbol index `up` of chain au/bu is channel up / 64+up, index `dn` of chain ad/bd is channel dn / 64+dn.
+template <int G, int CNT>
+__device__ __forceinline__ void k_accum(const float (&w0)[G], const float (&w1)[G], const float *wl, int first,
+                                        const float (&fau)[CNT], const float (&fad)[CNT], const float (&fbu)[CNT],
+                                        const float (&fbd)[CNT], float (&acc)[G], v4f (&macc)[4][(G + 3) / 4]) {
 #pragma unroll
-    for (int g = 0; g < G; g++) {
-        w0[g] = qreg[g][0] * st0;
-        w1[g] = qreg[g][1] * st1;
-        acc[g] = 0.f;
-    }
-    const uint32_t sb = hdr32[kMinMaxBytesK / 4 + lane];  // bit counts of slices 2*lane and 2*lane+1
-    const uint32_t start = wave_excl_scan((sb & 0xffffu) + (sb >> 16), lane);
-    const uint32_t *wm1 = hdr32 + kHdrBytesK / 4 - 1;
-    Quad qd;
-    qd.open(wm1, start, sb & 0xffffu, sb >> 16);
-    constexpr int kRounds = kHalf / NS, kTail = kHalf - kRounds * NS;
-#pragma unroll 2
-    for (int r = 0; r < kRounds; r++) {
-        float fau[NS], fad[NS], fbu[NS], fbd[NS];
-        qd.step<NS>(wm1, lut, mask2, fau, fad, fbu, fbd);
+    for (int k = 0; k < CNT; k++) {
+        const int up = first + k, dn = kSliceLen - 1 - up;  // symbol index inside the slice
+        if constexpr (G >= 4) {
 #pragma unroll
-        for (int k = 0; k < NS; k++) {
-            const int up = r * NS + k, dn = kSliceLen - 1 - up;  // symbol index inside the slice
+            for (int q = 0; q < G / 4; q++) {
+                macc[0][q] = mfma4(wl[up * G + 4 * q], fau[k], macc[0][q]);
+                macc[1][q] = mfma4(wl[dn * G + 4 * q], fad[k], macc[1][q]);
+                macc[2][q] = mfma4(wl[(kSliceLen + up) * G + 4 * q], fbu[k], macc[2][q]);
+                macc[3][q] = mfma4(wl[(kSliceLen + dn) * G + 4 * q], fbd[k], macc[3][q]);
+            }
+        } else {
 #pragma unroll
             for (int g = 0; g < G; g++) {
                 acc[g] = fmaf(bcast(w0[g], up), fau[k], acc[g]);
@@ -250,19 +253,92 @@ __device__ __forceinline__ void k_block(const uint32_t *hdr32, const char *lut, 
             }
         }
     }
+}
+
+// V: symbol index = token; chains au/ad belong to channel 2*lane, bu/bd to channel 2*lane+1.
+template <int G, int CNT>
+__device__ __forceinline__ void v_accum(const float (&w)[G], const float *wl, int first, const float (&fau)[CNT],
+                                        const float (&fad)[CNT], const float (&fbu)[CNT], const float (&fbd)[CNT],
+                                        float (&acc)[G][2], v4f (&macc)[4][(G + 3) / 4]) {
+#pragma unroll
+    for (int k = 0; k < CNT; k++) {
+        const int up = first + k, dn = kSliceLen - 1 - up;  // token index inside the block
+        if constexpr (G >= 4) {
+#pragma unroll
+            for (int q = 0; q < G / 4; q++) {
+                const float au_w = wl[up * G + 4 * q], ad_w = wl[dn * G + 4 * q];
+                macc[0][q] = mfma4(au_w, fau[k], macc[0][q]);
+                macc[1][q] = mfma4(ad_w, fad[k], macc[1][q]);
+                macc[2][q] = mfma4(au_w, fbu[k], macc[2][q]);
+                macc[3][q] = mfma4(ad_w, fbd[k], macc[3][q]);
+            }
+        } else {
+#pragma unroll
+            for (int g = 0; g < G; g++) {
+                const float wu = bcast(w[g], up), wd = bcast(w[g], dn);
+                acc[g][0] = fmaf(wu, fau[k], acc[g][0]);
+                acc[g][0] = fmaf(wd, fad[k], acc[g][0]);
+                acc[g][1] = fmaf(wu, fbu[k], acc[g][1]);
+                acc[g][1] = fmaf(wd, fbd[k], acc[g][1]);
+            }
+        }
+    }
+}
+
+// ---- K block: lane = token; its two slices are channels 0..63 and 64..127 ------------------------------------------
+// hdr32: the record (LDS or global); wts: this wave's LDS weight area (used by groups >= 4 only).  Leaves
+// scale * q.k' of this lane's token in score[].
+template <int G, int NS>
+__device__ __forceinline__ void k_block(const uint32_t *hdr32, const char *lut, uint32_t mask2, float *wts,
+                                        const float (&qreg)[G][2], float two_eb, float scale, int lane,
+                                        float (&score)[G]) {
+    // lane c holds the folded weights q_c * step_c of channels c and c + 64
+    const uint32_t mm0 = hdr32[lane], mm1 = hdr32[lane + 64];
+    const float mn0 = h2f(mm0 & 0xffffu), mn1 = h2f(mm1 & 0xffffu);
+    const float st0 = two_eb * (h2f(mm0 >> 16) - mn0), st1 = two_eb * (h2f(mm1 >> 16) - mn1);
+    float w0[G], w1[G], acc[G];
+    v4f macc[4][(G + 3) / 4];
+#pragma unroll
+    for (int g = 0; g < G; g++) {
+        w0[g] = qreg[g][0] * st0;
+        w1[g] = qreg[g][1] * st1;
+        acc[g] = 0.f;
+    }
+    if constexpr (G >= 4) {
+#pragma unroll
+        for (int g = 0; g < G; g++) {
+            wts[lane * G + g] = w0[g];
+            wts[(kSliceLen + lane) * G + g] = w1[g];
+        }
+#pragma unroll
+        for (int c = 0; c < 4; c++)
+#pragma unroll
+            for (int q = 0; q < G / 4; q++) macc[c][q] = (v4f){0.f, 0.f, 0.f, 0.f};
+    }
+    const float *wl = wts + (lane & 3);
+    const uint32_t sb = hdr32[kMinMaxBytesK / 4 + lane];  // bit counts of slices 2*lane and 2*lane+1
+    const uint32_t start = wave_excl_scan((sb & 0xffffu) + (sb >> 16), lane);
+    const uint32_t *wm1 = hdr32 + kHdrBytesK / 4 - 1;
+    if constexpr (G >= 4) wave_sync();
+    Quad qd;
+    qd.open(wm1, start, sb & 0xffffu, sb >> 16);
+    constexpr int kRounds = kHalf / NS, kTail = kHalf - kRounds * NS;
+#pragma unroll 2
+    for (int r = 0; r < kRounds; r++) {
+        float fau[NS], fad[NS], fbu[NS], fbd[NS];
+        qd.step<NS>(wm1, lut, mask2, fau, fad, fbu, fbd);
+        k_accum<G, NS>(w0, w1, wl, r * NS, fau, fad, fbu, fbd, acc, macc);
+    }
     if constexpr (kTail > 0) {
         float fau[kTail], fad[kTail], fbu[kTail], fbd[kTail];
         qd.step<kTail>(wm1, lut, mask2, fau, fad, fbu, fbd);
+        k_accum<G, kTail>(w0, w1, wl, kRounds * NS, fau, fad, fbu, fbd, acc, macc);
+    }
+    if constexpr (G >= 4) {
 #pragma unroll
-        for (int k = 0; k < kTail; k++) {
-            const int up = kRounds * NS + k, dn = kSliceLen - 1 - up;
-#pragma unroll
-            for (int g = 0; g < G; g++) {
-                acc[g] = fmaf(bcast(w0[g], up), fau[k], acc[g]);
-                acc[g] = fmaf(bcast(w0[g], dn), fad[k], acc[g]);
-                acc[g] = fmaf(bcast(w1[g], up), fbu[k], acc[g]);
-                acc[g] = fmaf(bcast(w1[g], dn), fbd[k], acc[g]);
-            }
+        for (int q = 0; q < G / 4; q++) {
+            const v4f t = macc[0][q] + macc[1][q] + macc[2][q] + macc[3][q];
+            acc[4 * q + 0] = t.x; acc[4 * q + 1] = t.y; acc[4 * q + 2] = t.z; acc[4 * q + 3] = t.w;
         }
     }
     // the constant part of the dot product, sum_c q_c min_c, is shared by all tokens of the block
@@ -273,21 +349,32 @@ __device__ __forceinline__ void k_block(const uint32_t *hdr32, const char *lut, 
 // ---- V block: lane = channels 2*lane and 2*lane+1 (its two slices) -------------------------------------------------
 // p[g] = softmax numerator of token `lane`.
 template <int G, int NS>
-__device__ __forceinline__ void v_block(const uint32_t *hdr32, const char *lut, uint32_t mask2, const float (&p)[G],
-                                        float two_eb, int lane, Soft<G> &st) {
+__device__ __forceinline__ void v_block(const uint32_t *hdr32, const char *lut, uint32_t mask2, float *wts,
+                                        const float (&p)[G], float two_eb, int lane, Soft<G> &st) {
     // lane t holds the folded weight p_t * step_t of token t
     const uint32_t mm = hdr32[lane];
     const float mn = h2f(mm & 0xffffu);
     const float step = two_eb * (h2f(mm >> 16) - mn);
     float w[G];
+    v4f macc[4][(G + 3) / 4];
 #pragma unroll
     for (int g = 0; g < G; g++) {
         w[g] = p[g] * step;
         st.bv[g] += p[g] * mn;
     }
+    if constexpr (G >= 4) {
+#pragma unroll
+        for (int g = 0; g < G; g++) wts[lane * G + g] = w[g];
+#pragma unroll
+        for (int c = 0; c < 4; c++)
+#pragma unroll
+            for (int q = 0; q < G / 4; q++) macc[c][q] = (v4f){0.f, 0.f, 0.f, 0.f};
+    }
+    const float *wl = wts + (lane & 3);
     const uint32_t sb = hdr32[kMinMaxBytesV / 4 + lane];
     const uint32_t start = wave_excl_scan((sb & 0xffffu) + (sb >> 16), lane);
     const uint32_t *wm1 = hdr32 + kHdrBytesV / 4 - 1;
+    if constexpr (G >= 4) wave_sync();
     Quad qd;
     qd.open(wm1, start, sb & 0xffffu, sb >> 16);
     constexpr int kRounds = kHalf / NS, kTail = kHalf - kRounds * NS;
@@ -295,33 +382,19 @@ __device__ __forceinline__ void v_block(const uint32_t *hdr32, const char *lut, 
     for (int r = 0; r < kRounds; r++) {
         float fau[NS], fad[NS], fbu[NS], fbd[NS];
         qd.step<NS>(wm1, lut, mask2, fau, fad, fbu, fbd);
-#pragma unroll
-        for (int k = 0; k < NS; k++) {
-            const int up = r * NS + k, dn = kSliceLen - 1 - up;  // token index inside the block
-#pragma unroll
-            for (int g = 0; g < G; g++) {
-                const float wu = bcast(w[g], up), wd = bcast(w[g], dn);
-                st.acc[g][0] = fmaf(wu, fau[k], st.acc[g][0]);
-                st.acc[g][0] = fmaf(wd, fad[k], st.acc[g][0]);
-                st.acc[g][1] = fmaf(wu, fbu[k], st.acc[g][1]);
-                st.acc[g][1] = fmaf(wd, fbd[k], st.acc[g][1]);
-            }
-        }
+        v_accum<G, NS>(w, wl, r * NS, fau, fad, fbu, fbd, st.acc, macc);
     }
     if constexpr (kTail > 0) {
         float fau[kTail], fad[kTail], fbu[kTail], fbd[kTail];
         qd.step<kTail>(wm1, lut, mask2, fau, fad, fbu, fbd);
+        v_accum<G, kTail>(w, wl, kRounds * NS, fau, fad, fbu, fbd, st.acc, macc);
+    }
+    if constexpr (G >= 4) {
 #pragma unroll
-        for (int k = 0; k < kTail; k++) {
-            const int up = kRounds * NS + k, dn = kSliceLen - 1 - up;
-#pragma unroll
-            for (int g = 0; g < G; g++) {
-                const float wu = bcast(w[g], up), wd = bcast(w[g], dn);
-                st.acc[g][0] = fmaf(wu, fau[k], st.acc[g][0]);
-                st.acc[g][0] = fmaf(wd, fad[k], st.acc[g][0]);
-                st.acc[g][1] = fmaf(wu, fbu[k], st.acc[g][1]);
-                st.acc[g][1] = fmaf(wd, fbd[k], st.acc[g][1]);
-            }
+        for (int q = 0; q < G / 4; q++) {
+            const v4f a = macc[0][q] + macc[1][q], bsum = macc[2][q] + macc[3][q];
+            st.acc[4 * q + 0][0] += a.x; st.acc[4 * q + 1][0] += a.y; st.acc[4 * q + 2][0] += a.z; st.acc[4 * q + 3][0] += a.w;
+            st.acc[4 * q + 0][1] += bsum.x; st.acc[4 * q + 1][1] += bsum.y; st.acc[4 * q + 2][1] += bsum.z; st.acc[4 * q + 3][1] += bsum.w;
         }
     }
 }
@@ -329,15 +402,15 @@ __device__ __forceinline__ void v_block(const uint32_t *hdr32, const char *lut, 
 // Rare path: a record larger than the LDS staging area is decoded straight from global memory.  Kept out of line so
 // that it costs the common path no registers.
 template <int G, int NS>
-__device__ __noinline__ void k_block_global(const uint32_t *rec, const char *lut, uint32_t mask2,
+__device__ __noinline__ void k_block_global(const uint32_t *rec, const char *lut, uint32_t mask2, float *wts,
                                             const float (&qreg)[G][2], float two_eb, float scale, int lane,
                                             float (&score)[G]) {
-    k_block<G, NS>(rec, lut, mask2, qreg, two_eb, scale, lane, score);
+    k_block<G, NS>(rec, lut, mask2, wts, qreg, two_eb, scale, lane, score);
 }
 template <int G, int NS>
-__device__ __noinline__ void v_block_global(const uint32_t *rec, const char *lut, uint32_t mask2, const float (&p)[G],
-                                            float two_eb, int lane, Soft<G> &st) {
-    v_block<G, NS>(rec, lut, mask2, p, two_eb, lane, st);
+__device__ __noinline__ void v_block_global(const uint32_t *rec, const char *lut, uint32_t mask2, float *wts,
+                                            const float (&p)[G], float two_eb, int lane, Soft<G> &st) {
+    v_block<G, NS>(rec, lut, mask2, wts, p, two_eb, lane, st);
 }
 
 // A record on its way from global memory to the wave's LDS staging area: the first 8 KiB travel through
@@ -370,20 +443,21 @@ struct Prefetch {
 constexpr int kWaves = 4;
 constexpr int kThreads = 64 * kWaves;
 
-#ifndef KVC_WAVES_PER_SIMD
-#define KVC_WAVES_PER_SIMD 4
-#endif
+// Register budget: 4 waves per SIMD (128 VGPRs) for groups of 1 and 2 query heads; larger groups carry more
+// accumulators and weights and get 168 / 256 VGPRs instead of spilling.
+template <int G> struct WavesPerSimd { static constexpr int value = G >= 8 ? 2 : G >= 4 ? 3 : 4; };
 
-// LB = index width the decode tables are sized for (>= longest code word of both codebooks); a 32-bit window then
-// serves NS = floor(31 / LB) symbols.
+// LB = index width the decode tables are sized for (>= longest code word of both codebooks); a window then
+// serves NS = floor(kWindowBits / LB) symbols.
 template <int G, int LB>
-__global__ __launch_bounds__(kThreads, KVC_WAVES_PER_SIMD) void fused_attn_kernel(FusedArgs a) {
-    constexpr int NS = 31 / LB;
+__global__ __launch_bounds__(kThreads, WavesPerSimd<G>::value) void fused_attn_kernel(FusedArgs a) {
+    constexpr int NS = kWindowBits / LB;
     __shared__ __attribute__((aligned(16))) uint16_t lut_s[2][1 << LB];
     __shared__ __attribute__((aligned(16))) float qf[G * kD];
-    extern __shared__ __attribute__((aligned(16))) uint8_t smem[];  // one staging area per wave
+    extern __shared__ __attribute__((aligned(16))) uint8_t smem[];  // per wave: staging area; groups >= 4: + weights
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     uint8_t *stage = smem + (size_t)wave * a.stage_bytes;
+    float *wts = reinterpret_cast<float *>(smem + (size_t)kWaves * a.stage_bytes) + (G >= 4 ? wave * G * kD : 0);
     const char *lutK = reinterpret_cast<const char *>(&lut_s[0][0]);
     const char *lutV = reinterpret_cast<const char *>(&lut_s[1][0]);
 
@@ -438,12 +512,12 @@ __global__ __launch_bounds__(kThreads, KVC_WAVES_PER_SIMD) void fused_attn_kerne
         const uint8_t *recK = g.payload + (size_t)eK.off16 * 16, *recV = g.payload + (size_t)eV.off16 * 16;
         if (v_staged) pf.issue(recV, eV.size16, lane);  // V record travels while K is decoded
         if (k_staged) {
-            k_block<G, NS>(stage32, lutK, a.mask2[0], qreg, g.two_eb[0], a.scale, lane, score);
+            k_block<G, NS>(stage32, lutK, a.mask2[0], wts, qreg, g.two_eb[0], a.scale, lane, score);
         } else {  // larger than the staging area: decode from global memory (copies keep the hot state in registers)
             float q_tmp[G][2], s_tmp[G];
 #pragma unroll
             for (int gg = 0; gg < G; gg++) { q_tmp[gg][0] = qreg[gg][0]; q_tmp[gg][1] = qreg[gg][1]; }
-            k_block_global<G, NS>(reinterpret_cast<const uint32_t *>(recK), lutK, a.mask2[0], q_tmp, g.two_eb[0], a.scale,
+            k_block_global<G, NS>(reinterpret_cast<const uint32_t *>(recK), lutK, a.mask2[0], wts, q_tmp, g.two_eb[0], a.scale,
                                   lane, s_tmp);
 #pragma unroll
             for (int gg = 0; gg < G; gg++) score[gg] = s_tmp[gg];
@@ -461,13 +535,13 @@ __global__ __launch_bounds__(kThreads, KVC_WAVES_PER_SIMD) void fused_attn_kerne
             if (eKn.size16 <= stage16) pf.issue(g.payload + (size_t)eKn.off16 * 16, eKn.size16, lane);
         }
         if (v_staged) {
-            v_block<G, NS>(stage32, lutV, a.mask2[1], p, g.two_eb[1], lane, st);
+            v_block<G, NS>(stage32, lutV, a.mask2[1], wts, p, g.two_eb[1], lane, st);
         } else {
             Soft<G> st_tmp = st;
             float p_tmp[G];
 #pragma unroll
             for (int gg = 0; gg < G; gg++) p_tmp[gg] = p[gg];
-            v_block_global<G, NS>(reinterpret_cast<const uint32_t *>(recV), lutV, a.mask2[1], p_tmp, g.two_eb[1], lane,
+            v_block_global<G, NS>(reinterpret_cast<const uint32_t *>(recV), lutV, a.mask2[1], wts, p_tmp, g.two_eb[1], lane,
                                   st_tmp);
             st = st_tmp;
         }
@@ -600,7 +674,7 @@ hipError_t launch_fused_attn(const Geo &g, const uint16_t *q, float scale, float
     if (longest < 1 || longest > kLutBits) return hipErrorInvalidValue;
     a.mask2[0] = ((1u << bits_k) - 1u) << 1;
     a.mask2[1] = ((1u << bits_v) - 1u) << 1;
-    const size_t lds = (size_t)kWaves * stage_bytes;
+    const size_t lds = (size_t)kWaves * stage_bytes + (g.G >= 4 ? (size_t)kWaves * g.G * kD * 4 : 0);
     switch (g.G) {
         case 1: return launch_fused_g<1>(a, longest, lds, ev0, ev1, s);
         case 2: return launch_fused_g<2>(a, longest, lds, ev0, ev1, s);
