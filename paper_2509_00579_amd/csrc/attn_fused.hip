@@ -443,9 +443,9 @@ struct Prefetch {
 constexpr int kWaves = 4;
 constexpr int kThreads = 64 * kWaves;
 
-// Register budget: 4 waves per SIMD (128 VGPRs) for groups of 1 and 2 query heads; larger groups carry more
-// accumulators and weights and get 168 / 256 VGPRs instead of spilling.
-template <int G> struct WavesPerSimd { static constexpr int value = G >= 8 ? 2 : G >= 4 ? 3 : 4; };
+// Register budget: 4 waves per SIMD (128 VGPRs) for groups of 1 and 2 query heads, 3 (168) and 2 (256) for groups
+// of 4 and 8.
+template <int G> struct WavesPerSimd { static constexpr int value = fused_wgs_per_cu(G); };
 
 // LB = index width the decode tables are sized for (>= longest code word of both codebooks); a window then
 // serves NS = floor(kWindowBits / LB) symbols.

@@ -387,13 +387,14 @@ kvcomp_status kvcomp_attn_decode(kvcomp_ctx *ctx, const void *d_q, float scale, 
     if (ctx->n_blocks && !ctx->have_codebook) return fail(KVCOMP_ERR_STATE, "no codebook");
     hipStream_t s = static_cast<hipStream_t>(stream);
     const Geo &g = ctx->geo;
-    // Work split: the grid should fit the chip in a single round of workgroups (256 CUs x 4 resident workgroups of
-    // 4 waves), every wave owning whole block pairs; per-workgroup costs (tables, first record, split merge) are
-    // then paid once per resident slot instead of once per small workgroup.
+    // Work split: the grid should fit the chip in a single round of workgroups (256 CUs x the 2..4 workgroups of
+    // 4 waves that are resident per CU for this group size), every wave owning whole block pairs; per-workgroup
+    // costs (tables, first record, split merge) are then paid once per resident slot, and no second, partly filled
+    // round of workgroups trails the first.
     int n_splits = ctx->tune_splits;
     if (n_splits <= 0) {
         const int bh = g.B * g.H;
-        const int by_chip = std::max(1, 1024 / bh);
+        const int by_chip = std::max(1, kCUs * fused_wgs_per_cu(g.G) / bh);
         const int by_work = std::max(1, (ctx->n_blocks + 3) / 4);  // at least one block pair per wave
         n_splits = std::min(by_chip, by_work);
         int bps = (ctx->n_blocks + n_splits - 1) / std::max(n_splits, 1);

@@ -68,6 +68,10 @@ struct Geo {
 
 constexpr int kPartialStride = kD + 2;  // o[128], m, l
 constexpr int kMaxSplits = 64;
+constexpr int kCUs = 256;  // compute units of the MI355X
+// Workgroups (of 4 waves) of the fused kernel that are resident per CU = its waves per SIMD: groups of 4 and 8 query
+// heads carry more accumulators and weights and trade occupancy for registers instead of spilling.
+constexpr int fused_wgs_per_cu(int G) { return G >= 8 ? 2 : G >= 4 ? 3 : 4; }
 
 // ---- launches implemented in the .hip files ----
 hipError_t launch_histogram(const Geo &g, int which, const uint16_t *X, int seq_stride, int n_blk_per_bh,
