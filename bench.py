@@ -39,7 +39,9 @@ def parse_args():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--n-splits", type=int, default=0)
     ap.add_argument("--stage-bytes", type=int, default=0)
-    ap.add_argument("--max-code-len", type=int, default=0, help="longest Huffman code word (0 = library default 12)")
+    ap.add_argument("--max-code-len", type=int, default=0,
+                    help="longest Huffman code word; 0 = one bit more than a fixed-length code of the quantization "
+                         "levels needs (7 at rel_eb 1e-2), which keeps the decode table within two LDS rows")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch a 256 MiB device-to-device copy (reference for rocprofv3 FETCH_SIZE/WRITE_SIZE)")
     return ap.parse_args()
@@ -62,6 +64,9 @@ def main():
     rel_eb = args.rel_eb if args.rel_eb is not None else w.rel_eb
     B, H, Hq, S, T = w.batch, w.n_kv_heads, w.n_q_heads, w.seq, w.decode_steps
     scale = 1.0 / np.sqrt(128.0)
+    if args.max_code_len == 0:
+        levels = int(np.rint(1.0 / (2.0 * np.float32(rel_eb)))) + 1
+        args.max_code_len = int(np.ceil(np.log2(levels))) + 1
 
     # ---- inputs: generated on the host from the seed, resident in HBM before any timed region ----
     Kx, Vx = W.make_kv(B, H, S, w.seed)
@@ -215,7 +220,7 @@ def main():
         oh = H if B * H * S <= 32 * 4096 else max(1, (32 * 4096) // (ob * S))
         oh = min(oh, H)
         oc = oracle.OracleCache(ob, oh, oh * (Hq // H), max_seq, rel_eb, rel_eb,
-                                max_code_len=args.max_code_len or 12)
+                                max_code_len=args.max_code_len)
         oc.build_codebook(Kx[:ob, :, :oh], Vx[:ob, :, :oh])
         oc.compress_blocks(np.ascontiguousarray(Kx[:ob, :, :oh]), np.ascontiguousarray(Vx[:ob, :, :oh]))
         # about 10 s of CPU work: repeat decode steps (fresh query each) until the clock says so, at most 30 s
@@ -252,7 +257,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": f"{args.workload}: batch {B}, {H} kv heads / {Hq} q heads x 128, prompt {S} tokens, "
                                f"{T} decode steps (append one token, then fused decode attention), block 64, "
-                               f"rel_eb {rel_eb}, max code word {args.max_code_len or 12} bits",
+                               f"rel_eb {rel_eb}, max code word {args.max_code_len} bits",
                    "decode_loop": "hip graph replay" if graph is not None else "eager launches"},
         "pct_hbm_peak": 100.0 * value / HBM_PEAK_GBPS,
         "compression_ratio": stats0["compression_ratio"],
@@ -268,7 +273,7 @@ def main():
                           "fused_speedup": base_ms / (dec_ms / T)},
         "roofline": {"bound": "hbm", "kernel": "fused_attn_kernel", "achieved": achieved, "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
-                     "traffic": MEASURED_TRAFFIC.get((args.workload, rel_eb, args.max_code_len or 12)),
+                     "traffic": MEASURED_TRAFFIC.get((args.workload, rel_eb, args.max_code_len)),
                      "bytes_per_launch": kern_bytes, "avg_launch_ms": kern_ms, "launches_timed": launches,
                      "timing": "HIP events around every fused-kernel launch on the launch stream, one eager pass of "
                                "the step right after the timed region (the timed region replays a HIP graph)"},

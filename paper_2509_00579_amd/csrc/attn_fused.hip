@@ -72,14 +72,15 @@ __device__ __forceinline__ uint32_t wave_excl_scan(uint32_t v, int lane) {
 #ifndef KVC_READER
 #define KVC_READER 1
 #endif
-constexpr int kWindowBits = 31;
+constexpr int kJunkBits = 1;                  // low window bits that are not stream bits
+constexpr int kWindowBits = 32 - kJunkBits;  // stream bits per window
 #if KVC_READER == 1
 // Readers keep a 64-bit piece {hi,lo} of the stream in registers plus the next word in reading direction, fetched
 // one window ahead: one 4-byte LDS read per window, off the critical path (only table lookups depend on each other).
 struct UpReader {
     uint32_t P, idx, lo, hi, nx;  // P = (next unread payload bit) + 31 = window start in wm1 bit coordinates
     __device__ __forceinline__ void open(const uint32_t *wm1, uint32_t first_bit) {
-        P = first_bit + 31u;
+        P = first_bit + (uint32_t)kWindowBits;
         idx = P >> 5;
         lo = wm1[idx];
         hi = wm1[idx + 1];
@@ -100,7 +101,7 @@ struct DownReader {
     uint32_t P, idx, lo, hi, pv;  // P = (one past the next unread payload bit) + 1: the window [P, P+32) of wm1 ends
                                   // one bit above the next unread bit; bit-reversed it reads downwards
     __device__ __forceinline__ void open(const uint32_t *wm1, uint32_t end_bit) {
-        P = end_bit + 1u;
+        P = end_bit + (uint32_t)kJunkBits;
         idx = P >> 5;
         lo = wm1[idx];
         hi = wm1[idx + 1];
@@ -123,7 +124,7 @@ struct DownReader {
 // Every window re-reads its two words from LDS (one ds_read2_b32): least bookkeeping, more LDS traffic.
 struct UpReader {
     uint32_t P;  // (next unread payload bit) + 31 = window start in wm1 bit coordinates
-    __device__ __forceinline__ void open(const uint32_t *, uint32_t first_bit) { P = first_bit + 31u; }
+    __device__ __forceinline__ void open(const uint32_t *, uint32_t first_bit) { P = first_bit + (uint32_t)kWindowBits; }
     __device__ __forceinline__ uint32_t window(const uint32_t *wm1) const {
         const uint32_t idx = P >> 5;
         return __builtin_amdgcn_alignbit(wm1[idx + 1], wm1[idx], P);
@@ -132,7 +133,7 @@ struct UpReader {
 };
 struct DownReader {
     uint32_t P;  // (one past the next unread payload bit) + 1
-    __device__ __forceinline__ void open(const uint32_t *, uint32_t end_bit) { P = end_bit + 1u; }
+    __device__ __forceinline__ void open(const uint32_t *, uint32_t end_bit) { P = end_bit + (uint32_t)kJunkBits; }
     __device__ __forceinline__ uint32_t window(const uint32_t *wm1) const {
         const uint32_t idx = P >> 5;
         return __builtin_bitreverse32(__builtin_amdgcn_alignbit(wm1[idx + 1], wm1[idx], P));
@@ -141,21 +142,28 @@ struct DownReader {
 };
 #endif
 
-// Decode CNT symbols from a window.  lut: entry = (symbol << 8) | code length, indexed by the next `bits` stream
-// bits; mask2 = ((1 << bits) - 1) << 1.  CNT * (longest code word) <= 31 is the caller's promise.  Returns the
-// number of bits used.
+// Decode CNT symbols from a window.  lut: 16-bit entries (symbol << 8) | code length, indexed by the next `bits`
+// stream bits; mask2 = ((1 << bits) - 1) << 1.  CNT * (longest code word) <= kWindowBits is the caller's promise.
+// e[] receives the entries; returns the number of bits used.
+// (32-bit entries with the symbol as an fp16 number in the upper half, consumed by v_fma_mix_f32 without a
+// conversion, were measured too: one VALU instruction less per symbol, but the table takes twice the LDS rows and
+// the extra bank conflicts cost more than the instruction saves, except for tables of 64 entries where it is a tie.)
 template <int CNT>
-__device__ __forceinline__ uint32_t lookup(uint32_t win, const char *lut, uint32_t mask2, float (&f)[CNT]) {
+__device__ __forceinline__ uint32_t lookup(uint32_t win, const char *lut, uint32_t mask2, uint32_t (&e)[CNT]) {
     uint32_t tot = 0;
 #pragma unroll
     for (int k = 0; k < CNT; k++) {
-        const uint32_t e = *reinterpret_cast<const uint16_t *>(lut + (win & mask2));
-        win >>= (e & 31u);
-        tot += e;  // low byte: running sum of code lengths (at most 31, never carries)
-        f[k] = (float)(e >> 8);
+        e[k] = *reinterpret_cast<const uint16_t *>(lut + (win & mask2));
+        win >>= (e[k] & 31u);
+        tot += e[k];  // low byte: running sum of code lengths (at most 31, never carries)
     }
     return tot & 0xffu;
 }
+
+// the symbol of a table entry as fp32 (one v_cvt_f32_ubyte1)
+__device__ __forceinline__ float sym_f32(uint32_t e) { return (float)(e >> 8); }
+// acc + w * symbol
+__device__ __forceinline__ float fma_sym(float w, uint32_t e, float acc) { return fmaf(w, sym_f32(e), acc); }
 
 // The four chains of one lane (two slices x two directions) advance together, CNT symbols each.
 struct Quad {
@@ -169,8 +177,8 @@ struct Quad {
         bd.open(wm1, a0 + abits + bbits);
     }
     template <int CNT>
-    __device__ __forceinline__ void step(const uint32_t *wm1, const char *lut, uint32_t mask2, float (&fau)[CNT],
-                                         float (&fad)[CNT], float (&fbu)[CNT], float (&fbd)[CNT]) {
+    __device__ __forceinline__ void step(const uint32_t *wm1, const char *lut, uint32_t mask2, uint32_t (&fau)[CNT],
+                                         uint32_t (&fad)[CNT], uint32_t (&fbu)[CNT], uint32_t (&fbd)[CNT]) {
         const uint32_t u0 = lookup<CNT>(au.window(wm1), lut, mask2, fau);
         const uint32_t u1 = lookup<CNT>(ad.window(wm1), lut, mask2, fad);
         const uint32_t u2 = lookup<CNT>(bu.window(wm1), lut, mask2, fbu);
@@ -224,32 +232,37 @@ struct Soft {
 // weight of head i (read from LDS, layout [symbol index][head]) and its own decoded symbol, and receives the four
 // heads' products for its own token / channel.  One MFMA replaces four broadcasts and four FMAs.
 typedef float v4f __attribute__((ext_vector_type(4)));
+#ifndef KVC_MFMA_MIN_G
+#define KVC_MFMA_MIN_G 4
+#endif
+constexpr int kMfmaMinG = KVC_MFMA_MIN_G;  // smallest query-head group that accumulates with MFMA
 
 __device__ __forceinline__ v4f mfma4(float a, float b, v4f c) { return __builtin_amdgcn_mfma_f32_4x4x1f32(a, b, c, 0, 0, 0); }
 
 // K: symbol index `up` of chain au/bu is channel up / 64+up, index `dn` of chain ad/bd is channel dn / 64+dn.
 template <int G, int CNT>
 __device__ __forceinline__ void k_accum(const float (&w0)[G], const float (&w1)[G], const float *wl, int first,
-                                        const float (&fau)[CNT], const float (&fad)[CNT], const float (&fbu)[CNT],
-                                        const float (&fbd)[CNT], float (&acc)[G], v4f (&macc)[4][(G + 3) / 4]) {
+                                        const uint32_t (&fau)[CNT], const uint32_t (&fad)[CNT],
+                                        const uint32_t (&fbu)[CNT], const uint32_t (&fbd)[CNT], float (&acc)[G],
+                                        v4f (&macc)[4][(G + 3) / 4]) {
 #pragma unroll
     for (int k = 0; k < CNT; k++) {
         const int up = first + k, dn = kSliceLen - 1 - up;  // symbol index inside the slice
-        if constexpr (G >= 4) {
+        if constexpr (G >= kMfmaMinG) {
 #pragma unroll
-            for (int q = 0; q < G / 4; q++) {
-                macc[0][q] = mfma4(wl[up * G + 4 * q], fau[k], macc[0][q]);
-                macc[1][q] = mfma4(wl[dn * G + 4 * q], fad[k], macc[1][q]);
-                macc[2][q] = mfma4(wl[(kSliceLen + up) * G + 4 * q], fbu[k], macc[2][q]);
-                macc[3][q] = mfma4(wl[(kSliceLen + dn) * G + 4 * q], fbd[k], macc[3][q]);
+            for (int q = 0; q < (G + 3) / 4; q++) {
+                macc[0][q] = mfma4(wl[up * G + 4 * q], sym_f32(fau[k]), macc[0][q]);
+                macc[1][q] = mfma4(wl[dn * G + 4 * q], sym_f32(fad[k]), macc[1][q]);
+                macc[2][q] = mfma4(wl[(kSliceLen + up) * G + 4 * q], sym_f32(fbu[k]), macc[2][q]);
+                macc[3][q] = mfma4(wl[(kSliceLen + dn) * G + 4 * q], sym_f32(fbd[k]), macc[3][q]);
             }
         } else {
 #pragma unroll
             for (int g = 0; g < G; g++) {
-                acc[g] = fmaf(bcast(w0[g], up), fau[k], acc[g]);
-                acc[g] = fmaf(bcast(w0[g], dn), fad[k], acc[g]);
-                acc[g] = fmaf(bcast(w1[g], up), fbu[k], acc[g]);
-                acc[g] = fmaf(bcast(w1[g], dn), fbd[k], acc[g]);
+                acc[g] = fma_sym(bcast(w0[g], up), fau[k], acc[g]);
+                acc[g] = fma_sym(bcast(w0[g], dn), fad[k], acc[g]);
+                acc[g] = fma_sym(bcast(w1[g], up), fbu[k], acc[g]);
+                acc[g] = fma_sym(bcast(w1[g], dn), fbd[k], acc[g]);
             }
         }
     }
@@ -257,29 +270,29 @@ __device__ __forceinline__ void k_accum(const float (&w0)[G], const float (&w1)[
 
 // V: symbol index = token; chains au/ad belong to channel 2*lane, bu/bd to channel 2*lane+1.
 template <int G, int CNT>
-__device__ __forceinline__ void v_accum(const float (&w)[G], const float *wl, int first, const float (&fau)[CNT],
-                                        const float (&fad)[CNT], const float (&fbu)[CNT], const float (&fbd)[CNT],
-                                        float (&acc)[G][2], v4f (&macc)[4][(G + 3) / 4]) {
+__device__ __forceinline__ void v_accum(const float (&w)[G], const float *wl, int first, const uint32_t (&fau)[CNT],
+                                        const uint32_t (&fad)[CNT], const uint32_t (&fbu)[CNT],
+                                        const uint32_t (&fbd)[CNT], float (&acc)[G][2], v4f (&macc)[4][(G + 3) / 4]) {
 #pragma unroll
     for (int k = 0; k < CNT; k++) {
         const int up = first + k, dn = kSliceLen - 1 - up;  // token index inside the block
-        if constexpr (G >= 4) {
+        if constexpr (G >= kMfmaMinG) {
 #pragma unroll
-            for (int q = 0; q < G / 4; q++) {
+            for (int q = 0; q < (G + 3) / 4; q++) {
                 const float au_w = wl[up * G + 4 * q], ad_w = wl[dn * G + 4 * q];
-                macc[0][q] = mfma4(au_w, fau[k], macc[0][q]);
-                macc[1][q] = mfma4(ad_w, fad[k], macc[1][q]);
-                macc[2][q] = mfma4(au_w, fbu[k], macc[2][q]);
-                macc[3][q] = mfma4(ad_w, fbd[k], macc[3][q]);
+                macc[0][q] = mfma4(au_w, sym_f32(fau[k]), macc[0][q]);
+                macc[1][q] = mfma4(ad_w, sym_f32(fad[k]), macc[1][q]);
+                macc[2][q] = mfma4(au_w, sym_f32(fbu[k]), macc[2][q]);
+                macc[3][q] = mfma4(ad_w, sym_f32(fbd[k]), macc[3][q]);
             }
         } else {
 #pragma unroll
             for (int g = 0; g < G; g++) {
                 const float wu = bcast(w[g], up), wd = bcast(w[g], dn);
-                acc[g][0] = fmaf(wu, fau[k], acc[g][0]);
-                acc[g][0] = fmaf(wd, fad[k], acc[g][0]);
-                acc[g][1] = fmaf(wu, fbu[k], acc[g][1]);
-                acc[g][1] = fmaf(wd, fbd[k], acc[g][1]);
+                acc[g][0] = fma_sym(wu, fau[k], acc[g][0]);
+                acc[g][0] = fma_sym(wd, fad[k], acc[g][0]);
+                acc[g][1] = fma_sym(wu, fbu[k], acc[g][1]);
+                acc[g][1] = fma_sym(wd, fbd[k], acc[g][1]);
             }
         }
     }
@@ -304,7 +317,7 @@ __device__ __forceinline__ void k_block(const uint32_t *hdr32, const char *lut, 
         w1[g] = qreg[g][1] * st1;
         acc[g] = 0.f;
     }
-    if constexpr (G >= 4) {
+    if constexpr (G >= kMfmaMinG) {
 #pragma unroll
         for (int g = 0; g < G; g++) {
             wts[lane * G + g] = w0[g];
@@ -313,32 +326,34 @@ __device__ __forceinline__ void k_block(const uint32_t *hdr32, const char *lut, 
 #pragma unroll
         for (int c = 0; c < 4; c++)
 #pragma unroll
-            for (int q = 0; q < G / 4; q++) macc[c][q] = (v4f){0.f, 0.f, 0.f, 0.f};
+            for (int q = 0; q < (G + 3) / 4; q++) macc[c][q] = (v4f){0.f, 0.f, 0.f, 0.f};
     }
-    const float *wl = wts + (lane & 3);
+    const float *wl = wts + (lane & 3 & (G - 1));
     const uint32_t sb = hdr32[kMinMaxBytesK / 4 + lane];  // bit counts of slices 2*lane and 2*lane+1
     const uint32_t start = wave_excl_scan((sb & 0xffffu) + (sb >> 16), lane);
     const uint32_t *wm1 = hdr32 + kHdrBytesK / 4 - 1;
-    if constexpr (G >= 4) wave_sync();
+    if constexpr (G >= kMfmaMinG) wave_sync();
     Quad qd;
     qd.open(wm1, start, sb & 0xffffu, sb >> 16);
     constexpr int kRounds = kHalf / NS, kTail = kHalf - kRounds * NS;
 #pragma unroll 2
     for (int r = 0; r < kRounds; r++) {
-        float fau[NS], fad[NS], fbu[NS], fbd[NS];
+        uint32_t fau[NS], fad[NS], fbu[NS], fbd[NS];
         qd.step<NS>(wm1, lut, mask2, fau, fad, fbu, fbd);
         k_accum<G, NS>(w0, w1, wl, r * NS, fau, fad, fbu, fbd, acc, macc);
     }
     if constexpr (kTail > 0) {
-        float fau[kTail], fad[kTail], fbu[kTail], fbd[kTail];
+        uint32_t fau[kTail], fad[kTail], fbu[kTail], fbd[kTail];
         qd.step<kTail>(wm1, lut, mask2, fau, fad, fbu, fbd);
         k_accum<G, kTail>(w0, w1, wl, kRounds * NS, fau, fad, fbu, fbd, acc, macc);
     }
-    if constexpr (G >= 4) {
+    if constexpr (G >= kMfmaMinG) {
 #pragma unroll
-        for (int q = 0; q < G / 4; q++) {
+        for (int q = 0; q < (G + 3) / 4; q++) {
             const v4f t = macc[0][q] + macc[1][q] + macc[2][q] + macc[3][q];
-            acc[4 * q + 0] = t.x; acc[4 * q + 1] = t.y; acc[4 * q + 2] = t.z; acc[4 * q + 3] = t.w;
+            const float tt[4] = {t.x, t.y, t.z, t.w};
+#pragma unroll
+            for (int i = 0; i < 4 && 4 * q + i < G; i++) acc[4 * q + i] = tt[i];
         }
     }
     // the constant part of the dot product, sum_c q_c min_c, is shared by all tokens of the block
@@ -362,39 +377,43 @@ __device__ __forceinline__ void v_block(const uint32_t *hdr32, const char *lut, 
         w[g] = p[g] * step;
         st.bv[g] += p[g] * mn;
     }
-    if constexpr (G >= 4) {
+    if constexpr (G >= kMfmaMinG) {
 #pragma unroll
         for (int g = 0; g < G; g++) wts[lane * G + g] = w[g];
 #pragma unroll
         for (int c = 0; c < 4; c++)
 #pragma unroll
-            for (int q = 0; q < G / 4; q++) macc[c][q] = (v4f){0.f, 0.f, 0.f, 0.f};
+            for (int q = 0; q < (G + 3) / 4; q++) macc[c][q] = (v4f){0.f, 0.f, 0.f, 0.f};
     }
-    const float *wl = wts + (lane & 3);
+    const float *wl = wts + (lane & 3 & (G - 1));
     const uint32_t sb = hdr32[kMinMaxBytesV / 4 + lane];
     const uint32_t start = wave_excl_scan((sb & 0xffffu) + (sb >> 16), lane);
     const uint32_t *wm1 = hdr32 + kHdrBytesV / 4 - 1;
-    if constexpr (G >= 4) wave_sync();
+    if constexpr (G >= kMfmaMinG) wave_sync();
     Quad qd;
     qd.open(wm1, start, sb & 0xffffu, sb >> 16);
     constexpr int kRounds = kHalf / NS, kTail = kHalf - kRounds * NS;
 #pragma unroll 2
     for (int r = 0; r < kRounds; r++) {
-        float fau[NS], fad[NS], fbu[NS], fbd[NS];
+        uint32_t fau[NS], fad[NS], fbu[NS], fbd[NS];
         qd.step<NS>(wm1, lut, mask2, fau, fad, fbu, fbd);
         v_accum<G, NS>(w, wl, r * NS, fau, fad, fbu, fbd, st.acc, macc);
     }
     if constexpr (kTail > 0) {
-        float fau[kTail], fad[kTail], fbu[kTail], fbd[kTail];
+        uint32_t fau[kTail], fad[kTail], fbu[kTail], fbd[kTail];
         qd.step<kTail>(wm1, lut, mask2, fau, fad, fbu, fbd);
         v_accum<G, kTail>(w, wl, kRounds * NS, fau, fad, fbu, fbd, st.acc, macc);
     }
-    if constexpr (G >= 4) {
+    if constexpr (G >= kMfmaMinG) {
 #pragma unroll
-        for (int q = 0; q < G / 4; q++) {
+        for (int q = 0; q < (G + 3) / 4; q++) {
             const v4f a = macc[0][q] + macc[1][q], bsum = macc[2][q] + macc[3][q];
-            st.acc[4 * q + 0][0] += a.x; st.acc[4 * q + 1][0] += a.y; st.acc[4 * q + 2][0] += a.z; st.acc[4 * q + 3][0] += a.w;
-            st.acc[4 * q + 0][1] += bsum.x; st.acc[4 * q + 1][1] += bsum.y; st.acc[4 * q + 2][1] += bsum.z; st.acc[4 * q + 3][1] += bsum.w;
+            const float ta[4] = {a.x, a.y, a.z, a.w}, tb[4] = {bsum.x, bsum.y, bsum.z, bsum.w};
+#pragma unroll
+            for (int i = 0; i < 4 && 4 * q + i < G; i++) {
+                st.acc[4 * q + i][0] += ta[i];
+                st.acc[4 * q + i][1] += tb[i];
+            }
         }
     }
 }
@@ -443,6 +462,21 @@ struct Prefetch {
 constexpr int kWaves = 4;
 constexpr int kThreads = 64 * kWaves;
 
+// Developer instrumentation, compiled in with -DKVC_TRACE only: wave 0.. of every workgroup records the 100 MHz
+// wall clock at eight points of the kernel (the shader clock at points 1 and 5); kvcomp_trace_read() copies the records to the host.
+#ifdef KVC_TRACE
+constexpr int kTraceSlots = 8, kTraceWaves = 1 << 15;
+__device__ unsigned long long g_trace[kTraceWaves * kTraceSlots];
+#define KVC_MARK(k)                                                                                              \
+    do {                                                                                                         \
+        const unsigned wv = ((blockIdx.y * gridDim.x + blockIdx.x) * kWaves + wave);                             \
+        if (lane == 0 && wv < kTraceWaves)                                                                       \
+            g_trace[wv * kTraceSlots + (k)] = (k) == 1 || (k) == 5 ? clock64() : wall_clock64();                 \
+    } while (0)
+#else
+#define KVC_MARK(k) do { } while (0)
+#endif
+
 // Register budget: 4 waves per SIMD (128 VGPRs) for groups of 1 and 2 query heads, 3 (168) and 2 (256) for groups
 // of 4 and 8.
 template <int G> struct WavesPerSimd { static constexpr int value = fused_wgs_per_cu(G); };
@@ -457,10 +491,11 @@ __global__ __launch_bounds__(kThreads, WavesPerSimd<G>::value) void fused_attn_k
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];  // per wave: staging area; groups >= 4: + weights
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     uint8_t *stage = smem + (size_t)wave * a.stage_bytes;
-    float *wts = reinterpret_cast<float *>(smem + (size_t)kWaves * a.stage_bytes) + (G >= 4 ? wave * G * kD : 0);
+    float *wts = reinterpret_cast<float *>(smem + (size_t)kWaves * a.stage_bytes) + (G >= kMfmaMinG ? wave * G * kD : 0);
     const char *lutK = reinterpret_cast<const char *>(&lut_s[0][0]);
     const char *lutV = reinterpret_cast<const char *>(&lut_s[1][0]);
 
+    KVC_MARK(0);
     const Geo &g = a.g;
     const int split = blockIdx.x, bh = blockIdx.y;
     const int b = bh / g.H, h = bh - b * g.H;
@@ -495,6 +530,7 @@ __global__ __launch_bounds__(kThreads, WavesPerSimd<G>::value) void fused_attn_k
     pf.n16 = 0;
     if (j < j1 && eK.size16 <= stage16) pf.issue(g.payload + (size_t)eK.off16 * 16, eK.size16, lane);
     __syncthreads();
+    KVC_MARK(1);
     float qreg[G][2];
 #pragma unroll
     for (int gg = 0; gg < G; gg++) { qreg[gg][0] = qf[gg * kD + lane]; qreg[gg][1] = qf[gg * kD + lane + 64]; }
@@ -506,6 +542,11 @@ __global__ __launch_bounds__(kThreads, WavesPerSimd<G>::value) void fused_attn_k
         if (eK.size16 <= stage16) pf.commit(stage4, lane);
         wave_sync();
     }
+    KVC_MARK(2);
+#ifdef KVC_TRACE
+    bool first = true;
+#endif
+    __builtin_amdgcn_s_setprio(3);
     while (j < j1) {
         float score[G], p[G];
         const bool k_staged = eK.size16 <= stage16, v_staged = eV.size16 <= stage16;
@@ -522,6 +563,9 @@ __global__ __launch_bounds__(kThreads, WavesPerSimd<G>::value) void fused_attn_k
 #pragma unroll
             for (int gg = 0; gg < G; gg++) score[gg] = s_tmp[gg];
         }
+#ifdef KVC_TRACE
+        if (first) KVC_MARK(3);
+#endif
 #pragma unroll
         for (int gg = 0; gg < G; gg++) p[gg] = st.update(gg, score[gg]);
         wave_sync();  // every lane is done with the K record
@@ -545,14 +589,29 @@ __global__ __launch_bounds__(kThreads, WavesPerSimd<G>::value) void fused_attn_k
                                   st_tmp);
             st = st_tmp;
         }
+#ifdef KVC_TRACE
+        if (first) KVC_MARK(4);
+        first = false;
+#endif
         wave_sync();
         if (jn < j1 && eKn.size16 <= stage16) pf.commit(stage4, lane);
         wave_sync();
         eK = eKn;
         eV = eVn;
         j = jn;
+        {   // The SIMD issues from its oldest wave first, so the four resident waves finish one after the other and
+            // the last one runs alone, unable to fill the VALU.  Waves that are behind get the issue slots instead:
+            // the priority falls with the share of the work that is done, and the waves finish together.
+            const int total = (j1 - j0 - wave + kWaves - 1) / kWaves, left = (j1 - j + kWaves - 1) / kWaves;
+            const int q4 = total > 0 ? (4 * left + total - 1) / total : 0;  // 4 .. 0
+            if (q4 >= 4) __builtin_amdgcn_s_setprio(3);
+            else if (q4 == 3) __builtin_amdgcn_s_setprio(2);
+            else if (q4 == 2) __builtin_amdgcn_s_setprio(1);
+            else __builtin_amdgcn_s_setprio(0);
+        }
     }
 
+    KVC_MARK(5);
     // The buffered fp16 tokens (Section 3.2.3: the newest vectors take part too): last split, wave 0.
     if (split == a.n_splits - 1 && wave == 0 && a.n_res > 0) {
         const size_t res_tensor = (size_t)g.B * kBT * g.H * kD;
@@ -629,7 +688,9 @@ __global__ __launch_bounds__(kThreads, WavesPerSimd<G>::value) void fused_attn_k
             if (c == 0) { store_agent(dst + kD, M); store_agent(dst + kD + 1, L); }
         }
     }
+    KVC_MARK(6);
     if (a.n_splits > 1) finish_splits<G, kThreads>(g.partials, g.counters + bh, row0, a.n_splits, a.out, tid);
+    KVC_MARK(7);
 }
 
 template <int G, int LB>
@@ -650,11 +711,13 @@ static hipError_t launch_fused_gn(const FusedArgs &a, size_t lds, hipEvent_t ev0
 template <int G>
 static hipError_t launch_fused_g(const FusedArgs &a, int longest, size_t lds, hipEvent_t ev0, hipEvent_t ev1,
                                  hipStream_t s) {
-    if (longest <= 6) return launch_fused_gn<G, 6>(a, lds, ev0, ev1, s);
-    if (longest <= 7) return launch_fused_gn<G, 7>(a, lds, ev0, ev1, s);
-    if (longest <= 8) return launch_fused_gn<G, 8>(a, lds, ev0, ev1, s);
-    if (longest <= 10) return launch_fused_gn<G, 10>(a, lds, ev0, ev1, s);
-    return launch_fused_gn<G, 12>(a, lds, ev0, ev1, s);
+    switch (fused_table_bits(longest)) {
+        case 6: return launch_fused_gn<G, 6>(a, lds, ev0, ev1, s);
+        case 7: return launch_fused_gn<G, 7>(a, lds, ev0, ev1, s);
+        case 8: return launch_fused_gn<G, 8>(a, lds, ev0, ev1, s);
+        case 10: return launch_fused_gn<G, 10>(a, lds, ev0, ev1, s);
+        default: return launch_fused_gn<G, 12>(a, lds, ev0, ev1, s);
+    }
 }
 
 hipError_t launch_fused_attn(const Geo &g, const uint16_t *q, float scale, float *out, int n_blocks, int n_res,
@@ -672,9 +735,9 @@ hipError_t launch_fused_attn(const Geo &g, const uint16_t *q, float scale, float
     const int bits_k = g.lut_bits[0], bits_v = g.lut_bits[1];
     const int longest = bits_k > bits_v ? bits_k : bits_v;
     if (longest < 1 || longest > kLutBits) return hipErrorInvalidValue;
-    a.mask2[0] = ((1u << bits_k) - 1u) << 1;
-    a.mask2[1] = ((1u << bits_v) - 1u) << 1;
-    const size_t lds = (size_t)kWaves * stage_bytes + (g.G >= 4 ? (size_t)kWaves * g.G * kD * 4 : 0);
+    a.mask2[0] = ((1u << bits_k) - 1u) << kJunkBits;
+    a.mask2[1] = ((1u << bits_v) - 1u) << kJunkBits;
+    const size_t lds = (size_t)kWaves * stage_bytes + (g.G >= kMfmaMinG ? (size_t)kWaves * g.G * kD * 4 : 0);
     switch (g.G) {
         case 1: return launch_fused_g<1>(a, longest, lds, ev0, ev1, s);
         case 2: return launch_fused_g<2>(a, longest, lds, ev0, ev1, s);
@@ -683,6 +746,13 @@ hipError_t launch_fused_attn(const Geo &g, const uint16_t *q, float scale, float
         default: return hipErrorInvalidValue;
     }
 }
+
+#ifdef KVC_TRACE
+extern "C" int kvcomp_trace_read(unsigned long long *host, size_t n) {
+    if (n > (size_t)kTraceWaves * kTraceSlots) n = (size_t)kTraceWaves * kTraceSlots;
+    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(g_trace), n * sizeof(unsigned long long));
+}
+#endif
 
 // ---- statistics (metrics path, not part of the hot loop) --------------------------------------------------------
 // Sums record sizes and code-word bits over all blocks in use by walking the Block Offsets Array and the slice bit

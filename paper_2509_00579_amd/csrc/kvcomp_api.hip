@@ -387,14 +387,22 @@ kvcomp_status kvcomp_attn_decode(kvcomp_ctx *ctx, const void *d_q, float scale, 
     if (ctx->n_blocks && !ctx->have_codebook) return fail(KVCOMP_ERR_STATE, "no codebook");
     hipStream_t s = static_cast<hipStream_t>(stream);
     const Geo &g = ctx->geo;
-    // Work split: the grid should fit the chip in a single round of workgroups (256 CUs x the 2..4 workgroups of
-    // 4 waves that are resident per CU for this group size), every wave owning whole block pairs; per-workgroup
-    // costs (tables, first record, split merge) are then paid once per resident slot, and no second, partly filled
-    // round of workgroups trails the first.
+    // Work split: the grid should fit the chip in a single round of workgroups (256 CUs x the workgroups of 4 waves
+    // that registers and LDS let be resident per CU for this group size and table width), every wave owning whole
+    // block pairs; per-workgroup costs (tables, first record, split merge) are then paid once per resident slot,
+    // and no second, partly filled round of workgroups trails the first.
+    const int longest = std::max(g.lut_bits[0], g.lut_bits[1]);
+    const size_t lds_fixed = fused_lds_fixed(g.G, longest);
+    int stage = ctx->tune_stage;
+    if (stage <= 0) stage = (int)align_up((size_t)ctx->max_size16 * 16 + 16, 256);
+    stage = std::max(stage, 4608);
+    stage = (int)align_up(stage, 16);
+    if (lds_fixed + 4 * (size_t)stage > (size_t)kLdsBytesPerCU) stage = (int)((kLdsBytesPerCU - lds_fixed) / 4 / 16 * 16);
     int n_splits = ctx->tune_splits;
     if (n_splits <= 0) {
         const int bh = g.B * g.H;
-        const int by_chip = std::max(1, kCUs * fused_wgs_per_cu(g.G) / bh);
+        const int resident = std::max(1, std::min(fused_wgs_per_cu(g.G), (int)(kLdsBytesPerCU / (lds_fixed + 4 * (size_t)stage))));
+        const int by_chip = std::max(1, kCUs * resident / bh);
         const int by_work = std::max(1, (ctx->n_blocks + 3) / 4);  // at least one block pair per wave
         n_splits = std::min(by_chip, by_work);
         int bps = (ctx->n_blocks + n_splits - 1) / std::max(n_splits, 1);
@@ -402,13 +410,6 @@ kvcomp_status kvcomp_attn_decode(kvcomp_ctx *ctx, const void *d_q, float scale, 
         n_splits = bps > 0 ? (ctx->n_blocks + bps - 1) / bps : 1;
     }
     n_splits = std::max(1, std::min({n_splits, (int)kMaxSplits, std::max(ctx->n_blocks, 1)}));
-    int stage = ctx->tune_stage;
-    if (stage <= 0) stage = (int)align_up((size_t)ctx->max_size16 * 16 + 16, 256);
-    stage = std::max(stage, 4608);
-    stage = (int)align_up(stage, 16);
-    const size_t lds_fixed = 2 * kLutSize * 2 + (size_t)g.G * kD * 4 + 1024;  // decode tables, q, slack
-    const size_t lds_max = 160 * 1024;
-    if (lds_fixed + 4 * (size_t)stage > lds_max) stage = (int)((lds_max - lds_fixed) / 4 / 16 * 16);
     hipEvent_t ev0 = nullptr, ev1 = nullptr;
     if (ctx->profiling) {
         if (ctx->events_used + 2 > ctx->events.size()) {

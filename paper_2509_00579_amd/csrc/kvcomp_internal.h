@@ -72,6 +72,16 @@ constexpr int kCUs = 256;  // compute units of the MI355X
 // Workgroups (of 4 waves) of the fused kernel that are resident per CU = its waves per SIMD: groups of 4 and 8 query
 // heads carry more accumulators and weights and trade occupancy for registers instead of spilling.
 constexpr int fused_wgs_per_cu(int G) { return G >= 8 ? 2 : G >= 4 ? 3 : 4; }
+// Index width the fused kernel's LDS decode tables are compiled for, given the longest code word in use.
+constexpr int fused_table_bits(int longest) {
+    return longest <= 6 ? 6 : longest <= 7 ? 7 : longest <= 8 ? 8 : longest <= 10 ? 10 : 12;
+}
+constexpr int kLdsBytesPerCU = 160 * 1024;
+// LDS of one fused-kernel workgroup apart from the per-wave staging areas: two decode tables of 16-bit entries, the
+// query rows, and (groups of 4 and 8 heads) the per-wave weight areas of the MFMA accumulation.
+constexpr size_t fused_lds_fixed(int G, int longest) {
+    return ((size_t)4 << fused_table_bits(longest)) + (size_t)G * kD * 4 + (G >= 4 ? (size_t)4 * G * kD * 4 : 0) + 512;
+}
 
 // ---- launches implemented in the .hip files ----
 hipError_t launch_histogram(const Geo &g, int which, const uint16_t *X, int seq_stride, int n_blk_per_bh,
