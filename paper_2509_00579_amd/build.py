@@ -61,5 +61,12 @@ def build(verbose: bool = False, extra_flags=(), out: pathlib.Path | None = None
     return lib
 
 
+def device_assembly(src: str) -> str:
+    """gfx950 assembly text of one source file, compiled with the library's flags (for checks on the generated code)."""
+    cmd = [_hipcc(), *FLAGS, "--cuda-device-only", "-S", str(CSRC / src), "-o", "-"]
+    r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.DEVNULL, text=True, check=True)
+    return r.stdout
+
+
 if __name__ == "__main__":
     build(verbose=True)

@@ -225,8 +225,9 @@ struct Soft {
 };
 
 // ---- accumulation of one round of decoded symbols -----------------------------------------------------------------
-// Query-head groups of 1 and 2: the folded weight of the current symbol is wave-uniform, lives in one lane's register
-// and is broadcast with v_readlane; one FMA per symbol and head.
+// The folded weight of the current symbol is wave-uniform.  Query-head groups of 1 and 2: every fourth step, lane i
+// of each quad of lanes fetches the weight of step s + i from LDS (four addresses, no bank conflict); the FMA of
+// step s + i then takes it through a quad broadcast.  No instruction is spent on the broadcast itself.
 // Groups of 4 and 8 (GQA): a decode step is a small matrix product -- (heads x 1) weights times (1 x lanes) decoded
 // symbols -- which is what v_mfma_f32_4x4x1f32 computes for each group of four lanes: lane i of a group supplies the
 // weight of head i (read from LDS, layout [symbol index][head]) and its own decoded symbol, and receives the four
@@ -237,11 +238,33 @@ typedef float v4f __attribute__((ext_vector_type(4)));
 #endif
 constexpr int kMfmaMinG = KVC_MFMA_MIN_G;  // smallest query-head group that accumulates with MFMA
 
+// acc + (w of lane Q of this lane's quad) * symbol: the quad broadcast is a DPP modifier of the FMA's first operand,
+// no instruction of its own.  w must not have been written by a VALU instruction in the two instructions before
+// (it comes from an LDS read).
+template <int Q>
+__device__ __forceinline__ float fma_quad_c(float w, float sym, float acc) {
+    static_assert(Q >= 0 && Q < 4, "quad lane");
+    if constexpr (Q == 0) asm("v_fmac_f32_dpp %0, %1, %2 quad_perm:[0,0,0,0] row_mask:0xf bank_mask:0xf" : "+v"(acc) : "v"(w), "v"(sym));
+    if constexpr (Q == 1) asm("v_fmac_f32_dpp %0, %1, %2 quad_perm:[1,1,1,1] row_mask:0xf bank_mask:0xf" : "+v"(acc) : "v"(w), "v"(sym));
+    if constexpr (Q == 2) asm("v_fmac_f32_dpp %0, %1, %2 quad_perm:[2,2,2,2] row_mask:0xf bank_mask:0xf" : "+v"(acc) : "v"(w), "v"(sym));
+    if constexpr (Q == 3) asm("v_fmac_f32_dpp %0, %1, %2 quad_perm:[3,3,3,3] row_mask:0xf bank_mask:0xf" : "+v"(acc) : "v"(w), "v"(sym));
+    return acc;
+}
+__device__ __forceinline__ float fma_quad(float w, int q, uint32_t e, float acc) {
+    const float sym = sym_f32(e);
+    switch (q & 3) {
+        case 0: return fma_quad_c<0>(w, sym, acc);
+        case 1: return fma_quad_c<1>(w, sym, acc);
+        case 2: return fma_quad_c<2>(w, sym, acc);
+        default: return fma_quad_c<3>(w, sym, acc);
+    }
+}
+
 __device__ __forceinline__ v4f mfma4(float a, float b, v4f c) { return __builtin_amdgcn_mfma_f32_4x4x1f32(a, b, c, 0, 0, 0); }
 
 // K: symbol index `up` of chain au/bu is channel up / 64+up, index `dn` of chain ad/bd is channel dn / 64+dn.
 template <int G, int CNT>
-__device__ __forceinline__ void k_accum(const float (&w0)[G], const float (&w1)[G], const float *wl, int first,
+__device__ __forceinline__ void k_accum(const float *wl, const float *wdn, float (&wq)[4][G], int first,
                                         const uint32_t (&fau)[CNT], const uint32_t (&fad)[CNT],
                                         const uint32_t (&fbu)[CNT], const uint32_t (&fbd)[CNT], float (&acc)[G],
                                         v4f (&macc)[4][(G + 3) / 4]) {
@@ -257,12 +280,22 @@ __device__ __forceinline__ void k_accum(const float (&w0)[G], const float (&w1)[
                 macc[3][q] = mfma4(wl[(kSliceLen + dn) * G + 4 * q], sym_f32(fbd[k]), macc[3][q]);
             }
         } else {
+            const int q = up & 3;
+            if (q == 0) {  // wl = weights + (lane & 3) * G, wdn = weights - (lane & 3) * G
+#pragma unroll
+                for (int g = 0; g < G; g++) {
+                    wq[0][g] = wl[up * G + g];
+                    wq[1][g] = wdn[dn * G + g];
+                    wq[2][g] = wl[(kSliceLen + up) * G + g];
+                    wq[3][g] = wdn[(kSliceLen + dn) * G + g];
+                }
+            }
 #pragma unroll
             for (int g = 0; g < G; g++) {
-                acc[g] = fma_sym(bcast(w0[g], up), fau[k], acc[g]);
-                acc[g] = fma_sym(bcast(w0[g], dn), fad[k], acc[g]);
-                acc[g] = fma_sym(bcast(w1[g], up), fbu[k], acc[g]);
-                acc[g] = fma_sym(bcast(w1[g], dn), fbd[k], acc[g]);
+                acc[g] = fma_quad(wq[0][g], q, fau[k], acc[g]);
+                acc[g] = fma_quad(wq[1][g], q, fad[k], acc[g]);
+                acc[g] = fma_quad(wq[2][g], q, fbu[k], acc[g]);
+                acc[g] = fma_quad(wq[3][g], q, fbd[k], acc[g]);
             }
         }
     }
@@ -270,9 +303,10 @@ __device__ __forceinline__ void k_accum(const float (&w0)[G], const float (&w1)[
 
 // V: symbol index = token; chains au/ad belong to channel 2*lane, bu/bd to channel 2*lane+1.
 template <int G, int CNT>
-__device__ __forceinline__ void v_accum(const float (&w)[G], const float *wl, int first, const uint32_t (&fau)[CNT],
-                                        const uint32_t (&fad)[CNT], const uint32_t (&fbu)[CNT],
-                                        const uint32_t (&fbd)[CNT], float (&acc)[G][2], v4f (&macc)[4][(G + 3) / 4]) {
+__device__ __forceinline__ void v_accum(const float *wl, const float *wdn, float (&wq)[2][G], int first,
+                                        const uint32_t (&fau)[CNT], const uint32_t (&fad)[CNT],
+                                        const uint32_t (&fbu)[CNT], const uint32_t (&fbd)[CNT], float (&acc)[G][2],
+                                        v4f (&macc)[4][(G + 3) / 4]) {
 #pragma unroll
     for (int k = 0; k < CNT; k++) {
         const int up = first + k, dn = kSliceLen - 1 - up;  // token index inside the block
@@ -286,20 +320,27 @@ __device__ __forceinline__ void v_accum(const float (&w)[G], const float *wl, in
                 macc[3][q] = mfma4(ad_w, sym_f32(fbd[k]), macc[3][q]);
             }
         } else {
+            const int q = up & 3;
+            if (q == 0) {
+#pragma unroll
+                for (int g = 0; g < G; g++) {
+                    wq[0][g] = wl[up * G + g];
+                    wq[1][g] = wdn[dn * G + g];
+                }
+            }
 #pragma unroll
             for (int g = 0; g < G; g++) {
-                const float wu = bcast(w[g], up), wd = bcast(w[g], dn);
-                acc[g][0] = fma_sym(wu, fau[k], acc[g][0]);
-                acc[g][0] = fma_sym(wd, fad[k], acc[g][0]);
-                acc[g][1] = fma_sym(wu, fbu[k], acc[g][1]);
-                acc[g][1] = fma_sym(wd, fbd[k], acc[g][1]);
+                acc[g][0] = fma_quad(wq[0][g], q, fau[k], acc[g][0]);
+                acc[g][0] = fma_quad(wq[1][g], q, fad[k], acc[g][0]);
+                acc[g][1] = fma_quad(wq[0][g], q, fbu[k], acc[g][1]);
+                acc[g][1] = fma_quad(wq[1][g], q, fbd[k], acc[g][1]);
             }
         }
     }
 }
 
 // ---- K block: lane = token; its two slices are channels 0..63 and 64..127 ------------------------------------------
-// hdr32: the record (LDS or global); wts: this wave's LDS weight area (used by groups >= 4 only).  Leaves
+// hdr32: the record (LDS or global); wts: this wave's LDS weight area.  Leaves
 // scale * q.k' of this lane's token in score[].
 template <int G, int NS>
 __device__ __forceinline__ void k_block(const uint32_t *hdr32, const char *lut, uint32_t mask2, float *wts,
@@ -317,35 +358,45 @@ __device__ __forceinline__ void k_block(const uint32_t *hdr32, const char *lut, 
         w1[g] = qreg[g][1] * st1;
         acc[g] = 0.f;
     }
-    if constexpr (G >= kMfmaMinG) {
 #pragma unroll
-        for (int g = 0; g < G; g++) {
-            wts[lane * G + g] = w0[g];
-            wts[(kSliceLen + lane) * G + g] = w1[g];
-        }
-#pragma unroll
-        for (int c = 0; c < 4; c++)
-#pragma unroll
-            for (int q = 0; q < (G + 3) / 4; q++) macc[c][q] = (v4f){0.f, 0.f, 0.f, 0.f};
+    for (int g = 0; g < G; g++) {  // LDS layout [channel][head]
+        wts[lane * G + g] = w0[g];
+        wts[(kSliceLen + lane) * G + g] = w1[g];
     }
-    const float *wl = wts + (lane & 3 & (G - 1));
+#pragma unroll
+    for (int c = 0; c < 4; c++)
+#pragma unroll
+        for (int q = 0; q < (G + 3) / 4; q++) macc[c][q] = (v4f){0.f, 0.f, 0.f, 0.f};
+    // MFMA: lane i of a quad supplies head i.  Otherwise: lane i of a quad fetches the weights of step s + i.
+    const float *wl = G >= kMfmaMinG ? wts + (lane & 3) : wts + (lane & 3) * G;
+    const float *wdn = wts - (lane & 3) * G;
+    float wq[4][G];
     const uint32_t sb = hdr32[kMinMaxBytesK / 4 + lane];  // bit counts of slices 2*lane and 2*lane+1
     const uint32_t start = wave_excl_scan((sb & 0xffffu) + (sb >> 16), lane);
     const uint32_t *wm1 = hdr32 + kHdrBytesK / 4 - 1;
-    if constexpr (G >= kMfmaMinG) wave_sync();
+    wave_sync();
     Quad qd;
     qd.open(wm1, start, sb & 0xffffu, sb >> 16);
     constexpr int kRounds = kHalf / NS, kTail = kHalf - kRounds * NS;
+    if constexpr (G >= kMfmaMinG) {
 #pragma unroll 2
-    for (int r = 0; r < kRounds; r++) {
-        uint32_t fau[NS], fad[NS], fbu[NS], fbd[NS];
-        qd.step<NS>(wm1, lut, mask2, fau, fad, fbu, fbd);
-        k_accum<G, NS>(w0, w1, wl, r * NS, fau, fad, fbu, fbd, acc, macc);
+        for (int r = 0; r < kRounds; r++) {
+            uint32_t fau[NS], fad[NS], fbu[NS], fbd[NS];
+            qd.step<NS>(wm1, lut, mask2, fau, fad, fbu, fbd);
+            k_accum<G, NS>(wl, wdn, wq, r * NS, fau, fad, fbu, fbd, acc, macc);
+        }
+    } else {  // fully unrolled: the step number decides at compile time which quad lane holds the weight
+#pragma unroll
+        for (int r = 0; r < kRounds; r++) {
+            uint32_t fau[NS], fad[NS], fbu[NS], fbd[NS];
+            qd.step<NS>(wm1, lut, mask2, fau, fad, fbu, fbd);
+            k_accum<G, NS>(wl, wdn, wq, r * NS, fau, fad, fbu, fbd, acc, macc);
+        }
     }
     if constexpr (kTail > 0) {
         uint32_t fau[kTail], fad[kTail], fbu[kTail], fbd[kTail];
         qd.step<kTail>(wm1, lut, mask2, fau, fad, fbu, fbd);
-        k_accum<G, kTail>(w0, w1, wl, kRounds * NS, fau, fad, fbu, fbd, acc, macc);
+        k_accum<G, kTail>(wl, wdn, wq, kRounds * NS, fau, fad, fbu, fbd, acc, macc);
     }
     if constexpr (G >= kMfmaMinG) {
 #pragma unroll
@@ -377,32 +428,41 @@ __device__ __forceinline__ void v_block(const uint32_t *hdr32, const char *lut, 
         w[g] = p[g] * step;
         st.bv[g] += p[g] * mn;
     }
-    if constexpr (G >= kMfmaMinG) {
 #pragma unroll
-        for (int g = 0; g < G; g++) wts[lane * G + g] = w[g];
+    for (int g = 0; g < G; g++) wts[lane * G + g] = w[g];  // LDS layout [token][head]
 #pragma unroll
-        for (int c = 0; c < 4; c++)
+    for (int c = 0; c < 4; c++)
 #pragma unroll
-            for (int q = 0; q < (G + 3) / 4; q++) macc[c][q] = (v4f){0.f, 0.f, 0.f, 0.f};
-    }
-    const float *wl = wts + (lane & 3 & (G - 1));
+        for (int q = 0; q < (G + 3) / 4; q++) macc[c][q] = (v4f){0.f, 0.f, 0.f, 0.f};
+    const float *wl = G >= kMfmaMinG ? wts + (lane & 3) : wts + (lane & 3) * G;
+    const float *wdn = wts - (lane & 3) * G;
+    float wq[2][G];
     const uint32_t sb = hdr32[kMinMaxBytesV / 4 + lane];
     const uint32_t start = wave_excl_scan((sb & 0xffffu) + (sb >> 16), lane);
     const uint32_t *wm1 = hdr32 + kHdrBytesV / 4 - 1;
-    if constexpr (G >= kMfmaMinG) wave_sync();
+    wave_sync();
     Quad qd;
     qd.open(wm1, start, sb & 0xffffu, sb >> 16);
     constexpr int kRounds = kHalf / NS, kTail = kHalf - kRounds * NS;
+    if constexpr (G >= kMfmaMinG) {
 #pragma unroll 2
-    for (int r = 0; r < kRounds; r++) {
-        uint32_t fau[NS], fad[NS], fbu[NS], fbd[NS];
-        qd.step<NS>(wm1, lut, mask2, fau, fad, fbu, fbd);
-        v_accum<G, NS>(w, wl, r * NS, fau, fad, fbu, fbd, st.acc, macc);
+        for (int r = 0; r < kRounds; r++) {
+            uint32_t fau[NS], fad[NS], fbu[NS], fbd[NS];
+            qd.step<NS>(wm1, lut, mask2, fau, fad, fbu, fbd);
+            v_accum<G, NS>(wl, wdn, wq, r * NS, fau, fad, fbu, fbd, st.acc, macc);
+        }
+    } else {
+#pragma unroll
+        for (int r = 0; r < kRounds; r++) {
+            uint32_t fau[NS], fad[NS], fbu[NS], fbd[NS];
+            qd.step<NS>(wm1, lut, mask2, fau, fad, fbu, fbd);
+            v_accum<G, NS>(wl, wdn, wq, r * NS, fau, fad, fbu, fbd, st.acc, macc);
+        }
     }
     if constexpr (kTail > 0) {
         uint32_t fau[kTail], fad[kTail], fbu[kTail], fbd[kTail];
         qd.step<kTail>(wm1, lut, mask2, fau, fad, fbu, fbd);
-        v_accum<G, kTail>(w, wl, kRounds * NS, fau, fad, fbu, fbd, st.acc, macc);
+        v_accum<G, kTail>(wl, wdn, wq, kRounds * NS, fau, fad, fbu, fbd, st.acc, macc);
     }
     if constexpr (G >= kMfmaMinG) {
 #pragma unroll
@@ -488,10 +548,10 @@ __global__ __launch_bounds__(kThreads, WavesPerSimd<G>::value) void fused_attn_k
     constexpr int NS = kWindowBits / LB;
     __shared__ __attribute__((aligned(16))) uint16_t lut_s[2][1 << LB];
     __shared__ __attribute__((aligned(16))) float qf[G * kD];
-    extern __shared__ __attribute__((aligned(16))) uint8_t smem[];  // per wave: staging area; groups >= 4: + weights
+    extern __shared__ __attribute__((aligned(16))) uint8_t smem[];  // per wave: staging area + weights
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     uint8_t *stage = smem + (size_t)wave * a.stage_bytes;
-    float *wts = reinterpret_cast<float *>(smem + (size_t)kWaves * a.stage_bytes) + (G >= kMfmaMinG ? wave * G * kD : 0);
+    float *wts = reinterpret_cast<float *>(smem + (size_t)kWaves * a.stage_bytes) + wave * G * kD;
     const char *lutK = reinterpret_cast<const char *>(&lut_s[0][0]);
     const char *lutV = reinterpret_cast<const char *>(&lut_s[1][0]);
 
@@ -737,7 +797,7 @@ hipError_t launch_fused_attn(const Geo &g, const uint16_t *q, float scale, float
     if (longest < 1 || longest > kLutBits) return hipErrorInvalidValue;
     a.mask2[0] = ((1u << bits_k) - 1u) << kJunkBits;
     a.mask2[1] = ((1u << bits_v) - 1u) << kJunkBits;
-    const size_t lds = (size_t)kWaves * stage_bytes + (g.G >= kMfmaMinG ? (size_t)kWaves * g.G * kD * 4 : 0);
+    const size_t lds = (size_t)kWaves * stage_bytes + (size_t)kWaves * g.G * kD * 4;
     switch (g.G) {
         case 1: return launch_fused_g<1>(a, longest, lds, ev0, ev1, s);
         case 2: return launch_fused_g<2>(a, longest, lds, ev0, ev1, s);

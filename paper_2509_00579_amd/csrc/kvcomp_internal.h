@@ -78,9 +78,9 @@ constexpr int fused_table_bits(int longest) {
 }
 constexpr int kLdsBytesPerCU = 160 * 1024;
 // LDS of one fused-kernel workgroup apart from the per-wave staging areas: two decode tables of 16-bit entries, the
-// query rows, and (groups of 4 and 8 heads) the per-wave weight areas of the MFMA accumulation.
+// query rows and the per-wave weight areas.
 constexpr size_t fused_lds_fixed(int G, int longest) {
-    return ((size_t)4 << fused_table_bits(longest)) + (size_t)G * kD * 4 + (G >= 4 ? (size_t)4 * G * kD * 4 : 0) + 512;
+    return ((size_t)4 << fused_table_bits(longest)) + (size_t)G * kD * 4 + (size_t)4 * G * kD * 4 + 512;
 }
 
 // ---- launches implemented in the .hip files ----
