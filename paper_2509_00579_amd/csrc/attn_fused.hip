@@ -549,7 +549,9 @@ __global__ __launch_bounds__(kThreads, WavesPerSimd<G>::value) void fused_attn_k
     __shared__ __attribute__((aligned(16))) uint16_t lut_s[2][1 << LB];
     __shared__ __attribute__((aligned(16))) float qf[G * kD];
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];  // per wave: staging area + weights
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    // the wave number and everything derived from it (block numbers, table entries, record addresses) are scalars
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     uint8_t *stage = smem + (size_t)wave * a.stage_bytes;
     float *wts = reinterpret_cast<float *>(smem + (size_t)kWaves * a.stage_bytes) + wave * G * kD;
     const char *lutK = reinterpret_cast<const char *>(&lut_s[0][0]);
@@ -612,6 +614,12 @@ __global__ __launch_bounds__(kThreads, WavesPerSimd<G>::value) void fused_attn_k
         const bool k_staged = eK.size16 <= stage16, v_staged = eV.size16 <= stage16;
         const uint8_t *recK = g.payload + (size_t)eK.off16 * 16, *recV = g.payload + (size_t)eV.off16 * 16;
         if (v_staged) pf.issue(recV, eV.size16, lane);  // V record travels while K is decoded
+        const int jn = j + kWaves;  // the next pair's Block Offsets Array entries travel with it
+        BlockEntry eKn = {0, 0}, eVn = {0, 0};
+        if (jn < j1) {
+            eKn = tabK[jn];
+            eVn = tabV[jn];
+        }
         if (k_staged) {
             k_block<G, NS>(stage32, lutK, a.mask2[0], wts, qreg, g.two_eb[0], a.scale, lane, score);
         } else {  // larger than the staging area: decode from global memory (copies keep the hot state in registers)
@@ -631,13 +639,11 @@ __global__ __launch_bounds__(kThreads, WavesPerSimd<G>::value) void fused_attn_k
         wave_sync();  // every lane is done with the K record
         if (v_staged) pf.commit(stage4, lane);
         wave_sync();
-        const int jn = j + kWaves;
-        BlockEntry eKn = {0, 0}, eVn = {0, 0};
-        if (jn < j1) {
-            eKn = tabK[jn];
-            eVn = tabV[jn];
-            if (eKn.size16 <= stage16) pf.issue(g.payload + (size_t)eKn.off16 * 16, eKn.size16, lane);
-        }
+        eKn.off16 = __builtin_amdgcn_readfirstlane(eKn.off16);
+        eKn.size16 = __builtin_amdgcn_readfirstlane(eKn.size16);
+        eVn.off16 = __builtin_amdgcn_readfirstlane(eVn.off16);
+        eVn.size16 = __builtin_amdgcn_readfirstlane(eVn.size16);
+        if (jn < j1 && eKn.size16 <= stage16) pf.issue(g.payload + (size_t)eKn.off16 * 16, eKn.size16, lane);
         if (v_staged) {
             v_block<G, NS>(stage32, lutV, a.mask2[1], wts, p, g.two_eb[1], lane, st);
         } else {
