@@ -1,7 +1,8 @@
 // The uncompressed comparison kernel (Section 4.3 compares the fused kernel with a plain fp16 matrix-vector
 // product): decode attention on the fp16 cache [B, S, H, 128], sequence split over workgroups with an online
-// softmax, merged by the same combine kernel as the fused path.  HBM-bound: every K and V byte is read once with
-// 16-byte loads, four 256-byte rows per wave instruction.
+// softmax, merged inside the kernel like the fused path.  HBM-bound: every K and V byte is read once with 16-byte
+// loads.  Groups of 1 and 2 query heads form the scores on the vector ALU; groups of 4 and 8 (one K row serves
+// several heads, a small matrix product) on the matrix cores.
 #include <hip/hip_fp16.h>
 
 #include "kvcomp_internal.h"
@@ -19,6 +20,37 @@ __device__ __forceinline__ void unpack8(const uint4 &v, float (&x)[8]) {
 }
 
 constexpr int kBWaves = 4;
+
+// The waves of a workgroup have left (o[128], m, l) per query head in comb: merge them into the workgroup's partial
+// and, in the last workgroup of the (batch, kv head), the splits into the output.
+template <int G>
+__device__ __forceinline__ void merge_waves_and_splits(const float (&comb)[kBWaves][G][kPartialStride],
+                                                       float *__restrict__ partials, uint32_t *__restrict__ counters,
+                                                       float *__restrict__ out, int b, int h, int Hq, int split, int bh,
+                                                       int tid) {
+    for (int i = tid; i < G * kD; i += 64 * kBWaves) {
+        const int g = i / kD, c = i - g * kD;
+        float M = -INFINITY;
+        for (int w = 0; w < kBWaves; w++) M = fmaxf(M, comb[w][g][kD]);
+        float L = 0.f, O = 0.f;
+        for (int w = 0; w < kBWaves; w++) {
+            const float mw = comb[w][g][kD];
+            const float f = mw == -INFINITY ? 0.f : __expf(mw - M);
+            L += comb[w][g][kD + 1] * f;
+            O += comb[w][g][c] * f;
+        }
+        if (gridDim.x == 1) {
+            out[((size_t)b * Hq + (size_t)h * G + g) * kD + c] = O / L;
+        } else {
+            float *dst = partials + (((size_t)b * Hq + (size_t)h * G + g) * kMaxSplits + split) * kPartialStride;
+            store_agent(dst + c, O);
+            if (c == 0) { store_agent(dst + kD, M); store_agent(dst + kD + 1, L); }
+        }
+    }
+    if (gridDim.x > 1)
+        finish_splits<G, 64 * kBWaves>(partials, counters + bh, b * Hq + h * G, (int)gridDim.x, out, tid);
+}
+
 
 // Lane l of a wave owns channels 8*(l%16)..+7 and the tokens 4*i + l/16 (i = 0..15) of a 64-token tile.
 template <int G>
@@ -128,27 +160,161 @@ __global__ __launch_bounds__(64 * kBWaves) void baseline_attn_kernel(int B, int 
         }
     }
     __syncthreads();
-    for (int i = tid; i < G * kD; i += 64 * kBWaves) {
-        const int g = i / kD, c = i - g * kD;
-        float M = -INFINITY;
-        for (int w = 0; w < kBWaves; w++) M = fmaxf(M, comb[w][g][kD]);
-        float L = 0.f, O = 0.f;
-        for (int w = 0; w < kBWaves; w++) {
-            const float mw = comb[w][g][kD];
-            const float f = mw == -INFINITY ? 0.f : __expf(mw - M);
-            L += comb[w][g][kD + 1] * f;
-            O += comb[w][g][c] * f;
+    merge_waves_and_splits<G>(comb, partials, counters, out, b, h, Hq, split, bh, tid);
+}
+
+// ---- groups of 4 and 8 query heads --------------------------------------------------------------------------------
+// Scores of 16 tokens x (up to 16) heads per v_mfma_f32_16x16x16_f16: S^T = K Q^T, A = K tile, B = Q^T.
+//   A: lane l holds row (token) l % 16, reduction slots 4 * (l / 16) .. + 3
+//   B: lane l holds column (head) l % 16, the same slots;  D: lane l holds column l % 16, rows 4 * (l / 16) .. + 3
+// Which channel a reduction slot stands for is free as long as A and B agree: step (i, hh) maps slot (l / 16, r) to
+// channel 8 * (l / 16 + 4 i) + 4 hh + r, so that a lane's A operands for two steps are one 16-byte load of its K row.
+// The P V product stays on the vector ALU (lane = 8 channels x one token in four, as in the kernel above); the
+// softmax numerators reach it through LDS.
+typedef _Float16 half4_t __attribute__((ext_vector_type(4)));
+typedef float float4_t __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ half4_t as_half4(uint32_t lo, uint32_t hi) {
+    const uint2 v = make_uint2(lo, hi);
+    return __builtin_bit_cast(half4_t, v);
+}
+__device__ __forceinline__ void wave_lds_sync() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+template <int G>
+__global__ __launch_bounds__(64 * kBWaves, 3) void baseline_attn_gqa_kernel(
+    int B, int H, int Hq, const uint16_t *__restrict__ K, const uint16_t *__restrict__ V, int seq,
+    const uint16_t *__restrict__ q, float scale, float *__restrict__ partials, uint32_t *__restrict__ counters,
+    float *__restrict__ out, int tokens_per_split) {
+    static_assert(G == 4 || G == 8, "group size");
+    __shared__ float comb[kBWaves][G][kPartialStride];
+    __shared__ __attribute__((aligned(16))) float p_s[kBWaves][64][G];  // numerators of the wave's current tokens
+    __shared__ float alpha_s[kBWaves][G];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int split = blockIdx.x, bh = blockIdx.y, b = bh / H, h = bh - b * H;
+    const int j = lane & 15, gq = lane >> 4;  // matrix column / row group;  V phase: channels 8 j .. + 7, tokens 4 i + gq
+    const int cc = j * 8;
+    half4_t qb[4][2];
+#pragma unroll
+    for (int i = 0; i < 4; i++) {
+        uint4 v = make_uint4(0, 0, 0, 0);
+        if (j < G) v = *reinterpret_cast<const uint4 *>(q + ((size_t)b * Hq + (size_t)h * G + j) * kD + 8 * (gq + 4 * i));
+        qb[i][0] = as_half4(v.x, v.y);
+        qb[i][1] = as_half4(v.z, v.w);
+    }
+    float m = -INFINITY, lsum = 0.f;  // running maximum and sum of head j (lanes with j >= G idle along)
+    float acc[G][8];
+#pragma unroll
+    for (int g = 0; g < G; g++)
+#pragma unroll
+        for (int k = 0; k < 8; k++) acc[g][k] = 0.f;
+    const int t_begin = split * tokens_per_split;
+    const int t_end = min(t_begin + tokens_per_split, seq);
+    const size_t row = (size_t)H * kD;
+    const uint16_t *Kb = K + ((size_t)b * seq * H + h) * kD + 8 * gq;
+    const uint16_t *Vb = V + ((size_t)b * seq * H + h) * kD + cc;
+
+    for (int t0 = t_begin + wave * 64; t0 < t_end; t0 += 64 * kBWaves) {
+        uint4 kv[16];
+#pragma unroll
+        for (int tt = 0; tt < 4; tt++) {
+            const int t = t0 + 16 * tt + j;
+#pragma unroll
+            for (int i = 0; i < 4; i++)
+                kv[tt * 4 + i] = t < t_end ? *reinterpret_cast<const uint4 *>(Kb + (size_t)t * row + 32 * i)
+                                           : make_uint4(0, 0, 0, 0);
         }
-        if (gridDim.x == 1) {
-            out[((size_t)b * Hq + (size_t)h * G + g) * kD + c] = O / L;
-        } else {
-            float *dst = partials + (((size_t)b * Hq + (size_t)h * G + g) * kMaxSplits + split) * kPartialStride;
-            store_agent(dst + c, O);
-            if (c == 0) { store_agent(dst + kD, M); store_agent(dst + kD + 1, L); }
+        float s[16];
+        float ml = -INFINITY;
+#pragma unroll
+        for (int tt = 0; tt < 4; tt++) {
+            float4_t d = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int i = 0; i < 4; i++) {
+                const uint4 &v = kv[tt * 4 + i];
+                d = __builtin_amdgcn_mfma_f32_16x16x16f16(as_half4(v.x, v.y), qb[i][0], d, 0, 0, 0);
+                d = __builtin_amdgcn_mfma_f32_16x16x16f16(as_half4(v.z, v.w), qb[i][1], d, 0, 0, 0);
+            }
+            const float dd[4] = {d.x, d.y, d.z, d.w};
+#pragma unroll
+            for (int r = 0; r < 4; r++) {  // token t0 + 16 tt + 4 gq + r, head j
+                s[tt * 4 + r] = t0 + 16 * tt + 4 * gq + r < t_end ? scale * dd[r] : -INFINITY;
+                ml = fmaxf(ml, s[tt * 4 + r]);
+            }
+        }
+        ml = fmaxf(ml, __shfl_xor(ml, 16));
+        ml = fmaxf(ml, __shfl_xor(ml, 32));
+        const float mnew = fmaxf(m, ml);  // finite: the tile holds at least one token
+        const float alpha = __expf(m - mnew);
+        m = mnew;
+        float ps = 0.f;
+#pragma unroll
+        for (int tt = 0; tt < 4; tt++)
+#pragma unroll
+            for (int r = 0; r < 4; r++) {
+                const float pv = __expf(s[tt * 4 + r] - mnew);
+                ps += pv;
+                if (j < G) p_s[wave][16 * tt + 4 * gq + r][j] = pv;
+            }
+        lsum = lsum * alpha + ps;
+        if (gq == 0 && j < G) alpha_s[wave][j] = alpha;
+        wave_lds_sync();
+#pragma unroll
+        for (int g = 0; g < G; g++) {
+            const float al = alpha_s[wave][g];
+#pragma unroll
+            for (int k = 0; k < 8; k++) acc[g][k] *= al;
+        }
+        constexpr int kChunk = G == 8 ? 8 : 16;  // V rows in flight per lane (register budget)
+#pragma unroll 1
+        for (int i0 = 0; i0 < 16; i0 += kChunk) {
+            uint4 vv[kChunk];
+#pragma unroll
+            for (int i = 0; i < kChunk; i++) {
+                const int t = t0 + 4 * (i0 + i) + gq;
+                vv[i] = t < t_end ? *reinterpret_cast<const uint4 *>(Vb + (size_t)t * row) : make_uint4(0, 0, 0, 0);
+            }
+#pragma unroll
+            for (int i = 0; i < kChunk; i++) {
+                float x[8];
+                unpack8(vv[i], x);
+                float pg[G];
+#pragma unroll
+                for (int g4 = 0; g4 < G; g4 += 4) {
+                    const float4 t4 = *reinterpret_cast<const float4 *>(&p_s[wave][4 * (i0 + i) + gq][g4]);
+                    pg[g4] = t4.x; pg[g4 + 1] = t4.y; pg[g4 + 2] = t4.z; pg[g4 + 3] = t4.w;
+                }
+#pragma unroll
+                for (int g = 0; g < G; g++)
+#pragma unroll
+                    for (int k = 0; k < 8; k++) acc[g][k] = fmaf(pg[g], x[k], acc[g][k]);
+            }
+        }
+        wave_lds_sync();  // the next tile overwrites p_s
+    }
+    lsum += __shfl_xor(lsum, 16);
+    lsum += __shfl_xor(lsum, 32);
+    if (gq == 0 && j < G) {
+        comb[wave][j][kD] = m;
+        comb[wave][j][kD + 1] = lsum;
+    }
+#pragma unroll
+    for (int g = 0; g < G; g++) {
+#pragma unroll
+        for (int k = 0; k < 8; k++) {
+            acc[g][k] += __shfl_xor(acc[g][k], 16);
+            acc[g][k] += __shfl_xor(acc[g][k], 32);
+        }
+        if (gq == 0) {
+#pragma unroll
+            for (int k = 0; k < 8; k++) comb[wave][g][cc + k] = acc[g][k];
         }
     }
-    if (gridDim.x > 1)
-        finish_splits<G, 64 * kBWaves>(partials, counters + bh, b * Hq + h * G, (int)gridDim.x, out, tid);
+    __syncthreads();
+    merge_waves_and_splits<G>(comb, partials, counters, out, b, h, Hq, split, bh, tid);
 }
 
 hipError_t launch_baseline_attn(int B, int H, int Hq, const uint16_t *K, const uint16_t *V, int seq, const uint16_t *q,
@@ -162,8 +328,8 @@ hipError_t launch_baseline_attn(int B, int H, int Hq, const uint16_t *K, const u
     switch (G) {
         case 1: hipLaunchKernelGGL(baseline_attn_kernel<1>, grid, block, 0, s, B, H, Hq, K, V, seq, q, scale, partials, counters, out, tps); break;
         case 2: hipLaunchKernelGGL(baseline_attn_kernel<2>, grid, block, 0, s, B, H, Hq, K, V, seq, q, scale, partials, counters, out, tps); break;
-        case 4: hipLaunchKernelGGL(baseline_attn_kernel<4>, grid, block, 0, s, B, H, Hq, K, V, seq, q, scale, partials, counters, out, tps); break;
-        case 8: hipLaunchKernelGGL(baseline_attn_kernel<8>, grid, block, 0, s, B, H, Hq, K, V, seq, q, scale, partials, counters, out, tps); break;
+        case 4: hipLaunchKernelGGL(baseline_attn_gqa_kernel<4>, grid, block, 0, s, B, H, Hq, K, V, seq, q, scale, partials, counters, out, tps); break;
+        case 8: hipLaunchKernelGGL(baseline_attn_gqa_kernel<8>, grid, block, 0, s, B, H, Hq, K, V, seq, q, scale, partials, counters, out, tps); break;
         default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
