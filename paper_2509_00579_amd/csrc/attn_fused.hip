@@ -39,25 +39,47 @@ __device__ __forceinline__ float bcast(float v, int lane_idx) {
     return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), lane_idx));
 }
 
+// Wave-wide reductions and the prefix sum run on DPP row operations and v_readlane, not on ds_bpermute: the LDS pipe
+// is the busiest unit of this kernel and a butterfly of six dependent LDS round trips costs far more latency.
+template <int CTRL>
+__device__ __forceinline__ float dpp_f(float v) {  // lanes without a source read 0
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xf, 0xf, true));
+}
+template <int CTRL>
+__device__ __forceinline__ uint32_t dpp_u(uint32_t v) {
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, 0xf, 0xf, true);
+}
+constexpr int kDppXor1 = 0xB1, kDppXor2 = 0x4E;              // quad_perm [1,0,3,2] and [2,3,0,1]
+constexpr int kDppHalfMirror = 0x141, kDppMirror = 0x140;    // lane i <-> 7 - i (within 8) and i <-> 15 - i (within 16)
+constexpr int kDppRowShr = 0x110;                            // + n: lane i reads lane i - n of its row of 16
+
+// the same value in every lane
 __device__ __forceinline__ float wave_sum(float v) {
-#pragma unroll
-    for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m);
-    return v;
+    v += dpp_f<kDppXor1>(v);
+    v += dpp_f<kDppXor2>(v);
+    v += dpp_f<kDppHalfMirror>(v);
+    v += dpp_f<kDppMirror>(v);  // every lane: sum of its row of 16
+    return (bcast(v, 0) + bcast(v, 16)) + (bcast(v, 32) + bcast(v, 48));
 }
 __device__ __forceinline__ float wave_max(float v) {
-#pragma unroll
-    for (int m = 32; m >= 1; m >>= 1) v = fmaxf(v, __shfl_xor(v, m));
-    return v;
+    v = fmaxf(v, dpp_f<kDppXor1>(v));
+    v = fmaxf(v, dpp_f<kDppXor2>(v));
+    v = fmaxf(v, dpp_f<kDppHalfMirror>(v));
+    v = fmaxf(v, dpp_f<kDppMirror>(v));
+    return fmaxf(fmaxf(bcast(v, 0), bcast(v, 16)), fmaxf(bcast(v, 32), bcast(v, 48)));
 }
 // exclusive prefix sum over the 64 lanes
 __device__ __forceinline__ uint32_t wave_excl_scan(uint32_t v, int lane) {
     uint32_t inc = v;
-#pragma unroll
-    for (int d = 1; d < 64; d <<= 1) {
-        const uint32_t o = __shfl_up(inc, d);
-        if (lane >= d) inc += o;
-    }
-    return inc - v;
+    inc += dpp_u<kDppRowShr + 1>(inc);
+    inc += dpp_u<kDppRowShr + 2>(inc);
+    inc += dpp_u<kDppRowShr + 4>(inc);
+    inc += dpp_u<kDppRowShr + 8>(inc);  // inclusive within each row of 16
+    const uint32_t t0 = __builtin_amdgcn_readlane(inc, 15), t1 = __builtin_amdgcn_readlane(inc, 31),
+                   t2 = __builtin_amdgcn_readlane(inc, 47);
+    const int row = lane >> 4;
+    const uint32_t before = row == 0 ? 0u : row == 1 ? t0 : row == 2 ? t0 + t1 : t0 + t1 + t2;
+    return inc + before - v;
 }
 
 // A slice holds two decode chains (see the record layout): symbols 0..31 are read upwards from the slice start,
