@@ -400,20 +400,13 @@ __device__ __forceinline__ void k_block(const uint32_t *hdr32, const char *lut, 
     Quad qd;
     qd.open(wm1, start, sb & 0xffffu, sb >> 16);
     constexpr int kRounds = kHalf / NS, kTail = kHalf - kRounds * NS;
-    if constexpr (G >= kMfmaMinG) {
-#pragma unroll 2
-        for (int r = 0; r < kRounds; r++) {
-            uint32_t fau[NS], fad[NS], fbu[NS], fbd[NS];
-            qd.step<NS>(wm1, lut, mask2, fau, fad, fbu, fbd);
-            k_accum<G, NS>(wl, wdn, wq, r * NS, fau, fad, fbu, fbd, acc, macc);
-        }
-    } else {  // fully unrolled: the step number decides at compile time which quad lane holds the weight
+    // fully unrolled: the step number decides at compile time which quad lane holds the weight, and the scheduler
+    // may overlap the table lookups of one round with the accumulation of the previous one
 #pragma unroll
-        for (int r = 0; r < kRounds; r++) {
-            uint32_t fau[NS], fad[NS], fbu[NS], fbd[NS];
-            qd.step<NS>(wm1, lut, mask2, fau, fad, fbu, fbd);
-            k_accum<G, NS>(wl, wdn, wq, r * NS, fau, fad, fbu, fbd, acc, macc);
-        }
+    for (int r = 0; r < kRounds; r++) {
+        uint32_t fau[NS], fad[NS], fbu[NS], fbd[NS];
+        qd.step<NS>(wm1, lut, mask2, fau, fad, fbu, fbd);
+        k_accum<G, NS>(wl, wdn, wq, r * NS, fau, fad, fbu, fbd, acc, macc);
     }
     if constexpr (kTail > 0) {
         uint32_t fau[kTail], fad[kTail], fbu[kTail], fbd[kTail];
@@ -466,20 +459,11 @@ __device__ __forceinline__ void v_block(const uint32_t *hdr32, const char *lut, 
     Quad qd;
     qd.open(wm1, start, sb & 0xffffu, sb >> 16);
     constexpr int kRounds = kHalf / NS, kTail = kHalf - kRounds * NS;
-    if constexpr (G >= kMfmaMinG) {
-#pragma unroll 2
-        for (int r = 0; r < kRounds; r++) {
-            uint32_t fau[NS], fad[NS], fbu[NS], fbd[NS];
-            qd.step<NS>(wm1, lut, mask2, fau, fad, fbu, fbd);
-            v_accum<G, NS>(wl, wdn, wq, r * NS, fau, fad, fbu, fbd, st.acc, macc);
-        }
-    } else {
 #pragma unroll
-        for (int r = 0; r < kRounds; r++) {
-            uint32_t fau[NS], fad[NS], fbu[NS], fbd[NS];
-            qd.step<NS>(wm1, lut, mask2, fau, fad, fbu, fbd);
-            v_accum<G, NS>(wl, wdn, wq, r * NS, fau, fad, fbu, fbd, st.acc, macc);
-        }
+    for (int r = 0; r < kRounds; r++) {
+        uint32_t fau[NS], fad[NS], fbu[NS], fbd[NS];
+        qd.step<NS>(wm1, lut, mask2, fau, fad, fbu, fbd);
+        v_accum<G, NS>(wl, wdn, wq, r * NS, fau, fad, fbu, fbd, st.acc, macc);
     }
     if constexpr (kTail > 0) {
         uint32_t fau[kTail], fad[kTail], fbu[kTail], fbd[kTail];
