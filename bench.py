@@ -21,11 +21,16 @@ import time
 import numpy as np
 
 HBM_PEAK_GBPS = 8000.0  # MI355X HBM3E, published
-VALU_ISSUE_PER_S = 256 * 4 * 2.4e9 / 4  # wave64 VALU instructions per second: 256 CUs x 4 SIMDs, 4 cycles each
-VALU_INSTR_PER_SYMBOL = 9.1  # rocprofv3 SQ_INSTS_VALU / decoded wave-symbols (profiles/fused_attn_kernel_c1.md)
+# wave64 VALU instructions per second: the published 157.3 TFLOP/s of fp32 vector FMA = 256 CUs x 4 SIMDs x 2.4 GHz
+# x 32 lanes x 2 flops, i.e. one wave64 instruction per SIMD every 2 cycles
+VALU_ISSUE_PER_S = 157.3e12 / 2 / 64
+VALU_INSTR_PER_SYMBOL = 7.26  # rocprofv3 SQ_INSTS_VALU / decoded wave-symbols (profiles/fused_attn_kernel_c1.md)
+# share of the busy cycles in which the LDS pipe is active, the busiest unit of the fused kernel (rocprofv3
+# SQ_LDS_IDX_ACTIVE / SQ_BUSY_CU_CYCLES, profiles/): keyed like MEASURED_TRAFFIC
+MEASURED_LDS_BUSY = {("c1", 1e-2, 7): 0.38, ("c2", 1e-2, 7): 0.76}
 # HBM bytes per fused-kernel launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by a copy of known size
 # (profiles/); keyed by (workload, rel_eb, max code word); None where not measured.
-MEASURED_TRAFFIC = {("c1", 1e-2, 12): 26.82e6}  # bytes per launch, profiles/fused_attn_kernel_c1.md
+MEASURED_TRAFFIC = {("c1", 1e-2, 7): 31.56e6}  # bytes per launch, profiles/fused_attn_kernel_c1.md
 
 
 def parse_args():
@@ -270,19 +275,22 @@ def main():
         "store_GBps_fp16_in": (2 * B * H * S * 128 * 2) / (float(np.mean(store_ms)) * 1e-3) / 1e9,
         "fp16_baseline": {"ms": base_ms, "GBps": base_bytes / (base_ms * 1e-3) / 1e9,
                           "pct_hbm_peak": 100.0 * base_bytes / (base_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,
-                          "fused_speedup": base_ms / (dec_ms / T)},
+                          "fused_kernel_speedup": base_ms / kern_ms,  # kernel against kernel, both HIP-event timed
+                          "fused_step_speedup": base_ms / (dec_ms / T)},  # the fused side also appends a token
         "roofline": {"bound": "hbm", "kernel": "fused_attn_kernel", "achieved": achieved, "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
                      "traffic": MEASURED_TRAFFIC.get((args.workload, rel_eb, args.max_code_len)),
                      "bytes_per_launch": kern_bytes, "avg_launch_ms": kern_ms, "launches_timed": launches,
                      "timing": "HIP events around every fused-kernel launch on the launch stream, one eager pass of "
                                "the step right after the timed region (the timed region replays a HIP graph)"},
-        # The kernel is bound by VALU issue, not by HBM: symbols decoded per second against
-        # what the chip can issue at the measured instruction count per symbol.
+        # The kernel is not bound by HBM: per decoded symbol it spends one LDS table lookup and about seven VALU
+        # instructions.  Symbols decoded per second against what the vector ALUs could issue at the measured
+        # instruction count per symbol, and the measured share of cycles with the LDS pipe busy.
         "roofline_alu": {"bound": "alu", "achieved": symbols_per_launch / (kern_ms * 1e-3) / 1e12,
                          "peak": VALU_ISSUE_PER_S * 64 / VALU_INSTR_PER_SYMBOL / 1e12, "unit": "Tsymbol/s",
                          "frac": symbols_per_launch / (kern_ms * 1e-3) / (VALU_ISSUE_PER_S * 64 / VALU_INSTR_PER_SYMBOL),
-                         "valu_instr_per_symbol": VALU_INSTR_PER_SYMBOL},
+                         "valu_instr_per_symbol": VALU_INSTR_PER_SYMBOL,
+                         "lds_busy_frac": MEASURED_LDS_BUSY.get((args.workload, rel_eb, args.max_code_len))},
         "cpu_baseline": cpu,
     }
     print(json.dumps(result))

@@ -784,7 +784,6 @@ template <int G>
 static hipError_t launch_fused_g(const FusedArgs &a, int longest, size_t lds, hipEvent_t ev0, hipEvent_t ev1,
                                  hipStream_t s) {
     switch (fused_table_bits(longest)) {
-        case 6: return launch_fused_gn<G, 6>(a, lds, ev0, ev1, s);
         case 7: return launch_fused_gn<G, 7>(a, lds, ev0, ev1, s);
         case 8: return launch_fused_gn<G, 8>(a, lds, ev0, ev1, s);
         case 10: return launch_fused_gn<G, 10>(a, lds, ev0, ev1, s);

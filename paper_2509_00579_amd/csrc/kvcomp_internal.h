@@ -74,7 +74,8 @@ constexpr int kCUs = 256;  // compute units of the MI355X
 constexpr int fused_wgs_per_cu(int G) { return G >= 8 ? 2 : G >= 4 ? 3 : 4; }
 // Index width the fused kernel's LDS decode tables are compiled for, given the longest code word in use.
 constexpr int fused_table_bits(int longest) {
-    return longest <= 6 ? 6 : longest <= 7 ? 7 : longest <= 8 ? 8 : longest <= 10 ? 10 : 12;
+    // (a 6-bit variant with five symbols per window was measured slower: its 20 live table entries spill registers)
+    return longest <= 7 ? 7 : longest <= 8 ? 8 : longest <= 10 ? 10 : 12;
 }
 constexpr int kLdsBytesPerCU = 160 * 1024;
 // LDS of one fused-kernel workgroup apart from the per-wave staging areas: two decode tables of 16-bit entries, the

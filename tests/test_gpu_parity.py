@@ -266,7 +266,7 @@ def test_config1_full_size_sampled(gpu, oracle):
 
 @pytest.mark.parametrize("max_len,rel", [(6, 1e-2), (7, 1e-2), (7, 5e-3), (8, 5e-3), (10, 1e-2), (12, 1e-2)])
 def test_code_length_limits_select_every_decoder_variant(gpu, oracle, max_len, rel):
-    """Shorter maximum code words: more symbols per decode window (5, 4, 3, 3, 2 for limits 6, 7, 8, 10, 12)."""
+    """Shorter maximum code words: more symbols per decode window (4, 4, 3, 3, 2 for limits 6, 7, 8, 10, 12)."""
     _say(f"max_code_len={max_len} rel={rel}")
     B, H, Hq, S = 1, 2, 4, 330
     Kx, Vx = W.make_kv(B, H, S, 31)
