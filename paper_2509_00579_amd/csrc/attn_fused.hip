@@ -248,14 +248,21 @@ struct Soft {
 };
 
 // ---- accumulation of one round of decoded symbols -----------------------------------------------------------------
-// The folded weight of the current symbol is wave-uniform.  Query-head groups of 1 and 2: every fourth step, lane i
-// of each quad of lanes fetches the weight of step s + i from LDS (four addresses, no bank conflict); the FMA of
-// step s + i then takes it through a quad broadcast.  No instruction is spent on the broadcast itself.
-// Groups of 4 and 8 (GQA): a decode step is a small matrix product -- (heads x 1) weights times (1 x lanes) decoded
-// symbols -- which is what v_mfma_f32_4x4x1f32 computes for each group of four lanes: lane i of a group supplies the
-// weight of head i (read from LDS, layout [symbol index][head]) and its own decoded symbol, and receives the four
-// heads' products for its own token / channel.  One MFMA replaces four broadcasts and four FMAs.
+// The folded weight of the current symbol is wave-uniform.
+//
+// Query-head groups of 1 and 2: every fourth step, lane i of each quad of lanes fetches the weight of step s + i from
+// LDS (four addresses, no bank conflict); the FMA of step s + i then takes it through a quad broadcast.  No
+// instruction is spent on the broadcast itself.
+//
+// Groups of 4 and 8 (GQA): the update of one chain over the symbols of a round is a small matrix product,
+// (heads x symbols of the round) weights times (symbols of the round x lanes) decoded symbols, which is what
+// v_mfma_f32_4x4x4f16 computes for each quad of lanes: lane i of a quad supplies the weights of head i for the (up to
+// four) symbols of the round, and its own decoded symbols (fp16 holds 0..255 exactly), and receives the four heads'
+// sums for its own token / channel.  The weights are fp32 numbers split into two fp16 parts, w ~ hi + lo (22 bits
+// after a per-block power-of-two scaling that keeps them inside the fp16 range), one MFMA each: two MFMAs per
+// chain, round and four heads instead of one FMA per symbol and head.
 typedef float v4f __attribute__((ext_vector_type(4)));
+typedef _Float16 v4h __attribute__((ext_vector_type(4)));
 #ifndef KVC_MFMA_MIN_G
 #define KVC_MFMA_MIN_G 4
 #endif
@@ -283,88 +290,103 @@ __device__ __forceinline__ float fma_quad(float w, int q, uint32_t e, float acc)
     }
 }
 
-__device__ __forceinline__ v4f mfma4(float a, float b, v4f c) { return __builtin_amdgcn_mfma_f32_4x4x1f32(a, b, c, 0, 0, 0); }
-
-// K: symbol index `up` of chain au/bu is channel up / 64+up, index `dn` of chain ad/bd is channel dn / 64+dn.
+// K, groups of 1 and 2: symbol index `up` of chain au/bu is channel up / 64+up, index `dn` of chain ad/bd is channel
+// dn / 64+dn.  wl = weights + (lane & 3) * G, wdn = weights - (lane & 3) * G, weights laid out [channel][head].
 template <int G, int CNT>
 __device__ __forceinline__ void k_accum(const float *wl, const float *wdn, float (&wq)[4][G], int first,
                                         const uint32_t (&fau)[CNT], const uint32_t (&fad)[CNT],
-                                        const uint32_t (&fbu)[CNT], const uint32_t (&fbd)[CNT], float (&acc)[G],
-                                        v4f (&macc)[4][(G + 3) / 4]) {
+                                        const uint32_t (&fbu)[CNT], const uint32_t (&fbd)[CNT], float (&acc)[G]) {
 #pragma unroll
     for (int k = 0; k < CNT; k++) {
         const int up = first + k, dn = kSliceLen - 1 - up;  // symbol index inside the slice
-        if constexpr (G >= kMfmaMinG) {
-#pragma unroll
-            for (int q = 0; q < (G + 3) / 4; q++) {
-                macc[0][q] = mfma4(wl[up * G + 4 * q], sym_f32(fau[k]), macc[0][q]);
-                macc[1][q] = mfma4(wl[dn * G + 4 * q], sym_f32(fad[k]), macc[1][q]);
-                macc[2][q] = mfma4(wl[(kSliceLen + up) * G + 4 * q], sym_f32(fbu[k]), macc[2][q]);
-                macc[3][q] = mfma4(wl[(kSliceLen + dn) * G + 4 * q], sym_f32(fbd[k]), macc[3][q]);
-            }
-        } else {
-            const int q = up & 3;
-            if (q == 0) {  // wl = weights + (lane & 3) * G, wdn = weights - (lane & 3) * G
-#pragma unroll
-                for (int g = 0; g < G; g++) {
-                    wq[0][g] = wl[up * G + g];
-                    wq[1][g] = wdn[dn * G + g];
-                    wq[2][g] = wl[(kSliceLen + up) * G + g];
-                    wq[3][g] = wdn[(kSliceLen + dn) * G + g];
-                }
-            }
+        const int q = up & 3;
+        if (q == 0) {
 #pragma unroll
             for (int g = 0; g < G; g++) {
-                acc[g] = fma_quad(wq[0][g], q, fau[k], acc[g]);
-                acc[g] = fma_quad(wq[1][g], q, fad[k], acc[g]);
-                acc[g] = fma_quad(wq[2][g], q, fbu[k], acc[g]);
-                acc[g] = fma_quad(wq[3][g], q, fbd[k], acc[g]);
+                wq[0][g] = wl[up * G + g];
+                wq[1][g] = wdn[dn * G + g];
+                wq[2][g] = wl[(kSliceLen + up) * G + g];
+                wq[3][g] = wdn[(kSliceLen + dn) * G + g];
             }
+        }
+#pragma unroll
+        for (int g = 0; g < G; g++) {
+            acc[g] = fma_quad(wq[0][g], q, fau[k], acc[g]);
+            acc[g] = fma_quad(wq[1][g], q, fad[k], acc[g]);
+            acc[g] = fma_quad(wq[2][g], q, fbu[k], acc[g]);
+            acc[g] = fma_quad(wq[3][g], q, fbd[k], acc[g]);
         }
     }
 }
 
-// V: symbol index = token; chains au/ad belong to channel 2*lane, bu/bd to channel 2*lane+1.
+// V, groups of 1 and 2: symbol index = token; chains au/ad belong to channel 2*lane, bu/bd to channel 2*lane+1.
 template <int G, int CNT>
 __device__ __forceinline__ void v_accum(const float *wl, const float *wdn, float (&wq)[2][G], int first,
                                         const uint32_t (&fau)[CNT], const uint32_t (&fad)[CNT],
-                                        const uint32_t (&fbu)[CNT], const uint32_t (&fbd)[CNT], float (&acc)[G][2],
-                                        v4f (&macc)[4][(G + 3) / 4]) {
+                                        const uint32_t (&fbu)[CNT], const uint32_t (&fbd)[CNT], float (&acc)[G][2]) {
 #pragma unroll
     for (int k = 0; k < CNT; k++) {
         const int up = first + k, dn = kSliceLen - 1 - up;  // token index inside the block
-        if constexpr (G >= kMfmaMinG) {
-#pragma unroll
-            for (int q = 0; q < (G + 3) / 4; q++) {
-                const float au_w = wl[up * G + 4 * q], ad_w = wl[dn * G + 4 * q];
-                macc[0][q] = mfma4(au_w, sym_f32(fau[k]), macc[0][q]);
-                macc[1][q] = mfma4(ad_w, sym_f32(fad[k]), macc[1][q]);
-                macc[2][q] = mfma4(au_w, sym_f32(fbu[k]), macc[2][q]);
-                macc[3][q] = mfma4(ad_w, sym_f32(fbd[k]), macc[3][q]);
-            }
-        } else {
-            const int q = up & 3;
-            if (q == 0) {
-#pragma unroll
-                for (int g = 0; g < G; g++) {
-                    wq[0][g] = wl[up * G + g];
-                    wq[1][g] = wdn[dn * G + g];
-                }
-            }
+        const int q = up & 3;
+        if (q == 0) {
 #pragma unroll
             for (int g = 0; g < G; g++) {
-                acc[g][0] = fma_quad(wq[0][g], q, fau[k], acc[g][0]);
-                acc[g][0] = fma_quad(wq[1][g], q, fad[k], acc[g][0]);
-                acc[g][1] = fma_quad(wq[0][g], q, fbu[k], acc[g][1]);
-                acc[g][1] = fma_quad(wq[1][g], q, fbd[k], acc[g][1]);
+                wq[0][g] = wl[up * G + g];
+                wq[1][g] = wdn[dn * G + g];
             }
+        }
+#pragma unroll
+        for (int g = 0; g < G; g++) {
+            acc[g][0] = fma_quad(wq[0][g], q, fau[k], acc[g][0]);
+            acc[g][0] = fma_quad(wq[1][g], q, fad[k], acc[g][0]);
+            acc[g][1] = fma_quad(wq[0][g], q, fbu[k], acc[g][1]);
+            acc[g][1] = fma_quad(wq[1][g], q, fbd[k], acc[g][1]);
         }
     }
 }
 
+// ---- MFMA groups: the LDS weight area ---------------------------------------------------------------------------------
+// One 16-byte entry per (chain array, round, head): {hi[4], lo[4]} fp16, slot k = the chain's k-th symbol of that
+// round.  Chain arrays: K has four (channels 0..31 upwards, 63..32 downwards, 64..95 upwards, 127..96 downwards), V
+// two (tokens 0..31 upwards, 63..32 downwards).  Slots that no symbol uses (a last round with fewer symbols, rounds of
+// fewer than four) are zeroed once per wave at kernel start and never written.
+template <int NS>
+struct MfmaRounds {
+    static constexpr int kCount = (kSliceLen / 2 + NS - 1) / NS;  // rounds per chain, the last one may be short
+};
+
+// Power-of-two factor that brings the largest weight of the wave into [2^14, 2^15) (1 if all are zero); *inv = 1/f.
+__device__ __forceinline__ float fp16_scale(float amax, float *inv) {
+    const float m = wave_max(amax);
+    int e = 0;
+    if (m > 0.f) (void)frexpf(m, &e);  // m = f * 2^e, f in [0.5, 1)
+    *inv = ldexpf(1.f, e - 15);
+    return m > 0.f ? ldexpf(1.f, 15 - e) : 1.f;
+}
+// w * f as hi + lo
+__device__ __forceinline__ void split_fp16(float w, _Float16 *hi, _Float16 *lo) {
+    const _Float16 h = (_Float16)w;
+    *hi = h;
+    *lo = (_Float16)(w - (float)h);
+}
+// the chain's CNT decoded symbols of one round as the B operand (unused slots zero)
+template <int CNT>
+__device__ __forceinline__ v4h symbols_fp16(const uint32_t (&e)[CNT]) {
+    v4h b = {(_Float16)0.f, (_Float16)0.f, (_Float16)0.f, (_Float16)0.f};
+#pragma unroll
+    for (int k = 0; k < CNT; k++) b[k] = (_Float16)(unsigned short)(e[k] >> 8);
+    return b;
+}
+// macc += (hi + lo) . b for the heads 4 q + (lane & 3); entry = this lane's 16 bytes
+__device__ __forceinline__ v4f mfma_split(const uint4 entry, v4h b, v4f acc) {
+    const uint2 h2 = make_uint2(entry.x, entry.y), l2 = make_uint2(entry.z, entry.w);
+    acc = __builtin_amdgcn_mfma_f32_4x4x4f16(__builtin_bit_cast(v4h, h2), b, acc, 0, 0, 0);
+    return __builtin_amdgcn_mfma_f32_4x4x4f16(__builtin_bit_cast(v4h, l2), b, acc, 0, 0, 0);
+}
+
 // ---- K block: lane = token; its two slices are channels 0..63 and 64..127 ------------------------------------------
-// hdr32: the record (LDS or global); wts: this wave's LDS weight area.  Leaves
-// scale * q.k' of this lane's token in score[].
+// hdr32: the record (LDS or global); wts: this wave's LDS weight area.  Leaves scale * q.k' of this lane's token in
+// score[].
 template <int G, int NS>
 __device__ __forceinline__ void k_block(const uint32_t *hdr32, const char *lut, uint32_t mask2, float *wts,
                                         const float (&qreg)[G][2], float two_eb, float scale, int lane,
@@ -374,53 +396,97 @@ __device__ __forceinline__ void k_block(const uint32_t *hdr32, const char *lut, 
     const float mn0 = h2f(mm0 & 0xffffu), mn1 = h2f(mm1 & 0xffffu);
     const float st0 = two_eb * (h2f(mm0 >> 16) - mn0), st1 = two_eb * (h2f(mm1 >> 16) - mn1);
     float w0[G], w1[G], acc[G];
-    v4f macc[4][(G + 3) / 4];
 #pragma unroll
     for (int g = 0; g < G; g++) {
         w0[g] = qreg[g][0] * st0;
         w1[g] = qreg[g][1] * st1;
         acc[g] = 0.f;
     }
-#pragma unroll
-    for (int g = 0; g < G; g++) {  // LDS layout [channel][head]
-        wts[lane * G + g] = w0[g];
-        wts[(kSliceLen + lane) * G + g] = w1[g];
-    }
-#pragma unroll
-    for (int c = 0; c < 4; c++)
-#pragma unroll
-        for (int q = 0; q < (G + 3) / 4; q++) macc[c][q] = (v4f){0.f, 0.f, 0.f, 0.f};
-    // MFMA: lane i of a quad supplies head i.  Otherwise: lane i of a quad fetches the weights of step s + i.
-    const float *wl = G >= kMfmaMinG ? wts + (lane & 3) : wts + (lane & 3) * G;
-    const float *wdn = wts - (lane & 3) * G;
-    float wq[4][G];
     const uint32_t sb = hdr32[kMinMaxBytesK / 4 + lane];  // bit counts of slices 2*lane and 2*lane+1
     const uint32_t start = wave_excl_scan((sb & 0xffffu) + (sb >> 16), lane);
     const uint32_t *wm1 = hdr32 + kHdrBytesK / 4 - 1;
-    wave_sync();
-    Quad qd;
-    qd.open(wm1, start, sb & 0xffffu, sb >> 16);
     constexpr int kRounds = kHalf / NS, kTail = kHalf - kRounds * NS;
-    // fully unrolled: the step number decides at compile time which quad lane holds the weight, and the scheduler
-    // may overlap the table lookups of one round with the accumulation of the previous one
-#pragma unroll
-    for (int r = 0; r < kRounds; r++) {
-        uint32_t fau[NS], fad[NS], fbu[NS], fbd[NS];
-        qd.step<NS>(wm1, lut, mask2, fau, fad, fbu, fbd);
-        k_accum<G, NS>(wl, wdn, wq, r * NS, fau, fad, fbu, fbd, acc, macc);
-    }
-    if constexpr (kTail > 0) {
-        uint32_t fau[kTail], fad[kTail], fbu[kTail], fbd[kTail];
-        qd.step<kTail>(wm1, lut, mask2, fau, fad, fbu, fbd);
-        k_accum<G, kTail>(wl, wdn, wq, kRounds * NS, fau, fad, fbu, fbd, acc, macc);
-    }
+    Quad qd;
     if constexpr (G >= kMfmaMinG) {
+        constexpr int R = MfmaRounds<NS>::kCount, Q4 = G / 4;
+        float amax = 0.f;
 #pragma unroll
-        for (int q = 0; q < (G + 3) / 4; q++) {
-            const v4f t = macc[0][q] + macc[1][q] + macc[2][q] + macc[3][q];
-            const float tt[4] = {t.x, t.y, t.z, t.w};
+        for (int g = 0; g < G; g++) amax = fmaxf(amax, fmaxf(fabsf(w0[g]), fabsf(w1[g])));
+        float inv;
+        const float f = fp16_scale(amax, &inv);
+        // channel `lane` (and 64 + lane) is symbol idx of the up chain (lane < 32) or of the down chain
+        const int idx = lane < kHalf ? lane : kSliceLen - 1 - lane, arr = lane < kHalf ? 0 : 1;
+        const int round = idx / NS, slot = idx - round * NS;
+        _Float16 *w16 = reinterpret_cast<_Float16 *>(wts);
 #pragma unroll
-            for (int i = 0; i < 4 && 4 * q + i < G; i++) acc[4 * q + i] = tt[i];
+        for (int g = 0; g < G; g++) {
+            _Float16 hi, lo;
+            split_fp16(w0[g] * f, &hi, &lo);
+            w16[((arr * R + round) * G + g) * 8 + slot] = hi;
+            w16[((arr * R + round) * G + g) * 8 + 4 + slot] = lo;
+            split_fp16(w1[g] * f, &hi, &lo);
+            w16[(((arr + 2) * R + round) * G + g) * 8 + slot] = hi;
+            w16[(((arr + 2) * R + round) * G + g) * 8 + 4 + slot] = lo;
+        }
+        v4f macc[4][Q4];
+#pragma unroll
+        for (int c = 0; c < 4; c++)
+#pragma unroll
+            for (int q = 0; q < Q4; q++) macc[c][q] = (v4f){0.f, 0.f, 0.f, 0.f};
+        const uint4 *wrow = reinterpret_cast<const uint4 *>(wts) + (lane & 3);  // entry of head (lane & 3) + 4 q
+        wave_sync();
+        qd.open(wm1, start, sb & 0xffffu, sb >> 16);
+        auto accumulate = [&](int r, v4h bau, v4h bad, v4h bbu, v4h bbd) {
+#pragma unroll
+            for (int q = 0; q < Q4; q++) {
+                macc[0][q] = mfma_split(wrow[(0 * R + r) * G + 4 * q], bau, macc[0][q]);
+                macc[1][q] = mfma_split(wrow[(1 * R + r) * G + 4 * q], bad, macc[1][q]);
+                macc[2][q] = mfma_split(wrow[(2 * R + r) * G + 4 * q], bbu, macc[2][q]);
+                macc[3][q] = mfma_split(wrow[(3 * R + r) * G + 4 * q], bbd, macc[3][q]);
+            }
+        };
+#pragma unroll
+        for (int r = 0; r < kRounds; r++) {
+            uint32_t fau[NS], fad[NS], fbu[NS], fbd[NS];
+            qd.step<NS>(wm1, lut, mask2, fau, fad, fbu, fbd);
+            accumulate(r, symbols_fp16<NS>(fau), symbols_fp16<NS>(fad), symbols_fp16<NS>(fbu), symbols_fp16<NS>(fbd));
+        }
+        if constexpr (kTail > 0) {
+            uint32_t fau[kTail], fad[kTail], fbu[kTail], fbd[kTail];
+            qd.step<kTail>(wm1, lut, mask2, fau, fad, fbu, fbd);
+            accumulate(kRounds, symbols_fp16<kTail>(fau), symbols_fp16<kTail>(fad), symbols_fp16<kTail>(fbu),
+                       symbols_fp16<kTail>(fbd));
+        }
+#pragma unroll
+        for (int q = 0; q < Q4; q++) {
+            const v4f t = (macc[0][q] + macc[1][q]) + (macc[2][q] + macc[3][q]);
+            acc[4 * q + 0] = t.x * inv;
+            acc[4 * q + 1] = t.y * inv;
+            acc[4 * q + 2] = t.z * inv;
+            acc[4 * q + 3] = t.w * inv;
+        }
+    } else {
+#pragma unroll
+        for (int g = 0; g < G; g++) {  // LDS layout [channel][head]
+            wts[lane * G + g] = w0[g];
+            wts[(kSliceLen + lane) * G + g] = w1[g];
+        }
+        const float *wl = wts + (lane & 3) * G, *wdn = wts - (lane & 3) * G;
+        float wq[4][G];
+        wave_sync();
+        qd.open(wm1, start, sb & 0xffffu, sb >> 16);
+        // fully unrolled: the step number decides at compile time which quad lane holds the weight, and the
+        // scheduler may overlap the table lookups of one round with the accumulation of the previous one
+#pragma unroll
+        for (int r = 0; r < kRounds; r++) {
+            uint32_t fau[NS], fad[NS], fbu[NS], fbd[NS];
+            qd.step<NS>(wm1, lut, mask2, fau, fad, fbu, fbd);
+            k_accum<G, NS>(wl, wdn, wq, r * NS, fau, fad, fbu, fbd, acc);
+        }
+        if constexpr (kTail > 0) {
+            uint32_t fau[kTail], fad[kTail], fbu[kTail], fbd[kTail];
+            qd.step<kTail>(wm1, lut, mask2, fau, fad, fbu, fbd);
+            k_accum<G, kTail>(wl, wdn, wq, kRounds * NS, fau, fad, fbu, fbd, acc);
         }
     }
     // the constant part of the dot product, sum_c q_c min_c, is shared by all tokens of the block
@@ -438,49 +504,88 @@ __device__ __forceinline__ void v_block(const uint32_t *hdr32, const char *lut, 
     const float mn = h2f(mm & 0xffffu);
     const float step = two_eb * (h2f(mm >> 16) - mn);
     float w[G];
-    v4f macc[4][(G + 3) / 4];
 #pragma unroll
     for (int g = 0; g < G; g++) {
         w[g] = p[g] * step;
         st.bv[g] += p[g] * mn;
     }
-#pragma unroll
-    for (int g = 0; g < G; g++) wts[lane * G + g] = w[g];  // LDS layout [token][head]
-#pragma unroll
-    for (int c = 0; c < 4; c++)
-#pragma unroll
-        for (int q = 0; q < (G + 3) / 4; q++) macc[c][q] = (v4f){0.f, 0.f, 0.f, 0.f};
-    const float *wl = G >= kMfmaMinG ? wts + (lane & 3) : wts + (lane & 3) * G;
-    const float *wdn = wts - (lane & 3) * G;
-    float wq[2][G];
     const uint32_t sb = hdr32[kMinMaxBytesV / 4 + lane];
     const uint32_t start = wave_excl_scan((sb & 0xffffu) + (sb >> 16), lane);
     const uint32_t *wm1 = hdr32 + kHdrBytesV / 4 - 1;
-    wave_sync();
-    Quad qd;
-    qd.open(wm1, start, sb & 0xffffu, sb >> 16);
     constexpr int kRounds = kHalf / NS, kTail = kHalf - kRounds * NS;
-#pragma unroll
-    for (int r = 0; r < kRounds; r++) {
-        uint32_t fau[NS], fad[NS], fbu[NS], fbd[NS];
-        qd.step<NS>(wm1, lut, mask2, fau, fad, fbu, fbd);
-        v_accum<G, NS>(wl, wdn, wq, r * NS, fau, fad, fbu, fbd, st.acc, macc);
-    }
-    if constexpr (kTail > 0) {
-        uint32_t fau[kTail], fad[kTail], fbu[kTail], fbd[kTail];
-        qd.step<kTail>(wm1, lut, mask2, fau, fad, fbu, fbd);
-        v_accum<G, kTail>(wl, wdn, wq, kRounds * NS, fau, fad, fbu, fbd, st.acc, macc);
-    }
+    Quad qd;
     if constexpr (G >= kMfmaMinG) {
+        constexpr int R = MfmaRounds<NS>::kCount, Q4 = G / 4;
+        float amax = 0.f;
 #pragma unroll
-        for (int q = 0; q < (G + 3) / 4; q++) {
-            const v4f a = macc[0][q] + macc[1][q], bsum = macc[2][q] + macc[3][q];
-            const float ta[4] = {a.x, a.y, a.z, a.w}, tb[4] = {bsum.x, bsum.y, bsum.z, bsum.w};
+        for (int g = 0; g < G; g++) amax = fmaxf(amax, fabsf(w[g]));
+        float inv;
+        const float f = fp16_scale(amax, &inv);
+        const int idx = lane < kHalf ? lane : kSliceLen - 1 - lane, arr = lane < kHalf ? 0 : 1;
+        const int round = idx / NS, slot = idx - round * NS;
+        _Float16 *w16 = reinterpret_cast<_Float16 *>(wts);
 #pragma unroll
-            for (int i = 0; i < 4 && 4 * q + i < G; i++) {
-                st.acc[4 * q + i][0] += ta[i];
-                st.acc[4 * q + i][1] += tb[i];
+        for (int g = 0; g < G; g++) {
+            _Float16 hi, lo;
+            split_fp16(w[g] * f, &hi, &lo);
+            w16[((arr * R + round) * G + g) * 8 + slot] = hi;
+            w16[((arr * R + round) * G + g) * 8 + 4 + slot] = lo;
+        }
+        v4f macc[4][Q4];
+#pragma unroll
+        for (int c = 0; c < 4; c++)
+#pragma unroll
+            for (int q = 0; q < Q4; q++) macc[c][q] = (v4f){0.f, 0.f, 0.f, 0.f};
+        const uint4 *wrow = reinterpret_cast<const uint4 *>(wts) + (lane & 3);
+        wave_sync();
+        qd.open(wm1, start, sb & 0xffffu, sb >> 16);
+        auto accumulate = [&](int r, v4h bau, v4h bad, v4h bbu, v4h bbd) {
+#pragma unroll
+            for (int q = 0; q < Q4; q++) {
+                const uint4 eu = wrow[(0 * R + r) * G + 4 * q], ed = wrow[(1 * R + r) * G + 4 * q];
+                macc[0][q] = mfma_split(eu, bau, macc[0][q]);
+                macc[1][q] = mfma_split(ed, bad, macc[1][q]);
+                macc[2][q] = mfma_split(eu, bbu, macc[2][q]);
+                macc[3][q] = mfma_split(ed, bbd, macc[3][q]);
             }
+        };
+#pragma unroll
+        for (int r = 0; r < kRounds; r++) {
+            uint32_t fau[NS], fad[NS], fbu[NS], fbd[NS];
+            qd.step<NS>(wm1, lut, mask2, fau, fad, fbu, fbd);
+            accumulate(r, symbols_fp16<NS>(fau), symbols_fp16<NS>(fad), symbols_fp16<NS>(fbu), symbols_fp16<NS>(fbd));
+        }
+        if constexpr (kTail > 0) {
+            uint32_t fau[kTail], fad[kTail], fbu[kTail], fbd[kTail];
+            qd.step<kTail>(wm1, lut, mask2, fau, fad, fbu, fbd);
+            accumulate(kRounds, symbols_fp16<kTail>(fau), symbols_fp16<kTail>(fad), symbols_fp16<kTail>(fbu),
+                       symbols_fp16<kTail>(fbd));
+        }
+#pragma unroll
+        for (int q = 0; q < Q4; q++) {
+            const v4f a = macc[0][q] + macc[1][q], bsum = macc[2][q] + macc[3][q];
+            st.acc[4 * q + 0][0] += a.x * inv; st.acc[4 * q + 1][0] += a.y * inv;
+            st.acc[4 * q + 2][0] += a.z * inv; st.acc[4 * q + 3][0] += a.w * inv;
+            st.acc[4 * q + 0][1] += bsum.x * inv; st.acc[4 * q + 1][1] += bsum.y * inv;
+            st.acc[4 * q + 2][1] += bsum.z * inv; st.acc[4 * q + 3][1] += bsum.w * inv;
+        }
+    } else {
+#pragma unroll
+        for (int g = 0; g < G; g++) wts[lane * G + g] = w[g];  // LDS layout [token][head]
+        const float *wl = wts + (lane & 3) * G, *wdn = wts - (lane & 3) * G;
+        float wq[2][G];
+        wave_sync();
+        qd.open(wm1, start, sb & 0xffffu, sb >> 16);
+#pragma unroll
+        for (int r = 0; r < kRounds; r++) {
+            uint32_t fau[NS], fad[NS], fbu[NS], fbd[NS];
+            qd.step<NS>(wm1, lut, mask2, fau, fad, fbu, fbd);
+            v_accum<G, NS>(wl, wdn, wq, r * NS, fau, fad, fbu, fbd, st.acc);
+        }
+        if constexpr (kTail > 0) {
+            uint32_t fau[kTail], fad[kTail], fbu[kTail], fbd[kTail];
+            qd.step<kTail>(wm1, lut, mask2, fau, fad, fbu, fbd);
+            v_accum<G, kTail>(wl, wdn, wq, kRounds * NS, fau, fad, fbu, fbd, st.acc);
         }
     }
 }
@@ -560,7 +665,12 @@ __global__ __launch_bounds__(kThreads, WavesPerSimd<G>::value) void fused_attn_k
     // the wave number and everything derived from it (block numbers, table entries, record addresses) are scalars
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     uint8_t *stage = smem + (size_t)wave * a.stage_bytes;
-    float *wts = reinterpret_cast<float *>(smem + (size_t)kWaves * a.stage_bytes) + wave * G * kD;
+    constexpr int kWeightBytes = (int)fused_weight_bytes(G, LB);
+    static_assert(G < kMfmaMinG || kWeightBytes == 4 * MfmaRounds<NS>::kCount * G * 16, "weight area layout");
+    float *wts = reinterpret_cast<float *>(smem + (size_t)kWaves * a.stage_bytes + (size_t)wave * kWeightBytes);
+    if constexpr (G >= kMfmaMinG) {  // entries of symbols that do not exist stay zero for the whole kernel
+        for (int i = lane; i < kWeightBytes / 16; i += 64) reinterpret_cast<uint4 *>(wts)[i] = make_uint4(0, 0, 0, 0);
+    }
     const char *lutK = reinterpret_cast<const char *>(&lut_s[0][0]);
     const char *lutV = reinterpret_cast<const char *>(&lut_s[1][0]);
 
@@ -809,7 +919,7 @@ hipError_t launch_fused_attn(const Geo &g, const uint16_t *q, float scale, float
     if (longest < 1 || longest > kLutBits) return hipErrorInvalidValue;
     a.mask2[0] = ((1u << bits_k) - 1u) << kJunkBits;
     a.mask2[1] = ((1u << bits_v) - 1u) << kJunkBits;
-    const size_t lds = (size_t)kWaves * stage_bytes + (size_t)kWaves * g.G * kD * 4;
+    const size_t lds = (size_t)kWaves * stage_bytes + kWaves * fused_weight_bytes(g.G, fused_table_bits(longest));
     switch (g.G) {
         case 1: return launch_fused_g<1>(a, longest, lds, ev0, ev1, s);
         case 2: return launch_fused_g<2>(a, longest, lds, ev0, ev1, s);

@@ -78,10 +78,16 @@ constexpr int fused_table_bits(int longest) {
     return longest <= 7 ? 7 : longest <= 8 ? 8 : longest <= 10 ? 10 : 12;
 }
 constexpr int kLdsBytesPerCU = 160 * 1024;
+// Bytes of one wave's LDS weight area.  Groups of 1 and 2 heads: fp32 [128][G].  Groups of 4 and 8: one 16-byte entry
+// per (chain array of 4, round, head), rounds = ceil(32 / symbols per window).
+constexpr size_t fused_weight_bytes(int G, int table_bits) {
+    return G >= 4 ? (size_t)4 * ((32 + 31 / table_bits - 1) / (31 / table_bits)) * G * 16 : (size_t)G * kD * 4;
+}
 // LDS of one fused-kernel workgroup apart from the per-wave staging areas: two decode tables of 16-bit entries, the
 // query rows and the per-wave weight areas.
 constexpr size_t fused_lds_fixed(int G, int longest) {
-    return ((size_t)4 << fused_table_bits(longest)) + (size_t)G * kD * 4 + (size_t)4 * G * kD * 4 + 512;
+    return ((size_t)4 << fused_table_bits(longest)) + (size_t)G * kD * 4 +
+           4 * fused_weight_bytes(G, fused_table_bits(longest)) + 512;
 }
 
 // ---- launches implemented in the .hip files ----

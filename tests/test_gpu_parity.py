@@ -316,3 +316,27 @@ def test_long_code_words_and_length_limit(gpu, oracle):
     _attn_close(gc.attn_decode(_dev(q), SCALE).cpu().numpy(), oc.attn_decode(q, SCALE))
     _say(f"  largest record {gc.stats()['max_record_bytes']} B, CR {gc.stats()['compression_ratio']:.3f}")
     gc.close()
+
+
+@pytest.mark.parametrize("H,Hq", [(2, 2), (1, 4), (1, 8)])
+@pytest.mark.parametrize("k_scale,q_scale,v_scale", [(256.0, 1.0 / 256.0, 64.0), (1.0 / 64.0, 64.0, 1.0 / 32.0)])
+def test_attention_with_large_and_small_magnitudes(gpu, oracle, H, Hq, k_scale, q_scale, v_scale):
+    """K, q and V scaled by powers of two: the scores do not change, the folded weights (q step, p step) move by
+    several binades (the query-group path keeps them as scaled fp16 pairs)."""
+    _say(f"scaled inputs H={H} Hq={Hq} k x{k_scale} q x{q_scale} v x{v_scale}")
+    B, S = 1, 777
+    Kx, Vx = W.make_kv(B, H, S, 41)
+    Kx = (Kx.astype(np.float32) * k_scale).astype(np.float16)
+    Vx = (Vx.astype(np.float32) * v_scale).astype(np.float16)
+    q = (W.make_queries(B, Hq, 1, 41)[0].astype(np.float32) * q_scale).astype(np.float16)
+    assert np.isfinite(Kx.astype(np.float32)).all() and np.isfinite(Vx.astype(np.float32)).all()
+    oc = oracle.OracleCache(B, H, Hq, 1024, 1e-2, 1e-2, 0, 7)
+    oc.build_codebook(Kx, Vx)
+    oc.compress_blocks(Kx, Vx)
+    gc = gpu.KVCompCache(B, H, Hq, 1024, 1e-2, 1e-2, max_code_len=7)
+    gc.build_codebook(_dev(Kx), _dev(Vx))
+    gc.compress_blocks(_dev(Kx), _dev(Vx))
+    _assert_same_cache(oc, gc)
+    err = _attn_close(gc.attn_decode(_dev(q), SCALE).cpu().numpy(), oc.attn_decode(q, SCALE))
+    _say(f"  max abs err {err:.3e}")
+    gc.close()
