@@ -66,52 +66,69 @@ __global__ __launch_bounds__(256) void size_kernel(Geo g, const uint16_t *__rest
 }
 
 // ---- 2. placement ------------------------------------------------------------------------------------------
-// Items in order: tensor K then V; inside a tensor (b,h) major, block minor.  One workgroup of 1024 threads.
-__global__ __launch_bounds__(1024) void place_kernel(Geo g, int n_blk_per_bh, int dst_blk0) {
+// Items in order: tensor K then V; inside a tensor (b,h) major, block minor.  One workgroup of 1024 threads walks the
+// items in chunks of 8192: sizes are loaded coalesced into LDS, every thread scans its eight consecutive items, the
+// thread sums are scanned over the workgroup, and the offsets go back to the table coalesced.
+constexpr int kPlaceThreads = 1024, kPlacePerThread = 8, kPlaceChunk = kPlaceThreads * kPlacePerThread;
+__device__ __forceinline__ int place_pad(int i) { return i + (i >> 5); }  // one spare word per 32: no bank conflicts
+
+__global__ __launch_bounds__(kPlaceThreads) void place_kernel(Geo g, int n_blk_per_bh, int dst_blk0) {
+    __shared__ uint32_t val[kPlaceChunk + kPlaceChunk / 32];
     __shared__ uint32_t wave_tot[16];
-    __shared__ uint32_t base_s;
     const int tid = threadIdx.x;
-    const int BH = g.B * g.H;
-    const int n_items = 2 * BH * n_blk_per_bh;
-    const int chunk = (n_items + 1023) / 1024;
-    const int i0 = tid * chunk, i1 = min(i0 + chunk, n_items);
-    auto entry = [&](int i) -> BlockEntry * {
-        const int which = i / (BH * n_blk_per_bh);
-        const int rem = i - which * BH * n_blk_per_bh;
-        const int bh = rem / n_blk_per_bh, j = rem - bh * n_blk_per_bh;
-        return &g.table[((size_t)which * BH + bh) * g.max_blocks + dst_blk0 + j];
+    const int n_items = 2 * g.B * g.H * n_blk_per_bh;
+    auto entry = [&](int i) -> BlockEntry * {  // row = tensor * B*H + (b*H + h)
+        const int row = i / n_blk_per_bh, j = i - row * n_blk_per_bh;
+        return &g.table[(size_t)row * g.max_blocks + dst_blk0 + j];
     };
-    uint32_t sum = 0, biggest = 0;
-    for (int i = i0; i < i1; i++) {
-        const uint32_t s16 = entry(i)->size16;
-        sum += s16;
-        biggest = max(biggest, s16);
+    uint32_t base = g.ctrl->tail16, biggest = 0;
+    for (int c0 = 0; c0 < n_items; c0 += kPlaceChunk) {
+#pragma unroll
+        for (int k = 0; k < kPlacePerThread; k++) {
+            const int i = c0 + k * kPlaceThreads + tid;
+            const uint32_t s16 = i < n_items ? entry(i)->size16 : 0u;
+            biggest = max(biggest, s16);
+            val[place_pad(k * kPlaceThreads + tid)] = s16;
+        }
+        __syncthreads();
+        uint32_t mine[kPlacePerThread], sum = 0;
+#pragma unroll
+        for (int k = 0; k < kPlacePerThread; k++) {
+            mine[k] = val[place_pad(tid * kPlacePerThread + k)];
+            sum += mine[k];
+        }
+        uint32_t inc = sum;  // inclusive scan of `sum` over the 1024 threads
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            const uint32_t o = __shfl_up(inc, d);
+            if ((tid & 63) >= d) inc += o;
+        }
+        if ((tid & 63) == 63) wave_tot[tid >> 6] = inc;
+        __syncthreads();
+        uint32_t before = 0, all = 0;
+        for (int w = 0; w < 16; w++) {
+            if (w < (tid >> 6)) before += wave_tot[w];
+            all += wave_tot[w];
+        }
+        uint32_t at = base + before + inc - sum;
+#pragma unroll
+        for (int k = 0; k < kPlacePerThread; k++) {
+            val[place_pad(tid * kPlacePerThread + k)] = at;
+            at += mine[k];
+        }
+        __syncthreads();
+#pragma unroll
+        for (int k = 0; k < kPlacePerThread; k++) {
+            const int i = c0 + k * kPlaceThreads + tid;
+            if (i < n_items) entry(i)->off16 = val[place_pad(k * kPlaceThreads + tid)];
+        }
+        base += all;
+        __syncthreads();  // val and wave_tot are reused by the next chunk
     }
 #pragma unroll
     for (int m = 32; m >= 1; m >>= 1) biggest = max(biggest, (uint32_t)__shfl_xor(biggest, m));
     if ((tid & 63) == 0 && biggest) atomicMax(&g.ctrl->max_size16, biggest);
-    // inclusive scan of `sum` over the 1024 threads
-    uint32_t inc = sum;
-#pragma unroll
-    for (int d = 1; d < 64; d <<= 1) {
-        const uint32_t o = __shfl_up(inc, d);
-        if ((tid & 63) >= d) inc += o;
-    }
-    if ((tid & 63) == 63) wave_tot[tid >> 6] = inc;
-    if (tid == 0) base_s = g.ctrl->tail16;
-    __syncthreads();
-    uint32_t before = 0, all = 0;
-    for (int w = 0; w < 16; w++) {
-        if (w < (tid >> 6)) before += wave_tot[w];
-        all += wave_tot[w];
-    }
-    uint32_t at = base_s + before + inc - sum;
-    for (int i = i0; i < i1; i++) {
-        BlockEntry *e = entry(i);
-        e->off16 = at;
-        at += e->size16;
-    }
-    if (tid == 0) g.ctrl->tail16 = base_s + all;
+    if (tid == 0) g.ctrl->tail16 = base;
 }
 
 // ---- 3. write pass -----------------------------------------------------------------------------------------

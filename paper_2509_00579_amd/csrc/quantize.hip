@@ -4,15 +4,17 @@
 
 namespace kvc {
 
-// One workgroup walks over several 2D blocks, keeps a 256-bin histogram in LDS (one copy per wave to thin out
-// same-address atomics) and adds it to the global histogram once at the end.
+// One workgroup walks over several 2D blocks and keeps the histogram in LDS as [bin][32 copies], copy = lane % 32:
+// the lanes of a half-wave always hit 32 different banks and never the same word, so an LDS atomic instruction costs
+// its minimum however peaked the code distribution is (with one copy per wave, lanes with the same code serialise
+// and the kernel was bound by its LDS atomics).  The copies are summed and added to the global histogram at the end.
 template <int WHICH>
 __global__ __launch_bounds__(256) void histogram_kernel(Geo g, const uint16_t *__restrict__ X, int seq_stride,
                                                          int n_blk_per_bh, int n_blk_total) {
     __shared__ QuantShared sh;
-    __shared__ uint32_t hist[4][256];
-    const int tid = threadIdx.x;
-    for (int i = tid; i < 4 * 256; i += 256) (&hist[0][0])[i] = 0;
+    __shared__ uint32_t hist[256][32];
+    const int tid = threadIdx.x, copy = tid & 31;
+    for (int i = tid; i < 256 * 32; i += 256) (&hist[0][0])[i] = 0;
     __syncthreads();
     bool bad = false;
     for (int blk = blockIdx.x; blk < n_blk_total; blk += gridDim.x) {
@@ -23,11 +25,13 @@ __global__ __launch_bounds__(256) void histogram_kernel(Geo g, const uint16_t *_
 #pragma unroll
         for (int i = 0; i < 4; i++)
 #pragma unroll
-            for (int k = 0; k < 8; k++) atomicAdd(&hist[tid >> 6][r.code[i][k]], 1u);
+            for (int k = 0; k < 8; k++) atomicAdd(&hist[r.code[i][k]][copy], 1u);
         __syncthreads();  // unit_mn/unit_mx are rewritten by the next iteration
     }
     __syncthreads();
-    const uint32_t total = hist[0][tid] + hist[1][tid] + hist[2][tid] + hist[3][tid];
+    uint32_t total = 0;
+#pragma unroll
+    for (int c = 0; c < 32; c++) total += hist[tid][(c + tid) & 31];  // rotated: conflict-free across the bins
     if (total) atomicAdd(&g.hist[WHICH * 256 + tid], total);
     if (bad) atomicOr(&g.ctrl->nonfinite, 1u);
 }
