@@ -47,6 +47,9 @@ def parse_args():
     ap.add_argument("--max-code-len", type=int, default=0,
                     help="longest Huffman code word; 0 = one bit more than a fixed-length code of the quantization "
                          "levels needs (7 at rel_eb 1e-2), which keeps the decode table within two LDS rows")
+    ap.add_argument("--k-mode", type=int, default=0, choices=[0, 1],
+                    help="0: K quantized channel-wise inside a block (the workloads' definition); 1: one range per K "
+                         "block (BlockQuant)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch a 256 MiB device-to-device copy (reference for rocprofv3 FETCH_SIZE/WRITE_SIZE)")
     return ap.parse_args()
@@ -81,7 +84,7 @@ def main():
     dq, dkn, dvn = torch.from_numpy(qs).cuda(), torch.from_numpy(kn).cuda(), torch.from_numpy(vn).cuda()
     out = torch.empty((B, Hq, 128), dtype=torch.float32, device="cuda")
     max_seq = (S + T + 63) // 64 * 64
-    cache = binding.KVCompCache(B, H, Hq, max_seq, rel_eb, rel_eb, max_code_len=args.max_code_len)
+    cache = binding.KVCompCache(B, H, Hq, max_seq, rel_eb, rel_eb, k_mode=args.k_mode, max_code_len=args.max_code_len)
     cache.set_tuning(args.n_splits, args.stage_bytes)
 
     def store():
@@ -224,7 +227,7 @@ def main():
         ob = max(1, min(B, 2))                       # bounded sample: at most 2 sequences of the batch
         oh = H if B * H * S <= 32 * 4096 else max(1, (32 * 4096) // (ob * S))
         oh = min(oh, H)
-        oc = oracle.OracleCache(ob, oh, oh * (Hq // H), max_seq, rel_eb, rel_eb,
+        oc = oracle.OracleCache(ob, oh, oh * (Hq // H), max_seq, rel_eb, rel_eb, k_mode=args.k_mode,
                                 max_code_len=args.max_code_len)
         oc.build_codebook(Kx[:ob, :, :oh], Vx[:ob, :, :oh])
         oc.compress_blocks(np.ascontiguousarray(Kx[:ob, :, :oh]), np.ascontiguousarray(Vx[:ob, :, :oh]))
@@ -262,7 +265,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": f"{args.workload}: batch {B}, {H} kv heads / {Hq} q heads x 128, prompt {S} tokens, "
                                f"{T} decode steps (append one token, then fused decode attention), block 64, "
-                               f"rel_eb {rel_eb}, max code word {args.max_code_len} bits",
+                               f"rel_eb {rel_eb}, max code word {args.max_code_len} bits" + (", K BlockQuant" if args.k_mode else ""),
                    "decode_loop": "hip graph replay" if graph is not None else "eager launches"},
         "pct_hbm_peak": 100.0 * value / HBM_PEAK_GBPS,
         "compression_ratio": stats0["compression_ratio"],

@@ -48,7 +48,9 @@ typedef struct {
     int32_t max_seq;      /* capacity in tokens per sequence (prefill + appended)                             */
     float rel_eb_k;       /* relative error bound for K: |x - x'| <= rel_eb * (max - min) of the unit; the    */
     float rel_eb_v;       /*   paper's "relative quantization scale" (Section 4.2) is the bin width = 2*rel_eb */
-    int32_t k_mode;       /* 0: K units are channels inside a block (Section 3.1.1); 1: reserved (BlockQuant) */
+    int32_t k_mode;       /* 0: K units are channels inside a block (Section 3.1.1); 1: one unit per K block
+                             (BlockQuant, Section 4.2): the K record header then holds one {min,max} pair padded
+                             to 16 bytes instead of 128 pairs */
     int32_t max_code_len; /* longest Huffman code word allowed, <= 12 and 2^max_code_len >= number of levels  */
                           /*   (0 = default 12); shorter words cost compression but decode faster            */
 } kvcomp_config;
@@ -123,7 +125,7 @@ kvcomp_status kvcomp_get_stats(kvcomp_ctx *ctx, kvcomp_stats *h_out, void *strea
 
 /* Quantization codes and unit min/max of the full blocks of d_in (which = KVCOMP_K or KVCOMP_V) without touching the
  * cache.  h_codes: [batch*n_kv_heads*floor(seq/64)][64][128] bytes, blocks in (b,h,block) order, token-major tiles;
- * h_minmax_fp16: [blocks][units][2] fp16 bit patterns (units: 128 channels for K, 64 tokens for V).
+ * h_minmax_fp16: [blocks][units][2] fp16 bit patterns (units: 128 channels for K, or 1 with k_mode 1; 64 tokens for V).
  * d_scratch: device scratch of at least blocks*(8192 + 4*units) bytes. */
 kvcomp_status kvcomp_debug_codes(kvcomp_ctx *ctx, int which, const void *d_in, int seq, void *d_scratch,
                                  size_t scratch_bytes, uint8_t *h_codes, uint16_t *h_minmax_fp16, void *stream);

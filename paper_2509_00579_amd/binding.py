@@ -169,7 +169,7 @@ class KVCompCache:
     def debug_codes(self, which, X):
         S = X.shape[1]
         nblk = self.B * self.H * (S // BT)
-        units = D if which == K else BT
+        units = (1 if self.cfg.k_mode == 1 else D) if which == K else BT
         scratch = torch.empty(nblk * (BT * D + 4 * units), dtype=torch.uint8, device=self.device)
         codes = np.zeros((nblk, BT, D), np.uint8)
         mm = np.zeros((nblk, units, 2), np.uint16)

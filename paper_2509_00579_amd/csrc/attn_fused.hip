@@ -389,10 +389,12 @@ __device__ __forceinline__ v4f mfma_split(const uint4 entry, v4h b, v4f acc) {
 // score[].
 template <int G, int NS>
 __device__ __forceinline__ void k_block(const uint32_t *hdr32, const char *lut, uint32_t mask2, float *wts,
-                                        const float (&qreg)[G][2], float two_eb, float scale, int lane,
+                                        const float (&qreg)[G][2], float two_eb, float scale, int lane, int kmm,
                                         float (&score)[G]) {
-    // lane c holds the folded weights q_c * step_c of channels c and c + 64
-    const uint32_t mm0 = hdr32[lane], mm1 = hdr32[lane + 64];
+    // lane c holds the folded weights q_c * step_c of channels c and c + 64.  kmm = bytes of the {min,max} pairs in
+    // the header: 512 (one pair per channel) or 16 (BlockQuant: one pair for the whole block)
+    const bool per_channel = kmm == kMinMaxBytesK;
+    const uint32_t mm0 = hdr32[per_channel ? lane : 0], mm1 = hdr32[per_channel ? lane + 64 : 0];
     const float mn0 = h2f(mm0 & 0xffffu), mn1 = h2f(mm1 & 0xffffu);
     const float st0 = two_eb * (h2f(mm0 >> 16) - mn0), st1 = two_eb * (h2f(mm1 >> 16) - mn1);
     float w0[G], w1[G], acc[G];
@@ -402,9 +404,9 @@ __device__ __forceinline__ void k_block(const uint32_t *hdr32, const char *lut, 
         w1[g] = qreg[g][1] * st1;
         acc[g] = 0.f;
     }
-    const uint32_t sb = hdr32[kMinMaxBytesK / 4 + lane];  // bit counts of slices 2*lane and 2*lane+1
+    const uint32_t sb = hdr32[kmm / 4 + lane];  // bit counts of slices 2*lane and 2*lane+1
     const uint32_t start = wave_excl_scan((sb & 0xffffu) + (sb >> 16), lane);
-    const uint32_t *wm1 = hdr32 + kHdrBytesK / 4 - 1;
+    const uint32_t *wm1 = hdr32 + (kmm + 2 * kSlices) / 4 - 1;
     constexpr int kRounds = kHalf / NS, kTail = kHalf - kRounds * NS;
     Quad qd;
     if constexpr (G >= kMfmaMinG) {
@@ -594,9 +596,9 @@ __device__ __forceinline__ void v_block(const uint32_t *hdr32, const char *lut, 
 // that it costs the common path no registers.
 template <int G, int NS>
 __device__ __noinline__ void k_block_global(const uint32_t *rec, const char *lut, uint32_t mask2, float *wts,
-                                            const float (&qreg)[G][2], float two_eb, float scale, int lane,
+                                            const float (&qreg)[G][2], float two_eb, float scale, int lane, int kmm,
                                             float (&score)[G]) {
-    k_block<G, NS>(rec, lut, mask2, wts, qreg, two_eb, scale, lane, score);
+    k_block<G, NS>(rec, lut, mask2, wts, qreg, two_eb, scale, lane, kmm, score);
 }
 template <int G, int NS>
 __device__ __noinline__ void v_block_global(const uint32_t *rec, const char *lut, uint32_t mask2, float *wts,
@@ -738,13 +740,13 @@ __global__ __launch_bounds__(kThreads, WavesPerSimd<G>::value) void fused_attn_k
             eVn = tabV[jn];
         }
         if (k_staged) {
-            k_block<G, NS>(stage32, lutK, a.mask2[0], wts, qreg, g.two_eb[0], a.scale, lane, score);
+            k_block<G, NS>(stage32, lutK, a.mask2[0], wts, qreg, g.two_eb[0], a.scale, lane, g.k_minmax_bytes, score);
         } else {  // larger than the staging area: decode from global memory (copies keep the hot state in registers)
             float q_tmp[G][2], s_tmp[G];
 #pragma unroll
             for (int gg = 0; gg < G; gg++) { q_tmp[gg][0] = qreg[gg][0]; q_tmp[gg][1] = qreg[gg][1]; }
             k_block_global<G, NS>(reinterpret_cast<const uint32_t *>(recK), lutK, a.mask2[0], wts, q_tmp, g.two_eb[0], a.scale,
-                                  lane, s_tmp);
+                                  lane, g.k_minmax_bytes, s_tmp);
 #pragma unroll
             for (int gg = 0; gg < G; gg++) score[gg] = s_tmp[gg];
         }
@@ -952,7 +954,7 @@ __global__ __launch_bounds__(256) void stats_kernel(Geo g, int n_blocks) {
         const int bh = (int)(rem / n_blocks), j = (int)(rem - (long long)bh * n_blocks);
         const BlockEntry e = g.table[((size_t)which * BH + bh) * g.max_blocks + j];
         const uint16_t *sb = reinterpret_cast<const uint16_t *>(g.payload + (size_t)e.off16 * 16 +
-                                                                (which ? kMinMaxBytesV : kMinMaxBytesK));
+                                                                (which ? kMinMaxBytesV : g.k_minmax_bytes));
         const uint32_t v = (uint32_t)sb[lane] + sb[lane + 64];
         bits[which] += v;
         if (lane == 0) rec16[which] += e.size16;

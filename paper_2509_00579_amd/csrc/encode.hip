@@ -17,11 +17,11 @@ constexpr int kCodeRow = kD + 4;  // padded row of the LDS code tile (bytes)
 
 template <int WHICH>
 struct Rec {
-    static constexpr int minmax_bytes = WHICH == 0 ? kMinMaxBytesK : kMinMaxBytesV;
-    static constexpr int hdr_bytes = WHICH == 0 ? kHdrBytesK : kHdrBytesV;
-    static constexpr int n_units = WHICH == 0 ? kD : kBT;
     static constexpr int n_slices = kSlices;
     static constexpr int parts = 2;  // threads per slice, 32 symbols each
+    __device__ static int n_units(const Geo &g) { return WHICH == 0 ? g.k_units : kBT; }
+    __device__ static int minmax_bytes(const Geo &g) { return WHICH == 0 ? g.k_minmax_bytes : kMinMaxBytesV; }
+    __device__ static int hdr_bytes(const Geo &g) { return minmax_bytes(g) + 2 * kSlices; }
 };
 
 __device__ __forceinline__ uint32_t record_size16(int hdr_bytes, uint32_t total_bits) {
@@ -51,7 +51,7 @@ __global__ __launch_bounds__(256) void size_kernel(Geo g, const uint16_t *__rest
     enc[tid] = g.enc[WHICH * 512 + tid];
     TileRegs r;
     const bool bad = load_tile(X, seq_stride, g.H, bh / g.H, bh % g.H, j, tid, r);
-    quantize_tile<WHICH>(r, sh, tid, g.two_eb[WHICH], g.n_sym[WHICH]);  // has barriers: enc[] is visible after it
+    quantize_tile<WHICH>(r, sh, tid, g.two_eb[WHICH], g.n_sym[WHICH], g.k_units);  // has barriers: enc[] is visible after it
     uint32_t bits = 0;
 #pragma unroll
     for (int i = 0; i < 4; i++)
@@ -59,7 +59,7 @@ __global__ __launch_bounds__(256) void size_kernel(Geo g, const uint16_t *__rest
         for (int k = 0; k < 8; k++) bits += enc[r.code[i][k]] >> 16;
     const uint32_t total = block_sum(bits, scratch, tid);
     if (tid == 0) {
-        const uint32_t s16 = record_size16(Rec<WHICH>::hdr_bytes, total);
+        const uint32_t s16 = record_size16(Rec<WHICH>::hdr_bytes(g), total);
         g.table[((size_t)WHICH * g.B * g.H + bh) * g.max_blocks + dst_blk0 + j].size16 = s16;
     }
     if (bad) atomicOr(&g.ctrl->nonfinite, 1u);
@@ -148,7 +148,7 @@ __global__ __launch_bounds__(256) void write_kernel(Geo g, const uint16_t *__res
     for (int i = tid; i < (int)(sizeof(rec) / 4); i += 256) rec[i] = 0;
     TileRegs r;
     load_tile(X, seq_stride, g.H, bh / g.H, bh % g.H, j, tid, r);
-    quantize_tile<WHICH>(r, sh, tid, g.two_eb[WHICH], g.n_sym[WHICH]);
+    quantize_tile<WHICH>(r, sh, tid, g.two_eb[WHICH], g.n_sym[WHICH], g.k_units);
     // codes -> LDS tile (token-major rows, padded), header -> record
     const int c0 = tile_chan0(tid);
 #pragma unroll
@@ -158,7 +158,7 @@ __global__ __launch_bounds__(256) void write_kernel(Geo g, const uint16_t *__res
         dst[0] = r.code[i][0] | (r.code[i][1] << 8) | (r.code[i][2] << 16) | (r.code[i][3] << 24);
         dst[1] = r.code[i][4] | (r.code[i][5] << 8) | (r.code[i][6] << 16) | (r.code[i][7] << 24);
     }
-    if (tid < R::n_units) rec[tid] = float_to_half_bits(sh.unit_mn[tid]) | (float_to_half_bits(sh.unit_mx[tid]) << 16);
+    if (tid < R::n_units(g)) rec[tid] = float_to_half_bits(sh.unit_mn[tid]) | (float_to_half_bits(sh.unit_mx[tid]) << 16);
     __syncthreads();
     // Each thread encodes 32 symbols, half of one slice (Section 3.2.2 stage 2).  K: slice s = token s/2, channels
     // 64*(s%2)..+63 in channel order; V: slice s = channel s, tokens in order.  The first half of a slice is written
@@ -184,7 +184,7 @@ __global__ __launch_bounds__(256) void write_kernel(Geo g, const uint16_t *__res
     uint32_t slice_bits = bits;
 #pragma unroll
     for (int m = 1; m < R::parts; m <<= 1) slice_bits += __shfl_xor(slice_bits, m);
-    if (part == 0) reinterpret_cast<uint16_t *>(rec)[R::minmax_bytes / 2 + slice] = (uint16_t)slice_bits;
+    if (part == 0) reinterpret_cast<uint16_t *>(rec)[R::minmax_bytes(g) / 2 + slice] = (uint16_t)slice_bits;
     __syncthreads();
     uint32_t before = 0, total = 0;
 #pragma unroll
@@ -194,7 +194,7 @@ __global__ __launch_bounds__(256) void write_kernel(Geo g, const uint16_t *__res
     }
     // stage 4: aggregate all code words into one contiguous chunk in LDS.  Bit i of the chunk is bit (i % 32) of
     // word (i / 32); the table holds every code word in the bit order in which it enters the chunk.
-    uint32_t *pay = rec + R::hdr_bytes / 4;
+    uint32_t *pay = rec + R::hdr_bytes(g) / 4;
     uint32_t pos = before + inc - bits;
     uint32_t word = pos >> 5, fill = pos & 31;
     unsigned long long acc = 0;
@@ -213,7 +213,7 @@ __global__ __launch_bounds__(256) void write_kernel(Geo g, const uint16_t *__res
     __syncthreads();
     // stages 5-6: the offset was fixed by place_kernel; coalesced 16-byte stores of header + chunk + padding
     const BlockEntry e = g.table[((size_t)WHICH * g.B * g.H + bh) * g.max_blocks + dst_blk0 + j];
-    const uint32_t n16 = record_size16(R::hdr_bytes, total);  // equals e.size16 by construction
+    const uint32_t n16 = record_size16(R::hdr_bytes(g), total);  // equals e.size16 by construction
     uint4 *dst = reinterpret_cast<uint4 *>(g.payload + (size_t)e.off16 * 16);
     const uint4 *src = reinterpret_cast<const uint4 *>(rec);
     for (uint32_t i = tid; i < n16 && i < e.size16; i += 256) dst[i] = src[i];

@@ -49,7 +49,7 @@ bool valid_cfg(const kvcomp_config *c) {
     if (c->head_dim != kD || c->block_tokens != kBT) return false;
     if (c->max_seq < 1) return false;
     if (n_sym_for(c->rel_eb_k) < 0 || n_sym_for(c->rel_eb_v) < 0) return false;
-    if (c->k_mode != 0) return false;
+    if (c->k_mode != 0 && c->k_mode != 1) return false;
     if (c->max_code_len != 0) {  // every level needs a code word: 2^max_code_len >= number of levels
         const int levels = std::max(n_sym_for(c->rel_eb_k), n_sym_for(c->rel_eb_v));
         if (c->max_code_len > kLutBits || (1 << c->max_code_len) < levels) return false;
@@ -57,6 +57,10 @@ bool valid_cfg(const kvcomp_config *c) {
     if ((long long)c->batch * c->n_kv_heads * ((long long)c->max_seq / kBT + 1) > (1ll << 28)) return false;
     return true;
 }
+
+// header of a K record: {min,max} pairs (one per channel, or one for the block padded to 16 bytes) + slice bit counts
+int k_minmax_bytes(const kvcomp_config &c) { return c.k_mode == 1 ? 16 : kMinMaxBytesK; }
+int k_header_bytes(const kvcomp_config &c) { return k_minmax_bytes(c) + 2 * kSlices; }
 
 int code_len_limit(const kvcomp_config &c) { return c.max_code_len ? c.max_code_len : kLutBits; }
 
@@ -71,7 +75,7 @@ Layout make_layout(const kvcomp_config &c) {
     const size_t BH = (size_t)c.batch * c.n_kv_heads;
     L.max_blocks = c.max_seq / kBT;
     const int lim = code_len_limit(c);
-    const size_t worst_k = align_up(kHdrBytesK + (size_t)kTile * lim / 8, 16);
+    const size_t worst_k = align_up((size_t)k_header_bytes(c) + (size_t)kTile * lim / 8, 16);
     const size_t worst_v = align_up(kHdrBytesV + (size_t)kTile * lim / 8, 16);
     size_t at = 0;
     L.ctrl = at; at += 256;
@@ -237,6 +241,8 @@ kvcomp_status kvcomp_create(const kvcomp_config *cfg, void *d_arena, size_t aren
     g.Hq = cfg->n_q_heads;
     g.G = g.Hq / g.H;
     g.max_blocks = std::max(L.max_blocks, 1);
+    g.k_units = cfg->k_mode == 1 ? 1 : kD;
+    g.k_minmax_bytes = k_minmax_bytes(*cfg);
     g.two_eb[0] = 2.0f * cfg->rel_eb_k;
     g.two_eb[1] = 2.0f * cfg->rel_eb_v;
     g.n_sym[0] = n_sym_for(cfg->rel_eb_k);
@@ -449,7 +455,7 @@ kvcomp_status kvcomp_get_stats(kvcomp_ctx *ctx, kvcomp_stats *o, void *stream) {
     o->raw_bytes = 2 * BH * tokens * kD * 2;
     o->record_bytes_k = (int64_t)c.record16[0] * 16;
     o->record_bytes_v = (int64_t)c.record16[1] * 16;
-    o->header_bytes = nblk * (kHdrBytesK + kHdrBytesV);
+    o->header_bytes = nblk * (k_header_bytes(ctx->cfg) + kHdrBytesV);
     o->offsets_bytes = 2 * nblk * (long long)sizeof(BlockEntry);
     o->residual_bytes = 2 * BH * ctx->n_res * kD * 2;
     o->payload_bits_k = (int64_t)c.payload_bits[0];
@@ -468,7 +474,7 @@ kvcomp_status kvcomp_debug_codes(kvcomp_ctx *ctx, int which, const void *d_in, i
     if (seq < kBT) return fail(KVCOMP_ERR_INVALID_ARG, "seq must hold a full block");
     const Geo &g = ctx->geo;
     const size_t nblk = (size_t)g.B * g.H * (seq / kBT);
-    const size_t units = which == 0 ? kD : kBT;
+    const size_t units = which == 0 ? (size_t)g.k_units : kBT;
     const size_t codes_bytes = nblk * kTile, mm_bytes = nblk * units * 4;
     if (scratch_bytes < codes_bytes + mm_bytes) return fail(KVCOMP_ERR_CAPACITY, "scratch too small");
     hipStream_t s = static_cast<hipStream_t>(stream);

@@ -24,7 +24,7 @@ constexpr int kSlices = 128;
 constexpr int kSliceLen = 64;
 constexpr int kMinMaxBytesK = 4 * kD;
 constexpr int kMinMaxBytesV = 4 * kBT;
-constexpr int kHdrBytesK = kMinMaxBytesK + 2 * kSlices;   // 768
+constexpr int kHdrBytesK = kMinMaxBytesK + 2 * kSlices;   // 768 (channel-wise units; BlockQuant: 16 + 256)
 constexpr int kHdrBytesV = kMinMaxBytesV + 2 * kSlices;   // 512
 constexpr int kMaxPayloadBytes = kTile * kLutBits / 8;  // 12288
 constexpr int kMaxRecordBytes = kHdrBytesK + kMaxPayloadBytes + 16;
@@ -51,6 +51,8 @@ struct Ctrl {
 struct Geo {
     int B, H, Hq, G;
     int max_blocks;
+    int k_units;             // quantization units of a K block: 128 (one per channel) or 1 (BlockQuant, Section 4.2)
+    int k_minmax_bytes;      // their {min,max} fp16 pairs in the record header, padded to 16 bytes: 512 or 16
     float two_eb[2];   // bin width factor 2*rel_eb
     int n_sym[2];
     Ctrl *ctrl;

@@ -21,7 +21,7 @@ __global__ __launch_bounds__(256) void histogram_kernel(Geo g, const uint16_t *_
         const int bh = blk / n_blk_per_bh, j = blk - bh * n_blk_per_bh;
         TileRegs r;
         bad |= load_tile(X, seq_stride, g.H, bh / g.H, bh % g.H, j, tid, r);
-        quantize_tile<WHICH>(r, sh, tid, g.two_eb[WHICH], g.n_sym[WHICH]);
+        quantize_tile<WHICH>(r, sh, tid, g.two_eb[WHICH], g.n_sym[WHICH], g.k_units);
 #pragma unroll
         for (int i = 0; i < 4; i++)
 #pragma unroll
@@ -46,7 +46,7 @@ __global__ __launch_bounds__(256) void debug_codes_kernel(Geo g, const uint16_t 
     const int bh = blk / n_blk_per_bh, j = blk - bh * n_blk_per_bh;
     TileRegs r;
     const bool bad = load_tile(X, seq_stride, g.H, bh / g.H, bh % g.H, j, tid, r);
-    quantize_tile<WHICH>(r, sh, tid, g.two_eb[WHICH], g.n_sym[WHICH]);
+    quantize_tile<WHICH>(r, sh, tid, g.two_eb[WHICH], g.n_sym[WHICH], g.k_units);
     const int c0 = tile_chan0(tid);
 #pragma unroll
     for (int i = 0; i < 4; i++) {
@@ -56,7 +56,7 @@ __global__ __launch_bounds__(256) void debug_codes_kernel(Geo g, const uint16_t 
         pk.y = r.code[i][4] | (r.code[i][5] << 8) | (r.code[i][6] << 16) | (r.code[i][7] << 24);
         *reinterpret_cast<uint2 *>(codes + (size_t)blk * kTile + t * kD + c0) = pk;
     }
-    constexpr int units = WHICH == 0 ? kD : kBT;
+    const int units = WHICH == 0 ? g.k_units : kBT;
     if (tid < units) {
         minmax[((size_t)blk * units + tid) * 2 + 0] = (uint16_t)float_to_half_bits(sh.unit_mn[tid]);
         minmax[((size_t)blk * units + tid) * 2 + 1] = (uint16_t)float_to_half_bits(sh.unit_mx[tid]);

@@ -75,10 +75,47 @@ struct QuantShared {
 
 // Computes r.code and leaves the unit minima / maxima in sh.unit_mn / sh.unit_mx.
 // Contains __syncthreads(): must be called by all 256 threads of the workgroup.
+// k_units: 128 = K channel-wise inside the block (Section 3.1.1), 1 = one unit per K block (BlockQuant, Section 4.2);
+// ignored for V.
 template <int WHICH>
-__device__ __forceinline__ void quantize_tile(TileRegs &r, QuantShared &sh, int tid, float two_eb, int n_sym) {
+__device__ __forceinline__ void quantize_tile(TileRegs &r, QuantShared &sh, int tid, float two_eb, int n_sym,
+                                              int k_units) {
     const float top = (float)(n_sym - 1);
-    if (WHICH == 0) {
+    if (WHICH == 0 && k_units == 1) {
+        float a = r.x[0][0], z = r.x[0][0];
+#pragma unroll
+        for (int i = 0; i < 4; i++)
+#pragma unroll
+            for (int k = 0; k < 8; k++) {
+                a = fminf(a, r.x[i][k]);
+                z = fmaxf(z, r.x[i][k]);
+            }
+#pragma unroll
+        for (int m = 1; m < 64; m <<= 1) {
+            a = fminf(a, __shfl_xor(a, m));
+            z = fmaxf(z, __shfl_xor(z, m));
+        }
+        if ((tid & 63) == 0) {
+            sh.part_mn[tid >> 6][0] = a;
+            sh.part_mx[tid >> 6][0] = z;
+        }
+        __syncthreads();
+        if (tid == 0) {
+            sh.unit_mn[0] = canon_zero(fminf(fminf(sh.part_mn[0][0], sh.part_mn[1][0]),
+                                             fminf(sh.part_mn[2][0], sh.part_mn[3][0])));
+            sh.unit_mx[0] = canon_zero(fmaxf(fmaxf(sh.part_mx[0][0], sh.part_mx[1][0]),
+                                             fmaxf(sh.part_mx[2][0], sh.part_mx[3][0])));
+        }
+        __syncthreads();
+        a = sh.unit_mn[0];
+        z = sh.unit_mx[0];
+        const float range = z - a;
+        const float step = two_eb * range;
+#pragma unroll
+        for (int i = 0; i < 4; i++)
+#pragma unroll
+            for (int k = 0; k < 8; k++) r.code[i][k] = quant_code(r.x[i][k], a, step, range, top);
+    } else if (WHICH == 0) {
         float mn[8], mx[8];
 #pragma unroll
         for (int k = 0; k < 8; k++) {

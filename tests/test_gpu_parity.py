@@ -340,3 +340,41 @@ def test_attention_with_large_and_small_magnitudes(gpu, oracle, H, Hq, k_scale, 
     err = _attn_close(gc.attn_decode(_dev(q), SCALE).cpu().numpy(), oc.attn_decode(q, SCALE))
     _say(f"  max abs err {err:.3e}")
     gc.close()
+
+
+@pytest.mark.parametrize("H,Hq,max_len", [(2, 2, 12), (1, 4, 9), (1, 8, 7)])
+def test_block_quant_k(gpu, oracle, H, Hq, max_len):
+    """K with one quantization range per 2D block (BlockQuant, Section 4.2): codes, range, codebook, records (their
+    header holds one {min,max} pair), attention, and the append path with a flush."""
+    _say(f"BlockQuant K: H={H} Hq={Hq} max code word {max_len}")
+    B, S, rel = 2, 200, 1e-2
+    Kx, Vx = W.make_kv(B, H, S, 51)
+    Kx[1, 64:128, 0, :] = np.float16(-2.5)  # a constant K block
+    oc = oracle.OracleCache(B, H, Hq, 320, rel, rel, 1, max_len)
+    gc = gpu.KVCompCache(B, H, Hq, 320, rel, rel, k_mode=1, max_code_len=max_len)
+    oc.build_codebook(Kx, Vx)
+    gc.build_codebook(_dev(Kx), _dev(Vx))
+    codes_o, mm_o = oracle.tensor_quantize(K, Kx, rel, k_mode=1)
+    codes_g, mm_g = gc.debug_codes(K, _dev(Kx))
+    assert mm_g.shape == mm_o.shape == (B * H * (S // 64), 1, 2)
+    np.testing.assert_array_equal(mm_g, mm_o)
+    np.testing.assert_array_equal(codes_g, codes_o)
+    for which in (K, V):
+        ln_g, cd_g = gc.codebook(which)
+        np.testing.assert_array_equal(ln_g, oc.len[which])
+        np.testing.assert_array_equal(cd_g, oc.code[which])
+    oc.compress_blocks(Kx, Vx)
+    gc.compress_blocks(_dev(Kx), _dev(Vx))
+    _assert_same_cache(oc, gc)
+    kn, vn = W.make_new_tokens(B, H, 70, 51)
+    qs = W.make_queries(B, Hq, 70, 51)
+    for t in range(70):
+        oc.append_token(kn[t], vn[t])
+        gc.append_token(_dev(kn[t]), _dev(vn[t]))
+        if t in (0, 55, 56, 69):  # the flush happens at t = 55
+            err = _attn_close(gc.attn_decode(_dev(qs[t]), SCALE).cpu().numpy(), oc.attn_decode(qs[t], SCALE))
+            _say(f"  step {t}: max abs err {err:.3e}")
+    _assert_same_cache(oc, gc)
+    st = gc.stats()
+    _say(f"  CR {st['compression_ratio']:.3f}, K bits/symbol {st['payload_bits_k'] / (B * H * oc.n_blocks * 8192.0):.2f}")
+    gc.close()
