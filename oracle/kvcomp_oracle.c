@@ -170,6 +170,52 @@ void orc_dequantize_block(int which, int k_mode, const uint8_t *codes, const uin
         }
 }
 
+/* binary32 -> binary16, round to nearest even (overflow to infinity, gradual underflow). */
+static uint16_t float_to_half(float f) {
+    uint32_t x, sign, mant;
+    int32_t e;
+    memcpy(&x, &f, 4);
+    sign = (x >> 16) & 0x8000u;
+    e = (int32_t)((x >> 23) & 0xffu);
+    mant = x & 0x7fffffu;
+    if (e == 0xff) return (uint16_t)(sign | 0x7c00u | (mant ? 0x200u : 0u));
+    e -= 127;
+    if (e > 15) return (uint16_t)(sign | 0x7c00u);
+    if (e >= -14) {                       /* normal half: keep 10 mantissa bits, round on the 13 dropped ones */
+        uint32_t h = ((uint32_t)(e + 15) << 10) | (mant >> 13);
+        uint32_t rest = mant & 0x1fffu;
+        if (rest > 0x1000u || (rest == 0x1000u && (h & 1u))) h++;   /* a carry runs into the exponent: correct */
+        return (uint16_t)(sign | h);
+    }
+    if (e < -25) return (uint16_t)sign;    /* below half of the smallest subnormal */
+    {                                      /* subnormal half: value = m * 2^-24 */
+        uint32_t full = mant | 0x800000u;  /* 1.m as a 24-bit integer, value = full * 2^(e-23) */
+        int shift = -e - 1;                /* m = full >> shift, shift in 14..24 */
+        uint32_t h = full >> shift;
+        uint32_t rest = full & ((1u << shift) - 1u), halfway = 1u << (shift - 1);
+        if (rest > halfway || (rest == halfway && (h & 1u))) h++;
+        return (uint16_t)(sign | h);
+    }
+}
+uint16_t orc_float_to_half(float f) { return float_to_half(f); }
+
+/* Reconstruction as binary16, for the stand-alone decompression of the multi-kernel pipeline (Section 4.3 writes
+ * the decompressed cache back to memory in the cache's own precision): binary32 product code * width, binary32 sum
+ * with the minimum, one rounding to binary16.  out: [64][128] bit patterns. */
+void orc_reconstruct_block_fp16(int which, int k_mode, const uint8_t *codes, const uint16_t *minmax, float rel_eb,
+                                uint16_t *out) {
+    int t, c;
+    for (t = 0; t < BT; t++)
+        for (c = 0; c < D; c++) {
+            int u = unit_of(which, k_mode, t, c);
+            float mn = half_to_float(minmax[2 * u]);
+            float st = unit_step(minmax[2 * u], minmax[2 * u + 1], rel_eb);
+            float prod = (float)codes[t * D + c] * st;
+            float v = mn + prod;
+            out[t * D + c] = float_to_half(v);
+        }
+}
+
 /* ---------------------------------------------------------------- histogram ------------------------------- */
 
 void orc_histogram(const uint8_t *codes, size_t n, uint64_t *hist) {

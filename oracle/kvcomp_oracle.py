@@ -40,6 +40,10 @@ def lib():
         L.orc_quantize_block.argtypes = [C.c_int, C.c_int, u16p, C.c_float, u8p, u16p]
         L.orc_dequantize_block.restype = None
         L.orc_dequantize_block.argtypes = [C.c_int, C.c_int, u8p, u16p, C.c_float, f64p]
+        L.orc_reconstruct_block_fp16.restype = None
+        L.orc_reconstruct_block_fp16.argtypes = [C.c_int, C.c_int, u8p, u16p, C.c_float, u16p]
+        L.orc_float_to_half.restype = C.c_uint16
+        L.orc_float_to_half.argtypes = [C.c_float]
         L.orc_histogram.restype = None
         L.orc_histogram.argtypes = [u8p, C.c_size_t, u64p]
         L.orc_build_codebook.restype = C.c_int
@@ -112,6 +116,21 @@ def dequantize_block(which, codes, minmax, rel_eb, k_mode=0):
     lib().orc_dequantize_block(which, k_mode, _p(codes, C.c_uint8), _p(minmax, C.c_uint16), np.float32(rel_eb),
                                _p(out, C.c_double))
     return out
+
+
+def reconstruct_block_fp16(which, codes, minmax, rel_eb, k_mode=0):
+    """Reconstructed block as float16 [64,128]: binary32 code * width + min, rounded once to binary16."""
+    codes = np.ascontiguousarray(codes, np.uint8)
+    minmax = np.ascontiguousarray(minmax, np.uint16)
+    out = np.zeros((BT, D), np.uint16)
+    lib().orc_reconstruct_block_fp16(which, k_mode, _p(codes, C.c_uint8), _p(minmax, C.c_uint16), np.float32(rel_eb),
+                                     _p(out, C.c_uint16))
+    return out.view(np.float16)
+
+
+def float_to_half_bits(x):
+    """binary32 -> binary16 bit pattern, round to nearest even (the oracle's own conversion)."""
+    return int(lib().orc_float_to_half(float(x)))
 
 
 def histogram(codes):
@@ -299,6 +318,20 @@ class OracleCache:
                                   _p(out, C.c_double))
         if r:
             raise RuntimeError(f"orc_attn_decode failed: {r}")
+        return out
+
+    def decompress(self, which):
+        """The whole cache of one tensor as float16 [B, tokens, H, 128]: reconstructed blocks, then the buffered tokens."""
+        tokens = self.n_blocks * BT + self.n_res
+        out = np.zeros((self.B, tokens, self.H, D), np.float16)
+        for b in range(self.B):
+            for h in range(self.H):
+                for j in range(self.n_blocks):
+                    codes, mm = decode_block_serial(which, self.get_block(which, b, h, j), self.len[which],
+                                                    self._mode(which))
+                    out[b, j * BT:(j + 1) * BT, h] = reconstruct_block_fp16(which, codes, mm, self.rel_eb[which],
+                                                                            self._mode(which))
+        out[:, self.n_blocks * BT:] = self.res[which][:, : self.n_res]
         return out
 
     def get_block(self, which, b, h, j):

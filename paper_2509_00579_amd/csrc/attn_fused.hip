@@ -22,198 +22,11 @@
 //    reduction" of Section 3.3.2) inside the same launch.
 #include <hip/hip_fp16.h>
 
+#include "huff_decode.cuh"
 #include "kvcomp_internal.h"
 #include "split_combine.cuh"
 
 namespace kvc {
-
-__device__ __forceinline__ void wave_sync() {
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-}
-
-__device__ __forceinline__ float h2f(uint32_t bits) { return __half2float(__ushort_as_half((unsigned short)bits)); }
-
-// value of `v` in lane `lane_idx` (wave-uniform index), delivered in a scalar register
-__device__ __forceinline__ float bcast(float v, int lane_idx) {
-    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), lane_idx));
-}
-
-// Wave-wide reductions and the prefix sum run on DPP row operations and v_readlane, not on ds_bpermute: the LDS pipe
-// is the busiest unit of this kernel and a butterfly of six dependent LDS round trips costs far more latency.
-template <int CTRL>
-__device__ __forceinline__ float dpp_f(float v) {  // lanes without a source read 0
-    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xf, 0xf, true));
-}
-template <int CTRL>
-__device__ __forceinline__ uint32_t dpp_u(uint32_t v) {
-    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, 0xf, 0xf, true);
-}
-constexpr int kDppXor1 = 0xB1, kDppXor2 = 0x4E;              // quad_perm [1,0,3,2] and [2,3,0,1]
-constexpr int kDppHalfMirror = 0x141, kDppMirror = 0x140;    // lane i <-> 7 - i (within 8) and i <-> 15 - i (within 16)
-constexpr int kDppRowShr = 0x110;                            // + n: lane i reads lane i - n of its row of 16
-
-// the same value in every lane
-__device__ __forceinline__ float wave_sum(float v) {
-    v += dpp_f<kDppXor1>(v);
-    v += dpp_f<kDppXor2>(v);
-    v += dpp_f<kDppHalfMirror>(v);
-    v += dpp_f<kDppMirror>(v);  // every lane: sum of its row of 16
-    return (bcast(v, 0) + bcast(v, 16)) + (bcast(v, 32) + bcast(v, 48));
-}
-__device__ __forceinline__ float wave_max(float v) {
-    v = fmaxf(v, dpp_f<kDppXor1>(v));
-    v = fmaxf(v, dpp_f<kDppXor2>(v));
-    v = fmaxf(v, dpp_f<kDppHalfMirror>(v));
-    v = fmaxf(v, dpp_f<kDppMirror>(v));
-    return fmaxf(fmaxf(bcast(v, 0), bcast(v, 16)), fmaxf(bcast(v, 32), bcast(v, 48)));
-}
-// exclusive prefix sum over the 64 lanes
-__device__ __forceinline__ uint32_t wave_excl_scan(uint32_t v, int lane) {
-    uint32_t inc = v;
-    inc += dpp_u<kDppRowShr + 1>(inc);
-    inc += dpp_u<kDppRowShr + 2>(inc);
-    inc += dpp_u<kDppRowShr + 4>(inc);
-    inc += dpp_u<kDppRowShr + 8>(inc);  // inclusive within each row of 16
-    const uint32_t t0 = __builtin_amdgcn_readlane(inc, 15), t1 = __builtin_amdgcn_readlane(inc, 31),
-                   t2 = __builtin_amdgcn_readlane(inc, 47);
-    const int row = lane >> 4;
-    const uint32_t before = row == 0 ? 0u : row == 1 ? t0 : row == 2 ? t0 + t1 : t0 + t1 + t2;
-    return inc + before - v;
-}
-
-// A slice holds two decode chains (see the record layout): symbols 0..31 are read upwards from the slice start,
-// symbols 63..32 downwards from the slice end.
-//   wm1   payload words, pointer moved back by one word: payload bit x is bit x + 32 of wm1
-// A window is 32 stream bits whose bit 0 is a don't-care and whose bits 1.. are the next unread bits in reading
-// order, i.e. the stream already scaled to the byte offset of a 16-bit table entry.
-// KVC_READER selects how a chain fetches its stream bits (build-time, for measurements):
-//   1  look-ahead: {hi,lo} words in registers, next word fetched one window ahead (4-byte aligned LDS reads)
-//   0  every window re-reads its two words (one 8-byte LDS read): less bookkeeping, measured ~10 % slower
-// (Unaligned 4-byte LDS reads at byte granularity were also tried: correct on gfx950 but 2.4x slower.)
-#ifndef KVC_READER
-#define KVC_READER 1
-#endif
-constexpr int kJunkBits = 1;                  // low window bits that are not stream bits
-constexpr int kWindowBits = 32 - kJunkBits;  // stream bits per window
-#if KVC_READER == 1
-// Readers keep a 64-bit piece {hi,lo} of the stream in registers plus the next word in reading direction, fetched
-// one window ahead: one 4-byte LDS read per window, off the critical path (only table lookups depend on each other).
-struct UpReader {
-    uint32_t P, idx, lo, hi, nx;  // P = (next unread payload bit) + 31 = window start in wm1 bit coordinates
-    __device__ __forceinline__ void open(const uint32_t *wm1, uint32_t first_bit) {
-        P = first_bit + (uint32_t)kWindowBits;
-        idx = P >> 5;
-        lo = wm1[idx];
-        hi = wm1[idx + 1];
-        nx = wm1[idx + 2];
-    }
-    __device__ __forceinline__ uint32_t window(const uint32_t *) const { return __builtin_amdgcn_alignbit(hi, lo, P); }
-    __device__ __forceinline__ void advance(const uint32_t *wm1, uint32_t used) {  // used <= 31
-        P += used;
-        const uint32_t nidx = P >> 5;
-        const bool adv = nidx != idx;
-        lo = adv ? hi : lo;
-        hi = adv ? nx : hi;
-        idx = nidx;
-        nx = wm1[nidx + 2];
-    }
-};
-struct DownReader {
-    uint32_t P, idx, lo, hi, pv;  // P = (one past the next unread payload bit) + 1: the window [P, P+32) of wm1 ends
-                                  // one bit above the next unread bit; bit-reversed it reads downwards
-    __device__ __forceinline__ void open(const uint32_t *wm1, uint32_t end_bit) {
-        P = end_bit + (uint32_t)kJunkBits;
-        idx = P >> 5;
-        lo = wm1[idx];
-        hi = wm1[idx + 1];
-        pv = wm1[(int)idx - 1];
-    }
-    __device__ __forceinline__ uint32_t window(const uint32_t *) const {
-        return __builtin_bitreverse32(__builtin_amdgcn_alignbit(hi, lo, P));
-    }
-    __device__ __forceinline__ void advance(const uint32_t *wm1, uint32_t used) {  // used <= 31
-        P -= used;
-        const uint32_t nidx = P >> 5;
-        const bool adv = nidx != idx;
-        hi = adv ? lo : hi;
-        lo = adv ? pv : lo;
-        idx = nidx;
-        pv = wm1[(int)nidx - 1];
-    }
-};
-#else
-// Every window re-reads its two words from LDS (one ds_read2_b32): least bookkeeping, more LDS traffic.
-struct UpReader {
-    uint32_t P;  // (next unread payload bit) + 31 = window start in wm1 bit coordinates
-    __device__ __forceinline__ void open(const uint32_t *, uint32_t first_bit) { P = first_bit + (uint32_t)kWindowBits; }
-    __device__ __forceinline__ uint32_t window(const uint32_t *wm1) const {
-        const uint32_t idx = P >> 5;
-        return __builtin_amdgcn_alignbit(wm1[idx + 1], wm1[idx], P);
-    }
-    __device__ __forceinline__ void advance(const uint32_t *, uint32_t used) { P += used; }
-};
-struct DownReader {
-    uint32_t P;  // (one past the next unread payload bit) + 1
-    __device__ __forceinline__ void open(const uint32_t *, uint32_t end_bit) { P = end_bit + (uint32_t)kJunkBits; }
-    __device__ __forceinline__ uint32_t window(const uint32_t *wm1) const {
-        const uint32_t idx = P >> 5;
-        return __builtin_bitreverse32(__builtin_amdgcn_alignbit(wm1[idx + 1], wm1[idx], P));
-    }
-    __device__ __forceinline__ void advance(const uint32_t *, uint32_t used) { P -= used; }
-};
-#endif
-
-// Decode CNT symbols from a window.  lut: 16-bit entries (symbol << 8) | code length, indexed by the next `bits`
-// stream bits; mask2 = ((1 << bits) - 1) << 1.  CNT * (longest code word) <= kWindowBits is the caller's promise.
-// e[] receives the entries; returns the number of bits used.
-// (32-bit entries with the symbol as an fp16 number in the upper half, consumed by v_fma_mix_f32 without a
-// conversion, were measured too: one VALU instruction less per symbol, but the table takes twice the LDS rows and
-// the extra bank conflicts cost more than the instruction saves, except for tables of 64 entries where it is a tie.)
-template <int CNT>
-__device__ __forceinline__ uint32_t lookup(uint32_t win, const char *lut, uint32_t mask2, uint32_t (&e)[CNT]) {
-    uint32_t tot = 0;
-#pragma unroll
-    for (int k = 0; k < CNT; k++) {
-        e[k] = *reinterpret_cast<const uint16_t *>(lut + (win & mask2));
-        win >>= (e[k] & 31u);
-        tot += e[k];  // low byte: running sum of code lengths (at most 31, never carries)
-    }
-    return tot & 0xffu;
-}
-
-// the symbol of a table entry as fp32 (one v_cvt_f32_ubyte1)
-__device__ __forceinline__ float sym_f32(uint32_t e) { return (float)(e >> 8); }
-// acc + w * symbol
-__device__ __forceinline__ float fma_sym(float w, uint32_t e, float acc) { return fmaf(w, sym_f32(e), acc); }
-
-// The four chains of one lane (two slices x two directions) advance together, CNT symbols each.
-struct Quad {
-    UpReader au, bu;
-    DownReader ad, bd;
-    // a = [a0, a0 + abits), b follows it
-    __device__ __forceinline__ void open(const uint32_t *wm1, uint32_t a0, uint32_t abits, uint32_t bbits) {
-        au.open(wm1, a0);
-        ad.open(wm1, a0 + abits);
-        bu.open(wm1, a0 + abits);
-        bd.open(wm1, a0 + abits + bbits);
-    }
-    template <int CNT>
-    __device__ __forceinline__ void step(const uint32_t *wm1, const char *lut, uint32_t mask2, uint32_t (&fau)[CNT],
-                                         uint32_t (&fad)[CNT], uint32_t (&fbu)[CNT], uint32_t (&fbd)[CNT]) {
-        const uint32_t u0 = lookup<CNT>(au.window(wm1), lut, mask2, fau);
-        const uint32_t u1 = lookup<CNT>(ad.window(wm1), lut, mask2, fad);
-        const uint32_t u2 = lookup<CNT>(bu.window(wm1), lut, mask2, fbu);
-        const uint32_t u3 = lookup<CNT>(bd.window(wm1), lut, mask2, fbd);
-        au.advance(wm1, u0);
-        ad.advance(wm1, u1);
-        bu.advance(wm1, u2);
-        bd.advance(wm1, u3);
-    }
-};
-
-constexpr int kHalf = kSliceLen / 2;  // symbols per chain
 
 struct FusedArgs {
     Geo g;

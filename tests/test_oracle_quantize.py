@@ -167,3 +167,42 @@ def test_tensor_quantize_matches_block_by_block_gather(oracle):
                     np.testing.assert_array_equal(codes[i], c1)
                     np.testing.assert_array_equal(mm[i], m1)
                     i += 1
+
+
+def test_float_to_half_matches_numpy_on_a_dense_sweep(oracle):
+    """The oracle's own binary32 -> binary16 rounding against numpy's, on every half value, the midpoints between
+    neighbours (ties), just above and below them, and the overflow and underflow edges."""
+    halves = np.arange(0, 0x7c00, dtype=np.uint16).view(np.float16).astype(np.float32)
+    mids = (halves[:-1].astype(np.float64) + halves[1:].astype(np.float64)) / 2.0
+    cand = [halves, mids.astype(np.float32), np.nextafter(mids.astype(np.float32), np.float32(np.inf)),
+            np.nextafter(mids.astype(np.float32), np.float32(-np.inf)),
+            np.array([65504.0, 65519.99, 65520.0, 65520.01, 1e6, 2.0**-25, np.nextafter(np.float32(2.0**-25), np.float32(1)),
+                      2.0**-26, 0.0, 3.0e-8, 5.9604645e-08], np.float32)]
+    xs = np.concatenate(cand)
+    xs = np.concatenate([xs, -xs])
+    rng = np.random.default_rng(3)
+    pick = rng.choice(len(xs), 6000, replace=False)
+    with np.errstate(over="ignore"):
+        for x in xs[pick]:
+            assert oracle.float_to_half_bits(x) == int(np.float32(x).astype(np.float16).view(np.uint16)), float(x)
+
+
+def test_fp16_reconstruction_is_one_rounding_of_the_binary32_value(oracle):
+    rng = np.random.default_rng(11)
+    for which, k_mode in ((K, 0), (K, 1), (V, 0)):
+        x = (rng.standard_normal((64, 128)) * rng.lognormal(0, 1.0, 128)).astype(np.float16)
+        codes, mm = oracle.quantize_block(which, x, 1e-2, k_mode=k_mode)
+        rec = oracle.reconstruct_block_fp16(which, codes, mm, 1e-2, k_mode=k_mode)
+        mmf = mm.view(np.float16).astype(np.float32)
+        step = (np.float32(2.0) * np.float32(1e-2)) * (mmf[:, 1] - mmf[:, 0])
+        if which == V:
+            mn, st = mmf[:, 0][:, None], step[:, None]
+        elif k_mode == 1:
+            mn, st = mmf[0, 0], step[0]
+        else:
+            mn, st = mmf[:, 0][None, :], step[None, :]
+        expect = (mn + codes.astype(np.float32) * st).astype(np.float16)   # numpy: float32 ops, then one rounding
+        np.testing.assert_array_equal(rec.view(np.uint16), expect.view(np.uint16))
+        # and it stays within the error bound plus half a binary16 ulp of the input
+        exact = oracle.dequantize_block(which, codes, mm, 1e-2, k_mode=k_mode)
+        assert np.abs(rec.astype(np.float64) - exact).max() <= np.abs(exact).max() * 2.0**-11
