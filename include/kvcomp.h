@@ -140,6 +140,14 @@ kvcomp_status kvcomp_get_block(kvcomp_ctx *ctx, int which, int b, int h, int blk
 /* Copy the fp16 buffer (layout [batch][64][n_kv_heads][128]) to h_buf; *h_n_res receives the valid token count. */
 kvcomp_status kvcomp_get_residual(kvcomp_ctx *ctx, int which, uint16_t *h_buf, int *h_n_res, void *stream);
 
+/* Stand-alone decompression, the first stage of the multi-kernel pipeline that Section 4.3 compares the fused
+ * kernel with: writes the whole cache of one tensor (which: 0 = K, 1 = V) as fp16, element (b, t, h, c) at
+ * ((b*seq_stride + t)*n_kv_heads + h)*128 + c, for t < tokens in the cache: blocks reconstructed as
+ * fp16(min + float(code)*width) (binary32 multiply and add, one rounding), then the buffered tokens unchanged.
+ * d_out: DEVICE, caller-owned, 16-byte aligned, batch*seq_stride*n_kv_heads*128 fp16; seq_stride >= tokens
+ * (KVCOMP_ERR_CAPACITY otherwise).  Synchronises the stream once (it reads the largest record size). */
+kvcomp_status kvcomp_decompress(kvcomp_ctx *ctx, int which, void *d_out, int seq_stride, void *stream);
+
 /* Tuning knobs for measurements (0 = library default): number of sequence splits of the fused kernel, LDS staging
  * bytes per wave (records larger than this are decoded straight from global memory). */
 kvcomp_status kvcomp_set_tuning(kvcomp_ctx *ctx, int n_splits, int stage_bytes);

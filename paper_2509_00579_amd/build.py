@@ -10,7 +10,7 @@ HERE = pathlib.Path(__file__).resolve().parent
 CSRC = HERE / "csrc"
 LIB = HERE / "libkvcomp.so"
 OBJ = HERE / "_build"
-SOURCES = ["kvcomp_api.hip", "quantize.hip", "encode.hip", "attn_fused.hip", "attn_fp16.hip"]
+SOURCES = ["kvcomp_api.hip", "quantize.hip", "encode.hip", "attn_fused.hip", "attn_fp16.hip", "decompress.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off",
     "-fhip-fp32-correctly-rounded-divide-sqrt",

@@ -546,6 +546,25 @@ kvcomp_status kvcomp_get_residual(kvcomp_ctx *ctx, int which, uint16_t *h_buf, i
     return KVCOMP_OK;
 }
 
+kvcomp_status kvcomp_decompress(kvcomp_ctx *ctx, int which, void *d_out, int seq_stride, void *stream) {
+    if (!ctx || !d_out) return fail(KVCOMP_ERR_INVALID_ARG, "NULL argument");
+    if (which != 0 && which != 1) return fail(KVCOMP_ERR_INVALID_ARG, "which must be 0 (K) or 1 (V)");
+    if (!aligned16(d_out)) return fail(KVCOMP_ERR_INVALID_ARG, "d_out must be 16-byte aligned");
+    const int tokens = ctx->n_blocks * kBT + ctx->n_res;
+    if (seq_stride < tokens) return fail(KVCOMP_ERR_CAPACITY, "seq_stride %d below the %d tokens in the cache", seq_stride, tokens);
+    if (ctx->n_blocks && !ctx->have_codebook) return fail(KVCOMP_ERR_STATE, "no codebook");
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (ctx->n_blocks) {  // the largest record may have grown through flushes since the last synchronising call
+        kvcomp_status st = read_ctrl(ctx, s);
+        if (st) return st;
+        ctx->max_size16 = std::max(ctx->max_size16, ctx->h_ctrl->max_size16);
+    }
+    const int stage = (int)align_up((size_t)ctx->max_size16 * 16 + 16, 256);
+    HIP_TRY(launch_decompress(ctx->geo, which, static_cast<uint16_t *>(d_out), ctx->n_blocks, ctx->n_res, seq_stride,
+                              stage, s));
+    return KVCOMP_OK;
+}
+
 kvcomp_status kvcomp_set_tuning(kvcomp_ctx *ctx, int n_splits, int stage_bytes) {
     if (!ctx || n_splits < 0 || stage_bytes < 0) return fail(KVCOMP_ERR_INVALID_ARG, "bad argument");
     ctx->tune_splits = n_splits;

@@ -93,6 +93,8 @@ constexpr size_t fused_lds_fixed(int G, int longest) {
 }
 
 // ---- launches implemented in the .hip files ----
+hipError_t launch_decompress(const Geo &g, int which, uint16_t *out, int n_blocks, int n_res, int seq_stride,
+                             int stage_bytes, hipStream_t s);
 hipError_t launch_histogram(const Geo &g, int which, const uint16_t *X, int seq_stride, int n_blk_per_bh,
                             hipStream_t s);
 hipError_t launch_debug_codes(const Geo &g, int which, const uint16_t *X, int seq_stride, int n_blk_per_bh,

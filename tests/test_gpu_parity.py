@@ -378,3 +378,38 @@ def test_block_quant_k(gpu, oracle, H, Hq, max_len):
     st = gc.stats()
     _say(f"  CR {st['compression_ratio']:.3f}, K bits/symbol {st['payload_bits_k'] / (B * H * oc.n_blocks * 8192.0):.2f}")
     gc.close()
+
+
+@pytest.mark.parametrize("B,H,S,k_mode,max_len", [(2, 2, 200, 0, 7), (1, 3, 333, 1, 10), (1, 1, 64, 0, 12)])
+def test_stand_alone_decompression(gpu, oracle, B, H, S, k_mode, max_len):
+    """The decompressed cache (blocks reconstructed in fp16, then the buffered tokens) is bit-identical to the
+    oracle's, and the fp16 attention kernel on it (the multi-kernel pipeline) agrees with the oracle's attention up
+    to the fp16 rounding of the reconstructed values."""
+    _say(f"decompress B={B} H={H} S={S} k_mode={k_mode} max code word {max_len}")
+    Kx, Vx = W.make_kv(B, H, S, 61)
+    oc = oracle.OracleCache(B, H, H, S + 64, 1e-2, 2e-2, k_mode, max_len)
+    gc = gpu.KVCompCache(B, H, H, S + 64, 1e-2, 2e-2, k_mode=k_mode, max_code_len=max_len)
+    oc.build_codebook(Kx, Vx)
+    oc.compress_blocks(Kx, Vx)
+    gc.build_codebook(_dev(Kx), _dev(Vx))
+    gc.compress_blocks(_dev(Kx), _dev(Vx))
+    kn, vn = W.make_new_tokens(B, H, 5, 61)
+    for t in range(5):
+        oc.append_token(kn[t], vn[t])
+        gc.append_token(_dev(kn[t]), _dev(vn[t]))
+    tokens = S + 5
+    dec = {}
+    for which in (K, V):
+        ref = oc.decompress(which)
+        got = gc.decompress(which, tokens)
+        assert tuple(got.shape) == ref.shape == (B, tokens, H, 128)
+        np.testing.assert_array_equal(got.cpu().numpy().view(np.uint16), ref.view(np.uint16))
+        dec[which] = got
+    with pytest.raises(gpu.KvcompError) as e:
+        gc.decompress(K, tokens - 1)
+    assert e.value.status == gpu.ERR_CAPACITY
+    q = W.make_queries(B, H, 1, 61)[0]
+    out = gpu.BaselineFp16Attention(B, H, H)(dec[K], dec[V], _dev(q), SCALE).cpu().numpy()
+    ref = np.asarray(oc.attn_decode(q, SCALE))
+    assert np.abs(out - ref).max() <= 2e-3 * max(1.0, np.abs(ref).max())   # values rounded to fp16: 2^-11 relative each
+    gc.close()
