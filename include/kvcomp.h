@@ -148,6 +148,11 @@ kvcomp_status kvcomp_get_residual(kvcomp_ctx *ctx, int which, uint16_t *h_buf, i
  * (KVCOMP_ERR_CAPACITY otherwise).  Synchronises the stream once (it reads the largest record size). */
 kvcomp_status kvcomp_decompress(kvcomp_ctx *ctx, int which, void *d_out, int seq_stride, void *stream);
 
+/* The same call with the decoder of Section 3.3.1 instead of the table decoder: a branch-free walk of the
+ * array-based Huffman tree, one stream bit per step.  Same arguments, same output bit for bit; kept to compare the
+ * two decoders on this hardware. */
+kvcomp_status kvcomp_decompress_tree_walk(kvcomp_ctx *ctx, int which, void *d_out, int seq_stride, void *stream);
+
 /* Tuning knobs for measurements (0 = library default): number of sequence splits of the fused kernel, LDS staging
  * bytes per wave (records larger than this are decoded straight from global memory). */
 kvcomp_status kvcomp_set_tuning(kvcomp_ctx *ctx, int n_splits, int stage_bytes);

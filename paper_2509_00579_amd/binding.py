@@ -57,6 +57,7 @@ SIGNATURES = {
     "kvcomp_get_block": (_i, [_vp, _i, _i, _i, _i, _vp, C.c_size_t, C.POINTER(C.c_size_t), _vp]),
     "kvcomp_get_residual": (_i, [_vp, _i, _vp, C.POINTER(_i), _vp]),
     "kvcomp_decompress": (_i, [_vp, _i, _vp, _i, _vp]),
+    "kvcomp_decompress_tree_walk": (_i, [_vp, _i, _vp, _i, _vp]),
     "kvcomp_set_tuning": (_i, [_vp, _i, _i]),
     "kvcomp_set_profiling": (_i, [_vp, _i]),
     "kvcomp_get_profile": (_i, [_vp, C.POINTER(_i), C.POINTER(C.c_double)]),
@@ -207,12 +208,14 @@ class KVCompCache:
         _check(self.lib.kvcomp_get_residual(self.h, which, buf.ctypes.data_as(C.c_void_p), C.byref(n), _stream()))
         return buf.view(np.float16)[:, : n.value], n.value
 
-    def decompress(self, which, tokens, out=None):
-        """The cache of one tensor as fp16 [B, tokens, H, 128] (stand-alone decompression)."""
+    def decompress(self, which, tokens, out=None, tree_walk=False):
+        """The cache of one tensor as fp16 [B, tokens, H, 128] (stand-alone decompression; tree_walk: with the
+        bit-serial decoder instead of the table decoder)."""
         if out is None:
             out = torch.empty((self.B, tokens, self.H, D), dtype=torch.float16, device=self.device)
         assert out.is_cuda and out.is_contiguous() and out.dtype == torch.float16
-        _check(self.lib.kvcomp_decompress(self.h, which, C.c_void_p(out.data_ptr()), int(out.shape[1]), _stream()))
+        fn = self.lib.kvcomp_decompress_tree_walk if tree_walk else self.lib.kvcomp_decompress
+        _check(fn(self.h, which, C.c_void_p(out.data_ptr()), int(out.shape[1]), _stream()))
         return out
 
     def set_tuning(self, n_splits=0, stage_bytes=0):

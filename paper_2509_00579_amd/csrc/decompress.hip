@@ -18,16 +18,38 @@ struct DecompArgs {
     uint32_t mask2;
 };
 
+// One chain of the bit-serial decoder of Section 3.3.1: one stream bit per step, node = tree[node][bit], a symbol
+// is emitted and the walk restarts at the root when a leaf is reached; no branch depends on the data.
+struct TreeWalk {
+    int node, count;  // current inner node, symbols emitted so far
+    __device__ __forceinline__ void init() { node = 0; count = 0; }
+    // returns the symbol (>= 0) if this bit completed a code word of a chain that still has symbols to give, else -1
+    __device__ __forceinline__ int step(const int16_t *tree, uint32_t bit) {
+        const int next = tree[node * 2 + (int)bit];
+        const bool leaf = next < 0, live = count < kHalf;
+        node = leaf ? 0 : next;
+        const int sym = (leaf && live) ? ~next : -1;
+        count += (leaf && live) ? 1 : 0;
+        return sym;
+    }
+};
+
+// LB > 0: table decoder compiled for code words of up to LB bits.  LB == 0: the paper's bit-serial tree walk, kept for
+// an A/B on this hardware.
 template <int LB>
 __global__ __launch_bounds__(64 * kDecWaves) void decompress_kernel(DecompArgs a) {
-    constexpr int NS = kWindowBits / LB;
-    __shared__ __attribute__((aligned(16))) uint16_t lut_s[1 << LB];
+    constexpr bool kTree = LB == 0;
+    constexpr int NS = kTree ? 1 : kWindowBits / (kTree ? 1 : LB);
+    __shared__ __attribute__((aligned(16))) uint16_t lut_s[kTree ? 512 : (1 << LB)];
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];  // per wave: record staging, then the code tile
     const Geo &g = a.g;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int which = a.which;
-    {
+    if constexpr (kTree) {  // the tree of this tensor: 256 nodes x 2 children, 16 bits each
+        const uint4 *src = reinterpret_cast<const uint4 *>(g.tree + which * 512);
+        for (int i = tid; i < 64; i += 64 * kDecWaves) reinterpret_cast<uint4 *>(lut_s)[i] = src[i];
+    } else {
         const uint4 *src = reinterpret_cast<const uint4 *>(g.lut + which * kLutSize);
         uint4 *dst = reinterpret_cast<uint4 *>(lut_s);
         const int n16 = max(1, (2 << g.lut_bits[which]) / 16);
@@ -72,18 +94,55 @@ __global__ __launch_bounds__(64 * kDecWaves) void decompress_kernel(DecompArgs a
             tile[dn * kTileRow + 2 * lane + 1] = (uint8_t)(fd >> 8);
         }
     };
+    if constexpr (kTree) {
+        // All four chains of the lane walk one bit per step; a window gives 31 bits, then every reader moves on by
+        // 31.  A chain stops emitting after its 32 symbols; the wave runs until every chain of every lane is done.
+        const int16_t *tree = reinterpret_cast<const int16_t *>(lut_s);
+        TreeWalk tw[4];
+#pragma unroll
+        for (int c = 0; c < 4; c++) tw[c].init();
+        auto emit = [&](int c, int sym, int idx) {  // chain c emitted its idx-th symbol
+            if (sym < 0) return;
+            const int pos = (c & 1) ? kSliceLen - 1 - idx : idx;  // chains 1 and 3 read downwards
+            if (which == 0) tile[lane * kTileRow + (c >> 1) * kSliceLen + pos] = (uint8_t)sym;
+            else tile[pos * kTileRow + 2 * lane + (c >> 1)] = (uint8_t)sym;
+        };
+        // 32 symbols of at most 12 bits need at most 13 windows of 31 bits: the bound also ends the loop on a
+        // damaged table
+        bool busy = true;
+        for (int round = 0; round < 16 && busy; round++) {
+            uint32_t w0 = qd.au.window(wm1) >> kJunkBits, w1 = qd.ad.window(wm1) >> kJunkBits;
+            uint32_t w2 = qd.bu.window(wm1) >> kJunkBits, w3 = qd.bd.window(wm1) >> kJunkBits;
+#pragma unroll 1
+            for (int k = 0; k < kWindowBits; k++) {
+                const int i0 = tw[0].count, i1 = tw[1].count, i2 = tw[2].count, i3 = tw[3].count;
+                emit(0, tw[0].step(tree, w0 & 1u), i0);
+                emit(1, tw[1].step(tree, w1 & 1u), i1);
+                emit(2, tw[2].step(tree, w2 & 1u), i2);
+                emit(3, tw[3].step(tree, w3 & 1u), i3);
+                w0 >>= 1; w1 >>= 1; w2 >>= 1; w3 >>= 1;
+            }
+            qd.au.advance(wm1, kWindowBits);
+            qd.ad.advance(wm1, kWindowBits);
+            qd.bu.advance(wm1, kWindowBits);
+            qd.bd.advance(wm1, kWindowBits);
+            const bool mine = tw[0].count < kHalf || tw[1].count < kHalf || tw[2].count < kHalf || tw[3].count < kHalf;
+            busy = __any(mine);
+        }
+    } else {
 #pragma unroll 2
-    for (int r = 0; r < kRounds; r++) {
-        uint32_t fau[NS], fad[NS], fbu[NS], fbd[NS];
-        qd.step<NS>(wm1, lut, a.mask2, fau, fad, fbu, fbd);
+        for (int r = 0; r < kRounds; r++) {
+            uint32_t fau[NS], fad[NS], fbu[NS], fbd[NS];
+            qd.step<NS>(wm1, lut, a.mask2, fau, fad, fbu, fbd);
 #pragma unroll
-        for (int k = 0; k < NS; k++) put(r * NS + k, fau[k], fad[k], fbu[k], fbd[k]);
-    }
-    if constexpr (kTail > 0) {
-        uint32_t fau[kTail], fad[kTail], fbu[kTail], fbd[kTail];
-        qd.step<kTail>(wm1, lut, a.mask2, fau, fad, fbu, fbd);
+            for (int k = 0; k < NS; k++) put(r * NS + k, fau[k], fad[k], fbu[k], fbd[k]);
+        }
+        if constexpr (kTail > 0) {
+            uint32_t fau[kTail], fad[kTail], fbu[kTail], fbd[kTail];
+            qd.step<kTail>(wm1, lut, a.mask2, fau, fad, fbu, fbd);
 #pragma unroll
-        for (int k = 0; k < kTail; k++) put(kRounds * NS + k, fau[k], fad[k], fbu[k], fbd[k]);
+            for (int k = 0; k < kTail; k++) put(kRounds * NS + k, fau[k], fad[k], fbu[k], fbd[k]);
+        }
     }
     wave_sync();
     // dequantize and write: instruction i covers tokens 4 i + lane / 16, channels 8 (lane % 16) .. + 7 (four rows)
@@ -150,7 +209,7 @@ static hipError_t launch_dec(const DecompArgs &a, size_t lds, int grid, hipStrea
 }
 
 hipError_t launch_decompress(const Geo &g, int which, uint16_t *out, int n_blocks, int n_res, int seq_stride,
-                             int stage_bytes, hipStream_t s) {
+                             int stage_bytes, int tree_walk, hipStream_t s) {
     if (n_blocks > 0) {
         DecompArgs a;
         a.g = g;
@@ -166,6 +225,9 @@ hipError_t launch_decompress(const Geo &g, int which, uint16_t *out, int n_block
         const long long items = (long long)g.B * g.H * n_blocks;
         const int grid = (int)((items + kDecWaves - 1) / kDecWaves);
         hipError_t e;
+        if (tree_walk) {
+            e = launch_dec<0>(a, lds, grid, s);
+        } else
         switch (fused_table_bits(bits)) {
             case 7: e = launch_dec<7>(a, lds, grid, s); break;
             case 8: e = launch_dec<8>(a, lds, grid, s); break;

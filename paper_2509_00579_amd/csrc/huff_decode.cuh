@@ -168,8 +168,6 @@ __device__ __forceinline__ uint32_t lookup(uint32_t win, const char *lut, uint32
 
 // the symbol of a table entry as fp32 (one v_cvt_f32_ubyte1)
 __device__ __forceinline__ float sym_f32(uint32_t e) { return (float)(e >> 8); }
-// acc + w * symbol
-__device__ __forceinline__ float fma_sym(float w, uint32_t e, float acc) { return fmaf(w, sym_f32(e), acc); }
 
 // The four chains of one lane (two slices x two directions) advance together, CNT symbols each.
 struct Quad {

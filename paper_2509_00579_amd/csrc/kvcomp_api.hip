@@ -65,7 +65,7 @@ int k_header_bytes(const kvcomp_config &c) { return k_minmax_bytes(c) + 2 * kSli
 int code_len_limit(const kvcomp_config &c) { return c.max_code_len ? c.max_code_len : kLutBits; }
 
 struct Layout {
-    size_t ctrl, hist, enc, lut, counters, table, res, partials, payload, total;
+    size_t ctrl, hist, enc, lut, tree, counters, table, res, partials, payload, total;
     size_t payload_cap16;
     int max_blocks;
 };
@@ -82,6 +82,7 @@ Layout make_layout(const kvcomp_config &c) {
     L.hist = at; at += 2 * 256 * 4;
     L.enc = at; at += 4 * 256 * 4;
     L.lut = at; at += 2 * kLutSize * 2;
+    L.tree = at; at += 2 * 256 * 2 * 2;
     L.counters = at; at += align_up(BH * 4, 256);
     L.table = at; at += align_up(2 * BH * (size_t)std::max(L.max_blocks, 1) * sizeof(BlockEntry), 256);
     L.res = at; at += align_up(2 * (size_t)c.batch * kBT * c.n_kv_heads * kD * 2, 256);
@@ -177,6 +178,7 @@ struct kvcomp_ctx {
     uint32_t *h_hist;  // [2][256]
     uint32_t *h_enc;   // [2 tensors][2 directions][256]
     uint16_t *h_lut;   // [2][4096]
+    int16_t *h_tree;   // [2][256][2]
 };
 
 namespace {
@@ -251,6 +253,7 @@ kvcomp_status kvcomp_create(const kvcomp_config *cfg, void *d_arena, size_t aren
     g.hist = reinterpret_cast<uint32_t *>(c->arena + L.hist);
     g.enc = reinterpret_cast<uint32_t *>(c->arena + L.enc);
     g.lut = reinterpret_cast<uint16_t *>(c->arena + L.lut);
+    g.tree = reinterpret_cast<int16_t *>(c->arena + L.tree);
     g.lut_bits[0] = g.lut_bits[1] = kLutBits;
     g.counters = reinterpret_cast<uint32_t *>(c->arena + L.counters);
     g.table = reinterpret_cast<BlockEntry *>(c->arena + L.table);
@@ -258,7 +261,7 @@ kvcomp_status kvcomp_create(const kvcomp_config *cfg, void *d_arena, size_t aren
     g.partials = reinterpret_cast<float *>(c->arena + L.partials);
     g.payload = c->arena + L.payload;
     void *pinned = nullptr;
-    const size_t pin_bytes = 256 + 2 * 256 * 4 + 4 * 256 * 4 + 2 * kLutSize * 2;
+    const size_t pin_bytes = 256 + 2 * 256 * 4 + 4 * 256 * 4 + 2 * kLutSize * 2 + 2 * 256 * 2 * 2;
     hipError_t e = hipHostMalloc(&pinned, pin_bytes, hipHostMallocDefault);
     if (e != hipSuccess) {
         delete c;
@@ -269,6 +272,7 @@ kvcomp_status kvcomp_create(const kvcomp_config *cfg, void *d_arena, size_t aren
     c->h_hist = reinterpret_cast<uint32_t *>(pb + 256);
     c->h_enc = reinterpret_cast<uint32_t *>(pb + 256 + 2048);
     c->h_lut = reinterpret_cast<uint16_t *>(pb + 256 + 2048 + 4096);
+    c->h_tree = reinterpret_cast<int16_t *>(pb + 256 + 2048 + 4096 + 2 * kLutSize * 2);
     // control words, histogram, tables and the Block Offsets Array start at zero
     e = launch_fill_zero(c->arena, L.res, static_cast<hipStream_t>(stream));
     if (e != hipSuccess) {
@@ -335,9 +339,29 @@ kvcomp_status kvcomp_build_codebook(kvcomp_ctx *ctx, const void *d_K, const void
             enc[256 + sy] = ((uint32_t)L << 16) | ctx->code[w][sy];
             for (uint32_t k = 0; k < (1u << (bits - L)); k++) lut[rev | (k << L)] = (uint16_t)((sy << 8) | L);
         }
+        // the same codebook as an array-based tree (Section 3.3.1), for the bit-serial decoder kept for comparison
+        int16_t *tree = ctx->h_tree + 512 * w;
+        std::memset(tree, 0, 512 * 2);
+        int n_nodes = 1;
+        for (int sy = 0; sy < 256; sy++) {
+            const int L = ctx->len[w][sy];
+            if (!L) continue;
+            int node = 0;
+            for (int i = 0; i < L; i++) {
+                const int bit = (ctx->code[w][sy] >> (L - 1 - i)) & 1;  // code words enter the stream first bit first
+                int16_t &child = tree[node * 2 + bit];
+                if (i == L - 1) {
+                    child = (int16_t)~sy;
+                } else {
+                    if (child == 0) child = (int16_t)n_nodes++;
+                    node = child;
+                }
+            }
+        }
     }
     HIP_TRY(hipMemcpyAsync(g.enc, ctx->h_enc, 4 * 256 * 4, hipMemcpyHostToDevice, s));
     HIP_TRY(hipMemcpyAsync(g.lut, ctx->h_lut, 2 * kLutSize * 2, hipMemcpyHostToDevice, s));
+    HIP_TRY(hipMemcpyAsync(g.tree, ctx->h_tree, 2 * 256 * 2 * 2, hipMemcpyHostToDevice, s));
     HIP_TRY(hipStreamSynchronize(s));
     ctx->have_codebook = true;
     return KVCOMP_OK;
@@ -546,7 +570,8 @@ kvcomp_status kvcomp_get_residual(kvcomp_ctx *ctx, int which, uint16_t *h_buf, i
     return KVCOMP_OK;
 }
 
-kvcomp_status kvcomp_decompress(kvcomp_ctx *ctx, int which, void *d_out, int seq_stride, void *stream) {
+static kvcomp_status decompress_impl(kvcomp_ctx *ctx, int which, void *d_out, int seq_stride, int tree_walk,
+                                     void *stream) {
     if (!ctx || !d_out) return fail(KVCOMP_ERR_INVALID_ARG, "NULL argument");
     if (which != 0 && which != 1) return fail(KVCOMP_ERR_INVALID_ARG, "which must be 0 (K) or 1 (V)");
     if (!aligned16(d_out)) return fail(KVCOMP_ERR_INVALID_ARG, "d_out must be 16-byte aligned");
@@ -561,8 +586,16 @@ kvcomp_status kvcomp_decompress(kvcomp_ctx *ctx, int which, void *d_out, int seq
     }
     const int stage = (int)align_up((size_t)ctx->max_size16 * 16 + 16, 256);
     HIP_TRY(launch_decompress(ctx->geo, which, static_cast<uint16_t *>(d_out), ctx->n_blocks, ctx->n_res, seq_stride,
-                              stage, s));
+                              stage, tree_walk, s));
     return KVCOMP_OK;
+}
+
+kvcomp_status kvcomp_decompress(kvcomp_ctx *ctx, int which, void *d_out, int seq_stride, void *stream) {
+    return decompress_impl(ctx, which, d_out, seq_stride, 0, stream);
+}
+
+kvcomp_status kvcomp_decompress_tree_walk(kvcomp_ctx *ctx, int which, void *d_out, int seq_stride, void *stream) {
+    return decompress_impl(ctx, which, d_out, seq_stride, 1, stream);
 }
 
 kvcomp_status kvcomp_set_tuning(kvcomp_ctx *ctx, int n_splits, int stage_bytes) {

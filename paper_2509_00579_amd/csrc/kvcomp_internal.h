@@ -61,6 +61,8 @@ struct Geo {
                              //   [0]: first-bit-first (symbols 0..31 of a slice), [1]: last-bit-first (32..63)
     uint16_t *lut;           // [2][4096] (symbol << 8) | len, indexed by the next lut_bits[t] stream bits
     int lut_bits[2];         // index width of each decode table = longest code word of that codebook
+    int16_t *tree;           // [2][256][2] array-based Huffman tree (Section 3.3.1): child of node n for stream bit b;
+                             //   >= 0: inner node, < 0: leaf holding symbol ~child; the root is node 0
     uint32_t *counters;      // [B*H] split tickets of the fused kernel, zero between launches
     BlockEntry *table;       // [2][B*H][max_blocks]
     uint16_t *res;           // [2][B][64][H][128] fp16
@@ -94,7 +96,7 @@ constexpr size_t fused_lds_fixed(int G, int longest) {
 
 // ---- launches implemented in the .hip files ----
 hipError_t launch_decompress(const Geo &g, int which, uint16_t *out, int n_blocks, int n_res, int seq_stride,
-                             int stage_bytes, hipStream_t s);
+                             int stage_bytes, int tree_walk, hipStream_t s);
 hipError_t launch_histogram(const Geo &g, int which, const uint16_t *X, int seq_stride, int n_blk_per_bh,
                             hipStream_t s);
 hipError_t launch_debug_codes(const Geo &g, int which, const uint16_t *X, int seq_stride, int n_blk_per_bh,

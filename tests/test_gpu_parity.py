@@ -404,6 +404,8 @@ def test_stand_alone_decompression(gpu, oracle, B, H, S, k_mode, max_len):
         got = gc.decompress(which, tokens)
         assert tuple(got.shape) == ref.shape == (B, tokens, H, 128)
         np.testing.assert_array_equal(got.cpu().numpy().view(np.uint16), ref.view(np.uint16))
+        walked = gc.decompress(which, tokens, tree_walk=True)   # the bit-serial tree walk gives the same bits
+        np.testing.assert_array_equal(walked.cpu().numpy().view(np.uint16), ref.view(np.uint16))
         dec[which] = got
     with pytest.raises(gpu.KvcompError) as e:
         gc.decompress(K, tokens - 1)
