@@ -50,6 +50,9 @@ def parse_args():
     ap.add_argument("--k-mode", type=int, default=0, choices=[0, 1],
                     help="0: K quantized channel-wise inside a block (the workloads' definition); 1: one range per K "
                          "block (BlockQuant)")
+    ap.add_argument("--cold", action="store_true",
+                    help="also time the fused and the fp16 kernel with a 512 MiB copy before every launch (caches "
+                         "scrubbed); off by default so that a profile of the default run sees only warm launches")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch a 256 MiB device-to-device copy (reference for rocprofv3 FETCH_SIZE/WRITE_SIZE)")
     return ap.parse_args()
@@ -187,16 +190,18 @@ def main():
 
     # ---- the same launches with the caches scrubbed in between (the compressed cache of the small workloads fits
     # the 256 MiB last-level cache; a 512 MiB copy before every launch evicts it) ----
-    scrub_src = torch.empty(512 << 20, dtype=torch.uint8, device="cuda").fill_(1)
-    scrub_dst = torch.empty_like(scrub_src)
-    cache.set_profiling(True)
-    for i in range(min(T, 8)):
-        scrub_dst.copy_(scrub_src)
-        cache.attn_decode(dq[i], scale, out)
-    cold_launches, cold_total_ms = cache.get_profile()
-    cache.set_profiling(False)
-    cold_kern_ms = cold_total_ms / max(cold_launches, 1)
-    del scrub_src, scrub_dst
+    cold_kern_ms = None
+    if args.cold:
+        scrub_src = torch.empty(512 << 20, dtype=torch.uint8, device="cuda").fill_(1)
+        scrub_dst = torch.empty_like(scrub_src)
+        cache.set_profiling(True)
+        for i in range(min(T, 8)):
+            scrub_dst.copy_(scrub_src)
+            cache.attn_decode(dq[i], scale, out)
+        cold_launches, cold_total_ms = cache.get_profile()
+        cache.set_profiling(False)
+        cold_kern_ms = cold_total_ms / max(cold_launches, 1)
+        del scrub_src, scrub_dst
 
     if args.calibrate_copy:  # a plain copy of known size, so that the HBM byte counters of a --pmc run can be scaled
         src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").fill_(1)
@@ -234,18 +239,20 @@ def main():
     base_ms = ev[0].elapsed_time(ev[1]) / (3 * nrep)
     base_bytes = 2 * B * H * S * 128 * 2 + B * Hq * 128 * (2 + 4)
     # the fp16 kernel with the caches scrubbed before every launch, like the fused kernel above
-    scrub_src = torch.empty(512 << 20, dtype=torch.uint8, device="cuda").fill_(1)
-    scrub_dst = torch.empty_like(scrub_src)
-    cold = []
-    for i in range(8):
-        scrub_dst.copy_(scrub_src)
-        ev[2].record()
-        base(dK, dV, dq[i % T], scale, out)
-        ev[3].record()
-        ev[3].synchronize()
-        cold.append(ev[2].elapsed_time(ev[3]))
-    base_cold_ms = float(np.mean(cold))
-    del scrub_src, scrub_dst
+    base_cold_ms = None
+    if args.cold:
+        scrub_src = torch.empty(512 << 20, dtype=torch.uint8, device="cuda").fill_(1)
+        scrub_dst = torch.empty_like(scrub_src)
+        cold = []
+        for i in range(8):
+            scrub_dst.copy_(scrub_src)
+            ev[2].record()
+            base(dK, dV, dq[i % T], scale, out)
+            ev[3].record()
+            ev[3].synchronize()
+            cold.append(ev[2].elapsed_time(ev[3]))
+        base_cold_ms = float(np.mean(cold))
+        del scrub_src, scrub_dst
 
     # ---- the multi-kernel pipeline (decompress K, decompress V to fp16 in HBM, then the fp16 attention kernel) ----
     tokens_now = cache.stats()["n_blocks"] * 64 + cache.stats()["n_res"]
