@@ -415,3 +415,53 @@ def test_stand_alone_decompression(gpu, oracle, B, H, S, k_mode, max_len):
     ref = np.asarray(oc.attn_decode(q, SCALE))
     assert np.abs(out - ref).max() <= 2e-3 * max(1.0, np.abs(ref).max())   # values rounded to fp16: 2^-11 relative each
     gc.close()
+
+
+@pytest.mark.parametrize("name", ["c2", "c3", "c4"])
+def test_large_configs_full_size_sampled(gpu, oracle, name):
+    """The long-context, grouped-query and 70B-shaped workloads at their full prompt size, in the launch
+    configuration bench.py times (automatic splits, 7-bit code word limit).  The oracle quantizes the whole tensors
+    (the codebooks depend on all of it); records are compared on a sample of blocks and the attention output on two
+    (batch, kv head) pairs, which the oracle recomputes from its own compressed copy of those heads."""
+    w = W.CONFIGS[name]
+    B, H, Hq, S, rel = w.batch, w.n_kv_heads, w.n_q_heads, w.seq, w.rel_eb
+    G = Hq // H
+    _say(f"{name} full size: B={B} H={H} Hq={Hq} S={S}")
+    Kx, Vx = W.make_kv(B, H, S, w.seed)
+    gc = gpu.KVCompCache(B, H, Hq, S + 64, rel, rel, max_code_len=7)
+    dK, dV = _dev(Kx), _dev(Vx)
+    gc.build_codebook(dK, dV)
+    gc.compress_blocks(dK, dV)
+    del dK, dV
+    _say("  gpu compressed; oracle quantizes")
+    NB = S // 64
+    book, codes, mms = {}, {}, {}
+    for which, X in ((K, Kx), (V, Vx)):
+        codes[which], mms[which] = oracle.tensor_quantize(which, X, rel)
+        hist = oracle.histogram(codes[which])
+        np.testing.assert_array_equal(gc.histogram(which).astype(np.uint64), hist)
+        ln, cd, _ = oracle.build_codebook(hist, oracle.n_sym(rel), 7)
+        ln_g, cd_g = gc.codebook(which)
+        np.testing.assert_array_equal(ln_g, ln)
+        np.testing.assert_array_equal(cd_g, cd)
+        book[which] = (ln, cd)
+    rng = np.random.default_rng(5)
+    for _ in range(48):
+        which, b, h, j = int(rng.integers(2)), int(rng.integers(B)), int(rng.integers(H)), int(rng.integers(NB))
+        i = (b * H + h) * NB + j
+        rec = oracle.encode_block(which, codes[which][i], mms[which][i], *book[which])
+        got = gc.get_block(which, b, h, j)
+        assert len(got) == (len(rec) + 15) // 16 * 16
+        np.testing.assert_array_equal(got[: len(rec)], rec)
+        assert not got[len(rec):].any()
+    del codes, mms
+    q = W.make_queries(B, Hq, 1, w.seed)[0]
+    out = gc.attn_decode(_dev(q), SCALE).cpu().numpy()
+    for b, h in ((0, 0), (B - 1, H - 1)):
+        oc = oracle.OracleCache(1, 1, G, S + 64, rel, rel, 0, 7)
+        oc.len, oc.code = [book[K][0], book[V][0]], [book[K][1], book[V][1]]
+        oc.compress_blocks(np.ascontiguousarray(Kx[b:b + 1, :, h:h + 1]), np.ascontiguousarray(Vx[b:b + 1, :, h:h + 1]))
+        ref = oc.attn_decode(np.ascontiguousarray(q[b:b + 1, h * G:(h + 1) * G]), SCALE)
+        err = _attn_close(out[b:b + 1, h * G:(h + 1) * G], ref)
+        _say(f"  (b={b}, h={h}): attention max abs err {err:.3e}")
+    gc.close()
