@@ -616,3 +616,12 @@ int orc_num_threads(void) {
     return 1;
 #endif
 }
+
+/* n >= 1: number of threads for the following calls (timing with one core); no effect without OpenMP */
+void orc_set_num_threads(int n) {
+#ifdef _OPENMP
+    if (n >= 1) omp_set_num_threads(n);
+#else
+    (void)n;
+#endif
+}

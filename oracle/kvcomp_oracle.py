@@ -356,3 +356,9 @@ class OracleCache:
 
 def num_threads():
     return lib().orc_num_threads()
+
+
+def set_num_threads(n):
+    lib().orc_set_num_threads.restype = None
+    lib().orc_set_num_threads.argtypes = [C.c_int]
+    lib().orc_set_num_threads(int(n))
