@@ -425,6 +425,12 @@ __device__ __noinline__ void v_block_global(const uint32_t *rec, const char *lut
 #define KVC_PREFETCH_REGS 8
 #endif
 constexpr int kPrefetchRegs = KVC_PREFETCH_REGS;
+// The part of a record beyond what travels through registers (records above 8 KiB: only with code words near the
+// 12-bit limit).  Out of line so that its address arithmetic is not hoisted into the kernel's register budget.
+__device__ __noinline__ void copy_rest(uint4 *stage, const uint4 *src, uint32_t n16, int lane) {
+    for (uint32_t i = lane + 64 * kPrefetchRegs; i < n16; i += 64) stage[i] = src[i];
+}
+
 struct Prefetch {
     uint4 r[kPrefetchRegs];
     const uint4 *src;
@@ -442,7 +448,7 @@ struct Prefetch {
 #pragma unroll
         for (int i = 0; i < kPrefetchRegs; i++)
             if (lane + 64 * i < n16) stage[lane + 64 * i] = r[i];
-        for (uint32_t i = lane + 64 * kPrefetchRegs; i < n16; i += 64) stage[i] = src[i];
+        if (n16 > 64u * kPrefetchRegs) copy_rest(stage, src, n16, lane);
     }
 };
 
@@ -663,7 +669,10 @@ __global__ __launch_bounds__(kThreads, WavesPerSimd<G>::value) void fused_attn_k
     }
     __syncthreads();
     const int row0 = b * g.Hq + h * G;
-    for (int i = tid; i < G * kD; i += kThreads) {
+    // the thread number is rebuilt from the lane and the (scalar) wave number: nothing of the prologue has to stay
+    // in a register, or be spilled, across the decode loop for the sake of the merge
+    const int tid_m = lane + 64 * wave;
+    for (int i = tid_m; i < G * kD; i += kThreads) {
         const int gg = i / kD, c = i - gg * kD;
         float M = -INFINITY;
 #pragma unroll
@@ -687,7 +696,7 @@ __global__ __launch_bounds__(kThreads, WavesPerSimd<G>::value) void fused_attn_k
         }
     }
     KVC_MARK(6);
-    if (a.n_splits > 1) finish_splits<G, kThreads>(g.partials, g.counters + bh, row0, a.n_splits, a.out, tid);
+    if (a.n_splits > 1) finish_splits<G, kThreads>(g.partials, g.counters + bh, row0, a.n_splits, a.out, tid_m);
     KVC_MARK(7);
 }
 
