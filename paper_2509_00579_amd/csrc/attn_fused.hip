@@ -10,8 +10,9 @@
 //  * lookup-table decode instead of the bit-serial tree walk of Section 3.3.1: all 64 lanes of a wave advance in
 //    symbol lock-step (same trip count for every lane, no divergence), so the dequantization weight of the current
 //    symbol is the same for the whole wave.  It reaches the FMA through a DPP quad broadcast of values fetched from
-//    LDS once per four steps (groups of 1 and 2 query heads) or as the A operand of a 4x4x1 MFMA (groups of 4 and
-//    8), which keeps it off the VALU and nearly off the LDS pipe that the table lookups saturate.  The table is
+//    LDS once per four steps (groups of 1 and 2 query heads) or as the A operand of a 4x4x4 fp16 MFMA over the
+//    symbols of a window (groups of 4 and 8), which keeps it off the VALU and nearly off the LDS pipe that the table
+//    lookups load.  The table is
 //    indexed by as many stream bits as the longest code word of the codebook, and one 32-bit window serves several
 //    symbols (floor(31 / table width)) with no refill test in between;
 //  * the dequantization is folded into the weights: q.k' = sum_c q_c min_c + sum_c (q_c step_c) code_tc, and
