@@ -45,8 +45,9 @@ def parse_args():
     ap.add_argument("--n-splits", type=int, default=0)
     ap.add_argument("--stage-bytes", type=int, default=0)
     ap.add_argument("--max-code-len", type=int, default=0,
-                    help="longest Huffman code word; 0 = one bit more than a fixed-length code of the quantization "
-                         "levels needs (7 at rel_eb 1e-2), which keeps the decode table within two LDS rows")
+                    help="longest Huffman code word; 0 = 7 bits, or the width of a fixed-length code of the quantization "
+                         "levels if that is more (7 for every error bound of the workloads): the 128-entry decode "
+                         "table stays within two LDS rows and a 32-bit window serves four symbols")
     ap.add_argument("--k-mode", type=int, default=0, choices=[0, 1],
                     help="0: K quantized channel-wise inside a block (the workloads' definition); 1: one range per K "
                          "block (BlockQuant)")
@@ -77,7 +78,7 @@ def main():
     scale = 1.0 / np.sqrt(128.0)
     if args.max_code_len == 0:
         levels = int(np.rint(1.0 / (2.0 * np.float32(rel_eb)))) + 1
-        args.max_code_len = int(np.ceil(np.log2(levels))) + 1
+        args.max_code_len = max(7, int(np.ceil(np.log2(levels))))
 
     # ---- inputs: generated on the host from the seed, resident in HBM before any timed region ----
     Kx, Vx = W.make_kv(B, H, S, w.seed)
