@@ -463,7 +463,7 @@ constexpr int kTraceSlots = 8, kTraceWaves = 1 << 15;
 __device__ unsigned long long g_trace[kTraceWaves * kTraceSlots];
 #define KVC_MARK(k)                                                                                              \
     do {                                                                                                         \
-        const unsigned wv = ((blockIdx.y * gridDim.x + blockIdx.x) * kWaves + wave);                             \
+        const unsigned wv = (blockIdx.x * kWaves + wave);                                                        \
         if (lane == 0 && wv < kTraceWaves)                                                                       \
             g_trace[wv * kTraceSlots + (k)] = (k) == 1 || (k) == 5 ? clock64() : wall_clock64();                 \
     } while (0)
@@ -498,7 +498,13 @@ __global__ __launch_bounds__(kThreads, WavesPerSimd<G>::value) void fused_attn_k
 
     KVC_MARK(0);
     const Geo &g = a.g;
-    const int split = blockIdx.x, bh = blockIdx.y;
+    // Workgroups go to the eight XCDs round-robin by their linear number, and each XCD has its own L2.  Numbering the
+    // (batch-head, split) pairs so that an XCD gets a contiguous range of them keeps the splits of one head -- whose
+    // records are neighbours in memory and share cache lines at their ends, and whose partials the last of them
+    // merges -- behind one L2.
+    int item = blockIdx.x;
+    if ((gridDim.x & (kXCDs - 1)) == 0) item = (item & (kXCDs - 1)) * (gridDim.x / kXCDs) + item / kXCDs;
+    const int bh = item / a.n_splits, split = item - bh * a.n_splits;
     const int b = bh / g.H, h = bh - b * g.H;
 
     const int j0 = split * a.blocks_per_split;
@@ -711,7 +717,7 @@ static hipError_t launch_fused_gn(const FusedArgs &a, size_t lds, hipEvent_t ev0
         attr_set = lds;
     }
     if (ev0) (void)hipEventRecord(ev0, s);
-    hipLaunchKernelGGL((fused_attn_kernel<G, LB>), dim3(a.n_splits, a.g.B * a.g.H), dim3(kThreads), lds, s, a);
+    hipLaunchKernelGGL((fused_attn_kernel<G, LB>), dim3(a.n_splits * a.g.B * a.g.H), dim3(kThreads), lds, s, a);
     if (ev1) (void)hipEventRecord(ev1, s);
     return hipGetLastError();
 }

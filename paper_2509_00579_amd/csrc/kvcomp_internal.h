@@ -73,6 +73,7 @@ struct Geo {
 constexpr int kPartialStride = kD + 2;  // o[128], m, l
 constexpr int kMaxSplits = 64;
 constexpr int kCUs = 256;  // compute units of the MI355X
+constexpr int kXCDs = 8;   // accelerator dies, each with its own L2; workgroups are dealt to them round-robin
 // Workgroups (of 4 waves) of the fused kernel that are resident per CU = its waves per SIMD: groups of 4 and 8 query
 // heads carry more accumulators and weights and trade occupancy for registers instead of spilling.
 constexpr int fused_wgs_per_cu(int G) { return G >= 8 ? 2 : G >= 4 ? 3 : 4; }
