@@ -17,10 +17,17 @@ __global__ __launch_bounds__(256) void histogram_kernel(Geo g, const uint16_t *_
     for (int i = tid; i < 256 * 32; i += 256) (&hist[0][0])[i] = 0;
     __syncthreads();
     bool bad = false;
+    TileRaw raw;
+    auto fetch = [&](int blk) {  // clamped to the last block: the loads of the block after the last are harmless
+        const int bl = min(blk, n_blk_total - 1);
+        const int bh = bl / n_blk_per_bh, j = bl - bh * n_blk_per_bh;
+        load_tile_raw(X, seq_stride, g.H, bh / g.H, bh % g.H, j, tid, raw);
+    };
+    fetch(blockIdx.x);
     for (int blk = blockIdx.x; blk < n_blk_total; blk += gridDim.x) {
-        const int bh = blk / n_blk_per_bh, j = blk - bh * n_blk_per_bh;
         TileRegs r;
-        bad |= load_tile(X, seq_stride, g.H, bh / g.H, bh % g.H, j, tid, r);
+        bad |= unpack_tile(raw, r);
+        fetch(blk + gridDim.x);  // the next block's loads travel while this one is quantized
         quantize_tile<WHICH>(r, sh, tid, g.two_eb[WHICH], g.n_sym[WHICH], g.k_units);
 #pragma unroll
         for (int i = 0; i < 4; i++)
@@ -68,7 +75,7 @@ hipError_t launch_histogram(const Geo &g, int which, const uint16_t *X, int seq_
                             hipStream_t s) {
     const int total = g.B * g.H * n_blk_per_bh;
     if (total <= 0) return hipSuccess;
-    const int grid = total < 2048 ? total : 2048;
+    const int grid = total < 1024 ? total : 1024;  // four workgroups per CU (32 KiB of LDS each), several blocks each
     if (which == 0)
         hipLaunchKernelGGL(histogram_kernel<0>, dim3(grid), dim3(256), 0, s, g, X, seq_stride, n_blk_per_bh, total);
     else

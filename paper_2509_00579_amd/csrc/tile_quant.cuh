@@ -33,17 +33,27 @@ __device__ __forceinline__ uint32_t float_to_half_bits(float f) {  // f is exact
     return (uint32_t)__half_as_ushort(__float2half_rn(f));
 }
 
-// Returns true if any loaded value is Inf/NaN.
-__device__ __forceinline__ bool load_tile(const uint16_t *X, int seq_stride, int H, int b, int h, int blk, int tid,
-                                          TileRegs &r) {
-    bool bad = false;
+// The four 16-byte pieces of a thread, still packed: issued early (for the block after the current one) so that the
+// loads travel while the current block is quantized.
+struct TileRaw {
+    uint4 v[4];
+};
+__device__ __forceinline__ void load_tile_raw(const uint16_t *X, int seq_stride, int H, int b, int h, int blk, int tid,
+                                              TileRaw &raw) {
     const int c0 = tile_chan0(tid);
 #pragma unroll
     for (int i = 0; i < 4; i++) {
         const int t = blk * kBT + tile_token(tid, i);
         const size_t off = (((size_t)b * (size_t)seq_stride + (size_t)t) * (size_t)H + (size_t)h) * kD + (size_t)c0;
-        const uint4 v = *reinterpret_cast<const uint4 *>(X + off);
-        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+        raw.v[i] = *reinterpret_cast<const uint4 *>(X + off);
+    }
+}
+// Returns true if any value is Inf/NaN.
+__device__ __forceinline__ bool unpack_tile(const TileRaw &raw, TileRegs &r) {
+    bool bad = false;
+#pragma unroll
+    for (int i = 0; i < 4; i++) {
+        const uint32_t w[4] = {raw.v[i].x, raw.v[i].y, raw.v[i].z, raw.v[i].w};
 #pragma unroll
         for (int k = 0; k < 4; k++) {
             const uint32_t lo = w[k] & 0xffffu, hi = w[k] >> 16;
@@ -53,6 +63,13 @@ __device__ __forceinline__ bool load_tile(const uint16_t *X, int seq_stride, int
         }
     }
     return bad;
+}
+// Returns true if any loaded value is Inf/NaN.
+__device__ __forceinline__ bool load_tile(const uint16_t *X, int seq_stride, int H, int b, int h, int blk, int tid,
+                                          TileRegs &r) {
+    TileRaw raw;
+    load_tile_raw(X, seq_stride, H, b, h, blk, tid, raw);
+    return unpack_tile(raw, r);
 }
 
 __device__ __forceinline__ uint32_t quant_code(float x, float mn, float step, float range, float top) {
