@@ -565,18 +565,19 @@ size_t orc_tensor_encode(int which, int k_mode, const uint8_t *codes, const uint
  * (Section 3.3.2; Section 3.2.3: the whole cache, including the newest vectors, takes part).
  *   arena                 compressed records; k_off16 / v_off16 [B*H][max_blocks] give each block's record offset
  *                         in 16-byte units (the Block Offsets Array of Section 3)
- *   resK / resV           [B][64][H][128] binary16, the first n_res token slots valid
+ *   resK / resV           [B][res_tokens][H][128] binary16, the buffer of uncompressed tokens (Section 3.2.1:
+ *                         up to buffer_size of them), oldest first, the first n_res token slots valid
  *   q                     [B][Hq][128] binary16; query head g reads kv head g / (Hq / H)
  *   out                   [B][Hq][128] binary64
  * Returns 0 or a negative error.
  */
 int orc_attn_decode(int B, int H, int Hq, int k_mode, float rel_eb_k, float rel_eb_v, long n_blocks, long max_blocks,
                     const uint8_t *arena, const uint32_t *k_off16, const uint32_t *v_off16, const uint8_t *lenK,
-                    const uint8_t *lenV, const uint16_t *resK, const uint16_t *resV, int n_res, const uint16_t *q,
-                    double scale, double *out) {
+                    const uint8_t *lenV, const uint16_t *resK, const uint16_t *resV, int res_tokens, int n_res,
+                    const uint16_t *q, double scale, double *out) {
     int G = Hq / H, err = 0;
     long S = n_blocks * BT + n_res, bh;
-    if (G < 1 || G * H != Hq) return -1;
+    if (G < 1 || G * H != Hq || n_res > res_tokens) return -1;
 #pragma omp parallel for schedule(dynamic, 1)
     for (bh = 0; bh < (long)B * H; bh++) {
         int b = (int)(bh / H), h = (int)(bh % H), g, t, c, fin;
@@ -595,7 +596,7 @@ int orc_attn_decode(int B, int H, int Hq, int k_mode, float rel_eb_k, float rel_
         }
         for (t = 0; t < n_res; t++)
             for (c = 0; c < D; c++) {
-                size_t src = (((size_t)b * BT + (size_t)t) * (size_t)H + (size_t)h) * D + (size_t)c;
+                size_t src = (((size_t)b * (size_t)res_tokens + (size_t)t) * (size_t)H + (size_t)h) * D + (size_t)c;
                 Kd[((size_t)n_blocks * BT + (size_t)t) * D + c] = half_value(resK[src], &fin);
                 Vd[((size_t)n_blocks * BT + (size_t)t) * D + c] = half_value(resV[src], &fin);
             }

@@ -62,7 +62,8 @@ def lib():
         L.orc_tensor_encode.argtypes = [C.c_int, C.c_int, u8p, u16p, C.c_long, u8p, u32p, u8p, C.c_size_t, u32p]
         L.orc_attn_decode.restype = C.c_int
         L.orc_attn_decode.argtypes = [C.c_int, C.c_int, C.c_int, C.c_int, C.c_float, C.c_float, C.c_long, C.c_long,
-                                      u8p, u32p, u32p, u8p, u8p, u16p, u16p, C.c_int, u16p, C.c_double, f64p]
+                                      u8p, u32p, u32p, u8p, u8p, u16p, u16p, C.c_int, C.c_int, u16p, C.c_double,
+                                      f64p]
         L.orc_num_threads.restype = C.c_int
         _lib = L
     return _lib
@@ -223,9 +224,20 @@ def tensor_encode(which, codes, minmax, ln, cd, k_mode=0):
 
 
 class OracleCache:
-    """The growing compressed cache of one layer, CPU side (mirror of the four library calls)."""
+    """The growing compressed cache of one layer, CPU side (mirror of the four library calls).
 
-    def __init__(self, batch, n_kv_heads, n_q_heads, max_seq, rel_eb_k, rel_eb_v, k_mode=0, max_code_len=12):
+    buffer_tokens is the maximum buffer size of Section 3.2.1 / Section 4.2 (a multiple of the block size): new
+    tokens stay uncompressed in the buffer, oldest first; the append that brings the buffer to buffer_tokens
+    tokens cuts its oldest block of 64 tokens off and compresses it, so a warm cache keeps the newest
+    buffer_tokens-64 .. buffer_tokens-1 tokens as fp16.  A prompt is stored as if its tokens had been appended
+    one by one.
+    """
+
+    def __init__(self, batch, n_kv_heads, n_q_heads, max_seq, rel_eb_k, rel_eb_v, k_mode=0, max_code_len=12,
+                 buffer_tokens=BT):
+        if buffer_tokens < BT or buffer_tokens % BT:
+            raise ValueError("buffer_tokens must be a positive multiple of the block size")
+        self.W = buffer_tokens
         self.B, self.H, self.Hq = batch, n_kv_heads, n_q_heads
         self.max_blocks = max_seq // BT
         self.max_seq = max_seq
@@ -241,7 +253,7 @@ class OracleCache:
         self.size16 = [np.zeros((batch * n_kv_heads, self.max_blocks), np.uint32) for _ in range(2)]
         self.n_blocks = 0
         self.n_res = 0
-        self.res = [np.zeros((batch, BT, n_kv_heads, D), np.float16) for _ in range(2)]
+        self.res = [np.zeros((batch, buffer_tokens, n_kv_heads, D), np.float16) for _ in range(2)]
         self.payload_bits = [0, 0]
 
     def _mode(self, which):
@@ -277,33 +289,36 @@ class OracleCache:
         B, S, H, _ = Kx.shape
         if S > self.max_seq:
             raise RuntimeError("capacity")
-        NB = S // BT
+        NB = 0 if S < self.W else (S - self.W) // BT + 1  # blocks cut off by S appends to an empty buffer
         for which, X in ((K, Kx), (V, Vx)):
-            m = self._mode(which)
-            codes, mm = tensor_quantize(which, X, self.rel_eb[which], m)
-            recs, sizes = tensor_encode(which, codes, mm, self.len[which], self.code[which], m)
-            idx = [(bh, j) for bh in range(B * H) for j in range(NB)]
-            self._place(which, recs, sizes, idx)
+            if NB:
+                m = self._mode(which)
+                codes, mm = tensor_quantize(which, np.ascontiguousarray(X[:, : NB * BT]), self.rel_eb[which], m)
+                recs, sizes = tensor_encode(which, codes, mm, self.len[which], self.code[which], m)
+                idx = [(bh, j) for bh in range(B * H) for j in range(NB)]
+                self._place(which, recs, sizes, idx)
             self.res[which][:, : S - NB * BT] = X[:, NB * BT:]
         self.n_blocks = NB
         self.n_res = S - NB * BT
 
     def append_token(self, k_new, v_new):
-        """k_new, v_new: float16 [B,H,128].  The call that fills the 64th slot compresses the block at once."""
+        """k_new, v_new: float16 [B,H,128].  The call that fills the buffer compresses its oldest block at once."""
         if self.n_blocks * BT + self.n_res + 1 > self.max_seq:
             raise RuntimeError("capacity")
         self.res[K][:, self.n_res] = k_new
         self.res[V][:, self.n_res] = v_new
         self.n_res += 1
-        if self.n_res == BT:
+        if self.n_res == self.W:
             for which in (K, V):
                 m = self._mode(which)
-                codes, mm = tensor_quantize(which, self.res[which], self.rel_eb[which], m)
+                oldest = np.ascontiguousarray(self.res[which][:, :BT])
+                codes, mm = tensor_quantize(which, oldest, self.rel_eb[which], m)
                 recs, sizes = tensor_encode(which, codes, mm, self.len[which], self.code[which], m)
                 idx = [(bh, self.n_blocks) for bh in range(self.B * self.H)]
                 self._place(which, recs, sizes, idx)
+                self.res[which][:, : self.W - BT] = self.res[which][:, BT:].copy()
             self.n_blocks += 1
-            self.n_res = 0
+            self.n_res -= BT
 
     def attn_decode(self, q, scale):
         """q: float16 [B,Hq,128] -> float64 [B,Hq,128]."""
@@ -314,7 +329,7 @@ class OracleCache:
         r = lib().orc_attn_decode(self.B, self.H, self.Hq, self.k_mode, self.rel_eb[K], self.rel_eb[V], self.n_blocks,
                                   self.max_blocks, _p(arena, C.c_uint8), _p(self.off16[K], C.c_uint32),
                                   _p(self.off16[V], C.c_uint32), _p(self.len[K], C.c_uint8), _p(self.len[V], C.c_uint8),
-                                  _p(rk, C.c_uint16), _p(rv, C.c_uint16), self.n_res, _p(qb, C.c_uint16), float(scale),
+                                  _p(rk, C.c_uint16), _p(rv, C.c_uint16), self.W, self.n_res, _p(qb, C.c_uint16), float(scale),
                                   _p(out, C.c_double))
         if r:
             raise RuntimeError(f"orc_attn_decode failed: {r}")

@@ -97,6 +97,40 @@ def test_small_error_bound_converges_to_raw_attention(oracle):
     assert errs[3] < errs[0] / 4
 
 
+def test_tokens_in_the_buffer_take_part_unquantized(oracle):
+    # Section 3.2.3: the buffered fp16 vectors take part in attention as they are.  With a buffer larger than the
+    # sequence nothing is compressed and the result is plain softmax attention on the raw fp16 cache, whatever the
+    # codebook; with a window of 128 the newest tokens are exact and only the older ones carry quantization error.
+    B, H, Hq, S = 2, 2, 4, 300
+    Kx, Vx = W.make_kv(B, H, S, 16)
+    q = W.make_queries(B, Hq, 1, 16)[0]
+    scale = 1 / np.sqrt(128)
+    oc = oracle.OracleCache(B, H, Hq, 512, 2e-2, 2e-2, buffer_tokens=320)
+    oc.build_codebook(Kx, Vx)
+    oc.compress_blocks(Kx[:, :280], Vx[:, :280])
+    for t in range(280, S):
+        oc.append_token(Kx[:, t], Vx[:, t])
+    assert oc.n_blocks == 0 and oc.n_res == S
+    out = oc.attn_decode(q, scale)
+    for b in range(B):
+        for hq in range(Hq):
+            h = hq // 2
+            ref = _softmax_attention(q[b, hq].astype(np.float64), Kx[b, :, h].astype(np.float64),
+                                     Vx[b, :, h].astype(np.float64), scale)
+            np.testing.assert_allclose(out[b, hq], ref, rtol=1e-12, atol=1e-14)
+    win = oracle.OracleCache(B, H, Hq, 512, 2e-2, 2e-2, buffer_tokens=128)
+    win.build_codebook(Kx, Vx)
+    win.compress_blocks(Kx, Vx)
+    assert win.n_blocks == 3 and win.n_res == 108
+    out = win.attn_decode(q, scale)
+    for b in range(B):
+        for hq in range(Hq):
+            Kd, Vd = _dequantized(oracle, win, K, b, hq // 2), _dequantized(oracle, win, V, b, hq // 2)
+            np.testing.assert_array_equal(Kd[192:], Kx[b, 192:, hq // 2].astype(np.float64))
+            ref = _softmax_attention(q[b, hq].astype(np.float64), Kd, Vd, scale)
+            np.testing.assert_allclose(out[b, hq], ref, rtol=1e-12, atol=1e-14)
+
+
 def test_factored_dot_product_is_an_identity(oracle):
     # q . (min + code*step) == q.min + (q*step).code per channel-wise unit; sum_t p (vmin + vstep code) likewise
     rng = np.random.default_rng(16)

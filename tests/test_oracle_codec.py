@@ -205,6 +205,46 @@ def test_append_equals_prefill_of_the_longer_sequence(oracle):
             inc.append_token(Kx[:, 0], Vx[:, 0])
 
 
+@pytest.mark.parametrize("window", [128, 256])
+def test_larger_buffer_keeps_a_recent_window_uncompressed(oracle, window):
+    # Section 3.2.1 / Section 4.2 (maximum buffer size): the buffer holds up to `window` tokens; when it is full its
+    # oldest block is cut off and compressed.  Blocks are independent of the buffer size (same codebook), so block j
+    # must be the very record that the cache with the 64-token buffer holds; the buffer must hold the newest tokens
+    # in order, and storing a prompt must equal appending its tokens one by one.
+    B, H, S0, extra = 1, 2, 200, 250
+    S = S0 + extra
+    Kx, Vx = W.make_kv(B, H, S, 9)
+    small = oracle.OracleCache(B, H, H, 512, 1e-2, 1e-2)
+    small.build_codebook(Kx[:, :S0], Vx[:, :S0])
+    small.compress_blocks(Kx, Vx)
+    assert small.n_blocks == 7 and small.n_res == 2
+    inc = oracle.OracleCache(B, H, H, 512, 1e-2, 1e-2, buffer_tokens=window)
+    one = oracle.OracleCache(B, H, H, 512, 1e-2, 1e-2, buffer_tokens=window)
+    for oc in (inc, one):
+        oc.build_codebook(Kx[:, :S0], Vx[:, :S0])
+    one.compress_blocks(Kx, Vx)
+    inc.compress_blocks(Kx[:, :S0], Vx[:, :S0])
+    for t in range(S0, S):
+        inc.append_token(Kx[:, t], Vx[:, t])
+        # a warm buffer keeps between window-64 and window-1 tokens
+        tokens = t + 1
+        assert inc.n_blocks * 64 + inc.n_res == tokens
+        assert inc.n_res == tokens if tokens < window else window - 64 <= inc.n_res <= window - 1
+    nb = (S - window) // 64 + 1
+    for oc in (inc, one):
+        assert oc.n_blocks == nb and oc.n_res == S - 64 * nb
+        for which, X in ((K, Kx), (V, Vx)):
+            np.testing.assert_array_equal(oc.res[which][:, : oc.n_res], X[:, 64 * nb:])
+            for h in range(H):
+                for j in range(nb):
+                    np.testing.assert_array_equal(oc.get_block(which, 0, h, j), small.get_block(which, 0, h, j))
+            np.testing.assert_array_equal(oc.decompress(which)[:, : 64 * nb], small.decompress(which)[:, : 64 * nb])
+            np.testing.assert_array_equal(oc.decompress(which)[:, 64 * nb:], X[:, 64 * nb:])
+    assert bytes(inc.arena) != b"" and inc.stats()["residual_bytes"] == 2 * B * H * inc.n_res * 128 * 2
+    with pytest.raises(ValueError):
+        oracle.OracleCache(B, H, H, 512, 1e-2, 1e-2, buffer_tokens=100)
+
+
 def test_a_slice_decodes_from_both_ends_by_hand(oracle):
     # An independent, bit-by-bit prefix decoder written here (dictionary of code words) reads slice 0 of a K record
     # upwards from its start for symbols 0..31 and downwards from its end for symbols 63..32.
