@@ -51,6 +51,9 @@ def parse_args():
     ap.add_argument("--k-mode", type=int, default=0, choices=[0, 1],
                     help="0: K quantized channel-wise inside a block (the workloads' definition); 1: one range per K "
                          "block (BlockQuant)")
+    ap.add_argument("--buffer-tokens", type=int, default=64,
+                    help="capacity of the fp16 buffer of new tokens (multiple of 64): the newest tokens stay "
+                         "uncompressed, the oldest block of a full buffer is compressed; 64 = the workloads' definition")
     ap.add_argument("--cold", action="store_true",
                     help="also time the fused and the fp16 kernel with a 512 MiB copy before every launch (caches "
                          "scrubbed); off by default so that a profile of the default run sees only warm launches")
@@ -88,7 +91,8 @@ def main():
     dq, dkn, dvn = torch.from_numpy(qs).cuda(), torch.from_numpy(kn).cuda(), torch.from_numpy(vn).cuda()
     out = torch.empty((B, Hq, 128), dtype=torch.float32, device="cuda")
     max_seq = (S + T + 63) // 64 * 64
-    cache = binding.KVCompCache(B, H, Hq, max_seq, rel_eb, rel_eb, k_mode=args.k_mode, max_code_len=args.max_code_len)
+    cache = binding.KVCompCache(B, H, Hq, max_seq, rel_eb, rel_eb, k_mode=args.k_mode, max_code_len=args.max_code_len,
+                                buffer_tokens=args.buffer_tokens)
     cache.set_tuning(args.n_splits, args.stage_bytes)
 
     def store():
@@ -132,10 +136,13 @@ def main():
         ns = max(1, min(max(1, 256 * resident // (B * H)), -(-nb0 // 4)))
         bps = -(-(-(-nb0 // ns)) // 4) * 4
         n_splits_est = max(1, min(64, -(-nb0 // bps))) if bps else 1
+    def blocks_of(tokens):  # compressed blocks after `tokens` tokens: the buffer keeps the newest ones
+        return 0 if tokens < args.buffer_tokens else (tokens - args.buffer_tokens) // 64 + 1
+
     step_bytes = []
     for i in range(T):
         tokens = S + i + 1
-        step_bytes.append(decode_bytes(tokens // 64, tokens % 64, n_splits_est))
+        step_bytes.append(decode_bytes(blocks_of(tokens), tokens - 64 * blocks_of(tokens), n_splits_est))
     loop_bytes = float(sum(step_bytes))
 
     # ---- capture the decode loop (launch-bound at this size) in a HIP graph ----
@@ -187,7 +194,7 @@ def main():
     fused_bytes = [b - B * Hq * 128 * 4 - n_splits_est * B * Hq * 130 * 4 for b in step_bytes]  # no out, partials once
     kern_bytes = float(np.mean(fused_bytes))
     achieved = kern_bytes / (kern_ms * 1e-3) / 1e9
-    symbols_per_launch = 2.0 * B * H * float(np.mean([(S + i + 1) // 64 for i in range(T)])) * 8192
+    symbols_per_launch = 2.0 * B * H * float(np.mean([blocks_of(S + i + 1) for i in range(T)])) * 8192
 
     # ---- the same launches with the caches scrubbed in between (the compressed cache of the small workloads fits
     # the 256 MiB last-level cache; a 512 MiB copy before every launch evicts it) ----
@@ -295,7 +302,7 @@ def main():
         oh = H if B * H * S <= 32 * 4096 else max(1, (32 * 4096) // (ob * S))
         oh = min(oh, H)
         oc = oracle.OracleCache(ob, oh, oh * (Hq // H), max_seq, rel_eb, rel_eb, k_mode=args.k_mode,
-                                max_code_len=args.max_code_len)
+                                max_code_len=args.max_code_len, buffer_tokens=args.buffer_tokens)
         oc.build_codebook(Kx[:ob, :, :oh], Vx[:ob, :, :oh])
         oc.compress_blocks(np.ascontiguousarray(Kx[:ob, :, :oh]), np.ascontiguousarray(Vx[:ob, :, :oh]))
         # about 10 s of CPU work: repeat decode steps (fresh query each) until the clock says so, at most 30 s
@@ -344,7 +351,8 @@ def main():
         "data": "synthetic",
         "config": {"workload": f"{args.workload}: batch {B}, {H} kv heads / {Hq} q heads x 128, prompt {S} tokens, "
                                f"{T} decode steps (append one token, then fused decode attention), block 64, "
-                               f"rel_eb {rel_eb}, max code word {args.max_code_len} bits" + (", K BlockQuant" if args.k_mode else ""),
+                               f"rel_eb {rel_eb}, max code word {args.max_code_len} bits" + (", K BlockQuant" if args.k_mode else "")
+                               + (f", fp16 buffer of {args.buffer_tokens} tokens" if args.buffer_tokens != 64 else ""),
                    "decode_loop": "hip graph replay" if graph is not None else "eager launches"},
         "pct_hbm_peak": 100.0 * value / HBM_PEAK_GBPS,
         "compression_ratio": stats0["compression_ratio"],

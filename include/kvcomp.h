@@ -44,7 +44,7 @@ typedef struct {
     int32_t n_kv_heads;   /* KV heads                                                                         */
     int32_t n_q_heads;    /* query heads; n_q_heads / n_kv_heads must be 1, 2, 4 or 8                         */
     int32_t head_dim;     /* must be 128                                                                      */
-    int32_t block_tokens; /* must be 64 (also the size of the fp16 buffer of new tokens, Section 3.2.1)       */
+    int32_t block_tokens; /* must be 64                                                                       */
     int32_t max_seq;      /* capacity in tokens per sequence (prefill + appended)                             */
     float rel_eb_k;       /* relative error bound for K: |x - x'| <= rel_eb * (max - min) of the unit; the    */
     float rel_eb_v;       /*   paper's "relative quantization scale" (Section 4.2) is the bin width = 2*rel_eb */
@@ -53,11 +53,16 @@ typedef struct {
                              to 16 bytes instead of 128 pairs */
     int32_t max_code_len; /* longest Huffman code word allowed, <= 12 and 2^max_code_len >= number of levels  */
                           /*   (0 = default 12); shorter words cost compression but decode faster            */
+    int32_t buffer_tokens; /* capacity of the fp16 buffer of new tokens per sequence (Section 3.2.1; the "maximum
+                             buffer size" of Section 4.2): a multiple of 64 in 64..4096, 0 = 64.  The newest tokens
+                             stay uncompressed; the append that brings the buffer to buffer_tokens tokens cuts its
+                             oldest 64 off as one block and compresses it, so a warm cache holds the newest
+                             buffer_tokens-64 .. buffer_tokens-1 tokens as fp16 */
 } kvcomp_config;
 
 typedef struct {
     int64_t n_blocks;         /* compressed 2D blocks per (batch, head), same for K and V                     */
-    int64_t n_res;            /* tokens in the fp16 buffer (0..63)                                            */
+    int64_t n_res;            /* tokens in the fp16 buffer (0 .. buffer_tokens-1)                             */
     int64_t raw_bytes;        /* fp16 bytes of K and V for all tokens held                                    */
     int64_t record_bytes_k;   /* compressed records of K: headers + code words + padding                      */
     int64_t record_bytes_v;
@@ -97,17 +102,20 @@ kvcomp_status kvcomp_reset(kvcomp_ctx *ctx, int keep_codebook, void *stream);
  * Errors: INVALID_ARG (seq < 64 or > max_seq), NONFINITE, HIP. */
 kvcomp_status kvcomp_build_codebook(kvcomp_ctx *ctx, const void *d_K, const void *d_V, int seq, void *stream);
 
-/* Store stage for the prompt (Section 3.2.2, Figure 4): quantize and Huffman-encode the floor(seq/64) full
- * blocks of every (batch, head), one record per 2D block placed compactly in the arena (K records in (b,h,block)
- * order, then V records), fill the Block Offsets Array; the seq%64 newest tokens go to the fp16 buffer.  The cache
- * must be empty.  Inputs as for kvcomp_build_codebook.  SYNCHRONISES `stream` once at the end (reads back the
+/* Store stage for the prompt (Section 3.2.2, Figure 4): quantize and Huffman-encode the oldest blocks of every
+ * (batch, head), one record per 2D block placed compactly in the arena (K records in (b,h,block) order, then V
+ * records), fill the Block Offsets Array; the newest tokens go to the fp16 buffer.  The split is the one that seq
+ * calls of kvcomp_append_token would leave: floor(seq/64) blocks and seq%64 buffered tokens with the default
+ * buffer, in general n = 0 if seq < buffer_tokens, else floor((seq - buffer_tokens)/64) + 1 blocks and seq - 64 n
+ * buffered tokens.  The cache must be empty.  Inputs as for kvcomp_build_codebook.  SYNCHRONISES `stream` once at the end (reads back the
  * arena tail and the largest record size, and the non-finite flag).
  * Errors: STATE (no codebook / cache not empty), CAPACITY (seq > max_seq), NONFINITE, HIP. */
 kvcomp_status kvcomp_compress_blocks(kvcomp_ctx *ctx, const void *d_K, const void *d_V, int seq, void *stream);
 
 /* Decode-phase store (Section 3.2.1, Section 3.2.3): append one token per sequence.  d_k_new, d_v_new: device fp16
- * [batch, n_kv_heads, 128].  The token is copied into the fp16 buffer; the call that fills the 64th slot compresses
- * that block for every (batch, head) with the existing codebooks and appends the records at the arena tail.
+ * [batch, n_kv_heads, 128].  The token is copied into the fp16 buffer; the call that fills the buffer's last slot
+ * compresses the buffer's oldest 64 tokens as one block for every (batch, head) with the existing codebooks and
+ * appends the records at the arena tail.
  * Stream-ordered, never synchronises.  Errors: STATE (no codebook), CAPACITY (max_seq reached), HIP. */
 kvcomp_status kvcomp_append_token(kvcomp_ctx *ctx, const void *d_k_new, const void *d_v_new, void *stream);
 
@@ -137,7 +145,8 @@ kvcomp_status kvcomp_get_block_entry(kvcomp_ctx *ctx, int which, int b, int h, i
 /* Copy the record of block (b, h, blk) to h_buf (capacity cap); *h_bytes receives its size. */
 kvcomp_status kvcomp_get_block(kvcomp_ctx *ctx, int which, int b, int h, int blk, void *h_buf, size_t cap,
                                size_t *h_bytes, void *stream);
-/* Copy the fp16 buffer (layout [batch][64][n_kv_heads][128]) to h_buf; *h_n_res receives the valid token count. */
+/* Copy the fp16 buffer to h_buf, layout [batch][buffer_tokens][n_kv_heads][128] with the oldest buffered token
+ * first; *h_n_res receives the valid token count. */
 kvcomp_status kvcomp_get_residual(kvcomp_ctx *ctx, int which, uint16_t *h_buf, int *h_n_res, void *stream);
 
 /* Stand-alone decompression, the first stage of the multi-kernel pipeline that Section 4.3 compares the fused

@@ -24,7 +24,7 @@ OK, ERR_INVALID_ARG, ERR_STATE, ERR_CAPACITY, ERR_HIP, ERR_NONFINITE = 0, -1, -2
 class Config(C.Structure):
     _fields_ = [("batch", C.c_int32), ("n_kv_heads", C.c_int32), ("n_q_heads", C.c_int32), ("head_dim", C.c_int32),
                 ("block_tokens", C.c_int32), ("max_seq", C.c_int32), ("rel_eb_k", C.c_float), ("rel_eb_v", C.c_float),
-                ("k_mode", C.c_int32), ("max_code_len", C.c_int32)]
+                ("k_mode", C.c_int32), ("max_code_len", C.c_int32), ("buffer_tokens", C.c_int32)]
 
 
 class Stats(C.Structure):
@@ -107,17 +107,21 @@ def _dev_fp16(t, shape):
     return C.c_void_p(t.data_ptr())
 
 
-def make_config(batch, n_kv_heads, n_q_heads, max_seq, rel_eb_k, rel_eb_v, k_mode=0, max_code_len=0):
-    return Config(batch, n_kv_heads, n_q_heads, D, BT, max_seq, rel_eb_k, rel_eb_v, k_mode, max_code_len)
+def make_config(batch, n_kv_heads, n_q_heads, max_seq, rel_eb_k, rel_eb_v, k_mode=0, max_code_len=0,
+                buffer_tokens=0):
+    return Config(batch, n_kv_heads, n_q_heads, D, BT, max_seq, rel_eb_k, rel_eb_v, k_mode, max_code_len,
+                  buffer_tokens)
 
 
 class KVCompCache:
     """One layer's compressed KV cache on the GPU: the four calls of the hot path plus the parity exports."""
 
     def __init__(self, batch, n_kv_heads, n_q_heads, max_seq, rel_eb_k, rel_eb_v, k_mode=0, max_code_len=0,
-                 device="cuda:0"):
+                 buffer_tokens=0, device="cuda:0"):
         self.lib = load()
-        self.cfg = make_config(batch, n_kv_heads, n_q_heads, max_seq, rel_eb_k, rel_eb_v, k_mode, max_code_len)
+        self.cfg = make_config(batch, n_kv_heads, n_q_heads, max_seq, rel_eb_k, rel_eb_v, k_mode, max_code_len,
+                               buffer_tokens)
+        self.buffer_tokens = buffer_tokens or BT
         self.B, self.H, self.Hq, self.max_seq = batch, n_kv_heads, n_q_heads, max_seq
         self.device = torch.device(device)
         nbytes = self.lib.kvcomp_arena_bytes(C.byref(self.cfg))
@@ -203,7 +207,7 @@ class KVCompCache:
         return buf[: n.value].copy()
 
     def residual(self, which):
-        buf = np.zeros((self.B, BT, self.H, D), np.uint16)
+        buf = np.zeros((self.B, self.buffer_tokens, self.H, D), np.uint16)
         n = C.c_int()
         _check(self.lib.kvcomp_get_residual(self.h, which, buf.ctypes.data_as(C.c_void_p), C.byref(n), _stream()))
         return buf.view(np.float16)[:, : n.value], n.value

@@ -34,7 +34,7 @@ struct FusedArgs {
     const uint16_t *q;
     float *out;
     float scale;
-    int n_blocks, n_res, blocks_per_split, n_splits, stage_bytes;
+    int n_blocks, res_head, n_res, blocks_per_split, n_splits, stage_bytes;
     uint32_t mask2[2];
 };
 
@@ -420,6 +420,101 @@ __device__ __noinline__ void v_block_global(const uint32_t *rec, const char *lut
     v_block<G, NS>(rec, lut, mask2, wts, p, two_eb, lane, st);
 }
 
+constexpr int kWaves = 4;
+constexpr int kThreads = 64 * kWaves;
+
+// The buffered fp16 tokens (Section 3.2.3: the newest vectors take part too), in units of 16 tokens; this wave takes
+// units first_unit, first_unit + unit_step, ...  Token r of the buffer sits in slot (res_head + r) mod res_tokens;
+// res_head is a multiple of 64, so a unit never wraps.
+// A unit is read with 4 coalesced loads per tensor (one instruction = 4 rows of 256 bytes: lane = row l/16, 16-byte
+// piece l%16), K and V together and all in flight at once: a single wave has nothing else to hide the memory
+// latency with, and small units spread the buffer over many waves.  Scores of row 4i + l/16 are formed by a sum over
+// the row's 16 lanes, which is also the layout the V rows arrive in; the channel sums are then folded over the four
+// row groups and handed to the lanes that own them (lane l: channels 2l, 2l+1).
+// Out of line: it runs once, after the decode loop, and must not weigh on that loop's registers.
+constexpr int kUnitTokens = 16;
+template <int G>
+__device__ __noinline__ void buffered_tokens(const uint16_t *res, int res_tokens, int B, int H, int b, int h,
+                                             int res_head, int n_res, int first_unit, int unit_step,
+                                             const float *qf, float scale, int lane, Soft<G> &st) {
+    const size_t res_tensor = (size_t)B * res_tokens * H * kD;
+    const size_t row4 = (size_t)4 * H * kD;  // elements from one load to the next
+    const int n_units = (n_res + kUnitTokens - 1) / kUnitTokens;
+    const int grp = lane >> 4, sub = lane & 15;
+    const bool hi2 = (grp & 2) != 0, hi1 = (grp & 1) != 0;
+    const int owner = 16 * (lane & 3) + (lane >> 2);  // after the fold: the lane that holds channels 2*lane, 2*lane+1
+    for (int u = first_unit; u < n_units; u += unit_step) {
+        const int n_tok = min(kUnitTokens, n_res - u * kUnitTokens);
+        int slot0 = res_head + u * kUnitTokens;
+        if (slot0 >= res_tokens) slot0 -= res_tokens;
+        const uint16_t *kbase = res + (((size_t)b * res_tokens + slot0 + grp) * H + h) * kD + 8 * sub;
+        const uint16_t *vbase = kbase + res_tensor;
+        uint4 rk[4], rv[4];
+#pragma unroll
+        for (int i = 0; i < 4; i++)
+            rk[i] = 4 * i + grp < n_tok ? *reinterpret_cast<const uint4 *>(kbase + i * row4) : make_uint4(0, 0, 0, 0);
+#pragma unroll
+        for (int i = 0; i < 4; i++)
+            rv[i] = 4 * i + grp < n_tok ? *reinterpret_cast<const uint4 *>(vbase + i * row4) : make_uint4(0, 0, 0, 0);
+#pragma unroll 1
+        for (int gg = 0; gg < G; gg++) {
+            float qv[8];
+#pragma unroll
+            for (int k = 0; k < 8; k++) qv[k] = qf[gg * kD + 8 * sub + k];
+            float sc[4], mloc = -INFINITY;
+#pragma unroll
+            for (int i = 0; i < 4; i++) {
+                const uint32_t w[4] = {rk[i].x, rk[i].y, rk[i].z, rk[i].w};
+                float d = 0.f;
+#pragma unroll
+                for (int k = 0; k < 4; k++) {
+                    d = fmaf(qv[2 * k], h2f(w[k] & 0xffffu), d);
+                    d = fmaf(qv[2 * k + 1], h2f(w[k] >> 16), d);
+                }
+                d += dpp_f<kDppXor1>(d);
+                d += dpp_f<kDppXor2>(d);
+                d += dpp_f<kDppHalfMirror>(d);
+                d += dpp_f<kDppMirror>(d);  // the row's 16 lanes all hold its dot product
+                sc[i] = 4 * i + grp < n_tok ? scale * d : -INFINITY;
+                mloc = fmaxf(mloc, sc[i]);
+            }
+            mloc = wave_max(mloc);
+            const float mnew = fmaxf(st.m[gg], mloc);
+            const float alpha = __expf(st.m[gg] - mnew);
+            float psum = 0.f;
+#pragma unroll
+            for (int i = 0; i < 4; i++) {
+                sc[i] = __expf(sc[i] - mnew);
+                psum += sc[i];
+            }
+            st.l[gg] = st.l[gg] * alpha + (sub == 0 ? psum : 0.f);  // each row counted once
+            st.bv[gg] *= alpha;
+            st.m[gg] = mnew;
+            float av[8];
+#pragma unroll
+            for (int k = 0; k < 8; k++) av[k] = 0.f;
+#pragma unroll
+            for (int i = 0; i < 4; i++) {
+                const uint32_t w[4] = {rv[i].x, rv[i].y, rv[i].z, rv[i].w};
+#pragma unroll
+                for (int k = 0; k < 4; k++) {
+                    av[2 * k] = fmaf(sc[i], h2f(w[k] & 0xffffu), av[2 * k]);
+                    av[2 * k + 1] = fmaf(sc[i], h2f(w[k] >> 16), av[2 * k + 1]);
+                }
+            }
+            // fold the four row groups: groups 0,1 keep elements 0..3 and groups 2,3 elements 4..7, then each group r
+            // keeps elements 2r, 2r+1 -- the channels 8*sub + 2r, +1 summed over all 16 rows
+            float w4[4], w2[2];
+#pragma unroll
+            for (int k = 0; k < 4; k++) w4[k] = (hi2 ? av[4 + k] : av[k]) + __shfl_xor(hi2 ? av[k] : av[4 + k], 32);
+#pragma unroll
+            for (int k = 0; k < 2; k++) w2[k] = (hi1 ? w4[2 + k] : w4[k]) + __shfl_xor(hi1 ? w4[k] : w4[2 + k], 16);
+            st.acc[gg][0] = st.acc[gg][0] * alpha + __shfl(w2[0], owner);
+            st.acc[gg][1] = st.acc[gg][1] * alpha + __shfl(w2[1], owner);
+        }
+    }
+}
+
 // A record on its way from global memory to the wave's LDS staging area: the first 8 KiB travel through
 // registers (loads issued early, stored to LDS later), the rest is copied at commit time.
 #ifndef KVC_PREFETCH_REGS
@@ -453,8 +548,6 @@ struct Prefetch {
     }
 };
 
-constexpr int kWaves = 4;
-constexpr int kThreads = 64 * kWaves;
 
 // Developer instrumentation, compiled in with -DKVC_TRACE only: wave 0.. of every workgroup records the 100 MHz
 // wall clock at eight points of the kernel (the shader clock at points 1 and 5); kvcomp_trace_read() copies the records to the host.
@@ -623,40 +716,15 @@ __global__ __launch_bounds__(kThreads, WavesPerSimd<G>::value) void fused_attn_k
     }
 
     KVC_MARK(5);
-    // The buffered fp16 tokens (Section 3.2.3: the newest vectors take part too): last split, wave 0.
-    if (split == a.n_splits - 1 && wave == 0 && a.n_res > 0) {
-        const size_t res_tensor = (size_t)g.B * kBT * g.H * kD;
-        float acc[G], pr[G];
-#pragma unroll
-        for (int gg = 0; gg < G; gg++) acc[gg] = 0.f;
-        if (lane < a.n_res) {
-            const uint16_t *kr = g.res + (((size_t)b * kBT + lane) * g.H + h) * kD;
-            for (int c = 0; c < kD; c += 8) {
-                const uint4 v = *reinterpret_cast<const uint4 *>(kr + c);
-                const uint32_t w[4] = {v.x, v.y, v.z, v.w};
-#pragma unroll
-                for (int k = 0; k < 4; k++) {
-                    const float x0 = h2f(w[k] & 0xffffu), x1 = h2f(w[k] >> 16);
-#pragma unroll
-                    for (int gg = 0; gg < G; gg++) {
-                        acc[gg] = fmaf(qf[gg * kD + c + 2 * k], x0, acc[gg]);
-                        acc[gg] = fmaf(qf[gg * kD + c + 2 * k + 1], x1, acc[gg]);
-                    }
-                }
-            }
-        }
-#pragma unroll
-        for (int gg = 0; gg < G; gg++) pr[gg] = st.update(gg, lane < a.n_res ? a.scale * acc[gg] : -INFINITY);
-        const uint16_t *vr = g.res + res_tensor + (((size_t)b * kBT) * g.H + h) * kD;
-        for (int t = 0; t < a.n_res; t++) {
-            const uint32_t vv = *reinterpret_cast<const uint32_t *>(vr + (size_t)t * g.H * kD + 2 * lane);
-            const float v0 = h2f(vv & 0xffffu), v1 = h2f(vv >> 16);
-#pragma unroll
-            for (int gg = 0; gg < G; gg++) {
-                const float pw = bcast(pr[gg], t);
-                st.acc[gg][0] = fmaf(pw, v0, st.acc[gg][0]);
-                st.acc[gg][1] = fmaf(pw, v1, st.acc[gg][1]);
-            }
+    // the buffered fp16 tokens in units of 16: unit u goes to split n_splits-1 - u % n_splits (the last split is the
+    // short one), there to the waves in turn, starting after the wave that took the split's last block
+    if (a.n_res > 0) {
+        const int first = a.n_splits - 1 - split + a.n_splits * ((wave - (j1 - j0)) & (kWaves - 1));
+        if (first * kUnitTokens < a.n_res) {
+            Soft<G> st_tmp = st;
+            buffered_tokens<G>(g.res, g.res_tokens, g.B, g.H, b, h, a.res_head, a.n_res, first, kWaves * a.n_splits, qf,
+                               a.scale, lane, st_tmp);
+            st = st_tmp;
         }
     }
     wave_sync();
@@ -733,14 +801,15 @@ static hipError_t launch_fused_g(const FusedArgs &a, int longest, size_t lds, hi
     }
 }
 
-hipError_t launch_fused_attn(const Geo &g, const uint16_t *q, float scale, float *out, int n_blocks, int n_res,
-                             int n_splits, int stage_bytes, hipEvent_t ev0, hipEvent_t ev1, hipStream_t s) {
+hipError_t launch_fused_attn(const Geo &g, const uint16_t *q, float scale, float *out, int n_blocks, int res_head,
+                             int n_res, int n_splits, int stage_bytes, hipEvent_t ev0, hipEvent_t ev1, hipStream_t s) {
     FusedArgs a;
     a.g = g;
     a.q = q;
     a.out = out;
     a.scale = scale;
     a.n_blocks = n_blocks;
+    a.res_head = res_head;
     a.n_res = n_res;
     a.blocks_per_split = n_blocks > 0 ? (n_blocks + n_splits - 1) / n_splits : 0;
     a.n_splits = n_blocks > 0 ? (n_blocks + a.blocks_per_split - 1) / a.blocks_per_split : 1;

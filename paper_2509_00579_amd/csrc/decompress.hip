@@ -183,14 +183,21 @@ __global__ __launch_bounds__(64 * kDecWaves) void decompress_kernel(DecompArgs a
     }
 }
 
-// the buffered fp16 tokens follow the blocks
-__global__ void decompress_tail_kernel(Geo g, int which, uint16_t *out, int n_blocks, int n_res, int seq_stride) {
-    const size_t res_tensor = (size_t)g.B * kBT * g.H * kD;
-    const size_t n16 = (size_t)g.B * n_res * g.H * kD / 8;  // 16-byte units
+// the buffered fp16 tokens follow the blocks: token r of the buffer (oldest first) sits in slot
+// (res_head + r) mod res_tokens of the ring
+__global__ void decompress_tail_kernel(Geo g, int which, uint16_t *out, int n_blocks, int res_head, int n_res,
+                                       int seq_stride) {
+    const size_t res_tensor = (size_t)g.B * g.res_tokens * g.H * kD;
+    const size_t per_tok = (size_t)g.H * kD / 8;  // 16-byte units
+    const size_t per_b = (size_t)n_res * per_tok;
+    const size_t n16 = (size_t)g.B * per_b;
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += (size_t)gridDim.x * blockDim.x) {
-        const size_t per_b = (size_t)n_res * g.H * kD / 8;
         const size_t b = i / per_b, rem = i - b * per_b;  // rem indexes [r][h][c/8]
-        const uint4 v = reinterpret_cast<const uint4 *>(g.res + which * res_tensor + b * kBT * g.H * kD)[rem];
+        const size_t r = rem / per_tok, in_tok = rem - r * per_tok;
+        size_t slot = (size_t)res_head + r;
+        if (slot >= (size_t)g.res_tokens) slot -= (size_t)g.res_tokens;
+        const uint4 v = reinterpret_cast<const uint4 *>(g.res + which * res_tensor +
+                                                        (b * g.res_tokens + slot) * g.H * kD)[in_tok];
         reinterpret_cast<uint4 *>(out + ((size_t)b * seq_stride + (size_t)n_blocks * kBT) * g.H * kD)[rem] = v;
     }
 }
@@ -208,7 +215,7 @@ static hipError_t launch_dec(const DecompArgs &a, size_t lds, int grid, hipStrea
     return hipGetLastError();
 }
 
-hipError_t launch_decompress(const Geo &g, int which, uint16_t *out, int n_blocks, int n_res, int seq_stride,
+hipError_t launch_decompress(const Geo &g, int which, uint16_t *out, int n_blocks, int res_head, int n_res, int seq_stride,
                              int stage_bytes, int tree_walk, hipStream_t s) {
     if (n_blocks > 0) {
         DecompArgs a;
@@ -237,7 +244,8 @@ hipError_t launch_decompress(const Geo &g, int which, uint16_t *out, int n_block
         if (e != hipSuccess) return e;
     }
     if (n_res > 0) {
-        hipLaunchKernelGGL(decompress_tail_kernel, dim3(64), dim3(256), 0, s, g, which, out, n_blocks, n_res, seq_stride);
+        hipLaunchKernelGGL(decompress_tail_kernel, dim3(64), dim3(256), 0, s, g, which, out, n_blocks, res_head, n_res,
+                           seq_stride);
         return hipGetLastError();
     }
     return hipSuccess;

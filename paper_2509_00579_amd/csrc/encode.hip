@@ -232,8 +232,9 @@ hipError_t launch_encode(const Geo &g, const uint16_t *XK, const uint16_t *XV, i
 }
 
 // ---- fp16 buffer of the newest tokens (Section 3.2.1) ------------------------------------------------------
-// Buffer layout [tensor][B][64][H][128]: the same as an input tensor of 64 tokens, so a full buffer is compressed
-// by the kernels above without a gather.
+// Buffer layout [tensor][B][res_tokens][H][128]: the same as an input tensor of res_tokens tokens, so a block of the
+// buffer (64 consecutive slots) is compressed by the kernels above without a gather.  res_tokens is the maximum
+// buffer size (a multiple of 64); the host uses the slots as a ring of 64-token blocks.
 __global__ void copy_tail_kernel(Geo g, const uint16_t *__restrict__ XK, const uint16_t *__restrict__ XV, int seq,
                                  int first_tok, int n_tok) {
     const size_t per_tensor = (size_t)g.B * n_tok * g.H * 16;  // 16-byte chunks
@@ -247,7 +248,8 @@ __global__ void copy_tail_kernel(Geo g, const uint16_t *__restrict__ XK, const u
         const int b = (int)(r / n_tok);
         const uint16_t *X = which ? XV : XK;
         const uint4 v = *reinterpret_cast<const uint4 *>(X + (((size_t)b * seq + first_tok + t) * g.H + h) * kD + ch * 8);
-        uint16_t *dst = g.res + (size_t)which * g.B * kBT * g.H * kD + (((size_t)b * kBT + t) * g.H + h) * kD + ch * 8;
+        uint16_t *dst = g.res + (size_t)which * g.B * g.res_tokens * g.H * kD +
+                        (((size_t)b * g.res_tokens + t) * g.H + h) * kD + ch * 8;
         *reinterpret_cast<uint4 *>(dst) = v;
     }
 }
@@ -272,7 +274,8 @@ __global__ void append_kernel(Geo g, const uint16_t *__restrict__ k_new, const u
     const int h = r % g.H;
     const int b = r / g.H;
     const uint16_t *src = (which ? v_new : k_new) + ((size_t)b * g.H + h) * kD + ch * 8;
-    uint16_t *dst = g.res + (size_t)which * g.B * kBT * g.H * kD + (((size_t)b * kBT + slot) * g.H + h) * kD + ch * 8;
+    uint16_t *dst = g.res + (size_t)which * g.B * g.res_tokens * g.H * kD +
+                    (((size_t)b * g.res_tokens + slot) * g.H + h) * kD + ch * 8;
     *reinterpret_cast<uint4 *>(dst) = *reinterpret_cast<const uint4 *>(src);
 }
 

@@ -55,8 +55,13 @@ bool valid_cfg(const kvcomp_config *c) {
         if (c->max_code_len > kLutBits || (1 << c->max_code_len) < levels) return false;
     }
     if ((long long)c->batch * c->n_kv_heads * ((long long)c->max_seq / kBT + 1) > (1ll << 28)) return false;
+    if (c->buffer_tokens != 0 && (c->buffer_tokens < kBT || c->buffer_tokens % kBT || c->buffer_tokens > kMaxBufferTokens))
+        return false;
     return true;
 }
+
+// capacity of the fp16 buffer of new tokens (Section 3.2.1; the maximum buffer size of Section 4.2)
+int buffer_tokens(const kvcomp_config &c) { return c.buffer_tokens ? c.buffer_tokens : kBT; }
 
 // header of a K record: {min,max} pairs (one per channel, or one for the block padded to 16 bytes) + slice bit counts
 int k_minmax_bytes(const kvcomp_config &c) { return c.k_mode == 1 ? 16 : kMinMaxBytesK; }
@@ -85,7 +90,7 @@ Layout make_layout(const kvcomp_config &c) {
     L.tree = at; at += 2 * 256 * 2 * 2;
     L.counters = at; at += align_up(BH * 4, 256);
     L.table = at; at += align_up(2 * BH * (size_t)std::max(L.max_blocks, 1) * sizeof(BlockEntry), 256);
-    L.res = at; at += align_up(2 * (size_t)c.batch * kBT * c.n_kv_heads * kD * 2, 256);
+    L.res = at; at += align_up(2 * (size_t)c.batch * buffer_tokens(c) * c.n_kv_heads * kD * 2, 256);
     L.partials = at; at += align_up((size_t)c.batch * c.n_q_heads * kMaxSplits * kPartialStride * 4, 256);
     L.payload = at;
     const size_t pay = BH * (size_t)L.max_blocks * (worst_k + worst_v) + 256;
@@ -164,6 +169,7 @@ struct kvcomp_ctx {
     uint8_t *arena;
     bool have_codebook;
     int n_blocks, n_res;
+    int res_head;  // ring slot of the oldest buffered token, a multiple of 64
     uint8_t len[2][256];
     uint32_t code[2][256];
     uint32_t max_size16;
@@ -230,7 +236,7 @@ kvcomp_status kvcomp_create(const kvcomp_config *cfg, void *d_arena, size_t aren
     c->lay = L;
     c->arena = static_cast<uint8_t *>(d_arena);
     c->have_codebook = false;
-    c->n_blocks = c->n_res = 0;
+    c->n_blocks = c->n_res = c->res_head = 0;
     c->max_size16 = 0;
     c->tune_splits = c->tune_stage = 0;
     c->profiling = false;
@@ -258,6 +264,7 @@ kvcomp_status kvcomp_create(const kvcomp_config *cfg, void *d_arena, size_t aren
     g.counters = reinterpret_cast<uint32_t *>(c->arena + L.counters);
     g.table = reinterpret_cast<BlockEntry *>(c->arena + L.table);
     g.res = reinterpret_cast<uint16_t *>(c->arena + L.res);
+    g.res_tokens = buffer_tokens(*cfg);
     g.partials = reinterpret_cast<float *>(c->arena + L.partials);
     g.payload = c->arena + L.payload;
     void *pinned = nullptr;
@@ -296,7 +303,7 @@ kvcomp_status kvcomp_reset(kvcomp_ctx *ctx, int keep_codebook, void *stream) {
     if (!ctx) return fail(KVCOMP_ERR_INVALID_ARG, "ctx is NULL");
     hipStream_t s = static_cast<hipStream_t>(stream);
     HIP_TRY(launch_fill_zero(ctx->geo.ctrl, 256, s));
-    ctx->n_blocks = ctx->n_res = 0;
+    ctx->n_blocks = ctx->n_res = ctx->res_head = 0;
     ctx->max_size16 = 0;
     if (!keep_codebook) ctx->have_codebook = false;
     return KVCOMP_OK;
@@ -376,7 +383,9 @@ kvcomp_status kvcomp_compress_blocks(kvcomp_ctx *ctx, const void *d_K, const voi
     if (seq > ctx->cfg.max_seq) return fail(KVCOMP_ERR_CAPACITY, "seq %d exceeds max_seq %d", seq, ctx->cfg.max_seq);
     hipStream_t s = static_cast<hipStream_t>(stream);
     const Geo &g = ctx->geo;
-    const int nb = seq / kBT;
+    // as if the tokens had been appended one by one: the buffer keeps the newest tokens, its oldest block is cut off
+    // whenever it holds res_tokens of them
+    const int nb = seq < g.res_tokens ? 0 : (seq - g.res_tokens) / kBT + 1;
     const uint16_t *K = static_cast<const uint16_t *>(d_K), *V = static_cast<const uint16_t *>(d_V);
     HIP_TRY(launch_encode(g, K, V, seq, nb, 0, s));
     HIP_TRY(launch_copy_tail(g, K, V, seq, nb * kBT, seq - nb * kBT, s));
@@ -388,6 +397,7 @@ kvcomp_status kvcomp_compress_blocks(kvcomp_ctx *ctx, const void *d_K, const voi
     }
     ctx->n_blocks = nb;
     ctx->n_res = seq - nb * kBT;
+    ctx->res_head = 0;
     ctx->max_size16 = ctx->h_ctrl->max_size16;
     return KVCOMP_OK;
 }
@@ -400,13 +410,17 @@ kvcomp_status kvcomp_append_token(kvcomp_ctx *ctx, const void *d_k_new, const vo
         return fail(KVCOMP_ERR_CAPACITY, "max_seq %d reached", ctx->cfg.max_seq);
     hipStream_t s = static_cast<hipStream_t>(stream);
     const Geo &g = ctx->geo;
-    HIP_TRY(launch_append(g, static_cast<const uint16_t *>(d_k_new), static_cast<const uint16_t *>(d_v_new), ctx->n_res, s));
+    const int slot = (ctx->res_head + ctx->n_res) % g.res_tokens;
+    HIP_TRY(launch_append(g, static_cast<const uint16_t *>(d_k_new), static_cast<const uint16_t *>(d_v_new), slot, s));
     ctx->n_res++;
-    if (ctx->n_res == kBT) {  // the buffer is full: compress it as one block per (batch, head) and append the records
-        const uint16_t *rk = g.res, *rv = g.res + (size_t)g.B * kBT * g.H * kD;
-        HIP_TRY(launch_encode(g, rk, rv, kBT, 1, ctx->n_blocks, s));
+    if (ctx->n_res == g.res_tokens) {
+        // the buffer is full: cut its oldest block off, compress it as one block per (batch, head), append the records
+        const uint16_t *rk = g.res + (size_t)ctx->res_head * g.H * kD;
+        const uint16_t *rv = rk + (size_t)g.B * g.res_tokens * g.H * kD;
+        HIP_TRY(launch_encode(g, rk, rv, g.res_tokens, 1, ctx->n_blocks, s));
         ctx->n_blocks++;
-        ctx->n_res = 0;
+        ctx->n_res -= kBT;
+        ctx->res_head = (ctx->res_head + kBT) % g.res_tokens;
     }
     return KVCOMP_OK;
 }
@@ -458,8 +472,8 @@ kvcomp_status kvcomp_attn_decode(kvcomp_ctx *ctx, const void *d_q, float scale, 
         ev1 = ctx->events[ctx->events_used + 1];
         ctx->events_used += 2;
     }
-    HIP_TRY(launch_fused_attn(g, static_cast<const uint16_t *>(d_q), scale, d_out, ctx->n_blocks, ctx->n_res, n_splits,
-                              stage, ev0, ev1, s));
+    HIP_TRY(launch_fused_attn(g, static_cast<const uint16_t *>(d_q), scale, d_out, ctx->n_blocks, ctx->res_head, ctx->n_res,
+                              n_splits, stage, ev0, ev1, s));
     return KVCOMP_OK;
 }
 
@@ -562,9 +576,17 @@ kvcomp_status kvcomp_get_block(kvcomp_ctx *ctx, int which, int b, int h, int blk
 kvcomp_status kvcomp_get_residual(kvcomp_ctx *ctx, int which, uint16_t *h_buf, int *h_n_res, void *stream) {
     if (!ctx || !h_buf || !h_n_res || (which != 0 && which != 1)) return fail(KVCOMP_ERR_INVALID_ARG, "bad argument");
     const Geo &g = ctx->geo;
-    const size_t n = (size_t)g.B * kBT * g.H * kD;
+    const size_t per_tok = (size_t)g.H * kD, per_b = (size_t)g.res_tokens * per_tok;
+    const uint16_t *src = g.res + (size_t)g.B * per_b * which;
+    const size_t first = (size_t)(g.res_tokens - ctx->res_head);  // slots res_head .. end of the ring come first
     hipStream_t s = static_cast<hipStream_t>(stream);
-    HIP_TRY(hipMemcpyAsync(h_buf, g.res + n * which, n * 2, hipMemcpyDeviceToHost, s));
+    for (int b = 0; b < g.B; b++) {
+        HIP_TRY(hipMemcpyAsync(h_buf + b * per_b, src + b * per_b + ctx->res_head * per_tok, first * per_tok * 2,
+                               hipMemcpyDeviceToHost, s));
+        if (ctx->res_head)
+            HIP_TRY(hipMemcpyAsync(h_buf + b * per_b + first * per_tok, src + b * per_b, ctx->res_head * per_tok * 2,
+                                   hipMemcpyDeviceToHost, s));
+    }
     HIP_TRY(hipStreamSynchronize(s));
     *h_n_res = ctx->n_res;
     return KVCOMP_OK;
@@ -585,8 +607,8 @@ static kvcomp_status decompress_impl(kvcomp_ctx *ctx, int which, void *d_out, in
         ctx->max_size16 = std::max(ctx->max_size16, ctx->h_ctrl->max_size16);
     }
     const int stage = (int)align_up((size_t)ctx->max_size16 * 16 + 16, 256);
-    HIP_TRY(launch_decompress(ctx->geo, which, static_cast<uint16_t *>(d_out), ctx->n_blocks, ctx->n_res, seq_stride,
-                              stage, tree_walk, s));
+    HIP_TRY(launch_decompress(ctx->geo, which, static_cast<uint16_t *>(d_out), ctx->n_blocks, ctx->res_head, ctx->n_res,
+                              seq_stride, stage, tree_walk, s));
     return KVCOMP_OK;
 }
 

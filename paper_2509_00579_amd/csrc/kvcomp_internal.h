@@ -11,6 +11,7 @@ constexpr int kBT = 64;        // tokens per 2D block
 constexpr int kTile = kD * kBT;  // symbols per block
 constexpr int kLutBits = 12;   // decode table index width = longest code word allowed
 constexpr int kLutSize = 1 << kLutBits;
+constexpr int kMaxBufferTokens = 4096;  // largest fp16 buffer of new tokens per sequence
 
 // Record layout (Section 3.2.2: per-thread bit counts + one contiguous chunk per 2D block):
 //   K: [128 x {min,max} fp16][128 x u16 slice bits][payload words][pad to 16 B]
@@ -65,7 +66,8 @@ struct Geo {
                              //   >= 0: inner node, < 0: leaf holding symbol ~child; the root is node 0
     uint32_t *counters;      // [B*H] split tickets of the fused kernel, zero between launches
     BlockEntry *table;       // [2][B*H][max_blocks]
-    uint16_t *res;           // [2][B][64][H][128] fp16
+    uint16_t *res;           // [2][B][res_tokens][H][128] fp16 buffer of the newest tokens
+    int res_tokens;          // its capacity per sequence = maximum buffer size (Section 4.2), a multiple of 64
     float *partials;         // [B*Hq][max_splits][kPartialStride]
     uint8_t *payload;        // record arena
 };
@@ -96,7 +98,7 @@ constexpr size_t fused_lds_fixed(int G, int longest) {
 }
 
 // ---- launches implemented in the .hip files ----
-hipError_t launch_decompress(const Geo &g, int which, uint16_t *out, int n_blocks, int n_res, int seq_stride,
+hipError_t launch_decompress(const Geo &g, int which, uint16_t *out, int n_blocks, int res_head, int n_res, int seq_stride,
                              int stage_bytes, int tree_walk, hipStream_t s);
 hipError_t launch_histogram(const Geo &g, int which, const uint16_t *X, int seq_stride, int n_blk_per_bh,
                             hipStream_t s);
@@ -108,8 +110,8 @@ hipError_t launch_encode(const Geo &g, const uint16_t *XK, const uint16_t *XV, i
 hipError_t launch_copy_tail(const Geo &g, const uint16_t *XK, const uint16_t *XV, int seq, int first_tok, int n_tok,
                             hipStream_t s);
 hipError_t launch_append(const Geo &g, const uint16_t *k_new, const uint16_t *v_new, int slot, hipStream_t s);
-hipError_t launch_fused_attn(const Geo &g, const uint16_t *q, float scale, float *out, int n_blocks, int n_res,
-                             int n_splits, int stage_bytes, hipEvent_t ev0, hipEvent_t ev1, hipStream_t s);
+hipError_t launch_fused_attn(const Geo &g, const uint16_t *q, float scale, float *out, int n_blocks, int res_head,
+                             int n_res, int n_splits, int stage_bytes, hipEvent_t ev0, hipEvent_t ev1, hipStream_t s);
 hipError_t launch_baseline_attn(int B, int H, int Hq, const uint16_t *K, const uint16_t *V, int seq, const uint16_t *q,
                                 float scale, float *out, float *partials, uint32_t *counters, int n_splits,
                                 hipStream_t s);

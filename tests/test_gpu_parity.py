@@ -193,6 +193,44 @@ def test_append_path(gpu, oracle):
     gc.close()
 
 
+@pytest.mark.parametrize("B,H,Hq,window,S0,extra", [(2, 2, 2, 192, 200, 260), (1, 2, 8, 128, 70, 200),
+                                                    (1, 1, 8, 1024, 1100, 80), (2, 1, 1, 320, 40, 100)])
+def test_larger_buffer_window(gpu, oracle, B, H, Hq, window, S0, extra):
+    """A buffer of `window` > 64 tokens (Section 3.2.1, maximum buffer size of Section 4.2): the newest tokens stay
+    fp16, the oldest block of a full buffer is compressed.  Records, offsets, buffer contents (oldest first), the
+    decompressed cache and the attention output against the oracle, across several wrap-arounds of the ring."""
+    _say(f"buffer window {window}: B={B} H={H} Hq={Hq}, prompt {S0} + {extra} appended tokens")
+    max_seq = (S0 + extra + 63) // 64 * 64
+    Kx, Vx = W.make_kv(B, H, max(S0, 64), 27)
+    oc = oracle.OracleCache(B, H, Hq, max_seq, 1e-2, 1e-2, buffer_tokens=window)
+    gc = gpu.KVCompCache(B, H, Hq, max_seq, 1e-2, 1e-2, buffer_tokens=window)
+    oc.build_codebook(Kx, Vx)
+    gc.build_codebook(_dev(Kx), _dev(Vx))
+    oc.compress_blocks(Kx[:, :S0], Vx[:, :S0])
+    gc.compress_blocks(_dev(Kx[:, :S0]), _dev(Vx[:, :S0]))
+    _assert_same_cache(oc, gc)
+    kn, vn = W.make_new_tokens(B, H, extra, 27)
+    qs = W.make_queries(B, Hq, extra, 27)
+    dkn, dvn, dq = _dev(kn), _dev(vn), _dev(qs)
+    worst = 0.0
+    for t in range(extra):
+        oc.append_token(kn[t], vn[t])
+        gc.append_token(dkn[t], dvn[t])
+        if t % 23 == 0 or oc.n_res in (window - 64, window - 1) or t == extra - 1:   # before and after every flush
+            worst = max(worst, _attn_close(gc.attn_decode(dq[t], SCALE).cpu().numpy(), oc.attn_decode(qs[t], SCALE)))
+    tokens = S0 + extra
+    assert oc.n_blocks * 64 + oc.n_res == tokens
+    _assert_same_cache(oc, gc)
+    for which in (K, V):
+        got = gc.decompress(which, tokens).cpu().numpy()
+        np.testing.assert_array_equal(got.view(np.uint16), oc.decompress(which).view(np.uint16))
+    _say(f"  blocks {oc.n_blocks}, buffered {oc.n_res}, worst attention error {worst:.2e}")
+    gc.close()
+    for bad in (100, 32, 8192):
+        with pytest.raises(gpu.KvcompError):
+            gpu.KVCompCache(B, H, Hq, max_seq, 1e-2, 1e-2, buffer_tokens=bad)
+
+
 def test_error_paths(gpu):
     import torch
     _say("error paths (all detected on the host or by the kernels' own checks)")
