@@ -117,7 +117,7 @@ class KVCompCache:
     """One layer's compressed KV cache on the GPU: the four calls of the hot path plus the parity exports."""
 
     def __init__(self, batch, n_kv_heads, n_q_heads, max_seq, rel_eb_k, rel_eb_v, k_mode=0, max_code_len=0,
-                 buffer_tokens=0, device="cuda:0"):
+                 buffer_tokens=0, device="cuda:0", arena=None):
         self.lib = load()
         self.cfg = make_config(batch, n_kv_heads, n_q_heads, max_seq, rel_eb_k, rel_eb_v, k_mode, max_code_len,
                                buffer_tokens)
@@ -127,8 +127,11 @@ class KVCompCache:
         nbytes = self.lib.kvcomp_arena_bytes(C.byref(self.cfg))
         if nbytes == 0:
             raise KvcompError(ERR_INVALID_ARG, "invalid configuration")
-        self.arena = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
-        assert self.arena.data_ptr() % 256 == 0
+        if arena is None:
+            arena = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
+        assert arena.is_cuda and arena.dtype == torch.uint8 and arena.is_contiguous() and arena.numel() >= nbytes
+        assert arena.data_ptr() % 256 == 0
+        self.arena = arena
         h = C.c_void_p()
         _check(self.lib.kvcomp_create(C.byref(self.cfg), C.c_void_p(self.arena.data_ptr()), nbytes, _stream(), C.byref(h)))
         self.h = h
@@ -232,6 +235,42 @@ class KVCompCache:
         n, ms = C.c_int(), C.c_double()
         _check(self.lib.kvcomp_get_profile(self.h, C.byref(n), C.byref(ms)))
         return n.value, ms.value
+
+
+class KVCompLayers:
+    """The caches of all layers of a model: one context per layer (Section 3: buffers and codebooks are per layer,
+    the K and the V codebook of a layer are built from that layer's prompt), carved out of a single device
+    allocation.  `layers[i]` is the KVCompCache of layer i; nothing is computed here."""
+
+    def __init__(self, n_layers, batch, n_kv_heads, n_q_heads, max_seq, rel_eb_k, rel_eb_v, device="cuda:0", **kw):
+        lib = load()
+        cfg = make_config(batch, n_kv_heads, n_q_heads, max_seq, rel_eb_k, rel_eb_v, kw.get("k_mode", 0),
+                          kw.get("max_code_len", 0), kw.get("buffer_tokens", 0))
+        per_layer = lib.kvcomp_arena_bytes(C.byref(cfg))
+        if per_layer == 0 or n_layers < 1:
+            raise KvcompError(ERR_INVALID_ARG, "invalid configuration")
+        per_layer = (per_layer + 255) // 256 * 256
+        self.arena = torch.empty(n_layers * per_layer, dtype=torch.uint8, device=torch.device(device))
+        self.layers = [KVCompCache(batch, n_kv_heads, n_q_heads, max_seq, rel_eb_k, rel_eb_v, device=device,
+                                   arena=self.arena[i * per_layer:(i + 1) * per_layer], **kw) for i in range(n_layers)]
+
+    def __len__(self):
+        return len(self.layers)
+
+    def __getitem__(self, i):
+        return self.layers[i]
+
+    def stats(self):
+        """Byte counts summed over the layers, and the overall compression ratio."""
+        per = [c.stats() for c in self.layers]
+        tot = {k: sum(p[k] for p in per) for k in ("raw_bytes", "record_bytes_k", "record_bytes_v", "header_bytes",
+                                                    "offsets_bytes", "residual_bytes", "stored_bytes")}
+        tot["compression_ratio"] = tot["raw_bytes"] / tot["stored_bytes"] if tot["stored_bytes"] else 0.0
+        return tot
+
+    def close(self):
+        for c in self.layers:
+            c.close()
 
 
 class BaselineFp16Attention:

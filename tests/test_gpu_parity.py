@@ -231,6 +231,47 @@ def test_larger_buffer_window(gpu, oracle, B, H, Hq, window, S0, extra):
             gpu.KVCompCache(B, H, Hq, max_seq, 1e-2, 1e-2, buffer_tokens=bad)
 
 
+def test_layers_have_their_own_codebooks(gpu, oracle):
+    """One context per layer in a single allocation (Section 3: codebooks are per layer): every layer matches an oracle
+    cache of its own data, appends to one layer leave the others untouched, and the codebooks differ between layers
+    whose value distributions differ."""
+    _say("three layers in one arena, different data and error bounds per call order")
+    B, H, Hq, S = 1, 2, 4, 200
+    layers = gpu.KVCompLayers(3, B, H, Hq, 320, 1e-2, 2e-2, buffer_tokens=128)
+    assert len(layers) == 3
+    data, ocs = [], []
+    for i in range(3):
+        Kx, Vx = W.make_kv(B, H, S, 70 + i)
+        if i == 1:   # a layer with a narrow bell inside each unit's range: a different histogram, hence codebook
+            Kx = (Kx.astype(np.float32) ** 3 / 64).astype(np.float16)
+            Vx = (Vx.astype(np.float32) ** 3 / 64).astype(np.float16)
+        data.append((Kx, Vx))
+        oc = oracle.OracleCache(B, H, Hq, 320, 1e-2, 2e-2, buffer_tokens=128)
+        oc.build_codebook(Kx, Vx)
+        oc.compress_blocks(Kx, Vx)
+        ocs.append(oc)
+    for i in (2, 0, 1):   # any order
+        layers[i].build_codebook(_dev(data[i][0]), _dev(data[i][1]))
+        layers[i].compress_blocks(_dev(data[i][0]), _dev(data[i][1]))
+    kn, vn = W.make_new_tokens(B, H, 70, 70)
+    for t in range(70):   # layer 1 grows by 70 tokens (one more block), the others stay
+        ocs[1].append_token(kn[t], vn[t])
+        layers[1].append_token(_dev(kn[t]), _dev(vn[t]))
+    q = W.make_queries(B, Hq, 1, 70)[0]
+    for i in range(3):
+        _assert_same_cache(ocs[i], layers[i])
+        for w in (K, V):
+            ln, cd = layers[i].codebook(w)
+            np.testing.assert_array_equal(ln, ocs[i].len[w])
+            np.testing.assert_array_equal(cd, ocs[i].code[w])
+        _attn_close(layers[i].attn_decode(_dev(q), SCALE).cpu().numpy(), ocs[i].attn_decode(q, SCALE))
+    assert not np.array_equal(layers[0].codebook(K)[0], layers[1].codebook(K)[0])
+    tot = layers.stats()
+    assert tot["stored_bytes"] == sum(oc.stats()["stored_bytes"] for oc in ocs)
+    assert abs(tot["compression_ratio"] - sum(oc.stats()["raw_bytes"] for oc in ocs) / tot["stored_bytes"]) < 1e-12
+    layers.close()
+
+
 def test_error_paths(gpu):
     import torch
     _say("error paths (all detected on the host or by the kernels' own checks)")
