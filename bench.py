@@ -54,6 +54,9 @@ def parse_args():
     ap.add_argument("--buffer-tokens", type=int, default=64,
                     help="capacity of the fp16 buffer of new tokens (multiple of 64): the newest tokens stay "
                          "uncompressed, the oldest block of a full buffer is compressed; 64 = the workloads' definition")
+    ap.add_argument("--separate-append", action="store_true",
+                    help="run every decode step as kvcomp_append_token + kvcomp_attn_decode (two launches) instead of "
+                         "kvcomp_append_attn_decode")
     ap.add_argument("--cold", action="store_true",
                     help="also time the fused and the fp16 kernel with a 512 MiB copy before every launch (caches "
                          "scrubbed); off by default so that a profile of the default run sees only warm launches")
@@ -102,8 +105,11 @@ def main():
 
     def decode_loop():
         for i in range(T):
-            cache.append_token(dkn[i], dvn[i])
-            cache.attn_decode(dq[i], scale, out)
+            if args.separate_append:
+                cache.append_token(dkn[i], dvn[i])
+                cache.attn_decode(dq[i], scale, out)
+            else:   # the same step as one call (one launch unless the token completes a block)
+                cache.append_attn_decode(dkn[i], dvn[i], dq[i], scale, out)
 
     ev = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
 
@@ -353,7 +359,9 @@ def main():
                                f"{T} decode steps (append one token, then fused decode attention), block 64, "
                                f"rel_eb {rel_eb}, max code word {args.max_code_len} bits" + (", K BlockQuant" if args.k_mode else "")
                                + (f", fp16 buffer of {args.buffer_tokens} tokens" if args.buffer_tokens != 64 else ""),
-                   "decode_loop": "hip graph replay" if graph is not None else "eager launches"},
+                   "decode_loop": "hip graph replay" if graph is not None else "eager launches",
+                   "decode_step": "kvcomp_append_token + kvcomp_attn_decode" if args.separate_append
+                                  else "kvcomp_append_attn_decode (append fused into the attention launch)"},
         "pct_hbm_peak": 100.0 * value / HBM_PEAK_GBPS,
         "compression_ratio": stats0["compression_ratio"],
         "bits_per_symbol": {"k": stats0["payload_bits_k"] / (B * H * nb0 * 8192.0),

@@ -127,6 +127,14 @@ kvcomp_status kvcomp_append_token(kvcomp_ctx *ctx, const void *d_k_new, const vo
  * Errors: STATE (empty cache), HIP. */
 kvcomp_status kvcomp_attn_decode(kvcomp_ctx *ctx, const void *d_q, float scale, float *d_out, void *stream);
 
+/* kvcomp_append_token followed by kvcomp_attn_decode (Section 3.2.3 then Section 3.3.2: the step of the decode
+ * phase) in one call and, except for the token that fills the buffer and triggers the compression of a block, in
+ * one kernel launch: the wave that owns the newest token's row reads it from d_k_new / d_v_new and stores it into
+ * the fp16 buffer on the way.  Same arguments, same result definition, same errors as the two calls; d_k_new and
+ * d_v_new must stay unchanged until the launch has run.  Stream-ordered, never synchronises. */
+kvcomp_status kvcomp_append_attn_decode(kvcomp_ctx *ctx, const void *d_k_new, const void *d_v_new, const void *d_q,
+                                        float scale, float *d_out, void *stream);
+
 /* ---- metrics, parity and debug exports (these SYNCHRONISE `stream` and copy to HOST buffers) ------------- */
 
 kvcomp_status kvcomp_get_stats(kvcomp_ctx *ctx, kvcomp_stats *h_out, void *stream);

@@ -49,6 +49,7 @@ SIGNATURES = {
     "kvcomp_compress_blocks": (_i, [_vp, _vp, _vp, _i, _vp]),
     "kvcomp_append_token": (_i, [_vp, _vp, _vp, _vp]),
     "kvcomp_attn_decode": (_i, [_vp, _vp, _f, _vp, _vp]),
+    "kvcomp_append_attn_decode": (_i, [_vp, _vp, _vp, _vp, _f, _vp, _vp]),
     "kvcomp_get_stats": (_i, [_vp, C.POINTER(Stats), _vp]),
     "kvcomp_debug_codes": (_i, [_vp, _i, _vp, _i, _vp, C.c_size_t, _vp, _vp, _vp]),
     "kvcomp_get_histogram": (_i, [_vp, _i, _vp, _vp]),
@@ -164,6 +165,17 @@ class KVCompCache:
         assert out.is_cuda and out.dtype == torch.float32 and out.is_contiguous()
         _check(self.lib.kvcomp_attn_decode(self.h, _dev_fp16(q, (self.B, self.Hq, D)), float(scale),
                                            C.c_void_p(out.data_ptr()), _stream()))
+        return out
+
+    def append_attn_decode(self, k_new, v_new, q, scale, out=None):
+        """append_token followed by attn_decode, in one launch whenever no block has to be compressed."""
+        if out is None:
+            out = torch.empty((self.B, self.Hq, D), dtype=torch.float32, device=self.device)
+        assert out.is_cuda and out.dtype == torch.float32 and out.is_contiguous()
+        shape = (self.B, self.H, D)
+        _check(self.lib.kvcomp_append_attn_decode(self.h, _dev_fp16(k_new, shape), _dev_fp16(v_new, shape),
+                                                  _dev_fp16(q, (self.B, self.Hq, D)), float(scale),
+                                                  C.c_void_p(out.data_ptr()), _stream()))
         return out
 
     def reset(self, keep_codebook=True):

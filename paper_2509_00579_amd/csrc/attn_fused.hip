@@ -36,6 +36,10 @@ struct FusedArgs {
     float scale;
     int n_blocks, res_head, n_res, blocks_per_split, n_splits, stage_bytes;
     uint32_t mask2[2];
+    // append fused into this launch: the newest buffered token (number new_row of the buffer, oldest = 0) is not in the
+    // buffer yet but in k_new / v_new [B][H][128]; the wave that reads it also stores it there.  new_row < 0: none.
+    const uint16_t *k_new, *v_new;
+    int new_row;
 };
 
 // softmax state of one wave for G query heads
@@ -431,12 +435,16 @@ constexpr int kThreads = 64 * kWaves;
 // latency with, and small units spread the buffer over many waves.  Scores of row 4i + l/16 are formed by a sum over
 // the row's 16 lanes, which is also the layout the V rows arrive in; the channel sums are then folded over the four
 // row groups and handed to the lanes that own them (lane l: channels 2l, 2l+1).
+// When the append of the newest token is fused into the launch (new_row >= 0), its row comes from k_new / v_new
+// instead of the buffer, and the 16 lanes that read it store it into its buffer slot for the launches to come: one
+// wave of the grid per (batch, head) owns that row, so there is one writer and no reader of the slot in this launch.
 // Out of line: it runs once, after the decode loop, and must not weigh on that loop's registers.
 constexpr int kUnitTokens = 16;
 template <int G>
 __device__ __noinline__ void buffered_tokens(const uint16_t *res, int res_tokens, int B, int H, int b, int h,
                                              int res_head, int n_res, int first_unit, int unit_step,
-                                             const float *qf, float scale, int lane, Soft<G> &st) {
+                                             const float *qf, float scale, int lane, const uint16_t *k_new,
+                                             const uint16_t *v_new, int new_row, Soft<G> &st) {
     const size_t res_tensor = (size_t)B * res_tokens * H * kD;
     const size_t row4 = (size_t)4 * H * kD;  // elements from one load to the next
     const int n_units = (n_res + kUnitTokens - 1) / kUnitTokens;
@@ -447,15 +455,29 @@ __device__ __noinline__ void buffered_tokens(const uint16_t *res, int res_tokens
         const int n_tok = min(kUnitTokens, n_res - u * kUnitTokens);
         int slot0 = res_head + u * kUnitTokens;
         if (slot0 >= res_tokens) slot0 -= res_tokens;
-        const uint16_t *kbase = res + (((size_t)b * res_tokens + slot0 + grp) * H + h) * kD + 8 * sub;
-        const uint16_t *vbase = kbase + res_tensor;
+        const size_t buf_off = (((size_t)b * res_tokens + slot0 + grp) * H + h) * kD + 8 * sub;
+        const size_t new_off = ((size_t)b * H + h) * kD + 8 * sub;
+        const int row0 = u * kUnitTokens + grp;  // number of this lane's first row in the buffer, oldest token = 0
         uint4 rk[4], rv[4];
 #pragma unroll
-        for (int i = 0; i < 4; i++)
-            rk[i] = 4 * i + grp < n_tok ? *reinterpret_cast<const uint4 *>(kbase + i * row4) : make_uint4(0, 0, 0, 0);
+        for (int i = 0; i < 4; i++) {
+            const uint16_t *src = row0 + 4 * i == new_row ? k_new + new_off : res + buf_off + i * row4;
+            rk[i] = 4 * i + grp < n_tok ? *reinterpret_cast<const uint4 *>(src) : make_uint4(0, 0, 0, 0);
+        }
 #pragma unroll
-        for (int i = 0; i < 4; i++)
-            rv[i] = 4 * i + grp < n_tok ? *reinterpret_cast<const uint4 *>(vbase + i * row4) : make_uint4(0, 0, 0, 0);
+        for (int i = 0; i < 4; i++) {
+            const uint16_t *src = row0 + 4 * i == new_row ? v_new + new_off : res + res_tensor + buf_off + i * row4;
+            rv[i] = 4 * i + grp < n_tok ? *reinterpret_cast<const uint4 *>(src) : make_uint4(0, 0, 0, 0);
+        }
+        if (new_row >= 0) {
+            uint16_t *wr = const_cast<uint16_t *>(res) + buf_off;
+#pragma unroll
+            for (int i = 0; i < 4; i++)
+                if (row0 + 4 * i == new_row) {
+                    *reinterpret_cast<uint4 *>(wr + i * row4) = rk[i];
+                    *reinterpret_cast<uint4 *>(wr + res_tensor + i * row4) = rv[i];
+                }
+        }
 #pragma unroll 1
         for (int gg = 0; gg < G; gg++) {
             float qv[8];
@@ -723,7 +745,7 @@ __global__ __launch_bounds__(kThreads, WavesPerSimd<G>::value) void fused_attn_k
         if (first * kUnitTokens < a.n_res) {
             Soft<G> st_tmp = st;
             buffered_tokens<G>(g.res, g.res_tokens, g.B, g.H, b, h, a.res_head, a.n_res, first, kWaves * a.n_splits, qf,
-                               a.scale, lane, st_tmp);
+                               a.scale, lane, a.k_new, a.v_new, a.new_row, st_tmp);
             st = st_tmp;
         }
     }
@@ -802,8 +824,12 @@ static hipError_t launch_fused_g(const FusedArgs &a, int longest, size_t lds, hi
 }
 
 hipError_t launch_fused_attn(const Geo &g, const uint16_t *q, float scale, float *out, int n_blocks, int res_head,
-                             int n_res, int n_splits, int stage_bytes, hipEvent_t ev0, hipEvent_t ev1, hipStream_t s) {
+                             int n_res, const uint16_t *k_new, const uint16_t *v_new, int n_splits, int stage_bytes,
+                             hipEvent_t ev0, hipEvent_t ev1, hipStream_t s) {
     FusedArgs a;
+    a.k_new = k_new;
+    a.v_new = v_new;
+    a.new_row = k_new ? n_res - 1 : -1;  // n_res counts the token being appended
     a.g = g;
     a.q = q;
     a.out = out;

@@ -425,11 +425,10 @@ kvcomp_status kvcomp_append_token(kvcomp_ctx *ctx, const void *d_k_new, const vo
     return KVCOMP_OK;
 }
 
-kvcomp_status kvcomp_attn_decode(kvcomp_ctx *ctx, const void *d_q, float scale, float *d_out, void *stream) {
-    if (!ctx || !d_q || !d_out) return fail(KVCOMP_ERR_INVALID_ARG, "NULL argument");
-    if (ctx->n_blocks == 0 && ctx->n_res == 0) return fail(KVCOMP_ERR_STATE, "cache is empty");
-    if (ctx->n_blocks && !ctx->have_codebook) return fail(KVCOMP_ERR_STATE, "no codebook");
-    hipStream_t s = static_cast<hipStream_t>(stream);
+// One launch of the fused kernel over the cache as the host counts it (n_blocks, n_res).  k_new / v_new != NULL: the
+// newest buffered token is still there and not in the buffer.
+static kvcomp_status attn_impl(kvcomp_ctx *ctx, const void *d_q, float scale, float *d_out, const uint16_t *k_new,
+                               const uint16_t *v_new, hipStream_t s) {
     const Geo &g = ctx->geo;
     // Work split: the grid should fit the chip in a single round of workgroups (256 CUs x the workgroups of 4 waves
     // that registers and LDS let be resident per CU for this group size and table width), every wave owning whole
@@ -473,8 +472,34 @@ kvcomp_status kvcomp_attn_decode(kvcomp_ctx *ctx, const void *d_q, float scale, 
         ctx->events_used += 2;
     }
     HIP_TRY(launch_fused_attn(g, static_cast<const uint16_t *>(d_q), scale, d_out, ctx->n_blocks, ctx->res_head, ctx->n_res,
-                              n_splits, stage, ev0, ev1, s));
+                              k_new, v_new, n_splits, stage, ev0, ev1, s));
     return KVCOMP_OK;
+}
+
+kvcomp_status kvcomp_attn_decode(kvcomp_ctx *ctx, const void *d_q, float scale, float *d_out, void *stream) {
+    if (!ctx || !d_q || !d_out) return fail(KVCOMP_ERR_INVALID_ARG, "NULL argument");
+    if (ctx->n_blocks == 0 && ctx->n_res == 0) return fail(KVCOMP_ERR_STATE, "cache is empty");
+    if (ctx->n_blocks && !ctx->have_codebook) return fail(KVCOMP_ERR_STATE, "no codebook");
+    return attn_impl(ctx, d_q, scale, d_out, nullptr, nullptr, static_cast<hipStream_t>(stream));
+}
+
+kvcomp_status kvcomp_append_attn_decode(kvcomp_ctx *ctx, const void *d_k_new, const void *d_v_new, const void *d_q,
+                                        float scale, float *d_out, void *stream) {
+    if (!ctx || !d_k_new || !d_v_new || !d_q || !d_out) return fail(KVCOMP_ERR_INVALID_ARG, "NULL argument");
+    if (ctx->n_res + 1 == ctx->geo.res_tokens) {  // this token fills the buffer: the block is cut off first
+        kvcomp_status st = kvcomp_append_token(ctx, d_k_new, d_v_new, stream);
+        if (st) return st;
+        return kvcomp_attn_decode(ctx, d_q, scale, d_out, stream);
+    }
+    if (!aligned16(d_k_new) || !aligned16(d_v_new)) return fail(KVCOMP_ERR_INVALID_ARG, "k/v must be 16-byte aligned");
+    if (!ctx->have_codebook) return fail(KVCOMP_ERR_STATE, "no codebook: call kvcomp_build_codebook first");
+    if (ctx->n_blocks * kBT + ctx->n_res + 1 > ctx->cfg.max_seq)
+        return fail(KVCOMP_ERR_CAPACITY, "max_seq %d reached", ctx->cfg.max_seq);
+    ctx->n_res++;  // the kernel reads the token from d_k_new / d_v_new and stores it into its buffer slot
+    kvcomp_status st = attn_impl(ctx, d_q, scale, d_out, static_cast<const uint16_t *>(d_k_new),
+                                 static_cast<const uint16_t *>(d_v_new), static_cast<hipStream_t>(stream));
+    if (st) ctx->n_res--;
+    return st;
 }
 
 kvcomp_status kvcomp_get_stats(kvcomp_ctx *ctx, kvcomp_stats *o, void *stream) {

@@ -110,8 +110,11 @@ hipError_t launch_encode(const Geo &g, const uint16_t *XK, const uint16_t *XV, i
 hipError_t launch_copy_tail(const Geo &g, const uint16_t *XK, const uint16_t *XV, int seq, int first_tok, int n_tok,
                             hipStream_t s);
 hipError_t launch_append(const Geo &g, const uint16_t *k_new, const uint16_t *v_new, int slot, hipStream_t s);
+// k_new / v_new != NULL: the newest of the n_res buffered tokens is still in k_new / v_new [B][H][128]; the kernel
+// reads it from there and stores it into its buffer slot (append fused into the launch)
 hipError_t launch_fused_attn(const Geo &g, const uint16_t *q, float scale, float *out, int n_blocks, int res_head,
-                             int n_res, int n_splits, int stage_bytes, hipEvent_t ev0, hipEvent_t ev1, hipStream_t s);
+                             int n_res, const uint16_t *k_new, const uint16_t *v_new, int n_splits, int stage_bytes,
+                             hipEvent_t ev0, hipEvent_t ev1, hipStream_t s);
 hipError_t launch_baseline_attn(int B, int H, int Hq, const uint16_t *K, const uint16_t *V, int seq, const uint16_t *q,
                                 float scale, float *out, float *partials, uint32_t *counters, int n_splits,
                                 hipStream_t s);

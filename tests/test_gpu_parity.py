@@ -231,6 +231,46 @@ def test_larger_buffer_window(gpu, oracle, B, H, Hq, window, S0, extra):
             gpu.KVCompCache(B, H, Hq, max_seq, 1e-2, 1e-2, buffer_tokens=bad)
 
 
+@pytest.mark.parametrize("B,H,Hq,window,S0,extra", [(2, 2, 2, 64, 100, 150), (1, 2, 8, 128, 70, 200),
+                                                    (1, 1, 4, 192, 30, 260)])
+def test_append_fused_into_the_attention_launch(gpu, oracle, B, H, Hq, window, S0, extra):
+    """kvcomp_append_attn_decode = append_token then attn_decode: every step's output against the oracle's two calls,
+    and the cache afterwards (buffer contents included: the kernel stores the token it read from the caller's tensor)
+    bit for bit, across flushes and ring wrap-arounds; interleaved with the two separate calls."""
+    _say(f"append fused into attention: B={B} H={H} Hq={Hq} buffer {window}, prompt {S0} + {extra} tokens")
+    max_seq = (S0 + extra + 63) // 64 * 64
+    Kx, Vx = W.make_kv(B, H, max(S0, 64), 28)
+    oc = oracle.OracleCache(B, H, Hq, max_seq, 1e-2, 1e-2, buffer_tokens=window)
+    gc = gpu.KVCompCache(B, H, Hq, max_seq, 1e-2, 1e-2, buffer_tokens=window)
+    oc.build_codebook(Kx, Vx)
+    gc.build_codebook(_dev(Kx), _dev(Vx))
+    oc.compress_blocks(Kx[:, :S0], Vx[:, :S0])
+    gc.compress_blocks(_dev(Kx[:, :S0]), _dev(Vx[:, :S0]))
+    kn, vn = W.make_new_tokens(B, H, extra, 28)
+    qs = W.make_queries(B, Hq, extra, 28)
+    dkn, dvn, dq = _dev(kn), _dev(vn), _dev(qs)
+    worst = 0.0
+    for t in range(extra):
+        oc.append_token(kn[t], vn[t])
+        if t % 11 == 5:   # the two separate calls in between
+            gc.append_token(dkn[t], dvn[t])
+            out = gc.attn_decode(dq[t], SCALE)
+        else:
+            out = gc.append_attn_decode(dkn[t], dvn[t], dq[t], SCALE)
+        if t % 3 == 0 or oc.n_res in (window - 64, window - 63, window - 1):
+            worst = max(worst, _attn_close(out.cpu().numpy(), oc.attn_decode(qs[t], SCALE)))
+        if t in (0, 17, extra // 2):
+            _assert_same_cache(oc, gc)
+    _assert_same_cache(oc, gc)
+    _say(f"  blocks {oc.n_blocks}, buffered {oc.n_res}, worst attention error {worst:.2e}")
+    for _ in range(max_seq - S0 - extra):
+        gc.append_attn_decode(dkn[0], dvn[0], dq[0], SCALE)
+    with pytest.raises(gpu.KvcompError) as e:
+        gc.append_attn_decode(dkn[0], dvn[0], dq[0], SCALE)
+    assert e.value.status == gpu.ERR_CAPACITY
+    gc.close()
+
+
 def test_layers_have_their_own_codebooks(gpu, oracle):
     """One context per layer in a single allocation (Section 3: codebooks are per layer): every layer matches an oracle
     cache of its own data, appends to one layer leave the others untouched, and the codebooks differ between layers
