@@ -9,7 +9,7 @@ namespace kvc {
 // its minimum however peaked the code distribution is (with one copy per wave, lanes with the same code serialise
 // and the kernel was bound by its LDS atomics).  The copies are summed and added to the global histogram at the end.
 template <int WHICH>
-__global__ __launch_bounds__(256) void histogram_kernel(Geo g, const uint16_t *__restrict__ X, int seq_stride,
+__global__ __launch_bounds__(256, 4) void histogram_kernel(Geo g, const uint16_t *__restrict__ X, int seq_stride,
                                                          int n_blk_per_bh, int n_blk_total) {
     __shared__ QuantShared sh;
     __shared__ uint32_t hist[256][32];

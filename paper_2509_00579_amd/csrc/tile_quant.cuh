@@ -80,6 +80,34 @@ __device__ __forceinline__ uint32_t quant_code(float x, float mn, float step, fl
     return range == 0.0f ? 0u : (uint32_t)k;
 }
 
+// N values of one quantization unit at once, same result as quant_code for each.  The correctly rounded division is
+// most of the quantizer's instructions, so the quotient is first formed as d * rcp(step): v_rcp_f32 is accurate to
+// 1 ulp and the product adds half an ulp, so the result is within 2^-22 relative (below 2^-14 absolute for quotients
+// under 256) of the correctly rounded quotient, and rounds to the same integer unless it lies within that distance
+// of k + 1/2.  If any lane of the wave has a value within 2^-12 of such a boundary (a few per cent of the calls),
+// the whole group is redone with the division.
+template <int N>
+__device__ __forceinline__ void quant_codes(const float (&x)[N], float mn, float step, float range, float top,
+                                            uint32_t (&code)[N]) {
+    const float inv = __builtin_amdgcn_rcpf(step);
+    float q[N];
+    bool near = false;
+#pragma unroll
+    for (int n = 0; n < N; n++) {
+        q[n] = (x[n] - mn) * inv;
+        near |= fabsf(__builtin_amdgcn_fractf(q[n]) - 0.5f) < 0x1p-12f;
+    }
+    if (__builtin_amdgcn_ballot_w64(near) != 0) {
+#pragma unroll
+        for (int n = 0; n < N; n++) q[n] = (x[n] - mn) / step;
+    }
+#pragma unroll
+    for (int n = 0; n < N; n++) {
+        const float k = fminf(fmaxf(rintf(q[n]), 0.0f), top);
+        code[n] = range == 0.0f ? 0u : (uint32_t)k;
+    }
+}
+
 __device__ __forceinline__ float canon_zero(float v) { return v == 0.0f ? 0.0f : v; }
 
 // LDS scratch needed by quantize_tile.
@@ -129,9 +157,7 @@ __device__ __forceinline__ void quantize_tile(TileRegs &r, QuantShared &sh, int 
         const float range = z - a;
         const float step = two_eb * range;
 #pragma unroll
-        for (int i = 0; i < 4; i++)
-#pragma unroll
-            for (int k = 0; k < 8; k++) r.code[i][k] = quant_code(r.x[i][k], a, step, range, top);
+        for (int i = 0; i < 4; i++) quant_codes<8>(r.x[i], a, step, range, top, r.code[i]);
     } else if (WHICH == 0) {
         float mn[8], mx[8];
 #pragma unroll
@@ -166,8 +192,11 @@ __device__ __forceinline__ void quantize_tile(TileRegs &r, QuantShared &sh, int 
             const float a = sh.unit_mn[c0 + k], z = sh.unit_mx[c0 + k];
             const float range = z - a;
             const float step = two_eb * range;
+            const float xs[4] = {r.x[0][k], r.x[1][k], r.x[2][k], r.x[3][k]};
+            uint32_t cs[4];
+            quant_codes<4>(xs, a, step, range, top, cs);
 #pragma unroll
-            for (int i = 0; i < 4; i++) r.code[i][k] = quant_code(r.x[i][k], a, step, range, top);
+            for (int i = 0; i < 4; i++) r.code[i][k] = cs[i];
         }
     } else {
 #pragma unroll
@@ -191,8 +220,7 @@ __device__ __forceinline__ void quantize_tile(TileRegs &r, QuantShared &sh, int 
             }
             const float range = z - a;
             const float step = two_eb * range;
-#pragma unroll
-            for (int k = 0; k < 8; k++) r.code[i][k] = quant_code(r.x[i][k], a, step, range, top);
+            quant_codes<8>(r.x[i], a, step, range, top, r.code[i]);
         }
         __syncthreads();
     }
