@@ -4,9 +4,10 @@
 // Quantization follows Section 3.1.1 (K: channel-wise inside the block, V: token-wise) with the relative scale of
 // Section 4.2 read as bin width = 2 * rel_eb * (max - min):
 //     code = round_half_even((x - min) / width), clamped to [0, n_sym - 1];  range 0 -> code 0.
-// All arithmetic is IEEE binary32, one operation at a time (this file is compiled with -ffp-contract=off and
-// correctly rounded division), so that an independent implementation of the same operation sequence agrees bit
-// for bit.
+// The codes are those of IEEE binary32 arithmetic taken one operation at a time (this file is compiled with
+// -ffp-contract=off and correctly rounded division), so that an independent implementation of the same operation
+// sequence agrees bit for bit; quant_codes reaches them by a cheaper route wherever that provably gives the same
+// integer.
 //
 // Thread map (tid = 64*w + l): load i in 0..3 covers token 16*w + 4*i + l/16, channels 8*(l%16) .. +7, i.e. one wave
 // load instruction reads four contiguous 256-byte rows.
@@ -72,16 +73,9 @@ __device__ __forceinline__ bool load_tile(const uint16_t *X, int seq_stride, int
     return unpack_tile(raw, r);
 }
 
-__device__ __forceinline__ uint32_t quant_code(float x, float mn, float step, float range, float top) {
-    const float d = x - mn;
-    const float q = d / step;
-    float k = rintf(q);
-    k = fminf(fmaxf(k, 0.0f), top);
-    return range == 0.0f ? 0u : (uint32_t)k;
-}
-
-// N values of one quantization unit at once, same result as quant_code for each.  The correctly rounded division is
-// most of the quantizer's instructions, so the quotient is first formed as d * rcp(step): v_rcp_f32 is accurate to
+// Codes of N values of one quantization unit: code = clamp(rint((x - mn) / step), 0, top) with the correctly rounded
+// binary32 division, 0 if the unit's range is 0.  That division is most of the quantizer's instructions, so the
+// quotient is first formed as d * rcp(step): v_rcp_f32 is accurate to
 // 1 ulp and the product adds half an ulp, so the result is within 2^-22 relative (below 2^-14 absolute for quotients
 // under 256) of the correctly rounded quotient, and rounds to the same integer unless it lies within that distance
 // of k + 1/2.  If any lane of the wave has a value within 2^-12 of such a boundary (a few per cent of the calls),
