@@ -576,11 +576,47 @@ def test_large_configs_full_size_sampled(gpu, oracle, name):
     del codes, mms
     q = W.make_queries(B, Hq, 1, w.seed)[0]
     out = gc.attn_decode(_dev(q), SCALE).cpu().numpy()
+    sampled = {}
     for b, h in ((0, 0), (B - 1, H - 1)):
-        oc = oracle.OracleCache(1, 1, G, S + 64, rel, rel, 0, 7)
+        oc = oracle.OracleCache(1, 1, G, S + 64 + w.append_steps, rel, rel, 0, 7)
         oc.len, oc.code = [book[K][0], book[V][0]], [book[K][1], book[V][1]]
         oc.compress_blocks(np.ascontiguousarray(Kx[b:b + 1, :, h:h + 1]), np.ascontiguousarray(Vx[b:b + 1, :, h:h + 1]))
         ref = oc.attn_decode(np.ascontiguousarray(q[b:b + 1, h * G:(h + 1) * G]), SCALE)
         err = _attn_close(out[b:b + 1, h * G:(h + 1) * G], ref)
         _say(f"  (b={b}, h={h}): attention max abs err {err:.3e}")
+        sampled[(b, h)] = oc
+    gc.close()
+    if not w.append_steps:
+        return
+    # the streaming phase at full size: every decode step appends one token per sequence (a full buffer is compressed
+    # with the prompt's codebooks) and attends; the sampled heads are followed by oracle caches of their own
+    T = w.append_steps
+    _say(f"  streaming: {T} decode steps")
+    gc = gpu.KVCompCache(B, H, Hq, S + T, rel, rel, max_code_len=7)
+    dK, dV = _dev(Kx), _dev(Vx)
+    gc.build_codebook(dK, dV)
+    gc.compress_blocks(dK, dV)
+    del dK, dV
+    kn, vn = W.make_new_tokens(B, H, T, w.seed)
+    qs = W.make_queries(B, Hq, T, w.seed)
+    dkn, dvn, dq = _dev(kn), _dev(vn), _dev(qs)
+    check = {0, 62, 63, 64, 255, 256, T - 1}
+    outs = {}
+    for t in range(T):
+        o = gc.append_attn_decode(dkn[t], dvn[t], dq[t], SCALE)
+        if t in check:
+            outs[t] = o.cpu().numpy()
+    st = gc.stats()
+    assert st["n_blocks"] == (S + T) // 64 and st["n_res"] == (S + T) % 64
+    for (b, h), oc in sampled.items():
+        worst = 0.0
+        for t in range(T):
+            oc.append_token(kn[t][b:b + 1, h:h + 1], vn[t][b:b + 1, h:h + 1])
+            if t in check:
+                ref = oc.attn_decode(np.ascontiguousarray(qs[t][b:b + 1, h * G:(h + 1) * G]), SCALE)
+                worst = max(worst, _attn_close(outs[t][b:b + 1, h * G:(h + 1) * G], ref))
+        for which in (K, V):
+            for j in range(NB, oc.n_blocks):   # the blocks compressed while streaming
+                np.testing.assert_array_equal(gc.get_block(which, b, h, j), oc.get_block(which, 0, 0, j))
+        _say(f"  (b={b}, h={h}): {oc.n_blocks - NB} streamed blocks bit-exact, attention max abs err {worst:.3e}")
     gc.close()
