@@ -141,7 +141,7 @@ def main():
         resident = {1: 4, 2: 4, 4: 3, 8: 2}[Hq // H]  # fused-kernel workgroups per CU for this group size
         ns = max(1, min(max(1, 256 * resident // (B * H)), -(-nb0 // 4)))
         bps = -(-(-(-nb0 // ns)) // 4) * 4
-        n_splits_est = max(1, min(64, -(-nb0 // bps))) if bps else 1
+        n_splits_est = max(1, min(128, -(-nb0 // bps))) if bps else 1
     def blocks_of(tokens):  # compressed blocks after `tokens` tokens: the buffer keeps the newest ones
         return 0 if tokens < args.buffer_tokens else (tokens - args.buffer_tokens) // 64 + 1
 

@@ -73,7 +73,7 @@ struct Geo {
 };
 
 constexpr int kPartialStride = kD + 2;  // o[128], m, l
-constexpr int kMaxSplits = 64;
+constexpr int kMaxSplits = 128;
 constexpr int kCUs = 256;  // compute units of the MI355X
 constexpr int kXCDs = 8;   // accelerator dies, each with its own L2; workgroups are dealt to them round-robin
 // Workgroups (of 4 waves) of the fused kernel that are resident per CU = its waves per SIMD: groups of 4 and 8 query

@@ -271,6 +271,29 @@ def test_append_fused_into_the_attention_launch(gpu, oracle, B, H, Hq, window, S
     gc.close()
 
 
+def test_many_sequence_splits(gpu, oracle):
+    """One long sequence with a single KV head: the library splits it 128 ways (its maximum) so that the chip is
+    filled; every split count gives the oracle's result, also when the last split is short or the buffer holds
+    more 16-token units than there are splits."""
+    _say("one head, 20000 tokens: 128 splits (automatic), then 97, 5 and 1")
+    B, H, Hq, S = 1, 1, 2, 20000
+    Kx, Vx = W.make_kv(B, H, S, 29)
+    oc = oracle.OracleCache(B, H, Hq, S + 64, 1e-2, 1e-2, 0, 7, buffer_tokens=256)
+    gc = gpu.KVCompCache(B, H, Hq, S + 64, 1e-2, 1e-2, max_code_len=7, buffer_tokens=256)
+    oc.build_codebook(Kx, Vx)
+    oc.compress_blocks(Kx, Vx)
+    gc.build_codebook(_dev(Kx), _dev(Vx))
+    gc.compress_blocks(_dev(Kx), _dev(Vx))
+    assert oc.n_blocks == 309 and oc.n_res == 224
+    q = W.make_queries(B, Hq, 1, 29)[0]
+    ref = oc.attn_decode(q, SCALE)
+    for n_splits in (0, 97, 5, 1):
+        gc.set_tuning(n_splits=n_splits)
+        err = _attn_close(gc.attn_decode(_dev(q), SCALE).cpu().numpy(), ref)
+        _say(f"  n_splits {n_splits}: max abs err {err:.2e}")
+    gc.close()
+
+
 def test_layers_have_their_own_codebooks(gpu, oracle):
     """One context per layer in a single allocation (Section 3: codebooks are per layer): every layer matches an oracle
     cache of its own data, appends to one layer leave the others untouched, and the codebooks differ between layers
