@@ -40,6 +40,9 @@ def parse_args():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="c1", choices=["c0", "c1", "c2", "c3", "c4"])
     ap.add_argument("--rel-eb", type=float, default=None, help="override the workload's relative error bound")
+    ap.add_argument("--rel-eb-v", type=float, default=None,
+                    help="relative error bound of V if it differs from K's (the paper's operating points quantize V "
+                         "more coarsely than K)")
     ap.add_argument("--no-graph", action="store_true", help="launch the decode loop eagerly instead of replaying a HIP graph")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--n-splits", type=int, default=0)
@@ -82,8 +85,9 @@ def main():
     rel_eb = args.rel_eb if args.rel_eb is not None else w.rel_eb
     B, H, Hq, S, T = w.batch, w.n_kv_heads, w.n_q_heads, w.seq, w.decode_steps
     scale = 1.0 / np.sqrt(128.0)
+    rel_eb_v = args.rel_eb_v if args.rel_eb_v is not None else rel_eb
     if args.max_code_len == 0:
-        levels = int(np.rint(1.0 / (2.0 * np.float32(rel_eb)))) + 1
+        levels = int(np.rint(1.0 / (2.0 * np.float32(min(rel_eb, rel_eb_v))))) + 1
         args.max_code_len = max(7, int(np.ceil(np.log2(levels))))
 
     # ---- inputs: generated on the host from the seed, resident in HBM before any timed region ----
@@ -94,7 +98,7 @@ def main():
     dq, dkn, dvn = torch.from_numpy(qs).cuda(), torch.from_numpy(kn).cuda(), torch.from_numpy(vn).cuda()
     out = torch.empty((B, Hq, 128), dtype=torch.float32, device="cuda")
     max_seq = (S + T + 63) // 64 * 64
-    cache = binding.KVCompCache(B, H, Hq, max_seq, rel_eb, rel_eb, k_mode=args.k_mode, max_code_len=args.max_code_len,
+    cache = binding.KVCompCache(B, H, Hq, max_seq, rel_eb, rel_eb_v, k_mode=args.k_mode, max_code_len=args.max_code_len,
                                 buffer_tokens=args.buffer_tokens)
     cache.set_tuning(args.n_splits, args.stage_bytes)
 
@@ -334,7 +338,7 @@ def main():
         ob = max(1, min(B, 2))                       # bounded sample: at most 2 sequences of the batch
         oh = H if B * H * S <= 32 * 4096 else max(1, (32 * 4096) // (ob * S))
         oh = min(oh, H)
-        oc = oracle.OracleCache(ob, oh, oh * (Hq // H), max_seq, rel_eb, rel_eb, k_mode=args.k_mode,
+        oc = oracle.OracleCache(ob, oh, oh * (Hq // H), max_seq, rel_eb, rel_eb_v, k_mode=args.k_mode,
                                 max_code_len=args.max_code_len, buffer_tokens=args.buffer_tokens)
         oc.build_codebook(Kx[:ob, :, :oh], Vx[:ob, :, :oh])
         oc.compress_blocks(np.ascontiguousarray(Kx[:ob, :, :oh]), np.ascontiguousarray(Vx[:ob, :, :oh]))
@@ -384,7 +388,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": f"{args.workload}: batch {B}, {H} kv heads / {Hq} q heads x 128, prompt {S} tokens, "
                                f"{T} decode steps (append one token, then fused decode attention), block 64, "
-                               f"rel_eb {rel_eb}, max code word {args.max_code_len} bits" + (", K BlockQuant" if args.k_mode else "")
+                               f"rel_eb {rel_eb}" + (f" (V: {rel_eb_v})" if rel_eb_v != rel_eb else "") + f", max code word {args.max_code_len} bits" + (", K BlockQuant" if args.k_mode else "")
                                + (f", fp16 buffer of {args.buffer_tokens} tokens" if args.buffer_tokens != 64 else ""),
                    "decode_loop": "hip graph replay" if graph is not None else "eager launches",
                    "decode_step": "kvcomp_append_token + kvcomp_attn_decode" if args.separate_append
