@@ -226,6 +226,8 @@ __device__ __forceinline__ void k_block(const uint32_t *hdr32, const char *lut, 
     const uint32_t start = wave_excl_scan((sb & 0xffffu) + (sb >> 16), lane);
     const uint32_t *wm1 = hdr32 + (kmm + 2 * kSlices) / 4 - 1;
     constexpr int kRounds = kHalf / NS, kTail = kHalf - kRounds * NS;
+    constexpr int kP1 = NS > 4 ? 3 : NS, kP2 = NS - kP1;  // pieces of a window (kP2 = 0: taken whole)
+    static_assert(kTail <= 4 && (G < kMfmaMinG || kP2 == 0), "pieces");
     Quad qd;
     if constexpr (G >= kMfmaMinG) {
         constexpr int R = MfmaRounds<NS>::kCount, Q4 = G / 4;
@@ -299,9 +301,24 @@ __device__ __forceinline__ void k_block(const uint32_t *hdr32, const char *lut, 
         // scheduler may overlap the table lookups of one round with the accumulation of the previous one
 #pragma unroll
         for (int r = 0; r < kRounds; r++) {
-            uint32_t fau[NS], fad[NS], fbu[NS], fbd[NS];
-            qd.step<NS>(wm1, lut, mask2, fau, fad, fbu, fbd);
-            k_accum<G, NS>(wl, wdn, wq, r * NS, fau, fad, fbu, fbd, acc);
+            if constexpr (kP2 == 0) {
+                uint32_t fau[NS], fad[NS], fbu[NS], fbd[NS];
+                qd.step<NS>(wm1, lut, mask2, fau, fad, fbu, fbd);
+                k_accum<G, NS>(wl, wdn, wq, r * NS, fau, fad, fbu, fbd, acc);
+            } else {  // a window of more than four symbols is taken in two pieces: fewer table entries in flight
+                qd.begin(wm1);
+                {
+                    uint32_t fau[kP1], fad[kP1], fbu[kP1], fbd[kP1];
+                    qd.part<kP1>(lut, mask2, fau, fad, fbu, fbd);
+                    k_accum<G, kP1>(wl, wdn, wq, r * NS, fau, fad, fbu, fbd, acc);
+                }
+                {
+                    uint32_t fau[kP2 ? kP2 : 1], fad[kP2 ? kP2 : 1], fbu[kP2 ? kP2 : 1], fbd[kP2 ? kP2 : 1];
+                    qd.part<(kP2 ? kP2 : 1)>(lut, mask2, fau, fad, fbu, fbd);
+                    k_accum<G, (kP2 ? kP2 : 1)>(wl, wdn, wq, r * NS + kP1, fau, fad, fbu, fbd, acc);
+                }
+                qd.end(wm1);
+            }
         }
         if constexpr (kTail > 0) {
             uint32_t fau[kTail], fad[kTail], fbu[kTail], fbd[kTail];
@@ -333,6 +350,8 @@ __device__ __forceinline__ void v_block(const uint32_t *hdr32, const char *lut, 
     const uint32_t start = wave_excl_scan((sb & 0xffffu) + (sb >> 16), lane);
     const uint32_t *wm1 = hdr32 + kHdrBytesV / 4 - 1;
     constexpr int kRounds = kHalf / NS, kTail = kHalf - kRounds * NS;
+    constexpr int kP1 = NS > 4 ? 3 : NS, kP2 = NS - kP1;  // pieces of a window (kP2 = 0: taken whole)
+    static_assert(kTail <= 4 && (G < kMfmaMinG || kP2 == 0), "pieces");
     Quad qd;
     if constexpr (G >= kMfmaMinG) {
         constexpr int R = MfmaRounds<NS>::kCount, Q4 = G / 4;
@@ -398,9 +417,24 @@ __device__ __forceinline__ void v_block(const uint32_t *hdr32, const char *lut, 
         qd.open(wm1, start, sb & 0xffffu, sb >> 16);
 #pragma unroll
         for (int r = 0; r < kRounds; r++) {
-            uint32_t fau[NS], fad[NS], fbu[NS], fbd[NS];
-            qd.step<NS>(wm1, lut, mask2, fau, fad, fbu, fbd);
-            v_accum<G, NS>(wl, wdn, wq, r * NS, fau, fad, fbu, fbd, st.acc);
+            if constexpr (kP2 == 0) {
+                uint32_t fau[NS], fad[NS], fbu[NS], fbd[NS];
+                qd.step<NS>(wm1, lut, mask2, fau, fad, fbu, fbd);
+                v_accum<G, NS>(wl, wdn, wq, r * NS, fau, fad, fbu, fbd, st.acc);
+            } else {
+                qd.begin(wm1);
+                {
+                    uint32_t fau[kP1], fad[kP1], fbu[kP1], fbd[kP1];
+                    qd.part<kP1>(lut, mask2, fau, fad, fbu, fbd);
+                    v_accum<G, kP1>(wl, wdn, wq, r * NS, fau, fad, fbu, fbd, st.acc);
+                }
+                {
+                    uint32_t fau[kP2 ? kP2 : 1], fad[kP2 ? kP2 : 1], fbu[kP2 ? kP2 : 1], fbd[kP2 ? kP2 : 1];
+                    qd.part<(kP2 ? kP2 : 1)>(lut, mask2, fau, fad, fbu, fbd);
+                    v_accum<G, (kP2 ? kP2 : 1)>(wl, wdn, wq, r * NS + kP1, fau, fad, fbu, fbd, st.acc);
+                }
+                qd.end(wm1);
+            }
         }
         if constexpr (kTail > 0) {
             uint32_t fau[kTail], fad[kTail], fbu[kTail], fbd[kTail];
@@ -815,7 +849,10 @@ static hipError_t launch_fused_gn(const FusedArgs &a, size_t lds, hipEvent_t ev0
 template <int G>
 static hipError_t launch_fused_g(const FusedArgs &a, int longest, size_t lds, hipEvent_t ev0, hipEvent_t ev1,
                                  hipStream_t s) {
-    switch (fused_table_bits(longest)) {
+    switch (fused_attn_table_bits(longest, G)) {
+        case 6:
+            if constexpr (G < kMfmaMinG) return launch_fused_gn<G, 6>(a, lds, ev0, ev1, s);
+            return hipErrorInvalidValue;
         case 7: return launch_fused_gn<G, 7>(a, lds, ev0, ev1, s);
         case 8: return launch_fused_gn<G, 8>(a, lds, ev0, ev1, s);
         case 10: return launch_fused_gn<G, 10>(a, lds, ev0, ev1, s);
@@ -845,7 +882,7 @@ hipError_t launch_fused_attn(const Geo &g, const uint16_t *q, float scale, float
     if (longest < 1 || longest > kLutBits) return hipErrorInvalidValue;
     a.mask2[0] = ((1u << bits_k) - 1u) << kJunkBits;
     a.mask2[1] = ((1u << bits_v) - 1u) << kJunkBits;
-    const size_t lds = (size_t)kWaves * stage_bytes + kWaves * fused_weight_bytes(g.G, fused_table_bits(longest));
+    const size_t lds = (size_t)kWaves * stage_bytes + kWaves * fused_weight_bytes(g.G, fused_attn_table_bits(longest, g.G));
     switch (g.G) {
         case 1: return launch_fused_g<1>(a, longest, lds, ev0, ev1, s);
         case 2: return launch_fused_g<2>(a, longest, lds, ev0, ev1, s);

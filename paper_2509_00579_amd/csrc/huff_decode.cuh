@@ -154,8 +154,9 @@ struct DownReader {
 // (32-bit entries with the symbol as an fp16 number in the upper half, consumed by v_fma_mix_f32 without a
 // conversion, were measured too: one VALU instruction less per symbol, but the table takes twice the LDS rows and
 // the extra bank conflicts cost more than the instruction saves, except for tables of 64 entries where it is a tie.)
+// `win` is left at the first bit that was not used, so that a further call continues in the same window.
 template <int CNT>
-__device__ __forceinline__ uint32_t lookup(uint32_t win, const char *lut, uint32_t mask2, uint32_t (&e)[CNT]) {
+__device__ __forceinline__ uint32_t lookup_more(uint32_t &win, const char *lut, uint32_t mask2, uint32_t (&e)[CNT]) {
     uint32_t tot = 0;
 #pragma unroll
     for (int k = 0; k < CNT; k++) {
@@ -164,6 +165,10 @@ __device__ __forceinline__ uint32_t lookup(uint32_t win, const char *lut, uint32
         tot += e[k];  // low byte: running sum of code lengths (at most 31, never carries)
     }
     return tot & 0xffu;
+}
+template <int CNT>
+__device__ __forceinline__ uint32_t lookup(uint32_t win, const char *lut, uint32_t mask2, uint32_t (&e)[CNT]) {
+    return lookup_more<CNT>(win, lut, mask2, e);
 }
 
 // the symbol of a table entry as fp32 (one v_cvt_f32_ubyte1)
@@ -187,6 +192,30 @@ struct Quad {
         const uint32_t u1 = lookup<CNT>(ad.window(wm1), lut, mask2, fad);
         const uint32_t u2 = lookup<CNT>(bu.window(wm1), lut, mask2, fbu);
         const uint32_t u3 = lookup<CNT>(bd.window(wm1), lut, mask2, fbd);
+        au.advance(wm1, u0);
+        ad.advance(wm1, u1);
+        bu.advance(wm1, u2);
+        bd.advance(wm1, u3);
+    }
+    // The same in pieces, for windows that hold more symbols than the caller wants table entries in flight:
+    // begin(), then part<CNT>() once per piece (the pieces' CNT add up to what fits a window), then end().
+    uint32_t w0, w1, w2, w3, u0, u1, u2, u3;  // the four windows and the bits used so far; live from begin() to end()
+    __device__ __forceinline__ void begin(const uint32_t *wm1) {
+        w0 = au.window(wm1);
+        w1 = ad.window(wm1);
+        w2 = bu.window(wm1);
+        w3 = bd.window(wm1);
+        u0 = u1 = u2 = u3 = 0;
+    }
+    template <int CNT>
+    __device__ __forceinline__ void part(const char *lut, uint32_t mask2, uint32_t (&fau)[CNT], uint32_t (&fad)[CNT],
+                                         uint32_t (&fbu)[CNT], uint32_t (&fbd)[CNT]) {
+        u0 += lookup_more<CNT>(w0, lut, mask2, fau);
+        u1 += lookup_more<CNT>(w1, lut, mask2, fad);
+        u2 += lookup_more<CNT>(w2, lut, mask2, fbu);
+        u3 += lookup_more<CNT>(w3, lut, mask2, fbd);
+    }
+    __device__ __forceinline__ void end(const uint32_t *wm1) {
         au.advance(wm1, u0);
         ad.advance(wm1, u1);
         bu.advance(wm1, u2);

@@ -81,9 +81,11 @@ constexpr int kXCDs = 8;   // accelerator dies, each with its own L2; workgroups
 constexpr int fused_wgs_per_cu(int G) { return G >= 8 ? 2 : G >= 4 ? 3 : 4; }
 // Index width the fused kernel's LDS decode tables are compiled for, given the longest code word in use.
 constexpr int fused_table_bits(int longest) {
-    // (a 6-bit variant with five symbols per window was measured slower: its 20 live table entries spill registers)
     return longest <= 7 ? 7 : longest <= 8 ? 8 : longest <= 10 ? 10 : 12;
 }
+// The fused kernel's own choice: groups of 1 and 2 heads also have a 6-bit variant (five symbols per window, taken in
+// two pieces; a 64-entry table fills one row of LDS banks); the MFMA groups feed at most four symbols to a product.
+constexpr int fused_attn_table_bits(int longest, int G) { return G < 4 && longest <= 6 ? 6 : fused_table_bits(longest); }
 constexpr int kLdsBytesPerCU = 160 * 1024;
 // Bytes of one wave's LDS weight area.  Groups of 1 and 2 heads: fp32 [128][G].  Groups of 4 and 8: one 16-byte entry
 // per (chain array of 4, round, head), rounds = ceil(32 / symbols per window).
@@ -93,8 +95,8 @@ constexpr size_t fused_weight_bytes(int G, int table_bits) {
 // LDS of one fused-kernel workgroup apart from the per-wave staging areas: two decode tables of 16-bit entries, the
 // query rows and the per-wave weight areas.
 constexpr size_t fused_lds_fixed(int G, int longest) {
-    return ((size_t)4 << fused_table_bits(longest)) + (size_t)G * kD * 4 +
-           4 * fused_weight_bytes(G, fused_table_bits(longest)) + 512;
+    return ((size_t)4 << fused_attn_table_bits(longest, G)) + (size_t)G * kD * 4 +
+           4 * fused_weight_bytes(G, fused_attn_table_bits(longest, G)) + 512;
 }
 
 // ---- launches implemented in the .hip files ----

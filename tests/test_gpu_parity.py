@@ -406,11 +406,14 @@ def test_config1_full_size_sampled(gpu, oracle):
     gc.close()
 
 
-@pytest.mark.parametrize("max_len,rel", [(6, 1e-2), (7, 1e-2), (7, 5e-3), (8, 5e-3), (10, 1e-2), (12, 1e-2)])
-def test_code_length_limits_select_every_decoder_variant(gpu, oracle, max_len, rel):
-    """Shorter maximum code words: more symbols per decode window (4, 4, 3, 3, 2 for limits 6, 7, 8, 10, 12)."""
-    _say(f"max_code_len={max_len} rel={rel}")
-    B, H, Hq, S = 1, 2, 4, 330
+@pytest.mark.parametrize("max_len,rel,Hq", [(6, 1e-2, 4), (7, 1e-2, 4), (7, 5e-3, 4), (8, 5e-3, 4), (10, 1e-2, 4),
+                                            (12, 1e-2, 4), (6, 1e-2, 2), (5, 2e-2, 2), (5, 2e-2, 4), (6, 1e-2, 8),
+                                            (6, 1e-2, 16)])
+def test_code_length_limits_select_every_decoder_variant(gpu, oracle, max_len, rel, Hq):
+    """Shorter maximum code words: more symbols per decode window (5, 4, 3, 3, 2 for limits up to 6, 7, 8, 10, 12;
+    query-head groups of 4 and 8 take at most 4)."""
+    _say(f"max_code_len={max_len} rel={rel} Hq={Hq}")
+    B, H, S = 1, 2, 330
     Kx, Vx = W.make_kv(B, H, S, 31)
     oc = oracle.OracleCache(B, H, Hq, S + 64, rel, rel, max_code_len=max_len)
     oc.build_codebook(Kx, Vx)
