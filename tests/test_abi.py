@@ -56,7 +56,7 @@ def test_config_validation_needs_no_gpu(lib):
         assert lib.kvcomp_arena_bytes(ctypes.byref(bad)) == 0
     lib.kvcomp_baseline_workspace_bytes.restype = ctypes.c_size_t
     lib.kvcomp_baseline_workspace_bytes.argtypes = [ctypes.POINTER(binding.Config)]
-    assert lib.kvcomp_baseline_workspace_bytes(ctypes.byref(good)) == 32 * 64 * 130 * 4 + 32 * 4
+    assert lib.kvcomp_baseline_workspace_bytes(ctypes.byref(good)) == 32 * 128 * 130 * 4 + 32 * 4   # 128 split partials per query head + the tickets
 
 
 def test_library_codebook_matches_oracle_rules_without_a_gpu():
