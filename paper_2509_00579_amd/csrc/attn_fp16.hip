@@ -5,6 +5,7 @@
 // several heads, a small matrix product) on the matrix cores.
 #include <hip/hip_fp16.h>
 
+#include "huff_decode.cuh"
 #include "kvcomp_internal.h"
 #include "split_combine.cuh"
 
@@ -52,14 +53,18 @@ __device__ __forceinline__ void merge_waves_and_splits(const float (&comb)[kBWav
 }
 
 
-// Lane l of a wave owns channels 8*(l%16)..+7 and the tokens 4*i + l/16 (i = 0..15) of a 64-token tile.
+// Lane l of a wave owns channels 8*(l%16)..+7 and the tokens 4*i + l/16 (i = 0..15) of a 64-token tile: one load
+// instruction of the wave reads four whole 256-byte rows.  The loop is software-pipelined: the K rows of the next
+// tile are requested as soon as the scores of the current one are formed, behind the current tile's V rows, so that
+// a wave always has 16 KiB (and most of the time 32 KiB) on its way from memory; the 16-lane dot-product sums run on
+// DPP row operations, not on LDS permutes.
 template <int G>
-__global__ __launch_bounds__(64 * kBWaves) void baseline_attn_kernel(int B, int H, int Hq, const uint16_t *__restrict__ K,
-                                                                      const uint16_t *__restrict__ V, int seq,
-                                                                      const uint16_t *__restrict__ q, float scale,
-                                                                      float *__restrict__ partials,
-                                                                      uint32_t *__restrict__ counters,
-                                                                      float *__restrict__ out, int tokens_per_split) {
+__global__ __launch_bounds__(64 * kBWaves, 2) void baseline_attn_kernel(int B, int H, int Hq, const uint16_t *__restrict__ K,
+                                                                         const uint16_t *__restrict__ V, int seq,
+                                                                         const uint16_t *__restrict__ q, float scale,
+                                                                         float *__restrict__ partials,
+                                                                         uint32_t *__restrict__ counters,
+                                                                         float *__restrict__ out, int tokens_per_split) {
     __shared__ float comb[kBWaves][G][kPartialStride];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int split = blockIdx.x, bh = blockIdx.y, b = bh / H, h = bh - b * H;
@@ -84,14 +89,18 @@ __global__ __launch_bounds__(64 * kBWaves) void baseline_attn_kernel(int B, int 
     const uint16_t *Kb = K + ((size_t)b * seq * H + h) * kD + cc;
     const uint16_t *Vb = V + ((size_t)b * seq * H + h) * kD + cc;
 
-    for (int t0 = t_begin + wave * 64; t0 < t_end; t0 += 64 * kBWaves) {
-        float s[G][16];
-        uint4 kv[16];
+    uint4 kv[16];
+    auto load_k = [&](int t0) {
 #pragma unroll
         for (int i = 0; i < 16; i++) {
             const int t = t0 + 4 * i + sub;
             kv[i] = t < t_end ? *reinterpret_cast<const uint4 *>(Kb + (size_t)t * row) : make_uint4(0, 0, 0, 0);
         }
+    };
+    int t0 = t_begin + wave * 64;
+    if (t0 < t_end) load_k(t0);
+    for (; t0 < t_end; t0 += 64 * kBWaves) {
+        float s[G][16];
 #pragma unroll
         for (int i = 0; i < 16; i++) {
             float x[8];
@@ -102,11 +111,20 @@ __global__ __launch_bounds__(64 * kBWaves) void baseline_attn_kernel(int B, int 
                 float d = 0.f;
 #pragma unroll
                 for (int k = 0; k < 8; k++) d = fmaf(qr[g][k], x[k], d);
-#pragma unroll
-                for (int msk = 1; msk < 16; msk <<= 1) d += __shfl_xor(d, msk);
+                d += dpp_f<kDppXor1>(d);
+                d += dpp_f<kDppXor2>(d);
+                d += dpp_f<kDppHalfMirror>(d);
+                d += dpp_f<kDppMirror>(d);  // the row's 16 lanes all hold its dot product
                 s[g][i] = valid ? scale * d : -INFINITY;
             }
         }
+        uint4 vv[16];
+#pragma unroll
+        for (int i = 0; i < 16; i++) {
+            const int t = t0 + 4 * i + sub;
+            vv[i] = t < t_end ? *reinterpret_cast<const uint4 *>(Vb + (size_t)t * row) : make_uint4(0, 0, 0, 0);
+        }
+        if (t0 + 64 * kBWaves < t_end) load_k(t0 + 64 * kBWaves);  // behind the V rows: they are waited for first
         float p[G][16];
 #pragma unroll
         for (int g = 0; g < G; g++) {
@@ -130,10 +148,8 @@ __global__ __launch_bounds__(64 * kBWaves) void baseline_attn_kernel(int B, int 
         }
 #pragma unroll
         for (int i = 0; i < 16; i++) {
-            const int t = t0 + 4 * i + sub;
-            const uint4 v = t < t_end ? *reinterpret_cast<const uint4 *>(Vb + (size_t)t * row) : make_uint4(0, 0, 0, 0);
             float x[8];
-            unpack8(v, x);
+            unpack8(vv[i], x);
 #pragma unroll
             for (int g = 0; g < G; g++)
 #pragma unroll
@@ -185,7 +201,7 @@ __device__ __forceinline__ void wave_lds_sync() {
 }
 
 template <int G>
-__global__ __launch_bounds__(64 * kBWaves, 3) void baseline_attn_gqa_kernel(
+__global__ __launch_bounds__(64 * kBWaves, G == 8 ? 2 : 3) void baseline_attn_gqa_kernel(
     int B, int H, int Hq, const uint16_t *__restrict__ K, const uint16_t *__restrict__ V, int seq,
     const uint16_t *__restrict__ q, float scale, float *__restrict__ partials, uint32_t *__restrict__ counters,
     float *__restrict__ out, int tokens_per_split) {
@@ -217,8 +233,8 @@ __global__ __launch_bounds__(64 * kBWaves, 3) void baseline_attn_gqa_kernel(
     const uint16_t *Kb = K + ((size_t)b * seq * H + h) * kD + 8 * gq;
     const uint16_t *Vb = V + ((size_t)b * seq * H + h) * kD + cc;
 
-    for (int t0 = t_begin + wave * 64; t0 < t_end; t0 += 64 * kBWaves) {
-        uint4 kv[16];
+    uint4 kv[16];
+    auto load_k = [&](int t0) {
 #pragma unroll
         for (int tt = 0; tt < 4; tt++) {
             const int t = t0 + 16 * tt + j;
@@ -227,6 +243,14 @@ __global__ __launch_bounds__(64 * kBWaves, 3) void baseline_attn_gqa_kernel(
                 kv[tt * 4 + i] = t < t_end ? *reinterpret_cast<const uint4 *>(Kb + (size_t)t * row + 32 * i)
                                            : make_uint4(0, 0, 0, 0);
         }
+    };
+    // Groups of 8 run two waves per SIMD anyway (their accumulators) and have the registers to request the next
+    // tile's K rows early; groups of 4 are better off with three waves per SIMD and no look-ahead (measured).
+    constexpr bool kAhead = G == 8;
+    int t0 = t_begin + wave * 64;
+    if (kAhead && t0 < t_end) load_k(t0);
+    for (; t0 < t_end; t0 += 64 * kBWaves) {
+        if (!kAhead) load_k(t0);
         float s[16];
         float ml = -INFINITY;
 #pragma unroll
@@ -268,6 +292,8 @@ __global__ __launch_bounds__(64 * kBWaves, 3) void baseline_attn_gqa_kernel(
 #pragma unroll
             for (int k = 0; k < 8; k++) acc[g][k] *= al;
         }
+        // the K rows of the next tile travel with the V rows of this one (the scores above were their last use)
+        if (kAhead && t0 + 64 * kBWaves < t_end) load_k(t0 + 64 * kBWaves);
         constexpr int kChunk = G == 8 ? 8 : 16;  // V rows in flight per lane (register budget)
 #pragma unroll 1
         for (int i0 = 0; i0 < 16; i0 += kChunk) {

@@ -686,8 +686,11 @@ kvcomp_status kvcomp_baseline_fp16_attn(const kvcomp_config *cfg, const void *d_
     if (seq < 1) return fail(KVCOMP_ERR_INVALID_ARG, "seq must be positive");
     if (workspace_bytes < kvcomp_baseline_workspace_bytes(cfg)) return fail(KVCOMP_ERR_CAPACITY, "workspace too small");
     if (n_splits <= 0) {
+        // measured best with one workgroup per CU (two for groups of 8 heads): every wave keeps 16 to 32 KiB in flight,
+        // and more concurrent streams only cost locality in the memory system
         const int bh = cfg->batch * cfg->n_kv_heads;
-        n_splits = std::min({(int)kMaxSplits, std::max(1, seq / 256), std::max(1, (2048 + bh - 1) / bh)});
+        const int target = (G == 8 ? 2 : 1) * kCUs;
+        n_splits = std::min({(int)kMaxSplits, std::max(1, seq / 256), std::max(1, (target + bh - 1) / bh)});
     }
     n_splits = std::max(1, std::min(n_splits, (int)kMaxSplits));
     HIP_TRY(launch_baseline_attn(cfg->batch, cfg->n_kv_heads, cfg->n_q_heads, static_cast<const uint16_t *>(d_K),
