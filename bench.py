@@ -283,6 +283,18 @@ def main():
     ev[1].synchronize()
     base_ms = ev[0].elapsed_time(ev[1]) / (3 * nrep)
     base_bytes = 2 * B * H * S * 128 * 2 + B * Hq * 128 * (2 + 4)
+    # what a plain streaming read of the same two tensors takes (warm, like the kernels): the bound for any fp16 kernel
+    sink = torch.zeros(4, dtype=torch.uint8, device="cuda")
+    k8, v8 = dK.view(torch.uint8).reshape(-1), dV.view(torch.uint8).reshape(-1)
+    stream_bytes = 0
+    for r in range(11):   # the first round is a warm-up
+        if r == 1:
+            ev[2].record()
+        stream_bytes = binding.probe_read_stream(k8, sink) + binding.probe_read_stream(v8, sink)
+    ev[3].record()
+    ev[3].synchronize()
+    stream_ms = ev[2].elapsed_time(ev[3]) / 10
+    stream_GBps = stream_bytes / (stream_ms * 1e-3) / 1e9 if stream_bytes else None
     # the fp16 kernel with the caches scrubbed before every launch, like the fused kernel above
     base_cold_ms = None
     if args.cold:
@@ -404,6 +416,9 @@ def main():
         "store_GBps_fp16_in": (2 * B * H * S * 128 * 2) / (float(np.mean(store_ms)) * 1e-3) / 1e9,
         "fp16_baseline": {"ms": base_ms, "ms_cold": base_cold_ms, "GBps": base_bytes / (base_ms * 1e-3) / 1e9,
                           "pct_hbm_peak": 100.0 * base_bytes / (base_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+                          # a plain streaming read of the same K and V tensors (two launches, warm): no fp16
+                          # attention kernel can be faster than this
+                          "stream_read": {"ms": stream_ms, "GBps": stream_GBps, "bytes": stream_bytes},
                           "fused_kernel_speedup": base_ms / kern_ms,  # kernel against kernel, both HIP-event timed
                           "fused_step_speedup": base_ms / (dec_ms / T)},  # the fused side also appends a token
         # Section 4.3's comparison: decompress to fp16 in HBM (two launches, each synchronising once), then attention

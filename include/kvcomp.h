@@ -192,6 +192,12 @@ kvcomp_status kvcomp_baseline_fp16_attn(const kvcomp_config *cfg, const void *d_
                                         const void *d_q, float scale, float *d_out, void *d_workspace,
                                         size_t workspace_bytes, int n_splits, void *stream);
 
+/* Measurement aid: one plain streaming read of d_buf (DEVICE, 16-byte aligned) with 16-byte loads, the bound for any
+ * kernel that has to read an uncompressed cache of that size.  Up to 2048 workgroups read a whole number of 32 KiB pieces each,
+ * as much as fits into `bytes` (*h_bytes_read receives the total; 0 = nothing launched) and writes nothing; d_sink: DEVICE, 4 bytes, needed only so
+ * that the loads cannot be optimised away.  Stream-ordered; the caller times it. */
+kvcomp_status kvcomp_probe_read_stream(const void *d_buf, size_t bytes, void *d_sink, size_t *h_bytes_read, void *stream);
+
 const char *kvcomp_last_error(void);
 
 #ifdef __cplusplus

@@ -62,6 +62,7 @@ SIGNATURES = {
     "kvcomp_set_tuning": (_i, [_vp, _i, _i]),
     "kvcomp_set_profiling": (_i, [_vp, _i]),
     "kvcomp_get_profile": (_i, [_vp, C.POINTER(_i), C.POINTER(C.c_double)]),
+    "kvcomp_probe_read_stream": (_i, [_vp, C.c_size_t, _vp, C.POINTER(C.c_size_t), _vp]),
     "kvcomp_baseline_workspace_bytes": (C.c_size_t, [_cfgp]),
     "kvcomp_baseline_fp16_attn": (_i, [_cfgp, _vp, _vp, _i, _vp, _f, _vp, _vp, C.c_size_t, _i, _vp]),
     "kvcomp_last_error": (C.c_char_p, []),
@@ -283,6 +284,15 @@ class KVCompLayers:
     def close(self):
         for c in self.layers:
             c.close()
+
+
+def probe_read_stream(buf, sink):
+    """One plain streaming read of the uint8 CUDA tensor `buf` (measurement aid); returns the bytes it reads."""
+    assert buf.is_cuda and buf.is_contiguous() and sink.is_cuda and sink.numel() * sink.element_size() >= 4
+    n = C.c_size_t()
+    _check(load().kvcomp_probe_read_stream(C.c_void_p(buf.data_ptr()), buf.numel() * buf.element_size(),
+                                           C.c_void_p(sink.data_ptr()), C.byref(n), _stream()))
+    return n.value
 
 
 class BaselineFp16Attention:

@@ -343,6 +343,39 @@ __global__ __launch_bounds__(64 * kBWaves, G == 8 ? 2 : 3) void baseline_attn_gq
     merge_waves_and_splits<G>(comb, partials, counters, out, b, h, Hq, split, bh, tid);
 }
 
+// ---- a plain streaming read: the bound for any kernel that has to read the fp16 cache ---------------------------------
+// Every workgroup reads one contiguous chunk with 16-byte loads, eight in flight per lane, and folds the words;
+// the fold is stored only if it equals a value the caller's data does not produce (the loads must not be optimised
+// away), so normally nothing is written.
+constexpr int kStreamLoads = 8;
+__global__ __launch_bounds__(256) void read_stream_kernel(const uint4 *__restrict__ src, size_t per_wg16,
+                                                          uint32_t *__restrict__ sink) {
+    const uint4 *p = src + (size_t)blockIdx.x * per_wg16 + threadIdx.x;
+    uint32_t acc = 0;
+    for (size_t i = 0; i < per_wg16; i += 256 * kStreamLoads) {
+        uint4 v[kStreamLoads];
+#pragma unroll
+        for (int u = 0; u < kStreamLoads; u++) v[u] = p[i + (size_t)u * 256];
+#pragma unroll
+        for (int u = 0; u < kStreamLoads; u++) acc ^= v[u].x ^ v[u].y ^ v[u].z ^ v[u].w;
+    }
+    if (acc == 0x9e3779b9u && threadIdx.x == 1023) sink[0] = acc;  // never: blockDim.x is 256
+}
+
+// Up to 2048 workgroups, each reading a whole number of 32 KiB pieces (256 lanes x 8 loads x 16 bytes); *bytes_read
+// receives what is read in total (the largest such amount that fits into `bytes`).
+hipError_t launch_read_stream(const void *src, size_t bytes, uint32_t *sink, size_t *bytes_read, hipStream_t s) {
+    const size_t piece = (size_t)256 * kStreamLoads * 16;
+    const size_t grid = bytes / piece < 2048 ? bytes / piece : 2048;
+    *bytes_read = 0;
+    if (grid == 0) return hipSuccess;
+    const size_t per_wg = bytes / grid / piece * piece;
+    *bytes_read = per_wg * grid;
+    hipLaunchKernelGGL(read_stream_kernel, dim3((unsigned)grid), dim3(256), 0, s, static_cast<const uint4 *>(src),
+                       per_wg / 16, sink);
+    return hipGetLastError();
+}
+
 hipError_t launch_baseline_attn(int B, int H, int Hq, const uint16_t *K, const uint16_t *V, int seq, const uint16_t *q,
                                 float scale, float *out, float *partials, uint32_t *counters, int n_splits,
                                 hipStream_t s) {

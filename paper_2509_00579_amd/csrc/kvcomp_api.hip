@@ -674,6 +674,13 @@ size_t kvcomp_baseline_workspace_bytes(const kvcomp_config *cfg) {
     return (size_t)cfg->batch * cfg->n_q_heads * kMaxSplits * kPartialStride * 4 + (size_t)cfg->batch * cfg->n_kv_heads * 4;
 }
 
+kvcomp_status kvcomp_probe_read_stream(const void *d_buf, size_t bytes, void *d_sink, size_t *h_bytes_read, void *stream) {
+    if (!d_buf || !d_sink || !h_bytes_read) return fail(KVCOMP_ERR_INVALID_ARG, "NULL argument");
+    if (!aligned16(d_buf)) return fail(KVCOMP_ERR_INVALID_ARG, "d_buf must be 16-byte aligned");
+    HIP_TRY(launch_read_stream(d_buf, bytes, static_cast<uint32_t *>(d_sink), h_bytes_read, static_cast<hipStream_t>(stream)));
+    return KVCOMP_OK;
+}
+
 kvcomp_status kvcomp_baseline_fp16_attn(const kvcomp_config *cfg, const void *d_K, const void *d_V, int seq,
                                         const void *d_q, float scale, float *d_out, void *d_workspace,
                                         size_t workspace_bytes, int n_splits, void *stream) {

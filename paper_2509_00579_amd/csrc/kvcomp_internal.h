@@ -120,6 +120,7 @@ hipError_t launch_fused_attn(const Geo &g, const uint16_t *q, float scale, float
 hipError_t launch_baseline_attn(int B, int H, int Hq, const uint16_t *K, const uint16_t *V, int seq, const uint16_t *q,
                                 float scale, float *out, float *partials, uint32_t *counters, int n_splits,
                                 hipStream_t s);
+hipError_t launch_read_stream(const void *src, size_t bytes, uint32_t *sink, size_t *bytes_read, hipStream_t s);
 hipError_t launch_stats(const Geo &g, int n_blocks, hipStream_t s);
 hipError_t launch_fill_zero(void *p, size_t bytes, hipStream_t s);
 
