@@ -30,7 +30,7 @@ VALU_INSTR_PER_SYMBOL = 7.35  # rocprofv3 SQ_INSTS_VALU / decoded wave-symbols (
 MEASURED_LDS_BUSY = {("c1", 1e-2, 7): 0.38, ("c2", 1e-2, 7): 0.77}
 # HBM bytes per fused-kernel launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by a copy of known size
 # (profiles/); keyed by (workload, rel_eb, max code word); None where not measured.
-MEASURED_TRAFFIC = {("c1", 1e-2, 7): 27.06e6}  # bytes per launch, profiles/fused_attn_kernel_c1.md
+MEASURED_TRAFFIC = {("c1", 1e-2, 7): 27.05e6}  # bytes per launch, profiles/fused_attn_kernel_c1.md
 
 
 def parse_args():
