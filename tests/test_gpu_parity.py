@@ -294,6 +294,54 @@ def test_many_sequence_splits(gpu, oracle):
     gc.close()
 
 
+def _random_cases(n):
+    rng = np.random.default_rng(2024)
+    cases = []
+    for i in range(n):
+        H = int(rng.choice([1, 2, 3]))
+        G = int(rng.choice([1, 2, 4, 8]))
+        rel_k, rel_v = (float(x) for x in rng.choice([4e-3, 1e-2, 2e-2, 5e-2, 0.1], 2))
+        levels = int(np.rint(1.0 / (2.0 * np.float32(min(rel_k, rel_v))))) + 1
+        lo = int(np.ceil(np.log2(levels)))
+        cases.append((int(rng.choice([1, 2])), H, H * G, int(rng.integers(64, 700)), rel_k, rel_v,
+                      int(rng.choice([0, 1])), int(rng.integers(lo, 13)), int(rng.choice([64, 64, 128, 256])),
+                      int(rng.integers(0, 150)), 100 + i))
+    return cases
+
+
+@pytest.mark.parametrize("B,H,Hq,S,rel_k,rel_v,k_mode,max_len,window,extra,seed", _random_cases(12))
+def test_random_small_configs(gpu, oracle, B, H, Hq, S, rel_k, rel_v, k_mode, max_len, window, extra, seed):
+    """Seeded random combinations of batch, heads, group size, length, error bounds, K unit, code word limit, buffer
+    size and appended tokens: whole cache and decompressed tensors bit for bit, attention within tolerance."""
+    _say(f"random case: B={B} H={H} Hq={Hq} S={S} rel {rel_k}/{rel_v} k_mode={k_mode} limit {max_len} "
+         f"buffer {window} +{extra} tokens")
+    max_seq = (S + extra + 63) // 64 * 64
+    Kx, Vx = W.make_kv(B, H, S, seed)
+    oc = oracle.OracleCache(B, H, Hq, max_seq, rel_k, rel_v, k_mode, max_len, buffer_tokens=window)
+    gc = gpu.KVCompCache(B, H, Hq, max_seq, rel_k, rel_v, k_mode=k_mode, max_code_len=max_len, buffer_tokens=window)
+    oc.build_codebook(Kx, Vx)
+    gc.build_codebook(_dev(Kx), _dev(Vx))
+    oc.compress_blocks(Kx, Vx)
+    gc.compress_blocks(_dev(Kx), _dev(Vx))
+    kn, vn = W.make_new_tokens(B, H, max(extra, 1), seed)
+    qs = W.make_queries(B, Hq, max(extra, 1), seed)
+    for t in range(extra):
+        oc.append_token(kn[t], vn[t])
+        if t % 5 == 4:
+            gc.append_token(_dev(kn[t]), _dev(vn[t]))
+        else:
+            out = gc.append_attn_decode(_dev(kn[t]), _dev(vn[t]), _dev(qs[t]), SCALE)
+            if t % 16 == 0:
+                _attn_close(out.cpu().numpy(), oc.attn_decode(qs[t], SCALE))
+    _assert_same_cache(oc, gc)
+    _attn_close(gc.attn_decode(_dev(qs[0]), SCALE).cpu().numpy(), oc.attn_decode(qs[0], SCALE))
+    tokens = S + extra
+    for which in (K, V):
+        got = gc.decompress(which, tokens).cpu().numpy()
+        np.testing.assert_array_equal(got.view(np.uint16), oc.decompress(which).view(np.uint16))
+    gc.close()
+
+
 def test_layers_have_their_own_codebooks(gpu, oracle):
     """One context per layer in a single allocation (Section 3: codebooks are per layer): every layer matches an oracle
     cache of its own data, appends to one layer leave the others untouched, and the codebooks differ between layers
