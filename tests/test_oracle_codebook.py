@@ -158,6 +158,32 @@ def test_length_limit(oracle):
         assert sum(int(a) * int(b) for a, b in zip(f, ln[:n])) == _heap_huffman_cost(f)
 
 
+def test_every_admissible_limit_on_random_histograms(oracle):
+    # peaked histograms of the workloads' alphabet sizes under every limit from the fixed-length width up to 12: the
+    # limit holds, Kraft stays an equality, a more frequent level never gets a longer word, and the lengths are an
+    # optimal code for the counts after the reported number of halvings (checked against a heap Huffman written here)
+    rng = np.random.default_rng(77)
+    for nsym in (6, 8, 21, 26, 51, 101, 126):
+        for trial in range(3):
+            centre, width = rng.uniform(0, nsym), rng.uniform(0.5, nsym / 3)
+            counts = np.rint(1e6 * np.exp(-0.5 * ((np.arange(nsym) - centre) / width) ** 2)).astype(np.int64)
+            counts[rng.integers(0, nsym, 3)] = 0   # some levels unseen at prefill
+            for max_len in range(max(1, math.ceil(math.log2(nsym))), 13):
+                ln, cd, halv = oracle.build_codebook(_hist(counts), nsym, max_len)
+                assert 1 <= int(ln[:nsym].min()) and int(ln.max()) <= max_len and not ln[nsym:].any()
+                assert _kraft_units(ln) == 1 << 16
+                f = np.array([max(1, int(v)) for v in counts], dtype=object)
+                for _ in range(halv):
+                    f = np.array([max(1, (int(v) + 1) >> 1) for v in f], dtype=object)
+                assert sum(int(a) * int(b) for a, b in zip(f, ln[:nsym])) == _heap_huffman_cost(f)
+                order = np.argsort(-f.astype(np.float64), kind="stable")
+                lens_by_freq = [int(ln[i]) for i in order]
+                freqs = [int(f[i]) for i in order]
+                for a in range(nsym - 1):
+                    if freqs[a] > freqs[a + 1]:
+                        assert lens_by_freq[a] <= min(lens_by_freq[a + 1:])
+
+
 def test_unseen_levels_still_get_codes(oracle):
     # the codebook is built once at prefill and reused for later blocks: every level below n_sym must be encodable
     counts = [0] * 51
