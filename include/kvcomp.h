@@ -95,7 +95,8 @@ kvcomp_status kvcomp_reset(kvcomp_ctx *ctx, int keep_codebook, void *stream);
 /* ---- the four calls of the hot path ---------------------------------------------------------------------- */
 
 /* Store stage, step "histogram on the GPU, codebook once at prefill" (Section 3; Section 3.2): quantize the
- * floor(seq/64) full blocks of d_K and d_V (K: per channel inside each block, V: per token; Section 3.1.1),
+ * floor(seq/64) full blocks of d_K and d_V (K: per channel inside each block, or per block with k_mode 1; V: per
+ * token; Section 3.1.1, Section 4.2),
  * histogram the codes on the device, build one canonical Huffman codebook for K and one for V on the host and
  * upload the encode table and the decode lookup table.  d_K, d_V: device fp16 [batch, seq, n_kv_heads, 128],
  * read-only.  SYNCHRONISES `stream` (the histogram crosses to the host, as in the paper).
@@ -107,8 +108,8 @@ kvcomp_status kvcomp_build_codebook(kvcomp_ctx *ctx, const void *d_K, const void
  * records), fill the Block Offsets Array; the newest tokens go to the fp16 buffer.  The split is the one that seq
  * calls of kvcomp_append_token would leave: floor(seq/64) blocks and seq%64 buffered tokens with the default
  * buffer, in general n = 0 if seq < buffer_tokens, else floor((seq - buffer_tokens)/64) + 1 blocks and seq - 64 n
- * buffered tokens.  The cache must be empty.  Inputs as for kvcomp_build_codebook.  SYNCHRONISES `stream` once at the end (reads back the
- * arena tail and the largest record size, and the non-finite flag).
+ * buffered tokens.  The cache must be empty.  Inputs as for kvcomp_build_codebook.  SYNCHRONISES `stream` once at
+ * the end (reads back the arena tail and the largest record size, and the non-finite flag).
  * Errors: STATE (no codebook / cache not empty), CAPACITY (seq > max_seq), NONFINITE, HIP. */
 kvcomp_status kvcomp_compress_blocks(kvcomp_ctx *ctx, const void *d_K, const void *d_V, int seq, void *stream);
 
