@@ -321,9 +321,10 @@ kvcomp_status kvcomp_build_codebook(kvcomp_ctx *ctx, const void *d_K, const void
     HIP_TRY(launch_fill_zero(g.hist, 2 * 256 * 4, s));
     HIP_TRY(launch_histogram(g, 0, static_cast<const uint16_t *>(d_K), seq, seq / kBT, s));
     HIP_TRY(launch_histogram(g, 1, static_cast<const uint16_t *>(d_V), seq, seq / kBT, s));
-    HIP_TRY(hipMemcpyAsync(ctx->h_hist, g.hist, 2 * 256 * 4, hipMemcpyDeviceToHost, s));
-    kvcomp_status st = read_ctrl(ctx, s);
-    if (st) return st;
+    // control words and histograms are neighbours in the arena and in the pinned staging block: one copy
+    static_assert(sizeof(Ctrl) <= 256, "control words fill the first 256 bytes");
+    HIP_TRY(hipMemcpyAsync(ctx->h_ctrl, g.ctrl, 256 + 2 * 256 * 4, hipMemcpyDeviceToHost, s));
+    HIP_TRY(hipStreamSynchronize(s));
     if (ctx->h_ctrl->nonfinite) {
         (void)hipMemsetAsync(&g.ctrl->nonfinite, 0, sizeof(uint32_t), s);
         (void)hipStreamSynchronize(s);
@@ -366,9 +367,8 @@ kvcomp_status kvcomp_build_codebook(kvcomp_ctx *ctx, const void *d_K, const void
             }
         }
     }
-    HIP_TRY(hipMemcpyAsync(g.enc, ctx->h_enc, 4 * 256 * 4, hipMemcpyHostToDevice, s));
-    HIP_TRY(hipMemcpyAsync(g.lut, ctx->h_lut, 2 * kLutSize * 2, hipMemcpyHostToDevice, s));
-    HIP_TRY(hipMemcpyAsync(g.tree, ctx->h_tree, 2 * 256 * 2 * 2, hipMemcpyHostToDevice, s));
+    // encode tables, decode tables and trees are neighbours too: one upload
+    HIP_TRY(hipMemcpyAsync(g.enc, ctx->h_enc, 4 * 256 * 4 + 2 * kLutSize * 2 + 2 * 256 * 2 * 2, hipMemcpyHostToDevice, s));
     HIP_TRY(hipStreamSynchronize(s));
     ctx->have_codebook = true;
     return KVCOMP_OK;
