@@ -9,6 +9,10 @@
  *   - Pointers named d_* are DEVICE pointers (HIP global memory), pointers named h_* are HOST pointers.
  *   - The caller owns all device memory, including the arena handed to kvcomp_create; the library allocates no
  *     device memory.  `stream` arguments are a hipStream_t passed as void* (NULL = the default stream).
+ *   - The stream-ordered calls may be captured into a HIP graph (they launch kernels only).  A replay repeats the
+ *     device work, not the host-side bookkeeping of the context (block and buffer counts): replay a captured sequence
+ *     only from the cache state its capture started from, and bring the context back to a known state with eager
+ *     calls (kvcomp_reset + kvcomp_compress_blocks) before using it eagerly again.
  *   - One context holds the cache of one transformer layer (Section 3: buffers and codebooks are per layer).
  *     A context must be used by one host thread at a time.
  *   - KV tensors are fp16, shape [batch, seq, n_kv_heads, 128] (the paper's [context_len, head_num, head_dim]

@@ -342,6 +342,55 @@ def test_random_small_configs(gpu, oracle, B, H, Hq, S, rel_k, rel_v, k_mode, ma
     gc.close()
 
 
+def test_decode_loop_in_a_hip_graph(gpu, oracle):
+    """The decode loop (append + attention per step, one flush inside) captured in a HIP graph, as bench.py times it:
+    every replay -- with an eager reset and prefill of the cache in between -- must give the eager loop's outputs bit
+    for bit; the last step is also checked against the oracle."""
+    import torch
+    _say("decode loop of 20 steps in a HIP graph, three replays")
+    B, H, Hq, S0, T = 2, 2, 4, 180, 20      # 180 = 2 blocks + 52 buffered: the 12th append completes a block
+    Kx, Vx, oc, gc = _both(gpu, oracle, B, H, Hq, S0, S0, 256, 1e-2, 1e-2, 33)
+    kn, vn = W.make_new_tokens(B, H, T, 33)
+    qs = W.make_queries(B, Hq, T, 33)
+    dK, dV, dkn, dvn, dq = _dev(Kx[:, :S0]), _dev(Vx[:, :S0]), _dev(kn), _dev(vn), _dev(qs)
+    outs = torch.empty((T, B, Hq, 128), dtype=torch.float32, device="cuda:0")
+
+    def loop():
+        for t in range(T):
+            gc.append_attn_decode(dkn[t], dvn[t], dq[t], SCALE, outs[t])
+
+    def prefill():
+        gc.reset(keep_codebook=True)
+        gc.compress_blocks(dK, dV)
+
+    loop()
+    torch.cuda.synchronize()
+    eager = outs.cpu().numpy().copy()
+    for t in range(T):
+        oc.append_token(kn[t], vn[t])
+    _attn_close(eager[T - 1], oc.attn_decode(qs[T - 1], SCALE))
+    _assert_same_cache(oc, gc)
+    prefill()
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        loop()
+    for replay in range(3):
+        prefill()                      # eager work and a synchronisation between the replays
+        outs.zero_()
+        graph.replay()
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(outs.cpu().numpy(), eager, err_msg=f"replay {replay}")
+    # a replay runs the device work only: the context's host-side counters are where the last eager call left them
+    # (the prefill), so the cache is brought back to a consistent state eagerly before it is used again
+    prefill()
+    loop()
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(outs.cpu().numpy(), eager)
+    _assert_same_cache(oc, gc)
+    gc.close()
+
+
 def test_layers_have_their_own_codebooks(gpu, oracle):
     """One context per layer in a single allocation (Section 3: codebooks are per layer): every layer matches an oracle
     cache of its own data, appends to one layer leave the others untouched, and the codebooks differ between layers
