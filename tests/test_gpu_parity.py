@@ -391,6 +391,44 @@ def test_decode_loop_in_a_hip_graph(gpu, oracle):
     gc.close()
 
 
+def test_on_a_side_stream(gpu, oracle):
+    """Every call takes the caller's stream: the whole path on a non-default stream (default priority), with the
+    default stream kept busy by unrelated work, gives the same cache and attention."""
+    import torch
+    _say("the path on a side stream")
+    B, H, Hq, S = 1, 2, 4, 300
+    Kx, Vx = W.make_kv(B, H, S, 34)
+    oc = oracle.OracleCache(B, H, Hq, 384, 1e-2, 1e-2)
+    oc.build_codebook(Kx, Vx)
+    oc.compress_blocks(Kx, Vx)
+    kn, vn = W.make_new_tokens(B, H, 30, 34)
+    q = W.make_queries(B, Hq, 1, 34)[0]
+    for t in range(30):
+        oc.append_token(kn[t], vn[t])
+    dK, dV, dkn, dvn, dq = _dev(Kx), _dev(Vx), _dev(kn), _dev(vn), _dev(q)
+    busy = torch.empty(64 << 20, dtype=torch.uint8, device="cuda:0")
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        gc = gpu.KVCompCache(B, H, Hq, 384, 1e-2, 1e-2)
+        gc.build_codebook(dK, dV)
+        torch.cuda.default_stream().wait_stream(side)   # unrelated work on the default stream, ordered after this point
+        with torch.cuda.stream(torch.cuda.default_stream()):
+            for _ in range(4):
+                busy.fill_(1)
+        gc.compress_blocks(dK, dV)
+        for t in range(30):
+            if t % 2:
+                gc.append_token(dkn[t], dvn[t])
+            else:
+                gc.append_attn_decode(dkn[t], dvn[t], dq, SCALE)
+        out = gc.attn_decode(dq, SCALE)
+        side.synchronize()
+        _assert_same_cache(oc, gc)
+        _attn_close(out.cpu().numpy(), oc.attn_decode(q, SCALE))
+        gc.close()
+
+
 def test_layers_have_their_own_codebooks(gpu, oracle):
     """One context per layer in a single allocation (Section 3: codebooks are per layer): every layer matches an oracle
     cache of its own data, appends to one layer leave the others untouched, and the codebooks differ between layers
