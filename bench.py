@@ -25,6 +25,9 @@ HBM_PEAK_GBPS = 8000.0  # MI355X HBM3E, published
 # x 32 lanes x 2 flops, i.e. one wave64 instruction per SIMD every 2 cycles
 VALU_ISSUE_PER_S = 157.3e12 / 2 / 64
 VALU_INSTR_PER_SYMBOL = 7.35  # rocprofv3 SQ_INSTS_VALU / decoded wave-symbols (profiles/fused_attn_kernel_c1.md)
+# two of them per symbol (the byte-to-float conversion and the FMA with the DPP quad broadcast) issue at half rate
+# (paper_2509_00579_amd/probes/valu_issue.hip: 4 cycles per wave64 instruction instead of 2): 9.35 issue slots
+VALU_SLOTS_PER_SYMBOL = VALU_INSTR_PER_SYMBOL + 2.0
 # share of the busy cycles in which the LDS pipe is active, the busiest unit of the fused kernel (rocprofv3
 # SQ_LDS_IDX_ACTIVE / SQ_BUSY_CU_CYCLES, profiles/): keyed like MEASURED_TRAFFIC
 MEASURED_LDS_BUSY = {("c1", 1e-2, 7): 0.38, ("c2", 1e-2, 7): 0.77}
@@ -438,12 +441,13 @@ def main():
                                "event pair around every launch of one eager pass of the decode loop, which also sees "
                                "the gap to the previous kernel"},
         # The kernel is not bound by HBM: per decoded symbol it spends one LDS table lookup and about seven VALU
-        # instructions.  Symbols decoded per second against what the vector ALUs could issue at the measured
-        # instruction count per symbol, and the measured share of cycles with the LDS pipe busy.
+        # instructions, two of them at half rate.  Symbols decoded per second against what the vector ALUs could
+        # issue at that cost per symbol, and the measured share of cycles with the LDS pipe busy.
         "roofline_alu": {"bound": "alu", "achieved": symbols_per_launch / (kern_ms * 1e-3) / 1e12,
-                         "peak": VALU_ISSUE_PER_S * 64 / VALU_INSTR_PER_SYMBOL / 1e12, "unit": "Tsymbol/s",
-                         "frac": symbols_per_launch / (kern_ms * 1e-3) / (VALU_ISSUE_PER_S * 64 / VALU_INSTR_PER_SYMBOL),
+                         "peak": VALU_ISSUE_PER_S * 64 / VALU_SLOTS_PER_SYMBOL / 1e12, "unit": "Tsymbol/s",
+                         "frac": symbols_per_launch / (kern_ms * 1e-3) / (VALU_ISSUE_PER_S * 64 / VALU_SLOTS_PER_SYMBOL),
                          "valu_instr_per_symbol": VALU_INSTR_PER_SYMBOL,
+                         "valu_issue_slots_per_symbol": VALU_SLOTS_PER_SYMBOL,
                          "lds_busy_frac": MEASURED_LDS_BUSY.get((args.workload, rel_eb, args.max_code_len))},
         "cpu_baseline": cpu,
     }

@@ -1,4 +1,6 @@
-// VALU issue: cycles per v_fmac_f32 per wave and per SIMD for 1..8 waves per SIMD (independent accumulators).
+// VALU issue: cycles per instruction per wave and per SIMD for 1..8 waves per SIMD (independent accumulators):
+// kind 0 v_fmac_f32, 1 v_and_b32, 2 v_lshrrev_b32, 3 v_fmac_f32 with a DPP quad broadcast, 4 v_cvt_f32_ubyte1,
+// 5 v_readlane_b32.
 #include <hip/hip_runtime.h>
 #include <cstdio>
 #include <cstdlib>
@@ -19,6 +21,9 @@ __global__ __launch_bounds__(256) void probe(float *out, long long *cyc, int ite
                 if (KIND == 0) asm volatile("v_fmac_f32 %0, %1, %2" : "+v"(x[k]) : "v"(a), "v"(b));
                 if (KIND == 1) asm volatile("v_and_b32 %0, %1, %0" : "+v"(u[k]) : "v"(a));
                 if (KIND == 2) asm volatile("v_lshrrev_b32 %0, %1, %0" : "+v"(u[k]) : "v"(a));
+                if (KIND == 3) asm volatile("v_fmac_f32_dpp %0, %1, %2 quad_perm:[1,1,1,1] row_mask:0xf bank_mask:0xf" : "+v"(x[k]) : "v"(a), "v"(b));
+                if (KIND == 4) asm volatile("v_cvt_f32_ubyte1 %0, %1" : "=v"(x[k]) : "v"(u[k]));
+                if (KIND == 5) asm volatile("v_readlane_b32 %0, %1, 3" : "=s"(u[k]) : "v"(a));
             }
     }
     long long t1 = clock64();
@@ -32,8 +37,8 @@ int main() {
     CHECK(hipMalloc(&d_out, 8192 * 256 * 4)); CHECK(hipMemset(d_out, 0, 8192 * 256 * 4));
     CHECK(hipMalloc(&d_cyc, 2 * 8192 * 8));
     const int iters = 20000;
-    for (int kind = 0; kind < 3; kind++)
-        for (int wps : {1, 2, 4, 8}) {
+    for (int kind = 0; kind < 6; kind++)
+        for (int wps : {1, 2, 4}) {
             const int n_wg = 256 * wps;
             double us = 0;
             for (int rep = 0; rep < 2; rep++) {
@@ -42,6 +47,9 @@ int main() {
                 if (kind == 0) hipLaunchKernelGGL(probe<0>, dim3(n_wg), dim3(256), 0, 0, d_out, d_cyc, iters);
                 if (kind == 1) hipLaunchKernelGGL(probe<1>, dim3(n_wg), dim3(256), 0, 0, d_out, d_cyc, iters);
                 if (kind == 2) hipLaunchKernelGGL(probe<2>, dim3(n_wg), dim3(256), 0, 0, d_out, d_cyc, iters);
+                if (kind == 3) hipLaunchKernelGGL(probe<3>, dim3(n_wg), dim3(256), 0, 0, d_out, d_cyc, iters);
+                if (kind == 4) hipLaunchKernelGGL(probe<4>, dim3(n_wg), dim3(256), 0, 0, d_out, d_cyc, iters);
+                if (kind == 5) hipLaunchKernelGGL(probe<5>, dim3(n_wg), dim3(256), 0, 0, d_out, d_cyc, iters);
                 CHECK(hipDeviceSynchronize());
                 us = std::chrono::duration<double, std::micro>(std::chrono::steady_clock::now() - w0).count();
             }
