@@ -429,6 +429,28 @@ def test_on_a_side_stream(gpu, oracle):
         gc.close()
 
 
+@pytest.mark.parametrize("Hq,scale", [(2, 4.0), (8, 4.0), (2, 1e-4), (16, 30.0)])
+def test_sharp_and_flat_softmax(gpu, oracle, Hq, scale):
+    """Softmax scales far from 1/sqrt(128): with a large scale one token takes nearly all the weight (scores of the
+    order of +-10^3, partial maxima that differ by hundreds between waves and splits), with a tiny one the weights
+    are uniform.  Buffered tokens take part, so the sharpest token may sit in the fp16 buffer."""
+    _say(f"softmax scale {scale}, Hq={Hq}")
+    B, H, S = 1, 2, 1500
+    Kx, Vx = W.make_kv(B, H, S, 35)
+    oc = oracle.OracleCache(B, H, Hq, 1536, 1e-2, 1e-2, 0, 7, buffer_tokens=128)
+    gc = gpu.KVCompCache(B, H, Hq, 1536, 1e-2, 1e-2, max_code_len=7, buffer_tokens=128)
+    oc.build_codebook(Kx, Vx)
+    oc.compress_blocks(Kx, Vx)
+    gc.build_codebook(_dev(Kx), _dev(Vx))
+    gc.compress_blocks(_dev(Kx), _dev(Vx))
+    q = W.make_queries(B, Hq, 1, 35)[0]
+    for n_splits in (0, 1, 7):
+        gc.set_tuning(n_splits=n_splits)
+        err = _attn_close(gc.attn_decode(_dev(q), scale).cpu().numpy(), oc.attn_decode(q, scale))
+    _say(f"  max abs err {err:.2e}")
+    gc.close()
+
+
 def test_layers_have_their_own_codebooks(gpu, oracle):
     """One context per layer in a single allocation (Section 3: codebooks are per layer): every layer matches an oracle
     cache of its own data, appends to one layer leave the others untouched, and the codebooks differ between layers
