@@ -188,12 +188,14 @@ __device__ __forceinline__ void split_fp16(float w, _Float16 *hi, _Float16 *lo) 
     *lo = (_Float16)(w - (float)h);
 }
 // the chain's CNT decoded symbols of one round as the B operand (unused slots zero)
+// (the wide table holds the symbol as an fp16 number in the upper half of its entries: two entries give a packed
+// pair with one byte permute, no conversion)
 template <int CNT>
 __device__ __forceinline__ v4h symbols_fp16(const uint32_t (&e)[CNT]) {
-    v4h b = {(_Float16)0.f, (_Float16)0.f, (_Float16)0.f, (_Float16)0.f};
-#pragma unroll
-    for (int k = 0; k < CNT; k++) b[k] = (_Float16)(unsigned short)(e[k] >> 8);
-    return b;
+    const uint32_t e0 = e[0], e1 = CNT > 1 ? e[CNT > 1 ? 1 : 0] : 0u, e2 = CNT > 2 ? e[CNT > 2 ? 2 : 0] : 0u,
+                   e3 = CNT > 3 ? e[CNT > 3 ? 3 : 0] : 0u;
+    const uint2 v = make_uint2(__builtin_amdgcn_perm(e1, e0, 0x07060302u), __builtin_amdgcn_perm(e3, e2, 0x07060302u));
+    return __builtin_bit_cast(v4h, v);
 }
 // macc += (hi + lo) . b for the heads 4 q + (lane & 3); entry = this lane's 16 bytes
 __device__ __forceinline__ v4f mfma_split(const uint4 entry, v4h b, v4f acc) {
@@ -228,7 +230,7 @@ __device__ __forceinline__ void k_block(const uint32_t *hdr32, const char *lut, 
     constexpr int kRounds = kHalf / NS, kTail = kHalf - kRounds * NS;
     constexpr int kP1 = NS > 4 ? 3 : NS, kP2 = NS - kP1;  // pieces of a window (kP2 = 0: taken whole)
     static_assert(kTail <= 4 && (G < kMfmaMinG || kP2 == 0), "pieces");
-    Quad qd;
+    QuadT<(G >= kMfmaMinG ? 2 : 1)> qd;
     if constexpr (G >= kMfmaMinG) {
         constexpr int R = MfmaRounds<NS>::kCount, Q4 = G / 4;
         float amax = 0.f;
@@ -270,12 +272,12 @@ __device__ __forceinline__ void k_block(const uint32_t *hdr32, const char *lut, 
 #pragma unroll
         for (int r = 0; r < kRounds; r++) {
             uint32_t fau[NS], fad[NS], fbu[NS], fbd[NS];
-            qd.step<NS>(wm1, lut, mask2, fau, fad, fbu, fbd);
+            qd.template step<NS>(wm1, lut, mask2, fau, fad, fbu, fbd);
             accumulate(r, symbols_fp16<NS>(fau), symbols_fp16<NS>(fad), symbols_fp16<NS>(fbu), symbols_fp16<NS>(fbd));
         }
         if constexpr (kTail > 0) {
             uint32_t fau[kTail], fad[kTail], fbu[kTail], fbd[kTail];
-            qd.step<kTail>(wm1, lut, mask2, fau, fad, fbu, fbd);
+            qd.template step<kTail>(wm1, lut, mask2, fau, fad, fbu, fbd);
             accumulate(kRounds, symbols_fp16<kTail>(fau), symbols_fp16<kTail>(fad), symbols_fp16<kTail>(fbu),
                        symbols_fp16<kTail>(fbd));
         }
@@ -303,18 +305,18 @@ __device__ __forceinline__ void k_block(const uint32_t *hdr32, const char *lut, 
         for (int r = 0; r < kRounds; r++) {
             if constexpr (kP2 == 0) {
                 uint32_t fau[NS], fad[NS], fbu[NS], fbd[NS];
-                qd.step<NS>(wm1, lut, mask2, fau, fad, fbu, fbd);
+                qd.template step<NS>(wm1, lut, mask2, fau, fad, fbu, fbd);
                 k_accum<G, NS>(wl, wdn, wq, r * NS, fau, fad, fbu, fbd, acc);
             } else {  // a window of more than four symbols is taken in two pieces: fewer table entries in flight
                 qd.begin(wm1);
                 {
                     uint32_t fau[kP1], fad[kP1], fbu[kP1], fbd[kP1];
-                    qd.part<kP1>(lut, mask2, fau, fad, fbu, fbd);
+                    qd.template part<kP1>(lut, mask2, fau, fad, fbu, fbd);
                     k_accum<G, kP1>(wl, wdn, wq, r * NS, fau, fad, fbu, fbd, acc);
                 }
                 {
                     uint32_t fau[kP2 ? kP2 : 1], fad[kP2 ? kP2 : 1], fbu[kP2 ? kP2 : 1], fbd[kP2 ? kP2 : 1];
-                    qd.part<(kP2 ? kP2 : 1)>(lut, mask2, fau, fad, fbu, fbd);
+                    qd.template part<(kP2 ? kP2 : 1)>(lut, mask2, fau, fad, fbu, fbd);
                     k_accum<G, (kP2 ? kP2 : 1)>(wl, wdn, wq, r * NS + kP1, fau, fad, fbu, fbd, acc);
                 }
                 qd.end(wm1);
@@ -322,7 +324,7 @@ __device__ __forceinline__ void k_block(const uint32_t *hdr32, const char *lut, 
         }
         if constexpr (kTail > 0) {
             uint32_t fau[kTail], fad[kTail], fbu[kTail], fbd[kTail];
-            qd.step<kTail>(wm1, lut, mask2, fau, fad, fbu, fbd);
+            qd.template step<kTail>(wm1, lut, mask2, fau, fad, fbu, fbd);
             k_accum<G, kTail>(wl, wdn, wq, kRounds * NS, fau, fad, fbu, fbd, acc);
         }
     }
@@ -352,7 +354,7 @@ __device__ __forceinline__ void v_block(const uint32_t *hdr32, const char *lut, 
     constexpr int kRounds = kHalf / NS, kTail = kHalf - kRounds * NS;
     constexpr int kP1 = NS > 4 ? 3 : NS, kP2 = NS - kP1;  // pieces of a window (kP2 = 0: taken whole)
     static_assert(kTail <= 4 && (G < kMfmaMinG || kP2 == 0), "pieces");
-    Quad qd;
+    QuadT<(G >= kMfmaMinG ? 2 : 1)> qd;
     if constexpr (G >= kMfmaMinG) {
         constexpr int R = MfmaRounds<NS>::kCount, Q4 = G / 4;
         float amax = 0.f;
@@ -391,12 +393,12 @@ __device__ __forceinline__ void v_block(const uint32_t *hdr32, const char *lut, 
 #pragma unroll
         for (int r = 0; r < kRounds; r++) {
             uint32_t fau[NS], fad[NS], fbu[NS], fbd[NS];
-            qd.step<NS>(wm1, lut, mask2, fau, fad, fbu, fbd);
+            qd.template step<NS>(wm1, lut, mask2, fau, fad, fbu, fbd);
             accumulate(r, symbols_fp16<NS>(fau), symbols_fp16<NS>(fad), symbols_fp16<NS>(fbu), symbols_fp16<NS>(fbd));
         }
         if constexpr (kTail > 0) {
             uint32_t fau[kTail], fad[kTail], fbu[kTail], fbd[kTail];
-            qd.step<kTail>(wm1, lut, mask2, fau, fad, fbu, fbd);
+            qd.template step<kTail>(wm1, lut, mask2, fau, fad, fbu, fbd);
             accumulate(kRounds, symbols_fp16<kTail>(fau), symbols_fp16<kTail>(fad), symbols_fp16<kTail>(fbu),
                        symbols_fp16<kTail>(fbd));
         }
@@ -419,18 +421,18 @@ __device__ __forceinline__ void v_block(const uint32_t *hdr32, const char *lut, 
         for (int r = 0; r < kRounds; r++) {
             if constexpr (kP2 == 0) {
                 uint32_t fau[NS], fad[NS], fbu[NS], fbd[NS];
-                qd.step<NS>(wm1, lut, mask2, fau, fad, fbu, fbd);
+                qd.template step<NS>(wm1, lut, mask2, fau, fad, fbu, fbd);
                 v_accum<G, NS>(wl, wdn, wq, r * NS, fau, fad, fbu, fbd, st.acc);
             } else {
                 qd.begin(wm1);
                 {
                     uint32_t fau[kP1], fad[kP1], fbu[kP1], fbd[kP1];
-                    qd.part<kP1>(lut, mask2, fau, fad, fbu, fbd);
+                    qd.template part<kP1>(lut, mask2, fau, fad, fbu, fbd);
                     v_accum<G, kP1>(wl, wdn, wq, r * NS, fau, fad, fbu, fbd, st.acc);
                 }
                 {
                     uint32_t fau[kP2 ? kP2 : 1], fad[kP2 ? kP2 : 1], fbu[kP2 ? kP2 : 1], fbd[kP2 ? kP2 : 1];
-                    qd.part<(kP2 ? kP2 : 1)>(lut, mask2, fau, fad, fbu, fbd);
+                    qd.template part<(kP2 ? kP2 : 1)>(lut, mask2, fau, fad, fbu, fbd);
                     v_accum<G, (kP2 ? kP2 : 1)>(wl, wdn, wq, r * NS + kP1, fau, fad, fbu, fbd, st.acc);
                 }
                 qd.end(wm1);
@@ -438,7 +440,7 @@ __device__ __forceinline__ void v_block(const uint32_t *hdr32, const char *lut, 
         }
         if constexpr (kTail > 0) {
             uint32_t fau[kTail], fad[kTail], fbu[kTail], fbd[kTail];
-            qd.step<kTail>(wm1, lut, mask2, fau, fad, fbu, fbd);
+            qd.template step<kTail>(wm1, lut, mask2, fau, fad, fbu, fbd);
             v_accum<G, kTail>(wl, wdn, wq, kRounds * NS, fau, fad, fbu, fbd, st.acc);
         }
     }
@@ -628,8 +630,10 @@ template <int G> struct WavesPerSimd { static constexpr int value = fused_wgs_pe
 // serves NS = floor(kWindowBits / LB) symbols.
 template <int G, int LB>
 __global__ __launch_bounds__(kThreads, WavesPerSimd<G>::value) void fused_attn_kernel(FusedArgs a) {
-    constexpr int NS = kWindowBits / LB;
-    __shared__ __attribute__((aligned(16))) uint16_t lut_s[2][1 << LB];
+    constexpr bool kWide = G >= kMfmaMinG;  // 32-bit table entries and two junk bits per window for the MFMA groups
+    constexpr int NS = (32 - (kWide ? 2 : 1)) / LB;
+    static_assert(NS == kWindowBits / LB, "the second junk bit costs no symbol for the table widths in use");
+    __shared__ __attribute__((aligned(16))) uint16_t lut_s[2][(1 << LB) * (kWide ? 2 : 1)];
     __shared__ __attribute__((aligned(16))) float qf[G * kD];
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];  // per wave: staging area + weights
     const int tid = threadIdx.x, lane = tid & 63;
@@ -673,11 +677,20 @@ __global__ __launch_bounds__(kThreads, WavesPerSimd<G>::value) void fused_attn_k
         eV = tabV[j];
     }
     for (int t = 0; t < 2; t++) {
-        const uint4 *src = reinterpret_cast<const uint4 *>(g.lut + t * kLutSize);
-        uint4 *dst = reinterpret_cast<uint4 *>(&lut_s[t][0]);
-        const int n16 = max(1, (2 << g.lut_bits[t]) / 16);
-        for (int i = tid; i < n16; i += kThreads) dst[i] = src[i];
+        if constexpr (kWide) {  // {symbol << 8 | length} -> {fp16(symbol) << 16 | length}
+            uint32_t *dst = reinterpret_cast<uint32_t *>(&lut_s[t][0]);
+            for (int i = tid; i < (1 << g.lut_bits[t]); i += kThreads) {
+                const uint32_t e = g.lut[t * kLutSize + i];
+                dst[i] = ((uint32_t)__half_as_ushort(__float2half_rn((float)(e >> 8))) << 16) | (e & 0xffu);
+            }
+        } else {
+            const uint4 *src = reinterpret_cast<const uint4 *>(g.lut + t * kLutSize);
+            uint4 *dst = reinterpret_cast<uint4 *>(&lut_s[t][0]);
+            const int n16 = max(1, (2 << g.lut_bits[t]) / 16);
+            for (int i = tid; i < n16; i += kThreads) dst[i] = src[i];
+        }
     }
+    const uint32_t maskK = a.mask2[0] << (kWide ? 1 : 0), maskV = a.mask2[1] << (kWide ? 1 : 0);
     for (int i = tid; i < G * kD; i += kThreads) qf[i] = h2f(a.q[((size_t)b * g.Hq + (size_t)h * G) * kD + i]);
     Prefetch pf;
 #pragma unroll
@@ -715,12 +728,12 @@ __global__ __launch_bounds__(kThreads, WavesPerSimd<G>::value) void fused_attn_k
             eVn = tabV[jn];
         }
         if (k_staged) {
-            k_block<G, NS>(stage32, lutK, a.mask2[0], wts, qreg, g.two_eb[0], a.scale, lane, g.k_minmax_bytes, score);
+            k_block<G, NS>(stage32, lutK, maskK, wts, qreg, g.two_eb[0], a.scale, lane, g.k_minmax_bytes, score);
         } else {  // larger than the staging area: decode from global memory (copies keep the hot state in registers)
             float q_tmp[G][2], s_tmp[G];
 #pragma unroll
             for (int gg = 0; gg < G; gg++) { q_tmp[gg][0] = qreg[gg][0]; q_tmp[gg][1] = qreg[gg][1]; }
-            k_block_global<G, NS>(reinterpret_cast<const uint32_t *>(recK), lutK, a.mask2[0], wts, q_tmp, g.two_eb[0], a.scale,
+            k_block_global<G, NS>(reinterpret_cast<const uint32_t *>(recK), lutK, maskK, wts, q_tmp, g.two_eb[0], a.scale,
                                   lane, g.k_minmax_bytes, s_tmp);
 #pragma unroll
             for (int gg = 0; gg < G; gg++) score[gg] = s_tmp[gg];
@@ -739,13 +752,13 @@ __global__ __launch_bounds__(kThreads, WavesPerSimd<G>::value) void fused_attn_k
         eVn.size16 = __builtin_amdgcn_readfirstlane(eVn.size16);
         if (jn < j1 && eKn.size16 <= stage16) pf.issue(g.payload + (size_t)eKn.off16 * 16, eKn.size16, lane);
         if (v_staged) {
-            v_block<G, NS>(stage32, lutV, a.mask2[1], wts, p, g.two_eb[1], lane, st);
+            v_block<G, NS>(stage32, lutV, maskV, wts, p, g.two_eb[1], lane, st);
         } else {
             Soft<G> st_tmp = st;
             float p_tmp[G];
 #pragma unroll
             for (int gg = 0; gg < G; gg++) p_tmp[gg] = p[gg];
-            v_block_global<G, NS>(reinterpret_cast<const uint32_t *>(recV), lutV, a.mask2[1], wts, p_tmp, g.two_eb[1], lane,
+            v_block_global<G, NS>(reinterpret_cast<const uint32_t *>(recV), lutV, maskV, wts, p_tmp, g.two_eb[1], lane,
                                   st_tmp);
             st = st_tmp;
         }

@@ -95,7 +95,7 @@ constexpr size_t fused_weight_bytes(int G, int table_bits) {
 // LDS of one fused-kernel workgroup apart from the per-wave staging areas: two decode tables of 16-bit entries, the
 // query rows and the per-wave weight areas.
 constexpr size_t fused_lds_fixed(int G, int longest) {
-    return ((size_t)4 << fused_attn_table_bits(longest, G)) + (size_t)G * kD * 4 +
+    return ((size_t)(G >= 4 ? 8 : 4) << fused_attn_table_bits(longest, G)) + (size_t)G * kD * 4 +
            4 * fused_weight_bytes(G, fused_attn_table_bits(longest, G)) + 512;
 }
 
