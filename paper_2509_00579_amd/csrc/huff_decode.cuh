@@ -157,13 +157,12 @@ using DownReader = DownReaderT<kJunkBits>;
 // Decode CNT symbols from a window.  lut: 16-bit entries (symbol << 8) | code length, indexed by the next `bits`
 // stream bits; mask2 = ((1 << bits) - 1) << 1.  CNT * (longest code word) <= kWindowBits is the caller's promise.
 // e[] receives the entries; returns the number of bits used.
-// (32-bit entries with the symbol as an fp16 number in the upper half, consumed by v_fma_mix_f32 without a
-// conversion, were measured too: one VALU instruction less per symbol, but the table takes twice the LDS rows and
-// the extra bank conflicts cost more than the instruction saves, except for tables of 64 entries where it is a tie.)
 // `win` is left at the first bit that was not used, so that a further call continues in the same window.
 // WIDE: the table has 32-bit entries {symbol as an fp16 number, 0, code length} and the window two junk bits, so that
 // the masked window is again the byte offset of the entry (mask2 = ((1 << bits) - 1) << 2); only the low byte takes
-// part in the sum of lengths.
+// part in the sum of lengths.  The wide table takes twice the LDS rows (more bank conflicts per gather): it pays
+// where the fp16 symbol saves more than that costs -- as the operand of the MFMA accumulation, not for the scalar
+// path, where feeding it to v_fma_mix_f32 was measured slower than the byte conversion of the narrow entry.
 template <int CNT, bool WIDE = false>
 __device__ __forceinline__ uint32_t lookup_more(uint32_t &win, const char *lut, uint32_t mask2, uint32_t (&e)[CNT]) {
     uint32_t tot = 0;
