@@ -65,3 +65,33 @@ def test_library_codebook_matches_oracle_rules_without_a_gpu():
     import paper_2509_00579_amd.binding as b
     src = pathlib.Path(b.__file__).read_text()
     assert "oracle" not in src
+
+
+def _prototypes():
+    """name -> list of parameter declarations, parsed from the header."""
+    text = re.sub(r"/\*.*?\*/", "", HEADER.read_text(), flags=re.S)
+    text = re.sub(r"//[^\n]*", "", text)
+    out = {}
+    for m in re.finditer(r"\b(kvcomp_[a-z0-9_]+)\s*\(([^)]*)\)\s*;", text):
+        params = [p.strip() for p in m.group(2).split(",")]
+        out[m.group(1)] = [] if params in ([""], ["void"]) else params
+    return out
+
+
+def _kind(decl):
+    """Class of a C parameter as the binding has to marshal it."""
+    if "*" in decl:
+        return "pointer"
+    base = re.sub(r"\b(const|unsigned|signed)\b", "", decl).split()
+    return {"int": "int", "float": "float", "size_t": "size_t"}[base[0]]
+
+
+def test_binding_argument_lists_follow_the_header():
+    from paper_2509_00579_amd import binding
+    protos = _prototypes()
+    assert sorted(protos) == _declared()
+    kinds = {ctypes.c_int: "int", ctypes.c_float: "float", ctypes.c_size_t: "size_t"}
+    for name, (_, args) in binding.SIGNATURES.items():
+        want = [_kind(p) for p in protos[name]]
+        got = [kinds.get(a, "pointer") for a in args]
+        assert got == want, (name, protos[name])
