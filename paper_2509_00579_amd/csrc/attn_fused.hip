@@ -608,15 +608,23 @@ struct Prefetch {
 
 
 // Developer instrumentation, compiled in with -DKVC_TRACE only: wave 0.. of every workgroup records the 100 MHz
-// wall clock at eight points of the kernel (the shader clock at points 1 and 5); kvcomp_trace_read() copies the records to the host.
+// wall clock at eight points of the kernel (at point 1 instead where it runs: the HW_ID register in the low half and
+// the accelerator die in the high half; at point 5 the shader clock); kvcomp_trace_read() copies the records to the host.
 #ifdef KVC_TRACE
 constexpr int kTraceSlots = 8, kTraceWaves = 1 << 15;
 __device__ unsigned long long g_trace[kTraceWaves * kTraceSlots];
+__device__ __forceinline__ unsigned long long kvc_where() {
+    const unsigned hw = __builtin_amdgcn_s_getreg(4 | (0 << 6) | (31 << 11));   // HW_REG_HW_ID, all 32 bits
+    const unsigned xcc = __builtin_amdgcn_s_getreg(20 | (0 << 6) | (3 << 11));  // HW_REG_XCC_ID, bits 3:0
+    return ((unsigned long long)xcc << 32) | hw;
+}
 #define KVC_MARK(k)                                                                                              \
     do {                                                                                                         \
         const unsigned wv = (blockIdx.x * kWaves + wave);                                                        \
         if (lane == 0 && wv < kTraceWaves)                                                                       \
-            g_trace[wv * kTraceSlots + (k)] = (k) == 1 || (k) == 5 ? clock64() : wall_clock64();                 \
+            g_trace[wv * kTraceSlots + (k)] = (k) == 1   ? kvc_where()                                           \
+                                              : (k) == 5 ? (unsigned long long)clock64()                         \
+                                                         : (unsigned long long)wall_clock64();                   \
     } while (0)
 #else
 #define KVC_MARK(k) do { } while (0)

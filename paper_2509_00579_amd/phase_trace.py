@@ -50,8 +50,9 @@ def main():
     assert rc == 0, rc
     t = np.frombuffer(buf, dtype=np.uint64).reshape(-1, 8).astype(np.int64)
     t = t[t[:, 0] > 0]
-    t[:, 1] = t[:, 0]  # points 1 and 5 hold the shader clock, not the wall clock
-    t[:, 5] = t[:, 4]
+    where = t[:, 1].copy()  # point 1: HW_ID register (low half) and accelerator die (high half)
+    t[:, 1] = t[:, 0]
+    t[:, 5] = t[:, 4]       # point 5: shader clock, not the wall clock
     rel = (t - t[:, 0].min()) * 0.01  # microseconds
     names = ["entry", "(tables, q)", "first K record staged", "first K block done", "first V block done",
              "(all blocks)", "partials written", "exit"]
@@ -62,6 +63,19 @@ def main():
         col = rel[:, k]
         print("%-22s min %6.2f  p10 %6.2f  median %6.2f  p90 %6.2f  max %6.2f us" %
               (nm, col.min(), np.percentile(col, 10), np.median(col), np.percentile(col, 90), col.max()))
+    # placement: waves per SIMD and per CU, and how the last exit of a CU depends on its load
+    hw = where & 0xFFFFFFFF
+    cu = ((where >> 32) & 15) * 1024 + ((hw >> 13) & 7) * 32 + ((hw >> 12) & 1) * 16 + ((hw >> 8) & 15)
+    simd = cu * 4 + ((hw >> 4) & 3)
+    ids, per_cu = np.unique(cu, return_counts=True)
+    _, per_simd = np.unique(simd, return_counts=True)
+    print(f"{len(ids)} CUs in use; waves per CU: " +
+          ", ".join(f"{v}: {c} CUs" for v, c in zip(*np.unique(per_cu, return_counts=True))))
+    print("waves per SIMD: " + ", ".join(f"{v}: {c}" for v, c in zip(*np.unique(per_simd, return_counts=True))))
+    last = np.array([rel[cu == i, 7].max() for i in ids])
+    for v in np.unique(per_cu):
+        sel = last[per_cu == v]
+        print(f"  CUs with {v:2d} waves: last exit median {np.median(sel):6.2f}  max {sel.max():6.2f} us")
     cache.close()
 
 
