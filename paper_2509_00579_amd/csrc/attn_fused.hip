@@ -460,6 +460,441 @@ __device__ __noinline__ void v_block_global(const uint32_t *rec, const char *lut
     v_block<G, NS>(rec, lut, mask2, wts, p, two_eb, lane, st);
 }
 
+// Developer instrumentation of the tile path (-DKVC_TRACE only): the shader clock at points inside a block; every
+// block overwrites the previous one's, so the last block pair of every wave remains.
+#ifdef KVC_TRACE
+constexpr int kTickSlots = 16, kTickWaves = 1 << 15;
+__device__ unsigned long long g_ticks[kTickWaves * kTickSlots];
+#define KVC_TICK(k)                                                                          \
+    do {                                                                                     \
+        const unsigned wv_ = blockIdx.x * 4 + (threadIdx.x >> 6);                            \
+        if ((threadIdx.x & 63) == 0 && wv_ < kTickWaves) g_ticks[wv_ * kTickSlots + (k)] = clock64(); \
+    } while (0)
+#else
+#define KVC_TICK(k) do { } while (0)
+#endif
+
+// ---- groups of 4 and 8 query heads, tile path ---------------------------------------------------------------------
+// With several query heads per KV head the update of the accumulators is a matrix product, (heads x symbols) weights
+// times the decoded block, and the decode itself is the same for all heads.  The wave therefore decodes a block into
+// an LDS tile of bytes -- packing four table entries into a word costs less than one conversion and one FMA per
+// symbol and head -- and then multiplies the whole tile with the folded weights on v_mfma_i32_32x32x16_i8:
+//   * the table holds the symbols biased by -128 (symbol ^ 0x80 read as int8), so a tile word is an MFMA operand as
+//     it is, with no conversion;
+//   * a weight w is scaled by a per-block power of two to an integer W below 2^30 and split into four signed bytes,
+//     W = sum_j d_j 256^j; row 4 * head + j of the A operand holds digit j, the products are exact in int32, and the
+//     four digit rows of a head land in the same lane of the result, where they are recombined in fp32;
+//   * sum_c W_c (s_c - 128) misses 128 * sum_c W_c, which joins the constant term of the block.
+// Lane l of the result tiles holds column l % 32 (token of a K block, channel of a V block) for the heads
+// l / 32 + 2 i: the running softmax state lives in that layout and is converted to the per-channel layout of the
+// other paths once, after the last block.
+typedef int v16i __attribute__((ext_vector_type(16)));
+
+template <int G>
+struct TileSoft {
+    static constexpr int HL = G / 2;  // heads per lane: l / 32 + 2 i
+    float m[HL], l[HL], bv[HL], acc[HL][4];  // l, bv: this lane's share; acc[i][ct]: channel 32 ct + l % 32
+    __device__ __forceinline__ void init() {
+#pragma unroll
+        for (int i = 0; i < HL; i++) {
+            m[i] = -INFINITY; l[i] = 0.f; bv[i] = 0.f;
+#pragma unroll
+            for (int c = 0; c < 4; c++) acc[i][c] = 0.f;
+        }
+    }
+};
+
+// maximum / sum over the 32 lanes of this lane's half of the wave
+__device__ __forceinline__ float half_max(float v, bool upper) {
+    v = fmaxf(v, dpp_f<kDppXor1>(v));
+    v = fmaxf(v, dpp_f<kDppXor2>(v));
+    v = fmaxf(v, dpp_f<kDppHalfMirror>(v));
+    v = fmaxf(v, dpp_f<kDppMirror>(v));
+    const float lo = fmaxf(bcast(v, 0), bcast(v, 16)), hi = fmaxf(bcast(v, 32), bcast(v, 48));
+    return upper ? hi : lo;
+}
+__device__ __forceinline__ float half_sum(float v, bool upper) {
+    v += dpp_f<kDppXor1>(v);
+    v += dpp_f<kDppXor2>(v);
+    v += dpp_f<kDppHalfMirror>(v);
+    v += dpp_f<kDppMirror>(v);
+    const float lo = bcast(v, 0) + bcast(v, 16), hi = bcast(v, 32) + bcast(v, 48);
+    return upper ? hi : lo;
+}
+
+// bytes 1 of four table entries (the biased symbols) as one word, first entry in the lowest byte
+__device__ __forceinline__ uint32_t pack_syms(uint32_t e0, uint32_t e1, uint32_t e2, uint32_t e3) {
+    const uint32_t lo = __builtin_amdgcn_perm(e1, e0, 0x0c0c0501u), hi = __builtin_amdgcn_perm(e3, e2, 0x0c0c0501u);
+    return __builtin_amdgcn_perm(hi, lo, 0x05040100u);
+}
+
+// Decodes symbols 16 HALF .. 16 HALF + 15 of this lane's four chains into the tile: the up chain of a slice fills
+// bytes 0..15 of its 32-byte row segment upwards, the down chain bytes 31..16 downwards (so the segment holds 32
+// positions of the slice in ascending order: 16 HALF .. +15 and 48 - 16 HALF .. +15); a word is stored as soon as the
+// rounds have delivered its four symbols.  16 must be a multiple of NS.
+template <int NS>
+__device__ __forceinline__ void decode_half(Quad &qd, const uint32_t *wm1, const char *lut, uint32_t mask2,
+                                            uint8_t *seg_a, uint8_t *seg_b) {
+    static_assert(16 % NS == 0, "a half is a whole number of windows");
+    uint32_t eau[16], ead[16], ebu[16], ebd[16];
+    auto store_words = [&](int w0, int w1) {
+#pragma unroll
+        for (int w = w0; w < w1; w++) {
+            *reinterpret_cast<uint32_t *>(seg_a + 4 * w) = pack_syms(eau[4 * w], eau[4 * w + 1], eau[4 * w + 2], eau[4 * w + 3]);
+            *reinterpret_cast<uint32_t *>(seg_a + 28 - 4 * w) = pack_syms(ead[4 * w + 3], ead[4 * w + 2], ead[4 * w + 1], ead[4 * w]);
+            *reinterpret_cast<uint32_t *>(seg_b + 4 * w) = pack_syms(ebu[4 * w], ebu[4 * w + 1], ebu[4 * w + 2], ebu[4 * w + 3]);
+            *reinterpret_cast<uint32_t *>(seg_b + 28 - 4 * w) = pack_syms(ebd[4 * w + 3], ebd[4 * w + 2], ebd[4 * w + 1], ebd[4 * w]);
+        }
+    };
+#pragma unroll
+    for (int r = 0; r < 16 / NS; r++) {
+        uint32_t fau[NS], fad[NS], fbu[NS], fbd[NS];
+        qd.template step<NS>(wm1, lut, mask2, fau, fad, fbu, fbd);
+#pragma unroll
+        for (int k = 0; k < NS; k++) {
+            eau[r * NS + k] = fau[k]; ead[r * NS + k] = fad[k]; ebu[r * NS + k] = fbu[k]; ebd[r * NS + k] = fbd[k];
+        }
+        store_words(r * NS / 4, (r + 1) * NS / 4);
+    }
+}
+
+// power-of-two factor that brings the largest weight of the wave into [2^21, 2^22) (1 if all are zero); *inv = 1/f
+__device__ __forceinline__ float int_scale(float amax, float *inv) {
+    const float m = wave_max(amax);
+    int e = 0;
+    if (m > 0.f) (void)frexpf(m, &e);  // m = f * 2^e, f in [0.5, 1)
+    const int up = min(22 - e, 120);
+    *inv = ldexpf(1.f, -up);
+    return m > 0.f ? ldexpf(1.f, up) : 1.f;
+}
+// |W| <= 2^22 as d2 2^16 + d1 2^8 + d0 with signed bytes d_j: bytes 0..2 of the result
+__device__ __forceinline__ uint32_t signed_digits(int W) { return ((uint32_t)W + 0x00008080u) ^ 0x00008080u; }
+// words a..d (byte j = digit j of four consecutive columns) -> o[j] = digit j of the four columns, j < 3
+__device__ __forceinline__ void transpose_digits(uint32_t a, uint32_t b, uint32_t c, uint32_t d, uint32_t (&o)[3]) {
+    const uint32_t t0 = __builtin_amdgcn_perm(b, a, 0x05010400u), t1 = __builtin_amdgcn_perm(b, a, 0x07030602u);
+    const uint32_t t2 = __builtin_amdgcn_perm(d, c, 0x05010400u), t3 = __builtin_amdgcn_perm(d, c, 0x07030602u);
+    o[0] = __builtin_amdgcn_perm(t2, t0, 0x05040100u);
+    o[1] = __builtin_amdgcn_perm(t2, t0, 0x07060302u);
+    o[2] = __builtin_amdgcn_perm(t3, t1, 0x05040100u);
+}
+__device__ __forceinline__ long lds_pair(const uint8_t *p) {
+    const uint32_t *w = reinterpret_cast<const uint32_t *>(p);
+    return (long)(((unsigned long long)w[1] << 32) | w[0]);
+}
+// the digit sums of one head, rows 4 i .. 4 i + 2 of a result tile, as one number
+template <int I>
+__device__ __forceinline__ float join_digits(const v16i &d) {
+    return fmaf(fmaf((float)d[4 * I + 2], 256.f, (float)d[4 * I + 1]), 256.f, (float)d[4 * I]);
+}
+template <int HL>
+__device__ __forceinline__ void join_all(const v16i &d, float (&out)[HL]) {
+    out[0] = join_digits<0>(d);
+    out[1] = join_digits<1>(d);
+    if constexpr (HL > 2) {
+        out[HL > 2 ? 2 : 0] = join_digits<2>(d);
+        out[HL > 2 ? 3 : 0] = join_digits<3>(d);
+    }
+}
+constexpr int kARowK = kD + 4, kARowV = kBT + 4;  // bytes per row of the A operand while it is laid out in the tile area
+static_assert(32 * kARowK <= kTileBytes && 32 * kARowV <= kTileBytes, "A operand fits the tile area");
+
+// K block.  hdr32: the record (LDS or global); tile: this wave's tile area; qf: the query rows in LDS.
+// Updates the softmax state and leaves the softmax numerators of tokens l%32 and 32 + l%32 in p.
+// record_done() is called once the record has been read for the last time, before the last products: the place to
+// request the next record, whose loads then travel while few registers are live.
+template <int G, int NS, class F>
+__device__ __forceinline__ void k_tile_block(const uint32_t *hdr32, const char *lut, uint32_t mask2, uint8_t *tile,
+                                             const float *qf, float two_eb, float scale, int lane, int kmm,
+                                             TileSoft<G> &ts, float (&p)[G / 2][2], F &&record_done) {
+    constexpr int HL = G / 2;
+    // everything derived from the lane number is recomputed per block (a few instructions) instead of being kept in
+    // registers, or spilled, across the whole decode loop
+    asm volatile("" : "+v"(lane));
+    const int x = lane & 31, hv = lane >> 5;
+    const bool upper = hv != 0;
+    const bool per_channel = kmm == kMinMaxBytesK;
+    KVC_TICK(0);
+    // the A operand: folded weights q_c * step_c as integers, heads l/32 + 2i, channels 4 (l%32) .. +3
+    float cst[HL], inv;
+    long a[8];
+    {
+        float mn[4], stp[4];
+#pragma unroll
+        for (int c = 0; c < 4; c++) {
+            const uint32_t mm = hdr32[per_channel ? 4 * x + c : 0];
+            mn[c] = h2f(mm & 0xffffu);
+            stp[c] = two_eb * (h2f(mm >> 16) - mn[c]);
+        }
+        float qa[HL][4], amax = 0.f;
+#pragma unroll
+        for (int i = 0; i < HL; i++)
+#pragma unroll
+            for (int c = 0; c < 4; c++) {
+                qa[i][c] = qf[(hv + 2 * i) * kD + 4 * x + c];
+                amax = fmaxf(amax, fabsf(qa[i][c] * stp[c]));
+            }
+        const float f = int_scale(amax, &inv);
+#pragma unroll
+        for (int i = 0; i < HL; i++) {
+            uint32_t dg[4];
+            float wsum = 0.f, qm = 0.f;
+#pragma unroll
+            for (int c = 0; c < 4; c++) {
+                const int W = (int)(qa[i][c] * stp[c] * f);
+                wsum += (float)W;
+                qm = fmaf(qa[i][c], mn[c], qm);
+                dg[c] = signed_digits(W);
+            }
+            uint32_t rows[3];
+            transpose_digits(dg[0], dg[1], dg[2], dg[3], rows);
+            const int head = hv + 2 * i;
+#pragma unroll
+            for (int j = 0; j < 3; j++) *reinterpret_cast<uint32_t *>(tile + (4 * head + j) * kARowK + 4 * x) = rows[j];
+            cst[i] = half_sum(fmaf(128.f * inv, wsum, qm), upper);
+        }
+        wave_sync();
+#pragma unroll
+        for (int ks = 0; ks < 8; ks++) {
+            a[ks] = lds_pair(tile + x * kARowK + 16 * ks + 8 * hv);
+            if ((x & 3) == 3 || x >= 4 * G) a[ks] = 0;  // rows that hold no digit
+        }
+        wave_sync();
+    }
+    KVC_TICK(1);
+    const uint32_t sb = hdr32[kmm / 4 + lane];  // bit counts of slices 2*lane and 2*lane+1
+    const uint32_t start = wave_excl_scan((sb & 0xffffu) + (sb >> 16), lane);
+    const uint32_t *wm1 = hdr32 + (kmm + 2 * kSlices) / 4 - 1;
+    Quad qd;
+    qd.open(wm1, start, sb & 0xffffu, sb >> 16);
+    uint8_t *row = tile + lane * kTileRowK;  // lane = token; 64 bytes: the two slices' segments
+    constexpr bool kBoth = tile_halves_at_once(G) == 2;  // decode both halves (into two tiles), then multiply
+    float sc[HL][2];
+    v16i d[2];
+    // tile bytes 0..15 | 16..31 | 32..47 | 48..63 of half h hold channels 16h.. | 48-16h.. | 64+16h.. | 112-16h..
+    auto products = [&](int half, const uint8_t *t0) {
+#pragma unroll
+        for (int ks = 0; ks < 4; ks++) {
+            const int kk = half == 0 ? (ks == 0 ? 0 : ks == 1 ? 3 : ks == 2 ? 4 : 7) : (ks == 0 ? 1 : ks == 1 ? 2 : ks == 2 ? 5 : 6);
+#pragma unroll
+            for (int t = 0; t < 2; t++)
+                d[t] = __builtin_amdgcn_mfma_i32_32x32x16_i8(a[kk], lds_pair(t0 + (32 * t + x) * kTileRowK + 16 * ks + 8 * hv),
+                                                             d[t], 0, 0, 0);
+        }
+    };
+    auto clear = [&] {
+#pragma unroll
+        for (int t = 0; t < 2; t++)
+#pragma unroll
+            for (int k = 0; k < 16; k++) d[t][k] = 0;
+    };
+    auto join = [&](bool first) {
+#pragma unroll
+        for (int t = 0; t < 2; t++) {
+            float v[HL];
+            join_all<HL>(d[t], v);
+#pragma unroll
+            for (int i = 0; i < HL; i++) sc[i][t] = first ? v[i] : sc[i][t] + v[i];
+        }
+    };
+    if constexpr (kBoth) {
+        decode_half<NS>(qd, wm1, lut, mask2, row, row + 32);
+        KVC_TICK(2);
+        decode_half<NS>(qd, wm1, lut, mask2, row + kTileBytes, row + kTileBytes + 32);
+        wave_sync();
+        record_done();
+        clear();
+        products(0, tile);
+        products(1, tile + kTileBytes);
+        join(true);
+        wave_sync();
+    } else {
+#pragma unroll
+        for (int half = 0; half < 2; half++) {
+            decode_half<NS>(qd, wm1, lut, mask2, row, row + 32);
+            wave_sync();
+            if (half == 0) KVC_TICK(2);
+            if (half == 1) record_done();
+            clear();
+            products(half, tile);
+            join(half == 0);
+            wave_sync();
+        }
+    }
+    KVC_TICK(3);
+#pragma unroll
+    for (int i = 0; i < HL; i++) {
+        sc[i][0] = scale * fmaf(inv, sc[i][0], cst[i]);
+        sc[i][1] = scale * fmaf(inv, sc[i][1], cst[i]);
+        const float mnew = fmaxf(ts.m[i], half_max(fmaxf(sc[i][0], sc[i][1]), upper));
+        const float alpha = __expf(ts.m[i] - mnew);
+        p[i][0] = __expf(sc[i][0] - mnew);
+        p[i][1] = __expf(sc[i][1] - mnew);
+        ts.l[i] = ts.l[i] * alpha + (p[i][0] + p[i][1]);
+        ts.bv[i] *= alpha;
+#pragma unroll
+        for (int c = 0; c < 4; c++) ts.acc[i][c] *= alpha;
+        ts.m[i] = mnew;
+    }
+    KVC_TICK(4);
+}
+
+// V block.  p: softmax numerators of tokens l%32 and 32 + l%32 for this lane's heads.
+template <int G, int NS, class F>
+__device__ __forceinline__ void v_tile_block(const uint32_t *hdr32, const char *lut, uint32_t mask2, uint8_t *tile,
+                                             const float (&p)[G / 2][2], float two_eb, int lane, TileSoft<G> &ts,
+                                             F &&record_done) {
+    constexpr int HL = G / 2;
+    asm volatile("" : "+v"(lane));
+    const int x = lane & 31, hv = lane >> 5;
+    KVC_TICK(5);
+    float inv;
+    long a[4];
+    {
+        float mn[2], stp[2];
+#pragma unroll
+        for (int t = 0; t < 2; t++) {
+            const uint32_t mm = hdr32[32 * t + x];
+            mn[t] = h2f(mm & 0xffffu);
+            stp[t] = two_eb * (h2f(mm >> 16) - mn[t]);
+        }
+        float amax = 0.f;
+#pragma unroll
+        for (int i = 0; i < HL; i++) amax = fmaxf(amax, fmaxf(p[i][0] * stp[0], p[i][1] * stp[1]));
+        const float f = int_scale(amax, &inv);
+#pragma unroll
+        for (int i = 0; i < HL; i++) {
+            const int head = hv + 2 * i;
+            float wsum = 0.f;
+#pragma unroll
+            for (int t = 0; t < 2; t++) {
+                const int W = (int)(p[i][t] * stp[t] * f);
+                wsum += (float)W;
+                const uint32_t dg = signed_digits(W);
+#pragma unroll
+                for (int j = 0; j < 3; j++) tile[(4 * head + j) * kARowV + 32 * t + x] = (uint8_t)(dg >> (8 * j));
+            }
+            ts.bv[i] += fmaf(128.f * inv, wsum, fmaf(p[i][0], mn[0], p[i][1] * mn[1]));
+        }
+        wave_sync();
+#pragma unroll
+        for (int ks = 0; ks < 4; ks++) {
+            a[ks] = lds_pair(tile + x * kARowV + 16 * ks + 8 * hv);
+            if ((x & 3) == 3 || x >= 4 * G) a[ks] = 0;
+        }
+        wave_sync();
+    }
+    KVC_TICK(6);
+    const uint32_t sb = hdr32[kMinMaxBytesV / 4 + lane];
+    const uint32_t start = wave_excl_scan((sb & 0xffffu) + (sb >> 16), lane);
+    const uint32_t *wm1 = hdr32 + kHdrBytesV / 4 - 1;
+    Quad qd;
+    qd.open(wm1, start, sb & 0xffffu, sb >> 16);
+    // lane = channels 2*lane and 2*lane+1; channel n sits in tile row (n & 1) * 64 + n / 2, 32 bytes per row
+    constexpr bool kBoth = tile_halves_at_once(G) == 2;
+    uint8_t *row_a = tile + lane * kTileRowV, *row_b = tile + (kSliceLen + lane) * kTileRowV;
+    v16i d[4];
+    // row bytes 0..15 | 16..31 of half h hold tokens 16h.. | 48-16h..
+    auto products = [&](int half, const uint8_t *t0) {
+#pragma unroll
+        for (int ks = 0; ks < 2; ks++) {
+            const int kk = half == 0 ? (ks == 0 ? 0 : 3) : (ks == 0 ? 1 : 2);
+#pragma unroll
+            for (int ct = 0; ct < 4; ct++) {
+                const int n = 32 * ct + x, r = (n & 1) * kSliceLen + (n >> 1);
+                d[ct] = __builtin_amdgcn_mfma_i32_32x32x16_i8(a[kk], lds_pair(t0 + r * kTileRowV + 16 * ks + 8 * hv), d[ct], 0,
+                                                              0, 0);
+            }
+        }
+    };
+    auto clear = [&] {
+#pragma unroll
+        for (int ct = 0; ct < 4; ct++)
+#pragma unroll
+            for (int k = 0; k < 16; k++) d[ct][k] = 0;
+    };
+    auto join = [&] {
+#pragma unroll
+        for (int ct = 0; ct < 4; ct++) {
+            float v[HL];
+            join_all<HL>(d[ct], v);
+#pragma unroll
+            for (int i = 0; i < HL; i++) ts.acc[i][ct] = fmaf(inv, v[i], ts.acc[i][ct]);
+        }
+    };
+    if constexpr (kBoth) {
+        decode_half<NS>(qd, wm1, lut, mask2, row_a, row_b);
+        KVC_TICK(7);
+        decode_half<NS>(qd, wm1, lut, mask2, row_a + kTileBytes, row_b + kTileBytes);
+        wave_sync();
+        record_done();
+        clear();
+        products(0, tile);
+        products(1, tile + kTileBytes);
+        KVC_TICK(8);
+        join();
+        wave_sync();
+    } else {
+#pragma unroll
+        for (int half = 0; half < 2; half++) {
+            decode_half<NS>(qd, wm1, lut, mask2, row_a, row_b);
+            wave_sync();
+            if (half == 0) KVC_TICK(7);
+            if (half == 1) record_done();
+            clear();
+            products(half, tile);
+            join();
+            wave_sync();
+            if (half == 0) KVC_TICK(8);
+        }
+    }
+    KVC_TICK(9);
+}
+
+// Rare path: a record larger than the LDS staging area (one that an append flushed after the host last looked at the
+// record sizes) is decoded straight from global memory, out of line.
+template <int G, int NS>
+__device__ __noinline__ void k_tile_block_global(const uint32_t *rec, const char *lut, uint32_t mask2, uint8_t *tile,
+                                                 const float *qf, float two_eb, float scale, int lane, int kmm,
+                                                 TileSoft<G> &ts, float (&p)[G / 2][2]) {
+    k_tile_block<G, NS>(rec, lut, mask2, tile, qf, two_eb, scale, lane, kmm, ts, p, [] {});
+}
+template <int G, int NS>
+__device__ __noinline__ void v_tile_block_global(const uint32_t *rec, const char *lut, uint32_t mask2, uint8_t *tile,
+                                                 const float (&p)[G / 2][2], float two_eb, int lane, TileSoft<G> &ts) {
+    v_tile_block<G, NS>(rec, lut, mask2, tile, p, two_eb, lane, ts, [] {});
+}
+
+// The tile path's state in the layout of the other paths (lane = channels 2*lane, 2*lane+1 of every head; l and bv
+// in lane 0 only): through `area`, G * 128 + 3 * G floats of LDS.
+template <int G>
+__device__ __forceinline__ void tile_state_to_soft(const TileSoft<G> &ts, float *area, int lane, Soft<G> &st) {
+    constexpr int HL = G / 2;
+    const int x = lane & 31, hv = lane >> 5;
+    wave_sync();
+#pragma unroll
+    for (int i = 0; i < HL; i++) {
+        const int head = hv + 2 * i;
+#pragma unroll
+        for (int ct = 0; ct < 4; ct++) area[head * kD + 32 * ct + x] = ts.acc[i][ct];
+        const float l = half_sum(ts.l[i], hv != 0), bv = half_sum(ts.bv[i], hv != 0);
+        if (x == 0) {
+            area[G * kD + 3 * head] = ts.m[i];
+            area[G * kD + 3 * head + 1] = l;
+            area[G * kD + 3 * head + 2] = bv;
+        }
+    }
+    wave_sync();
+#pragma unroll
+    for (int g = 0; g < G; g++) {
+        st.acc[g][0] = area[g * kD + 2 * lane];
+        st.acc[g][1] = area[g * kD + 2 * lane + 1];
+        st.m[g] = area[G * kD + 3 * g];
+        st.l[g] = lane == 0 ? area[G * kD + 3 * g + 1] : 0.f;
+        st.bv[g] = lane == 0 ? area[G * kD + 3 * g + 2] : 0.f;
+    }
+    wave_sync();
+}
+
 constexpr int kWaves = 4;
 constexpr int kThreads = 64 * kWaves;
 
@@ -606,6 +1041,27 @@ struct Prefetch {
     }
 };
 
+// The tile path's variant: the record goes from global memory straight into the staging area with LDS-direct loads
+// (lane l of load i delivers its 16 bytes to byte 1024 i + 16 l; lanes beyond the record are masked out), issued when
+// the previous record has been decoded -- no register holds it on the way.  The rest of a record above 8 KiB is copied
+// at wait time.
+struct DirectStage {
+    const uint4 *src;
+    uint32_t n16;
+    __device__ __forceinline__ void issue(const uint8_t *rec, uint32_t size16, uint8_t *stage, int lane) {
+        src = reinterpret_cast<const uint4 *>(rec);
+        n16 = size16;
+#pragma unroll
+        for (int i = 0; i < kPrefetchRegs; i++)
+            if (lane + 64 * i < size16)
+                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(src + lane + 64 * i),
+                                                 (__attribute__((address_space(3))) void *)(stage + 1024 * i), 16, 0, 0);
+    }
+    __device__ __forceinline__ void wait(uint4 *stage4, int lane) const {
+        __builtin_amdgcn_s_waitcnt(0);  // vmcnt(0): the loads have written the LDS
+        if (n16 > 64u * kPrefetchRegs) copy_rest(stage4, src, n16, lane);
+    }
+};
 
 // Developer instrumentation, compiled in with -DKVC_TRACE only: wave 0.. of every workgroup records the 100 MHz
 // wall clock at eight points of the kernel (at point 1 instead where it runs: the HW_ID register in the low half and
@@ -638,7 +1094,8 @@ template <int G> struct WavesPerSimd { static constexpr int value = fused_wgs_pe
 // serves NS = floor(kWindowBits / LB) symbols.
 template <int G, int LB>
 __global__ __launch_bounds__(kThreads, WavesPerSimd<G>::value) void fused_attn_kernel(FusedArgs a) {
-    constexpr bool kWide = G >= kMfmaMinG;  // 32-bit table entries and two junk bits per window for the MFMA groups
+    constexpr bool kTile = kGqaTile && G >= kMfmaMinG;  // decode into an LDS tile, int8 MFMA over the tile
+    constexpr bool kWide = G >= kMfmaMinG && !kTile;   // 32-bit table entries and two junk bits per window (4x4x4 path)
     constexpr int NS = (32 - (kWide ? 2 : 1)) / LB;
     static_assert(NS == kWindowBits / LB, "the second junk bit costs no symbol for the table widths in use");
     __shared__ __attribute__((aligned(16))) uint16_t lut_s[2][(1 << LB) * (kWide ? 2 : 1)];
@@ -649,9 +1106,10 @@ __global__ __launch_bounds__(kThreads, WavesPerSimd<G>::value) void fused_attn_k
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     uint8_t *stage = smem + (size_t)wave * a.stage_bytes;
     constexpr int kWeightBytes = (int)fused_weight_bytes(G, LB);
-    static_assert(G < kMfmaMinG || kWeightBytes == 4 * MfmaRounds<NS>::kCount * G * 16, "weight area layout");
+    static_assert(G < kMfmaMinG || kTile || kWeightBytes == 4 * MfmaRounds<NS>::kCount * G * 16, "weight area layout");
+    static_assert(!kTile || kWeightBytes == kTileBytes * tile_halves_at_once(G), "tile area");
     float *wts = reinterpret_cast<float *>(smem + (size_t)kWaves * a.stage_bytes + (size_t)wave * kWeightBytes);
-    if constexpr (G >= kMfmaMinG) {  // entries of symbols that do not exist stay zero for the whole kernel
+    if constexpr (kWide) {  // entries of symbols that do not exist stay zero for the whole kernel
         for (int i = lane; i < kWeightBytes / 16; i += 64) reinterpret_cast<uint4 *>(wts)[i] = make_uint4(0, 0, 0, 0);
     }
     const char *lutK = reinterpret_cast<const char *>(&lut_s[0][0]);
@@ -695,7 +1153,13 @@ __global__ __launch_bounds__(kThreads, WavesPerSimd<G>::value) void fused_attn_k
             const uint4 *src = reinterpret_cast<const uint4 *>(g.lut + t * kLutSize);
             uint4 *dst = reinterpret_cast<uint4 *>(&lut_s[t][0]);
             const int n16 = max(1, (2 << g.lut_bits[t]) / 16);
-            for (int i = tid; i < n16; i += kThreads) dst[i] = src[i];
+            for (int i = tid; i < n16; i += kThreads) {
+                uint4 v = src[i];
+                if constexpr (kTile) {  // the tile holds symbol - 128 as int8
+                    v.x ^= 0x80008000u; v.y ^= 0x80008000u; v.z ^= 0x80008000u; v.w ^= 0x80008000u;
+                }
+                dst[i] = v;
+            }
         }
     }
     const uint32_t maskK = a.mask2[0] << (kWide ? 1 : 0), maskV = a.mask2[1] << (kWide ? 1 : 0);
@@ -705,18 +1169,34 @@ __global__ __launch_bounds__(kThreads, WavesPerSimd<G>::value) void fused_attn_k
     for (int i = 0; i < kPrefetchRegs; i++) pf.r[i] = make_uint4(0, 0, 0, 0);
     pf.src = nullptr;
     pf.n16 = 0;
-    if (j < j1 && eK.size16 <= stage16) pf.issue(g.payload + (size_t)eK.off16 * 16, eK.size16, lane);
+    DirectStage ds;
+    ds.src = nullptr;
+    ds.n16 = 0;
+    if (j < j1 && eK.size16 <= stage16) {
+        if constexpr (kTile) ds.issue(g.payload + (size_t)eK.off16 * 16, eK.size16, stage, lane);
+        else pf.issue(g.payload + (size_t)eK.off16 * 16, eK.size16, lane);
+    }
     __syncthreads();
     KVC_MARK(1);
-    float qreg[G][2];
+    // q in registers: channels lane and lane + 64 (the tile path reads its q from LDS once per block)
+    constexpr int kQ0 = kTile ? G / 2 : G;
+    float qreg[kTile ? 1 : G][2];
+    if constexpr (!kTile) {
 #pragma unroll
-    for (int gg = 0; gg < G; gg++) { qreg[gg][0] = qf[gg * kD + lane]; qreg[gg][1] = qf[gg * kD + lane + 64]; }
+        for (int gg = 0; gg < G; gg++) { qreg[gg][0] = qf[gg * kD + lane]; qreg[gg][1] = qf[gg * kD + lane + 64]; }
+    }
 
     Soft<G> st;
     st.init();
+    TileSoft<kTile ? G : 2> ts;
+    ts.init();
+    uint8_t *tile = reinterpret_cast<uint8_t *>(wts);
 
     if (j < j1) {
-        if (eK.size16 <= stage16) pf.commit(stage4, lane);
+        if (eK.size16 <= stage16) {
+            if constexpr (kTile) ds.wait(stage4, lane);
+            else pf.commit(stage4, lane);
+        }
         wave_sync();
     }
     KVC_MARK(2);
@@ -728,13 +1208,31 @@ __global__ __launch_bounds__(kThreads, WavesPerSimd<G>::value) void fused_attn_k
         float score[G], p[G];
         const bool k_staged = eK.size16 <= stage16, v_staged = eV.size16 <= stage16;
         const uint8_t *recK = g.payload + (size_t)eK.off16 * 16, *recV = g.payload + (size_t)eV.off16 * 16;
-        if (v_staged) pf.issue(recV, eV.size16, lane);  // V record travels while K is decoded
+        if (!kTile && v_staged) pf.issue(recV, eV.size16, lane);  // V record travels while K is decoded
         const int jn = j + kWaves;  // the next pair's Block Offsets Array entries travel with it
         BlockEntry eKn = {0, 0}, eVn = {0, 0};
         if (jn < j1) {
             eKn = tabK[jn];
             eVn = tabV[jn];
         }
+        float pt[kQ0][2];  // tile path: softmax numerators in the layout of the result tiles
+        if constexpr (kTile) {
+            // The next record is requested when the current one has been decoded: its registers are then live across
+            // the products and the softmax only, not across a decode.
+            if (k_staged) {
+                k_tile_block<G, NS>(stage32, lutK, maskK, tile, qf, g.two_eb[0], a.scale, lane, g.k_minmax_bytes, ts, pt,
+                                    [&] { if (v_staged) ds.issue(recV, eV.size16, stage, lane); });
+            } else {
+                TileSoft<G> ts_tmp = ts;
+                float p_tmp[kQ0][2];
+                k_tile_block_global<G, NS>(reinterpret_cast<const uint32_t *>(recK), lutK, maskK, tile, qf, g.two_eb[0],
+                                           a.scale, lane, g.k_minmax_bytes, ts_tmp, p_tmp);
+                ts = ts_tmp;
+#pragma unroll
+                for (int i = 0; i < kQ0; i++) { pt[i][0] = p_tmp[i][0]; pt[i][1] = p_tmp[i][1]; }
+                if (v_staged) ds.issue(recV, eV.size16, stage, lane);
+            }
+        } else {
         if (k_staged) {
             k_block<G, NS>(stage32, lutK, maskK, wts, qreg, g.two_eb[0], a.scale, lane, g.k_minmax_bytes, score);
         } else {  // larger than the staging area: decode from global memory (copies keep the hot state in registers)
@@ -746,19 +1244,41 @@ __global__ __launch_bounds__(kThreads, WavesPerSimd<G>::value) void fused_attn_k
 #pragma unroll
             for (int gg = 0; gg < G; gg++) score[gg] = s_tmp[gg];
         }
+        }
 #ifdef KVC_TRACE
         if (first) KVC_MARK(3);
 #endif
+        if constexpr (!kTile) {
 #pragma unroll
-        for (int gg = 0; gg < G; gg++) p[gg] = st.update(gg, score[gg]);
+            for (int gg = 0; gg < G; gg++) p[gg] = st.update(gg, score[gg]);
+        }
         wave_sync();  // every lane is done with the K record
-        if (v_staged) pf.commit(stage4, lane);
+        if (v_staged) {
+            if constexpr (kTile) ds.wait(stage4, lane);
+            else pf.commit(stage4, lane);
+        }
         wave_sync();
         eKn.off16 = __builtin_amdgcn_readfirstlane(eKn.off16);
         eKn.size16 = __builtin_amdgcn_readfirstlane(eKn.size16);
         eVn.off16 = __builtin_amdgcn_readfirstlane(eVn.off16);
         eVn.size16 = __builtin_amdgcn_readfirstlane(eVn.size16);
-        if (jn < j1 && eKn.size16 <= stage16) pf.issue(g.payload + (size_t)eKn.off16 * 16, eKn.size16, lane);
+        const bool next_staged = jn < j1 && eKn.size16 <= stage16;
+        if (!kTile && next_staged) pf.issue(g.payload + (size_t)eKn.off16 * 16, eKn.size16, lane);
+        if constexpr (kTile) {
+            if (v_staged) {
+                v_tile_block<G, NS>(stage32, lutV, maskV, tile, pt, g.two_eb[1], lane, ts,
+                                    [&] { if (next_staged) ds.issue(g.payload + (size_t)eKn.off16 * 16, eKn.size16, stage, lane); });
+            } else {
+                TileSoft<G> ts_tmp = ts;
+                float p_tmp[kQ0][2];
+#pragma unroll
+                for (int i = 0; i < kQ0; i++) { p_tmp[i][0] = pt[i][0]; p_tmp[i][1] = pt[i][1]; }
+                v_tile_block_global<G, NS>(reinterpret_cast<const uint32_t *>(recV), lutV, maskV, tile, p_tmp, g.two_eb[1],
+                                           lane, ts_tmp);
+                ts = ts_tmp;
+                if (next_staged) ds.issue(g.payload + (size_t)eKn.off16 * 16, eKn.size16, stage, lane);
+            }
+        } else {
         if (v_staged) {
             v_block<G, NS>(stage32, lutV, maskV, wts, p, g.two_eb[1], lane, st);
         } else {
@@ -770,12 +1290,16 @@ __global__ __launch_bounds__(kThreads, WavesPerSimd<G>::value) void fused_attn_k
                                   st_tmp);
             st = st_tmp;
         }
+        }
 #ifdef KVC_TRACE
         if (first) KVC_MARK(4);
         first = false;
 #endif
         wave_sync();
-        if (jn < j1 && eKn.size16 <= stage16) pf.commit(stage4, lane);
+        if (jn < j1 && eKn.size16 <= stage16) {
+            if constexpr (kTile) ds.wait(stage4, lane);
+            else pf.commit(stage4, lane);
+        }
         wave_sync();
         eK = eKn;
         eV = eVn;
@@ -793,6 +1317,7 @@ __global__ __launch_bounds__(kThreads, WavesPerSimd<G>::value) void fused_attn_k
     }
 
     KVC_MARK(5);
+    if constexpr (kTile) tile_state_to_soft<G>(ts, reinterpret_cast<float *>(tile), lane, st);
     // the buffered fp16 tokens in units of 16: unit u goes to split n_splits-1 - u % n_splits (the last split is the
     // short one), there to the waves in turn, starting after the wave that took the split's last block
     if (a.n_res > 0) {
@@ -875,8 +1400,12 @@ static hipError_t launch_fused_g(const FusedArgs &a, int longest, size_t lds, hi
             if constexpr (G < kMfmaMinG) return launch_fused_gn<G, 6>(a, lds, ev0, ev1, s);
             return hipErrorInvalidValue;
         case 7: return launch_fused_gn<G, 7>(a, lds, ev0, ev1, s);
-        case 8: return launch_fused_gn<G, 8>(a, lds, ev0, ev1, s);
-        case 10: return launch_fused_gn<G, 10>(a, lds, ev0, ev1, s);
+        case 8:
+            if constexpr (!(kGqaTile && G >= kMfmaMinG)) return launch_fused_gn<G, 8>(a, lds, ev0, ev1, s);
+            return hipErrorInvalidValue;
+        case 10:
+            if constexpr (!(kGqaTile && G >= kMfmaMinG)) return launch_fused_gn<G, 10>(a, lds, ev0, ev1, s);
+            return hipErrorInvalidValue;
         default: return launch_fused_gn<G, 12>(a, lds, ev0, ev1, s);
     }
 }
@@ -917,6 +1446,10 @@ hipError_t launch_fused_attn(const Geo &g, const uint16_t *q, float scale, float
 extern "C" int kvcomp_trace_read(unsigned long long *host, size_t n) {
     if (n > (size_t)kTraceWaves * kTraceSlots) n = (size_t)kTraceWaves * kTraceSlots;
     return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(g_trace), n * sizeof(unsigned long long));
+}
+extern "C" int kvcomp_ticks_read(unsigned long long *host, size_t n) {
+    if (n > (size_t)kTickWaves * kTickSlots) n = (size_t)kTickWaves * kTickSlots;
+    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(g_ticks), n * sizeof(unsigned long long));
 }
 #endif
 

@@ -76,6 +76,19 @@ def main():
     for v in np.unique(per_cu):
         sel = last[per_cu == v]
         print(f"  CUs with {v:2d} waves: last exit median {np.median(sel):6.2f}  max {sel.max():6.2f} us")
+    if hasattr(lib, "kvcomp_ticks_read") and w.n_q_heads // w.n_kv_heads >= 4:
+        # tile path: shader-clock cycles between points inside the last block pair of every wave
+        m = (1 << 15) * 16
+        tb = (C.c_ulonglong * m)()
+        lib.kvcomp_ticks_read.argtypes = [C.c_void_p, C.c_size_t]
+        assert lib.kvcomp_ticks_read(tb, m) == 0
+        tk = np.frombuffer(tb, dtype=np.uint64).reshape(-1, 16).astype(np.int64)
+        tk = tk[tk[:, 0] > 0]
+        steps = ["K weights", "K decode 1", "K rest", "K softmax", "(between)", "V weights", "V decode 1", "V mfma 1", "V rest"]
+        for k, nm in enumerate(steps):
+            dcol = tk[:, k + 1] - tk[:, k]
+            print("%-12s median %7.0f  p90 %7.0f cycles" % (nm, np.median(dcol), np.percentile(dcol, 90)))
+        print("block pair   median %7.0f cycles" % np.median(tk[:, 9] - tk[:, 0]))
     cache.close()
 
 
