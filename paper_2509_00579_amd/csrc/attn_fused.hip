@@ -9,10 +9,10 @@
 // What differs from the paper's kernel, and why (gfx950):
 //  * lookup-table decode instead of the bit-serial tree walk of Section 3.3.1: all 64 lanes of a wave advance in
 //    symbol lock-step (same trip count for every lane, no divergence), so the dequantization weight of the current
-//    symbol is the same for the whole wave.  It reaches the FMA through a DPP quad broadcast of values fetched from
-//    LDS once per four steps (groups of 1 and 2 query heads) or as the A operand of a 4x4x4 fp16 MFMA over the
-//    symbols of a window (groups of 4 and 8), which keeps it off the VALU and nearly off the LDS pipe that the table
-//    lookups load.  The table is
+//    symbol is the same for the whole wave.  For groups of 1 and 2 query heads it reaches the FMA through a DPP quad
+//    broadcast of values fetched from LDS once per four steps, which keeps it off the VALU and nearly off the LDS pipe
+//    that the table lookups load; for groups of 4 and 8 the wave decodes into an LDS tile of bytes and multiplies the
+//    tile with the weights of all heads on int8 MFMA (see "tile path" below).  The table is
 //    indexed by as many stream bits as the longest code word of the codebook, and one 32-bit window serves several
 //    symbols (floor(31 / table width)) with no refill test in between;
 //  * the dequantization is folded into the weights: q.k' = sum_c q_c min_c + sum_c (q_c step_c) code_tc, and
@@ -70,21 +70,8 @@ struct Soft {
 //
 // Query-head groups of 1 and 2: every fourth step, lane i of each quad of lanes fetches the weight of step s + i from
 // LDS (four addresses, no bank conflict); the FMA of step s + i then takes it through a quad broadcast.  No
-// instruction is spent on the broadcast itself.
-//
-// Groups of 4 and 8 (GQA): the update of one chain over the symbols of a round is a small matrix product,
-// (heads x symbols of the round) weights times (symbols of the round x lanes) decoded symbols, which is what
-// v_mfma_f32_4x4x4f16 computes for each quad of lanes: lane i of a quad supplies the weights of head i for the (up to
-// four) symbols of the round, and its own decoded symbols (fp16 holds 0..255 exactly), and receives the four heads'
-// sums for its own token / channel.  The weights are fp32 numbers split into two fp16 parts, w ~ hi + lo (22 bits
-// after a per-block power-of-two scaling that keeps them inside the fp16 range), one MFMA each: two MFMAs per
-// chain, round and four heads instead of one FMA per symbol and head.
-typedef float v4f __attribute__((ext_vector_type(4)));
-typedef _Float16 v4h __attribute__((ext_vector_type(4)));
-#ifndef KVC_MFMA_MIN_G
-#define KVC_MFMA_MIN_G 4
-#endif
-constexpr int kMfmaMinG = KVC_MFMA_MIN_G;  // smallest query-head group that accumulates with MFMA
+// instruction is spent on the broadcast itself.  (Groups of 4 and 8: the tile path further down.)
+constexpr int kTileMinG = 4;  // smallest query-head group on the tile path
 
 // acc + (w of lane Q of this lane's quad) * symbol: the quad broadcast is a DPP modifier of the FMA's first operand,
 // no instruction of its own.  w must not have been written by a VALU instruction in the two instructions before
@@ -163,47 +150,6 @@ __device__ __forceinline__ void v_accum(const float *wl, const float *wdn, float
     }
 }
 
-// ---- MFMA groups: the LDS weight area ---------------------------------------------------------------------------------
-// One 16-byte entry per (chain array, round, head): {hi[4], lo[4]} fp16, slot k = the chain's k-th symbol of that
-// round.  Chain arrays: K has four (channels 0..31 upwards, 63..32 downwards, 64..95 upwards, 127..96 downwards), V
-// two (tokens 0..31 upwards, 63..32 downwards).  Slots that no symbol uses (a last round with fewer symbols, rounds of
-// fewer than four) are zeroed once per wave at kernel start and never written.
-template <int NS>
-struct MfmaRounds {
-    static constexpr int kCount = (kSliceLen / 2 + NS - 1) / NS;  // rounds per chain, the last one may be short
-};
-
-// Power-of-two factor that brings the largest weight of the wave into [2^14, 2^15) (1 if all are zero); *inv = 1/f.
-__device__ __forceinline__ float fp16_scale(float amax, float *inv) {
-    const float m = wave_max(amax);
-    int e = 0;
-    if (m > 0.f) (void)frexpf(m, &e);  // m = f * 2^e, f in [0.5, 1)
-    *inv = ldexpf(1.f, e - 15);
-    return m > 0.f ? ldexpf(1.f, 15 - e) : 1.f;
-}
-// w * f as hi + lo
-__device__ __forceinline__ void split_fp16(float w, _Float16 *hi, _Float16 *lo) {
-    const _Float16 h = (_Float16)w;
-    *hi = h;
-    *lo = (_Float16)(w - (float)h);
-}
-// the chain's CNT decoded symbols of one round as the B operand (unused slots zero)
-// (the wide table holds the symbol as an fp16 number in the upper half of its entries: two entries give a packed
-// pair with one byte permute, no conversion)
-template <int CNT>
-__device__ __forceinline__ v4h symbols_fp16(const uint32_t (&e)[CNT]) {
-    const uint32_t e0 = e[0], e1 = CNT > 1 ? e[CNT > 1 ? 1 : 0] : 0u, e2 = CNT > 2 ? e[CNT > 2 ? 2 : 0] : 0u,
-                   e3 = CNT > 3 ? e[CNT > 3 ? 3 : 0] : 0u;
-    const uint2 v = make_uint2(__builtin_amdgcn_perm(e1, e0, 0x07060302u), __builtin_amdgcn_perm(e3, e2, 0x07060302u));
-    return __builtin_bit_cast(v4h, v);
-}
-// macc += (hi + lo) . b for the heads 4 q + (lane & 3); entry = this lane's 16 bytes
-__device__ __forceinline__ v4f mfma_split(const uint4 entry, v4h b, v4f acc) {
-    const uint2 h2 = make_uint2(entry.x, entry.y), l2 = make_uint2(entry.z, entry.w);
-    acc = __builtin_amdgcn_mfma_f32_4x4x4f16(__builtin_bit_cast(v4h, h2), b, acc, 0, 0, 0);
-    return __builtin_amdgcn_mfma_f32_4x4x4f16(__builtin_bit_cast(v4h, l2), b, acc, 0, 0, 0);
-}
-
 // ---- K block: lane = token; its two slices are channels 0..63 and 64..127 ------------------------------------------
 // hdr32: the record (LDS or global); wts: this wave's LDS weight area.  Leaves scale * q.k' of this lane's token in
 // score[].
@@ -229,67 +175,9 @@ __device__ __forceinline__ void k_block(const uint32_t *hdr32, const char *lut, 
     const uint32_t *wm1 = hdr32 + (kmm + 2 * kSlices) / 4 - 1;
     constexpr int kRounds = kHalf / NS, kTail = kHalf - kRounds * NS;
     constexpr int kP1 = NS > 4 ? 3 : NS, kP2 = NS - kP1;  // pieces of a window (kP2 = 0: taken whole)
-    static_assert(kTail <= 4 && (G < kMfmaMinG || kP2 == 0), "pieces");
-    QuadT<(G >= kMfmaMinG ? 2 : 1)> qd;
-    if constexpr (G >= kMfmaMinG) {
-        constexpr int R = MfmaRounds<NS>::kCount, Q4 = G / 4;
-        float amax = 0.f;
-#pragma unroll
-        for (int g = 0; g < G; g++) amax = fmaxf(amax, fmaxf(fabsf(w0[g]), fabsf(w1[g])));
-        float inv;
-        const float f = fp16_scale(amax, &inv);
-        // channel `lane` (and 64 + lane) is symbol idx of the up chain (lane < 32) or of the down chain
-        const int idx = lane < kHalf ? lane : kSliceLen - 1 - lane, arr = lane < kHalf ? 0 : 1;
-        const int round = idx / NS, slot = idx - round * NS;
-        _Float16 *w16 = reinterpret_cast<_Float16 *>(wts);
-#pragma unroll
-        for (int g = 0; g < G; g++) {
-            _Float16 hi, lo;
-            split_fp16(w0[g] * f, &hi, &lo);
-            w16[((arr * R + round) * G + g) * 8 + slot] = hi;
-            w16[((arr * R + round) * G + g) * 8 + 4 + slot] = lo;
-            split_fp16(w1[g] * f, &hi, &lo);
-            w16[(((arr + 2) * R + round) * G + g) * 8 + slot] = hi;
-            w16[(((arr + 2) * R + round) * G + g) * 8 + 4 + slot] = lo;
-        }
-        v4f macc[4][Q4];
-#pragma unroll
-        for (int c = 0; c < 4; c++)
-#pragma unroll
-            for (int q = 0; q < Q4; q++) macc[c][q] = (v4f){0.f, 0.f, 0.f, 0.f};
-        const uint4 *wrow = reinterpret_cast<const uint4 *>(wts) + (lane & 3);  // entry of head (lane & 3) + 4 q
-        wave_sync();
-        qd.open(wm1, start, sb & 0xffffu, sb >> 16);
-        auto accumulate = [&](int r, v4h bau, v4h bad, v4h bbu, v4h bbd) {
-#pragma unroll
-            for (int q = 0; q < Q4; q++) {
-                macc[0][q] = mfma_split(wrow[(0 * R + r) * G + 4 * q], bau, macc[0][q]);
-                macc[1][q] = mfma_split(wrow[(1 * R + r) * G + 4 * q], bad, macc[1][q]);
-                macc[2][q] = mfma_split(wrow[(2 * R + r) * G + 4 * q], bbu, macc[2][q]);
-                macc[3][q] = mfma_split(wrow[(3 * R + r) * G + 4 * q], bbd, macc[3][q]);
-            }
-        };
-#pragma unroll
-        for (int r = 0; r < kRounds; r++) {
-            uint32_t fau[NS], fad[NS], fbu[NS], fbd[NS];
-            qd.template step<NS>(wm1, lut, mask2, fau, fad, fbu, fbd);
-            accumulate(r, symbols_fp16<NS>(fau), symbols_fp16<NS>(fad), symbols_fp16<NS>(fbu), symbols_fp16<NS>(fbd));
-        }
-        if constexpr (kTail > 0) {
-            uint32_t fau[kTail], fad[kTail], fbu[kTail], fbd[kTail];
-            qd.template step<kTail>(wm1, lut, mask2, fau, fad, fbu, fbd);
-            accumulate(kRounds, symbols_fp16<kTail>(fau), symbols_fp16<kTail>(fad), symbols_fp16<kTail>(fbu),
-                       symbols_fp16<kTail>(fbd));
-        }
-#pragma unroll
-        for (int q = 0; q < Q4; q++) {
-            const v4f t = (macc[0][q] + macc[1][q]) + (macc[2][q] + macc[3][q]);
-            acc[4 * q + 0] = t.x * inv;
-            acc[4 * q + 1] = t.y * inv;
-            acc[4 * q + 2] = t.z * inv;
-            acc[4 * q + 3] = t.w * inv;
-        }
-    } else {
+    static_assert(kTail <= 4 && G < kTileMinG, "pieces; groups of 4 and 8 take the tile path");
+    Quad qd;
+    {
 #pragma unroll
         for (int g = 0; g < G; g++) {  // LDS layout [channel][head]
             wts[lane * G + g] = w0[g];
@@ -305,18 +193,18 @@ __device__ __forceinline__ void k_block(const uint32_t *hdr32, const char *lut, 
         for (int r = 0; r < kRounds; r++) {
             if constexpr (kP2 == 0) {
                 uint32_t fau[NS], fad[NS], fbu[NS], fbd[NS];
-                qd.template step<NS>(wm1, lut, mask2, fau, fad, fbu, fbd);
+                qd.step<NS>(wm1, lut, mask2, fau, fad, fbu, fbd);
                 k_accum<G, NS>(wl, wdn, wq, r * NS, fau, fad, fbu, fbd, acc);
             } else {  // a window of more than four symbols is taken in two pieces: fewer table entries in flight
                 qd.begin(wm1);
                 {
                     uint32_t fau[kP1], fad[kP1], fbu[kP1], fbd[kP1];
-                    qd.template part<kP1>(lut, mask2, fau, fad, fbu, fbd);
+                    qd.part<kP1>(lut, mask2, fau, fad, fbu, fbd);
                     k_accum<G, kP1>(wl, wdn, wq, r * NS, fau, fad, fbu, fbd, acc);
                 }
                 {
                     uint32_t fau[kP2 ? kP2 : 1], fad[kP2 ? kP2 : 1], fbu[kP2 ? kP2 : 1], fbd[kP2 ? kP2 : 1];
-                    qd.template part<(kP2 ? kP2 : 1)>(lut, mask2, fau, fad, fbu, fbd);
+                    qd.part<(kP2 ? kP2 : 1)>(lut, mask2, fau, fad, fbu, fbd);
                     k_accum<G, (kP2 ? kP2 : 1)>(wl, wdn, wq, r * NS + kP1, fau, fad, fbu, fbd, acc);
                 }
                 qd.end(wm1);
@@ -324,7 +212,7 @@ __device__ __forceinline__ void k_block(const uint32_t *hdr32, const char *lut, 
         }
         if constexpr (kTail > 0) {
             uint32_t fau[kTail], fad[kTail], fbu[kTail], fbd[kTail];
-            qd.template step<kTail>(wm1, lut, mask2, fau, fad, fbu, fbd);
+            qd.step<kTail>(wm1, lut, mask2, fau, fad, fbu, fbd);
             k_accum<G, kTail>(wl, wdn, wq, kRounds * NS, fau, fad, fbu, fbd, acc);
         }
     }
@@ -353,64 +241,9 @@ __device__ __forceinline__ void v_block(const uint32_t *hdr32, const char *lut, 
     const uint32_t *wm1 = hdr32 + kHdrBytesV / 4 - 1;
     constexpr int kRounds = kHalf / NS, kTail = kHalf - kRounds * NS;
     constexpr int kP1 = NS > 4 ? 3 : NS, kP2 = NS - kP1;  // pieces of a window (kP2 = 0: taken whole)
-    static_assert(kTail <= 4 && (G < kMfmaMinG || kP2 == 0), "pieces");
-    QuadT<(G >= kMfmaMinG ? 2 : 1)> qd;
-    if constexpr (G >= kMfmaMinG) {
-        constexpr int R = MfmaRounds<NS>::kCount, Q4 = G / 4;
-        float amax = 0.f;
-#pragma unroll
-        for (int g = 0; g < G; g++) amax = fmaxf(amax, fabsf(w[g]));
-        float inv;
-        const float f = fp16_scale(amax, &inv);
-        const int idx = lane < kHalf ? lane : kSliceLen - 1 - lane, arr = lane < kHalf ? 0 : 1;
-        const int round = idx / NS, slot = idx - round * NS;
-        _Float16 *w16 = reinterpret_cast<_Float16 *>(wts);
-#pragma unroll
-        for (int g = 0; g < G; g++) {
-            _Float16 hi, lo;
-            split_fp16(w[g] * f, &hi, &lo);
-            w16[((arr * R + round) * G + g) * 8 + slot] = hi;
-            w16[((arr * R + round) * G + g) * 8 + 4 + slot] = lo;
-        }
-        v4f macc[4][Q4];
-#pragma unroll
-        for (int c = 0; c < 4; c++)
-#pragma unroll
-            for (int q = 0; q < Q4; q++) macc[c][q] = (v4f){0.f, 0.f, 0.f, 0.f};
-        const uint4 *wrow = reinterpret_cast<const uint4 *>(wts) + (lane & 3);
-        wave_sync();
-        qd.open(wm1, start, sb & 0xffffu, sb >> 16);
-        auto accumulate = [&](int r, v4h bau, v4h bad, v4h bbu, v4h bbd) {
-#pragma unroll
-            for (int q = 0; q < Q4; q++) {
-                const uint4 eu = wrow[(0 * R + r) * G + 4 * q], ed = wrow[(1 * R + r) * G + 4 * q];
-                macc[0][q] = mfma_split(eu, bau, macc[0][q]);
-                macc[1][q] = mfma_split(ed, bad, macc[1][q]);
-                macc[2][q] = mfma_split(eu, bbu, macc[2][q]);
-                macc[3][q] = mfma_split(ed, bbd, macc[3][q]);
-            }
-        };
-#pragma unroll
-        for (int r = 0; r < kRounds; r++) {
-            uint32_t fau[NS], fad[NS], fbu[NS], fbd[NS];
-            qd.template step<NS>(wm1, lut, mask2, fau, fad, fbu, fbd);
-            accumulate(r, symbols_fp16<NS>(fau), symbols_fp16<NS>(fad), symbols_fp16<NS>(fbu), symbols_fp16<NS>(fbd));
-        }
-        if constexpr (kTail > 0) {
-            uint32_t fau[kTail], fad[kTail], fbu[kTail], fbd[kTail];
-            qd.template step<kTail>(wm1, lut, mask2, fau, fad, fbu, fbd);
-            accumulate(kRounds, symbols_fp16<kTail>(fau), symbols_fp16<kTail>(fad), symbols_fp16<kTail>(fbu),
-                       symbols_fp16<kTail>(fbd));
-        }
-#pragma unroll
-        for (int q = 0; q < Q4; q++) {
-            const v4f a = macc[0][q] + macc[1][q], bsum = macc[2][q] + macc[3][q];
-            st.acc[4 * q + 0][0] += a.x * inv; st.acc[4 * q + 1][0] += a.y * inv;
-            st.acc[4 * q + 2][0] += a.z * inv; st.acc[4 * q + 3][0] += a.w * inv;
-            st.acc[4 * q + 0][1] += bsum.x * inv; st.acc[4 * q + 1][1] += bsum.y * inv;
-            st.acc[4 * q + 2][1] += bsum.z * inv; st.acc[4 * q + 3][1] += bsum.w * inv;
-        }
-    } else {
+    static_assert(kTail <= 4 && G < kTileMinG, "pieces; groups of 4 and 8 take the tile path");
+    Quad qd;
+    {
 #pragma unroll
         for (int g = 0; g < G; g++) wts[lane * G + g] = w[g];  // LDS layout [token][head]
         const float *wl = wts + (lane & 3) * G, *wdn = wts - (lane & 3) * G;
@@ -421,18 +254,18 @@ __device__ __forceinline__ void v_block(const uint32_t *hdr32, const char *lut, 
         for (int r = 0; r < kRounds; r++) {
             if constexpr (kP2 == 0) {
                 uint32_t fau[NS], fad[NS], fbu[NS], fbd[NS];
-                qd.template step<NS>(wm1, lut, mask2, fau, fad, fbu, fbd);
+                qd.step<NS>(wm1, lut, mask2, fau, fad, fbu, fbd);
                 v_accum<G, NS>(wl, wdn, wq, r * NS, fau, fad, fbu, fbd, st.acc);
             } else {
                 qd.begin(wm1);
                 {
                     uint32_t fau[kP1], fad[kP1], fbu[kP1], fbd[kP1];
-                    qd.template part<kP1>(lut, mask2, fau, fad, fbu, fbd);
+                    qd.part<kP1>(lut, mask2, fau, fad, fbu, fbd);
                     v_accum<G, kP1>(wl, wdn, wq, r * NS, fau, fad, fbu, fbd, st.acc);
                 }
                 {
                     uint32_t fau[kP2 ? kP2 : 1], fad[kP2 ? kP2 : 1], fbu[kP2 ? kP2 : 1], fbd[kP2 ? kP2 : 1];
-                    qd.template part<(kP2 ? kP2 : 1)>(lut, mask2, fau, fad, fbu, fbd);
+                    qd.part<(kP2 ? kP2 : 1)>(lut, mask2, fau, fad, fbu, fbd);
                     v_accum<G, (kP2 ? kP2 : 1)>(wl, wdn, wq, r * NS + kP1, fau, fad, fbu, fbd, st.acc);
                 }
                 qd.end(wm1);
@@ -440,7 +273,7 @@ __device__ __forceinline__ void v_block(const uint32_t *hdr32, const char *lut, 
         }
         if constexpr (kTail > 0) {
             uint32_t fau[kTail], fad[kTail], fbu[kTail], fbd[kTail];
-            qd.template step<kTail>(wm1, lut, mask2, fau, fad, fbu, fbd);
+            qd.step<kTail>(wm1, lut, mask2, fau, fad, fbu, fbd);
             v_accum<G, kTail>(wl, wdn, wq, kRounds * NS, fau, fad, fbu, fbd, st.acc);
         }
     }
@@ -549,7 +382,7 @@ __device__ __forceinline__ void decode_half(Quad &qd, const uint32_t *wm1, const
 #pragma unroll
     for (int r = 0; r < 16 / NS; r++) {
         uint32_t fau[NS], fad[NS], fbu[NS], fbd[NS];
-        qd.template step<NS>(wm1, lut, mask2, fau, fad, fbu, fbd);
+        qd.step<NS>(wm1, lut, mask2, fau, fad, fbu, fbd);
 #pragma unroll
         for (int k = 0; k < NS; k++) {
             eau[r * NS + k] = fau[k]; ead[r * NS + k] = fad[k]; ebu[r * NS + k] = fbu[k]; ebd[r * NS + k] = fbd[k];
@@ -1094,11 +927,9 @@ template <int G> struct WavesPerSimd { static constexpr int value = fused_wgs_pe
 // serves NS = floor(kWindowBits / LB) symbols.
 template <int G, int LB>
 __global__ __launch_bounds__(kThreads, WavesPerSimd<G>::value) void fused_attn_kernel(FusedArgs a) {
-    constexpr bool kTile = kGqaTile && G >= kMfmaMinG;  // decode into an LDS tile, int8 MFMA over the tile
-    constexpr bool kWide = G >= kMfmaMinG && !kTile;   // 32-bit table entries and two junk bits per window (4x4x4 path)
-    constexpr int NS = (32 - (kWide ? 2 : 1)) / LB;
-    static_assert(NS == kWindowBits / LB, "the second junk bit costs no symbol for the table widths in use");
-    __shared__ __attribute__((aligned(16))) uint16_t lut_s[2][(1 << LB) * (kWide ? 2 : 1)];
+    constexpr bool kTile = G >= kTileMinG;  // decode into an LDS tile, int8 MFMA over the tile
+    constexpr int NS = kWindowBits / LB;
+    __shared__ __attribute__((aligned(16))) uint16_t lut_s[2][1 << LB];
     __shared__ __attribute__((aligned(16))) float qf[G * kD];
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];  // per wave: staging area + weights
     const int tid = threadIdx.x, lane = tid & 63;
@@ -1106,12 +937,8 @@ __global__ __launch_bounds__(kThreads, WavesPerSimd<G>::value) void fused_attn_k
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     uint8_t *stage = smem + (size_t)wave * a.stage_bytes;
     constexpr int kWeightBytes = (int)fused_weight_bytes(G, LB);
-    static_assert(G < kMfmaMinG || kTile || kWeightBytes == 4 * MfmaRounds<NS>::kCount * G * 16, "weight area layout");
     static_assert(!kTile || kWeightBytes == kTileBytes * tile_halves_at_once(G), "tile area");
     float *wts = reinterpret_cast<float *>(smem + (size_t)kWaves * a.stage_bytes + (size_t)wave * kWeightBytes);
-    if constexpr (kWide) {  // entries of symbols that do not exist stay zero for the whole kernel
-        for (int i = lane; i < kWeightBytes / 16; i += 64) reinterpret_cast<uint4 *>(wts)[i] = make_uint4(0, 0, 0, 0);
-    }
     const char *lutK = reinterpret_cast<const char *>(&lut_s[0][0]);
     const char *lutV = reinterpret_cast<const char *>(&lut_s[1][0]);
 
@@ -1143,26 +970,18 @@ __global__ __launch_bounds__(kThreads, WavesPerSimd<G>::value) void fused_attn_k
         eV = tabV[j];
     }
     for (int t = 0; t < 2; t++) {
-        if constexpr (kWide) {  // {symbol << 8 | length} -> {fp16(symbol) << 16 | length}
-            uint32_t *dst = reinterpret_cast<uint32_t *>(&lut_s[t][0]);
-            for (int i = tid; i < (1 << g.lut_bits[t]); i += kThreads) {
-                const uint32_t e = g.lut[t * kLutSize + i];
-                dst[i] = ((uint32_t)__half_as_ushort(__float2half_rn((float)(e >> 8))) << 16) | (e & 0xffu);
+        const uint4 *src = reinterpret_cast<const uint4 *>(g.lut + t * kLutSize);
+        uint4 *dst = reinterpret_cast<uint4 *>(&lut_s[t][0]);
+        const int n16 = max(1, (2 << g.lut_bits[t]) / 16);
+        for (int i = tid; i < n16; i += kThreads) {
+            uint4 v = src[i];
+            if constexpr (kTile) {  // the tile holds symbol - 128 as int8
+                v.x ^= 0x80008000u; v.y ^= 0x80008000u; v.z ^= 0x80008000u; v.w ^= 0x80008000u;
             }
-        } else {
-            const uint4 *src = reinterpret_cast<const uint4 *>(g.lut + t * kLutSize);
-            uint4 *dst = reinterpret_cast<uint4 *>(&lut_s[t][0]);
-            const int n16 = max(1, (2 << g.lut_bits[t]) / 16);
-            for (int i = tid; i < n16; i += kThreads) {
-                uint4 v = src[i];
-                if constexpr (kTile) {  // the tile holds symbol - 128 as int8
-                    v.x ^= 0x80008000u; v.y ^= 0x80008000u; v.z ^= 0x80008000u; v.w ^= 0x80008000u;
-                }
-                dst[i] = v;
-            }
+            dst[i] = v;
         }
     }
-    const uint32_t maskK = a.mask2[0] << (kWide ? 1 : 0), maskV = a.mask2[1] << (kWide ? 1 : 0);
+    const uint32_t maskK = a.mask2[0], maskV = a.mask2[1];
     for (int i = tid; i < G * kD; i += kThreads) qf[i] = h2f(a.q[((size_t)b * g.Hq + (size_t)h * G) * kD + i]);
     Prefetch pf;
 #pragma unroll
@@ -1397,14 +1216,14 @@ static hipError_t launch_fused_g(const FusedArgs &a, int longest, size_t lds, hi
                                  hipStream_t s) {
     switch (fused_attn_table_bits(longest, G)) {
         case 6:
-            if constexpr (G < kMfmaMinG) return launch_fused_gn<G, 6>(a, lds, ev0, ev1, s);
+            if constexpr (G < kTileMinG) return launch_fused_gn<G, 6>(a, lds, ev0, ev1, s);
             return hipErrorInvalidValue;
         case 7: return launch_fused_gn<G, 7>(a, lds, ev0, ev1, s);
         case 8:
-            if constexpr (!(kGqaTile && G >= kMfmaMinG)) return launch_fused_gn<G, 8>(a, lds, ev0, ev1, s);
+            if constexpr (G < kTileMinG) return launch_fused_gn<G, 8>(a, lds, ev0, ev1, s);
             return hipErrorInvalidValue;
         case 10:
-            if constexpr (!(kGqaTile && G >= kMfmaMinG)) return launch_fused_gn<G, 10>(a, lds, ev0, ev1, s);
+            if constexpr (G < kTileMinG) return launch_fused_gn<G, 10>(a, lds, ev0, ev1, s);
             return hipErrorInvalidValue;
         default: return launch_fused_gn<G, 12>(a, lds, ev0, ev1, s);
     }

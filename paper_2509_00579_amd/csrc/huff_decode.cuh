@@ -83,11 +83,10 @@ constexpr int kWindowBits = 32 - kJunkBits;  // stream bits per window
 #if KVC_READER == 1
 // Readers keep a 64-bit piece {hi,lo} of the stream in registers plus the next word in reading direction, fetched
 // one window ahead: one 4-byte LDS read per window, off the critical path (only table lookups depend on each other).
-template <int JB>
-struct UpReaderT {
-    uint32_t P, idx, lo, hi, nx;  // P = (next unread payload bit) + 32 - JB = window start in wm1 bit coordinates
+struct UpReader {
+    uint32_t P, idx, lo, hi, nx;  // P = (next unread payload bit) + 32 - kJunkBits = window start in wm1 bit coordinates
     __device__ __forceinline__ void open(const uint32_t *wm1, uint32_t first_bit) {
-        P = first_bit + (uint32_t)(32 - JB);
+        P = first_bit + (uint32_t)(32 - kJunkBits);
         idx = P >> 5;
         lo = wm1[idx];
         hi = wm1[idx + 1];
@@ -104,12 +103,11 @@ struct UpReaderT {
         nx = wm1[nidx + 2];
     }
 };
-template <int JB>
-struct DownReaderT {
-    uint32_t P, idx, lo, hi, pv;  // P = (one past the next unread payload bit) + JB: the window [P, P+32) of wm1 ends
-                                  // JB bits above the next unread bit; bit-reversed it reads downwards
+struct DownReader {
+    uint32_t P, idx, lo, hi, pv;  // P = (one past the next unread payload bit) + kJunkBits: the window [P, P+32) of wm1 ends
+                                  // kJunkBits bits above the next unread bit; bit-reversed it reads downwards
     __device__ __forceinline__ void open(const uint32_t *wm1, uint32_t end_bit) {
-        P = end_bit + (uint32_t)JB;
+        P = end_bit + (uint32_t)kJunkBits;
         idx = P >> 5;
         lo = wm1[idx];
         hi = wm1[idx + 1];
@@ -130,20 +128,18 @@ struct DownReaderT {
 };
 #else
 // Every window re-reads its two words from LDS (one ds_read2_b32): least bookkeeping, more LDS traffic.
-template <int JB>
-struct UpReaderT {
-    uint32_t P;  // (next unread payload bit) + 32 - JB = window start in wm1 bit coordinates
-    __device__ __forceinline__ void open(const uint32_t *, uint32_t first_bit) { P = first_bit + (uint32_t)(32 - JB); }
+struct UpReader {
+    uint32_t P;  // (next unread payload bit) + 32 - kJunkBits = window start in wm1 bit coordinates
+    __device__ __forceinline__ void open(const uint32_t *, uint32_t first_bit) { P = first_bit + (uint32_t)(32 - kJunkBits); }
     __device__ __forceinline__ uint32_t window(const uint32_t *wm1) const {
         const uint32_t idx = P >> 5;
         return __builtin_amdgcn_alignbit(wm1[idx + 1], wm1[idx], P);
     }
     __device__ __forceinline__ void advance(const uint32_t *, uint32_t used) { P += used; }
 };
-template <int JB>
-struct DownReaderT {
-    uint32_t P;  // (one past the next unread payload bit) + JB
-    __device__ __forceinline__ void open(const uint32_t *, uint32_t end_bit) { P = end_bit + (uint32_t)JB; }
+struct DownReader {
+    uint32_t P;  // (one past the next unread payload bit) + kJunkBits
+    __device__ __forceinline__ void open(const uint32_t *, uint32_t end_bit) { P = end_bit + (uint32_t)kJunkBits; }
     __device__ __forceinline__ uint32_t window(const uint32_t *wm1) const {
         const uint32_t idx = P >> 5;
         return __builtin_bitreverse32(__builtin_amdgcn_alignbit(wm1[idx + 1], wm1[idx], P));
@@ -151,44 +147,34 @@ struct DownReaderT {
     __device__ __forceinline__ void advance(const uint32_t *, uint32_t used) { P -= used; }
 };
 #endif
-using UpReader = UpReaderT<kJunkBits>;
-using DownReader = DownReaderT<kJunkBits>;
 
 // Decode CNT symbols from a window.  lut: 16-bit entries (symbol << 8) | code length, indexed by the next `bits`
 // stream bits; mask2 = ((1 << bits) - 1) << 1.  CNT * (longest code word) <= kWindowBits is the caller's promise.
 // e[] receives the entries; returns the number of bits used.
 // `win` is left at the first bit that was not used, so that a further call continues in the same window.
-// WIDE: the table has 32-bit entries {symbol as an fp16 number, 0, code length} and the window two junk bits, so that
-// the masked window is again the byte offset of the entry (mask2 = ((1 << bits) - 1) << 2); only the low byte takes
-// part in the sum of lengths.  The wide table takes twice the LDS rows (more bank conflicts per gather): it pays
-// where the fp16 symbol saves more than that costs -- as the operand of the MFMA accumulation, not for the scalar
-// path, where feeding it to v_fma_mix_f32 was measured slower than the byte conversion of the narrow entry.
-template <int CNT, bool WIDE = false>
+template <int CNT>
 __device__ __forceinline__ uint32_t lookup_more(uint32_t &win, const char *lut, uint32_t mask2, uint32_t (&e)[CNT]) {
     uint32_t tot = 0;
 #pragma unroll
     for (int k = 0; k < CNT; k++) {
-        if constexpr (WIDE) e[k] = *reinterpret_cast<const uint32_t *>(lut + (win & mask2));
-        else e[k] = *reinterpret_cast<const uint16_t *>(lut + (win & mask2));
+        e[k] = *reinterpret_cast<const uint16_t *>(lut + (win & mask2));
         win >>= (e[k] & 31u);
         tot += e[k];  // low byte: running sum of code lengths (at most 31, never carries)
     }
     return tot & 0xffu;
 }
-template <int CNT, bool WIDE = false>
+template <int CNT>
 __device__ __forceinline__ uint32_t lookup(uint32_t win, const char *lut, uint32_t mask2, uint32_t (&e)[CNT]) {
-    return lookup_more<CNT, WIDE>(win, lut, mask2, e);
+    return lookup_more<CNT>(win, lut, mask2, e);
 }
 
 // the symbol of a table entry as fp32 (one v_cvt_f32_ubyte1)
 __device__ __forceinline__ float sym_f32(uint32_t e) { return (float)(e >> 8); }
 
 // The four chains of one lane (two slices x two directions) advance together, CNT symbols each.
-template <int JB>
-struct QuadT {
-    static constexpr bool kWide = JB == 2;
-    UpReaderT<JB> au, bu;
-    DownReaderT<JB> ad, bd;
+struct Quad {
+    UpReader au, bu;
+    DownReader ad, bd;
     // a = [a0, a0 + abits), b follows it
     __device__ __forceinline__ void open(const uint32_t *wm1, uint32_t a0, uint32_t abits, uint32_t bbits) {
         au.open(wm1, a0);
@@ -199,10 +185,10 @@ struct QuadT {
     template <int CNT>
     __device__ __forceinline__ void step(const uint32_t *wm1, const char *lut, uint32_t mask2, uint32_t (&fau)[CNT],
                                          uint32_t (&fad)[CNT], uint32_t (&fbu)[CNT], uint32_t (&fbd)[CNT]) {
-        const uint32_t u0 = lookup<CNT, kWide>(au.window(wm1), lut, mask2, fau);
-        const uint32_t u1 = lookup<CNT, kWide>(ad.window(wm1), lut, mask2, fad);
-        const uint32_t u2 = lookup<CNT, kWide>(bu.window(wm1), lut, mask2, fbu);
-        const uint32_t u3 = lookup<CNT, kWide>(bd.window(wm1), lut, mask2, fbd);
+        const uint32_t u0 = lookup<CNT>(au.window(wm1), lut, mask2, fau);
+        const uint32_t u1 = lookup<CNT>(ad.window(wm1), lut, mask2, fad);
+        const uint32_t u2 = lookup<CNT>(bu.window(wm1), lut, mask2, fbu);
+        const uint32_t u3 = lookup<CNT>(bd.window(wm1), lut, mask2, fbd);
         au.advance(wm1, u0);
         ad.advance(wm1, u1);
         bu.advance(wm1, u2);
@@ -221,10 +207,10 @@ struct QuadT {
     template <int CNT>
     __device__ __forceinline__ void part(const char *lut, uint32_t mask2, uint32_t (&fau)[CNT], uint32_t (&fad)[CNT],
                                          uint32_t (&fbu)[CNT], uint32_t (&fbd)[CNT]) {
-        u0 += lookup_more<CNT, kWide>(w0, lut, mask2, fau);
-        u1 += lookup_more<CNT, kWide>(w1, lut, mask2, fad);
-        u2 += lookup_more<CNT, kWide>(w2, lut, mask2, fbu);
-        u3 += lookup_more<CNT, kWide>(w3, lut, mask2, fbd);
+        u0 += lookup_more<CNT>(w0, lut, mask2, fau);
+        u1 += lookup_more<CNT>(w1, lut, mask2, fad);
+        u2 += lookup_more<CNT>(w2, lut, mask2, fbu);
+        u3 += lookup_more<CNT>(w3, lut, mask2, fbd);
     }
     __device__ __forceinline__ void end(const uint32_t *wm1) {
         au.advance(wm1, u0);
@@ -233,8 +219,6 @@ struct QuadT {
         bd.advance(wm1, u3);
     }
 };
-
-using Quad = QuadT<kJunkBits>;
 
 constexpr int kHalf = kSliceLen / 2;  // symbols per chain
 

@@ -76,13 +76,8 @@ constexpr int kPartialStride = kD + 2;  // o[128], m, l
 constexpr int kMaxSplits = 128;
 constexpr int kCUs = 256;  // compute units of the MI355X
 constexpr int kXCDs = 8;   // accelerator dies, each with its own L2; workgroups are dealt to them round-robin
-// How groups of 4 and 8 query heads accumulate (build-time, for measurements):
-//   1  a wave decodes a block into an LDS tile of bytes and multiplies it with the weights on int8 MFMA
-//   0  every round of decoded symbols goes through 4x4x4 fp16 MFMAs straight from registers
-#ifndef KVC_GQA_TILE
-#define KVC_GQA_TILE 1
-#endif
-constexpr bool kGqaTile = KVC_GQA_TILE != 0;
+// Groups of 4 and 8 query heads: a wave decodes a block into an LDS tile of bytes and multiplies the tile with the
+// weights of all heads on int8 MFMA.
 // The tile holds half a block at a time (16 symbols of each of the 4 x 64 decode chains):
 constexpr int kTileRowK = 64 + 4;            // bytes per token row of a K half tile (one spare word: no bank conflicts)
 constexpr int kTileRowV = 32 + 4;            // bytes per channel row of a V half tile
@@ -93,31 +88,28 @@ static_assert(kBT * kTileRowK <= kTileBytes, "K tile fits");
 // (two waves per SIMD).
 constexpr int tile_halves_at_once(int G) { return G >= 8 ? 2 : 1; }
 // Workgroups (of 4 waves) of the fused kernel that are resident per CU = its waves per SIMD: groups of 4 and 8 query
-// heads trade occupancy for registers (4x4x4 path) or for the LDS tiles (tile path).
+// heads trade occupancy for registers and for the LDS tiles.
 constexpr int fused_wgs_per_cu(int G) { return G >= 8 ? 2 : G >= 4 ? 3 : 4; }
 // Index width the fused kernel's LDS decode tables are compiled for, given the longest code word in use.
 constexpr int fused_table_bits(int longest) {
     return longest <= 7 ? 7 : longest <= 8 ? 8 : longest <= 10 ? 10 : 12;
 }
 // The fused kernel's own choice: groups of 1 and 2 heads also have a 6-bit variant (five symbols per window, taken in
-// two pieces; a 64-entry table fills one row of LDS banks); the 4x4x4 MFMA feeds at most four symbols to a product.
-// The tile path works on halves of 16 symbols, a whole number of windows of 4 or 2 symbols: widths 7 and 12.
+// two pieces; a 64-entry table fills one row of LDS banks).  Groups of 4 and 8 work on halves of 16 symbols, a whole
+// number of windows of 4 or 2 symbols: widths 7 and 12.
 constexpr int fused_attn_table_bits(int longest, int G) {
-    return G < 4 ? (longest <= 6 ? 6 : fused_table_bits(longest)) : kGqaTile ? (longest <= 7 ? 7 : 12) : fused_table_bits(longest);
+    return G < 4 ? (longest <= 6 ? 6 : fused_table_bits(longest)) : longest <= 7 ? 7 : 12;
 }
 constexpr int kLdsBytesPerCU = 160 * 1024;
 // Bytes of one wave's LDS area next to its staging area.  Groups of 1 and 2 heads: fp32 weights [128][G].  Groups of
-// 4 and 8: the tile of decoded symbols, or (4x4x4 path) one 16-byte weight entry per (chain array of 4, round, head),
-// rounds = ceil(32 / symbols per window).
-constexpr size_t fused_weight_bytes(int G, int table_bits) {
-    return G >= 4 ? (kGqaTile ? (size_t)kTileBytes * tile_halves_at_once(G)
-                              : (size_t)4 * ((32 + 31 / table_bits - 1) / (31 / table_bits)) * G * 16)
-                  : (size_t)G * kD * 4;
+// 4 and 8: the tile(s) of decoded symbols.
+constexpr size_t fused_weight_bytes(int G, int /*table_bits*/) {
+    return G >= 4 ? (size_t)kTileBytes * tile_halves_at_once(G) : (size_t)G * kD * 4;
 }
-// LDS of one fused-kernel workgroup apart from the per-wave staging areas: two decode tables (16-bit entries; 32-bit
-// ones on the 4x4x4 path), the query rows and the per-wave areas above.
+// LDS of one fused-kernel workgroup apart from the per-wave staging areas: two decode tables of 16-bit entries, the
+// query rows and the per-wave areas above.
 constexpr size_t fused_lds_fixed(int G, int longest) {
-    return ((size_t)(G >= 4 && !kGqaTile ? 8 : 4) << fused_attn_table_bits(longest, G)) + (size_t)G * kD * 4 +
+    return ((size_t)4 << fused_attn_table_bits(longest, G)) + (size_t)G * kD * 4 +
            4 * fused_weight_bytes(G, fused_attn_table_bits(longest, G)) + 512;
 }
 
