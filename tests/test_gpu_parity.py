@@ -117,6 +117,8 @@ def test_config0_end_to_end(gpu, oracle):
     (1, 2, 8, 333, 5e-3, 1e-2),     # GQA group of 4
     (1, 1, 8, 192, 2e-2, 2e-2),     # GQA group of 8, no residual
     (3, 2, 4, 129, 1e-2, 1e-2),     # GQA group of 2, one-token tail
+    (1, 1, 8, 200, 2e-3, 2e-3),     # 251 quantization levels: symbols above 127 through the int8 products of a group
+    (1, 2, 8, 136, 2e-3, 4e-3),     # the same for a group of 4
 ])
 def test_records_and_attention(gpu, oracle, B, H, Hq, S, rel_k, rel_v):
     _say(f"records+attention B={B} H={H} Hq={Hq} S={S}")
