@@ -28,6 +28,10 @@ VALU_INSTR_PER_SYMBOL = 7.35  # rocprofv3 SQ_INSTS_VALU / decoded wave-symbols (
 # two of them per symbol (the byte-to-float conversion and the FMA with the DPP quad broadcast) issue at half rate
 # (paper_2509_00579_amd/probes/valu_issue.hip: 4 cycles per wave64 instruction instead of 2): 9.35 issue slots
 VALU_SLOTS_PER_SYMBOL = VALU_INSTR_PER_SYMBOL + 2.0
+# Groups of 4 and 8 query heads (tile path): vector instructions of the compiled decode loop per block pair (1956 and
+# 2342, of which 735 and 891 in encodings that issue at half rate) over its 256 wave-symbols -- static counts of the
+# generated code, not counter readings.  query heads per KV head -> (instructions, issue slots) per wave-symbol
+VALU_PER_SYMBOL_BY_GROUP = {4: (1956 / 256, (1956 + 735) / 256), 8: (2342 / 256, (2342 + 891) / 256)}
 # share of the busy cycles in which the LDS pipe is active, the busiest unit of the fused kernel (rocprofv3
 # SQ_LDS_IDX_ACTIVE / SQ_BUSY_CU_CYCLES, profiles/): keyed like MEASURED_TRAFFIC
 MEASURED_LDS_BUSY = {("c1", 1e-2, 7): 0.38, ("c2", 1e-2, 7): 0.77}
@@ -388,6 +392,7 @@ def main():
                          f"restricted to batch {ob} x {oh} kv heads, seq {S}",
                "seconds": tc1 - tc0}
 
+    valu_instr, valu_slots = VALU_PER_SYMBOL_BY_GROUP.get(Hq // H, (VALU_INSTR_PER_SYMBOL, VALU_SLOTS_PER_SYMBOL))
     result = {
         "metric": "fused decode-attention GB/s (compressed) & % HBM peak; compression ratio",
         "value": value,
@@ -444,10 +449,10 @@ def main():
         # instructions, two of them at half rate.  Symbols decoded per second against what the vector ALUs could
         # issue at that cost per symbol, and the measured share of cycles with the LDS pipe busy.
         "roofline_alu": {"bound": "alu", "achieved": symbols_per_launch / (kern_ms * 1e-3) / 1e12,
-                         "peak": VALU_ISSUE_PER_S * 64 / VALU_SLOTS_PER_SYMBOL / 1e12, "unit": "Tsymbol/s",
-                         "frac": symbols_per_launch / (kern_ms * 1e-3) / (VALU_ISSUE_PER_S * 64 / VALU_SLOTS_PER_SYMBOL),
-                         "valu_instr_per_symbol": VALU_INSTR_PER_SYMBOL,
-                         "valu_issue_slots_per_symbol": VALU_SLOTS_PER_SYMBOL,
+                         "peak": VALU_ISSUE_PER_S * 64 / valu_slots / 1e12, "unit": "Tsymbol/s",
+                         "frac": symbols_per_launch / (kern_ms * 1e-3) / (VALU_ISSUE_PER_S * 64 / valu_slots),
+                         "valu_instr_per_symbol": valu_instr,
+                         "valu_issue_slots_per_symbol": valu_slots,
                          "lds_busy_frac": MEASURED_LDS_BUSY.get((args.workload, rel_eb, args.max_code_len))},
         "cpu_baseline": cpu,
     }
