@@ -28,10 +28,10 @@ VALU_INSTR_PER_SYMBOL = 7.35  # rocprofv3 SQ_INSTS_VALU / decoded wave-symbols (
 # two of them per symbol (the byte-to-float conversion and the FMA with the DPP quad broadcast) issue at half rate
 # (paper_2509_00579_amd/probes/valu_issue.hip: 4 cycles per wave64 instruction instead of 2): 9.35 issue slots
 VALU_SLOTS_PER_SYMBOL = VALU_INSTR_PER_SYMBOL + 2.0
-# Groups of 4 and 8 query heads (tile path): vector instructions of the compiled decode loop per block pair (1956 and
-# 2342, of which 735 and 891 in encodings that issue at half rate) over its 256 wave-symbols -- static counts of the
-# generated code, not counter readings.  query heads per KV head -> (instructions, issue slots) per wave-symbol
-VALU_PER_SYMBOL_BY_GROUP = {4: (1956 / 256, (1956 + 735) / 256), 8: (2342 / 256, (2342 + 891) / 256)}
+# Groups of 4 and 8 query heads (tile path): rocprofv3 SQ_INSTS_VALU per decoded wave-symbol (7.98 and 9.28,
+# profiles/fused_attn_kernel_c2.md); in the compiled decode loop 735 of 1956 and 891 of 2342 vector instructions have
+# encodings that issue at half rate and take a second slot.  query heads per KV head -> (instructions, issue slots)
+VALU_PER_SYMBOL_BY_GROUP = {4: (7.98, 7.98 * (1 + 735 / 1956)), 8: (9.28, 9.28 * (1 + 891 / 2342))}
 # share of the busy cycles in which the LDS pipe is active, the busiest unit of the fused kernel (rocprofv3
 # SQ_LDS_IDX_ACTIVE / SQ_BUSY_CU_CYCLES, profiles/): keyed like MEASURED_TRAFFIC
 MEASURED_LDS_BUSY = {("c1", 1e-2, 7): 0.38, ("c2", 1e-2, 7): 0.77}
