@@ -570,7 +570,7 @@ def test_config1_full_size_sampled(gpu, oracle):
                                             (6, 1e-2, 16)])
 def test_code_length_limits_select_every_decoder_variant(gpu, oracle, max_len, rel, Hq):
     """Shorter maximum code words: more symbols per decode window (5, 4, 3, 3, 2 for limits up to 6, 7, 8, 10, 12;
-    query-head groups of 4 and 8 take at most 4)."""
+    query-head groups of 4 and 8: 4 for limits up to 7, 2 above)."""
     _say(f"max_code_len={max_len} rel={rel} Hq={Hq}")
     B, H, S = 1, 2, 330
     Kx, Vx = W.make_kv(B, H, S, 31)
@@ -591,10 +591,12 @@ def test_code_length_limits_select_every_decoder_variant(gpu, oracle, max_len, r
     gc.close()
 
 
-def test_long_code_words_and_length_limit(gpu, oracle):
+@pytest.mark.parametrize("G", [1, 4, 8])
+def test_long_code_words_and_length_limit(gpu, oracle, G):
     """A geometric code histogram at prefill drives the code words to the 12-bit limit (count halving on both sides);
-    the later blocks then use every level, so records are large and the two-symbols-per-window decoder runs."""
-    _say("geometric prefill histogram -> 12-bit code words")
+    the later blocks then use every level, so records are large (above the 8 KiB that the first stage of the record
+    staging moves) and the two-symbols-per-window decoder runs, for one query head per KV head and for groups."""
+    _say(f"geometric prefill histogram -> 12-bit code words, {G} query heads per KV head")
     B, H, S = 1, 2, 256
     rng = np.random.default_rng(32)
     Kx, Vx = W.make_kv(B, H, S, 32)
@@ -604,11 +606,11 @@ def test_long_code_words_and_length_limit(gpu, oracle):
     vp = geo.astype(np.float16)
     vp[..., 0], vp[..., 1] = 0, 50      # every V unit (token over the channels) spans [0, 50]
     Kx[:, :64], Vx[:, :64] = kp, vp
-    oc = oracle.OracleCache(B, H, H, S, 1e-2, 1e-2)
+    oc = oracle.OracleCache(B, H, G * H, S, 1e-2, 1e-2)
     oc.build_codebook(Kx[:, :64], Vx[:, :64])
     assert oc.halvings[K] > 0 and int(oc.len[K].max()) == 12 and int(oc.len[V].max()) == 12
     oc.compress_blocks(Kx, Vx)
-    gc = gpu.KVCompCache(B, H, H, S, 1e-2, 1e-2)
+    gc = gpu.KVCompCache(B, H, G * H, S, 1e-2, 1e-2)
     gc.build_codebook(_dev(Kx[:, :64]), _dev(Vx[:, :64]))
     gc.compress_blocks(_dev(Kx), _dev(Vx))
     for which in (K, V):
@@ -616,7 +618,7 @@ def test_long_code_words_and_length_limit(gpu, oracle):
         np.testing.assert_array_equal(ln_g, oc.len[which])
         np.testing.assert_array_equal(cd_g, oc.code[which])
     _assert_same_cache(oc, gc)
-    q = W.make_queries(B, H, 1, 32)[0]
+    q = W.make_queries(B, G * H, 1, 32)[0]
     _attn_close(gc.attn_decode(_dev(q), SCALE).cpu().numpy(), oc.attn_decode(q, SCALE))
     _say(f"  largest record {gc.stats()['max_record_bytes']} B, CR {gc.stats()['compression_ratio']:.3f}")
     gc.close()
