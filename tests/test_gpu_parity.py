@@ -142,22 +142,23 @@ def test_all_residual_and_tiny_sequences(gpu, oracle):
         gc.close()
 
 
-def test_symbols_unseen_at_codebook_build(gpu, oracle):
-    _say("codebook from a narrow prefix, later data uses every level")
+@pytest.mark.parametrize("G", [1, 4, 8])
+def test_symbols_unseen_at_codebook_build(gpu, oracle, G):
+    _say(f"codebook from a narrow prefix, later data uses every level; {G} query heads per KV head")
     B, H, S = 1, 2, 256
     Kx, Vx = W.make_kv(B, H, S, 24)
     # the first 64 tokens use only three distinct values per unit -> the histogram sees few levels
     Kx[:, :64] = np.float16(0.0); Kx[:, 0:64:2] = np.float16(1.0); Kx[:, 1:64:7] = np.float16(0.5)
     Vx[:, :64] = np.float16(0.0); Vx[:, :64, :, ::2] = np.float16(1.0); Vx[:, :64, :, 1::7] = np.float16(0.5)
-    oc = oracle.OracleCache(B, H, H, S, 1e-2, 1e-2)
+    oc = oracle.OracleCache(B, H, G * H, S, 1e-2, 1e-2)
     oc.build_codebook(Kx[:, :64], Vx[:, :64])
     oc.compress_blocks(Kx, Vx)
-    gc = gpu.KVCompCache(B, H, H, S, 1e-2, 1e-2)
+    gc = gpu.KVCompCache(B, H, G * H, S, 1e-2, 1e-2)
     gc.build_codebook(_dev(Kx[:, :64]), _dev(Vx[:, :64]))
     gc.compress_blocks(_dev(Kx), _dev(Vx))
     assert int(oc.len[K].max()) > 8  # rare levels got long code words
     _assert_same_cache(oc, gc)
-    q = W.make_queries(B, H, 1, 24)[0]
+    q = W.make_queries(B, G * H, 1, 24)[0]
     _attn_close(gc.attn_decode(_dev(q), SCALE).cpu().numpy(), oc.attn_decode(q, SCALE))
     # the same cache decoded with a staging area smaller than its records (global-memory path)
     assert gc.stats()["max_record_bytes"] > 4608
