@@ -4,7 +4,8 @@
 // of one token with a lookup table -- each slice from both ends, four independent decode chains of 32 symbols per
 // lane -- and accumulates q.k in registers; the wave then updates a running softmax and decodes the V record of the
 // same block, every lane owning two channels (two slices, again four chains) and accumulating p.v in registers.  No
-// decompressed value ever leaves the registers (Section 3.3.2).
+// decompressed value ever leaves the compute unit (Section 3.3.2): decoded symbols stay in registers for groups of 1
+// and 2 query heads and pass through an LDS tile of quantization codes for groups of 4 and 8.
 //
 // What differs from the paper's kernel, and why (gfx950):
 //  * lookup-table decode instead of the bit-serial tree walk of Section 3.3.1: all 64 lanes of a wave advance in
@@ -18,7 +19,8 @@
 //  * the dequantization is folded into the weights: q.k' = sum_c q_c min_c + sum_c (q_c step_c) code_tc, and
 //    p.v'  = sum_t p_t min_t + sum_t (p_t step_t) code_tc: one convert and one FMA per decoded symbol;
 //  * K and V of a block are handled by the same wave back to back with an online softmax, so scores never go to
-//    memory; while one record is decoded the next one is already on its way from HBM into registers;
+//    memory; while one record is decoded the next one is already on its way from HBM into registers (tile path:
+//    straight into LDS while the products of the previous record run);
 //  * the sequence is split over workgroups; the workgroup that finishes last merges the splits (the "sum
 //    reduction" of Section 3.3.2) inside the same launch.
 #include <hip/hip_fp16.h>
