@@ -363,35 +363,61 @@ __device__ __forceinline__ uint32_t pack_syms(uint32_t e0, uint32_t e1, uint32_t
     return __builtin_amdgcn_perm(hi, lo, 0x05040100u);
 }
 
-// Decodes symbols 16 HALF .. 16 HALF + 15 of this lane's four chains into the tile: the up chain of a slice fills
-// bytes 0..15 of its 32-byte row segment upwards, the down chain bytes 31..16 downwards (so the segment holds 32
-// positions of the slice in ascending order: 16 HALF .. +15 and 48 - 16 HALF .. +15); a word is stored as soon as the
-// rounds have delivered its four symbols.  16 must be a multiple of NS.
-template <int NS>
-__device__ __forceinline__ void decode_half(Quad &qd, const uint32_t *wm1, const char *lut, uint32_t mask2,
-                                            uint8_t *seg_a, uint8_t *seg_b) {
-    static_assert(16 % NS == 0, "a half is a whole number of windows");
-    uint32_t eau[16], ead[16], ebu[16], ebd[16];
+// The table entries of the 4 x 32 symbols of a lane's chains while they wait to be packed (fully unrolled code: an
+// entry lives in a register from its lookup to the store of its word).
+struct ChainSyms {
+    uint32_t au[kHalf], ad[kHalf], bu[kHalf], bd[kHalf];
+};
+// Decodes symbols S0 .. S1-1 of this lane's four chains (whole windows of NS symbols from S0 on; the last window of a
+// chain may be short) and stores tile words W0 .. W1-1 as soon as their four symbols are there, including words that
+// an earlier span completed but was not allowed to store.  Word w holds symbols 4w .. 4w+3; it belongs to half w / 4,
+// whose row segments start half_stride bytes after those of half 0.  Inside a 32-byte segment the up chain of a slice
+// fills bytes 0..15 upwards and the down chain bytes 31..16 downwards, so that the segment holds 32 positions of the
+// slice in ascending order: 16 h .. +15 and 48 - 16 h .. +15.
+template <int NS, int S0, int S1, int W0, int W1>
+__device__ __forceinline__ void decode_span(Quad &qd, const uint32_t *wm1, const char *lut, uint32_t mask2, ChainSyms &e,
+                                            uint8_t *seg_a, uint8_t *seg_b, int half_stride) {
+    static_assert(S0 % NS == 0 && S0 < S1 && S1 <= kHalf && (S1 % NS == 0 || S1 == kHalf), "whole windows");
     auto store_words = [&](int w0, int w1) {
 #pragma unroll
         for (int w = w0; w < w1; w++) {
-            *reinterpret_cast<uint32_t *>(seg_a + 4 * w) = pack_syms(eau[4 * w], eau[4 * w + 1], eau[4 * w + 2], eau[4 * w + 3]);
-            *reinterpret_cast<uint32_t *>(seg_a + 28 - 4 * w) = pack_syms(ead[4 * w + 3], ead[4 * w + 2], ead[4 * w + 1], ead[4 * w]);
-            *reinterpret_cast<uint32_t *>(seg_b + 4 * w) = pack_syms(ebu[4 * w], ebu[4 * w + 1], ebu[4 * w + 2], ebu[4 * w + 3]);
-            *reinterpret_cast<uint32_t *>(seg_b + 28 - 4 * w) = pack_syms(ebd[4 * w + 3], ebd[4 * w + 2], ebd[4 * w + 1], ebd[4 * w]);
+            const int k = w & 3;
+            uint8_t *a = seg_a + (w >> 2) * half_stride, *b = seg_b + (w >> 2) * half_stride;
+            *reinterpret_cast<uint32_t *>(a + 4 * k) = pack_syms(e.au[4 * w], e.au[4 * w + 1], e.au[4 * w + 2], e.au[4 * w + 3]);
+            *reinterpret_cast<uint32_t *>(a + 28 - 4 * k) = pack_syms(e.ad[4 * w + 3], e.ad[4 * w + 2], e.ad[4 * w + 1], e.ad[4 * w]);
+            *reinterpret_cast<uint32_t *>(b + 4 * k) = pack_syms(e.bu[4 * w], e.bu[4 * w + 1], e.bu[4 * w + 2], e.bu[4 * w + 3]);
+            *reinterpret_cast<uint32_t *>(b + 28 - 4 * k) = pack_syms(e.bd[4 * w + 3], e.bd[4 * w + 2], e.bd[4 * w + 1], e.bd[4 * w]);
         }
     };
+    constexpr auto imin = [](int x, int y) { return x < y ? x : y; };
+    constexpr auto imax = [](int x, int y) { return x > y ? x : y; };
+    store_words(W0, imin(W1, S0 / 4));
+    constexpr int kFull = (S1 - S0) / NS, kTail = (S1 - S0) - kFull * NS;
 #pragma unroll
-    for (int r = 0; r < 16 / NS; r++) {
+    for (int r = 0; r < kFull; r++) {
         uint32_t fau[NS], fad[NS], fbu[NS], fbd[NS];
         qd.step<NS>(wm1, lut, mask2, fau, fad, fbu, fbd);
+        const int s = S0 + r * NS;
 #pragma unroll
         for (int k = 0; k < NS; k++) {
-            eau[r * NS + k] = fau[k]; ead[r * NS + k] = fad[k]; ebu[r * NS + k] = fbu[k]; ebd[r * NS + k] = fbd[k];
+            e.au[s + k] = fau[k]; e.ad[s + k] = fad[k]; e.bu[s + k] = fbu[k]; e.bd[s + k] = fbd[k];
         }
-        store_words(r * NS / 4, (r + 1) * NS / 4);
+        store_words(imax(W0, s / 4), imin(W1, (s + NS) / 4));
+    }
+    if constexpr (kTail > 0) {
+        uint32_t fau[kTail], fad[kTail], fbu[kTail], fbd[kTail];
+        qd.step<kTail>(wm1, lut, mask2, fau, fad, fbu, fbd);
+        constexpr int s = S0 + kFull * NS;
+#pragma unroll
+        for (int k = 0; k < kTail; k++) {
+            e.au[s + k] = fau[k]; e.ad[s + k] = fad[k]; e.bu[s + k] = fbu[k]; e.bd[s + k] = fbd[k];
+        }
+        store_words(imax(W0, s / 4), imin(W1, (s + kTail) / 4));
     }
 }
+// first symbol that the second span of a block decodes when the product runs after each half: the first half's
+// windows are whole, so they may reach into the second half (its entries then wait in registers)
+constexpr int tile_first_span(int NS) { return (16 + NS - 1) / NS * NS; }
 
 // power-of-two factor that brings the largest weight of the wave into [2^21, 2^22) (1 if all are zero); *inv = 1/f
 __device__ __forceinline__ float int_scale(float amax, float *inv) {
@@ -531,10 +557,11 @@ __device__ __forceinline__ void k_tile_block(const uint32_t *hdr32, const char *
             for (int i = 0; i < HL; i++) sc[i][t] = first ? v[i] : sc[i][t] + v[i];
         }
     };
+    ChainSyms syms;
+    constexpr int kP = tile_first_span(NS);
     if constexpr (kBoth) {
-        decode_half<NS>(qd, wm1, lut, mask2, row, row + 32);
+        decode_span<NS, 0, kHalf, 0, 8>(qd, wm1, lut, mask2, syms, row, row + 32, kTileBytes);
         KVC_TICK(2);
-        decode_half<NS>(qd, wm1, lut, mask2, row + kTileBytes, row + kTileBytes + 32);
         wave_sync();
         record_done();
         clear();
@@ -545,7 +572,8 @@ __device__ __forceinline__ void k_tile_block(const uint32_t *hdr32, const char *
     } else {
 #pragma unroll
         for (int half = 0; half < 2; half++) {
-            decode_half<NS>(qd, wm1, lut, mask2, row, row + 32);
+            if (half == 0) decode_span<NS, 0, kP, 0, 4>(qd, wm1, lut, mask2, syms, row, row + 32, 0);
+            else decode_span<NS, kP, kHalf, 4, 8>(qd, wm1, lut, mask2, syms, row, row + 32, 0);
             wave_sync();
             if (half == 0) KVC_TICK(2);
             if (half == 1) record_done();
@@ -656,10 +684,11 @@ __device__ __forceinline__ void v_tile_block(const uint32_t *hdr32, const char *
             for (int i = 0; i < HL; i++) ts.acc[i][ct] = fmaf(inv, v[i], ts.acc[i][ct]);
         }
     };
+    ChainSyms syms;
+    constexpr int kP = tile_first_span(NS);
     if constexpr (kBoth) {
-        decode_half<NS>(qd, wm1, lut, mask2, row_a, row_b);
+        decode_span<NS, 0, kHalf, 0, 8>(qd, wm1, lut, mask2, syms, row_a, row_b, kTileBytes);
         KVC_TICK(7);
-        decode_half<NS>(qd, wm1, lut, mask2, row_a + kTileBytes, row_b + kTileBytes);
         wave_sync();
         record_done();
         clear();
@@ -671,7 +700,8 @@ __device__ __forceinline__ void v_tile_block(const uint32_t *hdr32, const char *
     } else {
 #pragma unroll
         for (int half = 0; half < 2; half++) {
-            decode_half<NS>(qd, wm1, lut, mask2, row_a, row_b);
+            if (half == 0) decode_span<NS, 0, kP, 0, 4>(qd, wm1, lut, mask2, syms, row_a, row_b, 0);
+            else decode_span<NS, kP, kHalf, 4, 8>(qd, wm1, lut, mask2, syms, row_a, row_b, 0);
             wave_sync();
             if (half == 0) KVC_TICK(7);
             if (half == 1) record_done();
@@ -1218,15 +1248,10 @@ static hipError_t launch_fused_g(const FusedArgs &a, int longest, size_t lds, hi
                                  hipStream_t s) {
     switch (fused_attn_table_bits(longest, G)) {
         case 6:
-            if constexpr (G < kTileMinG) return launch_fused_gn<G, 6>(a, lds, ev0, ev1, s);
-            return hipErrorInvalidValue;
+            return launch_fused_gn<G, 6>(a, lds, ev0, ev1, s);
         case 7: return launch_fused_gn<G, 7>(a, lds, ev0, ev1, s);
-        case 8:
-            if constexpr (G < kTileMinG) return launch_fused_gn<G, 8>(a, lds, ev0, ev1, s);
-            return hipErrorInvalidValue;
-        case 10:
-            if constexpr (G < kTileMinG) return launch_fused_gn<G, 10>(a, lds, ev0, ev1, s);
-            return hipErrorInvalidValue;
+        case 8: return launch_fused_gn<G, 8>(a, lds, ev0, ev1, s);
+        case 10: return launch_fused_gn<G, 10>(a, lds, ev0, ev1, s);
         default: return launch_fused_gn<G, 12>(a, lds, ev0, ev1, s);
     }
 }

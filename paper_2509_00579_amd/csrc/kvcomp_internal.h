@@ -94,12 +94,9 @@ constexpr int fused_wgs_per_cu(int G) { return G >= 8 ? 2 : G >= 4 ? 3 : 4; }
 constexpr int fused_table_bits(int longest) {
     return longest <= 7 ? 7 : longest <= 8 ? 8 : longest <= 10 ? 10 : 12;
 }
-// The fused kernel's own choice: groups of 1 and 2 heads also have a 6-bit variant (five symbols per window, taken in
-// two pieces; a 64-entry table fills one row of LDS banks).  Groups of 4 and 8 work on halves of 16 symbols, a whole
-// number of windows of 4 or 2 symbols: widths 7 and 12.
-constexpr int fused_attn_table_bits(int longest, int G) {
-    return G < 4 ? (longest <= 6 ? 6 : fused_table_bits(longest)) : longest <= 7 ? 7 : 12;
-}
+// The fused kernel's own choice: it also has a 6-bit variant (five symbols per window; a 64-entry table fills one row
+// of LDS banks).
+constexpr int fused_attn_table_bits(int longest, int /*G*/) { return longest <= 6 ? 6 : fused_table_bits(longest); }
 constexpr int kLdsBytesPerCU = 160 * 1024;
 // Bytes of one wave's LDS area next to its staging area.  Groups of 1 and 2 heads: fp32 weights [128][G].  Groups of
 // 4 and 8: the tile(s) of decoded symbols.

@@ -568,10 +568,11 @@ def test_config1_full_size_sampled(gpu, oracle):
 
 @pytest.mark.parametrize("max_len,rel,Hq", [(6, 1e-2, 4), (7, 1e-2, 4), (7, 5e-3, 4), (8, 5e-3, 4), (10, 1e-2, 4),
                                             (12, 1e-2, 4), (6, 1e-2, 2), (5, 2e-2, 2), (5, 2e-2, 4), (6, 1e-2, 8),
-                                            (6, 1e-2, 16)])
+                                            (6, 1e-2, 16), (8, 5e-3, 8), (10, 1e-2, 8), (12, 1e-2, 16), (8, 5e-3, 16),
+                                            (10, 5e-3, 16)])
 def test_code_length_limits_select_every_decoder_variant(gpu, oracle, max_len, rel, Hq):
     """Shorter maximum code words: more symbols per decode window (5, 4, 3, 3, 2 for limits up to 6, 7, 8, 10, 12;
-    query-head groups of 4 and 8: 4 for limits up to 7, 2 above)."""
+    for every size of query-head group)."""
     _say(f"max_code_len={max_len} rel={rel} Hq={Hq}")
     B, H, S = 1, 2, 330
     Kx, Vx = W.make_kv(B, H, S, 31)
