@@ -34,7 +34,7 @@ VALU_SLOTS_PER_SYMBOL = VALU_INSTR_PER_SYMBOL + 2.0
 VALU_PER_SYMBOL_BY_GROUP = {4: (7.98, 7.98 * (1 + 735 / 1956)), 8: (9.28, 9.28 * (1 + 891 / 2342))}
 # share of the busy cycles in which the LDS pipe is active, the busiest unit of the fused kernel (rocprofv3
 # SQ_LDS_IDX_ACTIVE / SQ_BUSY_CU_CYCLES, profiles/): keyed like MEASURED_TRAFFIC
-MEASURED_LDS_BUSY = {("c1", 1e-2, 7): 0.38, ("c2", 1e-2, 7): 0.77}
+MEASURED_LDS_BUSY = {("c1", 1e-2, 7): 0.38, ("c2", 1e-2, 7): 0.77, ("c3", 1e-2, 7): 0.69, ("c4", 1e-2, 7): 0.54}
 # HBM bytes per fused-kernel launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by a copy of known size
 # (profiles/); keyed by (workload, rel_eb, max code word); None where not measured.
 MEASURED_TRAFFIC = {("c1", 1e-2, 7): 27.05e6}  # bytes per launch, profiles/fused_attn_kernel_c1.md
