@@ -364,34 +364,30 @@ __device__ __forceinline__ uint32_t pack_syms(uint32_t e0, uint32_t e1, uint32_t
 }
 
 // The table entries of the 4 x 32 symbols of a lane's chains while they wait to be packed (fully unrolled code: an
-// entry lives in a register from its lookup to the store of its word).
+// entry lives in a register from its lookup to the packing of its word).
 struct ChainSyms {
     uint32_t au[kHalf], ad[kHalf], bu[kHalf], bd[kHalf];
 };
+// The decoded symbols (biased bytes) of the lane's two slices, four per word, in ascending position inside the slice:
+// word j of a slice holds positions 4j .. 4j+3.  The up chain delivers words 0, 1, .. and the down chain 15, 14, ..
+struct SliceWords {
+    uint32_t a[16], b[16];
+};
 // Decodes symbols S0 .. S1-1 of this lane's four chains (whole windows of NS symbols from S0 on; the last window of a
-// chain may be short) and stores tile words W0 .. W1-1 as soon as their four symbols are there, including words that
-// an earlier span completed but was not allowed to store.  Word w holds symbols 4w .. 4w+3; it belongs to half w / 4,
-// whose row segments start half_stride bytes after those of half 0.  Inside a 32-byte segment the up chain of a slice
-// fills bytes 0..15 upwards and the down chain bytes 31..16 downwards, so that the segment holds 32 positions of the
-// slice in ascending order: 16 h .. +15 and 48 - 16 h .. +15.
-template <int NS, int S0, int S1, int W0, int W1>
+// chain may be short) and packs every word whose four symbols are there.
+template <int NS, int S0, int S1>
 __device__ __forceinline__ void decode_span(Quad &qd, const uint32_t *wm1, const char *lut, uint32_t mask2, ChainSyms &e,
-                                            uint8_t *seg_a, uint8_t *seg_b, int half_stride) {
+                                            SliceWords &p) {
     static_assert(S0 % NS == 0 && S0 < S1 && S1 <= kHalf && (S1 % NS == 0 || S1 == kHalf), "whole windows");
-    auto store_words = [&](int w0, int w1) {
+    auto pack_words = [&](int w0, int w1) {
 #pragma unroll
         for (int w = w0; w < w1; w++) {
-            const int k = w & 3;
-            uint8_t *a = seg_a + (w >> 2) * half_stride, *b = seg_b + (w >> 2) * half_stride;
-            *reinterpret_cast<uint32_t *>(a + 4 * k) = pack_syms(e.au[4 * w], e.au[4 * w + 1], e.au[4 * w + 2], e.au[4 * w + 3]);
-            *reinterpret_cast<uint32_t *>(a + 28 - 4 * k) = pack_syms(e.ad[4 * w + 3], e.ad[4 * w + 2], e.ad[4 * w + 1], e.ad[4 * w]);
-            *reinterpret_cast<uint32_t *>(b + 4 * k) = pack_syms(e.bu[4 * w], e.bu[4 * w + 1], e.bu[4 * w + 2], e.bu[4 * w + 3]);
-            *reinterpret_cast<uint32_t *>(b + 28 - 4 * k) = pack_syms(e.bd[4 * w + 3], e.bd[4 * w + 2], e.bd[4 * w + 1], e.bd[4 * w]);
+            p.a[w] = pack_syms(e.au[4 * w], e.au[4 * w + 1], e.au[4 * w + 2], e.au[4 * w + 3]);
+            p.a[15 - w] = pack_syms(e.ad[4 * w + 3], e.ad[4 * w + 2], e.ad[4 * w + 1], e.ad[4 * w]);
+            p.b[w] = pack_syms(e.bu[4 * w], e.bu[4 * w + 1], e.bu[4 * w + 2], e.bu[4 * w + 3]);
+            p.b[15 - w] = pack_syms(e.bd[4 * w + 3], e.bd[4 * w + 2], e.bd[4 * w + 1], e.bd[4 * w]);
         }
     };
-    constexpr auto imin = [](int x, int y) { return x < y ? x : y; };
-    constexpr auto imax = [](int x, int y) { return x > y ? x : y; };
-    store_words(W0, imin(W1, S0 / 4));
     constexpr int kFull = (S1 - S0) / NS, kTail = (S1 - S0) - kFull * NS;
 #pragma unroll
     for (int r = 0; r < kFull; r++) {
@@ -402,7 +398,7 @@ __device__ __forceinline__ void decode_span(Quad &qd, const uint32_t *wm1, const
         for (int k = 0; k < NS; k++) {
             e.au[s + k] = fau[k]; e.ad[s + k] = fad[k]; e.bu[s + k] = fbu[k]; e.bd[s + k] = fbd[k];
         }
-        store_words(imax(W0, s / 4), imin(W1, (s + NS) / 4));
+        pack_words(s / 4, (s + NS) / 4);
     }
     if constexpr (kTail > 0) {
         uint32_t fau[kTail], fad[kTail], fbu[kTail], fbd[kTail];
@@ -412,12 +408,25 @@ __device__ __forceinline__ void decode_span(Quad &qd, const uint32_t *wm1, const
         for (int k = 0; k < kTail; k++) {
             e.au[s + k] = fau[k]; e.ad[s + k] = fad[k]; e.bu[s + k] = fbu[k]; e.bd[s + k] = fbd[k];
         }
-        store_words(imax(W0, s / 4), imin(W1, (s + kTail) / 4));
+        pack_words(s / 4, (s + kTail) / 4);
     }
 }
-// first symbol that the second span of a block decodes when the product runs after each half: the first half's
-// windows are whole, so they may reach into the second half (its entries then wait in registers)
+// first symbol that the second span of a block decodes when the products run after each half: the first half's
+// windows are whole, so they may reach into the second half
 constexpr int tile_first_span(int NS) { return (16 + NS - 1) / NS * NS; }
+
+// The B operands of v_mfma_i32_32x32x16_i8 for one step of 16 positions (words w[0..3] of a slice) straight from
+// registers.  Lane l of the operand supplies column l % 32 and positions 8 (l / 32) .. +7.  With one slice per lane and
+// 64 lanes there are two column tiles: tile 0 wants words 0, 1 of lanes 0..31 in its lower half and words 2, 3 of the
+// same lanes in its upper half, tile 1 words 0, 1 of lanes 32..63 in its lower half and their words 2, 3 in its upper
+// half -- which is what v_permlane32_swap_b32 makes of (word 0, word 2) and of (word 1, word 3).
+typedef unsigned int v2u __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ void step_operands(uint32_t w0, uint32_t w1, uint32_t w2, uint32_t w3, long &tile0, long &tile1) {
+    const v2u r0 = __builtin_amdgcn_permlane32_swap(w0, w2, false, false);
+    const v2u r1 = __builtin_amdgcn_permlane32_swap(w1, w3, false, false);
+    tile0 = (long)(((unsigned long long)r1.x << 32) | r0.x);
+    tile1 = (long)(((unsigned long long)r1.y << 32) | r0.y);
+}
 
 // power-of-two factor that brings the largest weight of the wave into [2^21, 2^22) (1 if all are zero); *inv = 1/f
 __device__ __forceinline__ float int_scale(float amax, float *inv) {
@@ -527,20 +536,20 @@ __device__ __forceinline__ void k_tile_block(const uint32_t *hdr32, const char *
     const uint32_t *wm1 = hdr32 + (kmm + 2 * kSlices) / 4 - 1;
     Quad qd;
     qd.open(wm1, start, sb & 0xffffu, sb >> 16);
-    uint8_t *row = tile + lane * kTileRowK;  // lane = token; 64 bytes: the two slices' segments
-    constexpr bool kBoth = tile_halves_at_once(G) == 2;  // decode both halves (into two tiles), then multiply
+    constexpr bool kBoth = tile_halves_at_once(G) == 2;  // decode the whole block, then multiply once
     float sc[HL][2];
-    v16i d[2];
-    // tile bytes 0..15 | 16..31 | 32..47 | 48..63 of half h hold channels 16h.. | 48-16h.. | 64+16h.. | 112-16h..
-    auto products = [&](int half, const uint8_t *t0) {
-#pragma unroll
-        for (int ks = 0; ks < 4; ks++) {
-            const int kk = half == 0 ? (ks == 0 ? 0 : ks == 1 ? 3 : ks == 2 ? 4 : 7) : (ks == 0 ? 1 : ks == 1 ? 2 : ks == 2 ? 5 : 6);
-#pragma unroll
-            for (int t = 0; t < 2; t++)
-                d[t] = __builtin_amdgcn_mfma_i32_32x32x16_i8(a[kk], lds_pair(t0 + (32 * t + x) * kTileRowK + 16 * ks + 8 * hv),
-                                                             d[t], 0, 0, 0);
-        }
+    v16i d[2];  // result tiles: tokens 0..31 and 32..63
+    ChainSyms syms;
+    SliceWords pw;  // lane = token: slice a = its channels 0..63, slice b = its channels 64..127
+    // one step of 16 channels of either slice: steps 0..3 are channels 0..63, steps 4..7 channels 64..127
+    auto products = [&](int ks) {
+        long t0, t1;
+        step_operands(pw.a[4 * ks], pw.a[4 * ks + 1], pw.a[4 * ks + 2], pw.a[4 * ks + 3], t0, t1);
+        d[0] = __builtin_amdgcn_mfma_i32_32x32x16_i8(a[ks], t0, d[0], 0, 0, 0);
+        d[1] = __builtin_amdgcn_mfma_i32_32x32x16_i8(a[ks], t1, d[1], 0, 0, 0);
+        step_operands(pw.b[4 * ks], pw.b[4 * ks + 1], pw.b[4 * ks + 2], pw.b[4 * ks + 3], t0, t1);
+        d[0] = __builtin_amdgcn_mfma_i32_32x32x16_i8(a[4 + ks], t0, d[0], 0, 0, 0);
+        d[1] = __builtin_amdgcn_mfma_i32_32x32x16_i8(a[4 + ks], t1, d[1], 0, 0, 0);
     };
     auto clear = [&] {
 #pragma unroll
@@ -557,31 +566,31 @@ __device__ __forceinline__ void k_tile_block(const uint32_t *hdr32, const char *
             for (int i = 0; i < HL; i++) sc[i][t] = first ? v[i] : sc[i][t] + v[i];
         }
     };
-    ChainSyms syms;
     constexpr int kP = tile_first_span(NS);
+    // a half of a block is 16 symbols of every chain: the up chains deliver step h, the down chains step 3 - h
     if constexpr (kBoth) {
-        decode_span<NS, 0, kHalf, 0, 8>(qd, wm1, lut, mask2, syms, row, row + 32, kTileBytes);
+        decode_span<NS, 0, kHalf>(qd, wm1, lut, mask2, syms, pw);
         KVC_TICK(2);
         wave_sync();
         record_done();
         clear();
-        products(0, tile);
-        products(1, tile + kTileBytes);
-        join(true);
-        wave_sync();
-    } else {
 #pragma unroll
-        for (int half = 0; half < 2; half++) {
-            if (half == 0) decode_span<NS, 0, kP, 0, 4>(qd, wm1, lut, mask2, syms, row, row + 32, 0);
-            else decode_span<NS, kP, kHalf, 4, 8>(qd, wm1, lut, mask2, syms, row, row + 32, 0);
-            wave_sync();
-            if (half == 0) KVC_TICK(2);
-            if (half == 1) record_done();
-            clear();
-            products(half, tile);
-            join(half == 0);
-            wave_sync();
-        }
+        for (int ks = 0; ks < 4; ks++) products(ks);
+        join(true);
+    } else {
+        decode_span<NS, 0, kP>(qd, wm1, lut, mask2, syms, pw);
+        KVC_TICK(2);
+        clear();
+        products(0);
+        products(3);
+        join(true);
+        decode_span<NS, kP, kHalf>(qd, wm1, lut, mask2, syms, pw);
+        wave_sync();
+        record_done();
+        clear();
+        products(1);
+        products(2);
+        join(false);
     }
     KVC_TICK(3);
 #pragma unroll
@@ -647,27 +656,28 @@ __device__ __forceinline__ void v_tile_block(const uint32_t *hdr32, const char *
         wave_sync();
     }
     KVC_TICK(6);
-    const uint32_t sb = hdr32[kMinMaxBytesV / 4 + lane];
-    const uint32_t start = wave_excl_scan((sb & 0xffffu) + (sb >> 16), lane);
+    // lane = channels lane (slice a) and 64 + lane (slice b), so that a result tile of 32 channels is one slice of 32
+    // neighbouring lanes; slice s starts where the bits of slices 0 .. s-1 end
+    const uint16_t *bits16 = reinterpret_cast<const uint16_t *>(hdr32 + kMinMaxBytesV / 4);
+    const uint32_t abits = bits16[lane], bbits = bits16[kSliceLen + lane];
+    const uint32_t start_a = wave_excl_scan(abits, lane);
+    const uint32_t start_b = (uint32_t)__builtin_amdgcn_readlane((int)(start_a + abits), 63) + wave_excl_scan(bbits, lane);
     const uint32_t *wm1 = hdr32 + kHdrBytesV / 4 - 1;
     Quad qd;
-    qd.open(wm1, start, sb & 0xffffu, sb >> 16);
-    // lane = channels 2*lane and 2*lane+1; channel n sits in tile row (n & 1) * 64 + n / 2, 32 bytes per row
+    qd.open2(wm1, start_a, abits, start_b, bbits);
     constexpr bool kBoth = tile_halves_at_once(G) == 2;
-    uint8_t *row_a = tile + lane * kTileRowV, *row_b = tile + (kSliceLen + lane) * kTileRowV;
-    v16i d[4];
-    // row bytes 0..15 | 16..31 of half h hold tokens 16h.. | 48-16h..
-    auto products = [&](int half, const uint8_t *t0) {
-#pragma unroll
-        for (int ks = 0; ks < 2; ks++) {
-            const int kk = half == 0 ? (ks == 0 ? 0 : 3) : (ks == 0 ? 1 : 2);
-#pragma unroll
-            for (int ct = 0; ct < 4; ct++) {
-                const int n = 32 * ct + x, r = (n & 1) * kSliceLen + (n >> 1);
-                d[ct] = __builtin_amdgcn_mfma_i32_32x32x16_i8(a[kk], lds_pair(t0 + r * kTileRowV + 16 * ks + 8 * hv), d[ct], 0,
-                                                              0, 0);
-            }
-        }
+    v16i d[4];  // result tiles: channels 0..31, 32..63 (slice a), 64..95, 96..127 (slice b)
+    ChainSyms syms;
+    SliceWords pw;
+    // one step of 16 tokens of both slices
+    auto products = [&](int ks) {
+        long t0, t1;
+        step_operands(pw.a[4 * ks], pw.a[4 * ks + 1], pw.a[4 * ks + 2], pw.a[4 * ks + 3], t0, t1);
+        d[0] = __builtin_amdgcn_mfma_i32_32x32x16_i8(a[ks], t0, d[0], 0, 0, 0);
+        d[1] = __builtin_amdgcn_mfma_i32_32x32x16_i8(a[ks], t1, d[1], 0, 0, 0);
+        step_operands(pw.b[4 * ks], pw.b[4 * ks + 1], pw.b[4 * ks + 2], pw.b[4 * ks + 3], t0, t1);
+        d[2] = __builtin_amdgcn_mfma_i32_32x32x16_i8(a[ks], t0, d[2], 0, 0, 0);
+        d[3] = __builtin_amdgcn_mfma_i32_32x32x16_i8(a[ks], t1, d[3], 0, 0, 0);
     };
     auto clear = [&] {
 #pragma unroll
@@ -684,33 +694,32 @@ __device__ __forceinline__ void v_tile_block(const uint32_t *hdr32, const char *
             for (int i = 0; i < HL; i++) ts.acc[i][ct] = fmaf(inv, v[i], ts.acc[i][ct]);
         }
     };
-    ChainSyms syms;
     constexpr int kP = tile_first_span(NS);
     if constexpr (kBoth) {
-        decode_span<NS, 0, kHalf, 0, 8>(qd, wm1, lut, mask2, syms, row_a, row_b, kTileBytes);
+        decode_span<NS, 0, kHalf>(qd, wm1, lut, mask2, syms, pw);
         KVC_TICK(7);
         wave_sync();
         record_done();
         clear();
-        products(0, tile);
-        products(1, tile + kTileBytes);
+#pragma unroll
+        for (int ks = 0; ks < 4; ks++) products(ks);
         KVC_TICK(8);
         join();
-        wave_sync();
     } else {
-#pragma unroll
-        for (int half = 0; half < 2; half++) {
-            if (half == 0) decode_span<NS, 0, kP, 0, 4>(qd, wm1, lut, mask2, syms, row_a, row_b, 0);
-            else decode_span<NS, kP, kHalf, 4, 8>(qd, wm1, lut, mask2, syms, row_a, row_b, 0);
-            wave_sync();
-            if (half == 0) KVC_TICK(7);
-            if (half == 1) record_done();
-            clear();
-            products(half, tile);
-            join();
-            wave_sync();
-            if (half == 0) KVC_TICK(8);
-        }
+        decode_span<NS, 0, kP>(qd, wm1, lut, mask2, syms, pw);
+        KVC_TICK(7);
+        clear();
+        products(0);
+        products(3);
+        join();
+        KVC_TICK(8);
+        decode_span<NS, kP, kHalf>(qd, wm1, lut, mask2, syms, pw);
+        wave_sync();
+        record_done();
+        clear();
+        products(1);
+        products(2);
+        join();
     }
     KVC_TICK(9);
 }
@@ -969,7 +978,7 @@ __global__ __launch_bounds__(kThreads, WavesPerSimd<G>::value) void fused_attn_k
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     uint8_t *stage = smem + (size_t)wave * a.stage_bytes;
     constexpr int kWeightBytes = (int)fused_weight_bytes(G, LB);
-    static_assert(!kTile || kWeightBytes == kTileBytes * tile_halves_at_once(G), "tile area");
+    static_assert(!kTile || kWeightBytes == kTileBytes, "tile area");
     float *wts = reinterpret_cast<float *>(smem + (size_t)kWaves * a.stage_bytes + (size_t)wave * kWeightBytes);
     const char *lutK = reinterpret_cast<const char *>(&lut_s[0][0]);
     const char *lutV = reinterpret_cast<const char *>(&lut_s[1][0]);

@@ -182,6 +182,13 @@ struct Quad {
         bu.open(wm1, a0 + abits);
         bd.open(wm1, a0 + abits + bbits);
     }
+    // the same for two slices that do not follow each other in the record
+    __device__ __forceinline__ void open2(const uint32_t *wm1, uint32_t a0, uint32_t abits, uint32_t b0, uint32_t bbits) {
+        au.open(wm1, a0);
+        ad.open(wm1, a0 + abits);
+        bu.open(wm1, b0);
+        bd.open(wm1, b0 + bbits);
+    }
     template <int CNT>
     __device__ __forceinline__ void step(const uint32_t *wm1, const char *lut, uint32_t mask2, uint32_t (&fau)[CNT],
                                          uint32_t (&fad)[CNT], uint32_t (&fbu)[CNT], uint32_t (&fbd)[CNT]) {

@@ -78,14 +78,12 @@ constexpr int kCUs = 256;  // compute units of the MI355X
 constexpr int kXCDs = 8;   // accelerator dies, each with its own L2; workgroups are dealt to them round-robin
 // Groups of 4 and 8 query heads: a wave decodes a block into an LDS tile of bytes and multiplies the tile with the
 // weights of all heads on int8 MFMA.
-// The tile holds half a block at a time (16 symbols of each of the 4 x 64 decode chains):
-constexpr int kTileRowK = 64 + 4;            // bytes per token row of a K half tile (one spare word: no bank conflicts)
-constexpr int kTileRowV = 32 + 4;            // bytes per channel row of a V half tile
-constexpr int kTileBytes = kD * kTileRowV;   // 4608; also holds the A operand while it is being laid out
-static_assert(kBT * kTileRowK <= kTileBytes, "K tile fits");
-// Groups of 4 multiply after every half (three waves per SIMD fit); groups of 8, whose lanes carry twice the heads
-// through every recombination of a result tile, decode both halves into two such tiles and multiply once per block
-// (two waves per SIMD).
+// A wave's LDS area next to its staging area: the A operand (32 rows of 128 + 4 bytes) while it is laid out, and the
+// running state when it changes layout after the last block.
+constexpr int kTileBytes = 4352;
+// Groups of 4 multiply after every half of a block (16 symbols of every decode chain; three waves per SIMD fit);
+// groups of 8, whose lanes carry twice the heads through every recombination of a result tile, decode the whole block
+// and multiply once (two waves per SIMD).
 constexpr int tile_halves_at_once(int G) { return G >= 8 ? 2 : 1; }
 // Workgroups (of 4 waves) of the fused kernel that are resident per CU = its waves per SIMD: groups of 4 and 8 query
 // heads trade occupancy for registers and for the LDS tiles.
@@ -101,7 +99,7 @@ constexpr int kLdsBytesPerCU = 160 * 1024;
 // Bytes of one wave's LDS area next to its staging area.  Groups of 1 and 2 heads: fp32 weights [128][G].  Groups of
 // 4 and 8: the tile(s) of decoded symbols.
 constexpr size_t fused_weight_bytes(int G, int /*table_bits*/) {
-    return G >= 4 ? (size_t)kTileBytes * tile_halves_at_once(G) : (size_t)G * kD * 4;
+    return G >= 4 ? (size_t)kTileBytes : (size_t)G * kD * 4;
 }
 // LDS of one fused-kernel workgroup apart from the per-wave staging areas: two decode tables of 16-bit entries, the
 // query rows and the per-wave areas above.
