@@ -28,13 +28,13 @@ VALU_INSTR_PER_SYMBOL = 7.35  # rocprofv3 SQ_INSTS_VALU / decoded wave-symbols (
 # two of them per symbol (the byte-to-float conversion and the FMA with the DPP quad broadcast) issue at half rate
 # (paper_2509_00579_amd/probes/valu_issue.hip: 4 cycles per wave64 instruction instead of 2): 9.35 issue slots
 VALU_SLOTS_PER_SYMBOL = VALU_INSTR_PER_SYMBOL + 2.0
-# Groups of 4 and 8 query heads (tile path): rocprofv3 SQ_INSTS_VALU per decoded wave-symbol (7.98 and 9.28,
-# profiles/fused_attn_kernel_c2.md); in the compiled decode loop 735 of 1956 and 891 of 2342 vector instructions have
+# Groups of 4 and 8 query heads (tile path): rocprofv3 SQ_INSTS_VALU per decoded wave-symbol (8.10 and 9.29,
+# profiles/fused_attn_kernel_c2.md); in the compiled decode loop 733 of 1968 and 825 of 2210 vector instructions have
 # encodings that issue at half rate and take a second slot.  query heads per KV head -> (instructions, issue slots)
-VALU_PER_SYMBOL_BY_GROUP = {4: (7.98, 7.98 * (1 + 735 / 1956)), 8: (9.28, 9.28 * (1 + 891 / 2342))}
+VALU_PER_SYMBOL_BY_GROUP = {4: (8.10, 8.10 * (1 + 733 / 1968)), 8: (9.29, 9.29 * (1 + 825 / 2210))}
 # share of the busy cycles in which the LDS pipe is active, the busiest unit of the fused kernel (rocprofv3
 # SQ_LDS_IDX_ACTIVE / SQ_BUSY_CU_CYCLES, profiles/): keyed like MEASURED_TRAFFIC
-MEASURED_LDS_BUSY = {("c1", 1e-2, 7): 0.38, ("c2", 1e-2, 7): 0.77, ("c3", 1e-2, 7): 0.69, ("c4", 1e-2, 7): 0.54}
+MEASURED_LDS_BUSY = {("c1", 1e-2, 7): 0.38, ("c2", 1e-2, 7): 0.77, ("c3", 1e-2, 7): 0.63, ("c4", 1e-2, 7): 0.51}
 # HBM bytes per fused-kernel launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by a copy of known size
 # (profiles/); keyed by (workload, rel_eb, max code word); None where not measured.
 MEASURED_TRAFFIC = {("c1", 1e-2, 7): 27.05e6}  # bytes per launch, profiles/fused_attn_kernel_c1.md

@@ -4,16 +4,16 @@
 // of one token with a lookup table -- each slice from both ends, four independent decode chains of 32 symbols per
 // lane -- and accumulates q.k in registers; the wave then updates a running softmax and decodes the V record of the
 // same block, every lane owning two channels (two slices, again four chains) and accumulating p.v in registers.  No
-// decompressed value ever leaves the compute unit (Section 3.3.2): decoded symbols stay in registers for groups of 1
-// and 2 query heads and pass through an LDS tile of quantization codes for groups of 4 and 8.
+// decompressed value ever leaves the registers (Section 3.3.2): groups of 4 and 8 query heads keep the decoded
+// quantization codes packed four to a register and hand them to the matrix cores from there.
 //
 // What differs from the paper's kernel, and why (gfx950):
 //  * lookup-table decode instead of the bit-serial tree walk of Section 3.3.1: all 64 lanes of a wave advance in
 //    symbol lock-step (same trip count for every lane, no divergence), so the dequantization weight of the current
 //    symbol is the same for the whole wave.  For groups of 1 and 2 query heads it reaches the FMA through a DPP quad
 //    broadcast of values fetched from LDS once per four steps, which keeps it off the VALU and nearly off the LDS pipe
-//    that the table lookups load; for groups of 4 and 8 the wave decodes into an LDS tile of bytes and multiplies the
-//    tile with the weights of all heads on int8 MFMA (see "tile path" below).  The table is
+//    that the table lookups load; for groups of 4 and 8 the wave packs the decoded bytes into registers and multiplies
+//    them with the weights of all heads on int8 MFMA (see "tile path" below).  The table is
 //    indexed by as many stream bits as the longest code word of the codebook, and one 32-bit window serves several
 //    symbols (floor(31 / table width)) with no refill test in between;
 //  * the dequantization is folded into the weights: q.k' = sum_c q_c min_c + sum_c (q_c step_c) code_tc, and
@@ -311,14 +311,16 @@ __device__ unsigned long long g_ticks[kTickWaves * kTickSlots];
 
 // ---- groups of 4 and 8 query heads, tile path ---------------------------------------------------------------------
 // With several query heads per KV head the update of the accumulators is a matrix product, (heads x symbols) weights
-// times the decoded block, and the decode itself is the same for all heads.  The wave therefore decodes a block into
-// an LDS tile of bytes -- packing four table entries into a word costs less than one conversion and one FMA per
-// symbol and head -- and then multiplies the whole tile with the folded weights on v_mfma_i32_32x32x16_i8:
-//   * the table holds the symbols biased by -128 (symbol ^ 0x80 read as int8), so a tile word is an MFMA operand as
-//     it is, with no conversion;
-//   * a weight w is scaled by a per-block power of two to an integer W below 2^30 and split into four signed bytes,
+// times the decoded block, and the decode itself is the same for all heads.  The wave therefore only packs the
+// decoded symbols, four table entries to a register -- less work than one conversion and one FMA per symbol and
+// head -- and multiplies them with the folded weights on v_mfma_i32_32x32x16_i8, whose result tiles (32 rows of
+// weights x 32 columns) give the path its name:
+//   * the table holds the symbols biased by -128 (symbol ^ 0x80 read as int8), so a register of packed symbols is an
+//     MFMA operand as it is, with no conversion; the operand wants 32 columns x 16 positions from 64 lanes that hold
+//     one slice each, which one v_permlane32_swap_b32 per register arranges (step_operands);
+//   * a weight w is scaled by a per-block power of two to an integer W below 2^22 and split into three signed bytes,
 //     W = sum_j d_j 256^j; row 4 * head + j of the A operand holds digit j, the products are exact in int32, and the
-//     four digit rows of a head land in the same lane of the result, where they are recombined in fp32;
+//     digit rows of a head land in the same lane of the result, where they are recombined in fp32;
 //   * sum_c W_c (s_c - 128) misses 128 * sum_c W_c, which joins the constant term of the block.
 // Lane l of the result tiles holds column l % 32 (token of a K block, channel of a V block) for the heads
 // l / 32 + 2 i: the running softmax state lives in that layout and is converted to the per-channel layout of the
@@ -468,7 +470,8 @@ __device__ __forceinline__ void join_all(const v16i &d, float (&out)[HL]) {
 constexpr int kARowK = kD + 4, kARowV = kBT + 4;  // bytes per row of the A operand while it is laid out in the tile area
 static_assert(32 * kARowK <= kTileBytes && 32 * kARowV <= kTileBytes, "A operand fits the tile area");
 
-// K block.  hdr32: the record (LDS or global); tile: this wave's tile area; qf: the query rows in LDS.
+// K block.  hdr32: the record (LDS or global); tile: this wave's LDS area for laying out the A operand; qf: the query
+// rows in LDS.
 // Updates the softmax state and leaves the softmax numerators of tokens l%32 and 32 + l%32 in p.
 // record_done() is called once the record has been read for the last time, before the last products: the place to
 // request the next record, whose loads then travel while few registers are live.
@@ -968,7 +971,7 @@ template <int G> struct WavesPerSimd { static constexpr int value = fused_wgs_pe
 // serves NS = floor(kWindowBits / LB) symbols.
 template <int G, int LB>
 __global__ __launch_bounds__(kThreads, WavesPerSimd<G>::value) void fused_attn_kernel(FusedArgs a) {
-    constexpr bool kTile = G >= kTileMinG;  // decode into an LDS tile, int8 MFMA over the tile
+    constexpr bool kTile = G >= kTileMinG;  // packed symbols in registers, int8 MFMA
     constexpr int NS = kWindowBits / LB;
     __shared__ __attribute__((aligned(16))) uint16_t lut_s[2][1 << LB];
     __shared__ __attribute__((aligned(16))) float qf[G * kD];
@@ -1016,7 +1019,7 @@ __global__ __launch_bounds__(kThreads, WavesPerSimd<G>::value) void fused_attn_k
         const int n16 = max(1, (2 << g.lut_bits[t]) / 16);
         for (int i = tid; i < n16; i += kThreads) {
             uint4 v = src[i];
-            if constexpr (kTile) {  // the tile holds symbol - 128 as int8
+            if constexpr (kTile) {  // the MFMA operands hold symbol - 128 as int8
                 v.x ^= 0x80008000u; v.y ^= 0x80008000u; v.z ^= 0x80008000u; v.w ^= 0x80008000u;
             }
             dst[i] = v;
