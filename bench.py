@@ -78,7 +78,7 @@ def parse_args():
 def main():
     args = parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        sys.exit("bench.py: this build runs on ONE GPU (the path shards by batch/head without exchange; see DESIGN.md); "
+        sys.exit("bench.py: this build runs on ONE GPU (the path would shard by batch and KV head, with no exchange per step); "
                  "--gpus N with N > 1 is not supported")
 
     import torch
