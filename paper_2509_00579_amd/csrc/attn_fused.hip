@@ -539,7 +539,7 @@ __device__ __forceinline__ void k_tile_block(const uint32_t *hdr32, const char *
     const uint32_t *wm1 = hdr32 + (kmm + 2 * kSlices) / 4 - 1;
     Quad qd;
     qd.open(wm1, start, sb & 0xffffu, sb >> 16);
-    constexpr bool kBoth = tile_halves_at_once(G) == 2;  // decode the whole block, then multiply once
+    constexpr bool kBoth = tile_halves_at_once(G) == 2;  // one recombination per block instead of one per half
     float sc[HL][2];
     v16i d[2];  // result tiles: tokens 0..31 and 32..63
     ChainSyms syms;
@@ -571,14 +571,17 @@ __device__ __forceinline__ void k_tile_block(const uint32_t *hdr32, const char *
     };
     constexpr int kP = tile_first_span(NS);
     // a half of a block is 16 symbols of every chain: the up chains deliver step h, the down chains step 3 - h
-    if constexpr (kBoth) {
-        decode_span<NS, 0, kHalf>(qd, wm1, lut, mask2, syms, pw);
+    if constexpr (kBoth) {  // the products of the first half run while the second half is decoded; one recombination
+        decode_span<NS, 0, kP>(qd, wm1, lut, mask2, syms, pw);
         KVC_TICK(2);
+        clear();
+        products(0);
+        products(3);
+        decode_span<NS, kP, kHalf>(qd, wm1, lut, mask2, syms, pw);
         wave_sync();
         record_done();
-        clear();
-#pragma unroll
-        for (int ks = 0; ks < 4; ks++) products(ks);
+        products(1);
+        products(2);
         join(true);
     } else {
         decode_span<NS, 0, kP>(qd, wm1, lut, mask2, syms, pw);
@@ -699,13 +702,16 @@ __device__ __forceinline__ void v_tile_block(const uint32_t *hdr32, const char *
     };
     constexpr int kP = tile_first_span(NS);
     if constexpr (kBoth) {
-        decode_span<NS, 0, kHalf>(qd, wm1, lut, mask2, syms, pw);
+        decode_span<NS, 0, kP>(qd, wm1, lut, mask2, syms, pw);
         KVC_TICK(7);
+        clear();
+        products(0);
+        products(3);
+        decode_span<NS, kP, kHalf>(qd, wm1, lut, mask2, syms, pw);
         wave_sync();
         record_done();
-        clear();
-#pragma unroll
-        for (int ks = 0; ks < 4; ks++) products(ks);
+        products(1);
+        products(2);
         KVC_TICK(8);
         join();
     } else {

@@ -81,9 +81,10 @@ constexpr int kXCDs = 8;   // accelerator dies, each with its own L2; workgroups
 // A wave's LDS area next to its staging area: the A operand (32 rows of 128 + 4 bytes) while it is laid out, and the
 // running state when it changes layout after the last block.
 constexpr int kTileBytes = 4352;
-// Groups of 4 multiply after every half of a block (16 symbols of every decode chain; three waves per SIMD fit);
-// groups of 8, whose lanes carry twice the heads through every recombination of a result tile, decode the whole block
-// and multiply once (two waves per SIMD).
+// Both groups multiply after every half of a block (16 symbols of every decode chain), so that the products of the
+// first half run while the second half is decoded.  Groups of 4 recombine the result tiles after each half (few
+// registers: three waves per SIMD fit); groups of 8, whose lanes carry twice the heads through every recombination,
+// keep the integer accumulators across both halves and recombine once (two waves per SIMD).  2 = recombine once.
 constexpr int tile_halves_at_once(int G) { return G >= 8 ? 2 : 1; }
 // Workgroups (of 4 waves) of the fused kernel that are resident per CU = its waves per SIMD: groups of 4 and 8 query
 // heads trade occupancy for registers and for the LDS tiles.
