@@ -571,33 +571,21 @@ __device__ __forceinline__ void k_tile_block(const uint32_t *hdr32, const char *
     };
     constexpr int kP = tile_first_span(NS);
     // a half of a block is 16 symbols of every chain: the up chains deliver step h, the down chains step 3 - h
-    if constexpr (kBoth) {  // the products of the first half run while the second half is decoded; one recombination
-        decode_span<NS, 0, kP>(qd, wm1, lut, mask2, syms, pw);
-        KVC_TICK(2);
-        clear();
-        products(0);
-        products(3);
-        decode_span<NS, kP, kHalf>(qd, wm1, lut, mask2, syms, pw);
-        wave_sync();
-        record_done();
-        products(1);
-        products(2);
-        join(true);
-    } else {
-        decode_span<NS, 0, kP>(qd, wm1, lut, mask2, syms, pw);
-        KVC_TICK(2);
-        clear();
-        products(0);
-        products(3);
-        join(true);
-        decode_span<NS, kP, kHalf>(qd, wm1, lut, mask2, syms, pw);
-        wave_sync();
-        record_done();
-        clear();
-        products(1);
-        products(2);
-        join(false);
-    }
+    // The products of the first half run while the second half is decoded (no fence in between: everything is in
+    // registers).
+    decode_span<NS, 0, kP>(qd, wm1, lut, mask2, syms, pw);
+    KVC_TICK(2);
+    clear();
+    products(0);
+    products(3);
+    if constexpr (!kBoth) join(true);
+    decode_span<NS, kP, kHalf>(qd, wm1, lut, mask2, syms, pw);
+    wave_sync();
+    record_done();
+    if constexpr (!kBoth) clear();
+    products(1);
+    products(2);
+    join(kBoth);
     KVC_TICK(3);
 #pragma unroll
     for (int i = 0; i < HL; i++) {
@@ -701,35 +689,20 @@ __device__ __forceinline__ void v_tile_block(const uint32_t *hdr32, const char *
         }
     };
     constexpr int kP = tile_first_span(NS);
-    if constexpr (kBoth) {
-        decode_span<NS, 0, kP>(qd, wm1, lut, mask2, syms, pw);
-        KVC_TICK(7);
-        clear();
-        products(0);
-        products(3);
-        decode_span<NS, kP, kHalf>(qd, wm1, lut, mask2, syms, pw);
-        wave_sync();
-        record_done();
-        products(1);
-        products(2);
-        KVC_TICK(8);
-        join();
-    } else {
-        decode_span<NS, 0, kP>(qd, wm1, lut, mask2, syms, pw);
-        KVC_TICK(7);
-        clear();
-        products(0);
-        products(3);
-        join();
-        KVC_TICK(8);
-        decode_span<NS, kP, kHalf>(qd, wm1, lut, mask2, syms, pw);
-        wave_sync();
-        record_done();
-        clear();
-        products(1);
-        products(2);
-        join();
-    }
+    decode_span<NS, 0, kP>(qd, wm1, lut, mask2, syms, pw);
+    KVC_TICK(7);
+    clear();
+    products(0);
+    products(3);
+    if constexpr (!kBoth) join();
+    KVC_TICK(8);
+    decode_span<NS, kP, kHalf>(qd, wm1, lut, mask2, syms, pw);
+    wave_sync();
+    record_done();
+    if constexpr (!kBoth) clear();
+    products(1);
+    products(2);
+    join();
     KVC_TICK(9);
 }
 

@@ -84,12 +84,8 @@ def main():
         assert lib.kvcomp_ticks_read(tb, m) == 0
         tk = np.frombuffer(tb, dtype=np.uint64).reshape(-1, 16).astype(np.int64)
         tk = tk[tk[:, 0] > 0]
-        if w.n_q_heads // w.n_kv_heads >= 8:   # both halves of a block are decoded before the products
-            steps = ["K weights", "K decode", "K products", "K softmax", "(staging wait)", "V weights", "V decode",
-                     "V products", "V recombination"]
-        else:                                   # products after every half
-            steps = ["K weights", "K first half", "K second half + products", "K softmax", "(staging wait)", "V weights",
-                     "V first half", "V first products", "V second half + products"]
+        steps = ["K weights", "K first half", "K second half + products", "K softmax", "(staging wait)", "V weights",
+                 "V first half", "V first products", "V second half + products"]
         for k, nm in enumerate(steps):
             dcol = tk[:, k + 1] - tk[:, k]
             print("%-26s median %7.0f  p90 %7.0f cycles" % (nm, np.median(dcol), np.percentile(dcol, 90)))
