@@ -103,8 +103,10 @@ kvcomp_status kvcomp_reset(kvcomp_ctx *ctx, int keep_codebook, void *stream);
  * token; Section 3.1.1, Section 4.2),
  * histogram the codes on the device, build one canonical Huffman codebook for K and one for V on the host and
  * upload the encode table and the decode lookup table.  d_K, d_V: device fp16 [batch, seq, n_kv_heads, 128],
- * read-only.  SYNCHRONISES `stream` (the histogram crosses to the host, as in the paper).
- * Errors: INVALID_ARG (seq < 64 or > max_seq), NONFINITE, HIP. */
+ * read-only.  The cache must be empty (the codebooks are built once per prefill and reused, Section 3; new tables
+ * would invalidate existing records): kvcomp_reset first.  SYNCHRONISES `stream` (the histogram crosses to the host,
+ * as in the paper).
+ * Errors: INVALID_ARG (seq < 64 or > max_seq), STATE (cache not empty), NONFINITE, HIP. */
 kvcomp_status kvcomp_build_codebook(kvcomp_ctx *ctx, const void *d_K, const void *d_V, int seq, void *stream);
 
 /* Store stage for the prompt (Section 3.2.2, Figure 4): quantize and Huffman-encode the oldest blocks of every
@@ -121,7 +123,9 @@ kvcomp_status kvcomp_compress_blocks(kvcomp_ctx *ctx, const void *d_K, const voi
  * [batch, n_kv_heads, 128].  The token is copied into the fp16 buffer; the call that fills the buffer's last slot
  * compresses the buffer's oldest 64 tokens as one block for every (batch, head) with the existing codebooks and
  * appends the records at the arena tail.
- * Stream-ordered, never synchronises.  Errors: STATE (no codebook), CAPACITY (max_seq reached), HIP. */
+ * Stream-ordered, never synchronises.  Errors: STATE (no codebook), CAPACITY (max_seq reached), HIP.  An Inf or NaN
+ * in an appended token is noticed when its block is compressed and reported (NONFINITE) by the next call that
+ * synchronises: kvcomp_get_stats, kvcomp_decompress, kvcomp_compress_blocks, kvcomp_build_codebook. */
 kvcomp_status kvcomp_append_token(kvcomp_ctx *ctx, const void *d_k_new, const void *d_v_new, void *stream);
 
 /* Fetch stage (Section 3.3.2, Figure 1): one decode-attention step over the whole cache.  For every query head:
@@ -142,6 +146,9 @@ kvcomp_status kvcomp_append_attn_decode(kvcomp_ctx *ctx, const void *d_k_new, co
 
 /* ---- metrics, parity and debug exports (these SYNCHRONISE `stream` and copy to HOST buffers) ------------- */
 
+/* Also reports, once, what kernels flagged since the last synchronising call: NONFINITE (an appended token held Inf
+ * or NaN), CAPACITY (a flush found the record arena full and wrote nothing: only a captured flush replayed without
+ * the eager calls in between gets there). */
 kvcomp_status kvcomp_get_stats(kvcomp_ctx *ctx, kvcomp_stats *h_out, void *stream);
 
 /* Quantization codes and unit min/max of the full blocks of d_in (which = KVCOMP_K or KVCOMP_V) without touching the
@@ -167,7 +174,8 @@ kvcomp_status kvcomp_get_residual(kvcomp_ctx *ctx, int which, uint16_t *h_buf, i
  * ((b*seq_stride + t)*n_kv_heads + h)*128 + c, for t < tokens in the cache: blocks reconstructed as
  * fp16(min + float(code)*width) (binary32 multiply and add, one rounding), then the buffered tokens unchanged.
  * d_out: DEVICE, caller-owned, 16-byte aligned, batch*seq_stride*n_kv_heads*128 fp16; seq_stride >= tokens
- * (KVCOMP_ERR_CAPACITY otherwise).  Synchronises the stream once (it reads the largest record size). */
+ * (KVCOMP_ERR_CAPACITY otherwise).  Synchronises the stream once (it reads the largest record size, and reports
+ * the flags described at kvcomp_get_stats). */
 kvcomp_status kvcomp_decompress(kvcomp_ctx *ctx, int which, void *d_out, int seq_stride, void *stream);
 
 /* The same call with the decoder of Section 3.3.1 instead of the table decoder: a branch-free walk of the

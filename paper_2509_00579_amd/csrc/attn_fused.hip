@@ -295,20 +295,6 @@ __device__ __noinline__ void v_block_global(const uint32_t *rec, const char *lut
     v_block<G, NS>(rec, lut, mask2, wts, p, two_eb, lane, st);
 }
 
-// Developer instrumentation of the tile path (-DKVC_TRACE only): the shader clock at points inside a block; every
-// block overwrites the previous one's, so the last block pair of every wave remains.
-#ifdef KVC_TRACE
-constexpr int kTickSlots = 16, kTickWaves = 1 << 15;
-__device__ unsigned long long g_ticks[kTickWaves * kTickSlots];
-#define KVC_TICK(k)                                                                          \
-    do {                                                                                     \
-        const unsigned wv_ = blockIdx.x * 4 + (threadIdx.x >> 6);                            \
-        if ((threadIdx.x & 63) == 0 && wv_ < kTickWaves) g_ticks[wv_ * kTickSlots + (k)] = clock64(); \
-    } while (0)
-#else
-#define KVC_TICK(k) do { } while (0)
-#endif
-
 // ---- groups of 4 and 8 query heads, tile path ---------------------------------------------------------------------
 // With several query heads per KV head the update of the accumulators is a matrix product, (heads x symbols) weights
 // times the decoded block, and the decode itself is the same for all heads.  The wave therefore only packs the
@@ -486,7 +472,6 @@ __device__ __forceinline__ void k_tile_block(const uint32_t *hdr32, const char *
     const int x = lane & 31, hv = lane >> 5;
     const bool upper = hv != 0;
     const bool per_channel = kmm == kMinMaxBytesK;
-    KVC_TICK(0);
     // the A operand: folded weights q_c * step_c as integers, heads l/32 + 2i, channels 4 (l%32) .. +3
     float cst[HL], inv;
     long a[8];
@@ -513,7 +498,7 @@ __device__ __forceinline__ void k_tile_block(const uint32_t *hdr32, const char *
             float wsum = 0.f, qm = 0.f;
 #pragma unroll
             for (int c = 0; c < 4; c++) {
-                const int W = (int)(qa[i][c] * stp[c] * f);
+                const int W = __float2int_rn(qa[i][c] * stp[c] * f);  // |W| <= 2^22
                 wsum += (float)W;
                 qm = fmaf(qa[i][c], mn[c], qm);
                 dg[c] = signed_digits(W);
@@ -533,7 +518,6 @@ __device__ __forceinline__ void k_tile_block(const uint32_t *hdr32, const char *
         }
         wave_sync();
     }
-    KVC_TICK(1);
     const uint32_t sb = hdr32[kmm / 4 + lane];  // bit counts of slices 2*lane and 2*lane+1
     const uint32_t start = wave_excl_scan((sb & 0xffffu) + (sb >> 16), lane);
     const uint32_t *wm1 = hdr32 + (kmm + 2 * kSlices) / 4 - 1;
@@ -574,7 +558,6 @@ __device__ __forceinline__ void k_tile_block(const uint32_t *hdr32, const char *
     // The products of the first half run while the second half is decoded (no fence in between: everything is in
     // registers).
     decode_span<NS, 0, kP>(qd, wm1, lut, mask2, syms, pw);
-    KVC_TICK(2);
     clear();
     products(0);
     products(3);
@@ -586,7 +569,6 @@ __device__ __forceinline__ void k_tile_block(const uint32_t *hdr32, const char *
     products(1);
     products(2);
     join(kBoth);
-    KVC_TICK(3);
 #pragma unroll
     for (int i = 0; i < HL; i++) {
         sc[i][0] = scale * fmaf(inv, sc[i][0], cst[i]);
@@ -601,7 +583,6 @@ __device__ __forceinline__ void k_tile_block(const uint32_t *hdr32, const char *
         for (int c = 0; c < 4; c++) ts.acc[i][c] *= alpha;
         ts.m[i] = mnew;
     }
-    KVC_TICK(4);
 }
 
 // V block.  p: softmax numerators of tokens l%32 and 32 + l%32 for this lane's heads.
@@ -612,7 +593,6 @@ __device__ __forceinline__ void v_tile_block(const uint32_t *hdr32, const char *
     constexpr int HL = G / 2;
     asm volatile("" : "+v"(lane));
     const int x = lane & 31, hv = lane >> 5;
-    KVC_TICK(5);
     float inv;
     long a[4];
     {
@@ -633,7 +613,7 @@ __device__ __forceinline__ void v_tile_block(const uint32_t *hdr32, const char *
             float wsum = 0.f;
 #pragma unroll
             for (int t = 0; t < 2; t++) {
-                const int W = (int)(p[i][t] * stp[t] * f);
+                const int W = __float2int_rn(p[i][t] * stp[t] * f);  // |W| <= 2^22
                 wsum += (float)W;
                 const uint32_t dg = signed_digits(W);
 #pragma unroll
@@ -649,7 +629,6 @@ __device__ __forceinline__ void v_tile_block(const uint32_t *hdr32, const char *
         }
         wave_sync();
     }
-    KVC_TICK(6);
     // lane = channels lane (slice a) and 64 + lane (slice b), so that a result tile of 32 channels is one slice of 32
     // neighbouring lanes; slice s starts where the bits of slices 0 .. s-1 end
     const uint16_t *bits16 = reinterpret_cast<const uint16_t *>(hdr32 + kMinMaxBytesV / 4);
@@ -690,12 +669,10 @@ __device__ __forceinline__ void v_tile_block(const uint32_t *hdr32, const char *
     };
     constexpr int kP = tile_first_span(NS);
     decode_span<NS, 0, kP>(qd, wm1, lut, mask2, syms, pw);
-    KVC_TICK(7);
     clear();
     products(0);
     products(3);
     if constexpr (!kBoth) join();
-    KVC_TICK(8);
     decode_span<NS, kP, kHalf>(qd, wm1, lut, mask2, syms, pw);
     wave_sync();
     record_done();
@@ -703,7 +680,6 @@ __device__ __forceinline__ void v_tile_block(const uint32_t *hdr32, const char *
     products(1);
     products(2);
     join();
-    KVC_TICK(9);
 }
 
 // Rare path: a record larger than the LDS staging area (one that an append flushed after the host last looked at the
@@ -866,10 +842,7 @@ __device__ __noinline__ void buffered_tokens(const uint16_t *res, int res_tokens
 
 // A record on its way from global memory to the wave's LDS staging area: the first 8 KiB travel through
 // registers (loads issued early, stored to LDS later), the rest is copied at commit time.
-#ifndef KVC_PREFETCH_REGS
-#define KVC_PREFETCH_REGS 8
-#endif
-constexpr int kPrefetchRegs = KVC_PREFETCH_REGS;
+constexpr int kPrefetchRegs = 8;
 // The part of a record beyond what travels through registers (records above 8 KiB: only with code words near the
 // 12-bit limit).  Out of line so that its address arithmetic is not hoisted into the kernel's register budget.
 __device__ __noinline__ void copy_rest(uint4 *stage, const uint4 *src, uint32_t n16, int lane) {
@@ -919,29 +892,6 @@ struct DirectStage {
     }
 };
 
-// Developer instrumentation, compiled in with -DKVC_TRACE only: wave 0.. of every workgroup records the 100 MHz
-// wall clock at eight points of the kernel (at point 1 instead where it runs: the HW_ID register in the low half and
-// the accelerator die in the high half; at point 5 the shader clock); kvcomp_trace_read() copies the records to the host.
-#ifdef KVC_TRACE
-constexpr int kTraceSlots = 8, kTraceWaves = 1 << 15;
-__device__ unsigned long long g_trace[kTraceWaves * kTraceSlots];
-__device__ __forceinline__ unsigned long long kvc_where() {
-    const unsigned hw = __builtin_amdgcn_s_getreg(4 | (0 << 6) | (31 << 11));   // HW_REG_HW_ID, all 32 bits
-    const unsigned xcc = __builtin_amdgcn_s_getreg(20 | (0 << 6) | (3 << 11));  // HW_REG_XCC_ID, bits 3:0
-    return ((unsigned long long)xcc << 32) | hw;
-}
-#define KVC_MARK(k)                                                                                              \
-    do {                                                                                                         \
-        const unsigned wv = (blockIdx.x * kWaves + wave);                                                        \
-        if (lane == 0 && wv < kTraceWaves)                                                                       \
-            g_trace[wv * kTraceSlots + (k)] = (k) == 1   ? kvc_where()                                           \
-                                              : (k) == 5 ? (unsigned long long)clock64()                         \
-                                                         : (unsigned long long)wall_clock64();                   \
-    } while (0)
-#else
-#define KVC_MARK(k) do { } while (0)
-#endif
-
 // Register budget: 4 waves per SIMD (128 VGPRs) for groups of 1 and 2 query heads, 3 (168) and 2 (256) for groups
 // of 4 and 8.
 template <int G> struct WavesPerSimd { static constexpr int value = fused_wgs_per_cu(G); };
@@ -965,7 +915,6 @@ __global__ __launch_bounds__(kThreads, WavesPerSimd<G>::value) void fused_attn_k
     const char *lutK = reinterpret_cast<const char *>(&lut_s[0][0]);
     const char *lutV = reinterpret_cast<const char *>(&lut_s[1][0]);
 
-    KVC_MARK(0);
     const Geo &g = a.g;
     // Workgroups go to the eight XCDs round-robin by their linear number, and each XCD has its own L2.  Numbering the
     // (batch-head, split) pairs so that an XCD gets a contiguous range of them keeps the splits of one head -- whose
@@ -1019,7 +968,6 @@ __global__ __launch_bounds__(kThreads, WavesPerSimd<G>::value) void fused_attn_k
         else pf.issue(g.payload + (size_t)eK.off16 * 16, eK.size16, lane);
     }
     __syncthreads();
-    KVC_MARK(1);
     // q in registers: channels lane and lane + 64 (the tile path reads its q from LDS once per block)
     constexpr int kQ0 = kTile ? G / 2 : G;
     float qreg[kTile ? 1 : G][2];
@@ -1041,10 +989,6 @@ __global__ __launch_bounds__(kThreads, WavesPerSimd<G>::value) void fused_attn_k
         }
         wave_sync();
     }
-    KVC_MARK(2);
-#ifdef KVC_TRACE
-    bool first = true;
-#endif
     __builtin_amdgcn_s_setprio(3);
     while (j < j1) {
         float score[G], p[G];
@@ -1087,9 +1031,6 @@ __global__ __launch_bounds__(kThreads, WavesPerSimd<G>::value) void fused_attn_k
             for (int gg = 0; gg < G; gg++) score[gg] = s_tmp[gg];
         }
         }
-#ifdef KVC_TRACE
-        if (first) KVC_MARK(3);
-#endif
         if constexpr (!kTile) {
 #pragma unroll
             for (int gg = 0; gg < G; gg++) p[gg] = st.update(gg, score[gg]);
@@ -1133,10 +1074,6 @@ __global__ __launch_bounds__(kThreads, WavesPerSimd<G>::value) void fused_attn_k
             st = st_tmp;
         }
         }
-#ifdef KVC_TRACE
-        if (first) KVC_MARK(4);
-        first = false;
-#endif
         wave_sync();
         if (jn < j1 && eKn.size16 <= stage16) {
             if constexpr (kTile) ds.wait(stage4, lane);
@@ -1158,7 +1095,6 @@ __global__ __launch_bounds__(kThreads, WavesPerSimd<G>::value) void fused_attn_k
         }
     }
 
-    KVC_MARK(5);
     if constexpr (kTile) tile_state_to_soft<G>(ts, reinterpret_cast<float *>(tile), lane, st);
     // the buffered fp16 tokens in units of 16: unit u goes to split n_splits-1 - u % n_splits (the last split is the
     // short one), there to the waves in turn, starting after the wave that took the split's last block
@@ -1214,9 +1150,7 @@ __global__ __launch_bounds__(kThreads, WavesPerSimd<G>::value) void fused_attn_k
             if (c == 0) { store_agent(dst + kD, M); store_agent(dst + kD + 1, L); }
         }
     }
-    KVC_MARK(6);
     if (a.n_splits > 1) finish_splits<G, kThreads>(g.partials, g.counters + bh, row0, a.n_splits, a.out, tid_m);
-    KVC_MARK(7);
 }
 
 template <int G, int LB>
@@ -1279,16 +1213,6 @@ hipError_t launch_fused_attn(const Geo &g, const uint16_t *q, float scale, float
     }
 }
 
-#ifdef KVC_TRACE
-extern "C" int kvcomp_trace_read(unsigned long long *host, size_t n) {
-    if (n > (size_t)kTraceWaves * kTraceSlots) n = (size_t)kTraceWaves * kTraceSlots;
-    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(g_trace), n * sizeof(unsigned long long));
-}
-extern "C" int kvcomp_ticks_read(unsigned long long *host, size_t n) {
-    if (n > (size_t)kTickWaves * kTickSlots) n = (size_t)kTickWaves * kTickSlots;
-    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(g_ticks), n * sizeof(unsigned long long));
-}
-#endif
 
 // ---- statistics (metrics path, not part of the hot loop) --------------------------------------------------------
 // Sums record sizes and code-word bits over all blocks in use by walking the Block Offsets Array and the slice bit

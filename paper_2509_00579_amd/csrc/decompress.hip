@@ -65,8 +65,12 @@ __global__ __launch_bounds__(64 * kDecWaves) void decompress_kernel(DecompArgs a
     const BlockEntry e = g.table[((size_t)which * g.B * g.H + bh) * g.max_blocks + j];
     const uint32_t size16 = __builtin_amdgcn_readfirstlane(e.size16), off16 = __builtin_amdgcn_readfirstlane(e.off16);
     const uint4 *src = reinterpret_cast<const uint4 *>(g.payload + (size_t)off16 * 16);
-    // records larger than the staging area (cannot happen: the host sizes it from the largest record) are skipped
-    if (size16 * 16u + 16u > (uint32_t)a.stage_bytes) return;
+    // a record larger than the staging area (the host sizes it from the largest record, so only a corrupted table gets
+    // here) is not decoded: the fault bit makes the next synchronising call fail
+    if (size16 * 16u + 16u > (uint32_t)a.stage_bytes) {
+        if (lane == 0) atomicOr(&g.ctrl->fault, kFaultStageSmall);
+        return;
+    }
     for (uint32_t i = lane; i < size16; i += 64) reinterpret_cast<uint4 *>(stage)[i] = src[i];
     wave_sync();
     const uint32_t *hdr32 = reinterpret_cast<const uint32_t *>(stage);

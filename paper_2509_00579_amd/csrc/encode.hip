@@ -81,7 +81,26 @@ __global__ __launch_bounds__(kPlaceThreads) void place_kernel(Geo g, int n_blk_p
         const int row = i / n_blk_per_bh, j = i - row * n_blk_per_bh;
         return &g.table[(size_t)row * g.max_blocks + dst_blk0 + j];
     };
-    uint32_t base = g.ctrl->tail16, biggest = 0;
+    // The host only starts a placement that fits the arena.  A replay of a captured flush without the eager calls in
+    // between (which the interface forbids) would advance the tail on every replay: the sizes are therefore summed
+    // first, and a placement that would run past the arena sets a fault bit, points its entries at the arena start
+    // (so that later readers stay in bounds) and leaves the tail where it is; the write pass then writes nothing.
+    unsigned long long need = 0;
+    for (int i = tid; i < n_items; i += kPlaceThreads) need += entry(i)->size16;
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) need += __shfl_xor(need, m);
+    __shared__ unsigned long long need_s[16];
+    if ((tid & 63) == 0) need_s[tid >> 6] = need;
+    __syncthreads();
+    need = 0;
+    for (int w = 0; w < 16; w++) need += need_s[w];
+    const uint32_t tail0 = g.ctrl->tail16;
+    if ((unsigned long long)tail0 + need > (unsigned long long)g.payload_cap16) {
+        for (int i = tid; i < n_items; i += kPlaceThreads) entry(i)->off16 = 0;
+        if (tid == 0) atomicOr(&g.ctrl->fault, kFaultArenaFull);
+        return;
+    }
+    uint32_t base = tail0, biggest = 0;
     for (int c0 = 0; c0 < n_items; c0 += kPlaceChunk) {
 #pragma unroll
         for (int k = 0; k < kPlacePerThread; k++) {
@@ -143,6 +162,7 @@ __global__ __launch_bounds__(256) void write_kernel(Geo g, const uint16_t *__res
     __shared__ __attribute__((aligned(16))) uint32_t rec[(kMaxRecordBytes + 15) / 16 * 4];
     const int tid = threadIdx.x, blk = blockIdx.x;
     const int bh = blk / n_blk_per_bh, j = blk - bh * n_blk_per_bh;
+    if (g.ctrl->fault & kFaultArenaFull) return;  // the placement found no room (uniform over the workgroup)
     enc[tid] = g.enc[WHICH * 512 + tid];
     enc[256 + tid] = g.enc[WHICH * 512 + 256 + tid];
     for (int i = tid; i < (int)(sizeof(rec) / 4); i += 256) rec[i] = 0;
@@ -216,6 +236,7 @@ __global__ __launch_bounds__(256) void write_kernel(Geo g, const uint16_t *__res
     const uint32_t n16 = record_size16(R::hdr_bytes(g), total);  // equals e.size16 by construction
     uint4 *dst = reinterpret_cast<uint4 *>(g.payload + (size_t)e.off16 * 16);
     const uint4 *src = reinterpret_cast<const uint4 *>(rec);
+    if ((unsigned long long)e.off16 + e.size16 > (unsigned long long)g.payload_cap16) return;
     for (uint32_t i = tid; i < n16 && i < e.size16; i += 256) dst[i] = src[i];
 }
 

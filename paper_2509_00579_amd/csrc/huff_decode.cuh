@@ -71,16 +71,9 @@ __device__ __forceinline__ uint32_t wave_excl_scan(uint32_t v, int lane) {
 //   wm1   payload words, pointer moved back by one word: payload bit x is bit x + 32 of wm1
 // A window is 32 stream bits whose bit 0 is a don't-care and whose bits 1.. are the next unread bits in reading
 // order, i.e. the stream already scaled to the byte offset of a 16-bit table entry.
-// KVC_READER selects how a chain fetches its stream bits (build-time, for measurements):
-//   1  look-ahead: {hi,lo} words in registers, next word fetched one window ahead (4-byte aligned LDS reads)
-//   0  every window re-reads its two words (one 8-byte LDS read): less bookkeeping, measured ~10 % slower
-// (Unaligned 4-byte LDS reads at byte granularity were also tried: correct on gfx950 but 2.4x slower.)
-#ifndef KVC_READER
-#define KVC_READER 1
-#endif
+// (Unaligned 4-byte LDS reads at byte granularity, and re-reading both words of every window, were tried: slower.)
 constexpr int kJunkBits = 1;                  // low window bits that are not stream bits
 constexpr int kWindowBits = 32 - kJunkBits;  // stream bits per window
-#if KVC_READER == 1
 // Readers keep a 64-bit piece {hi,lo} of the stream in registers plus the next word in reading direction, fetched
 // one window ahead: one 4-byte LDS read per window, off the critical path (only table lookups depend on each other).
 struct UpReader {
@@ -126,27 +119,6 @@ struct DownReader {
         pv = wm1[(int)nidx - 1];
     }
 };
-#else
-// Every window re-reads its two words from LDS (one ds_read2_b32): least bookkeeping, more LDS traffic.
-struct UpReader {
-    uint32_t P;  // (next unread payload bit) + 32 - kJunkBits = window start in wm1 bit coordinates
-    __device__ __forceinline__ void open(const uint32_t *, uint32_t first_bit) { P = first_bit + (uint32_t)(32 - kJunkBits); }
-    __device__ __forceinline__ uint32_t window(const uint32_t *wm1) const {
-        const uint32_t idx = P >> 5;
-        return __builtin_amdgcn_alignbit(wm1[idx + 1], wm1[idx], P);
-    }
-    __device__ __forceinline__ void advance(const uint32_t *, uint32_t used) { P += used; }
-};
-struct DownReader {
-    uint32_t P;  // (one past the next unread payload bit) + kJunkBits
-    __device__ __forceinline__ void open(const uint32_t *, uint32_t end_bit) { P = end_bit + (uint32_t)kJunkBits; }
-    __device__ __forceinline__ uint32_t window(const uint32_t *wm1) const {
-        const uint32_t idx = P >> 5;
-        return __builtin_bitreverse32(__builtin_amdgcn_alignbit(wm1[idx + 1], wm1[idx], P));
-    }
-    __device__ __forceinline__ void advance(const uint32_t *, uint32_t used) { P -= used; }
-};
-#endif
 
 // Decode CNT symbols from a window.  lut: 16-bit entries (symbol << 8) | code length, indexed by the next `bits`
 // stream bits; mask2 = ((1 << bits) - 1) << 1.  CNT * (longest code word) <= kWindowBits is the caller's promise.

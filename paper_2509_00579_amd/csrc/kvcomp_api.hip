@@ -2,6 +2,7 @@
 // Huffman codebook (the paper builds the codebooks on the CPU from a GPU histogram, Section 3).
 #include <algorithm>
 #include <cstdarg>
+#include <cstddef>
 #include <cstdio>
 #include <cstring>
 #include <new>
@@ -9,9 +10,11 @@
 #include <vector>
 
 #include "../../include/kvcomp.h"
+#include "host_logic.h"
 #include "kvcomp_internal.h"
 
 using namespace kvc;
+using namespace kvc::host;
 
 namespace {
 
@@ -30,135 +33,6 @@ kvcomp_status fail(kvcomp_status st, const char *fmt, ...) {
         hipError_t e_ = (expr);                                                                    \
         if (e_ != hipSuccess) return fail(KVCOMP_ERR_HIP, "%s: %s", #expr, hipGetErrorString(e_)); \
     } while (0)
-
-size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
-
-int n_sym_for(float rel_eb) {
-    if (!(rel_eb > 0.0f) || rel_eb > 0.5f) return -1;
-    const float two_eb = 2.0f * rel_eb;
-    const int n = (int)__builtin_rintf(1.0f / two_eb) + 1;
-    return (n < 2 || n > 256) ? -1 : n;
-}
-
-bool valid_cfg(const kvcomp_config *c) {
-    if (!c) return false;
-    if (c->batch < 1 || c->n_kv_heads < 1 || c->n_q_heads < c->n_kv_heads) return false;
-    if (c->n_q_heads % c->n_kv_heads) return false;
-    const int G = c->n_q_heads / c->n_kv_heads;
-    if (G != 1 && G != 2 && G != 4 && G != 8) return false;
-    if (c->head_dim != kD || c->block_tokens != kBT) return false;
-    if (c->max_seq < 1) return false;
-    if (n_sym_for(c->rel_eb_k) < 0 || n_sym_for(c->rel_eb_v) < 0) return false;
-    if (c->k_mode != 0 && c->k_mode != 1) return false;
-    if (c->max_code_len != 0) {  // every level needs a code word: 2^max_code_len >= number of levels
-        const int levels = std::max(n_sym_for(c->rel_eb_k), n_sym_for(c->rel_eb_v));
-        if (c->max_code_len > kLutBits || (1 << c->max_code_len) < levels) return false;
-    }
-    if ((long long)c->batch * c->n_kv_heads * ((long long)c->max_seq / kBT + 1) > (1ll << 28)) return false;
-    if (c->buffer_tokens != 0 && (c->buffer_tokens < kBT || c->buffer_tokens % kBT || c->buffer_tokens > kMaxBufferTokens))
-        return false;
-    return true;
-}
-
-// capacity of the fp16 buffer of new tokens (Section 3.2.1; the maximum buffer size of Section 4.2)
-int buffer_tokens(const kvcomp_config &c) { return c.buffer_tokens ? c.buffer_tokens : kBT; }
-
-// header of a K record: {min,max} pairs (one per channel, or one for the block padded to 16 bytes) + slice bit counts
-int k_minmax_bytes(const kvcomp_config &c) { return c.k_mode == 1 ? 16 : kMinMaxBytesK; }
-int k_header_bytes(const kvcomp_config &c) { return k_minmax_bytes(c) + 2 * kSlices; }
-
-int code_len_limit(const kvcomp_config &c) { return c.max_code_len ? c.max_code_len : kLutBits; }
-
-struct Layout {
-    size_t ctrl, hist, enc, lut, tree, counters, table, res, partials, payload, total;
-    size_t payload_cap16;
-    int max_blocks;
-};
-
-Layout make_layout(const kvcomp_config &c) {
-    Layout L;
-    const size_t BH = (size_t)c.batch * c.n_kv_heads;
-    L.max_blocks = c.max_seq / kBT;
-    const int lim = code_len_limit(c);
-    const size_t worst_k = align_up((size_t)k_header_bytes(c) + (size_t)kTile * lim / 8, 16);
-    const size_t worst_v = align_up(kHdrBytesV + (size_t)kTile * lim / 8, 16);
-    size_t at = 0;
-    L.ctrl = at; at += 256;
-    L.hist = at; at += 2 * 256 * 4;
-    L.enc = at; at += 4 * 256 * 4;
-    L.lut = at; at += 2 * kLutSize * 2;
-    L.tree = at; at += 2 * 256 * 2 * 2;
-    L.counters = at; at += align_up(BH * 4, 256);
-    L.table = at; at += align_up(2 * BH * (size_t)std::max(L.max_blocks, 1) * sizeof(BlockEntry), 256);
-    L.res = at; at += align_up(2 * (size_t)c.batch * buffer_tokens(c) * c.n_kv_heads * kD * 2, 256);
-    L.partials = at; at += align_up((size_t)c.batch * c.n_q_heads * kMaxSplits * kPartialStride * 4, 256);
-    L.payload = at;
-    const size_t pay = BH * (size_t)L.max_blocks * (worst_k + worst_v) + 256;
-    L.payload_cap16 = pay / 16;
-    at += align_up(pay, 256);
-    L.total = at;
-    return L;
-}
-
-// ---- Huffman codebook (Section 3.1.2), canonical and length-limited --------------------------------------------
-// Two-queue construction over leaves sorted by (count, symbol); on equal weight a leaf is taken before a merged
-// node and merged nodes leave in creation order, which fixes the code lengths uniquely.
-void huffman_lengths(const std::vector<uint64_t> &f, std::vector<int> &len) {
-    const int n = (int)f.size();
-    std::vector<int> order(n);
-    std::iota(order.begin(), order.end(), 0);
-    std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return f[a] < f[b]; });
-    struct Node { uint64_t w; int kid[2]; };
-    std::vector<Node> nodes;
-    nodes.reserve(2 * n);
-    for (int i = 0; i < n; i++) nodes.push_back({f[order[i]], {-1, -1}});
-    int leaf = 0, ihead = n;
-    auto take = [&]() {
-        const bool has_leaf = leaf < n, has_int = ihead < (int)nodes.size();
-        if (has_leaf && (!has_int || nodes[leaf].w <= nodes[ihead].w)) return leaf++;
-        return ihead++;
-    };
-    for (int k = 0; k < n - 1; k++) {
-        const int a = take(), b = take();
-        nodes.push_back({nodes[a].w + nodes[b].w, {a, b}});
-    }
-    std::vector<int> depth(nodes.size(), 0);
-    for (int i = (int)nodes.size() - 1; i >= n; i--) {
-        depth[nodes[i].kid[0]] = depth[i] + 1;
-        depth[nodes[i].kid[1]] = depth[i] + 1;
-    }
-    len.assign(n, 0);
-    for (int i = 0; i < n; i++) len[order[i]] = depth[i];
-}
-
-void build_codebook_host(const uint32_t *hist, int n_sym, int max_len, uint8_t *len_out, uint32_t *code_out) {
-    std::vector<uint64_t> f(n_sym);
-    for (int s = 0; s < n_sym; s++) f[s] = hist[s] ? hist[s] : 1;  // later blocks reuse the codebook: no level unencodable
-    std::vector<int> len;
-    for (;;) {
-        huffman_lengths(f, len);
-        if (*std::max_element(len.begin(), len.end()) <= max_len) break;
-        for (auto &v : f) v = std::max<uint64_t>(1, (v + 1) >> 1);
-    }
-    std::memset(len_out, 0, 256);
-    std::memset(code_out, 0, 256 * sizeof(uint32_t));
-    std::vector<int> by(n_sym);
-    std::iota(by.begin(), by.end(), 0);
-    std::stable_sort(by.begin(), by.end(), [&](int a, int b) { return len[a] < len[b]; });
-    uint32_t code = 0;
-    for (int i = 0; i < n_sym; i++) {
-        const int s = by[i];
-        if (i) code = (code + 1) << (len[s] - len[by[i - 1]]);
-        len_out[s] = (uint8_t)len[s];
-        code_out[s] = code;
-    }
-}
-
-uint32_t reverse_bits(uint32_t v, int n) {
-    uint32_t r = 0;
-    for (int i = 0; i < n; i++) r |= ((v >> i) & 1u) << (n - 1 - i);
-    return r;
-}
 
 }  // namespace
 
@@ -208,6 +82,21 @@ kvcomp_status fold_profile(kvcomp_ctx *ctx) {
 }
 
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// After read_ctrl: what the kernels flagged since the last synchronising call (a non-finite input value, e.g. in a
+// token that an append flushed; a kernel that refused work).  Clears the flags on the device.
+kvcomp_status check_flags(kvcomp_ctx *ctx, hipStream_t s) {
+    const uint32_t nonfinite = ctx->h_ctrl->nonfinite, fault = ctx->h_ctrl->fault;
+    if (!nonfinite && !fault) return KVCOMP_OK;
+    static_assert(offsetof(Ctrl, nonfinite) == 8 && offsetof(Ctrl, fault) == 12, "the two flags are neighbours");
+    HIP_TRY(hipMemsetAsync(&ctx->geo.ctrl->nonfinite, 0, 2 * sizeof(uint32_t), s));
+    HIP_TRY(hipStreamSynchronize(s));
+    if (nonfinite) return fail(KVCOMP_ERR_NONFINITE, "an input held Inf or NaN");
+    if (fault & kFaultArenaFull)
+        return fail(KVCOMP_ERR_CAPACITY, "a flush found the record arena full (a captured flush replayed without the "
+                                         "eager calls in between?): its blocks were not written");
+    return fail(KVCOMP_ERR_STATE, "the decompressor met a record larger than its staging area: that block was skipped");
+}
 
 }  // namespace
 
@@ -267,6 +156,7 @@ kvcomp_status kvcomp_create(const kvcomp_config *cfg, void *d_arena, size_t aren
     g.res_tokens = buffer_tokens(*cfg);
     g.partials = reinterpret_cast<float *>(c->arena + L.partials);
     g.payload = c->arena + L.payload;
+    g.payload_cap16 = (uint32_t)L.payload_cap16;
     void *pinned = nullptr;
     const size_t pin_bytes = 256 + 2 * 256 * 4 + 4 * 256 * 4 + 2 * kLutSize * 2 + 2 * 256 * 2 * 2;
     hipError_t e = hipHostMalloc(&pinned, pin_bytes, hipHostMallocDefault);
@@ -314,6 +204,9 @@ kvcomp_status kvcomp_build_codebook(kvcomp_ctx *ctx, const void *d_K, const void
     if (!aligned16(d_K) || !aligned16(d_V)) return fail(KVCOMP_ERR_INVALID_ARG, "K/V must be 16-byte aligned");
     if (seq < kBT || seq > ctx->cfg.max_seq)
         return fail(KVCOMP_ERR_INVALID_ARG, "seq %d outside [64, max_seq=%d]", seq, ctx->cfg.max_seq);
+    // the codebooks are built once, at prefill, and reused (Section 3): new tables under existing records would make
+    // every one of them decode to garbage
+    if (ctx->n_blocks || ctx->n_res) return fail(KVCOMP_ERR_STATE, "cache is not empty: kvcomp_reset first");
     const long long symbols = (long long)ctx->geo.B * ctx->geo.H * (seq / kBT) * kTile;
     if (symbols >= (1ll << 32)) return fail(KVCOMP_ERR_INVALID_ARG, "more than 2^32 symbols per tensor");
     hipStream_t s = static_cast<hipStream_t>(stream);
@@ -325,47 +218,14 @@ kvcomp_status kvcomp_build_codebook(kvcomp_ctx *ctx, const void *d_K, const void
     static_assert(sizeof(Ctrl) <= 256, "control words fill the first 256 bytes");
     HIP_TRY(hipMemcpyAsync(ctx->h_ctrl, g.ctrl, 256 + 2 * 256 * 4, hipMemcpyDeviceToHost, s));
     HIP_TRY(hipStreamSynchronize(s));
-    if (ctx->h_ctrl->nonfinite) {
-        (void)hipMemsetAsync(&g.ctrl->nonfinite, 0, sizeof(uint32_t), s);
-        (void)hipStreamSynchronize(s);
-        return fail(KVCOMP_ERR_NONFINITE, "input holds Inf or NaN");
+    {
+        kvcomp_status st = check_flags(ctx, s);
+        if (st) return st;
     }
     for (int w = 0; w < 2; w++) {
         build_codebook_host(ctx->h_hist + 256 * w, g.n_sym[w], code_len_limit(ctx->cfg), ctx->len[w], ctx->code[w]);
-        uint32_t *enc = ctx->h_enc + 512 * w;  // [0..256): written first-bit-first, [256..512): last-bit-first
-        uint16_t *lut = ctx->h_lut + kLutSize * w;
-        std::memset(enc, 0, 512 * 4);
-        std::memset(lut, 0, kLutSize * 2);
-        // the decode table is indexed by as many stream bits as the longest code word of this codebook
-        const int bits = *std::max_element(ctx->len[w], ctx->len[w] + 256);
-        ctx->geo.lut_bits[w] = bits;
-        for (int sy = 0; sy < 256; sy++) {
-            const int L = ctx->len[w][sy];
-            if (!L) continue;
-            const uint32_t rev = reverse_bits(ctx->code[w][sy], L);  // first stream bit = bit 0 of the index
-            enc[sy] = ((uint32_t)L << 16) | rev;
-            enc[256 + sy] = ((uint32_t)L << 16) | ctx->code[w][sy];
-            for (uint32_t k = 0; k < (1u << (bits - L)); k++) lut[rev | (k << L)] = (uint16_t)((sy << 8) | L);
-        }
-        // the same codebook as an array-based tree (Section 3.3.1), for the bit-serial decoder kept for comparison
-        int16_t *tree = ctx->h_tree + 512 * w;
-        std::memset(tree, 0, 512 * 2);
-        int n_nodes = 1;
-        for (int sy = 0; sy < 256; sy++) {
-            const int L = ctx->len[w][sy];
-            if (!L) continue;
-            int node = 0;
-            for (int i = 0; i < L; i++) {
-                const int bit = (ctx->code[w][sy] >> (L - 1 - i)) & 1;  // code words enter the stream first bit first
-                int16_t &child = tree[node * 2 + bit];
-                if (i == L - 1) {
-                    child = (int16_t)~sy;
-                } else {
-                    if (child == 0) child = (int16_t)n_nodes++;
-                    node = child;
-                }
-            }
-        }
+        ctx->geo.lut_bits[w] = build_tables(ctx->len[w], ctx->code[w], ctx->h_enc + 512 * w, ctx->h_lut + kLutSize * w,
+                                            ctx->h_tree + 512 * w);
     }
     // encode tables, decode tables and trees are neighbours too: one upload
     HIP_TRY(hipMemcpyAsync(g.enc, ctx->h_enc, 4 * 256 * 4 + 2 * kLutSize * 2 + 2 * 256 * 2 * 2, hipMemcpyHostToDevice, s));
@@ -391,9 +251,10 @@ kvcomp_status kvcomp_compress_blocks(kvcomp_ctx *ctx, const void *d_K, const voi
     HIP_TRY(launch_copy_tail(g, K, V, seq, nb * kBT, seq - nb * kBT, s));
     kvcomp_status st = read_ctrl(ctx, s);
     if (st) return st;
-    if (ctx->h_ctrl->nonfinite) {
-        (void)launch_fill_zero(g.ctrl, 256, s);
-        return fail(KVCOMP_ERR_NONFINITE, "input holds Inf or NaN");
+    if (ctx->h_ctrl->nonfinite || ctx->h_ctrl->fault) {
+        st = check_flags(ctx, s);
+        (void)launch_fill_zero(g.ctrl, 256, s);  // nothing of this call stays in the cache
+        return st;
     }
     ctx->n_blocks = nb;
     ctx->n_res = seq - nb * kBT;
@@ -508,6 +369,8 @@ kvcomp_status kvcomp_get_stats(kvcomp_ctx *ctx, kvcomp_stats *o, void *stream) {
     HIP_TRY(hipMemsetAsync(ctx->geo.ctrl->payload_bits, 0, 4 * sizeof(unsigned long long), s));
     HIP_TRY(launch_stats(ctx->geo, ctx->n_blocks, s));
     kvcomp_status st = read_ctrl(ctx, s);
+    if (st) return st;
+    st = check_flags(ctx, s);
     if (st) return st;
     const Ctrl &c = *ctx->h_ctrl;
     const long long BH = (long long)ctx->geo.B * ctx->geo.H;
@@ -628,6 +491,8 @@ static kvcomp_status decompress_impl(kvcomp_ctx *ctx, int which, void *d_out, in
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (ctx->n_blocks) {  // the largest record may have grown through flushes since the last synchronising call
         kvcomp_status st = read_ctrl(ctx, s);
+        if (st) return st;
+        st = check_flags(ctx, s);
         if (st) return st;
         ctx->max_size16 = std::max(ctx->max_size16, ctx->h_ctrl->max_size16);
     }

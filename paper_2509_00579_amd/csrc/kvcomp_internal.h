@@ -4,49 +4,24 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "kvcomp_consts.h"
+
 namespace kvc {
-
-constexpr int kD = 128;        // head_dim
-constexpr int kBT = 64;        // tokens per 2D block
-constexpr int kTile = kD * kBT;  // symbols per block
-constexpr int kLutBits = 12;   // decode table index width = longest code word allowed
-constexpr int kLutSize = 1 << kLutBits;
-constexpr int kMaxBufferTokens = 4096;  // largest fp16 buffer of new tokens per sequence
-
-// Record layout (Section 3.2.2: per-thread bit counts + one contiguous chunk per 2D block):
-//   K: [128 x {min,max} fp16][128 x u16 slice bits][payload words][pad to 16 B]
-//   V: [ 64 x {min,max} fp16][128 x u16 slice bits][payload words][pad to 16 B]
-// Every block has 128 slices of 64 symbols: K slice s = token s/2, channels 64*(s%2)..+63; V slice s = channel s,
-// tokens 0..63.  A decoding lane owns two consecutive slices (K: one token; V: channels 2*lane, 2*lane+1).
-// A slice is written from both ends: symbols 0..31 first-bit-first upwards from its start, symbols 32..63
-// last-bit-first after them, so that reading downwards from the slice end yields symbols 63..32 first-bit-first.
-// Each slice is thus two independent decode chains; its end needs no extra offset (it is the next slice's start).
-constexpr int kSlices = 128;
-constexpr int kSliceLen = 64;
-constexpr int kMinMaxBytesK = 4 * kD;
-constexpr int kMinMaxBytesV = 4 * kBT;
-constexpr int kHdrBytesK = kMinMaxBytesK + 2 * kSlices;   // 768 (channel-wise units; BlockQuant: 16 + 256)
-constexpr int kHdrBytesV = kMinMaxBytesV + 2 * kSlices;   // 512
-constexpr int kMaxPayloadBytes = kTile * kLutBits / 8;  // 12288
-constexpr int kMaxRecordBytes = kHdrBytesK + kMaxPayloadBytes + 16;
-
-// Block Offsets Array entry (Section 3): where the record of a 2D block lives, in 16-byte units from the start of
-// the payload arena, and how long it is.
-struct BlockEntry {
-    uint32_t off16;
-    uint32_t size16;
-};
 
 // Device-side control words, first bytes of the arena.
 struct Ctrl {
     uint32_t tail16;        // first free 16-byte unit of the payload arena
     uint32_t max_size16;    // largest record so far
     uint32_t nonfinite;     // set when an input value was Inf/NaN
-    uint32_t pad;
+    uint32_t fault;         // kFault* bits set by kernels that refused work; read and cleared at the synchronising calls
     // filled by the statistics kernel only (kvcomp_get_stats)
     unsigned long long payload_bits[2];
     unsigned long long record16[2];  // sum of record sizes per tensor, 16-byte units
 };
+
+// Ctrl::fault bits
+constexpr uint32_t kFaultArenaFull = 1u;    // a placement would have run past the record arena: nothing was written
+constexpr uint32_t kFaultStageSmall = 2u;   // the stand-alone decompressor met a record larger than its staging area
 
 // Geometry + device pointers, passed by value to kernels.
 struct Geo {
@@ -70,10 +45,9 @@ struct Geo {
     int res_tokens;          // its capacity per sequence = maximum buffer size (Section 4.2), a multiple of 64
     float *partials;         // [B*Hq][max_splits][kPartialStride]
     uint8_t *payload;        // record arena
+    uint32_t payload_cap16;  // its capacity in 16-byte units
 };
 
-constexpr int kPartialStride = kD + 2;  // o[128], m, l
-constexpr int kMaxSplits = 128;
 constexpr int kCUs = 256;  // compute units of the MI355X
 constexpr int kXCDs = 8;   // accelerator dies, each with its own L2; workgroups are dealt to them round-robin
 // Groups of 4 and 8 query heads: a wave decodes a block into an LDS tile of bytes and multiplies the tile with the

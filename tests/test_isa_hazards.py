@@ -4,6 +4,7 @@ The query-weight broadcast of the fused kernel is a DPP modifier on v_fmac_f32, 
 CDNA ISA asks for two wait states between a VALU instruction that writes a VGPR and a DPP instruction that reads
 it; the hardware does not interlock and the compiler's hazard recogniser does not look into inline assembly.  The
 weights come from LDS reads, so no such pair should exist: this test fails if a compiler change ever creates one.
+The walk follows the control flow backwards (fall-through and every branch into a label), not just the text order.
 """
 import re
 
@@ -31,13 +32,60 @@ def asm():
     return B.device_assembly("attn_fused.hip")
 
 
-def test_dpp_fma_source_is_not_written_by_the_two_preceding_valu_instructions(asm):
-    insts = []
+def _parse(asm):
+    """Instructions in program order, the label positions, and for every label the instructions that branch to it."""
+    insts, labels = [], {}
     for line in asm.splitlines():
         line = line.split(";")[0].strip()
-        if not line or line.startswith(".") or line.endswith(":"):
+        if not line or line.startswith("."):
+            if line.endswith(":"):          # local labels look like .LBB0_12:
+                labels[line[:-1]] = len(insts)
+            continue
+        if line.endswith(":"):
+            labels[line[:-1]] = len(insts)
             continue
         insts.append(line)
+    at = {}
+    for lab, pos in labels.items():
+        at.setdefault(pos, []).append(lab)
+    branches = {}
+    for i, ins in enumerate(insts):
+        name = ins.split()[0]
+        if name == "s_branch" or name.startswith("s_cbranch"):
+            branches.setdefault(ins.split()[1], []).append(i)
+    return insts, at, branches
+
+
+def _check_back(insts, at, branches, i, wait, dpp_src, ins, seen):
+    """Walk backwards from instruction i (exclusive) over every path that can reach it, `wait` wait states so far."""
+    while wait < 2:
+        # predecessors through branches to a label that sits right before instruction i
+        for lab in at.get(i, []):
+            for b in branches.get(lab, []):
+                if (b, wait) not in seen:
+                    seen.add((b, wait))
+                    _check_back(insts, at, branches, b + 1, wait, dpp_src, ins, seen)
+        j = i - 1
+        if j < 0:
+            return
+        prev = insts[j]
+        name = prev.split()[0]
+        if name in ("s_branch", "s_endpgm", "s_setpc_b64") and at.get(i):
+            return                          # no fall-through into the label: only the branches above lead here
+        if name == "s_nop":
+            wait += int(prev.split()[1], 0) + 1
+        else:
+            if name.startswith("v_") and not name.startswith("v_cmp"):
+                dst = _regs(prev.split(None, 1)[1].split(",")[0])
+                assert not (dst & dpp_src), f"VALU write too close to a DPP read:\n  {prev}\n  {ins}"
+            wait += 1
+        i = j
+
+
+def test_dpp_fma_source_is_not_written_by_the_two_preceding_valu_instructions(asm):
+    """Backwards from every v_fmac_f32_dpp over two wait states, along the straight line and along every branch that
+    enters a label on the way (so a write at the end of a predecessor block counts too)."""
+    insts, at, branches = _parse(asm)
     n_dpp = 0
     for i, ins in enumerate(insts):
         if not ins.startswith("v_fmac_f32_dpp"):
@@ -46,17 +94,29 @@ def test_dpp_fma_source_is_not_written_by_the_two_preceding_valu_instructions(as
         ops = ins.split(None, 1)[1].split(",")
         dpp_src = _regs(ops[1].split()[0])
         assert dpp_src, ins
-        wait = 0
-        j = i - 1
-        while j >= 0 and wait < 2:
-            prev = insts[j]
-            name = prev.split()[0]
-            if name == "s_nop":
-                wait += int(prev.split()[1], 0) + 1
-            else:
-                if name.startswith("v_") and not name.startswith("v_cmp"):
-                    dst = _regs(prev.split(None, 1)[1].split(",")[0])
-                    assert not (dst & dpp_src), f"VALU write too close to a DPP read:\n  {prev}\n  {ins}"
-                wait += 1
-            j -= 1
+        _check_back(insts, at, branches, i, 0, dpp_src, ins, set())
     assert n_dpp > 0, "the fused kernel no longer uses v_fmac_f32_dpp: drop or adapt this test"
+
+
+def test_the_walk_sees_a_write_at_the_end_of_a_predecessor_block():
+    """The checker itself, on hand-written snippets: a VALU write that reaches the DPP read through a branch is found,
+    one that is two wait states away is not."""
+    bad = """
+        v_mov_b32 v5, v9
+        s_cbranch_scc1 .LBB0_2
+    .LBB0_1:
+        s_nop 0
+        s_branch .LBB0_3
+    .LBB0_2:
+        v_fmac_f32_dpp v1, v5, v2 quad_perm:[0,0,0,0] row_mask:0xf bank_mask:0xf
+    .LBB0_3:
+        s_endpgm
+    """
+    insts, at, branches = _parse(bad)
+    i = next(k for k, x in enumerate(insts) if x.startswith("v_fmac_f32_dpp"))
+    with pytest.raises(AssertionError):
+        _check_back(insts, at, branches, i, 0, {5}, insts[i], set())
+    good = bad.replace("s_cbranch_scc1 .LBB0_2", "s_nop 1\n        s_cbranch_scc1 .LBB0_2")
+    insts, at, branches = _parse(good)
+    i = next(k for k, x in enumerate(insts) if x.startswith("v_fmac_f32_dpp"))
+    _check_back(insts, at, branches, i, 0, {5}, insts[i], set())
