@@ -167,9 +167,8 @@ def measure(torch, args, name, rel_eb, rel_eb_v, steps, warmup, headline):
     if args.n_splits:
         n_splits_est = args.n_splits
     else:  # mirrors the library's split heuristic (only used to count the bytes of the split partials)
-        resident = {1: 4, 2: 4, 4: 3, 8: 2}[Hq // H]  # fused-kernel workgroups per CU for this group size
-        ns = max(1, min(max(1, 256 * resident // (B * H)), -(-nb0 // 4)))
-        bps = -(-(-(-nb0 // ns)) // 4) * 4
+        ns = max(1, min(max(1, 256 // (B * H)), -(-nb0 // 4)))
+        bps = -(-nb0 // ns)
         n_splits_est = max(1, min(128, -(-nb0 // bps))) if bps else 1
 
     def blocks_of(tokens):  # compressed blocks after `tokens` tokens: the buffer keeps the newest ones

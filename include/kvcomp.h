@@ -184,8 +184,9 @@ kvcomp_status kvcomp_decompress(kvcomp_ctx *ctx, int which, void *d_out, int seq
 kvcomp_status kvcomp_decompress_tree_walk(kvcomp_ctx *ctx, int which, void *d_out, int seq_stride, void *stream);
 
 /* Tuning knobs for measurements (0 = library default): number of sequence splits of the fused kernel, LDS staging
- * bytes per wave (records larger than this are decoded straight from global memory). */
-kvcomp_status kvcomp_set_tuning(kvcomp_ctx *ctx, int n_splits, int stage_bytes);
+ * bytes per wave (records larger than this are decoded straight from global memory), waves per workgroup of the
+ * fused kernel (at most 16, 12, 8 for groups of 1-2, 4, 8 query heads). */
+kvcomp_status kvcomp_set_tuning(kvcomp_ctx *ctx, int n_splits, int stage_bytes, int waves_per_workgroup);
 
 /* Kernel timing with HIP events on the launch stream: when enabled, every kvcomp_attn_decode records an event pair
  * around its fused decode kernel.  kvcomp_get_profile synchronises, returns the number of timed launches and their

@@ -59,7 +59,7 @@ SIGNATURES = {
     "kvcomp_get_residual": (_i, [_vp, _i, _vp, C.POINTER(_i), _vp]),
     "kvcomp_decompress": (_i, [_vp, _i, _vp, _i, _vp]),
     "kvcomp_decompress_tree_walk": (_i, [_vp, _i, _vp, _i, _vp]),
-    "kvcomp_set_tuning": (_i, [_vp, _i, _i]),
+    "kvcomp_set_tuning": (_i, [_vp, _i, _i, _i]),
     "kvcomp_set_profiling": (_i, [_vp, _i]),
     "kvcomp_get_profile": (_i, [_vp, C.POINTER(_i), C.POINTER(C.c_double)]),
     "kvcomp_probe_read_stream": (_i, [_vp, C.c_size_t, _vp, C.POINTER(C.c_size_t), _vp]),
@@ -238,8 +238,8 @@ class KVCompCache:
         _check(fn(self.h, which, C.c_void_p(out.data_ptr()), int(out.shape[1]), _stream()))
         return out
 
-    def set_tuning(self, n_splits=0, stage_bytes=0):
-        _check(self.lib.kvcomp_set_tuning(self.h, n_splits, stage_bytes))
+    def set_tuning(self, n_splits=0, stage_bytes=0, waves=0):
+        _check(self.lib.kvcomp_set_tuning(self.h, n_splits, stage_bytes, waves))
 
     def set_profiling(self, enable):
         _check(self.lib.kvcomp_set_profiling(self.h, int(enable)))

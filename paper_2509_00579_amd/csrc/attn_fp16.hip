@@ -49,7 +49,7 @@ __device__ __forceinline__ void merge_waves_and_splits(const float (&comb)[kBWav
         }
     }
     if (gridDim.x > 1)
-        finish_splits<G, 64 * kBWaves>(partials, counters + bh, b * Hq + h * G, (int)gridDim.x, out, tid);
+        finish_splits<G>(partials, counters + bh, b * Hq + h * G, (int)gridDim.x, out, tid, 64 * kBWaves);
 }
 
 

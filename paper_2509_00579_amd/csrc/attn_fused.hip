@@ -37,7 +37,7 @@ struct FusedArgs {
     float *out;
     float scale;
     int n_blocks, res_head, n_res, blocks_per_split, n_splits, stage_bytes;
-    uint32_t mask2[2];
+    uint32_t mask[2];   // table index mask of each tensor, already scaled to the byte offset of an entry
     // append fused into this launch: the newest buffered token (number new_row of the buffer, oldest = 0) is not in the
     // buffer yet but in k_new / v_new [B][H][128]; the wave that reads it also stores it there.  new_row < 0: none.
     const uint16_t *k_new, *v_new;
@@ -87,8 +87,7 @@ __device__ __forceinline__ float fma_quad_c(float w, float sym, float acc) {
     if constexpr (Q == 3) asm("v_fmac_f32_dpp %0, %1, %2 quad_perm:[3,3,3,3] row_mask:0xf bank_mask:0xf" : "+v"(acc) : "v"(w), "v"(sym));
     return acc;
 }
-__device__ __forceinline__ float fma_quad(float w, int q, uint32_t e, float acc) {
-    const float sym = sym_f32(e);
+__device__ __forceinline__ float fma_quad(float w, int q, float sym, float acc) {
     switch (q & 3) {
         case 0: return fma_quad_c<0>(w, sym, acc);
         case 1: return fma_quad_c<1>(w, sym, acc);
@@ -99,12 +98,13 @@ __device__ __forceinline__ float fma_quad(float w, int q, uint32_t e, float acc)
 
 // K, groups of 1 and 2: symbol index `up` of chain au/bu is channel up / 64+up, index `dn` of chain ad/bd is channel
 // dn / 64+dn.  wl = weights + (lane & 3) * G, wdn = weights - (lane & 3) * G, weights laid out [channel][head].
-template <int G, int CNT>
+// CNT table entries of SP symbols each, the first of them symbol `first` of its chain.
+template <int G, int CNT, int SP>
 __device__ __forceinline__ void k_accum(const float *wl, const float *wdn, float (&wq)[4][G], int first,
                                         const uint32_t (&fau)[CNT], const uint32_t (&fad)[CNT],
                                         const uint32_t (&fbu)[CNT], const uint32_t (&fbd)[CNT], float (&acc)[G]) {
 #pragma unroll
-    for (int k = 0; k < CNT; k++) {
+    for (int k = 0; k < CNT * SP; k++) {
         const int up = first + k, dn = kSliceLen - 1 - up;  // symbol index inside the slice
         const int q = up & 3;
         if (q == 0) {
@@ -116,23 +116,28 @@ __device__ __forceinline__ void k_accum(const float *wl, const float *wdn, float
                 wq[3][g] = wdn[(kSliceLen + dn) * G + g];
             }
         }
+        const bool second = SP == 2 && (k & 1);
+        const float s0 = second ? sym2_f32(fau[k / SP]) : sym_f32(fau[k / SP]);
+        const float s1 = second ? sym2_f32(fad[k / SP]) : sym_f32(fad[k / SP]);
+        const float s2 = second ? sym2_f32(fbu[k / SP]) : sym_f32(fbu[k / SP]);
+        const float s3 = second ? sym2_f32(fbd[k / SP]) : sym_f32(fbd[k / SP]);
 #pragma unroll
         for (int g = 0; g < G; g++) {
-            acc[g] = fma_quad(wq[0][g], q, fau[k], acc[g]);
-            acc[g] = fma_quad(wq[1][g], q, fad[k], acc[g]);
-            acc[g] = fma_quad(wq[2][g], q, fbu[k], acc[g]);
-            acc[g] = fma_quad(wq[3][g], q, fbd[k], acc[g]);
+            acc[g] = fma_quad(wq[0][g], q, s0, acc[g]);
+            acc[g] = fma_quad(wq[1][g], q, s1, acc[g]);
+            acc[g] = fma_quad(wq[2][g], q, s2, acc[g]);
+            acc[g] = fma_quad(wq[3][g], q, s3, acc[g]);
         }
     }
 }
 
 // V, groups of 1 and 2: symbol index = token; chains au/ad belong to channel 2*lane, bu/bd to channel 2*lane+1.
-template <int G, int CNT>
+template <int G, int CNT, int SP>
 __device__ __forceinline__ void v_accum(const float *wl, const float *wdn, float (&wq)[2][G], int first,
                                         const uint32_t (&fau)[CNT], const uint32_t (&fad)[CNT],
                                         const uint32_t (&fbu)[CNT], const uint32_t (&fbd)[CNT], float (&acc)[G][2]) {
 #pragma unroll
-    for (int k = 0; k < CNT; k++) {
+    for (int k = 0; k < CNT * SP; k++) {
         const int up = first + k, dn = kSliceLen - 1 - up;  // token index inside the block
         const int q = up & 3;
         if (q == 0) {
@@ -142,23 +147,30 @@ __device__ __forceinline__ void v_accum(const float *wl, const float *wdn, float
                 wq[1][g] = wdn[dn * G + g];
             }
         }
+        const bool second = SP == 2 && (k & 1);
+        const float s0 = second ? sym2_f32(fau[k / SP]) : sym_f32(fau[k / SP]);
+        const float s1 = second ? sym2_f32(fad[k / SP]) : sym_f32(fad[k / SP]);
+        const float s2 = second ? sym2_f32(fbu[k / SP]) : sym_f32(fbu[k / SP]);
+        const float s3 = second ? sym2_f32(fbd[k / SP]) : sym_f32(fbd[k / SP]);
 #pragma unroll
         for (int g = 0; g < G; g++) {
-            acc[g][0] = fma_quad(wq[0][g], q, fau[k], acc[g][0]);
-            acc[g][0] = fma_quad(wq[1][g], q, fad[k], acc[g][0]);
-            acc[g][1] = fma_quad(wq[0][g], q, fbu[k], acc[g][1]);
-            acc[g][1] = fma_quad(wq[1][g], q, fbd[k], acc[g][1]);
+            acc[g][0] = fma_quad(wq[0][g], q, s0, acc[g][0]);
+            acc[g][0] = fma_quad(wq[1][g], q, s1, acc[g][0]);
+            acc[g][1] = fma_quad(wq[0][g], q, s2, acc[g][1]);
+            acc[g][1] = fma_quad(wq[1][g], q, s3, acc[g][1]);
         }
     }
 }
 
 // ---- K block: lane = token; its two slices are channels 0..63 and 64..127 ------------------------------------------
 // hdr32: the record (LDS or global); wts: this wave's LDS weight area.  Leaves scale * q.k' of this lane's token in
-// score[].
-template <int G, int NS>
-__device__ __forceinline__ void k_block(const uint32_t *hdr32, const char *lut, uint32_t mask2, float *wts,
+// score[].  LB: the table width the kernel is compiled for (see DecodeMode).
+template <int G, int LB>
+__device__ __forceinline__ void k_block(const uint32_t *hdr32, const char *lut, uint32_t mask, float *wts,
                                         const float (&qreg)[G][2], float two_eb, float scale, int lane, int kmm,
                                         float (&score)[G]) {
+    using M = DecodeMode<LB>;
+    constexpr int SP = M::kSymsPerLookup, NL = M::kLookupsPerWindow;
     // lane c holds the folded weights q_c * step_c of channels c and c + 64.  kmm = bytes of the {min,max} pairs in
     // the header: 512 (one pair per channel) or 16 (BlockQuant: one pair for the whole block)
     const bool per_channel = kmm == kMinMaxBytesK;
@@ -175,10 +187,9 @@ __device__ __forceinline__ void k_block(const uint32_t *hdr32, const char *lut, 
     const uint32_t sb = hdr32[kmm / 4 + lane];  // bit counts of slices 2*lane and 2*lane+1
     const uint32_t start = wave_excl_scan((sb & 0xffffu) + (sb >> 16), lane);
     const uint32_t *wm1 = hdr32 + (kmm + 2 * kSlices) / 4 - 1;
-    constexpr int kRounds = kHalf / NS, kTail = kHalf - kRounds * NS;
-    constexpr int kP1 = NS > 4 ? 3 : NS, kP2 = NS - kP1;  // pieces of a window (kP2 = 0: taken whole)
-    static_assert(kTail <= 4 && G < kTileMinG, "pieces; groups of 4 and 8 take the tile path");
-    Quad qd;
+    constexpr int kRounds = M::kLookupsPerChain / NL, kTail = M::kLookupsPerChain - kRounds * NL;
+    static_assert(G < kTileMinG, "groups of 4 and 8 take the tile path");
+    Quad<M::J> qd;
     {
 #pragma unroll
         for (int g = 0; g < G; g++) {  // LDS layout [channel][head]
@@ -193,29 +204,14 @@ __device__ __forceinline__ void k_block(const uint32_t *hdr32, const char *lut, 
         // scheduler may overlap the table lookups of one round with the accumulation of the previous one
 #pragma unroll
         for (int r = 0; r < kRounds; r++) {
-            if constexpr (kP2 == 0) {
-                uint32_t fau[NS], fad[NS], fbu[NS], fbd[NS];
-                qd.step<NS>(wm1, lut, mask2, fau, fad, fbu, fbd);
-                k_accum<G, NS>(wl, wdn, wq, r * NS, fau, fad, fbu, fbd, acc);
-            } else {  // a window of more than four symbols is taken in two pieces: fewer table entries in flight
-                qd.begin(wm1);
-                {
-                    uint32_t fau[kP1], fad[kP1], fbu[kP1], fbd[kP1];
-                    qd.part<kP1>(lut, mask2, fau, fad, fbu, fbd);
-                    k_accum<G, kP1>(wl, wdn, wq, r * NS, fau, fad, fbu, fbd, acc);
-                }
-                {
-                    uint32_t fau[kP2 ? kP2 : 1], fad[kP2 ? kP2 : 1], fbu[kP2 ? kP2 : 1], fbd[kP2 ? kP2 : 1];
-                    qd.part<(kP2 ? kP2 : 1)>(lut, mask2, fau, fad, fbu, fbd);
-                    k_accum<G, (kP2 ? kP2 : 1)>(wl, wdn, wq, r * NS + kP1, fau, fad, fbu, fbd, acc);
-                }
-                qd.end(wm1);
-            }
+            uint32_t fau[NL], fad[NL], fbu[NL], fbd[NL];
+            qd.template step<NL>(wm1, lut, mask, fau, fad, fbu, fbd);
+            k_accum<G, NL, SP>(wl, wdn, wq, r * NL * SP, fau, fad, fbu, fbd, acc);
         }
         if constexpr (kTail > 0) {
-            uint32_t fau[kTail], fad[kTail], fbu[kTail], fbd[kTail];
-            qd.step<kTail>(wm1, lut, mask2, fau, fad, fbu, fbd);
-            k_accum<G, kTail>(wl, wdn, wq, kRounds * NS, fau, fad, fbu, fbd, acc);
+            uint32_t fau[kTail ? kTail : 1], fad[kTail ? kTail : 1], fbu[kTail ? kTail : 1], fbd[kTail ? kTail : 1];
+            qd.template step<(kTail ? kTail : 1)>(wm1, lut, mask, fau, fad, fbu, fbd);
+            k_accum<G, (kTail ? kTail : 1), SP>(wl, wdn, wq, kRounds * NL * SP, fau, fad, fbu, fbd, acc);
         }
     }
     // the constant part of the dot product, sum_c q_c min_c, is shared by all tokens of the block
@@ -225,9 +221,11 @@ __device__ __forceinline__ void k_block(const uint32_t *hdr32, const char *lut, 
 
 // ---- V block: lane = channels 2*lane and 2*lane+1 (its two slices) -------------------------------------------------
 // p[g] = softmax numerator of token `lane`.
-template <int G, int NS>
-__device__ __forceinline__ void v_block(const uint32_t *hdr32, const char *lut, uint32_t mask2, float *wts,
+template <int G, int LB>
+__device__ __forceinline__ void v_block(const uint32_t *hdr32, const char *lut, uint32_t mask, float *wts,
                                         const float (&p)[G], float two_eb, int lane, Soft<G> &st) {
+    using M = DecodeMode<LB>;
+    constexpr int SP = M::kSymsPerLookup, NL = M::kLookupsPerWindow;
     // lane t holds the folded weight p_t * step_t of token t
     const uint32_t mm = hdr32[lane];
     const float mn = h2f(mm & 0xffffu);
@@ -241,10 +239,9 @@ __device__ __forceinline__ void v_block(const uint32_t *hdr32, const char *lut, 
     const uint32_t sb = hdr32[kMinMaxBytesV / 4 + lane];
     const uint32_t start = wave_excl_scan((sb & 0xffffu) + (sb >> 16), lane);
     const uint32_t *wm1 = hdr32 + kHdrBytesV / 4 - 1;
-    constexpr int kRounds = kHalf / NS, kTail = kHalf - kRounds * NS;
-    constexpr int kP1 = NS > 4 ? 3 : NS, kP2 = NS - kP1;  // pieces of a window (kP2 = 0: taken whole)
-    static_assert(kTail <= 4 && G < kTileMinG, "pieces; groups of 4 and 8 take the tile path");
-    Quad qd;
+    constexpr int kRounds = M::kLookupsPerChain / NL, kTail = M::kLookupsPerChain - kRounds * NL;
+    static_assert(G < kTileMinG, "groups of 4 and 8 take the tile path");
+    Quad<M::J> qd;
     {
 #pragma unroll
         for (int g = 0; g < G; g++) wts[lane * G + g] = w[g];  // LDS layout [token][head]
@@ -254,45 +251,30 @@ __device__ __forceinline__ void v_block(const uint32_t *hdr32, const char *lut, 
         qd.open(wm1, start, sb & 0xffffu, sb >> 16);
 #pragma unroll
         for (int r = 0; r < kRounds; r++) {
-            if constexpr (kP2 == 0) {
-                uint32_t fau[NS], fad[NS], fbu[NS], fbd[NS];
-                qd.step<NS>(wm1, lut, mask2, fau, fad, fbu, fbd);
-                v_accum<G, NS>(wl, wdn, wq, r * NS, fau, fad, fbu, fbd, st.acc);
-            } else {
-                qd.begin(wm1);
-                {
-                    uint32_t fau[kP1], fad[kP1], fbu[kP1], fbd[kP1];
-                    qd.part<kP1>(lut, mask2, fau, fad, fbu, fbd);
-                    v_accum<G, kP1>(wl, wdn, wq, r * NS, fau, fad, fbu, fbd, st.acc);
-                }
-                {
-                    uint32_t fau[kP2 ? kP2 : 1], fad[kP2 ? kP2 : 1], fbu[kP2 ? kP2 : 1], fbd[kP2 ? kP2 : 1];
-                    qd.part<(kP2 ? kP2 : 1)>(lut, mask2, fau, fad, fbu, fbd);
-                    v_accum<G, (kP2 ? kP2 : 1)>(wl, wdn, wq, r * NS + kP1, fau, fad, fbu, fbd, st.acc);
-                }
-                qd.end(wm1);
-            }
+            uint32_t fau[NL], fad[NL], fbu[NL], fbd[NL];
+            qd.template step<NL>(wm1, lut, mask, fau, fad, fbu, fbd);
+            v_accum<G, NL, SP>(wl, wdn, wq, r * NL * SP, fau, fad, fbu, fbd, st.acc);
         }
         if constexpr (kTail > 0) {
-            uint32_t fau[kTail], fad[kTail], fbu[kTail], fbd[kTail];
-            qd.step<kTail>(wm1, lut, mask2, fau, fad, fbu, fbd);
-            v_accum<G, kTail>(wl, wdn, wq, kRounds * NS, fau, fad, fbu, fbd, st.acc);
+            uint32_t fau[kTail ? kTail : 1], fad[kTail ? kTail : 1], fbu[kTail ? kTail : 1], fbd[kTail ? kTail : 1];
+            qd.template step<(kTail ? kTail : 1)>(wm1, lut, mask, fau, fad, fbu, fbd);
+            v_accum<G, (kTail ? kTail : 1), SP>(wl, wdn, wq, kRounds * NL * SP, fau, fad, fbu, fbd, st.acc);
         }
     }
 }
 
 // Rare path: a record larger than the LDS staging area is decoded straight from global memory.  Kept out of line so
 // that it costs the common path no registers.
-template <int G, int NS>
-__device__ __noinline__ void k_block_global(const uint32_t *rec, const char *lut, uint32_t mask2, float *wts,
+template <int G, int LB>
+__device__ __noinline__ void k_block_global(const uint32_t *rec, const char *lut, uint32_t mask, float *wts,
                                             const float (&qreg)[G][2], float two_eb, float scale, int lane, int kmm,
                                             float (&score)[G]) {
-    k_block<G, NS>(rec, lut, mask2, wts, qreg, two_eb, scale, lane, kmm, score);
+    k_block<G, LB>(rec, lut, mask, wts, qreg, two_eb, scale, lane, kmm, score);
 }
-template <int G, int NS>
-__device__ __noinline__ void v_block_global(const uint32_t *rec, const char *lut, uint32_t mask2, float *wts,
+template <int G, int LB>
+__device__ __noinline__ void v_block_global(const uint32_t *rec, const char *lut, uint32_t mask, float *wts,
                                             const float (&p)[G], float two_eb, int lane, Soft<G> &st) {
-    v_block<G, NS>(rec, lut, mask2, wts, p, two_eb, lane, st);
+    v_block<G, LB>(rec, lut, mask, wts, p, two_eb, lane, st);
 }
 
 // ---- groups of 4 and 8 query heads, tile path ---------------------------------------------------------------------
@@ -350,53 +332,68 @@ __device__ __forceinline__ uint32_t pack_syms(uint32_t e0, uint32_t e1, uint32_t
     const uint32_t lo = __builtin_amdgcn_perm(e1, e0, 0x0c0c0501u), hi = __builtin_amdgcn_perm(e3, e2, 0x0c0c0501u);
     return __builtin_amdgcn_perm(hi, lo, 0x05040100u);
 }
+// the same from two entries of the pair table (bytes 1 and 2 of each are two consecutive symbols): e0's symbols in
+// the two lowest bytes; and with the four symbols in the opposite order (a chain that was read downwards)
+__device__ __forceinline__ uint32_t pack_pairs(uint32_t e0, uint32_t e1) { return __builtin_amdgcn_perm(e1, e0, 0x06050201u); }
+__device__ __forceinline__ uint32_t pack_pairs_rev(uint32_t e0, uint32_t e1) { return __builtin_amdgcn_perm(e1, e0, 0x01020506u); }
 
-// The table entries of the 4 x 32 symbols of a lane's chains while they wait to be packed (fully unrolled code: an
-// entry lives in a register from its lookup to the packing of its word).
+// The table entries of a lane's four chains while they wait to be packed (fully unrolled code: an entry lives in a
+// register from its lookup to the packing of its word).  NE entries per chain: 32 one-symbol or 16 two-symbol ones.
+template <int NE>
 struct ChainSyms {
-    uint32_t au[kHalf], ad[kHalf], bu[kHalf], bd[kHalf];
+    uint32_t au[NE], ad[NE], bu[NE], bd[NE];
 };
 // The decoded symbols (biased bytes) of the lane's two slices, four per word, in ascending position inside the slice:
 // word j of a slice holds positions 4j .. 4j+3.  The up chain delivers words 0, 1, .. and the down chain 15, 14, ..
 struct SliceWords {
     uint32_t a[16], b[16];
 };
-// Decodes symbols S0 .. S1-1 of this lane's four chains (whole windows of NS symbols from S0 on; the last window of a
-// chain may be short) and packs every word whose four symbols are there.
-template <int NS, int S0, int S1>
-__device__ __forceinline__ void decode_span(Quad &qd, const uint32_t *wm1, const char *lut, uint32_t mask2, ChainSyms &e,
-                                            SliceWords &p) {
+// Decodes symbols S0 .. S1-1 of this lane's four chains (whole windows from S0 on; the last window of a chain may be
+// short) and packs every word whose four symbols are there.
+template <int LB, int S0, int S1>
+__device__ __forceinline__ void decode_span(Quad<DecodeMode<LB>::J> &qd, const uint32_t *wm1, const char *lut, uint32_t mask,
+                                            ChainSyms<DecodeMode<LB>::kLookupsPerChain> &e, SliceWords &p) {
+    using M = DecodeMode<LB>;
+    constexpr int SP = M::kSymsPerLookup, NL = M::kLookupsPerWindow, NS = M::kSymsPerWindow;
     static_assert(S0 % NS == 0 && S0 < S1 && S1 <= kHalf && (S1 % NS == 0 || S1 == kHalf), "whole windows");
     auto pack_words = [&](int w0, int w1) {
 #pragma unroll
         for (int w = w0; w < w1; w++) {
-            p.a[w] = pack_syms(e.au[4 * w], e.au[4 * w + 1], e.au[4 * w + 2], e.au[4 * w + 3]);
-            p.a[15 - w] = pack_syms(e.ad[4 * w + 3], e.ad[4 * w + 2], e.ad[4 * w + 1], e.ad[4 * w]);
-            p.b[w] = pack_syms(e.bu[4 * w], e.bu[4 * w + 1], e.bu[4 * w + 2], e.bu[4 * w + 3]);
-            p.b[15 - w] = pack_syms(e.bd[4 * w + 3], e.bd[4 * w + 2], e.bd[4 * w + 1], e.bd[4 * w]);
+            if constexpr (SP == 1) {
+                p.a[w] = pack_syms(e.au[4 * w], e.au[4 * w + 1], e.au[4 * w + 2], e.au[4 * w + 3]);
+                p.a[15 - w] = pack_syms(e.ad[4 * w + 3], e.ad[4 * w + 2], e.ad[4 * w + 1], e.ad[4 * w]);
+                p.b[w] = pack_syms(e.bu[4 * w], e.bu[4 * w + 1], e.bu[4 * w + 2], e.bu[4 * w + 3]);
+                p.b[15 - w] = pack_syms(e.bd[4 * w + 3], e.bd[4 * w + 2], e.bd[4 * w + 1], e.bd[4 * w]);
+            } else {
+                p.a[w] = pack_pairs(e.au[2 * w], e.au[2 * w + 1]);
+                p.a[15 - w] = pack_pairs_rev(e.ad[2 * w], e.ad[2 * w + 1]);
+                p.b[w] = pack_pairs(e.bu[2 * w], e.bu[2 * w + 1]);
+                p.b[15 - w] = pack_pairs_rev(e.bd[2 * w], e.bd[2 * w + 1]);
+            }
         }
     };
-    constexpr int kFull = (S1 - S0) / NS, kTail = (S1 - S0) - kFull * NS;
+    constexpr int kFull = (S1 - S0) / NS, kTailSyms = (S1 - S0) - kFull * NS, kTail = kTailSyms / SP;
+    static_assert(kTailSyms % SP == 0, "a span ends on a whole table entry");
 #pragma unroll
     for (int r = 0; r < kFull; r++) {
-        uint32_t fau[NS], fad[NS], fbu[NS], fbd[NS];
-        qd.step<NS>(wm1, lut, mask2, fau, fad, fbu, fbd);
+        uint32_t fau[NL], fad[NL], fbu[NL], fbd[NL];
+        qd.template step<NL>(wm1, lut, mask, fau, fad, fbu, fbd);
         const int s = S0 + r * NS;
 #pragma unroll
-        for (int k = 0; k < NS; k++) {
-            e.au[s + k] = fau[k]; e.ad[s + k] = fad[k]; e.bu[s + k] = fbu[k]; e.bd[s + k] = fbd[k];
+        for (int k = 0; k < NL; k++) {
+            e.au[s / SP + k] = fau[k]; e.ad[s / SP + k] = fad[k]; e.bu[s / SP + k] = fbu[k]; e.bd[s / SP + k] = fbd[k];
         }
         pack_words(s / 4, (s + NS) / 4);
     }
     if constexpr (kTail > 0) {
-        uint32_t fau[kTail], fad[kTail], fbu[kTail], fbd[kTail];
-        qd.step<kTail>(wm1, lut, mask2, fau, fad, fbu, fbd);
+        uint32_t fau[kTail ? kTail : 1], fad[kTail ? kTail : 1], fbu[kTail ? kTail : 1], fbd[kTail ? kTail : 1];
+        qd.template step<(kTail ? kTail : 1)>(wm1, lut, mask, fau, fad, fbu, fbd);
         constexpr int s = S0 + kFull * NS;
 #pragma unroll
         for (int k = 0; k < kTail; k++) {
-            e.au[s + k] = fau[k]; e.ad[s + k] = fad[k]; e.bu[s + k] = fbu[k]; e.bd[s + k] = fbd[k];
+            e.au[s / SP + k] = fau[k]; e.ad[s / SP + k] = fad[k]; e.bu[s / SP + k] = fbu[k]; e.bd[s / SP + k] = fbd[k];
         }
-        pack_words(s / 4, (s + kTail) / 4);
+        pack_words(s / 4, (s + kTailSyms) / 4);
     }
 }
 // first symbol that the second span of a block decodes when the products run after each half: the first half's
@@ -461,7 +458,7 @@ static_assert(32 * kARowK <= kTileBytes && 32 * kARowV <= kTileBytes, "A operand
 // Updates the softmax state and leaves the softmax numerators of tokens l%32 and 32 + l%32 in p.
 // record_done() is called once the record has been read for the last time, before the last products: the place to
 // request the next record, whose loads then travel while few registers are live.
-template <int G, int NS, class F>
+template <int G, int LB, class F>
 __device__ __forceinline__ void k_tile_block(const uint32_t *hdr32, const char *lut, uint32_t mask2, uint8_t *tile,
                                              const float *qf, float two_eb, float scale, int lane, int kmm,
                                              TileSoft<G> &ts, float (&p)[G / 2][2], F &&record_done) {
@@ -521,12 +518,12 @@ __device__ __forceinline__ void k_tile_block(const uint32_t *hdr32, const char *
     const uint32_t sb = hdr32[kmm / 4 + lane];  // bit counts of slices 2*lane and 2*lane+1
     const uint32_t start = wave_excl_scan((sb & 0xffffu) + (sb >> 16), lane);
     const uint32_t *wm1 = hdr32 + (kmm + 2 * kSlices) / 4 - 1;
-    Quad qd;
+    Quad<DecodeMode<LB>::J> qd;
     qd.open(wm1, start, sb & 0xffffu, sb >> 16);
     constexpr bool kBoth = tile_halves_at_once(G) == 2;  // one recombination per block instead of one per half
     float sc[HL][2];
     v16i d[2];  // result tiles: tokens 0..31 and 32..63
-    ChainSyms syms;
+    ChainSyms<DecodeMode<LB>::kLookupsPerChain> syms;
     SliceWords pw;  // lane = token: slice a = its channels 0..63, slice b = its channels 64..127
     // one step of 16 channels of either slice: steps 0..3 are channels 0..63, steps 4..7 channels 64..127
     auto products = [&](int ks) {
@@ -553,16 +550,16 @@ __device__ __forceinline__ void k_tile_block(const uint32_t *hdr32, const char *
             for (int i = 0; i < HL; i++) sc[i][t] = first ? v[i] : sc[i][t] + v[i];
         }
     };
-    constexpr int kP = tile_first_span(NS);
+    constexpr int kP = tile_first_span(DecodeMode<LB>::kSymsPerWindow);
     // a half of a block is 16 symbols of every chain: the up chains deliver step h, the down chains step 3 - h
     // The products of the first half run while the second half is decoded (no fence in between: everything is in
     // registers).
-    decode_span<NS, 0, kP>(qd, wm1, lut, mask2, syms, pw);
+    decode_span<LB, 0, kP>(qd, wm1, lut, mask2, syms, pw);
     clear();
     products(0);
     products(3);
     if constexpr (!kBoth) join(true);
-    decode_span<NS, kP, kHalf>(qd, wm1, lut, mask2, syms, pw);
+    decode_span<LB, kP, kHalf>(qd, wm1, lut, mask2, syms, pw);
     wave_sync();
     record_done();
     if constexpr (!kBoth) clear();
@@ -586,7 +583,7 @@ __device__ __forceinline__ void k_tile_block(const uint32_t *hdr32, const char *
 }
 
 // V block.  p: softmax numerators of tokens l%32 and 32 + l%32 for this lane's heads.
-template <int G, int NS, class F>
+template <int G, int LB, class F>
 __device__ __forceinline__ void v_tile_block(const uint32_t *hdr32, const char *lut, uint32_t mask2, uint8_t *tile,
                                              const float (&p)[G / 2][2], float two_eb, int lane, TileSoft<G> &ts,
                                              F &&record_done) {
@@ -636,11 +633,11 @@ __device__ __forceinline__ void v_tile_block(const uint32_t *hdr32, const char *
     const uint32_t start_a = wave_excl_scan(abits, lane);
     const uint32_t start_b = (uint32_t)__builtin_amdgcn_readlane((int)(start_a + abits), 63) + wave_excl_scan(bbits, lane);
     const uint32_t *wm1 = hdr32 + kHdrBytesV / 4 - 1;
-    Quad qd;
+    Quad<DecodeMode<LB>::J> qd;
     qd.open2(wm1, start_a, abits, start_b, bbits);
     constexpr bool kBoth = tile_halves_at_once(G) == 2;
     v16i d[4];  // result tiles: channels 0..31, 32..63 (slice a), 64..95, 96..127 (slice b)
-    ChainSyms syms;
+    ChainSyms<DecodeMode<LB>::kLookupsPerChain> syms;
     SliceWords pw;
     // one step of 16 tokens of both slices
     auto products = [&](int ks) {
@@ -667,13 +664,13 @@ __device__ __forceinline__ void v_tile_block(const uint32_t *hdr32, const char *
             for (int i = 0; i < HL; i++) ts.acc[i][ct] = fmaf(inv, v[i], ts.acc[i][ct]);
         }
     };
-    constexpr int kP = tile_first_span(NS);
-    decode_span<NS, 0, kP>(qd, wm1, lut, mask2, syms, pw);
+    constexpr int kP = tile_first_span(DecodeMode<LB>::kSymsPerWindow);
+    decode_span<LB, 0, kP>(qd, wm1, lut, mask2, syms, pw);
     clear();
     products(0);
     products(3);
     if constexpr (!kBoth) join();
-    decode_span<NS, kP, kHalf>(qd, wm1, lut, mask2, syms, pw);
+    decode_span<LB, kP, kHalf>(qd, wm1, lut, mask2, syms, pw);
     wave_sync();
     record_done();
     if constexpr (!kBoth) clear();
@@ -684,16 +681,16 @@ __device__ __forceinline__ void v_tile_block(const uint32_t *hdr32, const char *
 
 // Rare path: a record larger than the LDS staging area (one that an append flushed after the host last looked at the
 // record sizes) is decoded straight from global memory, out of line.
-template <int G, int NS>
+template <int G, int LB>
 __device__ __noinline__ void k_tile_block_global(const uint32_t *rec, const char *lut, uint32_t mask2, uint8_t *tile,
                                                  const float *qf, float two_eb, float scale, int lane, int kmm,
                                                  TileSoft<G> &ts, float (&p)[G / 2][2]) {
-    k_tile_block<G, NS>(rec, lut, mask2, tile, qf, two_eb, scale, lane, kmm, ts, p, [] {});
+    k_tile_block<G, LB>(rec, lut, mask2, tile, qf, two_eb, scale, lane, kmm, ts, p, [] {});
 }
-template <int G, int NS>
+template <int G, int LB>
 __device__ __noinline__ void v_tile_block_global(const uint32_t *rec, const char *lut, uint32_t mask2, uint8_t *tile,
                                                  const float (&p)[G / 2][2], float two_eb, int lane, TileSoft<G> &ts) {
-    v_tile_block<G, NS>(rec, lut, mask2, tile, p, two_eb, lane, ts, [] {});
+    v_tile_block<G, LB>(rec, lut, mask2, tile, p, two_eb, lane, ts, [] {});
 }
 
 // The tile path's state in the layout of the other paths (lane = channels 2*lane, 2*lane+1 of every head; l and bv
@@ -727,8 +724,6 @@ __device__ __forceinline__ void tile_state_to_soft(const TileSoft<G> &ts, float 
     wave_sync();
 }
 
-constexpr int kWaves = 4;
-constexpr int kThreads = 64 * kWaves;
 
 // The buffered fp16 tokens (Section 3.2.3: the newest vectors take part too), in units of 16 tokens; this wave takes
 // units first_unit, first_unit + unit_step, ...  Token r of the buffer sits in slot (res_head + r) mod res_tokens;
@@ -892,26 +887,27 @@ struct DirectStage {
     }
 };
 
-// Register budget: 4 waves per SIMD (128 VGPRs) for groups of 1 and 2 query heads, 3 (168) and 2 (256) for groups
-// of 4 and 8.
-template <int G> struct WavesPerSimd { static constexpr int value = fused_wgs_per_cu(G); };
+// One workgroup per CU, as many waves as the registers allow per SIMD: 4 (128 VGPRs) for groups of 1 and 2 query
+// heads, 3 (168) and 2 (256) for groups of 4 and 8.  The host may launch fewer waves per workgroup (short sequences,
+// large staging areas).
+template <int G> struct MaxWaves { static constexpr int value = 4 * fused_waves_per_simd(G); };
 
-// LB = index width the decode tables are sized for (>= longest code word of both codebooks); a window then
-// serves NS = floor(kWindowBits / LB) symbols.
+// LB = the table width the kernel is compiled for (>= longest code word of both codebooks), see DecodeMode.
 template <int G, int LB>
-__global__ __launch_bounds__(kThreads, WavesPerSimd<G>::value) void fused_attn_kernel(FusedArgs a) {
+__global__ __launch_bounds__(64 * MaxWaves<G>::value, 1) void fused_attn_kernel(FusedArgs a) {
+    using M = DecodeMode<LB>;
     constexpr bool kTile = G >= kTileMinG;  // packed symbols in registers, int8 MFMA
-    constexpr int NS = kWindowBits / LB;
-    __shared__ __attribute__((aligned(16))) uint16_t lut_s[2][1 << LB];
+    __shared__ __attribute__((aligned(16))) uint8_t lut_s[2][M::kTableBytes];
     __shared__ __attribute__((aligned(16))) float qf[G * kD];
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];  // per wave: staging area + weights
-    const int tid = threadIdx.x, lane = tid & 63;
+    const int tid = threadIdx.x, lane = tid & 63, n_threads = blockDim.x;
     // the wave number and everything derived from it (block numbers, table entries, record addresses) are scalars
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int n_waves = __builtin_amdgcn_readfirstlane(n_threads >> 6);
     uint8_t *stage = smem + (size_t)wave * a.stage_bytes;
-    constexpr int kWeightBytes = (int)fused_weight_bytes(G, LB);
+    constexpr int kWeightBytes = (int)fused_weight_bytes(G);
     static_assert(!kTile || kWeightBytes == kTileBytes, "tile area");
-    float *wts = reinterpret_cast<float *>(smem + (size_t)kWaves * a.stage_bytes + (size_t)wave * kWeightBytes);
+    float *wts = reinterpret_cast<float *>(smem + (size_t)n_waves * a.stage_bytes + (size_t)wave * kWeightBytes);
     const char *lutK = reinterpret_cast<const char *>(&lut_s[0][0]);
     const char *lutV = reinterpret_cast<const char *>(&lut_s[1][0]);
 
@@ -942,19 +938,20 @@ __global__ __launch_bounds__(kThreads, WavesPerSimd<G>::value) void fused_attn_k
         eV = tabV[j];
     }
     for (int t = 0; t < 2; t++) {
-        const uint4 *src = reinterpret_cast<const uint4 *>(g.lut + t * kLutSize);
+        // pair table: 4096 entries of 4 bytes; otherwise 2^(longest code word of this tensor) entries of 2 bytes
+        const uint4 *src = M::kPair ? reinterpret_cast<const uint4 *>(g.lut2 + t * (1 << kPairIndexBits))
+                                    : reinterpret_cast<const uint4 *>(g.lut + t * kLutSize);
         uint4 *dst = reinterpret_cast<uint4 *>(&lut_s[t][0]);
-        const int n16 = max(1, (2 << g.lut_bits[t]) / 16);
-        for (int i = tid; i < n16; i += kThreads) {
+        const int n16 = M::kPair ? M::kTableBytes / 16 : max(1, (2 << g.lut_bits[t]) / 16);
+        const uint32_t flip = !kTile ? 0u : M::kPair ? 0x00808000u : 0x80008000u;  // the MFMA operands hold symbol - 128 as int8
+        for (int i = tid; i < n16; i += n_threads) {
             uint4 v = src[i];
-            if constexpr (kTile) {  // the MFMA operands hold symbol - 128 as int8
-                v.x ^= 0x80008000u; v.y ^= 0x80008000u; v.z ^= 0x80008000u; v.w ^= 0x80008000u;
-            }
+            v.x ^= flip; v.y ^= flip; v.z ^= flip; v.w ^= flip;
             dst[i] = v;
         }
     }
-    const uint32_t maskK = a.mask2[0], maskV = a.mask2[1];
-    for (int i = tid; i < G * kD; i += kThreads) qf[i] = h2f(a.q[((size_t)b * g.Hq + (size_t)h * G) * kD + i]);
+    const uint32_t maskK = a.mask[0], maskV = a.mask[1];
+    for (int i = tid; i < G * kD; i += n_threads) qf[i] = h2f(a.q[((size_t)b * g.Hq + (size_t)h * G) * kD + i]);
     Prefetch pf;
 #pragma unroll
     for (int i = 0; i < kPrefetchRegs; i++) pf.r[i] = make_uint4(0, 0, 0, 0);
@@ -995,7 +992,7 @@ __global__ __launch_bounds__(kThreads, WavesPerSimd<G>::value) void fused_attn_k
         const bool k_staged = eK.size16 <= stage16, v_staged = eV.size16 <= stage16;
         const uint8_t *recK = g.payload + (size_t)eK.off16 * 16, *recV = g.payload + (size_t)eV.off16 * 16;
         if (!kTile && v_staged) pf.issue(recV, eV.size16, lane);  // V record travels while K is decoded
-        const int jn = j + kWaves;  // the next pair's Block Offsets Array entries travel with it
+        const int jn = j + n_waves;  // the next pair's Block Offsets Array entries travel with it
         BlockEntry eKn = {0, 0}, eVn = {0, 0};
         if (jn < j1) {
             eKn = tabK[jn];
@@ -1006,12 +1003,12 @@ __global__ __launch_bounds__(kThreads, WavesPerSimd<G>::value) void fused_attn_k
             // The next record is requested when the current one has been decoded: its registers are then live across
             // the products and the softmax only, not across a decode.
             if (k_staged) {
-                k_tile_block<G, NS>(stage32, lutK, maskK, tile, qf, g.two_eb[0], a.scale, lane, g.k_minmax_bytes, ts, pt,
+                k_tile_block<G, LB>(stage32, lutK, maskK, tile, qf, g.two_eb[0], a.scale, lane, g.k_minmax_bytes, ts, pt,
                                     [&] { if (v_staged) ds.issue(recV, eV.size16, stage, lane); });
             } else {
                 TileSoft<G> ts_tmp = ts;
                 float p_tmp[kQ0][2];
-                k_tile_block_global<G, NS>(reinterpret_cast<const uint32_t *>(recK), lutK, maskK, tile, qf, g.two_eb[0],
+                k_tile_block_global<G, LB>(reinterpret_cast<const uint32_t *>(recK), lutK, maskK, tile, qf, g.two_eb[0],
                                            a.scale, lane, g.k_minmax_bytes, ts_tmp, p_tmp);
                 ts = ts_tmp;
 #pragma unroll
@@ -1020,12 +1017,12 @@ __global__ __launch_bounds__(kThreads, WavesPerSimd<G>::value) void fused_attn_k
             }
         } else {
         if (k_staged) {
-            k_block<G, NS>(stage32, lutK, maskK, wts, qreg, g.two_eb[0], a.scale, lane, g.k_minmax_bytes, score);
+            k_block<G, LB>(stage32, lutK, maskK, wts, qreg, g.two_eb[0], a.scale, lane, g.k_minmax_bytes, score);
         } else {  // larger than the staging area: decode from global memory (copies keep the hot state in registers)
             float q_tmp[G][2], s_tmp[G];
 #pragma unroll
             for (int gg = 0; gg < G; gg++) { q_tmp[gg][0] = qreg[gg][0]; q_tmp[gg][1] = qreg[gg][1]; }
-            k_block_global<G, NS>(reinterpret_cast<const uint32_t *>(recK), lutK, maskK, wts, q_tmp, g.two_eb[0], a.scale,
+            k_block_global<G, LB>(reinterpret_cast<const uint32_t *>(recK), lutK, maskK, wts, q_tmp, g.two_eb[0], a.scale,
                                   lane, g.k_minmax_bytes, s_tmp);
 #pragma unroll
             for (int gg = 0; gg < G; gg++) score[gg] = s_tmp[gg];
@@ -1049,27 +1046,27 @@ __global__ __launch_bounds__(kThreads, WavesPerSimd<G>::value) void fused_attn_k
         if (!kTile && next_staged) pf.issue(g.payload + (size_t)eKn.off16 * 16, eKn.size16, lane);
         if constexpr (kTile) {
             if (v_staged) {
-                v_tile_block<G, NS>(stage32, lutV, maskV, tile, pt, g.two_eb[1], lane, ts,
+                v_tile_block<G, LB>(stage32, lutV, maskV, tile, pt, g.two_eb[1], lane, ts,
                                     [&] { if (next_staged) ds.issue(g.payload + (size_t)eKn.off16 * 16, eKn.size16, stage, lane); });
             } else {
                 TileSoft<G> ts_tmp = ts;
                 float p_tmp[kQ0][2];
 #pragma unroll
                 for (int i = 0; i < kQ0; i++) { p_tmp[i][0] = pt[i][0]; p_tmp[i][1] = pt[i][1]; }
-                v_tile_block_global<G, NS>(reinterpret_cast<const uint32_t *>(recV), lutV, maskV, tile, p_tmp, g.two_eb[1],
+                v_tile_block_global<G, LB>(reinterpret_cast<const uint32_t *>(recV), lutV, maskV, tile, p_tmp, g.two_eb[1],
                                            lane, ts_tmp);
                 ts = ts_tmp;
                 if (next_staged) ds.issue(g.payload + (size_t)eKn.off16 * 16, eKn.size16, stage, lane);
             }
         } else {
         if (v_staged) {
-            v_block<G, NS>(stage32, lutV, maskV, wts, p, g.two_eb[1], lane, st);
+            v_block<G, LB>(stage32, lutV, maskV, wts, p, g.two_eb[1], lane, st);
         } else {
             Soft<G> st_tmp = st;
             float p_tmp[G];
 #pragma unroll
             for (int gg = 0; gg < G; gg++) p_tmp[gg] = p[gg];
-            v_block_global<G, NS>(reinterpret_cast<const uint32_t *>(recV), lutV, maskV, wts, p_tmp, g.two_eb[1], lane,
+            v_block_global<G, LB>(reinterpret_cast<const uint32_t *>(recV), lutV, maskV, wts, p_tmp, g.two_eb[1], lane,
                                   st_tmp);
             st = st_tmp;
         }
@@ -1083,10 +1080,10 @@ __global__ __launch_bounds__(kThreads, WavesPerSimd<G>::value) void fused_attn_k
         eK = eKn;
         eV = eVn;
         j = jn;
-        {   // The SIMD issues from its oldest wave first, so the four resident waves finish one after the other and
-            // the last one runs alone, unable to fill the VALU.  Waves that are behind get the issue slots instead:
+        {   // The SIMD issues from its oldest wave first, so its resident waves finish one after the other and the
+            // last one runs alone, unable to fill the VALU.  Waves that are behind get the issue slots instead:
             // the priority falls with the share of the work that is done, and the waves finish together.
-            const int total = (j1 - j0 - wave + kWaves - 1) / kWaves, left = (j1 - j + kWaves - 1) / kWaves;
+            const int total = (j1 - j0 - wave + n_waves - 1) / n_waves, left = (j1 - j + n_waves - 1) / n_waves;
             const int q4 = total > 0 ? (4 * left + total - 1) / total : 0;  // 4 .. 0
             if (q4 >= 4) __builtin_amdgcn_s_setprio(3);
             else if (q4 == 3) __builtin_amdgcn_s_setprio(2);
@@ -1099,10 +1096,12 @@ __global__ __launch_bounds__(kThreads, WavesPerSimd<G>::value) void fused_attn_k
     // the buffered fp16 tokens in units of 16: unit u goes to split n_splits-1 - u % n_splits (the last split is the
     // short one), there to the waves in turn, starting after the wave that took the split's last block
     if (a.n_res > 0) {
-        const int first = a.n_splits - 1 - split + a.n_splits * ((wave - (j1 - j0)) & (kWaves - 1));
+        int turn = (wave - (j1 - j0)) % n_waves;
+        if (turn < 0) turn += n_waves;
+        const int first = a.n_splits - 1 - split + a.n_splits * turn;
         if (first * kUnitTokens < a.n_res) {
             Soft<G> st_tmp = st;
-            buffered_tokens<G>(g.res, g.res_tokens, g.B, g.H, b, h, a.res_head, a.n_res, first, kWaves * a.n_splits, qf,
+            buffered_tokens<G>(g.res, g.res_tokens, g.B, g.H, b, h, a.res_head, a.n_res, first, n_waves * a.n_splits, qf,
                                a.scale, lane, a.k_new, a.v_new, a.new_row, st_tmp);
             st = st_tmp;
         }
@@ -1126,19 +1125,17 @@ __global__ __launch_bounds__(kThreads, WavesPerSimd<G>::value) void fused_attn_k
     const int row0 = b * g.Hq + h * G;
     // the thread number is rebuilt from the lane and the (scalar) wave number: nothing of the prologue has to stay
     // in a register, or be spilled, across the decode loop for the sake of the merge
-    const int tid_m = lane + 64 * wave;
-    for (int i = tid_m; i < G * kD; i += kThreads) {
+    const int tid_m = lane + 64 * wave, nt_m = 64 * n_waves;
+    for (int i = tid_m; i < G * kD; i += nt_m) {
         const int gg = i / kD, c = i - gg * kD;
-        float M = -INFINITY;
-#pragma unroll
-        for (int w = 0; w < kWaves; w++)
-            M = fmaxf(M, reinterpret_cast<const float *>(smem + (size_t)w * a.stage_bytes)[gg * kPartialStride + kD]);
+        float M_ = -INFINITY;
+        for (int w = 0; w < n_waves; w++)
+            M_ = fmaxf(M_, reinterpret_cast<const float *>(smem + (size_t)w * a.stage_bytes)[gg * kPartialStride + kD]);
         float L = 0.f, O = 0.f;
-#pragma unroll
-        for (int w = 0; w < kWaves; w++) {
+        for (int w = 0; w < n_waves; w++) {
             const float *cw = reinterpret_cast<const float *>(smem + (size_t)w * a.stage_bytes) + gg * kPartialStride;
             const float mw = cw[kD];
-            const float f = mw == -INFINITY ? 0.f : __expf(mw - M);
+            const float f = mw == -INFINITY ? 0.f : __expf(mw - M_);
             L += cw[kD + 1] * f;
             O += cw[c] * f;
         }
@@ -1147,14 +1144,15 @@ __global__ __launch_bounds__(kThreads, WavesPerSimd<G>::value) void fused_attn_k
         } else {
             float *dst = g.partials + ((size_t)(row0 + gg) * kMaxSplits + split) * kPartialStride;
             store_agent(dst + c, O);
-            if (c == 0) { store_agent(dst + kD, M); store_agent(dst + kD + 1, L); }
+            if (c == 0) { store_agent(dst + kD, M_); store_agent(dst + kD + 1, L); }
         }
     }
-    if (a.n_splits > 1) finish_splits<G, kThreads>(g.partials, g.counters + bh, row0, a.n_splits, a.out, tid_m);
+    if (a.n_splits > 1) finish_splits<G>(g.partials, g.counters + bh, row0, a.n_splits, a.out, tid_m, nt_m);
 }
 
 template <int G, int LB>
-static hipError_t launch_fused_gn(const FusedArgs &a, size_t lds, hipEvent_t ev0, hipEvent_t ev1, hipStream_t s) {
+static hipError_t launch_fused_gn(const FusedArgs &a, int n_waves, size_t lds, hipEvent_t ev0, hipEvent_t ev1,
+                                  hipStream_t s) {
     static size_t attr_set = 0;
     if (lds > attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&fused_attn_kernel<G, LB>),
@@ -1162,28 +1160,28 @@ static hipError_t launch_fused_gn(const FusedArgs &a, size_t lds, hipEvent_t ev0
         if (e != hipSuccess) return e;
         attr_set = lds;
     }
+    if (n_waves < 1 || n_waves > MaxWaves<G>::value) return hipErrorInvalidValue;
     if (ev0) (void)hipEventRecord(ev0, s);
-    hipLaunchKernelGGL((fused_attn_kernel<G, LB>), dim3(a.n_splits * a.g.B * a.g.H), dim3(kThreads), lds, s, a);
+    hipLaunchKernelGGL((fused_attn_kernel<G, LB>), dim3(a.n_splits * a.g.B * a.g.H), dim3(64 * n_waves), lds, s, a);
     if (ev1) (void)hipEventRecord(ev1, s);
     return hipGetLastError();
 }
 
 template <int G>
-static hipError_t launch_fused_g(const FusedArgs &a, int longest, size_t lds, hipEvent_t ev0, hipEvent_t ev1,
+static hipError_t launch_fused_g(const FusedArgs &a, int longest, int n_waves, size_t lds, hipEvent_t ev0, hipEvent_t ev1,
                                  hipStream_t s) {
-    switch (fused_attn_table_bits(longest, G)) {
-        case 6:
-            return launch_fused_gn<G, 6>(a, lds, ev0, ev1, s);
-        case 7: return launch_fused_gn<G, 7>(a, lds, ev0, ev1, s);
-        case 8: return launch_fused_gn<G, 8>(a, lds, ev0, ev1, s);
-        case 10: return launch_fused_gn<G, 10>(a, lds, ev0, ev1, s);
-        default: return launch_fused_gn<G, 12>(a, lds, ev0, ev1, s);
+    switch (fused_table_bits(longest)) {
+        case 6: return launch_fused_gn<G, 6>(a, n_waves, lds, ev0, ev1, s);
+        case 7: return launch_fused_gn<G, 7>(a, n_waves, lds, ev0, ev1, s);
+        case 8: return launch_fused_gn<G, 8>(a, n_waves, lds, ev0, ev1, s);
+        case 10: return launch_fused_gn<G, 10>(a, n_waves, lds, ev0, ev1, s);
+        default: return launch_fused_gn<G, 12>(a, n_waves, lds, ev0, ev1, s);
     }
 }
 
 hipError_t launch_fused_attn(const Geo &g, const uint16_t *q, float scale, float *out, int n_blocks, int res_head,
-                             int n_res, const uint16_t *k_new, const uint16_t *v_new, int n_splits, int stage_bytes,
-                             hipEvent_t ev0, hipEvent_t ev1, hipStream_t s) {
+                             int n_res, const uint16_t *k_new, const uint16_t *v_new, int n_splits, int n_waves,
+                             int stage_bytes, hipEvent_t ev0, hipEvent_t ev1, hipStream_t s) {
     FusedArgs a;
     a.k_new = k_new;
     a.v_new = v_new;
@@ -1201,18 +1199,21 @@ hipError_t launch_fused_attn(const Geo &g, const uint16_t *q, float scale, float
     const int bits_k = g.lut_bits[0], bits_v = g.lut_bits[1];
     const int longest = bits_k > bits_v ? bits_k : bits_v;
     if (longest < 1 || longest > kLutBits) return hipErrorInvalidValue;
-    a.mask2[0] = ((1u << bits_k) - 1u) << kJunkBits;
-    a.mask2[1] = ((1u << bits_v) - 1u) << kJunkBits;
-    const size_t lds = (size_t)kWaves * stage_bytes + kWaves * fused_weight_bytes(g.G, fused_attn_table_bits(longest, g.G));
+    if (fused_table_bits(longest) == 6) {  // pair tables: 12 index bits, entries of 4 bytes
+        a.mask[0] = a.mask[1] = ((1u << kPairIndexBits) - 1u) << 2;
+    } else {
+        a.mask[0] = ((1u << bits_k) - 1u) << 1;
+        a.mask[1] = ((1u << bits_v) - 1u) << 1;
+    }
+    const size_t lds = (size_t)n_waves * ((size_t)stage_bytes + fused_weight_bytes(g.G));
     switch (g.G) {
-        case 1: return launch_fused_g<1>(a, longest, lds, ev0, ev1, s);
-        case 2: return launch_fused_g<2>(a, longest, lds, ev0, ev1, s);
-        case 4: return launch_fused_g<4>(a, longest, lds, ev0, ev1, s);
-        case 8: return launch_fused_g<8>(a, longest, lds, ev0, ev1, s);
+        case 1: return launch_fused_g<1>(a, longest, n_waves, lds, ev0, ev1, s);
+        case 2: return launch_fused_g<2>(a, longest, n_waves, lds, ev0, ev1, s);
+        case 4: return launch_fused_g<4>(a, longest, n_waves, lds, ev0, ev1, s);
+        case 8: return launch_fused_g<8>(a, longest, n_waves, lds, ev0, ev1, s);
         default: return hipErrorInvalidValue;
     }
 }
-
 
 // ---- statistics (metrics path, not part of the hot loop) --------------------------------------------------------
 // Sums record sizes and code-word bits over all blocks in use by walking the Block Offsets Array and the slice bit

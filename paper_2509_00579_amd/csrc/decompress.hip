@@ -39,6 +39,7 @@ struct TreeWalk {
 template <int LB>
 __global__ __launch_bounds__(64 * kDecWaves) void decompress_kernel(DecompArgs a) {
     constexpr bool kTree = LB == 0;
+    constexpr int kWindowBits = 31;  // stream bits per window of 16-bit table entries
     constexpr int NS = kTree ? 1 : kWindowBits / (kTree ? 1 : LB);
     __shared__ __attribute__((aligned(16))) uint16_t lut_s[kTree ? 512 : (1 << LB)];
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];  // per wave: record staging, then the code tile
@@ -79,7 +80,7 @@ __global__ __launch_bounds__(64 * kDecWaves) void decompress_kernel(DecompArgs a
     const uint32_t start = wave_excl_scan((sb & 0xffffu) + (sb >> 16), lane);
     const uint32_t *wm1 = hdr32 + (mmb + 2 * kSlices) / 4 - 1;
     const char *lut = reinterpret_cast<const char *>(lut_s);
-    Quad qd;
+    Quad<1> qd;
     qd.open(wm1, start, sb & 0xffffu, sb >> 16);
     constexpr int kRounds = kHalf / NS, kTail = kHalf - kRounds * NS;
     // K: lane = token, chains au/ad = channels 0..63 (up / down), bu/bd = channels 64..127
@@ -115,8 +116,8 @@ __global__ __launch_bounds__(64 * kDecWaves) void decompress_kernel(DecompArgs a
         // damaged table
         bool busy = true;
         for (int round = 0; round < 16 && busy; round++) {
-            uint32_t w0 = qd.au.window(wm1) >> kJunkBits, w1 = qd.ad.window(wm1) >> kJunkBits;
-            uint32_t w2 = qd.bu.window(wm1) >> kJunkBits, w3 = qd.bd.window(wm1) >> kJunkBits;
+            uint32_t w0 = qd.au.window(wm1) >> 1, w1 = qd.ad.window(wm1) >> 1;
+            uint32_t w2 = qd.bu.window(wm1) >> 1, w3 = qd.bd.window(wm1) >> 1;
 #pragma unroll 1
             for (int k = 0; k < kWindowBits; k++) {
                 const int i0 = tw[0].count, i1 = tw[1].count, i2 = tw[2].count, i3 = tw[3].count;
@@ -137,13 +138,13 @@ __global__ __launch_bounds__(64 * kDecWaves) void decompress_kernel(DecompArgs a
 #pragma unroll 2
         for (int r = 0; r < kRounds; r++) {
             uint32_t fau[NS], fad[NS], fbu[NS], fbd[NS];
-            qd.step<NS>(wm1, lut, a.mask2, fau, fad, fbu, fbd);
+            qd.template step<NS>(wm1, lut, a.mask2, fau, fad, fbu, fbd);
 #pragma unroll
             for (int k = 0; k < NS; k++) put(r * NS + k, fau[k], fad[k], fbu[k], fbd[k]);
         }
         if constexpr (kTail > 0) {
             uint32_t fau[kTail], fad[kTail], fbu[kTail], fbd[kTail];
-            qd.step<kTail>(wm1, lut, a.mask2, fau, fad, fbu, fbd);
+            qd.template step<kTail>(wm1, lut, a.mask2, fau, fad, fbu, fbd);
 #pragma unroll
             for (int k = 0; k < kTail; k++) put(kRounds * NS + k, fau[k], fad[k], fbu[k], fbd[k]);
         }
@@ -231,7 +232,7 @@ hipError_t launch_decompress(const Geo &g, int which, uint16_t *out, int n_block
         a.stage_bytes = stage_bytes;
         const int bits = g.lut_bits[which];
         if (bits < 1 || bits > kLutBits) return hipErrorInvalidValue;
-        a.mask2 = ((1u << bits) - 1u) << kJunkBits;
+        a.mask2 = ((1u << bits) - 1u) << 1;
         const size_t lds = (size_t)kDecWaves * ((size_t)stage_bytes + kBT * kTileRow);
         const long long items = (long long)g.B * g.H * n_blocks;
         const int grid = (int)((items + kDecWaves - 1) / kDecWaves);
@@ -240,6 +241,7 @@ hipError_t launch_decompress(const Geo &g, int which, uint16_t *out, int n_block
             e = launch_dec<0>(a, lds, grid, s);
         } else
         switch (fused_table_bits(bits)) {
+            case 6:
             case 7: e = launch_dec<7>(a, lds, grid, s); break;
             case 8: e = launch_dec<8>(a, lds, grid, s); break;
             case 10: e = launch_dec<10>(a, lds, grid, s); break;

@@ -15,6 +15,8 @@
 namespace kvc {
 namespace host {
 
+constexpr int kPairEntries = 1 << 12;  // entries of a pair table (12 index bits)
+
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 inline int n_sym_for(float rel_eb) {
@@ -54,7 +56,7 @@ inline int k_header_bytes(const kvcomp_config &c) { return k_minmax_bytes(c) + 2
 inline int code_len_limit(const kvcomp_config &c) { return c.max_code_len ? c.max_code_len : kLutBits; }
 
 struct Layout {
-    size_t ctrl, hist, enc, lut, tree, counters, table, res, partials, payload, total;
+    size_t ctrl, hist, enc, lut, tree, lut2, counters, table, res, partials, payload, total;
     size_t payload_cap16;
     int max_blocks;
 };
@@ -72,6 +74,7 @@ inline Layout make_layout(const kvcomp_config &c) {
     L.enc = at; at += 4 * 256 * 4;
     L.lut = at; at += 2 * kLutSize * 2;
     L.tree = at; at += 2 * 256 * 2 * 2;
+    L.lut2 = at; at += 2 * kPairEntries * 4;
     L.counters = at; at += align_up(BH * 4, 256);
     L.table = at; at += align_up(2 * BH * (size_t)std::max(L.max_blocks, 1) * sizeof(BlockEntry), 256);
     L.res = at; at += align_up(2 * (size_t)c.batch * buffer_tokens(c) * c.n_kv_heads * kD * 2, 256);
@@ -180,6 +183,18 @@ inline int build_tables(const uint8_t *len, const uint32_t *code, uint32_t *enc,
         }
     }
     return bits;
+}
+
+// Pair table of a codebook whose code words have at most 6 bits (`bits` = its longest, lut = its decode table from
+// build_tables): entry i, for the next 12 stream bits i, = (length of the first two code words together) | first
+// symbol << 8 | second symbol << 16.  The code is complete (Kraft sum 1), so every bit pattern starts with a code word.
+inline void build_pair_table(const uint16_t *lut, int bits, uint32_t *lut2) {
+    const uint32_t m = (1u << bits) - 1u;
+    for (uint32_t i = 0; i < (uint32_t)kPairEntries; i++) {
+        const uint32_t e1 = lut[i & m], l1 = e1 & 0xffu;
+        const uint32_t e2 = lut[(i >> l1) & m], l2 = e2 & 0xffu;
+        lut2[i] = (l1 + l2) | ((e1 >> 8) << 8) | ((e2 >> 8) << 16);
+    }
 }
 
 }  // namespace host

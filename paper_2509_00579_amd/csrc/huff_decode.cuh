@@ -69,24 +69,25 @@ __device__ __forceinline__ uint32_t wave_excl_scan(uint32_t v, int lane) {
 // A slice holds two decode chains (see the record layout): symbols 0..31 are read upwards from the slice start,
 // symbols 63..32 downwards from the slice end.
 //   wm1   payload words, pointer moved back by one word: payload bit x is bit x + 32 of wm1
-// A window is 32 stream bits whose bit 0 is a don't-care and whose bits 1.. are the next unread bits in reading
-// order, i.e. the stream already scaled to the byte offset of a 16-bit table entry.
+// A window is 32 bits whose lowest J bits are don't-cares and whose bits J.. are the next unread stream bits in
+// reading order, i.e. the stream already scaled to the byte offset of a table entry of 2^J bytes (J = 1: 16-bit
+// entries, one symbol each; J = 2: 32-bit entries that deliver two symbols).
 // (Unaligned 4-byte LDS reads at byte granularity, and re-reading both words of every window, were tried: slower.)
-constexpr int kJunkBits = 1;                  // low window bits that are not stream bits
-constexpr int kWindowBits = 32 - kJunkBits;  // stream bits per window
+//
 // Readers keep a 64-bit piece {hi,lo} of the stream in registers plus the next word in reading direction, fetched
 // one window ahead: one 4-byte LDS read per window, off the critical path (only table lookups depend on each other).
+template <int J>
 struct UpReader {
-    uint32_t P, idx, lo, hi, nx;  // P = (next unread payload bit) + 32 - kJunkBits = window start in wm1 bit coordinates
+    uint32_t P, idx, lo, hi, nx;  // P = (next unread payload bit) + 32 - J = window start in wm1 bit coordinates
     __device__ __forceinline__ void open(const uint32_t *wm1, uint32_t first_bit) {
-        P = first_bit + (uint32_t)(32 - kJunkBits);
+        P = first_bit + (uint32_t)(32 - J);
         idx = P >> 5;
         lo = wm1[idx];
         hi = wm1[idx + 1];
         nx = wm1[idx + 2];
     }
     __device__ __forceinline__ uint32_t window(const uint32_t *) const { return __builtin_amdgcn_alignbit(hi, lo, P); }
-    __device__ __forceinline__ void advance(const uint32_t *wm1, uint32_t used) {  // used <= 31
+    __device__ __forceinline__ void advance(const uint32_t *wm1, uint32_t used) {  // used <= 32 - J
         P += used;
         const uint32_t nidx = P >> 5;
         const bool adv = nidx != idx;
@@ -96,11 +97,12 @@ struct UpReader {
         nx = wm1[nidx + 2];
     }
 };
+template <int J>
 struct DownReader {
-    uint32_t P, idx, lo, hi, pv;  // P = (one past the next unread payload bit) + kJunkBits: the window [P, P+32) of wm1 ends
-                                  // kJunkBits bits above the next unread bit; bit-reversed it reads downwards
+    uint32_t P, idx, lo, hi, pv;  // P = (one past the next unread payload bit) + J: the window [P, P+32) of wm1 ends J
+                                  // bits above the next unread bit; bit-reversed it reads downwards
     __device__ __forceinline__ void open(const uint32_t *wm1, uint32_t end_bit) {
-        P = end_bit + (uint32_t)kJunkBits;
+        P = end_bit + (uint32_t)J;
         idx = P >> 5;
         lo = wm1[idx];
         hi = wm1[idx + 1];
@@ -109,7 +111,7 @@ struct DownReader {
     __device__ __forceinline__ uint32_t window(const uint32_t *) const {
         return __builtin_bitreverse32(__builtin_amdgcn_alignbit(hi, lo, P));
     }
-    __device__ __forceinline__ void advance(const uint32_t *wm1, uint32_t used) {  // used <= 31
+    __device__ __forceinline__ void advance(const uint32_t *wm1, uint32_t used) {  // used <= 32 - J
         P -= used;
         const uint32_t nidx = P >> 5;
         const bool adv = nidx != idx;
@@ -120,33 +122,33 @@ struct DownReader {
     }
 };
 
-// Decode CNT symbols from a window.  lut: 16-bit entries (symbol << 8) | code length, indexed by the next `bits`
-// stream bits; mask2 = ((1 << bits) - 1) << 1.  CNT * (longest code word) <= kWindowBits is the caller's promise.
-// e[] receives the entries; returns the number of bits used.
-// `win` is left at the first bit that was not used, so that a further call continues in the same window.
-template <int CNT>
-__device__ __forceinline__ uint32_t lookup_more(uint32_t &win, const char *lut, uint32_t mask2, uint32_t (&e)[CNT]) {
+// CNT table lookups in a window.  J = 1: 16-bit entries (symbol << 8) | code length, indexed by the next `bits` stream
+// bits, mask = ((1 << bits) - 1) << 1.  J = 2: 32-bit entries of the pair table, indexed by the next 12 stream bits
+// (mask = 0xfff << 2): byte 0 = length of two consecutive code words together, byte 1 = first symbol, byte 2 = second
+// symbol.  CNT * (index width) <= 32 - J is the caller's promise.  e[] receives the entries; returns the number of
+// bits used.
+template <int J, int CNT>
+__device__ __forceinline__ uint32_t lookup(uint32_t win, const char *lut, uint32_t mask, uint32_t (&e)[CNT]) {
     uint32_t tot = 0;
 #pragma unroll
     for (int k = 0; k < CNT; k++) {
-        e[k] = *reinterpret_cast<const uint16_t *>(lut + (win & mask2));
+        if constexpr (J == 1) e[k] = *reinterpret_cast<const uint16_t *>(lut + (win & mask));
+        else e[k] = *reinterpret_cast<const uint32_t *>(lut + (win & mask));
         win >>= (e[k] & 31u);
         tot += e[k];  // low byte: running sum of code lengths (at most 31, never carries)
     }
     return tot & 0xffu;
 }
-template <int CNT>
-__device__ __forceinline__ uint32_t lookup(uint32_t win, const char *lut, uint32_t mask2, uint32_t (&e)[CNT]) {
-    return lookup_more<CNT>(win, lut, mask2, e);
-}
 
-// the symbol of a table entry as fp32 (one v_cvt_f32_ubyte1)
-__device__ __forceinline__ float sym_f32(uint32_t e) { return (float)(e >> 8); }
+// the symbols of a table entry as fp32 (one v_cvt_f32_ubyte1 / v_cvt_f32_ubyte2)
+__device__ __forceinline__ float sym_f32(uint32_t e) { return (float)((e >> 8) & 0xffu); }
+__device__ __forceinline__ float sym2_f32(uint32_t e) { return (float)((e >> 16) & 0xffu); }
 
-// The four chains of one lane (two slices x two directions) advance together, CNT symbols each.
+// The four chains of one lane (two slices x two directions) advance together, CNT lookups each.
+template <int J>
 struct Quad {
-    UpReader au, bu;
-    DownReader ad, bd;
+    UpReader<J> au, bu;
+    DownReader<J> ad, bd;
     // a = [a0, a0 + abits), b follows it
     __device__ __forceinline__ void open(const uint32_t *wm1, uint32_t a0, uint32_t abits, uint32_t bbits) {
         au.open(wm1, a0);
@@ -162,36 +164,12 @@ struct Quad {
         bd.open(wm1, b0 + bbits);
     }
     template <int CNT>
-    __device__ __forceinline__ void step(const uint32_t *wm1, const char *lut, uint32_t mask2, uint32_t (&fau)[CNT],
+    __device__ __forceinline__ void step(const uint32_t *wm1, const char *lut, uint32_t mask, uint32_t (&fau)[CNT],
                                          uint32_t (&fad)[CNT], uint32_t (&fbu)[CNT], uint32_t (&fbd)[CNT]) {
-        const uint32_t u0 = lookup<CNT>(au.window(wm1), lut, mask2, fau);
-        const uint32_t u1 = lookup<CNT>(ad.window(wm1), lut, mask2, fad);
-        const uint32_t u2 = lookup<CNT>(bu.window(wm1), lut, mask2, fbu);
-        const uint32_t u3 = lookup<CNT>(bd.window(wm1), lut, mask2, fbd);
-        au.advance(wm1, u0);
-        ad.advance(wm1, u1);
-        bu.advance(wm1, u2);
-        bd.advance(wm1, u3);
-    }
-    // The same in pieces, for windows that hold more symbols than the caller wants table entries in flight:
-    // begin(), then part<CNT>() once per piece (the pieces' CNT add up to what fits a window), then end().
-    uint32_t w0, w1, w2, w3, u0, u1, u2, u3;  // the four windows and the bits used so far; live from begin() to end()
-    __device__ __forceinline__ void begin(const uint32_t *wm1) {
-        w0 = au.window(wm1);
-        w1 = ad.window(wm1);
-        w2 = bu.window(wm1);
-        w3 = bd.window(wm1);
-        u0 = u1 = u2 = u3 = 0;
-    }
-    template <int CNT>
-    __device__ __forceinline__ void part(const char *lut, uint32_t mask2, uint32_t (&fau)[CNT], uint32_t (&fad)[CNT],
-                                         uint32_t (&fbu)[CNT], uint32_t (&fbd)[CNT]) {
-        u0 += lookup_more<CNT>(w0, lut, mask2, fau);
-        u1 += lookup_more<CNT>(w1, lut, mask2, fad);
-        u2 += lookup_more<CNT>(w2, lut, mask2, fbu);
-        u3 += lookup_more<CNT>(w3, lut, mask2, fbd);
-    }
-    __device__ __forceinline__ void end(const uint32_t *wm1) {
+        const uint32_t u0 = lookup<J, CNT>(au.window(wm1), lut, mask, fau);
+        const uint32_t u1 = lookup<J, CNT>(ad.window(wm1), lut, mask, fad);
+        const uint32_t u2 = lookup<J, CNT>(bu.window(wm1), lut, mask, fbu);
+        const uint32_t u3 = lookup<J, CNT>(bd.window(wm1), lut, mask, fbd);
         au.advance(wm1, u0);
         ad.advance(wm1, u1);
         bu.advance(wm1, u2);
@@ -200,5 +178,22 @@ struct Quad {
 };
 
 constexpr int kHalf = kSliceLen / 2;  // symbols per chain
+constexpr int kPairIndexBits = 12;    // index width of the pair table: two code words of up to 6 bits
+constexpr int kPairLongest = kPairIndexBits / 2;
+
+// How a kernel compiled for code words of up to LB bits decodes.  LB <= 6: the pair table (every lookup delivers two
+// symbols, so a chain of 32 symbols is 16 dependent lookups).  Otherwise the single-symbol table of 2^LB 16-bit
+// entries.
+template <int LB>
+struct DecodeMode {
+    static constexpr bool kPair = LB <= kPairLongest;
+    static constexpr int J = kPair ? 2 : 1;                               // log2 of the entry size in bytes
+    static constexpr int kIndexBits = kPair ? kPairIndexBits : LB;
+    static constexpr int kSymsPerLookup = kPair ? 2 : 1;
+    static constexpr int kLookupsPerWindow = (32 - J) / kIndexBits;       // pair table: 2; 7, 8, 10, 12 bits: 4, 3, 3, 2
+    static constexpr int kSymsPerWindow = kSymsPerLookup * kLookupsPerWindow;
+    static constexpr int kLookupsPerChain = kHalf / kSymsPerLookup;
+    static constexpr int kTableBytes = (kPair ? 4 : 2) << kIndexBits;     // per tensor
+};
 
 }  // namespace kvc

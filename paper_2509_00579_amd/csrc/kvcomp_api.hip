@@ -47,7 +47,7 @@ struct kvcomp_ctx {
     uint8_t len[2][256];
     uint32_t code[2][256];
     uint32_t max_size16;
-    int tune_splits, tune_stage;
+    int tune_splits, tune_stage, tune_waves;
     bool profiling;
     std::vector<hipEvent_t> events;  // pairs
     size_t events_used;
@@ -59,6 +59,7 @@ struct kvcomp_ctx {
     uint32_t *h_enc;   // [2 tensors][2 directions][256]
     uint16_t *h_lut;   // [2][4096]
     int16_t *h_tree;   // [2][256][2]
+    uint32_t *h_lut2;  // [2][4096]
 };
 
 namespace {
@@ -127,7 +128,7 @@ kvcomp_status kvcomp_create(const kvcomp_config *cfg, void *d_arena, size_t aren
     c->have_codebook = false;
     c->n_blocks = c->n_res = c->res_head = 0;
     c->max_size16 = 0;
-    c->tune_splits = c->tune_stage = 0;
+    c->tune_splits = c->tune_stage = c->tune_waves = 0;
     c->profiling = false;
     c->events_used = 0;
     c->prof_launches = 0;
@@ -149,6 +150,7 @@ kvcomp_status kvcomp_create(const kvcomp_config *cfg, void *d_arena, size_t aren
     g.enc = reinterpret_cast<uint32_t *>(c->arena + L.enc);
     g.lut = reinterpret_cast<uint16_t *>(c->arena + L.lut);
     g.tree = reinterpret_cast<int16_t *>(c->arena + L.tree);
+    g.lut2 = reinterpret_cast<uint32_t *>(c->arena + L.lut2);
     g.lut_bits[0] = g.lut_bits[1] = kLutBits;
     g.counters = reinterpret_cast<uint32_t *>(c->arena + L.counters);
     g.table = reinterpret_cast<BlockEntry *>(c->arena + L.table);
@@ -158,7 +160,7 @@ kvcomp_status kvcomp_create(const kvcomp_config *cfg, void *d_arena, size_t aren
     g.payload = c->arena + L.payload;
     g.payload_cap16 = (uint32_t)L.payload_cap16;
     void *pinned = nullptr;
-    const size_t pin_bytes = 256 + 2 * 256 * 4 + 4 * 256 * 4 + 2 * kLutSize * 2 + 2 * 256 * 2 * 2;
+    const size_t pin_bytes = 256 + 2 * 256 * 4 + 4 * 256 * 4 + 2 * kLutSize * 2 + 2 * 256 * 2 * 2 + 2 * kPairEntries * 4;
     hipError_t e = hipHostMalloc(&pinned, pin_bytes, hipHostMallocDefault);
     if (e != hipSuccess) {
         delete c;
@@ -170,6 +172,7 @@ kvcomp_status kvcomp_create(const kvcomp_config *cfg, void *d_arena, size_t aren
     c->h_enc = reinterpret_cast<uint32_t *>(pb + 256 + 2048);
     c->h_lut = reinterpret_cast<uint16_t *>(pb + 256 + 2048 + 4096);
     c->h_tree = reinterpret_cast<int16_t *>(pb + 256 + 2048 + 4096 + 2 * kLutSize * 2);
+    c->h_lut2 = reinterpret_cast<uint32_t *>(pb + 256 + 2048 + 4096 + 2 * kLutSize * 2 + 2 * 256 * 2 * 2);
     // control words, histogram, tables and the Block Offsets Array start at zero
     e = launch_fill_zero(c->arena, L.res, static_cast<hipStream_t>(stream));
     if (e != hipSuccess) {
@@ -226,9 +229,13 @@ kvcomp_status kvcomp_build_codebook(kvcomp_ctx *ctx, const void *d_K, const void
         build_codebook_host(ctx->h_hist + 256 * w, g.n_sym[w], code_len_limit(ctx->cfg), ctx->len[w], ctx->code[w]);
         ctx->geo.lut_bits[w] = build_tables(ctx->len[w], ctx->code[w], ctx->h_enc + 512 * w, ctx->h_lut + kLutSize * w,
                                             ctx->h_tree + 512 * w);
+        if (ctx->geo.lut_bits[w] <= 6) build_pair_table(ctx->h_lut + kLutSize * w, ctx->geo.lut_bits[w], ctx->h_lut2 + kPairEntries * w);
+        else std::memset(ctx->h_lut2 + kPairEntries * w, 0, kPairEntries * 4);
     }
     // encode tables, decode tables and trees are neighbours too: one upload
-    HIP_TRY(hipMemcpyAsync(g.enc, ctx->h_enc, 4 * 256 * 4 + 2 * kLutSize * 2 + 2 * 256 * 2 * 2, hipMemcpyHostToDevice, s));
+    static_assert(kPairEntries == kPairTableEntries, "pair table size");
+    HIP_TRY(hipMemcpyAsync(g.enc, ctx->h_enc, 4 * 256 * 4 + 2 * kLutSize * 2 + 2 * 256 * 2 * 2 + 2 * kPairEntries * 4,
+                           hipMemcpyHostToDevice, s));
     HIP_TRY(hipStreamSynchronize(s));
     ctx->have_codebook = true;
     return KVCOMP_OK;
@@ -291,29 +298,36 @@ kvcomp_status kvcomp_append_token(kvcomp_ctx *ctx, const void *d_k_new, const vo
 static kvcomp_status attn_impl(kvcomp_ctx *ctx, const void *d_q, float scale, float *d_out, const uint16_t *k_new,
                                const uint16_t *v_new, hipStream_t s) {
     const Geo &g = ctx->geo;
-    // Work split: the grid should fit the chip in a single round of workgroups (256 CUs x the workgroups of 4 waves
-    // that registers and LDS let be resident per CU for this group size and table width), every wave owning whole
-    // block pairs; per-workgroup costs (tables, first record, split merge) are then paid once per resident slot,
-    // and no second, partly filled round of workgroups trails the first.
+    // Work split: one workgroup per CU, holding as many waves as the registers allow per SIMD (16, 12 or 8 for groups
+    // of 1-2, 4, 8 query heads) and the LDS has room for (decode tables + a staging area per wave); the grid is one
+    // round of workgroups, every wave owning whole block pairs.  Per-workgroup costs (tables, split merge) are then
+    // paid once per CU, and the waves of a head's split merge through LDS.
     const int longest = std::max(g.lut_bits[0], g.lut_bits[1]);
     const size_t lds_fixed = fused_lds_fixed(g.G, longest);
     int stage = ctx->tune_stage;
     if (stage <= 0) stage = (int)align_up((size_t)ctx->max_size16 * 16 + 16, 256);
     stage = std::max(stage, 4608);
     stage = (int)align_up(stage, 16);
-    if (lds_fixed + 4 * (size_t)stage > (size_t)kLdsBytesPerCU) stage = (int)((kLdsBytesPerCU - lds_fixed) / 4 / 16 * 16);
+    const size_t per_wave_rest = fused_weight_bytes(g.G);
+    int max_waves = 4 * fused_waves_per_simd(g.G);
+    if (ctx->tune_waves > 0) max_waves = std::min(max_waves, ctx->tune_waves);
+    max_waves = std::max(1, std::min(max_waves, (int)((kLdsBytesPerCU - lds_fixed) / ((size_t)stage + per_wave_rest))));
+    if (lds_fixed + (size_t)stage + per_wave_rest > (size_t)kLdsBytesPerCU)
+        stage = (int)((kLdsBytesPerCU - lds_fixed - per_wave_rest) / 16 * 16);  // one wave, records above it from global memory
+    const int wgs_per_cu = std::max(1, std::min(4 * fused_waves_per_simd(g.G) / max_waves,
+                                                (int)(kLdsBytesPerCU / (lds_fixed + max_waves * ((size_t)stage + per_wave_rest)))));
     int n_splits = ctx->tune_splits;
     if (n_splits <= 0) {
         const int bh = g.B * g.H;
-        const int resident = std::max(1, std::min(fused_wgs_per_cu(g.G), (int)(kLdsBytesPerCU / (lds_fixed + 4 * (size_t)stage))));
-        const int by_chip = std::max(1, kCUs * resident / bh);
-        const int by_work = std::max(1, (ctx->n_blocks + 3) / 4);  // at least one block pair per wave
+        const int by_chip = std::max(1, kCUs * wgs_per_cu / bh);
+        const int by_work = std::max(1, (ctx->n_blocks + 3) / 4);  // at least one block pair per SIMD of the CU
         n_splits = std::min(by_chip, by_work);
-        int bps = (ctx->n_blocks + n_splits - 1) / std::max(n_splits, 1);
-        bps = (bps + 3) / 4 * 4;
-        n_splits = bps > 0 ? (ctx->n_blocks + bps - 1) / bps : 1;
     }
     n_splits = std::max(1, std::min({n_splits, (int)kMaxSplits, std::max(ctx->n_blocks, 1)}));
+    // waves of a workgroup: no more than its split has block pairs (a short sequence leaves wave slots empty rather
+    // than CUs), at least enough for the buffered tokens' units to spread
+    const int bps = ctx->n_blocks > 0 ? (ctx->n_blocks + n_splits - 1) / n_splits : 0;
+    int n_waves = std::max(1, std::min(max_waves, std::max(bps, std::min(4, (ctx->n_res + 15) / 16))));
     hipEvent_t ev0 = nullptr, ev1 = nullptr;
     if (ctx->profiling) {
         if (ctx->events_used + 2 > ctx->events.size()) {
@@ -333,7 +347,7 @@ static kvcomp_status attn_impl(kvcomp_ctx *ctx, const void *d_q, float scale, fl
         ctx->events_used += 2;
     }
     HIP_TRY(launch_fused_attn(g, static_cast<const uint16_t *>(d_q), scale, d_out, ctx->n_blocks, ctx->res_head, ctx->n_res,
-                              k_new, v_new, n_splits, stage, ev0, ev1, s));
+                              k_new, v_new, n_splits, n_waves, stage, ev0, ev1, s));
     return KVCOMP_OK;
 }
 
@@ -510,10 +524,11 @@ kvcomp_status kvcomp_decompress_tree_walk(kvcomp_ctx *ctx, int which, void *d_ou
     return decompress_impl(ctx, which, d_out, seq_stride, 1, stream);
 }
 
-kvcomp_status kvcomp_set_tuning(kvcomp_ctx *ctx, int n_splits, int stage_bytes) {
-    if (!ctx || n_splits < 0 || stage_bytes < 0) return fail(KVCOMP_ERR_INVALID_ARG, "bad argument");
+kvcomp_status kvcomp_set_tuning(kvcomp_ctx *ctx, int n_splits, int stage_bytes, int waves_per_workgroup) {
+    if (!ctx || n_splits < 0 || stage_bytes < 0 || waves_per_workgroup < 0) return fail(KVCOMP_ERR_INVALID_ARG, "bad argument");
     ctx->tune_splits = n_splits;
     ctx->tune_stage = stage_bytes;
+    ctx->tune_waves = waves_per_workgroup;
     return KVCOMP_OK;
 }
 

@@ -36,6 +36,9 @@ struct Geo {
     uint32_t *enc;           // [2 tensors][2][256]  (len << 16) | code word as it goes into the LSB-first stream:
                              //   [0]: first-bit-first (symbols 0..31 of a slice), [1]: last-bit-first (32..63)
     uint16_t *lut;           // [2][4096] (symbol << 8) | len, indexed by the next lut_bits[t] stream bits
+    uint32_t *lut2;          // [2][4096] pair tables, valid when both code books have code words of at most 6 bits:
+                             //   indexed by the next 12 stream bits; byte 0 = length of two code words together,
+                             //   byte 1 = first symbol, byte 2 = second symbol
     int lut_bits[2];         // index width of each decode table = longest code word of that codebook
     int16_t *tree;           // [2][256][2] array-based Huffman tree (Section 3.3.1): child of node n for stream bit b;
                              //   >= 0: inner node, < 0: leaf holding symbol ~child; the root is node 0
@@ -60,27 +63,23 @@ constexpr int kTileBytes = 4352;
 // registers: three waves per SIMD fit); groups of 8, whose lanes carry twice the heads through every recombination,
 // keep the integer accumulators across both halves and recombine once (two waves per SIMD).  2 = recombine once.
 constexpr int tile_halves_at_once(int G) { return G >= 8 ? 2 : 1; }
-// Workgroups (of 4 waves) of the fused kernel that are resident per CU = its waves per SIMD: groups of 4 and 8 query
-// heads trade occupancy for registers and for the LDS tiles.
-constexpr int fused_wgs_per_cu(int G) { return G >= 8 ? 2 : G >= 4 ? 3 : 4; }
-// Index width the fused kernel's LDS decode tables are compiled for, given the longest code word in use.
+// Waves of the fused kernel per SIMD, as the registers allow: groups of 4 and 8 query heads trade occupancy for
+// registers.  One workgroup per CU holds them all (4 SIMDs: 16, 12 or 8 waves).
+constexpr int fused_waves_per_simd(int G) { return G >= 8 ? 2 : G >= 4 ? 3 : 4; }
+// Table width a decode kernel is compiled for, given the longest code word in use.  6: code words of up to 6 bits,
+// decoded two at a time with the pair table (the fused kernel only; the stand-alone decompressor uses its 7-bit build).
 constexpr int fused_table_bits(int longest) {
-    return longest <= 7 ? 7 : longest <= 8 ? 8 : longest <= 10 ? 10 : 12;
+    return longest <= 6 ? 6 : longest <= 7 ? 7 : longest <= 8 ? 8 : longest <= 10 ? 10 : 12;
 }
-// The fused kernel's own choice: it also has a 6-bit variant (five symbols per window; a 64-entry table fills one row
-// of LDS banks).
-constexpr int fused_attn_table_bits(int longest, int /*G*/) { return longest <= 6 ? 6 : fused_table_bits(longest); }
+constexpr int kPairTableEntries = 1 << 12;  // per tensor, 4 bytes each
 constexpr int kLdsBytesPerCU = 160 * 1024;
 // Bytes of one wave's LDS area next to its staging area.  Groups of 1 and 2 heads: fp32 weights [128][G].  Groups of
-// 4 and 8: the tile(s) of decoded symbols.
-constexpr size_t fused_weight_bytes(int G, int /*table_bits*/) {
-    return G >= 4 ? (size_t)kTileBytes : (size_t)G * kD * 4;
-}
-// LDS of one fused-kernel workgroup apart from the per-wave staging areas: two decode tables of 16-bit entries, the
-// query rows and the per-wave areas above.
+// 4 and 8: the area in which the A operand is laid out.
+constexpr size_t fused_weight_bytes(int G) { return G >= 4 ? (size_t)kTileBytes : (size_t)G * kD * 4; }
+// LDS of one fused-kernel workgroup apart from the per-wave areas: the two decode tables, the query rows, the merge flag.
 constexpr size_t fused_lds_fixed(int G, int longest) {
-    return ((size_t)4 << fused_attn_table_bits(longest, G)) + (size_t)G * kD * 4 +
-           4 * fused_weight_bytes(G, fused_attn_table_bits(longest, G)) + 512;
+    return (fused_table_bits(longest) == 6 ? (size_t)2 * kPairTableEntries * 4 : (size_t)4 << fused_table_bits(longest)) +
+           (size_t)G * kD * 4 + 512;
 }
 
 // ---- launches implemented in the .hip files ----
@@ -99,8 +98,8 @@ hipError_t launch_append(const Geo &g, const uint16_t *k_new, const uint16_t *v_
 // k_new / v_new != NULL: the newest of the n_res buffered tokens is still in k_new / v_new [B][H][128]; the kernel
 // reads it from there and stores it into its buffer slot (append fused into the launch)
 hipError_t launch_fused_attn(const Geo &g, const uint16_t *q, float scale, float *out, int n_blocks, int res_head,
-                             int n_res, const uint16_t *k_new, const uint16_t *v_new, int n_splits, int stage_bytes,
-                             hipEvent_t ev0, hipEvent_t ev1, hipStream_t s);
+                             int n_res, const uint16_t *k_new, const uint16_t *v_new, int n_splits, int n_waves,
+                             int stage_bytes, hipEvent_t ev0, hipEvent_t ev1, hipStream_t s);
 hipError_t launch_baseline_attn(int B, int H, int Hq, const uint16_t *K, const uint16_t *V, int seq, const uint16_t *q,
                                 float scale, float *out, float *partials, uint32_t *counters, int n_splits,
                                 hipStream_t s);
