@@ -450,8 +450,16 @@ __device__ __forceinline__ void join_all(const v16i &d, float (&out)[HL]) {
         out[HL > 2 ? 3 : 0] = join_digits<3>(d);
     }
 }
-constexpr int kARowK = kD + 4, kARowV = kBT + 4;  // bytes per row of the A operand while it is laid out in the tile area
-static_assert(32 * kARowK <= kTileBytes && 32 * kARowV <= kTileBytes, "A operand fits the tile area");
+// Bytes per row of the A operand while it is laid out in the tile area.  Only the three digit rows of every head are
+// stored: row 4 * head + digit of the operand sits at row a_row() of the area; the operand's remaining rows are zero.
+constexpr int kARowK = kARowBytes, kARowV = kBT + 4;
+// x = row of the A operand that a lane supplies -> its row in the area (rows without a digit read a neighbour's and
+// are cleared afterwards)
+template <int G>
+__device__ __forceinline__ int a_row(int x) {
+    const int xr = min(x, 4 * G - 1);
+    return 3 * (xr >> 2) + min(xr & 3, 2);
+}
 
 // K block.  hdr32: the record (LDS or global); tile: this wave's LDS area for laying out the A operand; qf: the query
 // rows in LDS.
@@ -504,13 +512,13 @@ __device__ __forceinline__ void k_tile_block(const uint32_t *hdr32, const char *
             transpose_digits(dg[0], dg[1], dg[2], dg[3], rows);
             const int head = hv + 2 * i;
 #pragma unroll
-            for (int j = 0; j < 3; j++) *reinterpret_cast<uint32_t *>(tile + (4 * head + j) * kARowK + 4 * x) = rows[j];
+            for (int j = 0; j < 3; j++) *reinterpret_cast<uint32_t *>(tile + (3 * head + j) * kARowK + 4 * x) = rows[j];
             cst[i] = half_sum(fmaf(128.f * inv, wsum, qm), upper);
         }
         wave_sync();
 #pragma unroll
         for (int ks = 0; ks < 8; ks++) {
-            a[ks] = lds_pair(tile + x * kARowK + 16 * ks + 8 * hv);
+            a[ks] = lds_pair(tile + a_row<G>(x) * kARowK + 16 * ks + 8 * hv);
             if ((x & 3) == 3 || x >= 4 * G) a[ks] = 0;  // rows that hold no digit
         }
         wave_sync();
@@ -614,14 +622,14 @@ __device__ __forceinline__ void v_tile_block(const uint32_t *hdr32, const char *
                 wsum += (float)W;
                 const uint32_t dg = signed_digits(W);
 #pragma unroll
-                for (int j = 0; j < 3; j++) tile[(4 * head + j) * kARowV + 32 * t + x] = (uint8_t)(dg >> (8 * j));
+                for (int j = 0; j < 3; j++) tile[(3 * head + j) * kARowV + 32 * t + x] = (uint8_t)(dg >> (8 * j));
             }
             ts.bv[i] += fmaf(128.f * inv, wsum, fmaf(p[i][0], mn[0], p[i][1] * mn[1]));
         }
         wave_sync();
 #pragma unroll
         for (int ks = 0; ks < 4; ks++) {
-            a[ks] = lds_pair(tile + x * kARowV + 16 * ks + 8 * hv);
+            a[ks] = lds_pair(tile + a_row<G>(x) * kARowV + 16 * ks + 8 * hv);
             if ((x & 3) == 3 || x >= 4 * G) a[ks] = 0;
         }
         wave_sync();
@@ -887,14 +895,14 @@ struct DirectStage {
     }
 };
 
-// One workgroup per CU, as many waves as the registers allow per SIMD: 4 (128 VGPRs) for groups of 1 and 2 query
-// heads, 3 (168) and 2 (256) for groups of 4 and 8.  The host may launch fewer waves per workgroup (short sequences,
+// One workgroup per CU, as many waves as the registers allow per SIMD (fused_waves_per_simd): 4 (128 VGPRs), 3 (168)
+// or 2 (256).  The host may launch fewer waves per workgroup (short sequences,
 // large staging areas).
-template <int G> struct MaxWaves { static constexpr int value = 4 * fused_waves_per_simd(G); };
+template <int G, int LB> struct MaxWaves { static constexpr int value = 4 * fused_waves_per_simd(G, LB); };
 
 // LB = the table width the kernel is compiled for (>= longest code word of both codebooks), see DecodeMode.
 template <int G, int LB>
-__global__ __launch_bounds__(64 * MaxWaves<G>::value, 1) void fused_attn_kernel(FusedArgs a) {
+__global__ __launch_bounds__((64 * MaxWaves<G, LB>::value), 1) void fused_attn_kernel(FusedArgs a) {
     using M = DecodeMode<LB>;
     constexpr bool kTile = G >= kTileMinG;  // packed symbols in registers, int8 MFMA
     __shared__ __attribute__((aligned(16))) uint8_t lut_s[2][M::kTableBytes];
@@ -906,7 +914,6 @@ __global__ __launch_bounds__(64 * MaxWaves<G>::value, 1) void fused_attn_kernel(
     const int n_waves = __builtin_amdgcn_readfirstlane(n_threads >> 6);
     uint8_t *stage = smem + (size_t)wave * a.stage_bytes;
     constexpr int kWeightBytes = (int)fused_weight_bytes(G);
-    static_assert(!kTile || kWeightBytes == kTileBytes, "tile area");
     float *wts = reinterpret_cast<float *>(smem + (size_t)n_waves * a.stage_bytes + (size_t)wave * kWeightBytes);
     const char *lutK = reinterpret_cast<const char *>(&lut_s[0][0]);
     const char *lutV = reinterpret_cast<const char *>(&lut_s[1][0]);
@@ -1092,7 +1099,7 @@ __global__ __launch_bounds__(64 * MaxWaves<G>::value, 1) void fused_attn_kernel(
         }
     }
 
-    if constexpr (kTile) tile_state_to_soft<G>(ts, reinterpret_cast<float *>(tile), lane, st);
+    if constexpr (kTile) tile_state_to_soft<G>(ts, reinterpret_cast<float *>(stage), lane, st);  // the record area is free now
     // the buffered fp16 tokens in units of 16: unit u goes to split n_splits-1 - u % n_splits (the last split is the
     // short one), there to the waves in turn, starting after the wave that took the split's last block
     if (a.n_res > 0) {
@@ -1160,7 +1167,7 @@ static hipError_t launch_fused_gn(const FusedArgs &a, int n_waves, size_t lds, h
         if (e != hipSuccess) return e;
         attr_set = lds;
     }
-    if (n_waves < 1 || n_waves > MaxWaves<G>::value) return hipErrorInvalidValue;
+    if (n_waves < 1 || n_waves > MaxWaves<G, LB>::value) return hipErrorInvalidValue;
     if (ev0) (void)hipEventRecord(ev0, s);
     hipLaunchKernelGGL((fused_attn_kernel<G, LB>), dim3(a.n_splits * a.g.B * a.g.H), dim3(64 * n_waves), lds, s, a);
     if (ev1) (void)hipEventRecord(ev1, s);

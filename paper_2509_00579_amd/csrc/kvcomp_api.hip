@@ -309,12 +309,13 @@ static kvcomp_status attn_impl(kvcomp_ctx *ctx, const void *d_q, float scale, fl
     stage = std::max(stage, 4608);
     stage = (int)align_up(stage, 16);
     const size_t per_wave_rest = fused_weight_bytes(g.G);
-    int max_waves = 4 * fused_waves_per_simd(g.G);
+    const int reg_waves = 4 * fused_waves_per_simd(g.G, fused_table_bits(longest));
+    int max_waves = reg_waves;
     if (ctx->tune_waves > 0) max_waves = std::min(max_waves, ctx->tune_waves);
     max_waves = std::max(1, std::min(max_waves, (int)((kLdsBytesPerCU - lds_fixed) / ((size_t)stage + per_wave_rest))));
     if (lds_fixed + (size_t)stage + per_wave_rest > (size_t)kLdsBytesPerCU)
         stage = (int)((kLdsBytesPerCU - lds_fixed - per_wave_rest) / 16 * 16);  // one wave, records above it from global memory
-    const int wgs_per_cu = std::max(1, std::min(4 * fused_waves_per_simd(g.G) / max_waves,
+    const int wgs_per_cu = std::max(1, std::min(reg_waves / max_waves,
                                                 (int)(kLdsBytesPerCU / (lds_fixed + max_waves * ((size_t)stage + per_wave_rest)))));
     int n_splits = ctx->tune_splits;
     if (n_splits <= 0) {

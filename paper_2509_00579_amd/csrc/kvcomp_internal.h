@@ -53,19 +53,22 @@ struct Geo {
 
 constexpr int kCUs = 256;  // compute units of the MI355X
 constexpr int kXCDs = 8;   // accelerator dies, each with its own L2; workgroups are dealt to them round-robin
-// Groups of 4 and 8 query heads: a wave decodes a block into an LDS tile of bytes and multiplies the tile with the
-// weights of all heads on int8 MFMA.
-// A wave's LDS area next to its staging area: the A operand (32 rows of 128 + 4 bytes) while it is laid out, and the
-// running state when it changes layout after the last block.
-constexpr int kTileBytes = 4352;
+// Groups of 4 and 8 query heads: a wave packs the decoded symbols of a block into registers and multiplies them with the
+// weights of all heads on int8 MFMA.  A wave's LDS area next to its staging area holds the A operand while it is laid
+// out: three digit rows per head, 128 + 4 bytes each.
+constexpr int kARowBytes = kD + 4;
+constexpr int tile_bytes(int G) { return 3 * G * kARowBytes; }
 // Both groups multiply after every half of a block (16 symbols of every decode chain), so that the products of the
 // first half run while the second half is decoded.  Groups of 4 recombine the result tiles after each half (few
 // registers: three waves per SIMD fit); groups of 8, whose lanes carry twice the heads through every recombination,
 // keep the integer accumulators across both halves and recombine once (two waves per SIMD).  2 = recombine once.
 constexpr int tile_halves_at_once(int G) { return G >= 8 ? 2 : 1; }
 // Waves of the fused kernel per SIMD, as the registers allow: groups of 4 and 8 query heads trade occupancy for
-// registers.  One workgroup per CU holds them all (4 SIMDs: 16, 12 or 8 waves).
-constexpr int fused_waves_per_simd(int G) { return G >= 8 ? 2 : G >= 4 ? 3 : 4; }
+// registers.  One workgroup per CU holds them all (4 SIMDs: up to 16 waves).
+// The pair-table kernels (longest code word <= 6 bits) keep fewer table entries in flight and fit one wave more.
+constexpr int fused_waves_per_simd(int G, int table_bits) {
+    return table_bits <= 6 ? (G >= 4 ? 3 : 4) : (G >= 8 ? 2 : G >= 4 ? 3 : 4);
+}
 // Table width a decode kernel is compiled for, given the longest code word in use.  6: code words of up to 6 bits,
 // decoded two at a time with the pair table (the fused kernel only; the stand-alone decompressor uses its 7-bit build).
 constexpr int fused_table_bits(int longest) {
@@ -75,7 +78,7 @@ constexpr int kPairTableEntries = 1 << 12;  // per tensor, 4 bytes each
 constexpr int kLdsBytesPerCU = 160 * 1024;
 // Bytes of one wave's LDS area next to its staging area.  Groups of 1 and 2 heads: fp32 weights [128][G].  Groups of
 // 4 and 8: the area in which the A operand is laid out.
-constexpr size_t fused_weight_bytes(int G) { return G >= 4 ? (size_t)kTileBytes : (size_t)G * kD * 4; }
+constexpr size_t fused_weight_bytes(int G) { return G >= 4 ? (size_t)tile_bytes(G) : (size_t)G * kD * 4; }
 // LDS of one fused-kernel workgroup apart from the per-wave areas: the two decode tables, the query rows, the merge flag.
 constexpr size_t fused_lds_fixed(int G, int longest) {
     return (fused_table_bits(longest) == 6 ? (size_t)2 * kPairTableEntries * 4 : (size_t)4 << fused_table_bits(longest)) +
