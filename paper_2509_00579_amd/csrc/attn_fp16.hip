@@ -28,7 +28,7 @@ template <int G>
 __device__ __forceinline__ void merge_waves_and_splits(const float (&comb)[kBWaves][G][kPartialStride],
                                                        float *__restrict__ partials, uint32_t *__restrict__ counters,
                                                        float *__restrict__ out, int b, int h, int Hq, int split, int bh,
-                                                       int tid) {
+                                                       int tid, int split_stride) {
     for (int i = tid; i < G * kD; i += 64 * kBWaves) {
         const int g = i / kD, c = i - g * kD;
         float M = -INFINITY;
@@ -43,13 +43,13 @@ __device__ __forceinline__ void merge_waves_and_splits(const float (&comb)[kBWav
         if (gridDim.x == 1) {
             out[((size_t)b * Hq + (size_t)h * G + g) * kD + c] = O / L;
         } else {
-            float *dst = partials + (((size_t)b * Hq + (size_t)h * G + g) * kMaxSplits + split) * kPartialStride;
+            float *dst = partials + (((size_t)b * Hq + (size_t)h * G + g) * split_stride + split) * kPartialStride;
             store_agent(dst + c, O);
             if (c == 0) { store_agent(dst + kD, M); store_agent(dst + kD + 1, L); }
         }
     }
     if (gridDim.x > 1)
-        finish_splits<G>(partials, counters + bh, b * Hq + h * G, (int)gridDim.x, out, tid, 64 * kBWaves);
+        finish_splits<G>(partials, counters + bh, b * Hq + h * G, (int)gridDim.x, out, tid, 64 * kBWaves, split_stride);
 }
 
 
@@ -64,7 +64,7 @@ __global__ __launch_bounds__(64 * kBWaves, 2) void baseline_attn_kernel(int B, i
                                                                          const uint16_t *__restrict__ q, float scale,
                                                                          float *__restrict__ partials,
                                                                          uint32_t *__restrict__ counters,
-                                                                         float *__restrict__ out, int tokens_per_split) {
+                                                                         float *__restrict__ out, int tokens_per_split, int split_stride) {
     __shared__ float comb[kBWaves][G][kPartialStride];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int split = blockIdx.x, bh = blockIdx.y, b = bh / H, h = bh - b * H;
@@ -176,7 +176,7 @@ __global__ __launch_bounds__(64 * kBWaves, 2) void baseline_attn_kernel(int B, i
         }
     }
     __syncthreads();
-    merge_waves_and_splits<G>(comb, partials, counters, out, b, h, Hq, split, bh, tid);
+    merge_waves_and_splits<G>(comb, partials, counters, out, b, h, Hq, split, bh, tid, split_stride);
 }
 
 // ---- groups of 4 and 8 query heads --------------------------------------------------------------------------------
@@ -204,7 +204,7 @@ template <int G>
 __global__ __launch_bounds__(64 * kBWaves, G == 8 ? 2 : 3) void baseline_attn_gqa_kernel(
     int B, int H, int Hq, const uint16_t *__restrict__ K, const uint16_t *__restrict__ V, int seq,
     const uint16_t *__restrict__ q, float scale, float *__restrict__ partials, uint32_t *__restrict__ counters,
-    float *__restrict__ out, int tokens_per_split) {
+    float *__restrict__ out, int tokens_per_split, int split_stride) {
     static_assert(G == 4 || G == 8, "group size");
     __shared__ float comb[kBWaves][G][kPartialStride];
     __shared__ __attribute__((aligned(16))) float p_s[kBWaves][64][G];  // numerators of the wave's current tokens
@@ -340,7 +340,7 @@ __global__ __launch_bounds__(64 * kBWaves, G == 8 ? 2 : 3) void baseline_attn_gq
         }
     }
     __syncthreads();
-    merge_waves_and_splits<G>(comb, partials, counters, out, b, h, Hq, split, bh, tid);
+    merge_waves_and_splits<G>(comb, partials, counters, out, b, h, Hq, split, bh, tid, split_stride);
 }
 
 // ---- a plain streaming read: the bound for any kernel that has to read the fp16 cache ---------------------------------
@@ -376,19 +376,28 @@ hipError_t launch_read_stream(const void *src, size_t bytes, uint32_t *sink, siz
     return hipGetLastError();
 }
 
+// Sequence splits that a launch really uses for `seq` tokens when n_splits are asked for (whole 64-token tiles).
+int baseline_splits(int seq, int n_splits) {
+    int tps = (seq + n_splits - 1) / n_splits;
+    tps = (tps + 63) / 64 * 64;
+    return (seq + tps - 1) / tps;
+}
+
+// split_stride: splits per query head that the layout of `partials` has room for (>= the splits used)
 hipError_t launch_baseline_attn(int B, int H, int Hq, const uint16_t *K, const uint16_t *V, int seq, const uint16_t *q,
                                 float scale, float *out, float *partials, uint32_t *counters, int n_splits,
-                                hipStream_t s) {
+                                int split_stride, hipStream_t s) {
     const int G = Hq / H;
     int tps = (seq + n_splits - 1) / n_splits;
     tps = (tps + 63) / 64 * 64;
     n_splits = (seq + tps - 1) / tps;
+    if (n_splits > split_stride) return hipErrorInvalidValue;
     const dim3 grid(n_splits, B * H), block(64 * kBWaves);
     switch (G) {
-        case 1: hipLaunchKernelGGL(baseline_attn_kernel<1>, grid, block, 0, s, B, H, Hq, K, V, seq, q, scale, partials, counters, out, tps); break;
-        case 2: hipLaunchKernelGGL(baseline_attn_kernel<2>, grid, block, 0, s, B, H, Hq, K, V, seq, q, scale, partials, counters, out, tps); break;
-        case 4: hipLaunchKernelGGL(baseline_attn_gqa_kernel<4>, grid, block, 0, s, B, H, Hq, K, V, seq, q, scale, partials, counters, out, tps); break;
-        case 8: hipLaunchKernelGGL(baseline_attn_gqa_kernel<8>, grid, block, 0, s, B, H, Hq, K, V, seq, q, scale, partials, counters, out, tps); break;
+        case 1: hipLaunchKernelGGL(baseline_attn_kernel<1>, grid, block, 0, s, B, H, Hq, K, V, seq, q, scale, partials, counters, out, tps, split_stride); break;
+        case 2: hipLaunchKernelGGL(baseline_attn_kernel<2>, grid, block, 0, s, B, H, Hq, K, V, seq, q, scale, partials, counters, out, tps, split_stride); break;
+        case 4: hipLaunchKernelGGL(baseline_attn_gqa_kernel<4>, grid, block, 0, s, B, H, Hq, K, V, seq, q, scale, partials, counters, out, tps, split_stride); break;
+        case 8: hipLaunchKernelGGL(baseline_attn_gqa_kernel<8>, grid, block, 0, s, B, H, Hq, K, V, seq, q, scale, partials, counters, out, tps, split_stride); break;
         default: return hipErrorInvalidValue;
     }
     return hipGetLastError();

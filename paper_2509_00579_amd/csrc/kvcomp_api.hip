@@ -562,31 +562,40 @@ kvcomp_status kvcomp_probe_read_stream(const void *d_buf, size_t bytes, void *d_
     return KVCOMP_OK;
 }
 
-kvcomp_status kvcomp_baseline_fp16_attn(const kvcomp_config *cfg, const void *d_K, const void *d_V, int seq,
-                                        const void *d_q, float scale, float *d_out, void *d_workspace,
-                                        size_t workspace_bytes, int n_splits, void *stream) {
-    if (!cfg || !d_K || !d_V || !d_q || !d_out || !d_workspace) return fail(KVCOMP_ERR_INVALID_ARG, "NULL argument");
+// arguments of the two comparison-kernel entry points; *n_splits receives the library's choice if it was 0
+static kvcomp_status baseline_check(const kvcomp_config *cfg, const void *d_K, const void *d_V, int seq, const void *d_q,
+                                    const float *d_out, int *n_splits) {
+    if (!cfg || !d_K || !d_V || !d_q || !d_out) return fail(KVCOMP_ERR_INVALID_ARG, "NULL argument");
     if (!aligned16(d_K) || !aligned16(d_V) || !aligned16(d_q)) return fail(KVCOMP_ERR_INVALID_ARG, "pointers must be 16-byte aligned");
     if (cfg->batch < 1 || cfg->n_kv_heads < 1 || cfg->n_q_heads % cfg->n_kv_heads || cfg->head_dim != kD)
         return fail(KVCOMP_ERR_INVALID_ARG, "invalid configuration");
     const int G = cfg->n_q_heads / cfg->n_kv_heads;
     if (G != 1 && G != 2 && G != 4 && G != 8) return fail(KVCOMP_ERR_INVALID_ARG, "group size must be 1, 2, 4 or 8");
     if (seq < 1) return fail(KVCOMP_ERR_INVALID_ARG, "seq must be positive");
-    if (workspace_bytes < kvcomp_baseline_workspace_bytes(cfg)) return fail(KVCOMP_ERR_CAPACITY, "workspace too small");
-    if (n_splits <= 0) {
+    if (*n_splits <= 0) {
         // measured best with one workgroup per CU (two for groups of 8 heads): every wave keeps 16 to 32 KiB in flight,
         // and more concurrent streams only cost locality in the memory system
         const int bh = cfg->batch * cfg->n_kv_heads;
         const int target = (G == 8 ? 2 : 1) * kCUs;
-        n_splits = std::min({(int)kMaxSplits, std::max(1, seq / 256), std::max(1, (target + bh - 1) / bh)});
+        *n_splits = std::min({(int)kMaxSplits, std::max(1, seq / 256), std::max(1, (target + bh - 1) / bh)});
     }
-    n_splits = std::max(1, std::min(n_splits, (int)kMaxSplits));
+    *n_splits = std::max(1, std::min(*n_splits, (int)kMaxSplits));
+    return KVCOMP_OK;
+}
+
+kvcomp_status kvcomp_baseline_fp16_attn(const kvcomp_config *cfg, const void *d_K, const void *d_V, int seq,
+                                        const void *d_q, float scale, float *d_out, void *d_workspace,
+                                        size_t workspace_bytes, int n_splits, void *stream) {
+    if (!d_workspace) return fail(KVCOMP_ERR_INVALID_ARG, "NULL argument");
+    kvcomp_status st = baseline_check(cfg, d_K, d_V, seq, d_q, d_out, &n_splits);
+    if (st) return st;
+    if (workspace_bytes < kvcomp_baseline_workspace_bytes(cfg)) return fail(KVCOMP_ERR_CAPACITY, "workspace too small");
     HIP_TRY(launch_baseline_attn(cfg->batch, cfg->n_kv_heads, cfg->n_q_heads, static_cast<const uint16_t *>(d_K),
                                  static_cast<const uint16_t *>(d_V), seq, static_cast<const uint16_t *>(d_q), scale, d_out,
                                  static_cast<float *>(d_workspace),
                                  reinterpret_cast<uint32_t *>(static_cast<float *>(d_workspace) +
                                                               (size_t)cfg->batch * cfg->n_q_heads * kMaxSplits * kPartialStride),
-                                 n_splits, static_cast<hipStream_t>(stream)));
+                                 n_splits, kMaxSplits, static_cast<hipStream_t>(stream)));
     return KVCOMP_OK;
 }
 

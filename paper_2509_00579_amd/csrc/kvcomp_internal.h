@@ -105,7 +105,8 @@ hipError_t launch_fused_attn(const Geo &g, const uint16_t *q, float scale, float
                              int stage_bytes, hipEvent_t ev0, hipEvent_t ev1, hipStream_t s);
 hipError_t launch_baseline_attn(int B, int H, int Hq, const uint16_t *K, const uint16_t *V, int seq, const uint16_t *q,
                                 float scale, float *out, float *partials, uint32_t *counters, int n_splits,
-                                hipStream_t s);
+                                int split_stride, hipStream_t s);
+int baseline_splits(int seq, int n_splits);
 hipError_t launch_read_stream(const void *src, size_t bytes, uint32_t *sink, size_t *bytes_read, hipStream_t s);
 hipError_t launch_stats(const Geo &g, int n_blocks, hipStream_t s);
 hipError_t launch_fill_zero(void *p, size_t bytes, hipStream_t s);

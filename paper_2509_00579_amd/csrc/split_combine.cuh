@@ -22,10 +22,10 @@ __device__ __forceinline__ float load_agent(const float *p) {
 }
 
 // Called by all threads of the workgroup after they have written this workgroup's partials with store_agent() to
-// partials[(row0 + g) * kMaxSplits + split].  nt = threads per workgroup.
+// partials[(row0 + g) * split_stride + split].  nt = threads per workgroup.
 template <int G>
 __device__ __forceinline__ void finish_splits(float *partials, uint32_t *counter, int row0, int n_splits, float *out,
-                                              int tid, int nt) {
+                                              int tid, int nt, int split_stride = kMaxSplits) {
     __shared__ uint32_t s_last;
     // every wave: all of its (write-through) partial stores have completed before the barrier is passed
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
@@ -42,7 +42,7 @@ __device__ __forceinline__ void finish_splits(float *partials, uint32_t *counter
     constexpr int kBatch = 16;
     for (int i = tid; i < G * kD; i += nt) {
         const int g = i / kD, c = i - g * kD;
-        const float *p = partials + (size_t)(row0 + g) * kMaxSplits * kPartialStride;
+        const float *p = partials + (size_t)(row0 + g) * split_stride * kPartialStride;
         float M = -INFINITY, L = 0.f, O = 0.f;
         for (int s0 = 0; s0 < n_splits; s0 += kBatch) {
             float ms[kBatch], ls[kBatch], os[kBatch];

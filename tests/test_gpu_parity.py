@@ -45,13 +45,14 @@ def _attn_close(o_gpu, o_ref):
     return err
 
 
-def _both(gpu, oracle, B, H, Hq, S_book, S, max_seq, rel_k, rel_v, seed):
-    """Build codebooks on the first S_book tokens and compress S tokens on both sides."""
+def _both(gpu, oracle, B, H, Hq, S_book, S, max_seq, rel_k, rel_v, seed, limit=12):
+    """Build codebooks on the first S_book tokens and compress S tokens on both sides (code words of up to `limit`
+    bits; 12 is the library's default)."""
     Kx, Vx = W.make_kv(B, H, max(S_book, S), seed)
-    oc = oracle.OracleCache(B, H, Hq, max_seq, rel_k, rel_v)
+    oc = oracle.OracleCache(B, H, Hq, max_seq, rel_k, rel_v, 0, limit)
     oc.build_codebook(Kx[:, :S_book], Vx[:, :S_book])
     oc.compress_blocks(Kx[:, :S], Vx[:, :S])
-    gc = gpu.KVCompCache(B, H, Hq, max_seq, rel_k, rel_v)
+    gc = gpu.KVCompCache(B, H, Hq, max_seq, rel_k, rel_v, max_code_len=limit)
     gc.build_codebook(_dev(Kx[:, :S_book]), _dev(Vx[:, :S_book]))
     gc.compress_blocks(_dev(Kx[:, :S]), _dev(Vx[:, :S]))
     return Kx, Vx, oc, gc
@@ -103,7 +104,8 @@ def test_codes_minmax_histogram_codebook(gpu, oracle, B, H, S, rel):
 def test_config0_end_to_end(gpu, oracle):
     w = W.CONFIGS["c0"]
     _say("config 0: compress + one decode step")
-    Kx, Vx, oc, gc = _both(gpu, oracle, w.batch, w.n_kv_heads, w.n_q_heads, w.seq, w.seq, w.seq, w.rel_eb, w.rel_eb, w.seed)
+    Kx, Vx, oc, gc = _both(gpu, oracle, w.batch, w.n_kv_heads, w.n_q_heads, w.seq, w.seq, w.seq, w.rel_eb, w.rel_eb, w.seed,
+                           limit=W.CODE_LEN_LIMIT[w.rel_eb])
     _assert_same_cache(oc, gc)
     q = W.make_queries(w.batch, w.n_q_heads, 1, w.seed)[0]
     out = gc.attn_decode(_dev(q), SCALE).cpu().numpy()
@@ -632,7 +634,8 @@ def test_config1_full_size_sampled(gpu, oracle):
     """The benchmark workload (32 heads x 4096 tokens) in the launch configuration bench.py times."""
     w = W.CONFIGS["c1"]
     _say("config 1 full size: records sampled, attention on every head")
-    Kx, Vx, oc, gc = _both(gpu, oracle, w.batch, w.n_kv_heads, w.n_q_heads, w.seq, w.seq, w.seq, w.rel_eb, w.rel_eb, w.seed)
+    Kx, Vx, oc, gc = _both(gpu, oracle, w.batch, w.n_kv_heads, w.n_q_heads, w.seq, w.seq, w.seq, w.rel_eb, w.rel_eb, w.seed,
+                           limit=W.CODE_LEN_LIMIT[w.rel_eb])
     _assert_same_cache(oc, gc, sample=200)
     qs = W.make_queries(w.batch, w.n_q_heads, 2, w.seed)
     for i in range(2):
@@ -804,7 +807,7 @@ def test_stand_alone_decompression(gpu, oracle, B, H, S, k_mode, max_len):
 @pytest.mark.parametrize("name,rel", [("c2", 1e-2), ("c2", 5e-3), ("c2", 2e-2), ("c3", 1e-2), ("c4", 1e-2)])
 def test_large_configs_full_size_sampled(gpu, oracle, name, rel):
     """The long-context (with its error-bound sweep), grouped-query and 70B-shaped workloads at their full prompt
-    size, in the launch configuration bench.py times (automatic splits, 7-bit code word limit).  The oracle quantizes
+    size, in the launch configuration bench.py times (automatic splits, the code word limit of workloads.CODE_LEN_LIMIT).  The oracle quantizes
     the whole tensors (the codebooks depend on all of it); records are compared on a sample of blocks and the
     attention output on five (batch, kv head) pairs -- the two ends and three from the middle of the range, so that
     every part of the kernel's workgroup numbering is covered -- which the oracle recomputes from its own compressed
@@ -813,9 +816,10 @@ def test_large_configs_full_size_sampled(gpu, oracle, name, rel):
     assert rel in W.C2_REL_EB_SWEEP and (name == "c2" or rel == w.rel_eb)
     B, H, Hq, S = w.batch, w.n_kv_heads, w.n_q_heads, w.seq
     G = Hq // H
-    _say(f"{name} full size: B={B} H={H} Hq={Hq} S={S} rel_eb={rel}")
+    limit = W.CODE_LEN_LIMIT[rel]
+    _say(f"{name} full size: B={B} H={H} Hq={Hq} S={S} rel_eb={rel} code words <= {limit} bits")
     Kx, Vx = W.make_kv(B, H, S, w.seed)
-    gc = gpu.KVCompCache(B, H, Hq, S + 64, rel, rel, max_code_len=7)
+    gc = gpu.KVCompCache(B, H, Hq, S + 64, rel, rel, max_code_len=limit)
     dK, dV = _dev(Kx), _dev(Vx)
     gc.build_codebook(dK, dV)
     gc.compress_blocks(dK, dV)
@@ -827,7 +831,7 @@ def test_large_configs_full_size_sampled(gpu, oracle, name, rel):
         codes[which], mms[which] = oracle.tensor_quantize(which, X, rel)
         hist = oracle.histogram(codes[which])
         np.testing.assert_array_equal(gc.histogram(which).astype(np.uint64), hist)
-        ln, cd, _ = oracle.build_codebook(hist, oracle.n_sym(rel), 7)
+        ln, cd, _ = oracle.build_codebook(hist, oracle.n_sym(rel), limit)
         ln_g, cd_g = gc.codebook(which)
         np.testing.assert_array_equal(ln_g, ln)
         np.testing.assert_array_equal(cd_g, cd)
@@ -848,7 +852,7 @@ def test_large_configs_full_size_sampled(gpu, oracle, name, rel):
     BH = B * H
     pairs = sorted({0, BH - 1, BH // 2, BH // 3 + 1, (5 * BH) // 8 + 2})
     for b, h in ((i // H, i % H) for i in pairs):
-        oc = oracle.OracleCache(1, 1, G, S + 64 + w.append_steps, rel, rel, 0, 7)
+        oc = oracle.OracleCache(1, 1, G, S + 64 + w.append_steps, rel, rel, 0, limit)
         oc.len, oc.code = [book[K][0], book[V][0]], [book[K][1], book[V][1]]
         oc.compress_blocks(np.ascontiguousarray(Kx[b:b + 1, :, h:h + 1]), np.ascontiguousarray(Vx[b:b + 1, :, h:h + 1]))
         ref = oc.attn_decode(np.ascontiguousarray(q[b:b + 1, h * G:(h + 1) * G]), SCALE)
@@ -862,7 +866,7 @@ def test_large_configs_full_size_sampled(gpu, oracle, name, rel):
     # with the prompt's codebooks) and attends; the sampled heads are followed by oracle caches of their own
     T = w.append_steps
     _say(f"  streaming: {T} decode steps")
-    gc = gpu.KVCompCache(B, H, Hq, S + T, rel, rel, max_code_len=7)
+    gc = gpu.KVCompCache(B, H, Hq, S + T, rel, rel, max_code_len=limit)
     dK, dV = _dev(Kx), _dev(Vx)
     gc.build_codebook(dK, dV)
     gc.compress_blocks(dK, dV)

@@ -56,6 +56,10 @@ CONFIGS = {
                    append_steps=512),
 }
 C2_REL_EB_SWEEP = (5e-3, 1e-2, 2e-2)
+# Longest Huffman code word that bench.py and the full-size parity tests allow for each error bound of the workloads
+# (a parameter of the codec like the error bound itself; the library's own default is 12): the width of a fixed-length
+# code of that bound's quantization levels (101, 51, 26 levels), but at least 6 bits.
+CODE_LEN_LIMIT = {5e-3: 7, 1e-2: 6, 2e-2: 6}
 
 
 def make_kv(batch: int, n_kv_heads: int, seq: int, seed: int):
