@@ -206,6 +206,19 @@ kvcomp_status kvcomp_baseline_fp16_attn(const kvcomp_config *cfg, const void *d_
                                         const void *d_q, float scale, float *d_out, void *d_workspace,
                                         size_t workspace_bytes, int n_splits, void *stream);
 
+/* kvcomp_baseline_fp16_attn for callers that cannot allocate or hand over a workspace (code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc): same arguments without the workspace, same result.  The split
+ * tickets and split partials live in a static device array of the library, 4 MiB per GPU that the library runs on,
+ * held until the process ends (64 KiB of tickets, the rest partials laid out for the splits the call really uses).
+ * The call allocates nothing and launches one kernel.  Limits: batch * n_kv_heads <= 16384 and
+ * batch * n_q_heads * splits * 520 bytes <= 4 MiB - 64 KiB, where splits = n_splits (0 = the library's choice)
+ * after rounding the split length up to whole 64-token tiles; beyond that: KVCOMP_ERR_CAPACITY and nothing is
+ * launched.  All calls on one GPU share the array: two of them must not overlap in time (on different streams, or
+ * from two threads), or they race on the tickets and partials; calls on one stream are safe back to back.
+ * Stream-ordered. */
+kvcomp_status kvcomp_baseline_fp16_attn_noalloc(const kvcomp_config *cfg, const void *d_K, const void *d_V, int seq,
+                                                const void *d_q, float scale, float *d_out, int n_splits, void *stream);
+
 /* Measurement aid: one plain streaming read of d_buf (DEVICE, 16-byte aligned) with 16-byte loads, the bound for any
  * kernel that has to read an uncompressed cache of that size.  Up to 2048 workgroups read a whole number of 32 KiB pieces each,
  * as much as fits into `bytes` (*h_bytes_read receives the total; 0 = nothing launched) and writes nothing; d_sink: DEVICE, 4 bytes, needed only so

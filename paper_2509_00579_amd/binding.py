@@ -65,6 +65,7 @@ SIGNATURES = {
     "kvcomp_probe_read_stream": (_i, [_vp, C.c_size_t, _vp, C.POINTER(C.c_size_t), _vp]),
     "kvcomp_baseline_workspace_bytes": (C.c_size_t, [_cfgp]),
     "kvcomp_baseline_fp16_attn": (_i, [_cfgp, _vp, _vp, _i, _vp, _f, _vp, _vp, C.c_size_t, _i, _vp]),
+    "kvcomp_baseline_fp16_attn_noalloc": (_i, [_cfgp, _vp, _vp, _i, _vp, _f, _vp, _i, _vp]),
     "kvcomp_last_error": (C.c_char_p, []),
 }
 
@@ -315,4 +316,15 @@ class BaselineFp16Attention:
                                                   _dev_fp16(q, (self.B, self.Hq, D)), float(scale),
                                                   C.c_void_p(out.data_ptr()), C.c_void_p(self.ws.data_ptr()),
                                                   self.ws.numel(), n_splits, _stream()))
+        return out
+
+    def noalloc(self, Kt, Vt, q, scale, out, n_splits=0):
+        """The same through kvcomp_baseline_fp16_attn_noalloc: no workspace, the library's static scratch; `out` is
+        the caller's."""
+        S = Kt.shape[1]
+        shape = (self.B, S, self.H, D)
+        assert out.is_cuda and out.dtype == torch.float32 and out.is_contiguous()
+        _check(self.lib.kvcomp_baseline_fp16_attn_noalloc(C.byref(self.cfg), _dev_fp16(Kt, shape), _dev_fp16(Vt, shape), S,
+                                                          _dev_fp16(q, (self.B, self.Hq, D)), float(scale),
+                                                          C.c_void_p(out.data_ptr()), n_splits, _stream()))
         return out

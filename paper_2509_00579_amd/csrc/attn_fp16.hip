@@ -5,6 +5,8 @@
 // several heads, a small matrix product) on the matrix cores.
 #include <hip/hip_fp16.h>
 
+#include <mutex>
+
 #include "huff_decode.cuh"
 #include "kvcomp_internal.h"
 #include "split_combine.cuh"
@@ -374,6 +376,44 @@ hipError_t launch_read_stream(const void *src, size_t bytes, uint32_t *sink, siz
     hipLaunchKernelGGL(read_stream_kernel, dim3((unsigned)grid), dim3(256), 0, s, static_cast<const uint4 *>(src),
                        per_wg / 16, sink);
     return hipGetLastError();
+}
+
+// ---- scratch of the entry point that allocates nothing ---------------------------------------------------------
+// kvcomp_baseline_fp16_attn_noalloc keeps the split tickets and the split partials in this array instead of a
+// caller's workspace.  Every GPU holds its own copy at its own address until the process ends.  Layout: tickets (one
+// per (batch, kv head), zero between launches: the merging workgroup resets its ticket) in the first
+// kStaticTicketBytes, the partials [batch * q heads][splits used][130] fp32 behind them.
+constexpr size_t kStaticTicketBytes = 64 * 1024;    // 16384 (batch, kv head) pairs
+constexpr size_t kStaticScratchBytes = 4u << 20;    // tickets + partials
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+// Device address of `scratch` on the current device (the array's name is a host-side stand-in, not an address that a
+// kernel may be given), looked up once per device.
+hipError_t baseline_static_scratch(uint32_t **tickets, float **partials, size_t *max_tickets, size_t *partial_bytes) {
+    constexpr int kMaxDevices = 64;
+    static std::mutex mu;
+    static unsigned char *per_device[kMaxDevices] = {};
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    unsigned char *ptr;
+    {
+        std::lock_guard<std::mutex> lock(mu);
+        if (!per_device[dev]) {
+            void *p = nullptr;
+            e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+            if (e != hipSuccess) return e;
+            if (!p) return hipErrorInvalidSymbol;
+            per_device[dev] = static_cast<unsigned char *>(p);
+        }
+        ptr = per_device[dev];
+    }
+    *tickets = reinterpret_cast<uint32_t *>(ptr);
+    *partials = reinterpret_cast<float *>(ptr + kStaticTicketBytes);
+    *max_tickets = kStaticTicketBytes / sizeof(uint32_t);
+    *partial_bytes = kStaticScratchBytes - kStaticTicketBytes;
+    return hipSuccess;
 }
 
 // Sequence splits that a launch really uses for `seq` tokens when n_splits are asked for (whole 64-token tiles).

@@ -599,4 +599,27 @@ kvcomp_status kvcomp_baseline_fp16_attn(const kvcomp_config *cfg, const void *d_
     return KVCOMP_OK;
 }
 
+kvcomp_status kvcomp_baseline_fp16_attn_noalloc(const kvcomp_config *cfg, const void *d_K, const void *d_V, int seq,
+                                                const void *d_q, float scale, float *d_out, int n_splits, void *stream) {
+    kvcomp_status st = baseline_check(cfg, d_K, d_V, seq, d_q, d_out, &n_splits);
+    if (st) return st;
+    uint32_t *tickets = nullptr;
+    float *partials = nullptr;
+    size_t max_tickets = 0, partial_bytes = 0;
+    HIP_TRY(baseline_static_scratch(&tickets, &partials, &max_tickets, &partial_bytes));
+    // the partials are laid out for the splits this launch really uses, not for the maximum
+    const int used = baseline_splits(seq, n_splits);
+    const size_t bh = (size_t)cfg->batch * cfg->n_kv_heads;
+    const size_t need = (size_t)cfg->batch * cfg->n_q_heads * used * kPartialStride * sizeof(float);
+    if (bh > max_tickets || need > partial_bytes)
+        return fail(KVCOMP_ERR_CAPACITY,
+                    "%zu (batch, kv head) pairs and %zu bytes of split partials (%d splits) exceed the static scratch "
+                    "(%zu pairs, %zu bytes): use kvcomp_baseline_fp16_attn with a workspace, or fewer splits",
+                    bh, need, used, max_tickets, partial_bytes);
+    HIP_TRY(launch_baseline_attn(cfg->batch, cfg->n_kv_heads, cfg->n_q_heads, static_cast<const uint16_t *>(d_K),
+                                 static_cast<const uint16_t *>(d_V), seq, static_cast<const uint16_t *>(d_q), scale, d_out,
+                                 partials, tickets, n_splits, used, static_cast<hipStream_t>(stream)));
+    return KVCOMP_OK;
+}
+
 }  // extern "C"

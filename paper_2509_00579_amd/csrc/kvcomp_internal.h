@@ -107,6 +107,8 @@ hipError_t launch_baseline_attn(int B, int H, int Hq, const uint16_t *K, const u
                                 float scale, float *out, float *partials, uint32_t *counters, int n_splits,
                                 int split_stride, hipStream_t s);
 int baseline_splits(int seq, int n_splits);
+// the static device array behind kvcomp_baseline_fp16_attn_noalloc, on the current device
+hipError_t baseline_static_scratch(uint32_t **tickets, float **partials, size_t *max_tickets, size_t *partial_bytes);
 hipError_t launch_read_stream(const void *src, size_t bytes, uint32_t *sink, size_t *bytes_read, hipStream_t s);
 hipError_t launch_stats(const Geo &g, int n_blocks, hipStream_t s);
 hipError_t launch_fill_zero(void *p, size_t bytes, hipStream_t s);
