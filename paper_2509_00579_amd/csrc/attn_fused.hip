@@ -528,26 +528,23 @@ __device__ __forceinline__ void k_tile_block(const uint32_t *hdr32, const char *
     const uint32_t *wm1 = hdr32 + (kmm + 2 * kSlices) / 4 - 1;
     Quad<DecodeMode<LB>::J> qd;
     qd.open(wm1, start, sb & 0xffffu, sb >> 16);
-    constexpr bool kBoth = tile_halves_at_once(G) == 2;  // one recombination per block instead of one per half
+    constexpr bool kBoth = tile_halves_at_once(G, LB) == 2;  // one recombination per block instead of one per half
     float sc[HL][2];
     v16i d[2];  // result tiles: tokens 0..31 and 32..63
     ChainSyms<DecodeMode<LB>::kLookupsPerChain> syms;
     SliceWords pw;  // lane = token: slice a = its channels 0..63, slice b = its channels 64..127
     // one step of 16 channels of either slice: steps 0..3 are channels 0..63, steps 4..7 channels 64..127
-    auto products = [&](int ks) {
+    // fresh: the result tiles start at zero (the matrix instruction takes the constant as its addend: no register
+    // is cleared)
+    auto products = [&](int ks, bool fresh) {
+        const v16i zero = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
         long t0, t1;
         step_operands(pw.a[4 * ks], pw.a[4 * ks + 1], pw.a[4 * ks + 2], pw.a[4 * ks + 3], t0, t1);
-        d[0] = __builtin_amdgcn_mfma_i32_32x32x16_i8(a[ks], t0, d[0], 0, 0, 0);
-        d[1] = __builtin_amdgcn_mfma_i32_32x32x16_i8(a[ks], t1, d[1], 0, 0, 0);
+        d[0] = __builtin_amdgcn_mfma_i32_32x32x16_i8(a[ks], t0, fresh ? zero : d[0], 0, 0, 0);
+        d[1] = __builtin_amdgcn_mfma_i32_32x32x16_i8(a[ks], t1, fresh ? zero : d[1], 0, 0, 0);
         step_operands(pw.b[4 * ks], pw.b[4 * ks + 1], pw.b[4 * ks + 2], pw.b[4 * ks + 3], t0, t1);
         d[0] = __builtin_amdgcn_mfma_i32_32x32x16_i8(a[4 + ks], t0, d[0], 0, 0, 0);
         d[1] = __builtin_amdgcn_mfma_i32_32x32x16_i8(a[4 + ks], t1, d[1], 0, 0, 0);
-    };
-    auto clear = [&] {
-#pragma unroll
-        for (int t = 0; t < 2; t++)
-#pragma unroll
-            for (int k = 0; k < 16; k++) d[t][k] = 0;
     };
     auto join = [&](bool first) {
 #pragma unroll
@@ -563,16 +560,14 @@ __device__ __forceinline__ void k_tile_block(const uint32_t *hdr32, const char *
     // The products of the first half run while the second half is decoded (no fence in between: everything is in
     // registers).
     decode_span<LB, 0, kP>(qd, wm1, lut, mask2, syms, pw);
-    clear();
-    products(0);
-    products(3);
+    products(0, true);
+    products(3, false);
     if constexpr (!kBoth) join(true);
     decode_span<LB, kP, kHalf>(qd, wm1, lut, mask2, syms, pw);
     wave_sync();
     record_done();
-    if constexpr (!kBoth) clear();
-    products(1);
-    products(2);
+    products(1, !kBoth);
+    products(2, false);
     join(kBoth);
 #pragma unroll
     for (int i = 0; i < HL; i++) {
@@ -643,25 +638,20 @@ __device__ __forceinline__ void v_tile_block(const uint32_t *hdr32, const char *
     const uint32_t *wm1 = hdr32 + kHdrBytesV / 4 - 1;
     Quad<DecodeMode<LB>::J> qd;
     qd.open2(wm1, start_a, abits, start_b, bbits);
-    constexpr bool kBoth = tile_halves_at_once(G) == 2;
+    constexpr bool kBoth = tile_halves_at_once(G, LB) == 2;
     v16i d[4];  // result tiles: channels 0..31, 32..63 (slice a), 64..95, 96..127 (slice b)
     ChainSyms<DecodeMode<LB>::kLookupsPerChain> syms;
     SliceWords pw;
     // one step of 16 tokens of both slices
-    auto products = [&](int ks) {
+    auto products = [&](int ks, bool fresh) {   // fresh: the result tiles start at zero
+        const v16i zero = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
         long t0, t1;
         step_operands(pw.a[4 * ks], pw.a[4 * ks + 1], pw.a[4 * ks + 2], pw.a[4 * ks + 3], t0, t1);
-        d[0] = __builtin_amdgcn_mfma_i32_32x32x16_i8(a[ks], t0, d[0], 0, 0, 0);
-        d[1] = __builtin_amdgcn_mfma_i32_32x32x16_i8(a[ks], t1, d[1], 0, 0, 0);
+        d[0] = __builtin_amdgcn_mfma_i32_32x32x16_i8(a[ks], t0, fresh ? zero : d[0], 0, 0, 0);
+        d[1] = __builtin_amdgcn_mfma_i32_32x32x16_i8(a[ks], t1, fresh ? zero : d[1], 0, 0, 0);
         step_operands(pw.b[4 * ks], pw.b[4 * ks + 1], pw.b[4 * ks + 2], pw.b[4 * ks + 3], t0, t1);
-        d[2] = __builtin_amdgcn_mfma_i32_32x32x16_i8(a[ks], t0, d[2], 0, 0, 0);
-        d[3] = __builtin_amdgcn_mfma_i32_32x32x16_i8(a[ks], t1, d[3], 0, 0, 0);
-    };
-    auto clear = [&] {
-#pragma unroll
-        for (int ct = 0; ct < 4; ct++)
-#pragma unroll
-            for (int k = 0; k < 16; k++) d[ct][k] = 0;
+        d[2] = __builtin_amdgcn_mfma_i32_32x32x16_i8(a[ks], t0, fresh ? zero : d[2], 0, 0, 0);
+        d[3] = __builtin_amdgcn_mfma_i32_32x32x16_i8(a[ks], t1, fresh ? zero : d[3], 0, 0, 0);
     };
     auto join = [&] {
 #pragma unroll
@@ -674,16 +664,14 @@ __device__ __forceinline__ void v_tile_block(const uint32_t *hdr32, const char *
     };
     constexpr int kP = tile_first_span(DecodeMode<LB>::kSymsPerWindow);
     decode_span<LB, 0, kP>(qd, wm1, lut, mask2, syms, pw);
-    clear();
-    products(0);
-    products(3);
+    products(0, true);
+    products(3, false);
     if constexpr (!kBoth) join();
     decode_span<LB, kP, kHalf>(qd, wm1, lut, mask2, syms, pw);
     wave_sync();
     record_done();
-    if constexpr (!kBoth) clear();
-    products(1);
-    products(2);
+    products(1, !kBoth);
+    products(2, false);
     join();
 }
 

@@ -59,10 +59,10 @@ constexpr int kXCDs = 8;   // accelerator dies, each with its own L2; workgroups
 constexpr int kARowBytes = kD + 4;
 constexpr int tile_bytes(int G) { return 3 * G * kARowBytes; }
 // Both groups multiply after every half of a block (16 symbols of every decode chain), so that the products of the
-// first half run while the second half is decoded.  Groups of 4 recombine the result tiles after each half (few
-// registers: three waves per SIMD fit); groups of 8, whose lanes carry twice the heads through every recombination,
-// keep the integer accumulators across both halves and recombine once (two waves per SIMD).  2 = recombine once.
-constexpr int tile_halves_at_once(int G) { return G >= 8 ? 2 : 1; }
+// first half run while the second half is decoded, and recombine the result tiles after each half.  Groups of 8 on the
+// kernels with two waves per SIMD (single-symbol tables), where registers are plentiful, keep the integer accumulators
+// across both halves and recombine once.  2 = recombine once.
+constexpr int tile_halves_at_once(int G, int table_bits) { return G >= 8 && table_bits > 6 ? 2 : 1; }
 // Waves of the fused kernel per SIMD, as the registers allow: groups of 4 and 8 query heads trade occupancy for
 // registers.  One workgroup per CU holds them all (4 SIMDs: up to 16 waves).
 // The pair-table kernels (longest code word <= 6 bits) keep fewer table entries in flight and fit one wave more.
