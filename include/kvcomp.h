@@ -119,6 +119,19 @@ kvcomp_status kvcomp_build_codebook(kvcomp_ctx *ctx, const void *d_K, const void
  * Errors: STATE (no codebook / cache not empty), CAPACITY (seq > max_seq), NONFINITE, HIP. */
 kvcomp_status kvcomp_compress_blocks(kvcomp_ctx *ctx, const void *d_K, const void *d_V, int seq, void *stream);
 
+/* kvcomp_build_codebook followed by kvcomp_compress_blocks on the same tensors as one call (Section 3: the Store stage
+ * at prefill), with ONE quantization pass instead of three: the histogram pass keeps the quantization codes (one byte
+ * per value) and the unit min/max in d_workspace, and the size and write passes of the encoder read those instead of
+ * loading and quantizing the fp16 input again.  Same cache contents, byte for byte, as the two calls.  d_workspace:
+ * DEVICE, caller-owned, 16-byte aligned, at least kvcomp_prefill_workspace_bytes(cfg, seq) bytes (about half the size
+ * of K and V together); it is scratch and may be freed or reused once the call has returned.  The cache must be empty.
+ * SYNCHRONISES `stream` twice (histogram to the host; arena tail, largest record and flags at the end).
+ * Errors: INVALID_ARG (seq < 64 or > max_seq, alignment), STATE (cache not empty), CAPACITY (workspace too small),
+ * NONFINITE, HIP. */
+size_t kvcomp_prefill_workspace_bytes(const kvcomp_config *cfg, int seq);
+kvcomp_status kvcomp_prefill(kvcomp_ctx *ctx, const void *d_K, const void *d_V, int seq, void *d_workspace,
+                             size_t workspace_bytes, void *stream);
+
 /* Decode-phase store (Section 3.2.1, Section 3.2.3): append one token per sequence.  d_k_new, d_v_new: device fp16
  * [batch, n_kv_heads, 128].  The token is copied into the fp16 buffer; the call that fills the buffer's last slot
  * compresses the buffer's oldest 64 tokens as one block for every (batch, head) with the existing codebooks and

@@ -47,6 +47,8 @@ SIGNATURES = {
     "kvcomp_reset": (_i, [_vp, _i, _vp]),
     "kvcomp_build_codebook": (_i, [_vp, _vp, _vp, _i, _vp]),
     "kvcomp_compress_blocks": (_i, [_vp, _vp, _vp, _i, _vp]),
+    "kvcomp_prefill_workspace_bytes": (C.c_size_t, [_cfgp, _i]),
+    "kvcomp_prefill": (_i, [_vp, _vp, _vp, _i, _vp, C.c_size_t, _vp]),
     "kvcomp_append_token": (_i, [_vp, _vp, _vp, _vp]),
     "kvcomp_attn_decode": (_i, [_vp, _vp, _f, _vp, _vp]),
     "kvcomp_append_attn_decode": (_i, [_vp, _vp, _vp, _vp, _f, _vp, _vp]),
@@ -156,6 +158,20 @@ class KVCompCache:
         S = Kt.shape[1]
         shape = (self.B, S, self.H, D)
         _check(self.lib.kvcomp_compress_blocks(self.h, _dev_fp16(Kt, shape), _dev_fp16(Vt, shape), S, _stream()))
+
+    def prefill_workspace_bytes(self, S):
+        return self.lib.kvcomp_prefill_workspace_bytes(C.byref(self.cfg), S)
+
+    def prefill(self, Kt, Vt, workspace=None):
+        """build_codebook + compress_blocks with one quantization pass; `workspace`: a uint8 CUDA tensor of at least
+        prefill_workspace_bytes(S) bytes (allocated here if None)."""
+        S = Kt.shape[1]
+        shape = (self.B, S, self.H, D)
+        if workspace is None:
+            workspace = torch.empty(self.prefill_workspace_bytes(S), dtype=torch.uint8, device=self.device)
+        assert workspace.is_cuda and workspace.dtype == torch.uint8 and workspace.is_contiguous()
+        _check(self.lib.kvcomp_prefill(self.h, _dev_fp16(Kt, shape), _dev_fp16(Vt, shape), S,
+                                       C.c_void_p(workspace.data_ptr()), workspace.numel(), _stream()))
 
     def append_token(self, k_new, v_new):
         shape = (self.B, self.H, D)

@@ -39,10 +39,31 @@ __device__ __forceinline__ uint32_t block_sum(uint32_t v, uint32_t *scratch, int
     return scratch[0] + scratch[1] + scratch[2] + scratch[3];
 }
 
+// Codes and unit min/max that an earlier pass kept (launch_histogram with a workspace): where the encode kernels find
+// them instead of quantizing the input.  Blocks are numbered bh * blk_per_bh + j there.
+struct Kept {
+    const uint8_t *codes;    // [block][64][128]
+    const uint32_t *minmax;  // [block][units] {min,max} fp16 pairs
+    int blk_per_bh;
+};
+// this thread's codes of block `src` (thread map of tile_quant.cuh)
+__device__ __forceinline__ void load_kept_codes(const Kept &kept, size_t src, int tid, TileRegs &r) {
+    const int c0 = tile_chan0(tid);
+#pragma unroll
+    for (int i = 0; i < 4; i++) {
+        const uint2 pk = *reinterpret_cast<const uint2 *>(kept.codes + src * kTile + tile_token(tid, i) * kD + c0);
+#pragma unroll
+        for (int k = 0; k < 4; k++) {
+            r.code[i][k] = (pk.x >> (8 * k)) & 0xffu;
+            r.code[i][4 + k] = (pk.y >> (8 * k)) & 0xffu;
+        }
+    }
+}
+
 // ---- 1. size pass ------------------------------------------------------------------------------------------
-template <int WHICH>
+template <int WHICH, bool KEPT>
 __global__ __launch_bounds__(256) void size_kernel(Geo g, const uint16_t *__restrict__ X, int seq_stride,
-                                                    int n_blk_per_bh, int dst_blk0) {
+                                                    int n_blk_per_bh, int dst_blk0, Kept kept) {
     __shared__ QuantShared sh;
     __shared__ uint32_t enc[256];
     __shared__ uint32_t scratch[4];
@@ -50,8 +71,14 @@ __global__ __launch_bounds__(256) void size_kernel(Geo g, const uint16_t *__rest
     const int bh = blk / n_blk_per_bh, j = blk - bh * n_blk_per_bh;
     enc[tid] = g.enc[WHICH * 512 + tid];
     TileRegs r;
-    const bool bad = load_tile(X, seq_stride, g.H, bh / g.H, bh % g.H, j, tid, r);
-    quantize_tile<WHICH>(r, sh, tid, g.two_eb[WHICH], g.n_sym[WHICH], g.k_units);  // has barriers: enc[] is visible after it
+    bool bad = false;
+    if constexpr (KEPT) {
+        load_kept_codes(kept, (size_t)bh * kept.blk_per_bh + j, tid, r);
+        __syncthreads();  // enc[] is visible
+    } else {
+        bad = load_tile(X, seq_stride, g.H, bh / g.H, bh % g.H, j, tid, r);
+        quantize_tile<WHICH>(r, sh, tid, g.two_eb[WHICH], g.n_sym[WHICH], g.k_units);  // has barriers: enc[] is visible after it
+    }
     uint32_t bits = 0;
 #pragma unroll
     for (int i = 0; i < 4; i++)
@@ -151,9 +178,9 @@ __global__ __launch_bounds__(kPlaceThreads) void place_kernel(Geo g, int n_blk_p
 }
 
 // ---- 3. write pass -----------------------------------------------------------------------------------------
-template <int WHICH>
+template <int WHICH, bool KEPT>
 __global__ __launch_bounds__(256) void write_kernel(Geo g, const uint16_t *__restrict__ X, int seq_stride,
-                                                     int n_blk_per_bh, int dst_blk0) {
+                                                     int n_blk_per_bh, int dst_blk0, Kept kept) {
     using R = Rec<WHICH>;
     __shared__ QuantShared sh;
     __shared__ uint32_t enc[512];  // [0..256) first-bit-first, [256..512) last-bit-first
@@ -167,8 +194,12 @@ __global__ __launch_bounds__(256) void write_kernel(Geo g, const uint16_t *__res
     enc[256 + tid] = g.enc[WHICH * 512 + 256 + tid];
     for (int i = tid; i < (int)(sizeof(rec) / 4); i += 256) rec[i] = 0;
     TileRegs r;
-    load_tile(X, seq_stride, g.H, bh / g.H, bh % g.H, j, tid, r);
-    quantize_tile<WHICH>(r, sh, tid, g.two_eb[WHICH], g.n_sym[WHICH], g.k_units);
+    if constexpr (KEPT) {
+        load_kept_codes(kept, (size_t)bh * kept.blk_per_bh + j, tid, r);
+    } else {
+        load_tile(X, seq_stride, g.H, bh / g.H, bh % g.H, j, tid, r);
+        quantize_tile<WHICH>(r, sh, tid, g.two_eb[WHICH], g.n_sym[WHICH], g.k_units);
+    }
     // codes -> LDS tile (token-major rows, padded), header -> record
     const int c0 = tile_chan0(tid);
 #pragma unroll
@@ -178,7 +209,10 @@ __global__ __launch_bounds__(256) void write_kernel(Geo g, const uint16_t *__res
         dst[0] = r.code[i][0] | (r.code[i][1] << 8) | (r.code[i][2] << 16) | (r.code[i][3] << 24);
         dst[1] = r.code[i][4] | (r.code[i][5] << 8) | (r.code[i][6] << 16) | (r.code[i][7] << 24);
     }
-    if (tid < R::n_units(g)) rec[tid] = float_to_half_bits(sh.unit_mn[tid]) | (float_to_half_bits(sh.unit_mx[tid]) << 16);
+    if (tid < R::n_units(g)) {
+        if constexpr (KEPT) rec[tid] = kept.minmax[((size_t)bh * kept.blk_per_bh + j) * R::n_units(g) + tid];
+        else rec[tid] = float_to_half_bits(sh.unit_mn[tid]) | (float_to_half_bits(sh.unit_mx[tid]) << 16);
+    }
     __syncthreads();
     // Each thread encodes 32 symbols, half of one slice (Section 3.2.2 stage 2).  K: slice s = token s/2, channels
     // 64*(s%2)..+63 in channel order; V: slice s = channel s, tokens in order.  The first half of a slice is written
@@ -244,11 +278,27 @@ hipError_t launch_encode(const Geo &g, const uint16_t *XK, const uint16_t *XV, i
                          int dst_blk0, hipStream_t s) {
     const int total = g.B * g.H * n_blk_per_bh;
     if (total <= 0) return hipSuccess;
-    hipLaunchKernelGGL(size_kernel<0>, dim3(total), dim3(256), 0, s, g, XK, seq_stride, n_blk_per_bh, dst_blk0);
-    hipLaunchKernelGGL(size_kernel<1>, dim3(total), dim3(256), 0, s, g, XV, seq_stride, n_blk_per_bh, dst_blk0);
+    const Kept none = {nullptr, nullptr, 0};
+    hipLaunchKernelGGL((size_kernel<0, false>), dim3(total), dim3(256), 0, s, g, XK, seq_stride, n_blk_per_bh, dst_blk0, none);
+    hipLaunchKernelGGL((size_kernel<1, false>), dim3(total), dim3(256), 0, s, g, XV, seq_stride, n_blk_per_bh, dst_blk0, none);
     hipLaunchKernelGGL(place_kernel, dim3(1), dim3(1024), 0, s, g, n_blk_per_bh, dst_blk0);
-    hipLaunchKernelGGL(write_kernel<0>, dim3(total), dim3(256), 0, s, g, XK, seq_stride, n_blk_per_bh, dst_blk0);
-    hipLaunchKernelGGL(write_kernel<1>, dim3(total), dim3(256), 0, s, g, XV, seq_stride, n_blk_per_bh, dst_blk0);
+    hipLaunchKernelGGL((write_kernel<0, false>), dim3(total), dim3(256), 0, s, g, XK, seq_stride, n_blk_per_bh, dst_blk0, none);
+    hipLaunchKernelGGL((write_kernel<1, false>), dim3(total), dim3(256), 0, s, g, XV, seq_stride, n_blk_per_bh, dst_blk0, none);
+    return hipGetLastError();
+}
+
+// The same from codes and min/max kept by launch_histogram (kept_blk_per_bh blocks per (batch, head) there, of which
+// the first n_blk_per_bh are encoded): no second and third quantization of the input.
+hipError_t launch_encode_kept(const Geo &g, const uint8_t *codesK, const uint32_t *mmK, const uint8_t *codesV,
+                              const uint32_t *mmV, int kept_blk_per_bh, int n_blk_per_bh, hipStream_t s) {
+    const int total = g.B * g.H * n_blk_per_bh;
+    if (total <= 0) return hipSuccess;
+    const Kept kk = {codesK, mmK, kept_blk_per_bh}, kv = {codesV, mmV, kept_blk_per_bh};
+    hipLaunchKernelGGL((size_kernel<0, true>), dim3(total), dim3(256), 0, s, g, nullptr, 0, n_blk_per_bh, 0, kk);
+    hipLaunchKernelGGL((size_kernel<1, true>), dim3(total), dim3(256), 0, s, g, nullptr, 0, n_blk_per_bh, 0, kv);
+    hipLaunchKernelGGL(place_kernel, dim3(1), dim3(1024), 0, s, g, n_blk_per_bh, 0);
+    hipLaunchKernelGGL((write_kernel<0, true>), dim3(total), dim3(256), 0, s, g, nullptr, 0, n_blk_per_bh, 0, kk);
+    hipLaunchKernelGGL((write_kernel<1, true>), dim3(total), dim3(256), 0, s, g, nullptr, 0, n_blk_per_bh, 0, kv);
     return hipGetLastError();
 }
 

@@ -202,8 +202,30 @@ kvcomp_status kvcomp_reset(kvcomp_ctx *ctx, int keep_codebook, void *stream) {
     return KVCOMP_OK;
 }
 
-kvcomp_status kvcomp_build_codebook(kvcomp_ctx *ctx, const void *d_K, const void *d_V, int seq, void *stream) {
-    if (!ctx || !d_K || !d_V) return fail(KVCOMP_ERR_INVALID_ARG, "NULL argument");
+// Where kvcomp_prefill keeps the quantization codes and unit min/max between its histogram pass and its encode pass.
+struct PrefillWs {
+    uint8_t *codes[2];
+    uint32_t *minmax[2];
+    size_t total;
+};
+static PrefillWs prefill_layout(const kvcomp_config &c, int seq, void *base) {
+    const size_t nblk = (size_t)c.batch * c.n_kv_heads * (seq / kBT);
+    const size_t k_units = c.k_mode == 1 ? 1 : kD;
+    uint8_t *p = static_cast<uint8_t *>(base);
+    PrefillWs w;
+    size_t at = 0;
+    w.codes[0] = p + at; at += nblk * kTile;
+    w.codes[1] = p + at; at += nblk * kTile;
+    w.minmax[0] = reinterpret_cast<uint32_t *>(p + at); at += align_up(nblk * k_units * 4, 16);
+    w.minmax[1] = reinterpret_cast<uint32_t *>(p + at); at += align_up(nblk * kBT * 4, 16);
+    w.total = at;
+    return w;
+}
+
+// Histogram on the device, codebooks on the host, tables to the device (Section 3).  ws != NULL: the histogram pass
+// also keeps the codes and min/max of every block there.
+static kvcomp_status codebook_impl(kvcomp_ctx *ctx, const void *d_K, const void *d_V, int seq, const PrefillWs *ws,
+                                   hipStream_t s) {
     if (!aligned16(d_K) || !aligned16(d_V)) return fail(KVCOMP_ERR_INVALID_ARG, "K/V must be 16-byte aligned");
     if (seq < kBT || seq > ctx->cfg.max_seq)
         return fail(KVCOMP_ERR_INVALID_ARG, "seq %d outside [64, max_seq=%d]", seq, ctx->cfg.max_seq);
@@ -212,11 +234,12 @@ kvcomp_status kvcomp_build_codebook(kvcomp_ctx *ctx, const void *d_K, const void
     if (ctx->n_blocks || ctx->n_res) return fail(KVCOMP_ERR_STATE, "cache is not empty: kvcomp_reset first");
     const long long symbols = (long long)ctx->geo.B * ctx->geo.H * (seq / kBT) * kTile;
     if (symbols >= (1ll << 32)) return fail(KVCOMP_ERR_INVALID_ARG, "more than 2^32 symbols per tensor");
-    hipStream_t s = static_cast<hipStream_t>(stream);
     Geo &g = ctx->geo;
     HIP_TRY(launch_fill_zero(g.hist, 2 * 256 * 4, s));
-    HIP_TRY(launch_histogram(g, 0, static_cast<const uint16_t *>(d_K), seq, seq / kBT, s));
-    HIP_TRY(launch_histogram(g, 1, static_cast<const uint16_t *>(d_V), seq, seq / kBT, s));
+    HIP_TRY(launch_histogram(g, 0, static_cast<const uint16_t *>(d_K), seq, seq / kBT, ws ? ws->codes[0] : nullptr,
+                             ws ? ws->minmax[0] : nullptr, s));
+    HIP_TRY(launch_histogram(g, 1, static_cast<const uint16_t *>(d_V), seq, seq / kBT, ws ? ws->codes[1] : nullptr,
+                             ws ? ws->minmax[1] : nullptr, s));
     // control words and histograms are neighbours in the arena and in the pinned staging block: one copy
     static_assert(sizeof(Ctrl) <= 256, "control words fill the first 256 bytes");
     HIP_TRY(hipMemcpyAsync(ctx->h_ctrl, g.ctrl, 256 + 2 * 256 * 4, hipMemcpyDeviceToHost, s));
@@ -232,29 +255,19 @@ kvcomp_status kvcomp_build_codebook(kvcomp_ctx *ctx, const void *d_K, const void
         if (ctx->geo.lut_bits[w] <= 6) build_pair_table(ctx->h_lut + kLutSize * w, ctx->geo.lut_bits[w], ctx->h_lut2 + kPairEntries * w);
         else std::memset(ctx->h_lut2 + kPairEntries * w, 0, kPairEntries * 4);
     }
-    // encode tables, decode tables and trees are neighbours too: one upload
+    // encode tables, decode tables and trees are neighbours too: one upload (stream-ordered: whatever uses the tables
+    // comes after it on the same stream, and the pinned staging block is not rewritten before the next codebook)
     static_assert(kPairEntries == kPairTableEntries, "pair table size");
     HIP_TRY(hipMemcpyAsync(g.enc, ctx->h_enc, 4 * 256 * 4 + 2 * kLutSize * 2 + 2 * 256 * 2 * 2 + 2 * kPairEntries * 4,
                            hipMemcpyHostToDevice, s));
-    HIP_TRY(hipStreamSynchronize(s));
     ctx->have_codebook = true;
     return KVCOMP_OK;
 }
 
-kvcomp_status kvcomp_compress_blocks(kvcomp_ctx *ctx, const void *d_K, const void *d_V, int seq, void *stream) {
-    if (!ctx || !d_K || !d_V) return fail(KVCOMP_ERR_INVALID_ARG, "NULL argument");
-    if (!aligned16(d_K) || !aligned16(d_V)) return fail(KVCOMP_ERR_INVALID_ARG, "K/V must be 16-byte aligned");
-    if (!ctx->have_codebook) return fail(KVCOMP_ERR_STATE, "no codebook: call kvcomp_build_codebook first");
-    if (ctx->n_blocks || ctx->n_res) return fail(KVCOMP_ERR_STATE, "cache is not empty");
-    if (seq < 1) return fail(KVCOMP_ERR_INVALID_ARG, "seq must be positive");
-    if (seq > ctx->cfg.max_seq) return fail(KVCOMP_ERR_CAPACITY, "seq %d exceeds max_seq %d", seq, ctx->cfg.max_seq);
-    hipStream_t s = static_cast<hipStream_t>(stream);
+// After the encode launches of a prompt: the newest tokens to the fp16 buffer, then the one synchronisation that
+// brings the arena tail, the largest record and the flags to the host.
+static kvcomp_status finish_prompt(kvcomp_ctx *ctx, const uint16_t *K, const uint16_t *V, int seq, int nb, hipStream_t s) {
     const Geo &g = ctx->geo;
-    // as if the tokens had been appended one by one: the buffer keeps the newest tokens, its oldest block is cut off
-    // whenever it holds res_tokens of them
-    const int nb = seq < g.res_tokens ? 0 : (seq - g.res_tokens) / kBT + 1;
-    const uint16_t *K = static_cast<const uint16_t *>(d_K), *V = static_cast<const uint16_t *>(d_V);
-    HIP_TRY(launch_encode(g, K, V, seq, nb, 0, s));
     HIP_TRY(launch_copy_tail(g, K, V, seq, nb * kBT, seq - nb * kBT, s));
     kvcomp_status st = read_ctrl(ctx, s);
     if (st) return st;
@@ -268,6 +281,57 @@ kvcomp_status kvcomp_compress_blocks(kvcomp_ctx *ctx, const void *d_K, const voi
     ctx->res_head = 0;
     ctx->max_size16 = ctx->h_ctrl->max_size16;
     return KVCOMP_OK;
+}
+
+// blocks that seq appended tokens leave compressed: the buffer keeps the newest tokens, its oldest block is cut off
+// whenever it holds res_tokens of them
+static int prompt_blocks(const Geo &g, int seq) { return seq < g.res_tokens ? 0 : (seq - g.res_tokens) / kBT + 1; }
+
+kvcomp_status kvcomp_build_codebook(kvcomp_ctx *ctx, const void *d_K, const void *d_V, int seq, void *stream) {
+    if (!ctx || !d_K || !d_V) return fail(KVCOMP_ERR_INVALID_ARG, "NULL argument");
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    kvcomp_status st = codebook_impl(ctx, d_K, d_V, seq, nullptr, s);
+    if (st) return st;
+    HIP_TRY(hipStreamSynchronize(s));
+    return KVCOMP_OK;
+}
+
+kvcomp_status kvcomp_compress_blocks(kvcomp_ctx *ctx, const void *d_K, const void *d_V, int seq, void *stream) {
+    if (!ctx || !d_K || !d_V) return fail(KVCOMP_ERR_INVALID_ARG, "NULL argument");
+    if (!aligned16(d_K) || !aligned16(d_V)) return fail(KVCOMP_ERR_INVALID_ARG, "K/V must be 16-byte aligned");
+    if (!ctx->have_codebook) return fail(KVCOMP_ERR_STATE, "no codebook: call kvcomp_build_codebook first");
+    if (ctx->n_blocks || ctx->n_res) return fail(KVCOMP_ERR_STATE, "cache is not empty");
+    if (seq < 1) return fail(KVCOMP_ERR_INVALID_ARG, "seq must be positive");
+    if (seq > ctx->cfg.max_seq) return fail(KVCOMP_ERR_CAPACITY, "seq %d exceeds max_seq %d", seq, ctx->cfg.max_seq);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const Geo &g = ctx->geo;
+    const int nb = prompt_blocks(g, seq);
+    const uint16_t *K = static_cast<const uint16_t *>(d_K), *V = static_cast<const uint16_t *>(d_V);
+    HIP_TRY(launch_encode(g, K, V, seq, nb, 0, s));
+    return finish_prompt(ctx, K, V, seq, nb, s);
+}
+
+size_t kvcomp_prefill_workspace_bytes(const kvcomp_config *cfg, int seq) {
+    if (!valid_cfg(cfg) || seq < kBT) return 0;
+    return prefill_layout(*cfg, seq, nullptr).total;
+}
+
+kvcomp_status kvcomp_prefill(kvcomp_ctx *ctx, const void *d_K, const void *d_V, int seq, void *d_workspace,
+                             size_t workspace_bytes, void *stream) {
+    if (!ctx || !d_K || !d_V || !d_workspace) return fail(KVCOMP_ERR_INVALID_ARG, "NULL argument");
+    if (!aligned16(d_workspace)) return fail(KVCOMP_ERR_INVALID_ARG, "workspace must be 16-byte aligned");
+    if (seq < kBT || seq > ctx->cfg.max_seq)
+        return fail(KVCOMP_ERR_INVALID_ARG, "seq %d outside [64, max_seq=%d]", seq, ctx->cfg.max_seq);
+    const PrefillWs ws = prefill_layout(ctx->cfg, seq, d_workspace);
+    if (workspace_bytes < ws.total)
+        return fail(KVCOMP_ERR_CAPACITY, "workspace has %zu bytes, %zu needed", workspace_bytes, ws.total);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    kvcomp_status st = codebook_impl(ctx, d_K, d_V, seq, &ws, s);
+    if (st) return st;
+    const Geo &g = ctx->geo;
+    const int nb = prompt_blocks(g, seq);
+    HIP_TRY(launch_encode_kept(g, ws.codes[0], ws.minmax[0], ws.codes[1], ws.minmax[1], seq / kBT, nb, s));
+    return finish_prompt(ctx, static_cast<const uint16_t *>(d_K), static_cast<const uint16_t *>(d_V), seq, nb, s);
 }
 
 kvcomp_status kvcomp_append_token(kvcomp_ctx *ctx, const void *d_k_new, const void *d_v_new, void *stream) {

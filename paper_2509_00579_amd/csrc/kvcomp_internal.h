@@ -89,7 +89,9 @@ constexpr size_t fused_lds_fixed(int G, int longest) {
 hipError_t launch_decompress(const Geo &g, int which, uint16_t *out, int n_blocks, int res_head, int n_res, int seq_stride,
                              int stage_bytes, int tree_walk, hipStream_t s);
 hipError_t launch_histogram(const Geo &g, int which, const uint16_t *X, int seq_stride, int n_blk_per_bh,
-                            hipStream_t s);
+                            uint8_t *codes, uint32_t *minmax, hipStream_t s);
+hipError_t launch_encode_kept(const Geo &g, const uint8_t *codesK, const uint32_t *mmK, const uint8_t *codesV,
+                              const uint32_t *mmV, int kept_blk_per_bh, int n_blk_per_bh, hipStream_t s);
 hipError_t launch_debug_codes(const Geo &g, int which, const uint16_t *X, int seq_stride, int n_blk_per_bh,
                               uint8_t *d_codes, uint16_t *d_minmax, hipStream_t s);
 // size pass -> table[...].size16 ; place -> off16 + ctrl ; write pass -> records

@@ -8,9 +8,12 @@ namespace kvc {
 // the lanes of a half-wave always hit 32 different banks and never the same word, so an LDS atomic instruction costs
 // its minimum however peaked the code distribution is (with one copy per wave, lanes with the same code serialise
 // and the kernel was bound by its LDS atomics).  The copies are summed and added to the global histogram at the end.
-template <int WHICH>
+// KEEP: the codes ([block][64][128] bytes) and the unit min/max ([block][units] {min,max} fp16 pairs) of every block also
+// go to a caller's workspace, from where the encoder takes them instead of quantizing the input again (kvcomp_prefill).
+template <int WHICH, bool KEEP>
 __global__ __launch_bounds__(256, 4) void histogram_kernel(Geo g, const uint16_t *__restrict__ X, int seq_stride,
-                                                         int n_blk_per_bh, int n_blk_total) {
+                                                         int n_blk_per_bh, int n_blk_total, uint8_t *__restrict__ codes,
+                                                         uint32_t *__restrict__ minmax) {
     __shared__ QuantShared sh;
     __shared__ uint32_t hist[256][32];
     const int tid = threadIdx.x, copy = tid & 31;
@@ -33,6 +36,19 @@ __global__ __launch_bounds__(256, 4) void histogram_kernel(Geo g, const uint16_t
         for (int i = 0; i < 4; i++)
 #pragma unroll
             for (int k = 0; k < 8; k++) atomicAdd(&hist[r.code[i][k]][copy], 1u);
+        if constexpr (KEEP) {
+            const int c0 = tile_chan0(tid);
+#pragma unroll
+            for (int i = 0; i < 4; i++) {
+                uint2 pk;
+                pk.x = r.code[i][0] | (r.code[i][1] << 8) | (r.code[i][2] << 16) | (r.code[i][3] << 24);
+                pk.y = r.code[i][4] | (r.code[i][5] << 8) | (r.code[i][6] << 16) | (r.code[i][7] << 24);
+                *reinterpret_cast<uint2 *>(codes + (size_t)blk * kTile + tile_token(tid, i) * kD + c0) = pk;
+            }
+            const int units = WHICH == 0 ? g.k_units : kBT;
+            if (tid < units)
+                minmax[(size_t)blk * units + tid] = float_to_half_bits(sh.unit_mn[tid]) | (float_to_half_bits(sh.unit_mx[tid]) << 16);
+        }
         __syncthreads();  // unit_mn/unit_mx are rewritten by the next iteration
     }
     __syncthreads();
@@ -71,15 +87,21 @@ __global__ __launch_bounds__(256) void debug_codes_kernel(Geo g, const uint16_t 
     if (bad) atomicOr(&g.ctrl->nonfinite, 1u);
 }
 
+// codes / minmax != NULL: also keep the codes and the unit min/max of every block there
 hipError_t launch_histogram(const Geo &g, int which, const uint16_t *X, int seq_stride, int n_blk_per_bh,
-                            hipStream_t s) {
+                            uint8_t *codes, uint32_t *minmax, hipStream_t s) {
     const int total = g.B * g.H * n_blk_per_bh;
     if (total <= 0) return hipSuccess;
     const int grid = total < 1024 ? total : 1024;  // four workgroups per CU (32 KiB of LDS each), several blocks each
-    if (which == 0)
-        hipLaunchKernelGGL(histogram_kernel<0>, dim3(grid), dim3(256), 0, s, g, X, seq_stride, n_blk_per_bh, total);
+    const bool keep = codes != nullptr;
+    if (which == 0 && !keep)
+        hipLaunchKernelGGL((histogram_kernel<0, false>), dim3(grid), dim3(256), 0, s, g, X, seq_stride, n_blk_per_bh, total, codes, minmax);
+    else if (which == 0)
+        hipLaunchKernelGGL((histogram_kernel<0, true>), dim3(grid), dim3(256), 0, s, g, X, seq_stride, n_blk_per_bh, total, codes, minmax);
+    else if (!keep)
+        hipLaunchKernelGGL((histogram_kernel<1, false>), dim3(grid), dim3(256), 0, s, g, X, seq_stride, n_blk_per_bh, total, codes, minmax);
     else
-        hipLaunchKernelGGL(histogram_kernel<1>, dim3(grid), dim3(256), 0, s, g, X, seq_stride, n_blk_per_bh, total);
+        hipLaunchKernelGGL((histogram_kernel<1, true>), dim3(grid), dim3(256), 0, s, g, X, seq_stride, n_blk_per_bh, total, codes, minmax);
     return hipGetLastError();
 }
 

@@ -133,6 +133,61 @@ def test_records_and_attention(gpu, oracle, B, H, Hq, S, rel_k, rel_v):
     gc.close()
 
 
+@pytest.mark.parametrize("B,H,Hq,S,rel_k,rel_v,k_mode,limit,window", [
+    (2, 2, 2, 520, 1e-2, 2e-2, 0, 12, 64),     # ragged tail
+    (1, 3, 3, 333, 5e-3, 1e-2, 1, 9, 64),      # K BlockQuant: one {min,max} pair per block in the workspace
+    (1, 2, 8, 700, 1e-2, 1e-2, 0, 6, 256),     # buffer of 256 tokens: fewer blocks are encoded than were quantized
+    (2, 1, 4, 64, 2e-2, 2e-2, 0, 6, 64),       # a single block
+])
+def test_prefill_with_one_quantization_pass(gpu, oracle, B, H, Hq, S, rel_k, rel_v, k_mode, limit, window):
+    """kvcomp_prefill = kvcomp_build_codebook + kvcomp_compress_blocks with the codes kept in a workspace between the
+    histogram pass and the encoder: histograms, codebooks, records, offsets, buffer and attention against the oracle,
+    and the arena byte for byte against the two separate calls."""
+    _say(f"prefill B={B} H={H} Hq={Hq} S={S} rel {rel_k}/{rel_v} k_mode={k_mode} limit {limit} buffer {window}")
+    import torch
+    Kx, Vx = W.make_kv(B, H, S, 38)
+    Kx[0, 0:64, 0, 7] = np.float16(1.25)      # a constant K unit
+    oc = oracle.OracleCache(B, H, Hq, S + 64, rel_k, rel_v, k_mode, limit, buffer_tokens=window)
+    oc.build_codebook(Kx, Vx)
+    oc.compress_blocks(Kx, Vx)
+    gc = gpu.KVCompCache(B, H, Hq, S + 64, rel_k, rel_v, k_mode=k_mode, max_code_len=limit, buffer_tokens=window)
+    dK, dV = _dev(Kx), _dev(Vx)
+    ws = torch.full((gc.prefill_workspace_bytes(S) + 64,), 0xAB, dtype=torch.uint8, device="cuda:0")
+    gc.prefill(dK, dV, ws[: gc.prefill_workspace_bytes(S)])
+    assert (ws[gc.prefill_workspace_bytes(S):] == 0xAB).all()      # nothing written past the stated size
+    for which in (K, V):
+        np.testing.assert_array_equal(gc.histogram(which).astype(np.uint64), oc.hist[which])
+        ln_g, cd_g = gc.codebook(which)
+        np.testing.assert_array_equal(ln_g, oc.len[which])
+        np.testing.assert_array_equal(cd_g, oc.code[which])
+    _assert_same_cache(oc, gc)
+    q = W.make_queries(B, Hq, 1, 38)[0]
+    _attn_close(gc.attn_decode(_dev(q), SCALE).cpu().numpy(), oc.attn_decode(q, SCALE))
+    one_pass = [gc.get_block(w, b, h, j) for w in (K, V) for b in range(B) for h in range(H) for j in range(oc.n_blocks)]
+    gc.reset(keep_codebook=False)
+    gc.build_codebook(dK, dV)
+    gc.compress_blocks(dK, dV)
+    two_calls = [gc.get_block(w, b, h, j) for w in (K, V) for b in range(B) for h in range(H) for j in range(oc.n_blocks)]
+    for a, b_ in zip(one_pass, two_calls):
+        np.testing.assert_array_equal(a, b_)
+    # errors: too small a workspace, a cache that is not empty, non-finite input
+    with pytest.raises(gpu.KvcompError) as e:
+        gc.prefill(dK, dV, ws)
+    assert e.value.status == gpu.ERR_STATE
+    gc.reset(keep_codebook=False)
+    with pytest.raises(gpu.KvcompError) as e:
+        gc.prefill(dK, dV, ws[:1024])
+    assert e.value.status == gpu.ERR_CAPACITY
+    bad = Kx.copy()
+    bad[0, 3, 0, 5] = np.nan
+    with pytest.raises(gpu.KvcompError) as e:
+        gc.prefill(_dev(bad), dV, ws)
+    assert e.value.status == gpu.ERR_NONFINITE
+    gc.prefill(dK, dV, ws)
+    _assert_same_cache(oc, gc)
+    gc.close()
+
+
 def test_all_residual_and_tiny_sequences(gpu, oracle):
     _say("seq < 64: everything stays in the fp16 buffer")
     B, H, Hq = 2, 2, 4
