@@ -239,7 +239,8 @@ def measure(torch, args, name, rel_eb, rel_eb_v, steps, warmup, headline):
         pair_ms = total_ms / max(launches, 1)   # an event pair per launch also sees the gap to the previous kernel
     # ... and back to back, like the fp16 kernel below: launches of the fused kernel on the cache as the loop left it
     # (a graph replay, or eager launches), one event pair around all of them
-    krep = max(8, min(64, T))
+    krep = 64   # per replay; two warm-up replays, then three timed ones: the first hundred launches after the store and
+    # the host-side work around it run a few per cent slower than the steady state
     kgraph = None
     if not args.no_graph:
         try:
@@ -251,8 +252,8 @@ def measure(torch, args, name, rel_eb, rel_eb_v, steps, warmup, headline):
         except Exception:  # noqa: BLE001
             kgraph = None
         torch.cuda.synchronize()
-    for r in range(4):   # the first round is a warm-up
-        if r == 1:
+    for r in range(5):   # the first two rounds are a warm-up
+        if r == 2:
             ev[0].record()
         if kgraph is not None:
             kgraph.replay()
@@ -297,7 +298,7 @@ def measure(torch, args, name, rel_eb, rel_eb_v, steps, warmup, headline):
     for i in range(3):
         base(dK, dV, dq[i % T], scale, out)
     torch.cuda.synchronize()
-    nrep = max(8, min(64, T))
+    nrep = 64   # as for the fused kernel: two warm-up replays, three timed ones
     bgraph = None
     if not args.no_graph:
         try:
@@ -308,8 +309,9 @@ def measure(torch, args, name, rel_eb, rel_eb_v, steps, warmup, headline):
             bgraph = bg
         except Exception:  # noqa: BLE001
             bgraph = None
-    ev[0].record()
-    for _ in range(3):
+    for r in range(5):
+        if r == 2:
+            ev[0].record()
         if bgraph is not None:
             bgraph.replay()
         else:
@@ -570,8 +572,8 @@ def main():
                      "frac_cold": fk["frac_hbm_peak_cold"],
                      "avg_launch_ms_event_pair_each": fk["ms_event_pair_each"],
                      "timing": f"one HIP event pair around 3 x {fk['launches_timed'] // 3} back-to-back launches of the "
-                               "fused kernel on the cache as the decode loop left it (graph replay unless --no-graph), on "
-                               "the launch stream, right after the timed region; avg_launch_ms_event_pair_each: an "
+                               "fused kernel on the cache as the decode loop left it (graph replay unless --no-graph; two "
+                               "replays of warm-up before them), on the launch stream, right after the timed region; avg_launch_ms_event_pair_each: an "
                                "event pair around every launch of one eager pass of the decode loop, which also sees "
                                "the gap to the previous kernel; avg_launch_ms_cold: an event pair per launch with a "
                                "512 MiB copy before it"},

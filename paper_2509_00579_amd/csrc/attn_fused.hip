@@ -689,10 +689,43 @@ __device__ __noinline__ void v_tile_block_global(const uint32_t *rec, const char
     v_tile_block<G, LB>(rec, lut, mask2, tile, p, two_eb, lane, ts, [] {});
 }
 
-// The tile path's state in the layout of the other paths (lane = channels 2*lane, 2*lane+1 of every head; l and bv
-// in lane 0 only): through `area`, G * 128 + 3 * G floats of LDS.
+// A wave's softmax state parked in LDS, G * 128 + 3 * G floats: o[g][channel] then {m, l, bv} per head with l and bv
+// already summed over the lanes.  The state crosses the call of the out-of-line buffered-token code this way (through
+// a reference it would cross in scratch memory, i.e. through the memory system: microseconds on the critical path of
+// the wave that finishes last), and the tile path changes its layout this way.
 template <int G>
-__device__ __forceinline__ void tile_state_to_soft(const TileSoft<G> &ts, float *area, int lane, Soft<G> &st) {
+__device__ __forceinline__ void soft_to_area(const Soft<G> &st, float *area, int lane) {
+    wave_sync();
+#pragma unroll
+    for (int g = 0; g < G; g++) {
+        area[g * kD + 2 * lane] = st.acc[g][0];
+        area[g * kD + 2 * lane + 1] = st.acc[g][1];
+        const float l = wave_sum(st.l[g]), bv = wave_sum(st.bv[g]);
+        if (lane == 0) {
+            area[G * kD + 3 * g] = st.m[g];
+            area[G * kD + 3 * g + 1] = l;
+            area[G * kD + 3 * g + 2] = bv;
+        }
+    }
+    wave_sync();
+}
+// lane = channels 2*lane, 2*lane+1 of every head; l and bv in lane 0 only
+template <int G>
+__device__ __forceinline__ void area_to_soft(const float *area, int lane, Soft<G> &st) {
+    wave_sync();
+#pragma unroll
+    for (int g = 0; g < G; g++) {
+        st.acc[g][0] = area[g * kD + 2 * lane];
+        st.acc[g][1] = area[g * kD + 2 * lane + 1];
+        st.m[g] = area[G * kD + 3 * g];
+        st.l[g] = lane == 0 ? area[G * kD + 3 * g + 1] : 0.f;
+        st.bv[g] = lane == 0 ? area[G * kD + 3 * g + 2] : 0.f;
+    }
+    wave_sync();
+}
+// the tile path's state (lane l: column l % 32, heads l / 32 + 2 i) into the area
+template <int G>
+__device__ __forceinline__ void tile_state_to_area(const TileSoft<G> &ts, float *area, int lane) {
     constexpr int HL = G / 2;
     const int x = lane & 31, hv = lane >> 5;
     wave_sync();
@@ -707,15 +740,6 @@ __device__ __forceinline__ void tile_state_to_soft(const TileSoft<G> &ts, float 
             area[G * kD + 3 * head + 1] = l;
             area[G * kD + 3 * head + 2] = bv;
         }
-    }
-    wave_sync();
-#pragma unroll
-    for (int g = 0; g < G; g++) {
-        st.acc[g][0] = area[g * kD + 2 * lane];
-        st.acc[g][1] = area[g * kD + 2 * lane + 1];
-        st.m[g] = area[G * kD + 3 * g];
-        st.l[g] = lane == 0 ? area[G * kD + 3 * g + 1] : 0.f;
-        st.bv[g] = lane == 0 ? area[G * kD + 3 * g + 2] : 0.f;
     }
     wave_sync();
 }
@@ -738,7 +762,9 @@ template <int G>
 __device__ __noinline__ void buffered_tokens(const uint16_t *res, int res_tokens, int B, int H, int b, int h,
                                              int res_head, int n_res, int first_unit, int unit_step,
                                              const float *qf, float scale, int lane, const uint16_t *k_new,
-                                             const uint16_t *v_new, int new_row, Soft<G> &st) {
+                                             const uint16_t *v_new, int new_row, float *area) {
+    Soft<G> st;
+    area_to_soft<G>(area, lane, st);
     const size_t res_tensor = (size_t)B * res_tokens * H * kD;
     const size_t row4 = (size_t)4 * H * kD;  // elements from one load to the next
     const int n_units = (n_res + kUnitTokens - 1) / kUnitTokens;
@@ -829,6 +855,7 @@ __device__ __noinline__ void buffered_tokens(const uint16_t *res, int res_tokens
             st.acc[gg][1] = st.acc[gg][1] * alpha + __shfl(w2[1], owner);
         }
     }
+    soft_to_area<G>(st, area, lane);
 }
 
 // A record on its way from global memory to the wave's LDS staging area: the first 8 KiB travel through
@@ -1087,7 +1114,14 @@ __global__ __launch_bounds__((64 * MaxWaves<G, LB>::value), 1) void fused_attn_k
         }
     }
 
-    if constexpr (kTile) tile_state_to_soft<G>(ts, reinterpret_cast<float *>(stage), lane, st);  // the record area is free now
+    // The record area is free now: the tile path changes the layout of its state through it, and a wave with buffered
+    // tokens parks its state there across the out-of-line call.
+    float *area = reinterpret_cast<float *>(stage);
+    bool parked = false;
+    if constexpr (kTile) {
+        tile_state_to_area<G>(ts, area, lane);
+        parked = true;
+    }
     // the buffered fp16 tokens in units of 16: unit u goes to split n_splits-1 - u % n_splits (the last split is the
     // short one), there to the waves in turn, starting after the wave that took the split's last block
     if (a.n_res > 0) {
@@ -1095,12 +1129,13 @@ __global__ __launch_bounds__((64 * MaxWaves<G, LB>::value), 1) void fused_attn_k
         if (turn < 0) turn += n_waves;
         const int first = a.n_splits - 1 - split + a.n_splits * turn;
         if (first * kUnitTokens < a.n_res) {
-            Soft<G> st_tmp = st;
+            if (!parked) soft_to_area<G>(st, area, lane);
+            parked = true;
             buffered_tokens<G>(g.res, g.res_tokens, g.B, g.H, b, h, a.res_head, a.n_res, first, n_waves * a.n_splits, qf,
-                               a.scale, lane, a.k_new, a.v_new, a.new_row, st_tmp);
-            st = st_tmp;
+                               a.scale, lane, a.k_new, a.v_new, a.new_row, area);
         }
     }
+    if (parked) area_to_soft<G>(area, lane, st);
     wave_sync();
 
     // merge the waves of this workgroup into one partial (o[128], m, l) per query head
