@@ -424,6 +424,14 @@ __device__ __forceinline__ float int_scale(float amax, float *inv) {
 }
 // |W| <= 2^22 as d2 2^16 + d1 2^8 + d0 with signed bytes d_j: bytes 0..2 of the result
 __device__ __forceinline__ uint32_t signed_digits(int W) { return ((uint32_t)W + 0x00008080u) ^ 0x00008080u; }
+// Rounding to an integer inside the multiplication: for |a * b| <= 2^22, fma(a, b, 1.5 * 2^23) is rounded (to nearest,
+// ties to even) at unit spacing, and its bit pattern is kMagicBits + W with W = rint(a * b), also across the binade
+// boundary at W = 2^22.  One instruction instead of a product, a rounding and a conversion; W stays implicit:
+//   magic_digits(bits) = signed_digits(W), and sums of W are sums of bit patterns minus n * kMagicBits.
+constexpr float kMagic = 12582912.f;          // 1.5 * 2^23
+constexpr uint32_t kMagicBits = 0x4B400000u;  // its bit pattern
+__device__ __forceinline__ uint32_t magic_round(float a, float b) { return __float_as_uint(fmaf(a, b, kMagic)); }
+__device__ __forceinline__ uint32_t magic_digits(uint32_t bits) { return (bits + (0x00008080u - kMagicBits)) ^ 0x00008080u; }
 // words a..d (byte j = digit j of four consecutive columns) -> o[j] = digit j of the four columns, j < 3
 __device__ __forceinline__ void transpose_digits(uint32_t a, uint32_t b, uint32_t c, uint32_t d, uint32_t (&o)[3]) {
     const uint32_t t0 = __builtin_amdgcn_perm(b, a, 0x05010400u), t1 = __builtin_amdgcn_perm(b, a, 0x07030602u);
@@ -490,24 +498,30 @@ __device__ __forceinline__ void k_tile_block(const uint32_t *hdr32, const char *
         }
         float qa[HL][4], amax = 0.f;
 #pragma unroll
-        for (int i = 0; i < HL; i++)
+        for (int c = 0; c < 4; c++) {   // the largest |q_c step_c| of this lane: steps are not negative
+            float qmax = 0.f;
 #pragma unroll
-            for (int c = 0; c < 4; c++) {
+            for (int i = 0; i < HL; i++) {
                 qa[i][c] = qf[(hv + 2 * i) * kD + 4 * x + c];
-                amax = fmaxf(amax, fabsf(qa[i][c] * stp[c]));
+                qmax = fmaxf(qmax, fabsf(qa[i][c]));
             }
+            amax = fmaxf(amax, qmax * stp[c]);
+        }
         const float f = int_scale(amax, &inv);
 #pragma unroll
+        for (int c = 0; c < 4; c++) stp[c] *= f;   // exact: f is a power of two
+#pragma unroll
         for (int i = 0; i < HL; i++) {
-            uint32_t dg[4];
-            float wsum = 0.f, qm = 0.f;
+            uint32_t dg[4], wbits = 0;
+            float qm = 0.f;
 #pragma unroll
             for (int c = 0; c < 4; c++) {
-                const int W = __float2int_rn(qa[i][c] * stp[c] * f);  // |W| <= 2^22
-                wsum += (float)W;
+                const uint32_t bits = magic_round(qa[i][c], stp[c]);  // W = rint(q_c step_c f), |W| <= 2^22
+                wbits += bits;
                 qm = fmaf(qa[i][c], mn[c], qm);
-                dg[c] = signed_digits(W);
+                dg[c] = magic_digits(bits);
             }
+            const float wsum = (float)(int)(wbits - 4u * kMagicBits);
             uint32_t rows[3];
             transpose_digits(dg[0], dg[1], dg[2], dg[3], rows);
             const int head = hv + 2 * i;
@@ -603,22 +617,28 @@ __device__ __forceinline__ void v_tile_block(const uint32_t *hdr32, const char *
             mn[t] = h2f(mm & 0xffffu);
             stp[t] = two_eb * (h2f(mm >> 16) - mn[t]);
         }
-        float amax = 0.f;
+        float pmax[2] = {0.f, 0.f};
 #pragma unroll
-        for (int i = 0; i < HL; i++) amax = fmaxf(amax, fmaxf(p[i][0] * stp[0], p[i][1] * stp[1]));
-        const float f = int_scale(amax, &inv);
+        for (int i = 0; i < HL; i++) {
+            pmax[0] = fmaxf(pmax[0], p[i][0]);
+            pmax[1] = fmaxf(pmax[1], p[i][1]);
+        }
+        const float f = int_scale(fmaxf(pmax[0] * stp[0], pmax[1] * stp[1]), &inv);
+        stp[0] *= f;   // exact: f is a power of two
+        stp[1] *= f;
 #pragma unroll
         for (int i = 0; i < HL; i++) {
             const int head = hv + 2 * i;
-            float wsum = 0.f;
+            uint32_t wbits = 0;
 #pragma unroll
             for (int t = 0; t < 2; t++) {
-                const int W = __float2int_rn(p[i][t] * stp[t] * f);  // |W| <= 2^22
-                wsum += (float)W;
-                const uint32_t dg = signed_digits(W);
+                const uint32_t bits = magic_round(p[i][t], stp[t]);  // W = rint(p_t step_t f), |W| <= 2^22
+                wbits += bits;
+                const uint32_t dg = magic_digits(bits);
 #pragma unroll
                 for (int j = 0; j < 3; j++) tile[(3 * head + j) * kARowV + 32 * t + x] = (uint8_t)(dg >> (8 * j));
             }
+            const float wsum = (float)(int)(wbits - 2u * kMagicBits);
             ts.bv[i] += fmaf(128.f * inv, wsum, fmaf(p[i][0], mn[0], p[i][1] * mn[1]));
         }
         wave_sync();

@@ -43,3 +43,30 @@ def test_fp32_recombination_keeps_the_weights_precision():
     joined = (f(d[2]) * f(256.0) + f(d[1])) * f(256.0) + f(d[0])
     exact = (W @ (sym - 128)).astype(np.float64)
     assert np.abs(joined.astype(np.float64) - exact).max() <= 2.0 ** -22 * np.abs(exact).max()
+
+
+def test_rounding_inside_the_fma_and_digits_from_the_bit_pattern():
+    """The kernel forms W = rint(a * b) as fma(a, b, 1.5 * 2^23): the sum is rounded at unit spacing, and the bit
+    pattern of 1.5 * 2^23 + W is 0x4B400000 + W for every |W| <= 2^22 (also at W = 2^22, where the sum reaches 2^24).
+    The signed byte digits then come straight from the bit pattern: (bits + (0x8080 - 0x4B400000)) ^ 0x8080."""
+    rng = np.random.default_rng(10)
+    W = np.concatenate([rng.integers(-(1 << 22), (1 << 22) + 1, size=200000),
+                        np.array([0, 1, -1, (1 << 22), -(1 << 22), (1 << 22) - 1, 1 - (1 << 22), 32768, -32769])])
+    magic = np.float32(12582912.0)
+    assert magic.view(np.uint32) == 0x4B400000
+    sums = (magic.astype(np.float64) + W).astype(np.float32)          # exact: integers below 2^25 at unit spacing
+    assert np.array_equal(sums.astype(np.float64), 12582912.0 + W)
+    bits = sums.view(np.uint32).astype(np.int64)
+    assert np.array_equal(bits - 0x4B400000, W)
+    digits = ((bits + (0x8080 - 0x4B400000)) & 0xFFFFFFFF) ^ 0x8080
+    ref = ((W + 0x8080) & 0xFFFFFFFF) ^ 0x8080
+    assert np.array_equal(digits & 0xFFFFFF, ref & 0xFFFFFF)          # bytes 0..2 are the three digits
+    # a product that is not an integer is rounded to nearest, ties to even, by the single rounding of the fma
+    a = rng.standard_normal(50000).astype(np.float32)
+    b = (rng.standard_normal(50000) * 1e5).astype(np.float32)
+    keep = np.abs(a.astype(np.float64) * b.astype(np.float64)) < (1 << 22)
+    a, b = a[keep], b[keep]
+    exact = a.astype(np.float64) * b.astype(np.float64)               # exact: 24 x 24 bit significands
+    # (exact + magic) has at most 24 + 25 significant bits: exact in float64, so one rounding to float32 is the fma's
+    fused = (exact + 12582912.0).astype(np.float32)
+    assert np.array_equal(fused.view(np.uint32).astype(np.int64) - 0x4B400000, np.rint(exact).astype(np.int64))
