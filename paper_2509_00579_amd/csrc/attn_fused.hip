@@ -469,6 +469,8 @@ __device__ __forceinline__ int a_row(int x) {
     return 3 * (xr >> 2) + min(xr & 3, 2);
 }
 
+constexpr float kLazyMax = 8.f;  // how far a score may exceed the softmax reference before the state is rescaled
+
 // K block.  hdr32: the record (LDS or global); tile: this wave's LDS area for laying out the A operand; qf: the query
 // rows in LDS.
 // Updates the softmax state and leaves the softmax numerators of tokens l%32 and 32 + l%32 in p.
@@ -583,19 +585,36 @@ __device__ __forceinline__ void k_tile_block(const uint32_t *hdr32, const char *
     products(1, !kBoth);
     products(2, false);
     join(kBoth);
+    // Online softmax with a reference value m that only moves when it has to: the state is rescaled (a maximum over
+    // the tokens of every head, six multiplications per head) only when some score of the block exceeds its head's m
+    // by more than kLazyMax, which after the first blocks of a sequence split is rare.  Until then the numerators are
+    // at most e^kLazyMax instead of 1, which costs fp32 nothing; the merges divide by the same m.
+    const float si = scale * inv;
+    float over = -INFINITY;
 #pragma unroll
     for (int i = 0; i < HL; i++) {
-        sc[i][0] = scale * fmaf(inv, sc[i][0], cst[i]);
-        sc[i][1] = scale * fmaf(inv, sc[i][1], cst[i]);
-        const float mnew = fmaxf(ts.m[i], half_max(fmaxf(sc[i][0], sc[i][1]), upper));
-        const float alpha = __expf(ts.m[i] - mnew);
-        p[i][0] = __expf(sc[i][0] - mnew);
-        p[i][1] = __expf(sc[i][1] - mnew);
-        ts.l[i] = ts.l[i] * alpha + (p[i][0] + p[i][1]);
-        ts.bv[i] *= alpha;
+        const float sk = scale * cst[i];
+        sc[i][0] = fmaf(si, sc[i][0], sk);
+        sc[i][1] = fmaf(si, sc[i][1], sk);
+        over = fmaxf(over, fmaxf(sc[i][0], sc[i][1]) - ts.m[i]);   // m = -inf before the first block: +inf
+    }
+    if (__builtin_amdgcn_ballot_w64(over > kLazyMax) != 0) {
 #pragma unroll
-        for (int c = 0; c < 4; c++) ts.acc[i][c] *= alpha;
-        ts.m[i] = mnew;
+        for (int i = 0; i < HL; i++) {
+            const float mnew = fmaxf(ts.m[i], half_max(fmaxf(sc[i][0], sc[i][1]), upper));
+            const float alpha = __expf(ts.m[i] - mnew);
+            ts.l[i] *= alpha;
+            ts.bv[i] *= alpha;
+#pragma unroll
+            for (int c = 0; c < 4; c++) ts.acc[i][c] *= alpha;
+            ts.m[i] = mnew;
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < HL; i++) {
+        p[i][0] = __expf(sc[i][0] - ts.m[i]);
+        p[i][1] = __expf(sc[i][1] - ts.m[i]);
+        ts.l[i] += p[i][0] + p[i][1];
     }
 }
 
