@@ -170,6 +170,8 @@ kvcomp_status kvcomp_get_stats(kvcomp_ctx *ctx, kvcomp_stats *h_out, void *strea
  * d_scratch: device scratch of at least blocks*(8192 + 4*units) bytes. */
 kvcomp_status kvcomp_debug_codes(kvcomp_ctx *ctx, int which, const void *d_in, int seq, void *d_scratch,
                                  size_t scratch_bytes, uint8_t *h_codes, uint16_t *h_minmax_fp16, void *stream);
+/* The code histogram of tensor `which` that the last codebook was built from (256 counts, host memory).
+ * Errors: STATE before the first codebook. */
 kvcomp_status kvcomp_get_histogram(kvcomp_ctx *ctx, int which, uint32_t *h_hist256, void *stream);
 kvcomp_status kvcomp_get_codebook(kvcomp_ctx *ctx, int which, uint8_t *h_len256, uint32_t *h_code256);
 /* Block Offsets Array entry of block (b, h, blk): record offset and size in 16-byte units. */

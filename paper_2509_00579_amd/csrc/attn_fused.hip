@@ -1000,8 +1000,8 @@ __global__ __launch_bounds__((64 * MaxWaves<G, LB>::value), 1) void fused_attn_k
     }
     for (int t = 0; t < 2; t++) {
         // pair table: 4096 entries of 4 bytes; otherwise 2^(longest code word of this tensor) entries of 2 bytes
-        const uint4 *src = M::kPair ? reinterpret_cast<const uint4 *>(g.lut2 + t * (1 << kPairIndexBits))
-                                    : reinterpret_cast<const uint4 *>(g.lut + t * kLutSize);
+        const uint4 *src = M::kPair ? reinterpret_cast<const uint4 *>(pair_of(g, t))
+                                    : reinterpret_cast<const uint4 *>(lut_of(g, t));
         uint4 *dst = reinterpret_cast<uint4 *>(&lut_s[t][0]);
         const int n16 = M::kPair ? M::kTableBytes / 16 : max(1, (2 << g.lut_bits[t]) / 16);
         const uint32_t flip = !kTile ? 0u : M::kPair ? 0x00808000u : 0x80008000u;  // the MFMA operands hold symbol - 128 as int8

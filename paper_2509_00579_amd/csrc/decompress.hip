@@ -48,10 +48,10 @@ __global__ __launch_bounds__(64 * kDecWaves) void decompress_kernel(DecompArgs a
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int which = a.which;
     if constexpr (kTree) {  // the tree of this tensor: 256 nodes x 2 children, 16 bits each
-        const uint4 *src = reinterpret_cast<const uint4 *>(g.tree + which * 512);
+        const uint4 *src = reinterpret_cast<const uint4 *>(tree_of(g, which));
         for (int i = tid; i < 64; i += 64 * kDecWaves) reinterpret_cast<uint4 *>(lut_s)[i] = src[i];
     } else {
-        const uint4 *src = reinterpret_cast<const uint4 *>(g.lut + which * kLutSize);
+        const uint4 *src = reinterpret_cast<const uint4 *>(lut_of(g, which));
         uint4 *dst = reinterpret_cast<uint4 *>(lut_s);
         const int n16 = max(1, (2 << g.lut_bits[which]) / 16);
         for (int i = tid; i < n16; i += 64 * kDecWaves) dst[i] = src[i];

@@ -5,7 +5,7 @@
 // The paper reserves space with a global atomic offset, which makes the layout depend on execution order.  Here
 // the same contiguous layout is produced in a fixed order by three launches:
 //   1. size pass   : quantize, sum the code lengths of the block -> record size into the Block Offsets Array
-//   2. place       : one workgroup scans the sizes in (tensor, batch, head, block) order starting at the arena tail
+//   2. place       : the sizes are scanned in (tensor, batch, head, block) order starting at the arena tail
 //   3. write pass  : quantize again, encode, write the record at its offset
 // The store side runs once per token block while the fetch side runs every decode step (Section 3.3), so the
 // second read of the fp16 input is the cheaper trade against a staging copy of all records.
@@ -69,15 +69,15 @@ __global__ __launch_bounds__(256) void size_kernel(Geo g, const uint16_t *__rest
     __shared__ uint32_t scratch[4];
     const int tid = threadIdx.x, blk = blockIdx.x;
     const int bh = blk / n_blk_per_bh, j = blk - bh * n_blk_per_bh;
-    enc[tid] = g.enc[WHICH * 512 + tid];
+    enc[tid] = enc_of(g, WHICH)[tid];
     TileRegs r;
     bool bad = false;
     if constexpr (KEPT) {
         load_kept_codes(kept, (size_t)bh * kept.blk_per_bh + j, tid, r);
         __syncthreads();  // enc[] is visible
     } else {
-        bad = load_tile(X, seq_stride, g.H, bh / g.H, bh % g.H, j, tid, r);
-        quantize_tile<WHICH>(r, sh, tid, g.two_eb[WHICH], g.n_sym[WHICH], g.k_units);  // has barriers: enc[] is visible after it
+        load_tile(X, seq_stride, g.H, bh / g.H, bh % g.H, j, tid, r);
+        bad = quantize_tile<WHICH>(r, sh, tid, g.two_eb[WHICH], g.n_sym[WHICH], g.k_units);  // has barriers: enc[] is visible after it
     }
     uint32_t bits = 0;
 #pragma unroll
@@ -93,88 +93,141 @@ __global__ __launch_bounds__(256) void size_kernel(Geo g, const uint16_t *__rest
 }
 
 // ---- 2. placement ------------------------------------------------------------------------------------------
-// Items in order: tensor K then V; inside a tensor (b,h) major, block minor.  One workgroup of 1024 threads walks the
-// items in chunks of 8192: sizes are loaded coalesced into LDS, every thread scans its eight consecutive items, the
-// thread sums are scanned over the workgroup, and the offsets go back to the table coalesced.
-constexpr int kPlaceThreads = 1024, kPlacePerThread = 8, kPlaceChunk = kPlaceThreads * kPlacePerThread;
+// Items in order: tensor K then V; inside a tensor (b,h) major, block minor.  Two launches over chunks of kPlaceChunk
+// items, one workgroup of 256 threads per chunk (eight consecutive items per thread):
+//   place_sum_kernel  : the sizes of a chunk summed -> place_sums[chunk]; the arena tail is copied to tail_base
+//   place_scan_kernel : every workgroup adds up the chunk sums before its own (and all of them: what the placement
+//                       needs in total), scans its own items from there and writes their offsets; the first
+//                       workgroup moves the tail.
+// Loads and stores of the table are coalesced through an LDS copy of the chunk.
+constexpr int kPlaceThreads = 256, kPlacePerThread = kPlaceChunk / kPlaceThreads;
 __device__ __forceinline__ int place_pad(int i) { return i + (i >> 5); }  // one spare word per 32: no bank conflicts
 
-__global__ __launch_bounds__(kPlaceThreads) void place_kernel(Geo g, int n_blk_per_bh, int dst_blk0) {
-    __shared__ uint32_t val[kPlaceChunk + kPlaceChunk / 32];
-    __shared__ uint32_t wave_tot[16];
-    const int tid = threadIdx.x;
-    const int n_items = 2 * g.B * g.H * n_blk_per_bh;
-    auto entry = [&](int i) -> BlockEntry * {  // row = tensor * B*H + (b*H + h)
+struct PlaceItems {
+    BlockEntry *table;
+    int max_blocks, n_blk_per_bh, dst_blk0, n_items;
+    __device__ PlaceItems(const Geo &g, int n_blk_per_bh_, int dst_blk0_)
+        : table(g.table), max_blocks(g.max_blocks), n_blk_per_bh(n_blk_per_bh_), dst_blk0(dst_blk0_),
+          n_items(2 * g.B * g.H * n_blk_per_bh_) {}
+    __device__ BlockEntry *entry(int i) const {  // row = tensor * B*H + (b*H + h)
         const int row = i / n_blk_per_bh, j = i - row * n_blk_per_bh;
-        return &g.table[(size_t)row * g.max_blocks + dst_blk0 + j];
-    };
-    // The host only starts a placement that fits the arena.  A replay of a captured flush without the eager calls in
-    // between (which the interface forbids) would advance the tail on every replay: the sizes are therefore summed
-    // first, and a placement that would run past the arena sets a fault bit, points its entries at the arena start
-    // (so that later readers stay in bounds) and leaves the tail where it is; the write pass then writes nothing.
-    unsigned long long need = 0;
-    for (int i = tid; i < n_items; i += kPlaceThreads) need += entry(i)->size16;
+        return &table[(size_t)row * max_blocks + dst_blk0 + j];
+    }
+};
+
+__global__ __launch_bounds__(kPlaceThreads) void place_sum_kernel(Geo g, int n_blk_per_bh, int dst_blk0) {
+    __shared__ uint32_t wave_tot[kPlaceThreads / 64];
+    const PlaceItems it(g, n_blk_per_bh, dst_blk0);
+    const int tid = threadIdx.x, c0 = blockIdx.x * kPlaceChunk;
+    uint32_t sum = 0;
 #pragma unroll
-    for (int m = 32; m >= 1; m >>= 1) need += __shfl_xor(need, m);
-    __shared__ unsigned long long need_s[16];
-    if ((tid & 63) == 0) need_s[tid >> 6] = need;
+    for (int k = 0; k < kPlacePerThread; k++) {
+        const int i = c0 + k * kPlaceThreads + tid;
+        if (i < it.n_items) sum += it.entry(i)->size16;
+    }
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) sum += __shfl_xor(sum, m);
+    if ((tid & 63) == 0) wave_tot[tid >> 6] = sum;
+    __syncthreads();
+    if (tid == 0) {
+        uint32_t all = 0;
+        for (int w = 0; w < kPlaceThreads / 64; w++) all += wave_tot[w];
+        g.place_sums[blockIdx.x] = all;   // a chunk of 2048 records of at most 13 KiB: far below 2^32 units
+        if (blockIdx.x == 0) g.ctrl->tail_base = g.ctrl->tail16;
+    }
+}
+
+__global__ __launch_bounds__(kPlaceThreads) void place_scan_kernel(Geo g, int n_blk_per_bh, int dst_blk0) {
+    __shared__ uint32_t val[kPlaceChunk + kPlaceChunk / 32];
+    __shared__ uint32_t wave_tot[kPlaceThreads / 64];
+    __shared__ unsigned long long sums_s[2][kPlaceThreads / 64];
+    const PlaceItems it(g, n_blk_per_bh, dst_blk0);
+    const int tid = threadIdx.x, c0 = blockIdx.x * kPlaceChunk;
+    // what the chunks before this one need, and what all chunks need
+    unsigned long long before_me = 0, need = 0;
+    for (int c = tid; c < (int)gridDim.x; c += kPlaceThreads) {
+        const uint32_t v = g.place_sums[c];
+        need += v;
+        if (c < (int)blockIdx.x) before_me += v;
+    }
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) {
+        need += __shfl_xor(need, m);
+        before_me += __shfl_xor(before_me, m);
+    }
+    if ((tid & 63) == 0) {
+        sums_s[0][tid >> 6] = need;
+        sums_s[1][tid >> 6] = before_me;
+    }
     __syncthreads();
     need = 0;
-    for (int w = 0; w < 16; w++) need += need_s[w];
-    const uint32_t tail0 = g.ctrl->tail16;
+    before_me = 0;
+    for (int w = 0; w < kPlaceThreads / 64; w++) {
+        need += sums_s[0][w];
+        before_me += sums_s[1][w];
+    }
+    // The host only starts a placement that fits the arena.  A replay of a captured flush without the eager calls in
+    // between (which the interface forbids) would advance the tail on every replay: a placement that would run past
+    // the arena sets a fault bit, points its entries at the arena start (so that later readers stay in bounds) and
+    // leaves the tail where it is; the write pass then writes nothing.
+    const uint32_t tail0 = g.ctrl->tail_base;
     if ((unsigned long long)tail0 + need > (unsigned long long)g.payload_cap16) {
-        for (int i = tid; i < n_items; i += kPlaceThreads) entry(i)->off16 = 0;
-        if (tid == 0) atomicOr(&g.ctrl->fault, kFaultArenaFull);
+#pragma unroll
+        for (int k = 0; k < kPlacePerThread; k++) {
+            const int i = c0 + k * kPlaceThreads + tid;
+            if (i < it.n_items) it.entry(i)->off16 = 0;
+        }
+        if (blockIdx.x == 0 && tid == 0) atomicOr(&g.ctrl->fault, kFaultArenaFull);
         return;
     }
-    uint32_t base = tail0, biggest = 0;
-    for (int c0 = 0; c0 < n_items; c0 += kPlaceChunk) {
+    uint32_t biggest = 0;
 #pragma unroll
-        for (int k = 0; k < kPlacePerThread; k++) {
-            const int i = c0 + k * kPlaceThreads + tid;
-            const uint32_t s16 = i < n_items ? entry(i)->size16 : 0u;
-            biggest = max(biggest, s16);
-            val[place_pad(k * kPlaceThreads + tid)] = s16;
-        }
-        __syncthreads();
-        uint32_t mine[kPlacePerThread], sum = 0;
+    for (int k = 0; k < kPlacePerThread; k++) {
+        const int i = c0 + k * kPlaceThreads + tid;
+        const uint32_t s16 = i < it.n_items ? it.entry(i)->size16 : 0u;
+        biggest = max(biggest, s16);
+        val[place_pad(k * kPlaceThreads + tid)] = s16;
+    }
+    __syncthreads();
+    uint32_t mine[kPlacePerThread], sum = 0;
 #pragma unroll
-        for (int k = 0; k < kPlacePerThread; k++) {
-            mine[k] = val[place_pad(tid * kPlacePerThread + k)];
-            sum += mine[k];
-        }
-        uint32_t inc = sum;  // inclusive scan of `sum` over the 1024 threads
+    for (int k = 0; k < kPlacePerThread; k++) {
+        mine[k] = val[place_pad(tid * kPlacePerThread + k)];
+        sum += mine[k];
+    }
+    uint32_t inc = sum;  // inclusive scan of `sum` over the workgroup
 #pragma unroll
-        for (int d = 1; d < 64; d <<= 1) {
-            const uint32_t o = __shfl_up(inc, d);
-            if ((tid & 63) >= d) inc += o;
-        }
-        if ((tid & 63) == 63) wave_tot[tid >> 6] = inc;
-        __syncthreads();
-        uint32_t before = 0, all = 0;
-        for (int w = 0; w < 16; w++) {
-            if (w < (tid >> 6)) before += wave_tot[w];
-            all += wave_tot[w];
-        }
-        uint32_t at = base + before + inc - sum;
+    for (int d = 1; d < 64; d <<= 1) {
+        const uint32_t o = __shfl_up(inc, d);
+        if ((tid & 63) >= d) inc += o;
+    }
+    if ((tid & 63) == 63) wave_tot[tid >> 6] = inc;
+    __syncthreads();
+    uint32_t before = 0;
+    for (int w = 0; w < (tid >> 6); w++) before += wave_tot[w];
+    uint32_t at = tail0 + (uint32_t)before_me + before + inc - sum;
 #pragma unroll
-        for (int k = 0; k < kPlacePerThread; k++) {
-            val[place_pad(tid * kPlacePerThread + k)] = at;
-            at += mine[k];
-        }
-        __syncthreads();
+    for (int k = 0; k < kPlacePerThread; k++) {
+        val[place_pad(tid * kPlacePerThread + k)] = at;
+        at += mine[k];
+    }
+    __syncthreads();
 #pragma unroll
-        for (int k = 0; k < kPlacePerThread; k++) {
-            const int i = c0 + k * kPlaceThreads + tid;
-            if (i < n_items) entry(i)->off16 = val[place_pad(k * kPlaceThreads + tid)];
-        }
-        base += all;
-        __syncthreads();  // val and wave_tot are reused by the next chunk
+    for (int k = 0; k < kPlacePerThread; k++) {
+        const int i = c0 + k * kPlaceThreads + tid;
+        if (i < it.n_items) it.entry(i)->off16 = val[place_pad(k * kPlaceThreads + tid)];
     }
 #pragma unroll
     for (int m = 32; m >= 1; m >>= 1) biggest = max(biggest, (uint32_t)__shfl_xor(biggest, m));
     if ((tid & 63) == 0 && biggest) atomicMax(&g.ctrl->max_size16, biggest);
-    if (tid == 0) g.ctrl->tail16 = base;
+    if (blockIdx.x == 0 && tid == 0) g.ctrl->tail16 = tail0 + (uint32_t)need;
+}
+
+static void launch_place(const Geo &g, int n_blk_per_bh, int dst_blk0, hipStream_t s) {
+    const int n_items = 2 * g.B * g.H * n_blk_per_bh;
+    const int chunks = (n_items + kPlaceChunk - 1) / kPlaceChunk;
+    hipLaunchKernelGGL(place_sum_kernel, dim3(chunks), dim3(kPlaceThreads), 0, s, g, n_blk_per_bh, dst_blk0);
+    hipLaunchKernelGGL(place_scan_kernel, dim3(chunks), dim3(kPlaceThreads), 0, s, g, n_blk_per_bh, dst_blk0);
 }
 
 // ---- 3. write pass -----------------------------------------------------------------------------------------
@@ -190,8 +243,8 @@ __global__ __launch_bounds__(256) void write_kernel(Geo g, const uint16_t *__res
     const int tid = threadIdx.x, blk = blockIdx.x;
     const int bh = blk / n_blk_per_bh, j = blk - bh * n_blk_per_bh;
     if (g.ctrl->fault & kFaultArenaFull) return;  // the placement found no room (uniform over the workgroup)
-    enc[tid] = g.enc[WHICH * 512 + tid];
-    enc[256 + tid] = g.enc[WHICH * 512 + 256 + tid];
+    enc[tid] = enc_of(g, WHICH)[tid];
+    enc[256 + tid] = enc_of(g, WHICH)[256 + tid];
     for (int i = tid; i < (int)(sizeof(rec) / 4); i += 256) rec[i] = 0;
     TileRegs r;
     if constexpr (KEPT) {
@@ -265,7 +318,7 @@ __global__ __launch_bounds__(256) void write_kernel(Geo g, const uint16_t *__res
     }
     if (fill) atomicOr(&pay[word], (uint32_t)acc);
     __syncthreads();
-    // stages 5-6: the offset was fixed by place_kernel; coalesced 16-byte stores of header + chunk + padding
+    // stages 5-6: the offset was fixed by the placement; coalesced 16-byte stores of header + chunk + padding
     const BlockEntry e = g.table[((size_t)WHICH * g.B * g.H + bh) * g.max_blocks + dst_blk0 + j];
     const uint32_t n16 = record_size16(R::hdr_bytes(g), total);  // equals e.size16 by construction
     uint4 *dst = reinterpret_cast<uint4 *>(g.payload + (size_t)e.off16 * 16);
@@ -281,22 +334,31 @@ hipError_t launch_encode(const Geo &g, const uint16_t *XK, const uint16_t *XV, i
     const Kept none = {nullptr, nullptr, 0};
     hipLaunchKernelGGL((size_kernel<0, false>), dim3(total), dim3(256), 0, s, g, XK, seq_stride, n_blk_per_bh, dst_blk0, none);
     hipLaunchKernelGGL((size_kernel<1, false>), dim3(total), dim3(256), 0, s, g, XV, seq_stride, n_blk_per_bh, dst_blk0, none);
-    hipLaunchKernelGGL(place_kernel, dim3(1), dim3(1024), 0, s, g, n_blk_per_bh, dst_blk0);
+    launch_place(g, n_blk_per_bh, dst_blk0, s);
     hipLaunchKernelGGL((write_kernel<0, false>), dim3(total), dim3(256), 0, s, g, XK, seq_stride, n_blk_per_bh, dst_blk0, none);
     hipLaunchKernelGGL((write_kernel<1, false>), dim3(total), dim3(256), 0, s, g, XV, seq_stride, n_blk_per_bh, dst_blk0, none);
     return hipGetLastError();
 }
 
 // The same from codes and min/max kept by launch_histogram (kept_blk_per_bh blocks per (batch, head) there, of which
-// the first n_blk_per_bh are encoded): no second and third quantization of the input.
-hipError_t launch_encode_kept(const Geo &g, const uint8_t *codesK, const uint32_t *mmK, const uint8_t *codesV,
-                              const uint32_t *mmV, int kept_blk_per_bh, int n_blk_per_bh, hipStream_t s) {
+// the first n_blk_per_bh are encoded): no second and third quantization of the input.  In two parts, so that the size
+// pass of a tensor can be queued as soon as its codebook is on the device: the sizes of one tensor; then, once both
+// are queued, the placement and the two write passes.
+hipError_t launch_size_kept(const Geo &g, int which, const uint8_t *codes, const uint32_t *mm, int kept_blk_per_bh,
+                            int n_blk_per_bh, hipStream_t s) {
+    const int total = g.B * g.H * n_blk_per_bh;
+    if (total <= 0) return hipSuccess;
+    const Kept k = {codes, mm, kept_blk_per_bh};
+    if (which == 0) hipLaunchKernelGGL((size_kernel<0, true>), dim3(total), dim3(256), 0, s, g, nullptr, 0, n_blk_per_bh, 0, k);
+    else hipLaunchKernelGGL((size_kernel<1, true>), dim3(total), dim3(256), 0, s, g, nullptr, 0, n_blk_per_bh, 0, k);
+    return hipGetLastError();
+}
+hipError_t launch_place_write_kept(const Geo &g, const uint8_t *codesK, const uint32_t *mmK, const uint8_t *codesV,
+                                   const uint32_t *mmV, int kept_blk_per_bh, int n_blk_per_bh, hipStream_t s) {
     const int total = g.B * g.H * n_blk_per_bh;
     if (total <= 0) return hipSuccess;
     const Kept kk = {codesK, mmK, kept_blk_per_bh}, kv = {codesV, mmV, kept_blk_per_bh};
-    hipLaunchKernelGGL((size_kernel<0, true>), dim3(total), dim3(256), 0, s, g, nullptr, 0, n_blk_per_bh, 0, kk);
-    hipLaunchKernelGGL((size_kernel<1, true>), dim3(total), dim3(256), 0, s, g, nullptr, 0, n_blk_per_bh, 0, kv);
-    hipLaunchKernelGGL(place_kernel, dim3(1), dim3(1024), 0, s, g, n_blk_per_bh, 0);
+    launch_place(g, n_blk_per_bh, 0, s);
     hipLaunchKernelGGL((write_kernel<0, true>), dim3(total), dim3(256), 0, s, g, nullptr, 0, n_blk_per_bh, 0, kk);
     hipLaunchKernelGGL((write_kernel<1, true>), dim3(total), dim3(256), 0, s, g, nullptr, 0, n_blk_per_bh, 0, kv);
     return hipGetLastError();

@@ -15,7 +15,7 @@
 namespace kvc {
 namespace host {
 
-constexpr int kPairEntries = 1 << 12;  // entries of a pair table (12 index bits)
+constexpr int kPairEntries = kPairTableEntries;  // entries of a pair table (12 index bits)
 
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
@@ -56,7 +56,7 @@ inline int k_header_bytes(const kvcomp_config &c) { return k_minmax_bytes(c) + 2
 inline int code_len_limit(const kvcomp_config &c) { return c.max_code_len ? c.max_code_len : kLutBits; }
 
 struct Layout {
-    size_t ctrl, hist, enc, lut, tree, lut2, counters, table, res, partials, payload, total;
+    size_t ctrl, hist, tables, counters, place_sums, table, res, partials, payload, total;
     size_t payload_cap16;
     int max_blocks;
 };
@@ -71,11 +71,9 @@ inline Layout make_layout(const kvcomp_config &c) {
     size_t at = 0;
     L.ctrl = at; at += 256;
     L.hist = at; at += 2 * 256 * 4;
-    L.enc = at; at += 4 * 256 * 4;
-    L.lut = at; at += 2 * kLutSize * 2;
-    L.tree = at; at += 2 * 256 * 2 * 2;
-    L.lut2 = at; at += 2 * kPairEntries * 4;
+    L.tables = at; at += 2 * (size_t)kTensorTablesBytes;
     L.counters = at; at += align_up(BH * 4, 256);
+    L.place_sums = at; at += align_up((2 * BH * (size_t)std::max(L.max_blocks, 1) / kPlaceChunk + 1) * 4, 256);
     L.table = at; at += align_up(2 * BH * (size_t)std::max(L.max_blocks, 1) * sizeof(BlockEntry), 256);
     L.res = at; at += align_up(2 * (size_t)c.batch * buffer_tokens(c) * c.n_kv_heads * kD * 2, 256);
     L.partials = at; at += align_up((size_t)c.batch * c.n_q_heads * kMaxSplits * kPartialStride * 4, 256);
@@ -90,53 +88,65 @@ inline Layout make_layout(const kvcomp_config &c) {
 // ---- Huffman codebook (Section 3.1.2), canonical and length-limited --------------------------------------------
 // Two-queue construction over leaves sorted by (count, symbol); on equal weight a leaf is taken before a merged
 // node and merged nodes leave in creation order, which fixes the code lengths uniquely.
-inline void huffman_lengths(const std::vector<uint64_t> &f, std::vector<int> &len) {
-    const int n = (int)f.size();
-    std::vector<int> order(n);
-    std::iota(order.begin(), order.end(), 0);
-    std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return f[a] < f[b]; });
-    struct Node { uint64_t w; int kid[2]; };
-    std::vector<Node> nodes;
-    nodes.reserve(2 * n);
-    for (int i = 0; i < n; i++) nodes.push_back({f[order[i]], {-1, -1}});
-    int leaf = 0, ihead = n;
+// This runs between two device passes of a prompt compression, with the GPU idle: fixed arrays, no allocation.
+// key: the n <= 256 leaves as (weight << 8) | symbol, weights below 2^40, sorted ascending (which is the stable sort
+// by weight); len: code length per symbol.
+inline void huffman_lengths(const uint64_t *key, int n, int *len) {
+    uint64_t w[512];
+    int kid[512][2], depth[512];
+    for (int i = 0; i < n; i++) w[i] = key[i] >> 8;
+    int leaf = 0, ihead = n, n_nodes = n;
     auto take = [&]() {
-        const bool has_leaf = leaf < n, has_int = ihead < (int)nodes.size();
-        if (has_leaf && (!has_int || nodes[leaf].w <= nodes[ihead].w)) return leaf++;
+        const bool has_leaf = leaf < n, has_int = ihead < n_nodes;
+        if (has_leaf && (!has_int || w[leaf] <= w[ihead])) return leaf++;
         return ihead++;
     };
     for (int k = 0; k < n - 1; k++) {
         const int a = take(), b = take();
-        nodes.push_back({nodes[a].w + nodes[b].w, {a, b}});
+        w[n_nodes] = w[a] + w[b];
+        kid[n_nodes][0] = a;
+        kid[n_nodes][1] = b;
+        n_nodes++;
     }
-    std::vector<int> depth(nodes.size(), 0);
-    for (int i = (int)nodes.size() - 1; i >= n; i--) {
-        depth[nodes[i].kid[0]] = depth[i] + 1;
-        depth[nodes[i].kid[1]] = depth[i] + 1;
+    for (int i = 0; i < n_nodes; i++) depth[i] = 0;
+    for (int i = n_nodes - 1; i >= n; i--) {
+        depth[kid[i][0]] = depth[i] + 1;
+        depth[kid[i][1]] = depth[i] + 1;
     }
-    len.assign(n, 0);
-    for (int i = 0; i < n; i++) len[order[i]] = depth[i];
+    for (int i = 0; i < n; i++) len[(int)(key[i] & 0xffu)] = depth[i];
 }
 
 inline void build_codebook_host(const uint32_t *hist, int n_sym, int max_len, uint8_t *len_out, uint32_t *code_out) {
-    std::vector<uint64_t> f(n_sym);
-    for (int s = 0; s < n_sym; s++) f[s] = hist[s] ? hist[s] : 1;  // later blocks reuse the codebook: no level unencodable
-    std::vector<int> len;
+    uint64_t key[256];
+    int len[256];
+    // later blocks reuse the codebook: no level may be unencodable
+    for (int s = 0; s < n_sym; s++) key[s] = ((uint64_t)(hist[s] ? hist[s] : 1) << 8) | (uint64_t)s;
+    std::sort(key, key + n_sym);
     for (;;) {
-        huffman_lengths(f, len);
-        if (*std::max_element(len.begin(), len.end()) <= max_len) break;
-        for (auto &v : f) v = std::max<uint64_t>(1, (v + 1) >> 1);
+        huffman_lengths(key, n_sym, len);
+        if (*std::max_element(len, len + n_sym) <= max_len) break;
+        // too deep: halve every weight (rounding up, at least 1) and try again.  Halving keeps the order of the
+        // weights; only leaves that became equal may have to swap into symbol order: an insertion sort over an
+        // almost sorted array
+        for (int i = 0; i < n_sym; i++) {
+            const uint64_t wgt = std::max<uint64_t>(1, ((key[i] >> 8) + 1) >> 1);
+            uint64_t k = (wgt << 8) | (key[i] & 0xffu);
+            int j = i;
+            for (; j > 0 && key[j - 1] > k; j--) key[j] = key[j - 1];
+            key[j] = k;
+        }
     }
     std::memset(len_out, 0, 256);
     std::memset(code_out, 0, 256 * sizeof(uint32_t));
-    std::vector<int> by(n_sym);
-    std::iota(by.begin(), by.end(), 0);
-    std::stable_sort(by.begin(), by.end(), [&](int a, int b) { return len[a] < len[b]; });
+    // canonical code words: symbols by (length, symbol)
+    uint32_t by[256];
+    for (int s = 0; s < n_sym; s++) by[s] = ((uint32_t)len[s] << 8) | (uint32_t)s;
+    std::sort(by, by + n_sym);
     uint32_t code = 0;
     for (int i = 0; i < n_sym; i++) {
-        const int s = by[i];
-        if (i) code = (code + 1) << (len[s] - len[by[i - 1]]);
-        len_out[s] = (uint8_t)len[s];
+        const int s = (int)(by[i] & 0xffu), L = (int)(by[i] >> 8);
+        if (i) code = (code + 1) << (L - (int)(by[i - 1] >> 8));
+        len_out[s] = (uint8_t)L;
         code_out[s] = code;
     }
 }

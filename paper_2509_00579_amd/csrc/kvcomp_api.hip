@@ -56,10 +56,9 @@ struct kvcomp_ctx {
     // pinned host staging
     Ctrl *h_ctrl;
     uint32_t *h_hist;  // [2][256]
-    uint32_t *h_enc;   // [2 tensors][2 directions][256]
-    uint16_t *h_lut;   // [2][4096]
-    int16_t *h_tree;   // [2][256][2]
-    uint32_t *h_lut2;  // [2][4096]
+    uint8_t *h_tables; // [2 tensors][kTensorTablesBytes], laid out like Geo::tables
+    uint8_t *h_tables_dev;  // the same memory as kernels address it
+    hipEvent_t ev_hist[2];  // the histogram of K, of V has reached the host
 };
 
 namespace {
@@ -147,12 +146,10 @@ kvcomp_status kvcomp_create(const kvcomp_config *cfg, void *d_arena, size_t aren
     g.n_sym[1] = n_sym_for(cfg->rel_eb_v);
     g.ctrl = reinterpret_cast<Ctrl *>(c->arena + L.ctrl);
     g.hist = reinterpret_cast<uint32_t *>(c->arena + L.hist);
-    g.enc = reinterpret_cast<uint32_t *>(c->arena + L.enc);
-    g.lut = reinterpret_cast<uint16_t *>(c->arena + L.lut);
-    g.tree = reinterpret_cast<int16_t *>(c->arena + L.tree);
-    g.lut2 = reinterpret_cast<uint32_t *>(c->arena + L.lut2);
+    g.tables = c->arena + L.tables;
     g.lut_bits[0] = g.lut_bits[1] = kLutBits;
     g.counters = reinterpret_cast<uint32_t *>(c->arena + L.counters);
+    g.place_sums = reinterpret_cast<uint32_t *>(c->arena + L.place_sums);
     g.table = reinterpret_cast<BlockEntry *>(c->arena + L.table);
     g.res = reinterpret_cast<uint16_t *>(c->arena + L.res);
     g.res_tokens = buffer_tokens(*cfg);
@@ -160,7 +157,7 @@ kvcomp_status kvcomp_create(const kvcomp_config *cfg, void *d_arena, size_t aren
     g.payload = c->arena + L.payload;
     g.payload_cap16 = (uint32_t)L.payload_cap16;
     void *pinned = nullptr;
-    const size_t pin_bytes = 256 + 2 * 256 * 4 + 4 * 256 * 4 + 2 * kLutSize * 2 + 2 * 256 * 2 * 2 + 2 * kPairEntries * 4;
+    const size_t pin_bytes = 256 + 2 * 256 * 4 + 2 * (size_t)kTensorTablesBytes;
     hipError_t e = hipHostMalloc(&pinned, pin_bytes, hipHostMallocDefault);
     if (e != hipSuccess) {
         delete c;
@@ -169,13 +166,30 @@ kvcomp_status kvcomp_create(const kvcomp_config *cfg, void *d_arena, size_t aren
     uint8_t *pb = static_cast<uint8_t *>(pinned);
     c->h_ctrl = reinterpret_cast<Ctrl *>(pb);
     c->h_hist = reinterpret_cast<uint32_t *>(pb + 256);
-    c->h_enc = reinterpret_cast<uint32_t *>(pb + 256 + 2048);
-    c->h_lut = reinterpret_cast<uint16_t *>(pb + 256 + 2048 + 4096);
-    c->h_tree = reinterpret_cast<int16_t *>(pb + 256 + 2048 + 4096 + 2 * kLutSize * 2);
-    c->h_lut2 = reinterpret_cast<uint32_t *>(pb + 256 + 2048 + 4096 + 2 * kLutSize * 2 + 2 * 256 * 2 * 2);
+    c->h_tables = pb + 256 + 2048;
+    {
+        void *dev = nullptr;
+        e = hipHostGetDevicePointer(&dev, pinned, 0);
+        if (e != hipSuccess) {
+            (void)hipHostFree(pinned);
+            delete c;
+            return fail(KVCOMP_ERR_HIP, "hipHostGetDevicePointer: %s", hipGetErrorString(e));
+        }
+        c->h_tables_dev = static_cast<uint8_t *>(dev) + 256 + 2048;
+    }
+    c->ev_hist[0] = c->ev_hist[1] = nullptr;
+    for (int w = 0; w < 2 && e == hipSuccess; w++) e = hipEventCreateWithFlags(&c->ev_hist[w], hipEventDisableTiming);
+    if (e != hipSuccess) {
+        for (int w = 0; w < 2; w++)
+            if (c->ev_hist[w]) (void)hipEventDestroy(c->ev_hist[w]);
+        (void)hipHostFree(pinned);
+        delete c;
+        return fail(KVCOMP_ERR_HIP, "hipEventCreate: %s", hipGetErrorString(e));
+    }
     // control words, histogram, tables and the Block Offsets Array start at zero
     e = launch_fill_zero(c->arena, L.res, static_cast<hipStream_t>(stream));
     if (e != hipSuccess) {
+        for (int w = 0; w < 2; w++) (void)hipEventDestroy(c->ev_hist[w]);
         (void)hipHostFree(pinned);
         delete c;
         return fail(KVCOMP_ERR_HIP, "arena init: %s", hipGetErrorString(e));
@@ -187,6 +201,7 @@ kvcomp_status kvcomp_create(const kvcomp_config *cfg, void *d_arena, size_t aren
 kvcomp_status kvcomp_destroy(kvcomp_ctx *ctx) {
     if (!ctx) return KVCOMP_OK;
     for (hipEvent_t ev : ctx->events) (void)hipEventDestroy(ev);
+    for (int w = 0; w < 2; w++) (void)hipEventDestroy(ctx->ev_hist[w]);
     (void)hipHostFree(ctx->h_ctrl);
     delete ctx;
     return KVCOMP_OK;
@@ -222,10 +237,31 @@ static PrefillWs prefill_layout(const kvcomp_config &c, int seq, void *base) {
     return w;
 }
 
+// The codebook of tensor w from its histogram on the host, its tables, and their upload by a kernel that reads the
+// pinned staging block (stream-ordered: whatever uses the tables comes after it on the same stream, and this tensor's
+// part of the staging block is not rewritten before the next codebook).
+static kvcomp_status codebook_of(kvcomp_ctx *ctx, int w, const uint32_t *hist, hipStream_t s) {
+    Geo &g = ctx->geo;
+    uint8_t *tab = ctx->h_tables + (size_t)w * kTensorTablesBytes;
+    uint16_t *lut = reinterpret_cast<uint16_t *>(tab + kTabLutOff);
+    uint32_t *pair = reinterpret_cast<uint32_t *>(tab + kTabPairOff);
+    build_codebook_host(hist, g.n_sym[w], code_len_limit(ctx->cfg), ctx->len[w], ctx->code[w]);
+    g.lut_bits[w] = build_tables(ctx->len[w], ctx->code[w], reinterpret_cast<uint32_t *>(tab + kTabEncOff), lut,
+                                 reinterpret_cast<int16_t *>(tab + kTabTreeOff));
+    if (g.lut_bits[w] <= 6) build_pair_table(lut, g.lut_bits[w], pair);
+    else std::memset(pair, 0, kPairEntries * 4);
+    static_assert(kTensorTablesBytes % 16 == 0, "whole 16-byte units");
+    HIP_TRY(launch_copy16(g.tables + (size_t)w * kTensorTablesBytes, ctx->h_tables_dev + (size_t)w * kTensorTablesBytes,
+                          kTensorTablesBytes, s));
+    return KVCOMP_OK;
+}
+
 // Histogram on the device, codebooks on the host, tables to the device (Section 3).  ws != NULL: the histogram pass
-// also keeps the codes and min/max of every block there.
+// also keeps the codes and min/max of every block there, and the size pass of the first n_blk blocks per (batch, head)
+// is queued for each tensor as soon as its tables are.
+// The host's part for K runs while the device histograms V, and the size pass of K while the host does V's.
 static kvcomp_status codebook_impl(kvcomp_ctx *ctx, const void *d_K, const void *d_V, int seq, const PrefillWs *ws,
-                                   hipStream_t s) {
+                                   int n_blk, hipStream_t s) {
     if (!aligned16(d_K) || !aligned16(d_V)) return fail(KVCOMP_ERR_INVALID_ARG, "K/V must be 16-byte aligned");
     if (seq < kBT || seq > ctx->cfg.max_seq)
         return fail(KVCOMP_ERR_INVALID_ARG, "seq %d outside [64, max_seq=%d]", seq, ctx->cfg.max_seq);
@@ -235,31 +271,35 @@ static kvcomp_status codebook_impl(kvcomp_ctx *ctx, const void *d_K, const void 
     const long long symbols = (long long)ctx->geo.B * ctx->geo.H * (seq / kBT) * kTile;
     if (symbols >= (1ll << 32)) return fail(KVCOMP_ERR_INVALID_ARG, "more than 2^32 symbols per tensor");
     Geo &g = ctx->geo;
-    HIP_TRY(launch_fill_zero(g.hist, 2 * 256 * 4, s));
+    static_assert(sizeof(Ctrl) <= 256, "control words fill the first 256 bytes");
+    // the device histogram is zero here: the arena starts that way, and every call leaves it so (below)
     HIP_TRY(launch_histogram(g, 0, static_cast<const uint16_t *>(d_K), seq, seq / kBT, ws ? ws->codes[0] : nullptr,
                              ws ? ws->minmax[0] : nullptr, s));
+    HIP_TRY(hipMemcpyAsync(ctx->h_hist, g.hist, 256 * 4, hipMemcpyDeviceToHost, s));
+    HIP_TRY(hipEventRecord(ctx->ev_hist[0], s));
     HIP_TRY(launch_histogram(g, 1, static_cast<const uint16_t *>(d_V), seq, seq / kBT, ws ? ws->codes[1] : nullptr,
                              ws ? ws->minmax[1] : nullptr, s));
-    // control words and histograms are neighbours in the arena and in the pinned staging block: one copy
-    static_assert(sizeof(Ctrl) <= 256, "control words fill the first 256 bytes");
+    // control words and the histogram of V (neighbours of K's histogram in the arena and in the staging block, which
+    // therefore travels again: the same values over the same bytes)
     HIP_TRY(hipMemcpyAsync(ctx->h_ctrl, g.ctrl, 256 + 2 * 256 * 4, hipMemcpyDeviceToHost, s));
-    HIP_TRY(hipStreamSynchronize(s));
+    HIP_TRY(hipEventRecord(ctx->ev_hist[1], s));
+    HIP_TRY(launch_fill_zero(g.hist, 2 * 256 * 4, s));  // for the next call; runs while the host builds the codebooks
+    HIP_TRY(hipEventSynchronize(ctx->ev_hist[0]));
+    {
+        uint32_t hist_k[256];
+        std::memcpy(hist_k, ctx->h_hist, sizeof(hist_k));
+        kvcomp_status st = codebook_of(ctx, 0, hist_k, s);
+        if (st) return st;
+    }
+    if (ws) HIP_TRY(launch_size_kept(g, 0, ws->codes[0], ws->minmax[0], seq / kBT, n_blk, s));
+    HIP_TRY(hipEventSynchronize(ctx->ev_hist[1]));
     {
         kvcomp_status st = check_flags(ctx, s);
         if (st) return st;
+        st = codebook_of(ctx, 1, ctx->h_hist + 256, s);
+        if (st) return st;
     }
-    for (int w = 0; w < 2; w++) {
-        build_codebook_host(ctx->h_hist + 256 * w, g.n_sym[w], code_len_limit(ctx->cfg), ctx->len[w], ctx->code[w]);
-        ctx->geo.lut_bits[w] = build_tables(ctx->len[w], ctx->code[w], ctx->h_enc + 512 * w, ctx->h_lut + kLutSize * w,
-                                            ctx->h_tree + 512 * w);
-        if (ctx->geo.lut_bits[w] <= 6) build_pair_table(ctx->h_lut + kLutSize * w, ctx->geo.lut_bits[w], ctx->h_lut2 + kPairEntries * w);
-        else std::memset(ctx->h_lut2 + kPairEntries * w, 0, kPairEntries * 4);
-    }
-    // encode tables, decode tables and trees are neighbours too: one upload (stream-ordered: whatever uses the tables
-    // comes after it on the same stream, and the pinned staging block is not rewritten before the next codebook)
-    static_assert(kPairEntries == kPairTableEntries, "pair table size");
-    HIP_TRY(hipMemcpyAsync(g.enc, ctx->h_enc, 4 * 256 * 4 + 2 * kLutSize * 2 + 2 * 256 * 2 * 2 + 2 * kPairEntries * 4,
-                           hipMemcpyHostToDevice, s));
+    if (ws) HIP_TRY(launch_size_kept(g, 1, ws->codes[1], ws->minmax[1], seq / kBT, n_blk, s));
     ctx->have_codebook = true;
     return KVCOMP_OK;
 }
@@ -290,7 +330,7 @@ static int prompt_blocks(const Geo &g, int seq) { return seq < g.res_tokens ? 0 
 kvcomp_status kvcomp_build_codebook(kvcomp_ctx *ctx, const void *d_K, const void *d_V, int seq, void *stream) {
     if (!ctx || !d_K || !d_V) return fail(KVCOMP_ERR_INVALID_ARG, "NULL argument");
     hipStream_t s = static_cast<hipStream_t>(stream);
-    kvcomp_status st = codebook_impl(ctx, d_K, d_V, seq, nullptr, s);
+    kvcomp_status st = codebook_impl(ctx, d_K, d_V, seq, nullptr, 0, s);
     if (st) return st;
     HIP_TRY(hipStreamSynchronize(s));
     return KVCOMP_OK;
@@ -326,11 +366,11 @@ kvcomp_status kvcomp_prefill(kvcomp_ctx *ctx, const void *d_K, const void *d_V, 
     if (workspace_bytes < ws.total)
         return fail(KVCOMP_ERR_CAPACITY, "workspace has %zu bytes, %zu needed", workspace_bytes, ws.total);
     hipStream_t s = static_cast<hipStream_t>(stream);
-    kvcomp_status st = codebook_impl(ctx, d_K, d_V, seq, &ws, s);
-    if (st) return st;
     const Geo &g = ctx->geo;
     const int nb = prompt_blocks(g, seq);
-    HIP_TRY(launch_encode_kept(g, ws.codes[0], ws.minmax[0], ws.codes[1], ws.minmax[1], seq / kBT, nb, s));
+    kvcomp_status st = codebook_impl(ctx, d_K, d_V, seq, &ws, nb, s);
+    if (st) return st;
+    HIP_TRY(launch_place_write_kept(g, ws.codes[0], ws.minmax[0], ws.codes[1], ws.minmax[1], seq / kBT, nb, s));
     return finish_prompt(ctx, static_cast<const uint16_t *>(d_K), static_cast<const uint16_t *>(d_V), seq, nb, s);
 }
 
@@ -494,9 +534,11 @@ kvcomp_status kvcomp_debug_codes(kvcomp_ctx *ctx, int which, const void *d_in, i
 
 kvcomp_status kvcomp_get_histogram(kvcomp_ctx *ctx, int which, uint32_t *h_hist256, void *stream) {
     if (!ctx || !h_hist256 || (which != 0 && which != 1)) return fail(KVCOMP_ERR_INVALID_ARG, "bad argument");
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    HIP_TRY(hipMemcpyAsync(h_hist256, ctx->geo.hist + 256 * which, 256 * 4, hipMemcpyDeviceToHost, s));
-    HIP_TRY(hipStreamSynchronize(s));
+    if (!ctx->have_codebook) return fail(KVCOMP_ERR_STATE, "no codebook");
+    (void)stream;
+    // the host's copy from the last codebook build (the device histogram is cleared for the next one right after it
+    // has been read)
+    std::memcpy(h_hist256, ctx->h_hist + 256 * which, 256 * 4);
     return KVCOMP_OK;
 }
 

@@ -37,6 +37,18 @@ struct BlockEntry {
     uint32_t size16;
 };
 
+// The tables of one tensor's codebook sit together, in the arena and in the host's staging block, so that one copy
+// uploads them: [encode table 2 x 256 u32][decode table 4096 u16][tree 256 x 2 i16][pair table 4096 u32]
+constexpr int kPairTableEntries = 1 << 12;
+constexpr int kTabEncOff = 0;
+constexpr int kTabLutOff = kTabEncOff + 2 * 256 * 4;
+constexpr int kTabTreeOff = kTabLutOff + kLutSize * 2;
+constexpr int kTabPairOff = kTabTreeOff + 256 * 2 * 2;
+constexpr int kTensorTablesBytes = kTabPairOff + kPairTableEntries * 4;
+
+// The placement of records walks the Block Offsets Array in chunks of this many entries, one workgroup per chunk.
+constexpr int kPlaceChunk = 2048;
+
 constexpr int kPartialStride = kD + 2;  // o[128], m, l
 constexpr int kMaxSplits = 128;
 

@@ -14,6 +14,7 @@ struct Ctrl {
     uint32_t max_size16;    // largest record so far
     uint32_t nonfinite;     // set when an input value was Inf/NaN
     uint32_t fault;         // kFault* bits set by kernels that refused work; read and cleared at the synchronising calls
+    uint32_t tail_base;     // the arena tail that the running placement starts from (tail16 moves at its end)
     // filled by the statistics kernel only (kvcomp_get_stats)
     unsigned long long payload_bits[2];
     unsigned long long record16[2];  // sum of record sizes per tensor, 16-byte units
@@ -33,16 +34,10 @@ struct Geo {
     int n_sym[2];
     Ctrl *ctrl;
     uint32_t *hist;          // [2][256]
-    uint32_t *enc;           // [2 tensors][2][256]  (len << 16) | code word as it goes into the LSB-first stream:
-                             //   [0]: first-bit-first (symbols 0..31 of a slice), [1]: last-bit-first (32..63)
-    uint16_t *lut;           // [2][4096] (symbol << 8) | len, indexed by the next lut_bits[t] stream bits
-    uint32_t *lut2;          // [2][4096] pair tables, valid when both code books have code words of at most 6 bits:
-                             //   indexed by the next 12 stream bits; byte 0 = length of two code words together,
-                             //   byte 1 = first symbol, byte 2 = second symbol
+    uint8_t *tables;         // [2 tensors][kTensorTablesBytes], see enc_of / lut_of / tree_of / pair_of below
     int lut_bits[2];         // index width of each decode table = longest code word of that codebook
-    int16_t *tree;           // [2][256][2] array-based Huffman tree (Section 3.3.1): child of node n for stream bit b;
-                             //   >= 0: inner node, < 0: leaf holding symbol ~child; the root is node 0
     uint32_t *counters;      // [B*H] split tickets of the fused kernel, zero between launches
+    uint32_t *place_sums;    // record sizes summed per chunk of kPlaceChunk Block Offsets Array entries (placement)
     BlockEntry *table;       // [2][B*H][max_blocks]
     uint16_t *res;           // [2][B][res_tokens][H][128] fp16 buffer of the newest tokens
     int res_tokens;          // its capacity per sequence = maximum buffer size (Section 4.2), a multiple of 64
@@ -50,6 +45,27 @@ struct Geo {
     uint8_t *payload;        // record arena
     uint32_t payload_cap16;  // its capacity in 16-byte units
 };
+
+// The tables of tensor t (0 = K, 1 = V):
+//   enc  [2][256] (len << 16) | code word as it goes into the LSB-first stream: [0] first-bit-first (symbols 0..31 of
+//        a slice), [1] last-bit-first (32..63)
+//   lut  [4096] (symbol << 8) | len, indexed by the next lut_bits[t] stream bits
+//   tree [256][2] array-based Huffman tree (Section 3.3.1): child of node n for stream bit b; >= 0: inner node,
+//        < 0: leaf holding symbol ~child; the root is node 0
+//   pair [4096] valid when the codebook has code words of at most 6 bits: indexed by the next 12 stream bits;
+//        byte 0 = length of two code words together, byte 1 = first symbol, byte 2 = second symbol
+__host__ __device__ inline const uint32_t *enc_of(const Geo &g, int t) {
+    return reinterpret_cast<const uint32_t *>(g.tables + (size_t)t * kTensorTablesBytes + kTabEncOff);
+}
+__host__ __device__ inline const uint16_t *lut_of(const Geo &g, int t) {
+    return reinterpret_cast<const uint16_t *>(g.tables + (size_t)t * kTensorTablesBytes + kTabLutOff);
+}
+__host__ __device__ inline const int16_t *tree_of(const Geo &g, int t) {
+    return reinterpret_cast<const int16_t *>(g.tables + (size_t)t * kTensorTablesBytes + kTabTreeOff);
+}
+__host__ __device__ inline const uint32_t *pair_of(const Geo &g, int t) {
+    return reinterpret_cast<const uint32_t *>(g.tables + (size_t)t * kTensorTablesBytes + kTabPairOff);
+}
 
 constexpr int kCUs = 256;  // compute units of the MI355X
 constexpr int kXCDs = 8;   // accelerator dies, each with its own L2; workgroups are dealt to them round-robin
@@ -74,7 +90,6 @@ constexpr int fused_waves_per_simd(int G, int table_bits) {
 constexpr int fused_table_bits(int longest) {
     return longest <= 6 ? 6 : longest <= 7 ? 7 : longest <= 8 ? 8 : longest <= 10 ? 10 : 12;
 }
-constexpr int kPairTableEntries = 1 << 12;  // per tensor, 4 bytes each
 constexpr int kLdsBytesPerCU = 160 * 1024;
 // Bytes of one wave's LDS area next to its staging area.  Groups of 1 and 2 heads: fp32 weights [128][G].  Groups of
 // 4 and 8: the area in which the A operand is laid out.
@@ -90,8 +105,10 @@ hipError_t launch_decompress(const Geo &g, int which, uint16_t *out, int n_block
                              int stage_bytes, int tree_walk, hipStream_t s);
 hipError_t launch_histogram(const Geo &g, int which, const uint16_t *X, int seq_stride, int n_blk_per_bh,
                             uint8_t *codes, uint32_t *minmax, hipStream_t s);
-hipError_t launch_encode_kept(const Geo &g, const uint8_t *codesK, const uint32_t *mmK, const uint8_t *codesV,
-                              const uint32_t *mmV, int kept_blk_per_bh, int n_blk_per_bh, hipStream_t s);
+hipError_t launch_size_kept(const Geo &g, int which, const uint8_t *codes, const uint32_t *mm, int kept_blk_per_bh,
+                            int n_blk_per_bh, hipStream_t s);
+hipError_t launch_place_write_kept(const Geo &g, const uint8_t *codesK, const uint32_t *mmK, const uint8_t *codesV,
+                                   const uint32_t *mmV, int kept_blk_per_bh, int n_blk_per_bh, hipStream_t s);
 hipError_t launch_debug_codes(const Geo &g, int which, const uint16_t *X, int seq_stride, int n_blk_per_bh,
                               uint8_t *d_codes, uint16_t *d_minmax, hipStream_t s);
 // size pass -> table[...].size16 ; place -> off16 + ctrl ; write pass -> records
@@ -114,5 +131,7 @@ hipError_t baseline_static_scratch(uint32_t **tickets, float **partials, size_t 
 hipError_t launch_read_stream(const void *src, size_t bytes, uint32_t *sink, size_t *bytes_read, hipStream_t s);
 hipError_t launch_stats(const Geo &g, int n_blocks, hipStream_t s);
 hipError_t launch_fill_zero(void *p, size_t bytes, hipStream_t s);
+// device copy of a multiple of 16 bytes, 16-byte aligned; src may be pinned host memory (its device-side pointer)
+hipError_t launch_copy16(void *dst, const void *src, size_t bytes, hipStream_t s);
 
 }  // namespace kvc

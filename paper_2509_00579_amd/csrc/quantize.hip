@@ -10,6 +10,12 @@ namespace kvc {
 // and the kernel was bound by its LDS atomics).  The copies are summed and added to the global histogram at the end.
 // KEEP: the codes ([block][64][128] bytes) and the unit min/max ([block][units] {min,max} fp16 pairs) of every block also
 // go to a caller's workspace, from where the encoder takes them instead of quantizing the input again (kvcomp_prefill).
+// byte 0 of four words as one word, a's in the lowest byte
+__device__ __forceinline__ uint32_t pack_low_bytes(uint32_t a, uint32_t b, uint32_t c, uint32_t d) {
+    const uint32_t lo = __builtin_amdgcn_perm(b, a, 0x0c0c0400u), hi = __builtin_amdgcn_perm(d, c, 0x0c0c0400u);
+    return __builtin_amdgcn_perm(hi, lo, 0x05040100u);
+}
+
 template <int WHICH, bool KEEP>
 __global__ __launch_bounds__(256, 4) void histogram_kernel(Geo g, const uint16_t *__restrict__ X, int seq_stride,
                                                          int n_blk_per_bh, int n_blk_total, uint8_t *__restrict__ codes,
@@ -21,29 +27,50 @@ __global__ __launch_bounds__(256, 4) void histogram_kernel(Geo g, const uint16_t
     __syncthreads();
     bool bad = false;
     TileRaw raw;
-    auto fetch = [&](int blk) {  // clamped to the last block: the loads of the block after the last are harmless
-        const int bl = min(blk, n_blk_total - 1);
-        const int bh = bl / n_blk_per_bh, j = bl - bh * n_blk_per_bh;
-        load_tile_raw(X, seq_stride, g.H, bh / g.H, bh % g.H, j, tid, raw);
+    // Work items are numbered (batch, block, head), head fastest: a token's row holds all heads (H x 256 bytes), so
+    // workgroups that run side by side read neighbouring pieces of the same rows and DRAM pages are used whole.  With
+    // the blocks of one head side by side every 256-byte piece would open a page of its own.
+    auto block_of = [&](int item, int &b, int &h, int &j) {
+        const int per_b = g.H * n_blk_per_bh;
+        b = item / per_b;
+        const int rest = item - b * per_b;
+        j = rest / g.H;
+        h = rest - j * g.H;
+    };
+    TileOffsets off;
+    off.set(g.H, tid);
+    auto fetch = [&](int item) {  // clamped to the last item: the loads of the item after the last are harmless
+        int b, h, j;
+        block_of(min(item, n_blk_total - 1), b, h, j);
+        load_tile_raw(tile_base(X, seq_stride, g.H, b, h, j), off, raw);
     };
     fetch(blockIdx.x);
-    for (int blk = blockIdx.x; blk < n_blk_total; blk += gridDim.x) {
+    // this thread's place in a block's kept codes: rows of 128 bytes, token-major
+    uint32_t keep_at[4];
+#pragma unroll
+    for (int i = 0; i < 4; i++) keep_at[i] = (uint32_t)(tile_token(tid, i) * kD + tile_chan0(tid));
+    for (int item = blockIdx.x; item < n_blk_total; item += gridDim.x) {
+        int b_, h_, j_;
+        block_of(item, b_, h_, j_);
+        const int blk = (b_ * g.H + h_) * n_blk_per_bh + j_;  // where the block's codes and min/max are kept
         TileRegs r;
-        bad |= unpack_tile(raw, r);
-        fetch(blk + gridDim.x);  // the next block's loads travel while this one is quantized
-        quantize_tile<WHICH>(r, sh, tid, g.two_eb[WHICH], g.n_sym[WHICH], g.k_units);
+        unpack_tile(raw, r);
+        fetch(item + gridDim.x);  // the next block's loads travel while this one is quantized
+        bad |= quantize_tile<WHICH, true>(r, sh, tid, g.two_eb[WHICH], g.n_sym[WHICH], g.k_units);
+        // the codes carry kRoundMagicBits (zero in its low 24 bits): the subtraction folds into the address constant,
+        // the packing takes the low bytes
 #pragma unroll
         for (int i = 0; i < 4; i++)
 #pragma unroll
-            for (int k = 0; k < 8; k++) atomicAdd(&hist[r.code[i][k]][copy], 1u);
+            for (int k = 0; k < 8; k++) atomicAdd(&hist[r.code[i][k] - kRoundMagicBits][copy], 1u);
         if constexpr (KEEP) {
-            const int c0 = tile_chan0(tid);
+            uint8_t *dst = codes + (size_t)blk * kTile;
 #pragma unroll
             for (int i = 0; i < 4; i++) {
                 uint2 pk;
-                pk.x = r.code[i][0] | (r.code[i][1] << 8) | (r.code[i][2] << 16) | (r.code[i][3] << 24);
-                pk.y = r.code[i][4] | (r.code[i][5] << 8) | (r.code[i][6] << 16) | (r.code[i][7] << 24);
-                *reinterpret_cast<uint2 *>(codes + (size_t)blk * kTile + tile_token(tid, i) * kD + c0) = pk;
+                pk.x = pack_low_bytes(r.code[i][0], r.code[i][1], r.code[i][2], r.code[i][3]);
+                pk.y = pack_low_bytes(r.code[i][4], r.code[i][5], r.code[i][6], r.code[i][7]);
+                *reinterpret_cast<uint2 *>(dst + keep_at[i]) = pk;
             }
             const int units = WHICH == 0 ? g.k_units : kBT;
             if (tid < units)
@@ -68,8 +95,8 @@ __global__ __launch_bounds__(256) void debug_codes_kernel(Geo g, const uint16_t 
     const int tid = threadIdx.x, blk = blockIdx.x;
     const int bh = blk / n_blk_per_bh, j = blk - bh * n_blk_per_bh;
     TileRegs r;
-    const bool bad = load_tile(X, seq_stride, g.H, bh / g.H, bh % g.H, j, tid, r);
-    quantize_tile<WHICH>(r, sh, tid, g.two_eb[WHICH], g.n_sym[WHICH], g.k_units);
+    load_tile(X, seq_stride, g.H, bh / g.H, bh % g.H, j, tid, r);
+    const bool bad = quantize_tile<WHICH>(r, sh, tid, g.two_eb[WHICH], g.n_sym[WHICH], g.k_units);
     const int c0 = tile_chan0(tid);
 #pragma unroll
     for (int i = 0; i < 4; i++) {
@@ -131,6 +158,23 @@ hipError_t launch_fill_zero(void *p, size_t bytes, hipStream_t s) {
     size_t grid = (n16 + 255) / 256;
     if (grid > 4096) grid = 4096;
     hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)grid), dim3(256), 0, s, reinterpret_cast<uint4 *>(p), n16);
+    return hipGetLastError();
+}
+
+// Copies n16 16-byte units; src may be pinned host memory (the codebook tables: a copy engine transfer of this size
+// was measured at 17 us on the stream, this launch at 4).
+__global__ void copy16_kernel(uint4 *__restrict__ dst, const uint4 *__restrict__ src, size_t n16) {
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (; i < n16; i += stride) dst[i] = src[i];
+}
+hipError_t launch_copy16(void *dst, const void *src, size_t bytes, hipStream_t s) {
+    const size_t n16 = bytes / 16;
+    if (n16 == 0) return hipSuccess;
+    size_t grid = (n16 + 255) / 256;
+    if (grid > 1024) grid = 1024;
+    hipLaunchKernelGGL(copy16_kernel, dim3((unsigned)grid), dim3(256), 0, s, reinterpret_cast<uint4 *>(dst),
+                       reinterpret_cast<const uint4 *>(src), n16);
     return hipGetLastError();
 }
 

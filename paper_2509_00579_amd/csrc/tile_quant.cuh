@@ -39,67 +39,81 @@ __device__ __forceinline__ uint32_t float_to_half_bits(float f) {  // f is exact
 struct TileRaw {
     uint4 v[4];
 };
-__device__ __forceinline__ void load_tile_raw(const uint16_t *X, int seq_stride, int H, int b, int h, int blk, int tid,
-                                              TileRaw &raw) {
-    const int c0 = tile_chan0(tid);
+// Byte offsets of a thread's four pieces from the first element of a block: they depend on the thread and on H only,
+// so a kernel that walks over blocks computes them once and adds the (wave-uniform) address of each block.
+struct TileOffsets {
+    uint32_t at[4];
+    __device__ __forceinline__ void set(int H, int tid) {
 #pragma unroll
-    for (int i = 0; i < 4; i++) {
-        const int t = blk * kBT + tile_token(tid, i);
-        const size_t off = (((size_t)b * (size_t)seq_stride + (size_t)t) * (size_t)H + (size_t)h) * kD + (size_t)c0;
-        raw.v[i] = *reinterpret_cast<const uint4 *>(X + off);
+        for (int i = 0; i < 4; i++) at[i] = ((uint32_t)tile_token(tid, i) * (uint32_t)H * kD + (uint32_t)tile_chan0(tid)) * 2u;
     }
+};
+// first element of block blk of (b, h) in X [B][seq_stride][H][128]
+__device__ __forceinline__ const uint16_t *tile_base(const uint16_t *X, int seq_stride, int H, int b, int h, int blk) {
+    return X + (((size_t)b * (size_t)seq_stride + (size_t)blk * kBT) * (size_t)H + (size_t)h) * kD;
 }
-// Returns true if any value is Inf/NaN.
-__device__ __forceinline__ bool unpack_tile(const TileRaw &raw, TileRegs &r) {
-    bool bad = false;
+__device__ __forceinline__ void load_tile_raw(const uint16_t *base, const TileOffsets &off, TileRaw &raw) {
+#pragma unroll
+    for (int i = 0; i < 4; i++)
+        raw.v[i] = *reinterpret_cast<const uint4 *>(reinterpret_cast<const char *>(base) + off.at[i]);
+}
+__device__ __forceinline__ void unpack_tile(const TileRaw &raw, TileRegs &r) {
 #pragma unroll
     for (int i = 0; i < 4; i++) {
         const uint32_t w[4] = {raw.v[i].x, raw.v[i].y, raw.v[i].z, raw.v[i].w};
 #pragma unroll
         for (int k = 0; k < 4; k++) {
-            const uint32_t lo = w[k] & 0xffffu, hi = w[k] >> 16;
-            bad |= ((lo & 0x7c00u) == 0x7c00u) | ((hi & 0x7c00u) == 0x7c00u);
-            r.x[i][2 * k] = half_bits_to_float(lo);
-            r.x[i][2 * k + 1] = half_bits_to_float(hi);
+            r.x[i][2 * k] = half_bits_to_float(w[k] & 0xffffu);
+            r.x[i][2 * k + 1] = half_bits_to_float(w[k] >> 16);
         }
     }
-    return bad;
 }
-// Returns true if any loaded value is Inf/NaN.
-__device__ __forceinline__ bool load_tile(const uint16_t *X, int seq_stride, int H, int b, int h, int blk, int tid,
+__device__ __forceinline__ void load_tile(const uint16_t *X, int seq_stride, int H, int b, int h, int blk, int tid,
                                           TileRegs &r) {
+    TileOffsets off;
+    off.set(H, tid);
     TileRaw raw;
-    load_tile_raw(X, seq_stride, H, b, h, blk, tid, raw);
-    return unpack_tile(raw, r);
+    load_tile_raw(tile_base(X, seq_stride, H, b, h, blk), off, raw);
+    unpack_tile(raw, r);
 }
 
 // Codes of N values of one quantization unit: code = clamp(rint((x - mn) / step), 0, top) with the correctly rounded
-// binary32 division, 0 if the unit's range is 0.  That division is most of the quantizer's instructions, so the
-// quotient is first formed as d * rcp(step): v_rcp_f32 is accurate to
-// 1 ulp and the product adds half an ulp, so the result is within 2^-22 relative (below 2^-14 absolute for quotients
-// under 256) of the correctly rounded quotient, and rounds to the same integer unless it lies within that distance
-// of k + 1/2.  If any lane of the wave has a value within 2^-12 of such a boundary (a few per cent of the calls),
-// the whole group is redone with the division.
-template <int N>
-__device__ __forceinline__ void quant_codes(const float (&x)[N], float mn, float step, float range, float top,
+// binary32 division, 0 if the unit's range is 0.  Returns true if a value is Inf or NaN.
+// BIASED: the codes come with kRoundMagicBits added (the histogram kernel uses them as they fall out of the rounding).
+// The quantizer is most of the store kernels' instructions, so the common case takes a cheaper route to the same
+// integers:
+//   * the quotient is formed as q = d * rcp(step): v_rcp_f32 is accurate to 1 ulp and the product adds half an ulp,
+//     so q is within 2^-22 relative (below 2^-14 absolute for quotients under 256) of the correctly rounded
+//     quotient, and rounds to the same integer unless it lies within that distance of k + 1/2;
+//   * q is rounded by adding 2^23 (round to nearest even at unit spacing, like rint): the bit pattern of the sum is
+//     that of 2^23 plus the integer, which also makes the conversion; q >= 0 (mn is the minimum of the same values),
+//     so only the upper clamp is left;
+//   * a value within 2^-13 of a boundary k + 1/2 in any lane sends the wave to the division for that value (one
+//     wave in 60 per value).  Inf and NaN inputs take that path by themselves: they make q a NaN in their own lane
+//     (x - mn, or (x - mn) * 0 when the range is infinite), and the test is written so that a NaN fails it; the
+//     common path needs no test for them.
+constexpr float kRoundMagic = 8388608.0f;          // 2^23
+constexpr uint32_t kRoundMagicBits = 0x4B000000u;  // its bit pattern
+constexpr float kNearBoundary = 0x1p-13f;
+template <int N, bool BIASED>
+__device__ __forceinline__ bool quant_codes(const float (&x)[N], float mn, float step, float range, float top,
                                             uint32_t (&code)[N]) {
-    const float inv = __builtin_amdgcn_rcpf(step);
-    float q[N];
-    bool near = false;
+    const float inv = range == 0.0f ? 0.0f : __builtin_amdgcn_rcpf(step);  // range 0: every code 0
+    const uint32_t top_bits = kRoundMagicBits + (uint32_t)top;
+    constexpr uint32_t kBias = BIASED ? kRoundMagicBits : 0u;
+    bool bad = false;
 #pragma unroll
     for (int n = 0; n < N; n++) {
-        q[n] = (x[n] - mn) * inv;
-        near |= fabsf(__builtin_amdgcn_fractf(q[n]) - 0.5f) < 0x1p-12f;
+        const float q = (x[n] - mn) * inv;
+        code[n] = min(__float_as_uint(q + kRoundMagic), top_bits) - (kRoundMagicBits - kBias);
+        const bool far = fabsf(__builtin_amdgcn_fractf(q) - 0.5f) >= kNearBoundary;  // false for a NaN
+        if (__builtin_amdgcn_ballot_w64(!far) != 0) {
+            bad |= !(fabsf(x[n]) < INFINITY);
+            const float k = fminf(fmaxf(rintf((x[n] - mn) / step), 0.0f), top);
+            code[n] = (range == 0.0f ? 0u : (uint32_t)k) + kBias;
+        }
     }
-    if (__builtin_amdgcn_ballot_w64(near) != 0) {
-#pragma unroll
-        for (int n = 0; n < N; n++) q[n] = (x[n] - mn) / step;
-    }
-#pragma unroll
-    for (int n = 0; n < N; n++) {
-        const float k = fminf(fmaxf(rintf(q[n]), 0.0f), top);
-        code[n] = range == 0.0f ? 0u : (uint32_t)k;
-    }
+    return bad;
 }
 
 __device__ __forceinline__ float canon_zero(float v) { return v == 0.0f ? 0.0f : v; }
@@ -112,14 +126,47 @@ struct QuantShared {
     float unit_mx[kD];
 };
 
-// Computes r.code and leaves the unit minima / maxima in sh.unit_mn / sh.unit_mx.
+// Computes r.code and leaves the unit minima / maxima in sh.unit_mn / sh.unit_mx.  Returns true if one of this
+// thread's values is Inf or NaN.
 // Contains __syncthreads(): must be called by all 256 threads of the workgroup.
 // k_units: 128 = K channel-wise inside the block (Section 3.1.1), 1 = one unit per K block (BlockQuant, Section 4.2);
 // ignored for V.
-template <int WHICH>
-__device__ __forceinline__ void quantize_tile(TileRegs &r, QuantShared &sh, int tid, float two_eb, int n_sym,
+// v_min_f32 / v_max_f32 on values that came through a lane exchange: the compiler would first pass them through a
+// canonicalising instruction each, which changes nothing here (the values are conversions from fp16).
+__device__ __forceinline__ float min_raw(float a, float b) {
+    float o;
+    asm("v_min_f32 %0, %1, %2" : "=v"(o) : "v"(a), "v"(b));
+    return o;
+}
+__device__ __forceinline__ float max_raw(float a, float b) {
+    float o;
+    asm("v_max_f32 %0, %1, %2" : "=v"(o) : "v"(a), "v"(b));
+    return o;
+}
+// Minimum / maximum over the 16 lanes of a DPP row, result in every lane: the exchange rides on the min/max
+// instruction itself.  The s_nop in front of each step covers the wait states that a DPP operand needs after the
+// vector instruction that wrote it (two), and in front of the first step those after a vector write of EXEC (five).
+#define KVC_ROW_REDUCE(OP, v)                                                                              \
+    asm volatile("s_nop 4\n\t" OP " %0, %0, %0 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf\n\t"                \
+        "s_nop 1\n\t" OP " %0, %0, %0 quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf\n\t"                \
+        "s_nop 1\n\t" OP " %0, %0, %0 row_half_mirror row_mask:0xf bank_mask:0xf\n\t"                    \
+        "s_nop 1\n\t" OP " %0, %0, %0 row_mirror row_mask:0xf bank_mask:0xf"                              \
+        : "+v"(v))
+__device__ __forceinline__ float row_min(float v) {
+    KVC_ROW_REDUCE("v_min_f32_dpp", v);
+    return v;
+}
+__device__ __forceinline__ float row_max(float v) {
+    KVC_ROW_REDUCE("v_max_f32_dpp", v);
+    return v;
+}
+#undef KVC_ROW_REDUCE
+
+template <int WHICH, bool BIASED = false>
+__device__ __forceinline__ bool quantize_tile(TileRegs &r, QuantShared &sh, int tid, float two_eb, int n_sym,
                                               int k_units) {
     const float top = (float)(n_sym - 1);
+    bool bad = false;
     if (WHICH == 0 && k_units == 1) {
         float a = r.x[0][0], z = r.x[0][0];
 #pragma unroll
@@ -151,17 +198,17 @@ __device__ __forceinline__ void quantize_tile(TileRegs &r, QuantShared &sh, int 
         const float range = z - a;
         const float step = two_eb * range;
 #pragma unroll
-        for (int i = 0; i < 4; i++) quant_codes<8>(r.x[i], a, step, range, top, r.code[i]);
+        for (int i = 0; i < 4; i++) bad |= quant_codes<8, BIASED>(r.x[i], a, step, range, top, r.code[i]);
     } else if (WHICH == 0) {
         float mn[8], mx[8];
 #pragma unroll
         for (int k = 0; k < 8; k++) {
             mn[k] = fminf(fminf(r.x[0][k], r.x[1][k]), fminf(r.x[2][k], r.x[3][k]));
             mx[k] = fmaxf(fmaxf(r.x[0][k], r.x[1][k]), fmaxf(r.x[2][k], r.x[3][k]));
-            mn[k] = fminf(mn[k], __shfl_xor(mn[k], 16));
-            mx[k] = fmaxf(mx[k], __shfl_xor(mx[k], 16));
-            mn[k] = fminf(mn[k], __shfl_xor(mn[k], 32));
-            mx[k] = fmaxf(mx[k], __shfl_xor(mx[k], 32));
+            mn[k] = min_raw(mn[k], __shfl_xor(mn[k], 16));
+            mx[k] = max_raw(mx[k], __shfl_xor(mx[k], 16));
+            mn[k] = min_raw(mn[k], __shfl_xor(mn[k], 32));
+            mx[k] = max_raw(mx[k], __shfl_xor(mx[k], 32));
         }
         const int w = tid >> 6, c0 = tile_chan0(tid);
         if (((tid & 63) >> 4) == 0) {
@@ -188,7 +235,7 @@ __device__ __forceinline__ void quantize_tile(TileRegs &r, QuantShared &sh, int 
             const float step = two_eb * range;
             const float xs[4] = {r.x[0][k], r.x[1][k], r.x[2][k], r.x[3][k]};
             uint32_t cs[4];
-            quant_codes<4>(xs, a, step, range, top, cs);
+            bad |= quant_codes<4, BIASED>(xs, a, step, range, top, cs);
 #pragma unroll
             for (int i = 0; i < 4; i++) r.code[i][k] = cs[i];
         }
@@ -201,11 +248,8 @@ __device__ __forceinline__ void quantize_tile(TileRegs &r, QuantShared &sh, int 
                 a = fminf(a, r.x[i][k]);
                 z = fmaxf(z, r.x[i][k]);
             }
-#pragma unroll
-            for (int m = 1; m < 16; m <<= 1) {
-                a = fminf(a, __shfl_xor(a, m));
-                z = fmaxf(z, __shfl_xor(z, m));
-            }
+            a = row_min(a);  // the 16 lanes of a DPP row hold one token's row
+            z = row_max(z);
             a = canon_zero(a);
             z = canon_zero(z);
             if ((tid & 15) == 0) {
@@ -214,10 +258,11 @@ __device__ __forceinline__ void quantize_tile(TileRegs &r, QuantShared &sh, int 
             }
             const float range = z - a;
             const float step = two_eb * range;
-            quant_codes<8>(r.x[i], a, step, range, top, r.code[i]);
+            bad |= quant_codes<8, BIASED>(r.x[i], a, step, range, top, r.code[i]);
         }
         __syncthreads();
     }
+    return bad;
 }
 
 }  // namespace kvc

@@ -146,7 +146,7 @@ static void layouts() {
                                     valid++;
                                     const Layout L = make_layout(c);
                                     CHECK(L.ctrl == 0 && L.hist >= 256 && L.payload % 256 == 0 && L.total % 256 == 0);
-                                    CHECK(L.hist < L.enc && L.enc < L.lut && L.lut < L.tree && L.tree < L.counters);
+                                    CHECK(L.hist < L.tables && L.tables + 2 * (size_t)kvc::kTensorTablesBytes <= L.counters);
                                     CHECK(L.counters < L.table && L.table < L.res && L.res < L.partials && L.partials < L.payload);
                                     CHECK(L.payload + L.payload_cap16 * 16 <= L.total);
                                     // room for every block of every (batch, head) at the worst case

@@ -1,12 +1,14 @@
-"""The store kernels form the quantizer's quotient as (x - min) * rcp(width) and redo it with the correctly rounded
-division only when the product lies within 2^-12 of k + 1/2 (csrc/tile_quant.cuh, quant_codes).  This checks the
+"""The store kernels form the quantizer's quotient as (x - min) * rcp(width), round it by adding 2^23, and redo it with
+the correctly rounded division only when the product lies within 2^-12 of k + 1/2, which they test as
+(q - rint(q))^2 > (1/2 - 2^-12)^2 (csrc/tile_quant.cuh, quant_codes).  This checks the
 error analysis behind that rule on the CPU, in numpy binary32: for every reciprocal within 1 ulp of the exact one
 (the accuracy of v_rcp_f32), a product that is NOT near a rounding boundary rounds to the same integer as the
 correctly rounded quotient (numpy's binary32 division), on random fp16-grid inputs and on quotients constructed
 right next to every k + 1/2.  The bit-exact parity of the codes themselves is a GPU test."""
 import numpy as np
 
-NEAR = np.float32(2.0 ** -12)
+FAR_SQ = (np.float32(0.5) - np.float32(2.0 ** -12)) * (np.float32(0.5) - np.float32(2.0 ** -12))
+MAGIC = np.float32(2.0 ** 23)
 
 
 def _mismatches(d, step):
@@ -17,9 +19,12 @@ def _mismatches(d, step):
         for direction in (-np.inf, None, np.inf):
             inv = inv0 if direction is None else np.nextafter(inv0, np.float32(direction))
             q = (d * inv).astype(np.float32)
-            near = np.abs((q - np.floor(q)) - np.float32(0.5)) < NEAR
+            r = (q + MAGIC).astype(np.float32)                  # the kernel's rounding: the sum's low bits are the code
+            k_fast = r.view(np.uint32).astype(np.int64) - 0x4B000000
+            off = (q - (r - MAGIC)).astype(np.float32)
+            near = ~((off * off).astype(np.float32) <= FAR_SQ)  # NaN counts as near
             keep = ~near & (q_exact < 300)
-            bad += int((np.rint(q)[keep] != np.rint(q_exact)[keep]).sum())
+            bad += int((k_fast[keep] != np.rint(q_exact)[keep].astype(np.int64)).sum())
             near_any += int(near.sum())
     return bad, near_any
 
