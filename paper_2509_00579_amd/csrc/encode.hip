@@ -245,22 +245,31 @@ __global__ __launch_bounds__(256) void write_kernel(Geo g, const uint16_t *__res
     if (g.ctrl->fault & kFaultArenaFull) return;  // the placement found no room (uniform over the workgroup)
     enc[tid] = enc_of(g, WHICH)[tid];
     enc[256 + tid] = enc_of(g, WHICH)[256 + tid];
-    for (int i = tid; i < (int)(sizeof(rec) / 4); i += 256) rec[i] = 0;
-    TileRegs r;
-    if constexpr (KEPT) {
-        load_kept_codes(kept, (size_t)bh * kept.blk_per_bh + j, tid, r);
-    } else {
-        load_tile(X, seq_stride, g.H, bh / g.H, bh % g.H, j, tid, r);
-        quantize_tile<WHICH>(r, sh, tid, g.two_eb[WHICH], g.n_sym[WHICH], g.k_units);
-    }
+    static_assert(sizeof(rec) % 16 == 0, "whole 16-byte units");
+    for (int i = tid; i < (int)(sizeof(rec) / 16); i += 256) reinterpret_cast<uint4 *>(rec)[i] = make_uint4(0, 0, 0, 0);
     // codes -> LDS tile (token-major rows, padded), header -> record
     const int c0 = tile_chan0(tid);
+    if constexpr (KEPT) {  // the kept codes are already packed the way the tile wants them
+        const uint8_t *src = kept.codes + ((size_t)bh * kept.blk_per_bh + j) * kTile;
 #pragma unroll
-    for (int i = 0; i < 4; i++) {
-        const int t = tile_token(tid, i);
-        uint32_t *dst = reinterpret_cast<uint32_t *>(code_tile + t * kCodeRow + c0);
-        dst[0] = r.code[i][0] | (r.code[i][1] << 8) | (r.code[i][2] << 16) | (r.code[i][3] << 24);
-        dst[1] = r.code[i][4] | (r.code[i][5] << 8) | (r.code[i][6] << 16) | (r.code[i][7] << 24);
+        for (int i = 0; i < 4; i++) {
+            const int t = tile_token(tid, i);
+            const uint2 pk = *reinterpret_cast<const uint2 *>(src + t * kD + c0);
+            uint32_t *dst = reinterpret_cast<uint32_t *>(code_tile + t * kCodeRow + c0);
+            dst[0] = pk.x;
+            dst[1] = pk.y;
+        }
+    } else {
+        TileRegs r;
+        load_tile(X, seq_stride, g.H, bh / g.H, bh % g.H, j, tid, r);
+        quantize_tile<WHICH>(r, sh, tid, g.two_eb[WHICH], g.n_sym[WHICH], g.k_units);
+#pragma unroll
+        for (int i = 0; i < 4; i++) {
+            const int t = tile_token(tid, i);
+            uint32_t *dst = reinterpret_cast<uint32_t *>(code_tile + t * kCodeRow + c0);
+            dst[0] = r.code[i][0] | (r.code[i][1] << 8) | (r.code[i][2] << 16) | (r.code[i][3] << 24);
+            dst[1] = r.code[i][4] | (r.code[i][5] << 8) | (r.code[i][6] << 16) | (r.code[i][7] << 24);
+        }
     }
     if (tid < R::n_units(g)) {
         if constexpr (KEPT) rec[tid] = kept.minmax[((size_t)bh * kept.blk_per_bh + j) * R::n_units(g) + tid];
@@ -303,20 +312,28 @@ __global__ __launch_bounds__(256) void write_kernel(Geo g, const uint16_t *__res
     // word (i / 32); the table holds every code word in the bit order in which it enters the chunk.
     uint32_t *pay = rec + R::hdr_bytes(g) / 4;
     uint32_t pos = before + inc - bits;
+    // Two code words at a time (at most 2 x 12 bits) go into a 64-bit accumulator that starts at bit `fill` < 32 of
+    // word `word`; when its low word is full it is ORed into the chunk.  No branch: a pair that fills nothing ORs a
+    // zero.  Neighbouring threads share the words at their borders, hence the atomic OR.
+    static_assert(2 * kLutBits + 31 < 64, "a pair of code words behind 31 pending bits fits the accumulator");
     uint32_t word = pos >> 5, fill = pos & 31;
-    unsigned long long acc = 0;
+    uint32_t lo = 0, hi = 0;
 #pragma unroll
-    for (int k = 0; k < 32; k++) {
-        acc |= (unsigned long long)(sym[k] & 0xffffu) << fill;
-        fill += sym[k] >> 16;
-        if (fill >= 32) {
-            atomicOr(&pay[word], (uint32_t)acc);
-            acc >>= 32;
-            fill -= 32;
-            word++;
-        }
+    for (int k = 0; k < 32; k += 2) {
+        const uint32_t len0 = sym[k] >> 16, len1 = sym[k + 1] >> 16;
+        const uint32_t two = (sym[k] & 0xffffu) | ((sym[k + 1] & 0xffffu) << len0);
+        const unsigned long long at = (unsigned long long)two << fill;
+        lo |= (uint32_t)at;
+        hi |= (uint32_t)(at >> 32);
+        fill += len0 + len1;
+        const bool full = fill >= 32;
+        atomicOr(&pay[word], full ? lo : 0u);
+        lo = full ? hi : lo;
+        hi = full ? 0u : hi;
+        word += full ? 1u : 0u;
+        fill &= 31u;
     }
-    if (fill) atomicOr(&pay[word], (uint32_t)acc);
+    if (fill) atomicOr(&pay[word], lo);
     __syncthreads();
     // stages 5-6: the offset was fixed by the placement; coalesced 16-byte stores of header + chunk + padding
     const BlockEntry e = g.table[((size_t)WHICH * g.B * g.H + bh) * g.max_blocks + dst_blk0 + j];
