@@ -121,11 +121,13 @@ kvcomp_status kvcomp_compress_blocks(kvcomp_ctx *ctx, const void *d_K, const voi
 
 /* kvcomp_build_codebook followed by kvcomp_compress_blocks on the same tensors as one call (Section 3: the Store stage
  * at prefill), with ONE quantization pass instead of three: the histogram pass keeps the quantization codes (one byte
- * per value) and the unit min/max in d_workspace, and the size and write passes of the encoder read those instead of
- * loading and quantizing the fp16 input again.  Same cache contents, byte for byte, as the two calls.  d_workspace:
- * DEVICE, caller-owned, 16-byte aligned, at least kvcomp_prefill_workspace_bytes(cfg, seq) bytes (about half the size
- * of K and V together); it is scratch and may be freed or reused once the call has returned.  The cache must be empty.
- * SYNCHRONISES `stream` twice (histogram to the host; arena tail, largest record and flags at the end).
+ * per value), the unit min/max and a histogram per block in d_workspace; the record sizes then come from the block
+ * histograms and the write pass of the encoder reads the codes instead of loading and quantizing the fp16 input
+ * again.  Same cache contents, byte for byte, as the two calls.  d_workspace: DEVICE, caller-owned, 16-byte aligned,
+ * at least kvcomp_prefill_workspace_bytes(cfg, seq) bytes (about half the size of K and V together); it is scratch
+ * and may be freed or reused once the call has returned.  The cache must be empty.
+ * The host waits for the device three times (histogram of K, histogram of V; arena tail, largest record and flags at
+ * the end); its codebook work for K runs while the device histograms V.
  * Errors: INVALID_ARG (seq < 64 or > max_seq, alignment), STATE (cache not empty), CAPACITY (workspace too small),
  * NONFINITE, HIP. */
 size_t kvcomp_prefill_workspace_bytes(const kvcomp_config *cfg, int seq);

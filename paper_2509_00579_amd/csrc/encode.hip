@@ -9,6 +9,8 @@
 //   3. write pass  : quantize again, encode, write the record at its offset
 // The store side runs once per token block while the fetch side runs every decode step (Section 3.3), so the
 // second read of the fp16 input is the cheaper trade against a staging copy of all records.
+#include <algorithm>
+
 #include "tile_quant.cuh"
 
 namespace kvc {
@@ -39,31 +41,17 @@ __device__ __forceinline__ uint32_t block_sum(uint32_t v, uint32_t *scratch, int
     return scratch[0] + scratch[1] + scratch[2] + scratch[3];
 }
 
-// Codes and unit min/max that an earlier pass kept (launch_histogram with a workspace): where the encode kernels find
+// Codes and unit min/max that an earlier pass kept (launch_histogram with a workspace): where the write pass finds
 // them instead of quantizing the input.  Blocks are numbered bh * blk_per_bh + j there.
 struct Kept {
     const uint8_t *codes;    // [block][64][128]
     const uint32_t *minmax;  // [block][units] {min,max} fp16 pairs
     int blk_per_bh;
 };
-// this thread's codes of block `src` (thread map of tile_quant.cuh)
-__device__ __forceinline__ void load_kept_codes(const Kept &kept, size_t src, int tid, TileRegs &r) {
-    const int c0 = tile_chan0(tid);
-#pragma unroll
-    for (int i = 0; i < 4; i++) {
-        const uint2 pk = *reinterpret_cast<const uint2 *>(kept.codes + src * kTile + tile_token(tid, i) * kD + c0);
-#pragma unroll
-        for (int k = 0; k < 4; k++) {
-            r.code[i][k] = (pk.x >> (8 * k)) & 0xffu;
-            r.code[i][4 + k] = (pk.y >> (8 * k)) & 0xffu;
-        }
-    }
-}
-
 // ---- 1. size pass ------------------------------------------------------------------------------------------
-template <int WHICH, bool KEPT>
+template <int WHICH>
 __global__ __launch_bounds__(256) void size_kernel(Geo g, const uint16_t *__restrict__ X, int seq_stride,
-                                                    int n_blk_per_bh, int dst_blk0, Kept kept) {
+                                                    int n_blk_per_bh, int dst_blk0) {
     __shared__ QuantShared sh;
     __shared__ uint32_t enc[256];
     __shared__ uint32_t scratch[4];
@@ -71,14 +59,8 @@ __global__ __launch_bounds__(256) void size_kernel(Geo g, const uint16_t *__rest
     const int bh = blk / n_blk_per_bh, j = blk - bh * n_blk_per_bh;
     enc[tid] = enc_of(g, WHICH)[tid];
     TileRegs r;
-    bool bad = false;
-    if constexpr (KEPT) {
-        load_kept_codes(kept, (size_t)bh * kept.blk_per_bh + j, tid, r);
-        __syncthreads();  // enc[] is visible
-    } else {
-        load_tile(X, seq_stride, g.H, bh / g.H, bh % g.H, j, tid, r);
-        bad = quantize_tile<WHICH>(r, sh, tid, g.two_eb[WHICH], g.n_sym[WHICH], g.k_units);  // has barriers: enc[] is visible after it
-    }
+    load_tile(X, seq_stride, g.H, bh / g.H, bh % g.H, j, tid, r);
+    const bool bad = quantize_tile<WHICH>(r, sh, tid, g.two_eb[WHICH], g.n_sym[WHICH], g.k_units);  // has barriers: enc[] is visible after it
     uint32_t bits = 0;
 #pragma unroll
     for (int i = 0; i < 4; i++)
@@ -92,8 +74,33 @@ __global__ __launch_bounds__(256) void size_kernel(Geo g, const uint16_t *__rest
     if (bad) atomicOr(&g.ctrl->nonfinite, 1u);
 }
 
+// The size pass from the block histograms that the histogram pass kept ([block][256] u16, blocks numbered
+// bh * kept_blk_per_bh + j): a record's payload is sum over the symbols of count x code length.  One wave per block,
+// lane l takes symbols 4l .. 4l+3.
+constexpr int kSizeBlocksPerWave = 4;
+template <int WHICH>
+__global__ __launch_bounds__(256) void size_from_hist_kernel(Geo g, const uint16_t *__restrict__ block_hist,
+                                                              int kept_blk_per_bh, int n_blk_per_bh) {
+    const int lane = threadIdx.x & 63;
+    const int total = g.B * g.H * n_blk_per_bh;
+    uint32_t len[4];
+#pragma unroll
+    for (int k = 0; k < 4; k++) len[k] = enc_of(g, WHICH)[4 * lane + k] >> 16;
+    const int n_waves = gridDim.x * 4;
+    for (int item = blockIdx.x * 4 + (threadIdx.x >> 6); item < total; item += n_waves) {
+        const int bh = item / n_blk_per_bh, j = item - bh * n_blk_per_bh;
+        const uint2 c = *reinterpret_cast<const uint2 *>(block_hist + ((size_t)bh * kept_blk_per_bh + j) * 256 + 4 * lane);
+        uint32_t bits = (c.x & 0xffffu) * len[0] + (c.x >> 16) * len[1] + (c.y & 0xffffu) * len[2] + (c.y >> 16) * len[3];
+#pragma unroll
+        for (int m = 32; m >= 1; m >>= 1) bits += __shfl_xor(bits, m);
+        if (lane == 0)
+            g.table[((size_t)WHICH * g.B * g.H + bh) * g.max_blocks + j].size16 = record_size16(Rec<WHICH>::hdr_bytes(g), bits);
+    }
+}
+
 // ---- 2. placement ------------------------------------------------------------------------------------------
-// Items in order: tensor K then V; inside a tensor (b,h) major, block minor.  Two launches over chunks of kPlaceChunk
+// Items in order: tensor K then V (or one of them: the other's records are then placed by a launch of their own,
+// K's first); inside a tensor (b,h) major, block minor.  Two launches over chunks of kPlaceChunk
 // items, one workgroup of 256 threads per chunk (eight consecutive items per thread):
 //   place_sum_kernel  : the sizes of a chunk summed -> place_sums[chunk]; the arena tail is copied to tail_base
 //   place_scan_kernel : every workgroup adds up the chunk sums before its own (and all of them: what the placement
@@ -103,21 +110,22 @@ __global__ __launch_bounds__(256) void size_kernel(Geo g, const uint16_t *__rest
 constexpr int kPlaceThreads = 256, kPlacePerThread = kPlaceChunk / kPlaceThreads;
 __device__ __forceinline__ int place_pad(int i) { return i + (i >> 5); }  // one spare word per 32: no bank conflicts
 
+// tensors: 0 = K only, 1 = V only, 2 = K then V
 struct PlaceItems {
     BlockEntry *table;
-    int max_blocks, n_blk_per_bh, dst_blk0, n_items;
-    __device__ PlaceItems(const Geo &g, int n_blk_per_bh_, int dst_blk0_)
+    int max_blocks, n_blk_per_bh, dst_blk0, n_items, row0;
+    __device__ PlaceItems(const Geo &g, int n_blk_per_bh_, int dst_blk0_, int tensors)
         : table(g.table), max_blocks(g.max_blocks), n_blk_per_bh(n_blk_per_bh_), dst_blk0(dst_blk0_),
-          n_items(2 * g.B * g.H * n_blk_per_bh_) {}
+          n_items((tensors == 2 ? 2 : 1) * g.B * g.H * n_blk_per_bh_), row0(tensors == 1 ? g.B * g.H : 0) {}
     __device__ BlockEntry *entry(int i) const {  // row = tensor * B*H + (b*H + h)
         const int row = i / n_blk_per_bh, j = i - row * n_blk_per_bh;
-        return &table[(size_t)row * max_blocks + dst_blk0 + j];
+        return &table[(size_t)(row0 + row) * max_blocks + dst_blk0 + j];
     }
 };
 
-__global__ __launch_bounds__(kPlaceThreads) void place_sum_kernel(Geo g, int n_blk_per_bh, int dst_blk0) {
+__global__ __launch_bounds__(kPlaceThreads) void place_sum_kernel(Geo g, int n_blk_per_bh, int dst_blk0, int tensors) {
     __shared__ uint32_t wave_tot[kPlaceThreads / 64];
-    const PlaceItems it(g, n_blk_per_bh, dst_blk0);
+    const PlaceItems it(g, n_blk_per_bh, dst_blk0, tensors);
     const int tid = threadIdx.x, c0 = blockIdx.x * kPlaceChunk;
     uint32_t sum = 0;
 #pragma unroll
@@ -137,11 +145,11 @@ __global__ __launch_bounds__(kPlaceThreads) void place_sum_kernel(Geo g, int n_b
     }
 }
 
-__global__ __launch_bounds__(kPlaceThreads) void place_scan_kernel(Geo g, int n_blk_per_bh, int dst_blk0) {
+__global__ __launch_bounds__(kPlaceThreads) void place_scan_kernel(Geo g, int n_blk_per_bh, int dst_blk0, int tensors) {
     __shared__ uint32_t val[kPlaceChunk + kPlaceChunk / 32];
     __shared__ uint32_t wave_tot[kPlaceThreads / 64];
     __shared__ unsigned long long sums_s[2][kPlaceThreads / 64];
-    const PlaceItems it(g, n_blk_per_bh, dst_blk0);
+    const PlaceItems it(g, n_blk_per_bh, dst_blk0, tensors);
     const int tid = threadIdx.x, c0 = blockIdx.x * kPlaceChunk;
     // what the chunks before this one need, and what all chunks need
     unsigned long long before_me = 0, need = 0;
@@ -223,11 +231,11 @@ __global__ __launch_bounds__(kPlaceThreads) void place_scan_kernel(Geo g, int n_
     if (blockIdx.x == 0 && tid == 0) g.ctrl->tail16 = tail0 + (uint32_t)need;
 }
 
-static void launch_place(const Geo &g, int n_blk_per_bh, int dst_blk0, hipStream_t s) {
-    const int n_items = 2 * g.B * g.H * n_blk_per_bh;
+static void launch_place(const Geo &g, int n_blk_per_bh, int dst_blk0, int tensors, hipStream_t s) {
+    const int n_items = (tensors == 2 ? 2 : 1) * g.B * g.H * n_blk_per_bh;
     const int chunks = (n_items + kPlaceChunk - 1) / kPlaceChunk;
-    hipLaunchKernelGGL(place_sum_kernel, dim3(chunks), dim3(kPlaceThreads), 0, s, g, n_blk_per_bh, dst_blk0);
-    hipLaunchKernelGGL(place_scan_kernel, dim3(chunks), dim3(kPlaceThreads), 0, s, g, n_blk_per_bh, dst_blk0);
+    hipLaunchKernelGGL(place_sum_kernel, dim3(chunks), dim3(kPlaceThreads), 0, s, g, n_blk_per_bh, dst_blk0, tensors);
+    hipLaunchKernelGGL(place_scan_kernel, dim3(chunks), dim3(kPlaceThreads), 0, s, g, n_blk_per_bh, dst_blk0, tensors);
 }
 
 // ---- 3. write pass -----------------------------------------------------------------------------------------
@@ -349,35 +357,33 @@ hipError_t launch_encode(const Geo &g, const uint16_t *XK, const uint16_t *XV, i
     const int total = g.B * g.H * n_blk_per_bh;
     if (total <= 0) return hipSuccess;
     const Kept none = {nullptr, nullptr, 0};
-    hipLaunchKernelGGL((size_kernel<0, false>), dim3(total), dim3(256), 0, s, g, XK, seq_stride, n_blk_per_bh, dst_blk0, none);
-    hipLaunchKernelGGL((size_kernel<1, false>), dim3(total), dim3(256), 0, s, g, XV, seq_stride, n_blk_per_bh, dst_blk0, none);
-    launch_place(g, n_blk_per_bh, dst_blk0, s);
+    hipLaunchKernelGGL(size_kernel<0>, dim3(total), dim3(256), 0, s, g, XK, seq_stride, n_blk_per_bh, dst_blk0);
+    hipLaunchKernelGGL(size_kernel<1>, dim3(total), dim3(256), 0, s, g, XV, seq_stride, n_blk_per_bh, dst_blk0);
+    launch_place(g, n_blk_per_bh, dst_blk0, 2, s);
     hipLaunchKernelGGL((write_kernel<0, false>), dim3(total), dim3(256), 0, s, g, XK, seq_stride, n_blk_per_bh, dst_blk0, none);
     hipLaunchKernelGGL((write_kernel<1, false>), dim3(total), dim3(256), 0, s, g, XV, seq_stride, n_blk_per_bh, dst_blk0, none);
     return hipGetLastError();
 }
 
-// The same from codes and min/max kept by launch_histogram (kept_blk_per_bh blocks per (batch, head) there, of which
-// the first n_blk_per_bh are encoded): no second and third quantization of the input.  In two parts, so that the size
-// pass of a tensor can be queued as soon as its codebook is on the device: the sizes of one tensor; then, once both
-// are queued, the placement and the two write passes.
-hipError_t launch_size_kept(const Geo &g, int which, const uint8_t *codes, const uint32_t *mm, int kept_blk_per_bh,
-                            int n_blk_per_bh, hipStream_t s) {
+// The same for one tensor from what launch_histogram kept (kept_blk_per_bh blocks per (batch, head) there, of which the
+// first n_blk_per_bh are encoded): sizes from the block histograms, placement of this tensor's records behind the
+// arena tail, write pass from the kept codes.  K's records come before V's in the arena, so K can be placed and
+// written as soon as its codebook is on the device, before V's sizes exist.
+hipError_t launch_encode_kept(const Geo &g, int which, const uint8_t *codes, const uint32_t *mm, const uint16_t *block_hist,
+                              int kept_blk_per_bh, int n_blk_per_bh, hipStream_t s) {
     const int total = g.B * g.H * n_blk_per_bh;
     if (total <= 0) return hipSuccess;
+    const int grid = std::min((total + 4 * kSizeBlocksPerWave - 1) / (4 * kSizeBlocksPerWave), 2048);
     const Kept k = {codes, mm, kept_blk_per_bh};
-    if (which == 0) hipLaunchKernelGGL((size_kernel<0, true>), dim3(total), dim3(256), 0, s, g, nullptr, 0, n_blk_per_bh, 0, k);
-    else hipLaunchKernelGGL((size_kernel<1, true>), dim3(total), dim3(256), 0, s, g, nullptr, 0, n_blk_per_bh, 0, k);
-    return hipGetLastError();
-}
-hipError_t launch_place_write_kept(const Geo &g, const uint8_t *codesK, const uint32_t *mmK, const uint8_t *codesV,
-                                   const uint32_t *mmV, int kept_blk_per_bh, int n_blk_per_bh, hipStream_t s) {
-    const int total = g.B * g.H * n_blk_per_bh;
-    if (total <= 0) return hipSuccess;
-    const Kept kk = {codesK, mmK, kept_blk_per_bh}, kv = {codesV, mmV, kept_blk_per_bh};
-    launch_place(g, n_blk_per_bh, 0, s);
-    hipLaunchKernelGGL((write_kernel<0, true>), dim3(total), dim3(256), 0, s, g, nullptr, 0, n_blk_per_bh, 0, kk);
-    hipLaunchKernelGGL((write_kernel<1, true>), dim3(total), dim3(256), 0, s, g, nullptr, 0, n_blk_per_bh, 0, kv);
+    if (which == 0) {
+        hipLaunchKernelGGL(size_from_hist_kernel<0>, dim3(grid), dim3(256), 0, s, g, block_hist, kept_blk_per_bh, n_blk_per_bh);
+        launch_place(g, n_blk_per_bh, 0, 0, s);
+        hipLaunchKernelGGL((write_kernel<0, true>), dim3(total), dim3(256), 0, s, g, nullptr, 0, n_blk_per_bh, 0, k);
+    } else {
+        hipLaunchKernelGGL(size_from_hist_kernel<1>, dim3(grid), dim3(256), 0, s, g, block_hist, kept_blk_per_bh, n_blk_per_bh);
+        launch_place(g, n_blk_per_bh, 0, 1, s);
+        hipLaunchKernelGGL((write_kernel<1, true>), dim3(total), dim3(256), 0, s, g, nullptr, 0, n_blk_per_bh, 0, k);
+    }
     return hipGetLastError();
 }
 

@@ -221,6 +221,7 @@ kvcomp_status kvcomp_reset(kvcomp_ctx *ctx, int keep_codebook, void *stream) {
 struct PrefillWs {
     uint8_t *codes[2];
     uint32_t *minmax[2];
+    uint16_t *block_hist[2];  // [block][256]
     size_t total;
 };
 static PrefillWs prefill_layout(const kvcomp_config &c, int seq, void *base) {
@@ -233,6 +234,8 @@ static PrefillWs prefill_layout(const kvcomp_config &c, int seq, void *base) {
     w.codes[1] = p + at; at += nblk * kTile;
     w.minmax[0] = reinterpret_cast<uint32_t *>(p + at); at += align_up(nblk * k_units * 4, 16);
     w.minmax[1] = reinterpret_cast<uint32_t *>(p + at); at += align_up(nblk * kBT * 4, 16);
+    w.block_hist[0] = reinterpret_cast<uint16_t *>(p + at); at += nblk * 512;
+    w.block_hist[1] = reinterpret_cast<uint16_t *>(p + at); at += nblk * 512;
     w.total = at;
     return w;
 }
@@ -251,15 +254,17 @@ static kvcomp_status codebook_of(kvcomp_ctx *ctx, int w, const uint32_t *hist, h
     if (g.lut_bits[w] <= 6) build_pair_table(lut, g.lut_bits[w], pair);
     else std::memset(pair, 0, kPairEntries * 4);
     static_assert(kTensorTablesBytes % 16 == 0, "whole 16-byte units");
+    // V's upload (the last thing that runs after both histograms have been read) also clears the device histogram
+    // for the next call
     HIP_TRY(launch_copy16(g.tables + (size_t)w * kTensorTablesBytes, ctx->h_tables_dev + (size_t)w * kTensorTablesBytes,
-                          kTensorTablesBytes, s));
+                          kTensorTablesBytes, g.hist, w == 1 ? 2 * 256 * 4 : 0, s));
     return KVCOMP_OK;
 }
 
 // Histogram on the device, codebooks on the host, tables to the device (Section 3).  ws != NULL: the histogram pass
-// also keeps the codes and min/max of every block there, and the size pass of the first n_blk blocks per (batch, head)
-// is queued for each tensor as soon as its tables are.
-// The host's part for K runs while the device histograms V, and the size pass of K while the host does V's.
+// also keeps the codes, min/max and histogram of every block there, and the encoding of the first n_blk blocks per
+// (batch, head) is queued for each tensor as soon as its tables are.
+// The host's part for K runs while the device histograms V, and K's records are written while the host does V's.
 static kvcomp_status codebook_impl(kvcomp_ctx *ctx, const void *d_K, const void *d_V, int seq, const PrefillWs *ws,
                                    int n_blk, hipStream_t s) {
     if (!aligned16(d_K) || !aligned16(d_V)) return fail(KVCOMP_ERR_INVALID_ARG, "K/V must be 16-byte aligned");
@@ -272,18 +277,18 @@ static kvcomp_status codebook_impl(kvcomp_ctx *ctx, const void *d_K, const void 
     if (symbols >= (1ll << 32)) return fail(KVCOMP_ERR_INVALID_ARG, "more than 2^32 symbols per tensor");
     Geo &g = ctx->geo;
     static_assert(sizeof(Ctrl) <= 256, "control words fill the first 256 bytes");
-    // the device histogram is zero here: the arena starts that way, and every call leaves it so (below)
+    // the device histogram is zero here: the arena starts that way, and every call that got as far as reading it
+    // back leaves it so (codebook_of for V, or the failure path below)
     HIP_TRY(launch_histogram(g, 0, static_cast<const uint16_t *>(d_K), seq, seq / kBT, ws ? ws->codes[0] : nullptr,
-                             ws ? ws->minmax[0] : nullptr, s));
+                             ws ? ws->minmax[0] : nullptr, ws ? ws->block_hist[0] : nullptr, s));
     HIP_TRY(hipMemcpyAsync(ctx->h_hist, g.hist, 256 * 4, hipMemcpyDeviceToHost, s));
     HIP_TRY(hipEventRecord(ctx->ev_hist[0], s));
     HIP_TRY(launch_histogram(g, 1, static_cast<const uint16_t *>(d_V), seq, seq / kBT, ws ? ws->codes[1] : nullptr,
-                             ws ? ws->minmax[1] : nullptr, s));
+                             ws ? ws->minmax[1] : nullptr, ws ? ws->block_hist[1] : nullptr, s));
     // control words and the histogram of V (neighbours of K's histogram in the arena and in the staging block, which
     // therefore travels again: the same values over the same bytes)
     HIP_TRY(hipMemcpyAsync(ctx->h_ctrl, g.ctrl, 256 + 2 * 256 * 4, hipMemcpyDeviceToHost, s));
     HIP_TRY(hipEventRecord(ctx->ev_hist[1], s));
-    HIP_TRY(launch_fill_zero(g.hist, 2 * 256 * 4, s));  // for the next call; runs while the host builds the codebooks
     HIP_TRY(hipEventSynchronize(ctx->ev_hist[0]));
     {
         uint32_t hist_k[256];
@@ -291,15 +296,21 @@ static kvcomp_status codebook_impl(kvcomp_ctx *ctx, const void *d_K, const void 
         kvcomp_status st = codebook_of(ctx, 0, hist_k, s);
         if (st) return st;
     }
-    if (ws) HIP_TRY(launch_size_kept(g, 0, ws->codes[0], ws->minmax[0], seq / kBT, n_blk, s));
+    if (ws) HIP_TRY(launch_encode_kept(g, 0, ws->codes[0], ws->minmax[0], ws->block_hist[0], seq / kBT, n_blk, s));
     HIP_TRY(hipEventSynchronize(ctx->ev_hist[1]));
     {
         kvcomp_status st = check_flags(ctx, s);
-        if (st) return st;
+        if (st) {
+            // K's records may be on their way already: the cache was empty at entry, so it is again with the control
+            // words back at zero (arena tail, largest record)
+            if (ws) (void)launch_fill_zero(g.ctrl, 256, s);
+            (void)launch_fill_zero(g.hist, 2 * 256 * 4, s);
+            return st;
+        }
         st = codebook_of(ctx, 1, ctx->h_hist + 256, s);
         if (st) return st;
     }
-    if (ws) HIP_TRY(launch_size_kept(g, 1, ws->codes[1], ws->minmax[1], seq / kBT, n_blk, s));
+    if (ws) HIP_TRY(launch_encode_kept(g, 1, ws->codes[1], ws->minmax[1], ws->block_hist[1], seq / kBT, n_blk, s));
     ctx->have_codebook = true;
     return KVCOMP_OK;
 }
@@ -370,7 +381,6 @@ kvcomp_status kvcomp_prefill(kvcomp_ctx *ctx, const void *d_K, const void *d_V, 
     const int nb = prompt_blocks(g, seq);
     kvcomp_status st = codebook_impl(ctx, d_K, d_V, seq, &ws, nb, s);
     if (st) return st;
-    HIP_TRY(launch_place_write_kept(g, ws.codes[0], ws.minmax[0], ws.codes[1], ws.minmax[1], seq / kBT, nb, s));
     return finish_prompt(ctx, static_cast<const uint16_t *>(d_K), static_cast<const uint16_t *>(d_V), seq, nb, s);
 }
 

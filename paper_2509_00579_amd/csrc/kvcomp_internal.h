@@ -104,11 +104,9 @@ constexpr size_t fused_lds_fixed(int G, int longest) {
 hipError_t launch_decompress(const Geo &g, int which, uint16_t *out, int n_blocks, int res_head, int n_res, int seq_stride,
                              int stage_bytes, int tree_walk, hipStream_t s);
 hipError_t launch_histogram(const Geo &g, int which, const uint16_t *X, int seq_stride, int n_blk_per_bh,
-                            uint8_t *codes, uint32_t *minmax, hipStream_t s);
-hipError_t launch_size_kept(const Geo &g, int which, const uint8_t *codes, const uint32_t *mm, int kept_blk_per_bh,
-                            int n_blk_per_bh, hipStream_t s);
-hipError_t launch_place_write_kept(const Geo &g, const uint8_t *codesK, const uint32_t *mmK, const uint8_t *codesV,
-                                   const uint32_t *mmV, int kept_blk_per_bh, int n_blk_per_bh, hipStream_t s);
+                            uint8_t *codes, uint32_t *minmax, uint16_t *block_hist, hipStream_t s);
+hipError_t launch_encode_kept(const Geo &g, int which, const uint8_t *codes, const uint32_t *mm, const uint16_t *block_hist,
+                              int kept_blk_per_bh, int n_blk_per_bh, hipStream_t s);
 hipError_t launch_debug_codes(const Geo &g, int which, const uint16_t *X, int seq_stride, int n_blk_per_bh,
                               uint8_t *d_codes, uint16_t *d_minmax, hipStream_t s);
 // size pass -> table[...].size16 ; place -> off16 + ctrl ; write pass -> records
@@ -131,7 +129,8 @@ hipError_t baseline_static_scratch(uint32_t **tickets, float **partials, size_t 
 hipError_t launch_read_stream(const void *src, size_t bytes, uint32_t *sink, size_t *bytes_read, hipStream_t s);
 hipError_t launch_stats(const Geo &g, int n_blocks, hipStream_t s);
 hipError_t launch_fill_zero(void *p, size_t bytes, hipStream_t s);
-// device copy of a multiple of 16 bytes, 16-byte aligned; src may be pinned host memory (its device-side pointer)
-hipError_t launch_copy16(void *dst, const void *src, size_t bytes, hipStream_t s);
+// device copy of a multiple of 16 bytes, 16-byte aligned; src may be pinned host memory (its device-side pointer);
+// the same launch clears zero_bytes at `zero` (may be 0)
+hipError_t launch_copy16(void *dst, const void *src, size_t bytes, void *zero, size_t zero_bytes, hipStream_t s);
 
 }  // namespace kvc

@@ -8,8 +8,11 @@ namespace kvc {
 // the lanes of a half-wave always hit 32 different banks and never the same word, so an LDS atomic instruction costs
 // its minimum however peaked the code distribution is (with one copy per wave, lanes with the same code serialise
 // and the kernel was bound by its LDS atomics).  The copies are summed and added to the global histogram at the end.
-// KEEP: the codes ([block][64][128] bytes) and the unit min/max ([block][units] {min,max} fp16 pairs) of every block also
-// go to a caller's workspace, from where the encoder takes them instead of quantizing the input again (kvcomp_prefill).
+// KEEP: the codes ([block][64][128] bytes), the unit min/max ([block][units] {min,max} fp16 pairs) and the histogram
+// ([block][256] u16) of every block also go to a caller's workspace, from where the encoder takes them instead of
+// quantizing the input again (kvcomp_prefill): the record sizes then come from the block histograms and the code
+// lengths alone.  The LDS histogram is then that of one block: after a block's atomics thread b sums and clears the
+// copies of bin b.
 // byte 0 of four words as one word, a's in the lowest byte
 __device__ __forceinline__ uint32_t pack_low_bytes(uint32_t a, uint32_t b, uint32_t c, uint32_t d) {
     const uint32_t lo = __builtin_amdgcn_perm(b, a, 0x0c0c0400u), hi = __builtin_amdgcn_perm(d, c, 0x0c0c0400u);
@@ -19,13 +22,15 @@ __device__ __forceinline__ uint32_t pack_low_bytes(uint32_t a, uint32_t b, uint3
 template <int WHICH, bool KEEP>
 __global__ __launch_bounds__(256, 4) void histogram_kernel(Geo g, const uint16_t *__restrict__ X, int seq_stride,
                                                          int n_blk_per_bh, int n_blk_total, uint8_t *__restrict__ codes,
-                                                         uint32_t *__restrict__ minmax) {
+                                                         uint32_t *__restrict__ minmax,
+                                                         uint16_t *__restrict__ block_hist) {
     __shared__ QuantShared sh;
-    __shared__ uint32_t hist[256][32];
+    __shared__ __attribute__((aligned(16))) uint32_t hist[256][32];
     const int tid = threadIdx.x, copy = tid & 31;
     for (int i = tid; i < 256 * 32; i += 256) (&hist[0][0])[i] = 0;
     __syncthreads();
     bool bad = false;
+    uint32_t total = 0;  // of bin `tid`, over this workgroup's blocks
     TileRaw raw;
     // Work items are numbered (batch, block, head), head fastest: a token's row holds all heads (H x 256 bytes), so
     // workgroups that run side by side read neighbouring pieces of the same rows and DRAM pages are used whole.  With
@@ -75,13 +80,25 @@ __global__ __launch_bounds__(256, 4) void histogram_kernel(Geo g, const uint16_t
             const int units = WHICH == 0 ? g.k_units : kBT;
             if (tid < units)
                 minmax[(size_t)blk * units + tid] = float_to_half_bits(sh.unit_mn[tid]) | (float_to_half_bits(sh.unit_mx[tid]) << 16);
-        }
-        __syncthreads();  // unit_mn/unit_mx are rewritten by the next iteration
-    }
-    __syncthreads();
-    uint32_t total = 0;
+            __syncthreads();  // the block's atomics are done
+            uint32_t cnt = 0;
+            uint4 *mine = reinterpret_cast<uint4 *>(&hist[tid][0]);
 #pragma unroll
-    for (int c = 0; c < 32; c++) total += hist[tid][(c + tid) & 31];  // rotated: conflict-free across the bins
+            for (int c = 0; c < 8; c++) {  // rotated: neighbouring bins start at different banks
+                const uint4 v = mine[(c + tid) & 7];
+                cnt += (v.x + v.y) + (v.z + v.w);
+                mine[(c + tid) & 7] = make_uint4(0, 0, 0, 0);
+            }
+            total += cnt;
+            block_hist[(size_t)blk * 256 + tid] = (uint16_t)cnt;  // at most 8192
+        }
+        __syncthreads();  // unit_mn/unit_mx are rewritten by the next iteration; KEEP: the histogram is clear again
+    }
+    if constexpr (!KEEP) {
+        __syncthreads();
+#pragma unroll
+        for (int c = 0; c < 32; c++) total += hist[tid][(c + tid) & 31];  // rotated: conflict-free across the bins
+    }
     if (total) atomicAdd(&g.hist[WHICH * 256 + tid], total);
     if (bad) atomicOr(&g.ctrl->nonfinite, 1u);
 }
@@ -114,21 +131,21 @@ __global__ __launch_bounds__(256) void debug_codes_kernel(Geo g, const uint16_t 
     if (bad) atomicOr(&g.ctrl->nonfinite, 1u);
 }
 
-// codes / minmax != NULL: also keep the codes and the unit min/max of every block there
+// codes / minmax / block_hist != NULL: also keep the codes, the unit min/max and the histogram of every block there
 hipError_t launch_histogram(const Geo &g, int which, const uint16_t *X, int seq_stride, int n_blk_per_bh,
-                            uint8_t *codes, uint32_t *minmax, hipStream_t s) {
+                            uint8_t *codes, uint32_t *minmax, uint16_t *block_hist, hipStream_t s) {
     const int total = g.B * g.H * n_blk_per_bh;
     if (total <= 0) return hipSuccess;
     const int grid = total < 1024 ? total : 1024;  // four workgroups per CU (32 KiB of LDS each), several blocks each
     const bool keep = codes != nullptr;
     if (which == 0 && !keep)
-        hipLaunchKernelGGL((histogram_kernel<0, false>), dim3(grid), dim3(256), 0, s, g, X, seq_stride, n_blk_per_bh, total, codes, minmax);
+        hipLaunchKernelGGL((histogram_kernel<0, false>), dim3(grid), dim3(256), 0, s, g, X, seq_stride, n_blk_per_bh, total, codes, minmax, block_hist);
     else if (which == 0)
-        hipLaunchKernelGGL((histogram_kernel<0, true>), dim3(grid), dim3(256), 0, s, g, X, seq_stride, n_blk_per_bh, total, codes, minmax);
+        hipLaunchKernelGGL((histogram_kernel<0, true>), dim3(grid), dim3(256), 0, s, g, X, seq_stride, n_blk_per_bh, total, codes, minmax, block_hist);
     else if (!keep)
-        hipLaunchKernelGGL((histogram_kernel<1, false>), dim3(grid), dim3(256), 0, s, g, X, seq_stride, n_blk_per_bh, total, codes, minmax);
+        hipLaunchKernelGGL((histogram_kernel<1, false>), dim3(grid), dim3(256), 0, s, g, X, seq_stride, n_blk_per_bh, total, codes, minmax, block_hist);
     else
-        hipLaunchKernelGGL((histogram_kernel<1, true>), dim3(grid), dim3(256), 0, s, g, X, seq_stride, n_blk_per_bh, total, codes, minmax);
+        hipLaunchKernelGGL((histogram_kernel<1, true>), dim3(grid), dim3(256), 0, s, g, X, seq_stride, n_blk_per_bh, total, codes, minmax, block_hist);
     return hipGetLastError();
 }
 
@@ -161,20 +178,21 @@ hipError_t launch_fill_zero(void *p, size_t bytes, hipStream_t s) {
     return hipGetLastError();
 }
 
-// Copies n16 16-byte units; src may be pinned host memory (the codebook tables: a copy engine transfer of this size
-// was measured at 17 us on the stream, this launch at 4).
-__global__ void copy16_kernel(uint4 *__restrict__ dst, const uint4 *__restrict__ src, size_t n16) {
-    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    const size_t stride = (size_t)gridDim.x * blockDim.x;
-    for (; i < n16; i += stride) dst[i] = src[i];
+// Copies n16 16-byte units and clears zero16 more at `zero`; src may be pinned host memory (the codebook tables: a copy
+// engine transfer of this size was measured at 17 us on the stream, this launch at 4).
+__global__ void copy16_kernel(uint4 *__restrict__ dst, const uint4 *__restrict__ src, size_t n16, uint4 *__restrict__ zero,
+                              size_t zero16) {
+    const size_t stride = (size_t)gridDim.x * blockDim.x, first = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    for (size_t i = first; i < n16; i += stride) dst[i] = src[i];
+    for (size_t i = first; i < zero16; i += stride) zero[i] = make_uint4(0, 0, 0, 0);
 }
-hipError_t launch_copy16(void *dst, const void *src, size_t bytes, hipStream_t s) {
+hipError_t launch_copy16(void *dst, const void *src, size_t bytes, void *zero, size_t zero_bytes, hipStream_t s) {
     const size_t n16 = bytes / 16;
     if (n16 == 0) return hipSuccess;
     size_t grid = (n16 + 255) / 256;
     if (grid > 1024) grid = 1024;
     hipLaunchKernelGGL(copy16_kernel, dim3((unsigned)grid), dim3(256), 0, s, reinterpret_cast<uint4 *>(dst),
-                       reinterpret_cast<const uint4 *>(src), n16);
+                       reinterpret_cast<const uint4 *>(src), n16, reinterpret_cast<uint4 *>(zero), zero_bytes / 16);
     return hipGetLastError();
 }
 
