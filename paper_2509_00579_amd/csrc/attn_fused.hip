@@ -469,7 +469,11 @@ __device__ __forceinline__ int a_row(int x) {
     return 3 * (xr >> 2) + min(xr & 3, 2);
 }
 
-constexpr float kLazyMax = 8.f;  // how far a score may exceed the softmax reference before the state is rescaled
+// How far a score may exceed the softmax reference before the state is rescaled.  The numerators of a block then
+// reach e^kLazyMax, and because the integer weights of all heads share one power-of-two scale per block, a head
+// whose reference is behind costs the other heads that factor in weight resolution: 2 keeps the attention error
+// within a factor 8 of rescaling always (measured at the 70B shape: 1e-5 instead of 4e-6; with 8 it reached 1e-3).
+constexpr float kLazyMax = 2.f;
 
 // K block.  hdr32: the record (LDS or global); tile: this wave's LDS area for laying out the A operand; qf: the query
 // rows in LDS.
@@ -588,7 +592,7 @@ __device__ __forceinline__ void k_tile_block(const uint32_t *hdr32, const char *
     // Online softmax with a reference value m that only moves when it has to: the state is rescaled (a maximum over
     // the tokens of every head, six multiplications per head) only when some score of the block exceeds its head's m
     // by more than kLazyMax, which after the first blocks of a sequence split is rare.  Until then the numerators are
-    // at most e^kLazyMax instead of 1, which costs fp32 nothing; the merges divide by the same m.
+    // at most e^kLazyMax instead of 1; the merges divide by the same m.
     const float si = scale * inv;
     float over = -INFINITY;
 #pragma unroll

@@ -878,7 +878,14 @@ def test_large_configs_full_size_sampled(gpu, oracle, name, rel):
     dK, dV = _dev(Kx), _dev(Vx)
     gc.build_codebook(dK, dV)
     gc.compress_blocks(dK, dV)
+    # the same prompt through the one-pass entry point that bench.py times (sizes from block histograms, placement in
+    # several chunks, K written before V is sized): must give the same cache
+    gp = gpu.KVCompCache(B, H, Hq, S + 64, rel, rel, max_code_len=limit)
+    gp.prefill(dK, dV)
     del dK, dV
+    st_c, st_p = gc.stats(), gp.stats()
+    for key in ("n_blocks", "n_res", "record_bytes_k", "record_bytes_v", "payload_bits_k", "payload_bits_v", "stored_bytes"):
+        assert st_c[key] == st_p[key], key
     _say("  gpu compressed; oracle quantizes")
     NB = S // 64
     book, codes, mms = {}, {}, {}
@@ -891,15 +898,32 @@ def test_large_configs_full_size_sampled(gpu, oracle, name, rel):
         np.testing.assert_array_equal(ln_g, ln)
         np.testing.assert_array_equal(cd_g, cd)
         book[which] = (ln, cd)
+    # Placement at full size: the record size of EVERY block from the oracle's codes and code lengths (the sampled
+    # records below pin this size against oracle.encode_block), offsets by a running sum in (tensor, batch, head,
+    # block) order; the device's Block Offsets Array is compared on the sample and on the very last entry.
+    hdr = {K: 4 * 128 + 2 * 128, V: 4 * 64 + 2 * 128}
+    size16 = {}
+    for which in (K, V):
+        ln8 = book[which][0].astype(np.uint8)
+        bits = ln8[codes[which].reshape(B * H * NB, -1)].sum(axis=1, dtype=np.int64)
+        size16[which] = (hdr[which] + 4 * ((bits + 31) // 32) + 15) // 16
+    off16 = np.concatenate([[0], np.cumsum(np.concatenate([size16[K], size16[V]]))])
     rng = np.random.default_rng(5)
-    for _ in range(48):
-        which, b, h, j = int(rng.integers(2)), int(rng.integers(B)), int(rng.integers(H)), int(rng.integers(NB))
+    picks = [(int(rng.integers(2)), int(rng.integers(B)), int(rng.integers(H)), int(rng.integers(NB))) for _ in range(48)]
+    picks += [(K, 0, 0, 0), (K, B - 1, H - 1, NB - 1), (V, 0, 0, 0), (V, B - 1, H - 1, NB - 1)]
+    for which, b, h, j in picks:
         i = (b * H + h) * NB + j
         rec = oracle.encode_block(which, codes[which][i], mms[which][i], *book[which])
-        got = gc.get_block(which, b, h, j)
-        assert len(got) == (len(rec) + 15) // 16 * 16
-        np.testing.assert_array_equal(got[: len(rec)], rec)
-        assert not got[len(rec):].any()
+        assert (len(rec) + 15) // 16 == size16[which][i]
+        want = (int(off16[which * B * H * NB + i]), int(size16[which][i]))
+        assert gc.block_entry(which, b, h, j) == want, (which, b, h, j)
+        assert gp.block_entry(which, b, h, j) == want, (which, b, h, j)
+        for cache in (gc, gp):
+            got = cache.get_block(which, b, h, j)
+            assert len(got) == (len(rec) + 15) // 16 * 16
+            np.testing.assert_array_equal(got[: len(rec)], rec)
+            assert not got[len(rec):].any()
+    gp.close()
     del codes, mms
     q = W.make_queries(B, Hq, 1, w.seed)[0]
     out = gc.attn_decode(_dev(q), SCALE).cpu().numpy()
@@ -912,6 +936,9 @@ def test_large_configs_full_size_sampled(gpu, oracle, name, rel):
         oc.compress_blocks(np.ascontiguousarray(Kx[b:b + 1, :, h:h + 1]), np.ascontiguousarray(Vx[b:b + 1, :, h:h + 1]))
         ref = oc.attn_decode(np.ascontiguousarray(q[b:b + 1, h * G:(h + 1) * G]), SCALE)
         err = _attn_close(out[b:b + 1, h * G:(h + 1) * G], ref)
+        # well inside the 1e-3 bar: the kernels' own error is a few 1e-5 at most (integer weights of 22 bits, fp32
+        # accumulation); a tenfold loss of weight resolution would still pass the bar on these inputs and is caught here
+        assert err <= 2e-4 * max(1.0, float(np.abs(np.asarray(ref)).max())), err
         _say(f"  (b={b}, h={h}): attention max abs err {err:.3e}")
         sampled[(b, h)] = oc
     gc.close()
@@ -944,6 +971,7 @@ def test_large_configs_full_size_sampled(gpu, oracle, name, rel):
             if t in check:
                 ref = oc.attn_decode(np.ascontiguousarray(qs[t][b:b + 1, h * G:(h + 1) * G]), SCALE)
                 worst = max(worst, _attn_close(outs[t][b:b + 1, h * G:(h + 1) * G], ref))
+                assert worst <= 2e-4 * max(1.0, float(np.abs(np.asarray(ref)).max())), worst
         for which in (K, V):
             for j in range(NB, oc.n_blocks):   # the blocks compressed while streaming
                 np.testing.assert_array_equal(gc.get_block(which, b, h, j), oc.get_block(which, 0, 0, j))
