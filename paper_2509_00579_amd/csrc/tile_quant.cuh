@@ -119,7 +119,7 @@ __device__ __forceinline__ bool quant_codes(const float (&x)[N], float mn, float
 __device__ __forceinline__ float canon_zero(float v) { return v == 0.0f ? 0.0f : v; }
 
 // LDS scratch needed by quantize_tile.
-struct QuantShared {
+struct __attribute__((aligned(16))) QuantShared {
     float part_mn[4][kD];
     float part_mx[4][kD];
     float unit_mn[kD];  // K: per channel;  V: per token (first 64 entries)
@@ -211,12 +211,12 @@ __device__ __forceinline__ bool quantize_tile(TileRegs &r, QuantShared &sh, int 
             mx[k] = max_raw(mx[k], __shfl_xor(mx[k], 32));
         }
         const int w = tid >> 6, c0 = tile_chan0(tid);
-        if (((tid & 63) >> 4) == 0) {
-#pragma unroll
-            for (int k = 0; k < 8; k++) {
-                sh.part_mn[w][c0 + k] = mn[k];
-                sh.part_mx[w][c0 + k] = mx[k];
-            }
+        if (((tid & 63) >> 4) == 0) {  // 16-byte accesses: a thread's eight channels are neighbours, lanes follow each other
+            float4 *pmn = reinterpret_cast<float4 *>(&sh.part_mn[w][c0]), *pmx = reinterpret_cast<float4 *>(&sh.part_mx[w][c0]);
+            pmn[0] = make_float4(mn[0], mn[1], mn[2], mn[3]);
+            pmn[1] = make_float4(mn[4], mn[5], mn[6], mn[7]);
+            pmx[0] = make_float4(mx[0], mx[1], mx[2], mx[3]);
+            pmx[1] = make_float4(mx[4], mx[5], mx[6], mx[7]);
         }
         __syncthreads();
         if (tid < kD) {
@@ -228,9 +228,16 @@ __device__ __forceinline__ bool quantize_tile(TileRegs &r, QuantShared &sh, int 
             sh.unit_mx[tid] = canon_zero(z);
         }
         __syncthreads();
+        float umn[8], umx[8];
+        {
+            const float4 *pmn = reinterpret_cast<const float4 *>(&sh.unit_mn[c0]), *pmx = reinterpret_cast<const float4 *>(&sh.unit_mx[c0]);
+            const float4 a0 = pmn[0], a1 = pmn[1], z0 = pmx[0], z1 = pmx[1];
+            umn[0] = a0.x; umn[1] = a0.y; umn[2] = a0.z; umn[3] = a0.w; umn[4] = a1.x; umn[5] = a1.y; umn[6] = a1.z; umn[7] = a1.w;
+            umx[0] = z0.x; umx[1] = z0.y; umx[2] = z0.z; umx[3] = z0.w; umx[4] = z1.x; umx[5] = z1.y; umx[6] = z1.z; umx[7] = z1.w;
+        }
 #pragma unroll
         for (int k = 0; k < 8; k++) {
-            const float a = sh.unit_mn[c0 + k], z = sh.unit_mx[c0 + k];
+            const float a = umn[k], z = umx[k];
             const float range = z - a;
             const float step = two_eb * range;
             const float xs[4] = {r.x[0][k], r.x[1][k], r.x[2][k], r.x[3][k]};
