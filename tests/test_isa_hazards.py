@@ -120,3 +120,19 @@ def test_the_walk_sees_a_write_at_the_end_of_a_predecessor_block():
     insts, at, branches = _parse(good)
     i = next(k for k, x in enumerate(insts) if x.startswith("v_fmac_f32_dpp"))
     _check_back(insts, at, branches, i, 0, {5}, insts[i], set())
+
+
+@pytest.mark.parametrize("source", ["quantize.hip", "encode.hip"])
+def test_row_reductions_of_the_store_kernels_carry_their_wait_states(source):
+    """The store kernels reduce a token's row with v_min_f32_dpp / v_max_f32_dpp (inline assembly, csrc/tile_quant.cuh);
+    each of these reads the register the instruction before it wrote, so the assembly puts an s_nop of at least two
+    wait states (s_nop 1) directly in front of every one: checked on what the compiler emitted."""
+    lines = [l.split(";")[0].strip() for l in B.device_assembly(source).splitlines()]
+    lines = [l for l in lines if l and not l.startswith(".") and not l.endswith(":")]
+    found = 0
+    for i, ins in enumerate(lines):
+        if ins.split()[0] in ("v_min_f32_dpp", "v_max_f32_dpp"):
+            found += 1
+            prev = lines[i - 1].split()
+            assert prev[0] == "s_nop" and int(prev[1], 0) >= 1, (i, lines[i - 1], ins)
+    assert found >= 8   # the V quantizer is in every store kernel of both files
