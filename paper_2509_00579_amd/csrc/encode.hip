@@ -320,26 +320,39 @@ __global__ __launch_bounds__(256) void write_kernel(Geo g, const uint16_t *__res
     // word (i / 32); the table holds every code word in the bit order in which it enters the chunk.
     uint32_t *pay = rec + R::hdr_bytes(g) / 4;
     uint32_t pos = before + inc - bits;
-    // Two code words at a time (at most 2 x 12 bits) go into a 64-bit accumulator that starts at bit `fill` < 32 of
-    // word `word`; when its low word is full it is ORed into the chunk.  No branch: a pair that fills nothing ORs a
-    // zero.  Neighbouring threads share the words at their borders, hence the atomic OR.
+    // Several code words at a time go into a 64-bit accumulator that starts at bit `fill` < 32 of word `word`: four
+    // when the codebook's longest code word has at most 8 bits (4 x 8 + 31 pending bits fit), else two (2 x 12 + 31).
+    // When the accumulator's low word is full it is ORed into the chunk.  No branch per group: a group that fills
+    // nothing ORs a zero.  Neighbouring threads share the words at their borders, hence the atomic OR.
     static_assert(2 * kLutBits + 31 < 64, "a pair of code words behind 31 pending bits fits the accumulator");
     uint32_t word = pos >> 5, fill = pos & 31;
     uint32_t lo = 0, hi = 0;
-#pragma unroll
-    for (int k = 0; k < 32; k += 2) {
-        const uint32_t len0 = sym[k] >> 16, len1 = sym[k + 1] >> 16;
-        const uint32_t two = (sym[k] & 0xffffu) | ((sym[k + 1] & 0xffffu) << len0);
-        const unsigned long long at = (unsigned long long)two << fill;
+    auto push = [&](uint32_t group, uint32_t len) {  // len <= 32
+        const unsigned long long at = (unsigned long long)group << fill;
         lo |= (uint32_t)at;
         hi |= (uint32_t)(at >> 32);
-        fill += len0 + len1;
+        fill += len;
         const bool full = fill >= 32;
         atomicOr(&pay[word], full ? lo : 0u);
         lo = full ? hi : lo;
         hi = full ? 0u : hi;
         word += full ? 1u : 0u;
         fill &= 31u;
+    };
+    if (g.lut_bits[WHICH] <= 8) {  // uniform over the launch
+#pragma unroll
+        for (int k = 0; k < 32; k += 4) {
+            const uint32_t l0 = sym[k] >> 16, l1 = l0 + (sym[k + 1] >> 16), l2 = l1 + (sym[k + 2] >> 16);
+            const uint32_t four = (sym[k] & 0xffffu) | ((sym[k + 1] & 0xffffu) << l0) | ((sym[k + 2] & 0xffffu) << l1) |
+                                  ((sym[k + 3] & 0xffffu) << l2);
+            push(four, l2 + (sym[k + 3] >> 16));
+        }
+    } else {
+#pragma unroll
+        for (int k = 0; k < 32; k += 2) {
+            const uint32_t l0 = sym[k] >> 16;
+            push((sym[k] & 0xffffu) | ((sym[k + 1] & 0xffffu) << l0), l0 + (sym[k + 1] >> 16));
+        }
     }
     if (fill) atomicOr(&pay[word], lo);
     __syncthreads();
