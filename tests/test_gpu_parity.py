@@ -188,6 +188,41 @@ def test_prefill_with_one_quantization_pass(gpu, oracle, B, H, Hq, S, rel_k, rel
     gc.close()
 
 
+def test_one_context_two_prompts_with_different_codebooks(gpu, oracle):
+    """A context that is reset and filled again builds new codebooks: the tables that the second prompt is encoded and
+    decoded with must be the second prompt's (the tables travel from a pinned host block that is rewritten in place).
+    Second prompt: values on a coarse grid, so that most quantization levels are never used and the code lengths
+    differ from the first prompt's in almost every symbol."""
+    _say("one context, two prompts")
+    B, H, Hq, S = 1, 2, 2, 384
+    Ka, Va = W.make_kv(B, H, S, 61)
+    rng = np.random.default_rng(62)
+    Kb = (rng.integers(-3, 4, size=Ka.shape) * 0.5).astype(np.float16)
+    Vb = (rng.integers(0, 2, size=Va.shape) * 2.0 - 1.0).astype(np.float16)
+    gc = gpu.KVCompCache(B, H, Hq, S + 64, 1e-2, 1e-2, max_code_len=6)
+    q = W.make_queries(B, Hq, 1, 61)[0]
+    books = []
+    for Kx, Vx in ((Ka, Va), (Kb, Vb), (Ka, Va)):
+        oc = oracle.OracleCache(B, H, Hq, S + 64, 1e-2, 1e-2, 0, 6)
+        oc.build_codebook(Kx, Vx)
+        oc.compress_blocks(Kx, Vx)
+        gc.reset(keep_codebook=False)
+        gc.prefill(_dev(Kx), _dev(Vx))
+        for which in (K, V):
+            ln_g, cd_g = gc.codebook(which)
+            np.testing.assert_array_equal(ln_g, oc.len[which])
+            np.testing.assert_array_equal(cd_g, oc.code[which])
+        _assert_same_cache(oc, gc)
+        _attn_close(gc.attn_decode(_dev(q), SCALE).cpu().numpy(), oc.attn_decode(q, SCALE))
+        for which in (K, V):   # the stand-alone decompressor reads the single-symbol tables and the tree
+            ref = oc.decompress(which)
+            np.testing.assert_array_equal(gc.decompress(which, S).cpu().numpy().view(np.uint16), ref.view(np.uint16))
+            np.testing.assert_array_equal(gc.decompress(which, S, tree_walk=True).cpu().numpy().view(np.uint16), ref.view(np.uint16))
+        books.append(np.asarray(oc.len[K]).copy())
+    assert (books[0] != books[1]).sum() > 8    # the two prompts really have different codebooks
+    gc.close()
+
+
 def test_all_residual_and_tiny_sequences(gpu, oracle):
     _say("seq < 64: everything stays in the fp16 buffer")
     B, H, Hq = 2, 2, 4
