@@ -3,12 +3,15 @@
 // the newest tokens.
 //
 // The paper reserves space with a global atomic offset, which makes the layout depend on execution order.  Here
-// the same contiguous layout is produced in a fixed order by three launches:
-//   1. size pass   : quantize, sum the code lengths of the block -> record size into the Block Offsets Array
+// the same contiguous layout is produced in a fixed order by three steps:
+//   1. size pass   : sum the code lengths of the block -> record size into the Block Offsets Array
 //   2. place       : the sizes are scanned in (tensor, batch, head, block) order starting at the arena tail
-//   3. write pass  : quantize again, encode, write the record at its offset
-// The store side runs once per token block while the fetch side runs every decode step (Section 3.3), so the
-// second read of the fp16 input is the cheaper trade against a staging copy of all records.
+//   3. write pass  : encode, write the record at its offset
+// Blocks that the fp16 buffer sheds during decoding are quantized by both passes from the buffer (the store side runs
+// once per token block while the fetch side runs every decode step, Section 3.3: the second read of 64 tokens is the
+// cheaper trade against a staging copy of the records).  A prompt goes through the histogram pass first, which keeps
+// the codes, the unit min/max and a histogram per block: its sizes come from the block histograms and its write pass
+// reads the kept codes.
 #include <algorithm>
 
 #include "tile_quant.cuh"
