@@ -1272,7 +1272,7 @@ hipError_t launch_fused_attn(const Geo &g, const uint16_t *q, float scale, float
     const int bits_k = g.lut_bits[0], bits_v = g.lut_bits[1];
     const int longest = bits_k > bits_v ? bits_k : bits_v;
     if (longest < 1 || longest > kLutBits) return hipErrorInvalidValue;
-    if (fused_table_bits(longest) == 6 && KVC_PAIR) {  // pair tables: 12 index bits, entries of 4 bytes
+    if (fused_table_bits(longest) == 6) {  // pair tables: 12 index bits, entries of 4 bytes
         a.mask[0] = a.mask[1] = ((1u << kPairIndexBits) - 1u) << 2;
     } else {
         a.mask[0] = ((1u << bits_k) - 1u) << 1;

@@ -177,9 +177,6 @@ struct Quad {
     }
 };
 
-#ifndef KVC_PAIR
-#define KVC_PAIR 1
-#endif
 constexpr int kHalf = kSliceLen / 2;  // symbols per chain
 constexpr int kPairIndexBits = 12;    // index width of the pair table: two code words of up to 6 bits
 constexpr int kPairLongest = kPairIndexBits / 2;
@@ -189,7 +186,7 @@ constexpr int kPairLongest = kPairIndexBits / 2;
 // entries.
 template <int LB>
 struct DecodeMode {
-    static constexpr bool kPair = LB <= kPairLongest && KVC_PAIR;
+    static constexpr bool kPair = LB <= kPairLongest;
     static constexpr int J = kPair ? 2 : 1;                               // log2 of the entry size in bytes
     static constexpr int kIndexBits = kPair ? kPairIndexBits : LB;
     static constexpr int kSymsPerLookup = kPair ? 2 : 1;
