@@ -19,6 +19,11 @@
 namespace kvc {
 
 constexpr int kCodeRow = kD + 4;  // padded row of the LDS code tile (bytes)
+// Byte offset of token row t in the tile.  The second 32 rows start 64 bytes later: the two threads of a V slice read
+// rows t and t + 32 of one column in the same instruction, and 32 rows of 33 words are a whole number of LDS bank
+// rounds apart.
+constexpr int kCodeTileBytes = kBT * kCodeRow + 64;
+__device__ __forceinline__ int code_row(int t) { return t * kCodeRow + ((t >> 5) << 6); }
 
 template <int WHICH>
 struct Rec {
@@ -249,7 +254,7 @@ __global__ __launch_bounds__(256) void write_kernel(Geo g, const uint16_t *__res
     __shared__ QuantShared sh;
     __shared__ uint32_t enc[512];  // [0..256) first-bit-first, [256..512) last-bit-first
     __shared__ uint32_t wave_tot[4];
-    __shared__ __attribute__((aligned(16))) uint8_t code_tile[kBT * kCodeRow];
+    __shared__ __attribute__((aligned(16))) uint8_t code_tile[kCodeTileBytes];
     __shared__ __attribute__((aligned(16))) uint32_t rec[(kMaxRecordBytes + 15) / 16 * 4];
     const int tid = threadIdx.x, blk = blockIdx.x;
     const int bh = blk / n_blk_per_bh, j = blk - bh * n_blk_per_bh;
@@ -266,7 +271,7 @@ __global__ __launch_bounds__(256) void write_kernel(Geo g, const uint16_t *__res
         for (int i = 0; i < 4; i++) {
             const int t = tile_token(tid, i);
             const uint2 pk = *reinterpret_cast<const uint2 *>(src + t * kD + c0);
-            uint32_t *dst = reinterpret_cast<uint32_t *>(code_tile + t * kCodeRow + c0);
+            uint32_t *dst = reinterpret_cast<uint32_t *>(code_tile + code_row(t) + c0);
             dst[0] = pk.x;
             dst[1] = pk.y;
         }
@@ -277,7 +282,7 @@ __global__ __launch_bounds__(256) void write_kernel(Geo g, const uint16_t *__res
 #pragma unroll
         for (int i = 0; i < 4; i++) {
             const int t = tile_token(tid, i);
-            uint32_t *dst = reinterpret_cast<uint32_t *>(code_tile + t * kCodeRow + c0);
+            uint32_t *dst = reinterpret_cast<uint32_t *>(code_tile + code_row(t) + c0);
             dst[0] = r.code[i][0] | (r.code[i][1] << 8) | (r.code[i][2] << 16) | (r.code[i][3] << 24);
             dst[1] = r.code[i][4] | (r.code[i][5] << 8) | (r.code[i][6] << 16) | (r.code[i][7] << 24);
         }
@@ -297,7 +302,7 @@ __global__ __launch_bounds__(256) void write_kernel(Geo g, const uint16_t *__res
     for (int k = 0; k < 32; k++) {
         const int t = WHICH == 0 ? (slice >> 1) : 32 * part + k;
         const int c = WHICH == 0 ? kSliceLen * (slice & 1) + 32 * part + k : slice;
-        sym[k] = enc[256 * part + code_tile[t * kCodeRow + c]];
+        sym[k] = enc[256 * part + code_tile[code_row(t) + c]];
         bits += sym[k] >> 16;
     }
     // stage 3: inclusive scan of the bit counts over the workgroup -> bit offset of every thread
