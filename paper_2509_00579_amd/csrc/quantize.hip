@@ -82,12 +82,14 @@ __global__ __launch_bounds__(256, 4) void histogram_kernel(Geo g, const uint16_t
                 minmax[(size_t)blk * units + tid] = float_to_half_bits(sh.unit_mn[tid]) | (float_to_half_bits(sh.unit_mx[tid]) << 16);
             __syncthreads();  // the block's atomics are done
             uint32_t cnt = 0;
-            uint4 *mine = reinterpret_cast<uint4 *>(&hist[tid][0]);
+            if (tid < g.n_sym[WHICH]) {  // codes stay below the number of levels: the other bins are never touched
+                uint4 *mine = reinterpret_cast<uint4 *>(&hist[tid][0]);
 #pragma unroll
-            for (int c = 0; c < 8; c++) {  // rotated: neighbouring bins start at different banks
-                const uint4 v = mine[(c + tid) & 7];
-                cnt += (v.x + v.y) + (v.z + v.w);
-                mine[(c + tid) & 7] = make_uint4(0, 0, 0, 0);
+                for (int c = 0; c < 8; c++) {  // rotated: neighbouring bins start at different banks
+                    const uint4 v = mine[(c + tid) & 7];
+                    cnt += (v.x + v.y) + (v.z + v.w);
+                    mine[(c + tid) & 7] = make_uint4(0, 0, 0, 0);
+                }
             }
             total += cnt;
             block_hist[(size_t)blk * 256 + tid] = (uint16_t)cnt;  // at most 8192
